@@ -1,0 +1,225 @@
+"""ctypes front end of the CPU oracle (``attnqat_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()``
+and by the ``cpu_baseline`` leg of ``bench.py``.  It shares no code with the
+HIP library and never imports it.
+
+All tensors are numpy arrays; inputs are float32 (holding bf16-representable
+values), outputs float64.  Citations are to the paper's sections, equations
+and algorithms; see the C file's header for the readings taken.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "attnqat_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+E2M1_VALUES = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  Plain -O2: no fast-math, no reassociation."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+_vp, _i, _l, _d = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_double
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    L = ctypes.CDLL(_LIB)
+    L.oracle_e2m1_value.restype = _d
+    L.oracle_e2m1_value.argtypes = [_i]
+    L.oracle_e4m3_value.restype = _d
+    L.oracle_e4m3_value.argtypes = [_i]
+    L.oracle_e4m3_from_amax.restype = _i
+    L.oracle_e4m3_from_amax.argtypes = [_d]
+    L.oracle_e2m1_round.restype = _i
+    L.oracle_e2m1_round.argtypes = [_d, _d]
+    L.oracle_phi.restype = _i
+    L.oracle_phi.argtypes = [_vp, _l, _i, _i, _vp, _vp, _vp]
+    L.oracle_fwd_rows.restype = _i
+    L.oracle_fwd_rows.argtypes = [_vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i, _i,
+                                  _l, _vp, _vp, _vp, _vp, _vp]
+    L.oracle_bwd.restype = _i
+    L.oracle_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
+                             _vp, _vp, _vp]
+    L.oracle_bwd_dq_rows.restype = _i
+    L.oracle_bwd_dq_rows.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
+                                     _l, _vp, _vp, _vp, _vp]
+    L.oracle_bwd_dkdv_keys.restype = _i
+    L.oracle_bwd_dkdv_keys.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
+                                       _i, _i, _l, _vp, _vp, _vp, _vp, _vp, _vp]
+    L.oracle_num_threads.restype = _i
+    _lib = L
+    return L
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def num_threads() -> int:
+    return _load().oracle_num_threads()
+
+
+# ---------------------------------------------------------------- formats
+
+def e2m1_value(code: int) -> float:
+    return _load().oracle_e2m1_value(code)
+
+
+def e4m3_value(byte: int) -> float:
+    return _load().oracle_e4m3_value(byte)
+
+
+def e4m3_from_amax(amax: float) -> int:
+    """Byte of RNE_E4M3(amax/6), saturating at 448 (Eq. 1 with an E4M3 scale)."""
+    return _load().oracle_e4m3_from_amax(float(amax))
+
+
+def e2m1_round(ax: float, s: float) -> int:
+    """Magnitude index of RNE_E2M1(ax/s), saturating at 6 (Eq. 1)."""
+    return _load().oracle_e2m1_round(float(ax), float(s))
+
+
+def phi(x, scale_mode: int = 0):
+    """phi and phi^-1 along the last axis in blocks of 16 (Eq. 1, Eq. 2).
+
+    Returns (packed codes uint8 [..., d/2], E4M3 scale bytes uint8 [..., d/16],
+    dequantized float32 [..., d])."""
+    x = _f32(x)
+    d = x.shape[-1]
+    n = x.size // d
+    packed = np.empty(x.shape[:-1] + (d // 2,), np.uint8)
+    scales = np.empty(x.shape[:-1] + (d // 16,), np.uint8)
+    xf = np.empty_like(x)
+    rc = _load().oracle_phi(_p(x), n, d, scale_mode, _p(packed), _p(scales), _p(xf))
+    if rc:
+        raise ValueError(f"oracle_phi failed ({rc})")
+    return packed, scales, xf
+
+
+def fake_quant(x, scale_mode: int = 0):
+    """phi^-1(phi(x)) along the last axis."""
+    return phi(x, scale_mode)[2]
+
+
+# ---------------------------------------------------------------- attention
+
+def _prep_qkv(q, k, v, quant_qkv, scale_mode):
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    if quant_qkv:      # Alg. 2 first line: Q^F, K^F, V^F
+        q, k, v = fake_quant(q, scale_mode), fake_quant(k, scale_mode), fake_quant(v, scale_mode)
+    return q, k, v
+
+
+def flat_rows(B, Hq, L, rows):
+    """rows: iterable of (b, h, i) -> flat ids."""
+    return np.asarray([(b * Hq + h) * L + i for (b, h, i) in rows], dtype=np.int64)
+
+
+def fwd(q, k, v, causal: bool, Bk: int, quant_qkv: bool = True, quant_p: bool = True,
+        scale_mode: int = 0, rows=None, dump_p: bool = False):
+    """Alg. 2 (training forward; Alg. 1's O and L are the same numbers).
+
+    q [B,Hq,L,d], k/v [B,Hkv,L,d].  rows: None (all rows; outputs shaped
+    [B,Hq,L,...]) or an int64 array of flat ids (outputs shaped [n,...]).
+    Returns dict(O, Op, L[, P]) in float64 (P float32 [n, L])."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    qf, kf, vf = _prep_qkv(q, k, v, quant_qkv, scale_mode)
+    if rows is None:
+        n, shp, rp = B * Hq * L, (B, Hq, L), None
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        n, shp, rp = rows.size, (rows.size,), rows
+    O = np.empty(shp + (d,)); Op = np.empty(shp + (d,)); Lse = np.empty(shp)
+    P = np.empty((n, L), np.float32) if dump_p else None
+    rc = _load().oracle_fwd_rows(_p(qf), _p(kf), _p(vf), B, Hq, Hkv, L, d, int(causal), Bk,
+                                 int(quant_p), scale_mode, n, _p(rp),
+                                 _p(O), _p(Op), _p(Lse), _p(P))
+    if rc:
+        raise ValueError(f"oracle_fwd_rows failed ({rc})")
+    out = {"O": O, "Op": Op, "L": Lse}
+    if dump_p:
+        out["P"] = P
+    return out
+
+
+def bwd(q, k, v, do, Lse, Op, causal: bool, quant_qkv: bool = True, quant_p: bool = True,
+        scale_mode: int = 0):
+    """Alg. 3 on the whole problem.  Lse, Op: the forward's L and O'.
+    Returns dict(dQ, dK, dV) float64."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    qf, kf, vf = _prep_qkv(q, k, v, quant_qkv, scale_mode)
+    do, Lse, Op = _f32(do), _f64(Lse), _f64(Op)
+    dQ = np.empty((B, Hq, L, d)); dK = np.empty((B, Hkv, L, d)); dV = np.empty((B, Hkv, L, d))
+    rc = _load().oracle_bwd(_p(qf), _p(kf), _p(vf), _p(do), _p(Lse), _p(Op),
+                            B, Hq, Hkv, L, d, int(causal), int(quant_p), scale_mode,
+                            _p(dQ), _p(dK), _p(dV))
+    if rc:
+        raise ValueError(f"oracle_bwd failed ({rc})")
+    return {"dQ": dQ, "dK": dK, "dV": dV}
+
+
+def bwd_dq_rows(q, k, v, do, rows, Lse_rows, Op_rows, causal: bool,
+                quant_qkv: bool = True, quant_p: bool = True, scale_mode: int = 0):
+    """dQ of Alg. 3 for listed query rows (flat ids); Lse_rows/Op_rows from fwd(rows=...)."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    qf, kf, vf = _prep_qkv(q, k, v, quant_qkv, scale_mode)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    do, Lse_rows, Op_rows = _f32(do), _f64(Lse_rows), _f64(Op_rows)
+    dQ = np.empty((rows.size, d))
+    rc = _load().oracle_bwd_dq_rows(_p(qf), _p(kf), _p(vf), _p(do), B, Hq, Hkv, L, d,
+                                    int(causal), int(quant_p), scale_mode,
+                                    rows.size, _p(rows), _p(Lse_rows), _p(Op_rows), _p(dQ))
+    if rc:
+        raise ValueError(f"oracle_bwd_dq_rows failed ({rc})")
+    return dQ
+
+
+def bwd_dkdv_keys(q, k, v, do, b, hk, keys, Lse_grp, Op_grp, causal: bool,
+                  quant_qkv: bool = True, quant_p: bool = True, scale_mode: int = 0,
+                  dump_p: bool = False):
+    """dK, dV of Alg. 3 for listed key rows of kv head (b, hk).
+    Lse_grp [G,L], Op_grp [G,L,d]: forward outputs of the G query heads of the group."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    qf, kf, vf = _prep_qkv(q, k, v, quant_qkv, scale_mode)
+    keys = np.ascontiguousarray(keys, dtype=np.int64)
+    do, Lse_grp, Op_grp = _f32(do), _f64(Lse_grp), _f64(Op_grp)
+    assert Lse_grp.shape == (G, L) and Op_grp.shape == (G, L, d)
+    dK = np.empty((keys.size, d)); dV = np.empty((keys.size, d))
+    P = np.empty((keys.size, G, L), np.float32) if dump_p else None
+    rc = _load().oracle_bwd_dkdv_keys(_p(qf), _p(kf), _p(vf), _p(do), B, Hq, Hkv, L, d,
+                                      int(causal), int(quant_p), scale_mode, b, hk,
+                                      keys.size, _p(keys), _p(Lse_grp), _p(Op_grp),
+                                      _p(dK), _p(dV), _p(P))
+    if rc:
+        raise ValueError(f"oracle_bwd_dkdv_keys failed ({rc})")
+    return (dK, dV, P) if dump_p else (dK, dV)

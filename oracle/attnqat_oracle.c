@@ -1,0 +1,403 @@
+/*
+ * CPU oracle for NVFP4 fake-quantized attention (Attn-QAT).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, and meant to be checked against the
+ * paper by eye.  It shares no code with the HIP library and is used only by
+ * the tests, the smoke check and the benchmark's CPU-baseline leg.
+ *
+ * Arithmetic: fp64 everywhere, except that the operand of every phi(P) is
+ * first rounded to fp32 (the softmax is an fp32 quantity in the method,
+ * Sec. 3.3 "High-precision O for the backward pass"), and phi's rounding
+ * decisions are taken exactly on those fp32 values.
+ *
+ * What is implemented
+ *   phi / phi^-1           Sec. 3.1 "NVFP4 and SageAttention3", Eq. 1 and Eq. 2
+ *   forward (train+infer)  Alg. 2 "Attn-QAT Forward (Training)"; Alg. 1 is the
+ *                          same recurrence without O' (Eq. 3 == Eq. 4)
+ *   backward               Alg. 3 "Attn-QAT backward", with the two rules of
+ *                          Sec. 3.3: P is re-quantized, D comes from O'
+ *
+ * Readings of points the paper leaves open (all listed in the design notes):
+ *   - the block scale is stored as E4M3 (OCP "fn": bias 7, subnormals, max
+ *     448, no infinity): s = RNE_E4M3(max|X| / 6), saturating at 448; a scale
+ *     that rounds to 0 zeroes its block.  scale_mode 1 keeps Eq. 1 literally
+ *     (s = max|X|/6 as an fp32 number) for diagnostics.
+ *   - "round to the nearest FP4 value" is round-to-nearest-even on the real
+ *     quotient |x|/s, saturating at 6.
+ *   - P blocks are 16 consecutive keys aligned to absolute key indices that
+ *     are multiples of 16; masked and out-of-range keys count as 0.
+ *   - key tiles of Bk keys are visited in increasing order; the running max
+ *     used for quantizing P-tilde is the max over all tiles seen so far.
+ *
+ * Parity status: every exported function below is pinned by the CPU tests
+ * (format tables, closed forms, library attention with phi off, an independent
+ * row-wise transcription with phi on, autograd of the unrolled STE graph).
+ * Model-level claims of the paper (quality recovery) are parity unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ formats */
+
+/* E2M1 magnitudes, index = low three bits of a code (Sec. 1: 15 distinct values, max 6). */
+static const double E2M1[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+double oracle_e2m1_value(int code)
+{
+    double v = E2M1[code & 7];
+    return (code & 8) ? -v : v;
+}
+
+/* E4M3 value of a byte 0x00..0x7E (sign bit clear; 0x7F is NaN and never produced). */
+double oracle_e4m3_value(int byte)
+{
+    int e = (byte >> 3) & 15, m = byte & 7;
+    if (e == 0) return ldexp((double)m / 8.0, -6);
+    return ldexp(1.0 + (double)m / 8.0, e - 7);
+}
+
+/* Byte of RNE_E4M3(amax / 6), saturating at 448 (byte 0x7E).
+ * Decided on amax against 6 * midpoint, both exact in fp64, so the rounding
+ * is that of the real quotient. */
+int oracle_e4m3_from_amax(double amax)
+{
+    int i = 0;
+    while (i < 0x7E) {
+        double mid6 = 6.0 * 0.5 * (oracle_e4m3_value(i) + oracle_e4m3_value(i + 1));
+        if (amax > mid6 || (amax == mid6 && (i & 1))) ++i; else break;
+    }
+    return i;
+}
+
+/* Magnitude index of RNE_E2M1(ax / s), ax >= 0, s > 0, saturating at 6.
+ * Decided on ax against midpoint * s, exact in fp64. */
+int oracle_e2m1_round(double ax, double s)
+{
+    int i = 0;
+    while (i < 7) {
+        double mid = 0.5 * (E2M1[i] + E2M1[i + 1]) * s;
+        if (ax > mid || (ax == mid && (i & 1))) ++i; else break;
+    }
+    return i;
+}
+
+/* phi then phi^-1 on one block of n <= 16 values (Eq. 1, Eq. 2).
+ * code[i] = sign<<3 | magnitude index; *scale is the block scale as a number,
+ * *scale_byte its E4M3 byte (0 in scale_mode 1). */
+static void phi_block(const double* x, int n, int scale_mode,
+                      uint8_t* code, double* scale, uint8_t* scale_byte, double* xf)
+{
+    double amax = 0.0;
+    for (int i = 0; i < n; ++i) { double a = fabs(x[i]); if (a > amax) amax = a; }
+    double s; int sb = 0;
+    if (scale_mode == 0) { sb = oracle_e4m3_from_amax(amax); s = oracle_e4m3_value(sb); }
+    else                 { s = (double)(float)(amax / 6.0); }
+    for (int i = 0; i < n; ++i) {
+        int sign = signbit(x[i]) ? 8 : 0;
+        int mag = (s > 0.0) ? oracle_e2m1_round(fabs(x[i]), s) : 0;
+        if (code) code[i] = (uint8_t)(sign | mag);
+        if (xf) xf[i] = (sign ? -1.0 : 1.0) * s * E2M1[mag];
+    }
+    if (scale) *scale = s;
+    if (scale_byte) *scale_byte = (uint8_t)sb;
+}
+
+/* phi over the last axis of x[nrows, d] (blocks of 16 along d; d % 16 == 0).
+ * packed[nrows, d/2]: element 2k in bits 3:0, element 2k+1 in bits 7:4.
+ * scales[nrows, d/16] E4M3 bytes.  xf[nrows, d] = phi^-1(phi(x)).  Any output may be NULL. */
+int oracle_phi(const float* x, long nrows, int d, int scale_mode,
+               uint8_t* packed, uint8_t* scales, float* xf)
+{
+    if (!x || d < 16 || d % 16) return -1;
+    #pragma omp parallel for schedule(static)
+    for (long r = 0; r < nrows; ++r) {
+        for (int c0 = 0; c0 < d; c0 += 16) {
+            double xb[16], xfb[16], s; uint8_t code[16], sb;
+            for (int i = 0; i < 16; ++i) xb[i] = (double)x[r * d + c0 + i];
+            phi_block(xb, 16, scale_mode, code, &s, &sb, xfb);
+            if (packed) for (int i = 0; i < 16; i += 2)
+                packed[(r * d + c0 + i) / 2] = (uint8_t)(code[i] | (code[i + 1] << 4));
+            if (scales) scales[r * (d / 16) + c0 / 16] = sb;
+            if (xf) for (int i = 0; i < 16; ++i) xf[r * d + c0 + i] = (float)xfb[i];
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ forward */
+
+static double dot(const float* a, const float* b, int d)
+{
+    double s = 0.0;
+    for (int c = 0; c < d; ++c) s += (double)a[c] * (double)b[c];
+    return s;
+}
+
+/*
+ * Alg. 2 for a list of query rows (rows are independent of each other and of Bq).
+ * qf,kf,vf: Q^F, K^F, V^F (or the raw tensors when input quantization is off),
+ *           [B,Hq,L,d] / [B,Hkv,L,d]; query head h reads kv head h / (Hq/Hkv).
+ * rows:     nrows flat ids (b*Hq + h)*L + i, or NULL for all B*Hq*L rows in order.
+ * Outputs per listed row: O[nrows,d], Op[nrows,d] (= O'), Lse[nrows];
+ * Pdump[nrows, L] (optional) receives the dequantized P-tilde^F of each key as it
+ * entered the O update (0 for masked keys).
+ */
+int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
+                    int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
+                    int quant_p, int scale_mode,
+                    long nrows, const long* rows,
+                    double* O, double* Op, double* Lse, float* Pdump)
+{
+    if (!qf || !kf || !vf || Hq % Hkv || Bk < 16 || Bk % 16 || d < 1) return -1;
+    const int G = Hq / Hkv;
+    const double rs = 1.0 / sqrt((double)d);
+    if (!rows) nrows = (long)B * Hq * L;
+    int err = 0;
+    #pragma omp parallel
+    {
+        double* S  = (double*)malloc(sizeof(double) * Bk);
+        double* Pt = (double*)malloc(sizeof(double) * Bk);
+        double* Pf = (double*)malloc(sizeof(double) * Bk);
+        double* o  = (double*)malloc(sizeof(double) * d);
+        double* op = (double*)malloc(sizeof(double) * d);
+        if (!S || !Pt || !Pf || !o || !op) {
+            #pragma omp atomic write
+            err = 1;
+        } else {
+        #pragma omp for schedule(dynamic, 4)
+        for (long n = 0; n < nrows; ++n) {
+            long rid = rows ? rows[n] : n;
+            long i = rid % L; long bh = rid / L; int h = (int)(bh % Hq); int b = (int)(bh / Hq);
+            const float* qrow = qf + rid * d;
+            const float* kh = kf + ((long)b * Hkv + h / G) * L * d;
+            const float* vh = vf + ((long)b * Hkv + h / G) * L * d;
+            double m = -INFINITY, l = 0.0;
+            for (int c = 0; c < d; ++c) { o[c] = 0.0; op[c] = 0.0; }
+            if (Pdump) for (long k = 0; k < L; ++k) Pdump[n * L + k] = 0.0f;
+            long kend = causal ? i + 1 : L;           /* visible keys are [0, kend) */
+            for (long k0 = 0; k0 < kend; k0 += Bk) {  /* tiles with no visible key change nothing */
+                int nk = (int)((kend - k0 < Bk) ? kend - k0 : Bk);
+                double mt = -INFINITY;
+                for (int k = 0; k < nk; ++k) {
+                    S[k] = dot(qrow, kh + (k0 + k) * d, d) * rs;
+                    if (S[k] > mt) mt = S[k];
+                }
+                double mnew = (m > mt) ? m : mt;
+                double alpha = (m == -INFINITY) ? 0.0 : exp(m - mnew);
+                double rowsum = 0.0;
+                for (int k = 0; k < nk; ++k) {
+                    Pt[k] = (double)(float)exp(S[k] - mnew);   /* fp32 softmax numerator */
+                    rowsum += Pt[k];
+                }
+                for (int k = nk; k < Bk; ++k) Pt[k] = 0.0;      /* masked keys */
+                if (quant_p) {
+                    for (int k = 0; k < nk; k += 16)
+                        phi_block(Pt + k, 16, scale_mode, NULL, NULL, NULL, Pf + k);
+                } else {
+                    for (int k = 0; k < nk; ++k) Pf[k] = Pt[k];
+                }
+                l = alpha * l + rowsum;                          /* un-quantized P-tilde */
+                m = mnew;
+                for (int c = 0; c < d; ++c) { o[c] *= alpha; op[c] *= alpha; }
+                for (int k = 0; k < nk; ++k) {
+                    const float* vrow = vh + (k0 + k) * d;
+                    for (int c = 0; c < d; ++c) {
+                        o[c]  += Pf[k] * (double)vrow[c];
+                        op[c] += Pt[k] * (double)vrow[c];
+                    }
+                    if (Pdump) Pdump[n * L + k0 + k] = (float)Pf[k];
+                }
+            }
+            for (int c = 0; c < d; ++c) {
+                if (O)  O[n * d + c]  = o[c] / l;
+                if (Op) Op[n * d + c] = op[c] / l;
+            }
+            if (Lse) Lse[n] = m + log(l);
+        }
+        }
+        free(S); free(Pt); free(Pf); free(o); free(op);
+    }
+    return err ? -2 : 0;
+}
+
+/* ----------------------------------------------------------------- backward */
+
+/*
+ * One query row against one aligned block of 16 keys [k0, k0+16): the inner
+ * statements of Alg. 3.  nvis = number of keys of the block the row may see
+ * (the rest are masked: P = 0).  Returns P (fp32-rounded), P^F and dS.
+ */
+static void bwd_block(const float* qrow, const float* dorow, double lse, double D,
+                      const float* kh, const float* vh, long k0, int nvis, int d, double rs,
+                      int quant_p, int scale_mode, double* P, double* Pf, double* dS)
+{
+    for (int k = 0; k < 16; ++k) {
+        if (k < nvis) {
+            double s = dot(qrow, kh + (k0 + k) * d, d) * rs;
+            P[k] = (double)(float)exp(s - lse);
+        } else P[k] = 0.0;
+    }
+    if (quant_p) phi_block(P, 16, scale_mode, NULL, NULL, NULL, Pf);
+    else for (int k = 0; k < 16; ++k) Pf[k] = P[k];
+    for (int k = 0; k < 16; ++k) {
+        if (k < nvis) {
+            double dP = dot(dorow, vh + (k0 + k) * d, d);
+            dS[k] = P[k] * (dP - D) * rs;        /* fp32 P, not P^F (Sec. 3.3) */
+        } else dS[k] = 0.0;
+    }
+}
+
+static int nvis_of(long k0, long kend)
+{
+    long n = kend - k0;
+    return (int)(n < 0 ? 0 : (n > 16 ? 16 : n));
+}
+
+/*
+ * Alg. 3 on the whole problem.  Lse[B,Hq,L], Op[B,Hq,L,d] are the forward's L
+ * and O'.  dQ[B,Hq,L,d], dK/dV[B,Hkv,L,d] (summed over the query heads of a group).
+ */
+int oracle_bwd(const float* qf, const float* kf, const float* vf, const float* dO,
+               const double* Lse, const double* Op,
+               int B, int Hq, int Hkv, long L, int d, int causal,
+               int quant_p, int scale_mode,
+               double* dQ, double* dK, double* dV)
+{
+    if (!qf || !kf || !vf || !dO || !Lse || !Op || Hq % Hkv) return -1;
+    const int G = Hq / Hkv;
+    const double rs = 1.0 / sqrt((double)d);
+    memset(dQ, 0, sizeof(double) * (size_t)B * Hq * L * d);
+    memset(dK, 0, sizeof(double) * (size_t)B * Hkv * L * d);
+    memset(dV, 0, sizeof(double) * (size_t)B * Hkv * L * d);
+    #pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < (long)B * Hkv; ++u) {      /* one kv head: no two threads share dK/dV */
+        const float* kh = kf + u * L * d;
+        const float* vh = vf + u * L * d;
+        int b = (int)(u / Hkv), hk = (int)(u % Hkv);
+        for (int g = 0; g < G; ++g) {
+            long bh = (long)b * Hq + hk * G + g;
+            for (long i = 0; i < L; ++i) {
+                long rid = bh * L + i;
+                const float* qrow = qf + rid * d; const float* dorow = dO + rid * d;
+                double D = 0.0;                                   /* D = rowsum(dO o O') */
+                for (int c = 0; c < d; ++c) D += (double)dorow[c] * Op[rid * d + c];
+                long kend = causal ? i + 1 : L;
+                for (long k0 = 0; k0 < kend; k0 += 16) {
+                    double P[16], Pf[16], dS[16];
+                    int nv = nvis_of(k0, kend);
+                    bwd_block(qrow, dorow, Lse[rid], D, kh, vh, k0, nv, d, rs,
+                              quant_p, scale_mode, P, Pf, dS);
+                    for (int k = 0; k < nv; ++k) {
+                        long kr = (u * L + k0 + k) * d;
+                        for (int c = 0; c < d; ++c) {
+                            dV[kr + c] += Pf[k] * (double)dorow[c];
+                            dQ[rid * d + c] += dS[k] * (double)kh[(k0 + k) * d + c];
+                            dK[kr + c] += dS[k] * (double)qrow[c];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* dQ for a list of query rows (flat ids as in oracle_fwd_rows); Lse_rows[nrows]
+ * and Op_rows[nrows,d] belong to the same list. */
+int oracle_bwd_dq_rows(const float* qf, const float* kf, const float* vf, const float* dO,
+                       int B, int Hq, int Hkv, long L, int d, int causal,
+                       int quant_p, int scale_mode,
+                       long nrows, const long* rows,
+                       const double* Lse_rows, const double* Op_rows, double* dQ_rows)
+{
+    if (!rows || Hq % Hkv) return -1;
+    (void)B;
+    const int G = Hq / Hkv;
+    const double rs = 1.0 / sqrt((double)d);
+    #pragma omp parallel for schedule(dynamic, 1)
+    for (long n = 0; n < nrows; ++n) {
+        long rid = rows[n]; long i = rid % L; long bh = rid / L;
+        int h = (int)(bh % Hq), b = (int)(bh / Hq);
+        const float* kh = kf + ((long)b * Hkv + h / G) * L * d;
+        const float* vh = vf + ((long)b * Hkv + h / G) * L * d;
+        const float* qrow = qf + rid * d; const float* dorow = dO + rid * d;
+        double D = 0.0;
+        for (int c = 0; c < d; ++c) D += (double)dorow[c] * Op_rows[n * d + c];
+        for (int c = 0; c < d; ++c) dQ_rows[n * d + c] = 0.0;
+        long kend = causal ? i + 1 : L;
+        for (long k0 = 0; k0 < kend; k0 += 16) {
+            double P[16], Pf[16], dS[16];
+            int nv = nvis_of(k0, kend);
+            bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, d, rs,
+                      quant_p, scale_mode, P, Pf, dS);
+            for (int k = 0; k < nv; ++k)
+                for (int c = 0; c < d; ++c)
+                    dQ_rows[n * d + c] += dS[k] * (double)kh[(k0 + k) * d + c];
+        }
+    }
+    return 0;
+}
+
+/* dK and dV for a list of key rows of ONE kv head (b, hk).  Lse_grp[G,L] and
+ * Op_grp[G,L,d] hold L and O' of every query row of the G = Hq/Hkv query heads
+ * that read this kv head.  Pf_dump (optional) [nkeys, G, L] receives P^F[i, key]. */
+int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, const float* dO,
+                         int B, int Hq, int Hkv, long L, int d, int causal,
+                         int quant_p, int scale_mode,
+                         int b, int hk, long nkeys, const long* keys,
+                         const double* Lse_grp, const double* Op_grp,
+                         double* dK_keys, double* dV_keys, float* Pf_dump)
+{
+    if (!keys || Hq % Hkv || b < 0 || b >= B || hk < 0 || hk >= Hkv) return -1;
+    const int G = Hq / Hkv;
+    const double rs = 1.0 / sqrt((double)d);
+    const float* kh = kf + ((long)b * Hkv + hk) * L * d;
+    const float* vh = vf + ((long)b * Hkv + hk) * L * d;
+    /* D for every query row of the group */
+    double* Dg = (double*)malloc(sizeof(double) * (size_t)G * L);
+    if (!Dg) return -2;
+    #pragma omp parallel for schedule(static)
+    for (long r = 0; r < (long)G * L; ++r) {
+        long rid = ((long)b * Hq + hk * G) * L + r;
+        double D = 0.0;
+        for (int c = 0; c < d; ++c) D += (double)dO[rid * d + c] * Op_grp[r * d + c];
+        Dg[r] = D;
+    }
+    #pragma omp parallel for schedule(dynamic, 1)
+    for (long n = 0; n < nkeys; ++n) {
+        long key = keys[n]; long k0 = key - key % 16; int kk = (int)(key - k0);
+        for (int c = 0; c < d; ++c) { dK_keys[n * d + c] = 0.0; dV_keys[n * d + c] = 0.0; }
+        for (int g = 0; g < G; ++g) {
+            for (long i = 0; i < L; ++i) {
+                long kend = causal ? i + 1 : L;
+                if (Pf_dump) Pf_dump[(n * G + g) * L + i] = 0.0f;
+                if (key >= kend) continue;
+                long rid = ((long)b * Hq + hk * G + g) * L + i;
+                double P[16], Pf[16], dS[16];
+                bwd_block(qf + rid * d, dO + rid * d, Lse_grp[g * L + i], Dg[g * L + i],
+                          kh, vh, k0, nvis_of(k0, kend), d, rs, quant_p, scale_mode, P, Pf, dS);
+                for (int c = 0; c < d; ++c) {
+                    dV_keys[n * d + c] += Pf[kk] * (double)dO[rid * d + c];
+                    dK_keys[n * d + c] += dS[kk] * (double)qf[rid * d + c];
+                }
+                if (Pf_dump) Pf_dump[(n * G + g) * L + i] = (float)Pf[kk];
+            }
+        }
+    }
+    free(Dg);
+    return 0;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

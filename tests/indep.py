@@ -1,0 +1,118 @@
+"""Independent re-derivations used only to pin the oracle (never imported by it).
+
+Two implementations of phi (Eq. 1, Eq. 2 with an E4M3 block scale):
+  * ``phi_block_exact``: pure Python on ``fractions.Fraction`` -- every rounding
+    decision is taken on exact rationals by nearest-value search with
+    ties-to-even, no thresholds;
+  * ``fake_quant_np``: vectorised numpy; the E4M3 grid comes from torch's own
+    float8_e4m3fn decoder (a library table), decisions by ``searchsorted``.
+and a row-at-a-time numpy transcription of the training forward (Alg. 2).
+"""
+from fractions import Fraction
+
+import numpy as np
+import torch
+
+E2M1 = [Fraction(0), Fraction(1, 2), Fraction(1), Fraction(3, 2),
+        Fraction(2), Fraction(3), Fraction(4), Fraction(6)]
+
+
+def e4m3_grid_torch():
+    """All finite non-negative E4M3 values (bytes 0x00..0x7E) decoded by torch."""
+    b = torch.arange(0, 0x7F, dtype=torch.uint8)
+    return b.view(torch.float8_e4m3fn).to(torch.float64).numpy()
+
+
+_E4M3_FR = None
+
+
+def e4m3_grid_exact():
+    global _E4M3_FR
+    if _E4M3_FR is None:
+        vals = []
+        for byte in range(0x7F):
+            e, m = byte >> 3, byte & 7
+            if e == 0:
+                vals.append(Fraction(m, 8) * Fraction(1, 64))
+            else:
+                vals.append((1 + Fraction(m, 8)) * (Fraction(2) ** (e - 7)))
+        _E4M3_FR = vals
+    return _E4M3_FR
+
+
+def nearest_even_index(x: Fraction, grid) -> int:
+    """Index of the grid value nearest to x; ties to the even index; saturating."""
+    best, bi = None, 0
+    for i, g in enumerate(grid):
+        dist = abs(x - g)
+        if best is None or dist < best or (dist == best and i % 2 == 0 and bi % 2 == 1):
+            best, bi = dist, i
+    return bi
+
+
+def phi_block_exact(xs):
+    """xs: list of python floats (<=16). Returns (codes, scale_byte, dequantized Fractions)."""
+    fx = [Fraction(float(x)) for x in xs]
+    amax = max(abs(f) for f in fx) if fx else Fraction(0)
+    sb = nearest_even_index(amax / 6, e4m3_grid_exact())
+    s = e4m3_grid_exact()[sb]
+    codes, deq = [], []
+    for x, f in zip(xs, fx):
+        sign = 8 if np.signbit(np.float64(x)) else 0
+        mag = nearest_even_index(abs(f) / s, E2M1) if s > 0 else 0
+        codes.append(sign | mag)
+        deq.append((-1 if sign else 1) * s * E2M1[mag])
+    return codes, sb, deq
+
+
+def fake_quant_np(x, axis=-1):
+    """phi^-1(phi(x)) in float64 along ``axis`` in aligned blocks of 16 (zero padded)."""
+    x = np.moveaxis(np.asarray(x, dtype=np.float64), axis, -1)
+    n = x.shape[-1]
+    pad = (-n) % 16
+    xp = np.concatenate([x, np.zeros(x.shape[:-1] + (pad,))], axis=-1) if pad else x
+    blk = xp.reshape(xp.shape[:-1] + (-1, 16))
+    amax = np.abs(blk).max(axis=-1)
+    grid = e4m3_grid_torch()
+    mid6 = 6.0 * 0.5 * (grid[:-1] + grid[1:])             # exact in fp64
+    lo = np.searchsorted(mid6, amax, side="left")          # # of midpoints < amax
+    on_tie = (lo < mid6.size) & (mid6[np.minimum(lo, mid6.size - 1)] == amax)
+    idx = np.where(on_tie & (lo % 2 == 1), lo + 1, lo)     # at a tie pick the even byte
+    s = grid[idx][..., None]
+    vals = np.array([0, .5, 1, 1.5, 2, 3, 4, 6.0])
+    mids = 0.5 * (vals[:-1] + vals[1:])
+    a = np.abs(blk)
+    thr = mids[None, :] * s[..., None]                     # [..., 1, 7] exact products
+    gt = (a[..., None] > thr).sum(-1)
+    eq = (a[..., None] == thr)
+    tie_idx = np.argmax(eq, axis=-1)
+    has_tie = eq.any(-1)
+    mag = np.where(has_tie, np.where(tie_idx % 2 == 1, tie_idx + 1, tie_idx), gt)
+    mag = np.where(s > 0, mag, 0)
+    out = np.sign(blk) * s * vals[mag]
+    out = out.reshape(xp.shape)[..., :n]
+    return np.moveaxis(out, -1, axis)
+
+
+def attn_fwd_rowwise_np(qf, kf, vf, causal, Bk, quant_p=True):
+    """Alg. 2, one query row at a time, numpy float64; inputs already fake-quantized.
+    qf [L,d], kf/vf [L,d] (one head).  Returns O, O', Lse."""
+    L, d = qf.shape
+    O = np.zeros((L, d)); Op = np.zeros((L, d)); Lse = np.zeros(L)
+    for i in range(L):
+        m, l = -np.inf, 0.0
+        o = np.zeros(d); op = np.zeros(d)
+        kend = i + 1 if causal else L
+        for k0 in range(0, kend, Bk):
+            k1 = min(k0 + Bk, kend)
+            s = (kf[k0:k1] @ qf[i]) / np.sqrt(d)
+            mnew = max(m, s.max())
+            alpha = 0.0 if m == -np.inf else np.exp(m - mnew)
+            pt = np.exp(s - mnew).astype(np.float32).astype(np.float64)
+            pf = fake_quant_np(pt) if quant_p else pt      # blocks start at k0 (multiple of 16)
+            l = alpha * l + pt.sum()
+            o = alpha * o + pf @ vf[k0:k1]
+            op = alpha * op + pt @ vf[k0:k1]
+            m = mnew
+        O[i], Op[i], Lse[i] = o / l, op / l, m + np.log(l)
+    return O, Op, Lse
