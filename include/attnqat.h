@@ -1,0 +1,128 @@
+/*
+ * attnqat.h -- C ABI of the MI355X (gfx950) Attn-QAT hot path.
+ *
+ * NVFP4 fake-quantized attention: E2M1 elements with one E4M3 scale per 16
+ * elements (Sec. 3.1, Eq. 1-2), the inference forward (Alg. 1), the training
+ * forward that also emits the high-precision output O' (Alg. 2) and the
+ * backward that re-quantizes the recomputed P and takes D from O' (Alg. 3).
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a caller-owned DEVICE pointer (HBM).  Nothing is
+ *     allocated, freed or synchronised here: kernels are enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call
+ *     returns.  Scratch memory comes in through `workspace`; ask
+ *     attnqat_workspace_bytes() for its size.  The workspace may be reused by
+ *     the next call on the same stream.
+ *   - Tensors are contiguous, [B, H, L, d] with d innermost.  q/o/d_o/dq/o_hp
+ *     have H = Hq heads; k/v/dk/dv have H = Hkv heads; Hq % Hkv == 0 and query
+ *     head h reads kv head h / (Hq/Hkv) (grouped-query attention).
+ *   - L is both the query and the key length.  d is 64 or 128.
+ *   - dtype: ATTNQAT_BF16 (the only supported storage type of q,k,v,d_o and
+ *     of o,dq,dk,dv).  lse is fp32, o_hp is fp32.
+ *   - causal != 0: query i sees keys 0..i.
+ *   - Return value: ATTNQAT_OK or a negative ATTNQAT_E* code; on error no
+ *     kernel has been enqueued.  attnqat_strerror() names a code.
+ *   - P is quantized in groups of 16 consecutive keys aligned to absolute key
+ *     indices that are multiples of 16; key tiles of attnqat_block_k() keys are
+ *     visited in increasing order and P-tilde of a tile is quantized against
+ *     the running row maximum after that tile (Alg. 1/2 inner loop).  The key
+ *     tile size therefore is part of the forward's definition.
+ */
+#ifndef ATTNQAT_H
+#define ATTNQAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ATTNQAT_OK                  0
+#define ATTNQAT_EINVAL             -1   /* null pointer, non-positive size            */
+#define ATTNQAT_ESHAPE             -2   /* d not in {64,128}, Hq % Hkv != 0, L too big */
+#define ATTNQAT_EDTYPE             -3   /* dtype other than ATTNQAT_BF16              */
+#define ATTNQAT_EWORKSPACE         -4   /* workspace null or smaller than required    */
+#define ATTNQAT_ELAUNCH            -5   /* the HIP runtime refused a launch           */
+
+#define ATTNQAT_BF16                0
+
+#define ATTNQAT_WS_FWD              0   /* attnqat_fwd                                 */
+#define ATTNQAT_WS_FWD_INFER        1   /* attnqat_fwd_infer                           */
+#define ATTNQAT_WS_BWD              2   /* attnqat_bwd                                 */
+
+/*
+ * phi of Eq. 1 (Sec. 3.1) along d: for every 16 consecutive elements
+ *   scale = RNE_E4M3(max|x| / 6)   (saturating at 448; a scale of 0 zeroes the block)
+ *   code  = sign | RNE_E2M1(|x| / scale)   (ties to even, saturating at 6)
+ * x       [B,H,L,d] bf16 (device, read)
+ * codes   [B,H,L,d/2] bytes (device, written): element 2k in bits 3:0, 2k+1 in bits 7:4;
+ *         a code is sign<<3 | index into {0,.5,1,1.5,2,3,4,6}
+ * scales  [B,H,L,d/16] E4M3 bytes (device, written)
+ * xf      optional [B,H,L,d] bf16 (device, written): phi^-1(phi(x)) of Eq. 2; may be NULL
+ * codes and scales may be NULL when only xf is wanted.
+ */
+int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
+                     uint8_t* codes, uint8_t* scales, void* xf, void* stream);
+
+/*
+ * Training forward, Alg. 2: fake-quantizes q, k, v, runs the online-softmax
+ * recurrence with P-tilde fake-quantized before P.V, and also accumulates
+ * O' = sum P-tilde V^F with the un-quantized P-tilde.
+ * q [B,Hq,L,d], k,v [B,Hkv,L,d] bf16 (read)
+ * o    [B,Hq,L,d] bf16 (written)      lse [B,Hq,L] fp32 (written, natural log)
+ * o_hp [B,Hq,L,d] fp32 (written): O', for attnqat_bwd only
+ */
+int attnqat_fwd(const void* q, const void* k, const void* v,
+                int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                void* o, float* lse, float* o_hp,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Inference forward, Alg. 1 (the same O and lse as attnqat_fwd by Eq. 3 == Eq. 4,
+ * without O').  The Q/K/V quantization pass is part of the call.
+ */
+int attnqat_fwd_infer(const void* q, const void* k, const void* v,
+                      int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                      void* o, float* lse,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward, Alg. 3, with straight-through estimation (Eq. 5):
+ *   D = rowsum(dO o O');  P = exp(S - lse);  P^F = phi^-1(phi(P));
+ *   dV = P^F^T dO;  dP = dO V^F^T;  dS = P o (dP - D)/sqrt(d);  dQ = dS K^F;  dK = dS^T Q^F.
+ * q,k,v are the un-quantized inputs of the forward (they are fake-quantized
+ * again here, which is bit-identical); d_o [B,Hq,L,d] bf16; lse and o_hp are
+ * the forward's outputs.  dq [B,Hq,L,d], dk,dv [B,Hkv,L,d] bf16 (written; dk and
+ * dv are summed over the Hq/Hkv query heads of a group).
+ */
+int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
+                const float* lse, const float* o_hp,
+                int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                void* dq, void* dk, void* dv,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace the call named by `which` (ATTNQAT_WS_*) needs; 0 for bad arguments. */
+size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d);
+
+/* The key tile size B_k of Alg. 1/2 that the forward kernels implement. */
+int attnqat_block_k(void);
+
+/* Static, NUL-terminated description of a return code. */
+const char* attnqat_strerror(int code);
+
+/*
+ * Test hook: attnqat_fwd_infer that also writes the dequantized P-tilde^F that
+ * entered the O update, for the 128 query rows [row0, row0+128) of every head
+ * (row0 a multiple of 128): p_dump [B,Hq,128,L] fp32 (device, written; rows
+ * beyond L and masked keys get 0).
+ */
+int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
+                        int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                        void* o, float* lse, int row0, float* p_dump,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTNQAT_H */

@@ -1,0 +1,169 @@
+"""Thin Python binding of the gfx950 Attn-QAT C ABI (``include/attnqat.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libattnqat.so``.  PyTorch supplies device memory and the current stream.
+There is no CPU or PyTorch fallback: if the shared library is missing, loading
+fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattnqat.so")
+
+OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4, -5
+BF16 = 0
+WS_FWD, WS_FWD_INFER, WS_BWD = 0, 1, 2
+
+_vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+_SIGNATURES = {
+    "attnqat_quantize": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "attnqat_fwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_fwd_infer": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
+                         _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
+    "attnqat_block_k": (_i, []),
+    "attnqat_strerror": (ctypes.c_char_p, [_i]),
+    "attnqat_debug_fwd_p": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
+                                 _vp, _sz, _vp]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+_lib = None
+
+
+class AttnQatError(RuntimeError):
+    pass
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise AttnQatError(
+                f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "(hipcc --offload-arch=gfx950). There is no fallback path.")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise AttnQatError(f"attnqat error {rc}: {lib().attnqat_strerror(rc).decode()}")
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev_bf16(t, name):
+    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+        raise AttnQatError(f"{name} must be a contiguous 4-d bf16 CUDA tensor [B,H,L,d]")
+
+
+def block_k() -> int:
+    return lib().attnqat_block_k()
+
+
+def workspace_bytes(which: int, B: int, Hq: int, Hkv: int, L: int, d: int) -> int:
+    return lib().attnqat_workspace_bytes(which, B, Hq, Hkv, L, d)
+
+
+def _workspace(which, B, Hq, Hkv, L, d, workspace):
+    need = workspace_bytes(which, B, Hq, Hkv, L, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+    return workspace, workspace.numel()
+
+
+def attnqat_quantize(x, want_codes=True, want_xf=True):
+    """phi of Eq. 1 along d.  Returns (codes u8 [B,H,L,d/2], scales u8 [B,H,L,d/16], xf bf16)."""
+    _dev_bf16(x, "x")
+    B, H, L, d = x.shape
+    codes = torch.empty((B, H, L, d // 2), dtype=torch.uint8, device=x.device) if want_codes else None
+    scales = torch.empty((B, H, L, d // 16), dtype=torch.uint8, device=x.device) if want_codes else None
+    xf = torch.empty_like(x) if want_xf else None
+    _check(lib().attnqat_quantize(_ptr(x), B, H, L, d, BF16, _ptr(codes), _ptr(scales), _ptr(xf), _stream()))
+    return codes, scales, xf
+
+
+def attnqat_fwd(q, k, v, causal: bool, workspace=None, out=None):
+    """Alg. 2.  Returns (o bf16, lse fp32 [B,Hq,L], o_hp fp32)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+        o_hp = torch.empty((B, Hq, L, d), dtype=torch.float32, device=q.device)
+    else:
+        o, lse, o_hp = out
+    ws, nb = _workspace(WS_FWD, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_fwd(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+                             _ptr(o), _ptr(lse), _ptr(o_hp), _ptr(ws), nb, _stream()))
+    return o, lse, o_hp
+
+
+def attnqat_fwd_infer(q, k, v, causal: bool, workspace=None, out=None):
+    """Alg. 1.  Returns (o bf16, lse fp32)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_fwd_infer(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+                                   _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
+    return o, lse
+
+
+def attnqat_bwd(q, k, v, d_o, lse, o_hp, causal: bool, workspace=None, out=None):
+    """Alg. 3.  Returns (dq, dk, dv) bf16."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (d_o, "d_o")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if not (lse.dtype == torch.float32 and lse.is_contiguous() and o_hp.dtype == torch.float32
+            and o_hp.is_contiguous()):
+        raise AttnQatError("lse and o_hp must be contiguous fp32 tensors")
+    if out is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    else:
+        dq, dk, dv = out
+    ws, nb = _workspace(WS_BWD, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(o_hp),
+                             B, Hq, Hkv, L, d, int(causal), BF16,
+                             _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), nb, _stream()))
+    return dq, dk, dv
+
+
+def attnqat_debug_fwd_p(q, k, v, causal: bool, row0: int):
+    """Test hook: (o, lse, P-tilde^F fp32 [B,Hq,128,L]) for query rows [row0, row0+128)."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+    p = torch.empty((B, Hq, 128, L), dtype=torch.float32, device=q.device)
+    ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, None)
+    _check(lib().attnqat_debug_fwd_p(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+                                     _ptr(o), _ptr(lse), row0, _ptr(p), _ptr(ws), nb, _stream()))
+    return o, lse, p

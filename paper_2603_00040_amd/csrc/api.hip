@@ -1,0 +1,175 @@
+// extern "C" boundary: argument checks, workspace carving, kernel sequencing.
+#include "../../include/attnqat.h"
+#include "common.hpp"
+#include "kernels.hpp"
+
+using namespace aq;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Carver {
+    unsigned char* base; size_t off;
+    void* take(size_t bytes) { void* p = base ? base + off : nullptr; off += align_up(bytes); return p; }
+};
+
+int check_dims(int B, int Hq, int Hkv, int L, int d, int dtype)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || L < 1) return ATTNQAT_EINVAL;
+    if (dtype != ATTNQAT_BF16) return ATTNQAT_EDTYPE;
+    if ((d != 64 && d != 128) || Hq % Hkv != 0) return ATTNQAT_ESHAPE;
+    if (L > (1 << 20)) return ATTNQAT_ESHAPE;
+    const long long nqt = (long long)round_up(L, kRowPad) / 128;
+    if ((long long)B * Hq * nqt > 0x7FFFFFFFLL || (long long)B * Hq > 65535) return ATTNQAT_ESHAPE;
+    return ATTNQAT_OK;
+}
+
+// Workspace of the forward: fp16 Q^F, K^F (row-major) and V^F^T.
+struct FwdWs { void *qh, *kh, *vt; size_t bytes; };
+FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d)
+{
+    const size_t Lp = round_up(L, kRowPad);
+    Carver c{(unsigned char*)ws, 0};
+    FwdWs w;
+    w.qh = c.take((size_t)B * Hq * Lp * d * 2);
+    w.kh = c.take((size_t)B * Hkv * Lp * d * 2);
+    w.vt = c.take((size_t)B * Hkv * Lp * d * 2);
+    w.bytes = c.off;
+    return w;
+}
+
+// Workspace of the backward: bf16 copies (dO is not exactly representable in fp16).
+struct BwdWs { void *qb, *kb, *vb, *kt, *qt, *dob, *dot; float* delta; size_t bytes; };
+BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
+{
+    const size_t Lp = round_up(L, kRowPad);
+    Carver c{(unsigned char*)ws, 0};
+    BwdWs w;
+    const size_t nq = (size_t)B * Hq * Lp * d * 2, nk = (size_t)B * Hkv * Lp * d * 2;
+    w.qb = c.take(nq); w.kb = c.take(nk); w.vb = c.take(nk);
+    w.kt = c.take(nk); w.qt = c.take(nq); w.dob = c.take(nq); w.dot = c.take(nq);
+    w.delta = (float*)c.take((size_t)B * Hq * Lp * 4);
+    w.bytes = c.off;
+    return w;
+}
+
+int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int Hkv, int L, int d,
+               int causal, int dtype, bool train, void* o, float* lse, float* o_hp,
+               int dump_row0, float* p_dump, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse || (train && !o_hp)) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d);
+    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    // Alg. 1 line "phi(Q), phi(K), phi(V)" / Alg. 2 line "Q^F, K^F, V^F"
+    if (launch_prep(q, B * Hq, L, d, true, true, nullptr, nullptr, nullptr, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(k, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, w.kh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(v, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
+    if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, o, lse, o_hp, dump_row0, p_dump, st))
+        return ATTNQAT_ELAUNCH;
+    return ATTNQAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int attnqat_block_k(void) { return kBlockK; }
+
+const char* attnqat_strerror(int code)
+{
+    switch (code) {
+    case ATTNQAT_OK:         return "ok";
+    case ATTNQAT_EINVAL:     return "invalid argument (null pointer or non-positive size)";
+    case ATTNQAT_ESHAPE:     return "unsupported shape (d must be 64 or 128, Hq % Hkv == 0, L <= 2^20)";
+    case ATTNQAT_EDTYPE:     return "unsupported dtype (only ATTNQAT_BF16)";
+    case ATTNQAT_EWORKSPACE: return "workspace missing or too small (see attnqat_workspace_bytes)";
+    case ATTNQAT_ELAUNCH:    return "kernel launch failed";
+    default:                 return "unknown error code";
+    }
+}
+
+size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d)
+{
+    if (check_dims(B, Hq, Hkv, L, d, ATTNQAT_BF16)) return 0;
+    switch (which) {
+    case ATTNQAT_WS_FWD:
+    case ATTNQAT_WS_FWD_INFER: return carve_fwd(nullptr, B, Hq, Hkv, L, d).bytes;
+    case ATTNQAT_WS_BWD:       return carve_bwd(nullptr, B, Hq, Hkv, L, d).bytes;
+    default:                   return 0;
+    }
+}
+
+int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
+                     uint8_t* codes, uint8_t* scales, void* xf, void* stream)
+{
+    if (!x || (!codes && !scales && !xf)) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, H, H, L, d, dtype);
+    if (rc) return rc;
+    if (launch_prep(x, B * H, L, d, true, false, codes, scales, xf, nullptr, nullptr, (hipStream_t)stream))
+        return ATTNQAT_ELAUNCH;
+    return ATTNQAT_OK;
+}
+
+int attnqat_fwd(const void* q, const void* k, const void* v,
+                int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                void* o, float* lse, float* o_hp,
+                void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, true, o, lse, o_hp, 0, nullptr,
+                      workspace, workspace_bytes, stream);
+}
+
+int attnqat_fwd_infer(const void* q, const void* k, const void* v,
+                      int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                      void* o, float* lse,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, o, lse, nullptr, 0, nullptr,
+                      workspace, workspace_bytes, stream);
+}
+
+int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
+                        int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                        void* o, float* lse, int row0, float* p_dump,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!p_dump || row0 < 0 || row0 % 128 != 0) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    if (hipMemsetAsync(p_dump, 0, (size_t)B * Hq * 128 * L * sizeof(float), (hipStream_t)stream) != hipSuccess)
+        return ATTNQAT_ELAUNCH;
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, o, lse, nullptr, row0, p_dump,
+                      workspace, workspace_bytes, stream);
+}
+
+int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
+                const float* lse, const float* o_hp,
+                int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                void* dq, void* dk, void* dv,
+                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !d_o || !lse || !o_hp || !dq || !dk || !dv) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    BwdWs w = carve_bwd(workspace, B, Hq, Hkv, L, d);
+    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    // Q^F, K^F, V^F again (bit-identical to the forward's), plus transposed copies
+    if (launch_prep(q, B * Hq, L, d, true, false, nullptr, nullptr, nullptr, w.qb, w.qt, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(k, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.kb, w.kt, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(v, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, w.dot, st)) return ATTNQAT_ELAUNCH;
+    if (launch_delta(d_o, o_hp, B * Hq, L, d, w.delta, st)) return ATTNQAT_ELAUNCH;
+    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.kt, w.dob, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dq, st))
+        return ATTNQAT_ELAUNCH;
+    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.qt, w.dob, w.dot, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
+        return ATTNQAT_ELAUNCH;
+    return ATTNQAT_OK;
+}
+
+}  // extern "C"

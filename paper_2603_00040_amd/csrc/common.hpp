@@ -1,0 +1,82 @@
+// Shared device helpers for the gfx950 Attn-QAT kernels: vector types, the
+// NVFP4 rounding primitives (Sec. 3.1, Eq. 1-2) and the MFMA operand layouts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aq {
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+
+constexpr int kBlockK = 64;      // semantic key tile B_k of Alg. 1/2
+constexpr int kRowPad = 128;     // sequence lengths are padded to this in workspace copies
+
+__host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// ---- bf16 <-> fp32 (bit exact) -------------------------------------------
+__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ inline uint32_t pack_bf16x2_rne(float lo, float hi) {
+    return (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
+}
+__device__ inline uint32_t pack_f16x2(float lo, float hi) {
+    half2v h; h[0] = (half_t)lo; h[1] = (half_t)hi;      // RNE conversions
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// ---- NVFP4 rounding --------------------------------------------------------
+// Round v >= 0 to the E4M3 grid (RNE; subnormal spacing 2^-9 below 2^-6) by adding
+// and subtracting 1.5 * 2^(e+20): an fp32 add rounds to nearest-even at exactly the
+// E4M3 spacing of v's binade.  The caller clamps to 448.
+__device__ inline float rne_e4m3_grid(float v) {
+    uint32_t e = __float_as_uint(v) & 0x7F800000u;
+    e = e > 0x3C800000u ? e : 0x3C800000u;                 // binades below 2^-6 share 2^-6's spacing
+    float c = __uint_as_float(e + 0x0A400000u);            // 1.5 * 2^(e+20)
+    return (v + c) - c;
+}
+// Round 0 <= r <= 6 to the E2M1 grid {0,.5,1,1.5,2,3,4,6} (RNE), same trick with
+// 1.5 * 2^(e+22); binades below 1 share the spacing 0.5.
+__device__ inline float rne_e2m1_grid(float r) {
+    uint32_t e = __float_as_uint(r) & 0x7F800000u;
+    e = e > 0x3F800000u ? e : 0x3F800000u;
+    float c = __uint_as_float(e + 0x0B400000u);            // 1.5 * 2^(e+22)
+    return (r + c) - c;
+}
+// E4M3 byte of a value already on the E4M3 grid (0 <= s <= 448).
+__device__ inline uint32_t e4m3_byte_of(float s) {
+    uint32_t u = __float_as_uint(s);
+    if (s < 0.015625f) return (uint32_t)(s * 512.0f);      // subnormal: m * 2^-9
+    return (((u >> 23) - 120u) << 3) | ((u >> 20) & 7u);
+}
+// E2M1 magnitude index (0..7) of a value already on the E2M1 grid.
+__device__ inline uint32_t e2m1_index_of(float q) {
+    return q < 1.0f ? (uint32_t)(q * 2.0f) : (__float_as_uint(q) >> 22) - 252u;
+}
+
+// Block scale of Eq. 1, exact: RNE_E4M3(amax/6) saturating at 448.  amax/6 is an IEEE
+// (correctly rounded) division; for bf16 amax no quotient lies within 2^-13 (relative)
+// of an E4M3 rounding boundary without being on it, so rounding the fp32 quotient
+// equals rounding the real one.
+__device__ inline float block_scale_exact(float amax) {
+    float v = amax / 6.0f;
+    v = v < 448.0f ? v : 448.0f;
+    return rne_e4m3_grid(v);
+}
+
+// ---- cross-lane: combine the two 32-lane halves of a wave -------------------
+__device__ inline float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
+__device__ inline float xhalf_sum(float x) { return x + __shfl_xor(x, 32); }
+
+}  // namespace aq

@@ -1,0 +1,34 @@
+// Host-side launchers of the gfx950 kernels (one translation unit each).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aq {
+
+// phi (+ layout copies).  x [BH, L, D] bf16.  Any output may be null.
+//   codes/scales/xf_pub: the public packed NVFP4 tensor and its bf16 dequantized copy
+//   xr [BH, Lp, D]: dequantized rows, zero padded to Lp = round_up(L, 128)
+//   xt [BH, D, Lp]: the same, transposed, sequence positions permuted inside groups of 16
+//   quant=false copies x unchanged (bf16 only).  out_f16 selects fp16 for xr/xt.
+int launch_prep(const void* x, int BH, int L, int D, bool quant, bool out_f16,
+                uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st);
+
+// Alg. 1 (train=false) / Alg. 2 (train=true) on fp16 copies made by launch_prep.
+int launch_fwd(const void* qh, const void* kh, const void* vt,
+               int B, int Hq, int Hkv, int L, int D, bool causal, bool train,
+               void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st);
+
+// D = rowsum(dO o O') (Alg. 3, first line).  d_o bf16, o_hp fp32, [rows, D]; delta [BHq, Lp].
+int launch_delta(const void* d_o, const float* o_hp, int BHq, int L, int D, float* delta, hipStream_t st);
+
+// Alg. 3, query-stationary pass: dQ.
+int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* kt, const void* dob,
+                  const float* lse, const float* delta,
+                  int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st);
+
+// Alg. 3, key-stationary pass: dK, dV (summed over the query heads of a group).
+int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* qt, const void* dob,
+                    const void* dot, const float* lse, const float* delta,
+                    int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st);
+
+}  // namespace aq

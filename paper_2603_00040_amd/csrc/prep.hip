@@ -1,0 +1,154 @@
+// phi of Eq. 1 / Eq. 2 (Sec. 3.1) as a streaming kernel, plus the layout copies the
+// attention kernels read: the first line of Alg. 1 (phi(Q), phi(K), phi(V)) and of
+// Alg. 2 (Q^F, K^F, V^F).  HBM-bandwidth bound.
+//
+// One thread owns one block of 16 consecutive d-elements (32 bytes in).  A workgroup
+// covers 64 sequence positions; the optional transposed copy goes through LDS so that
+// both the row-major and the transposed stores are 16-byte vectors.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace aq {
+
+// Position p (0..15) inside a group of 16 sequence positions of a transposed copy holds
+// sequence index perm16(p): quads 1 and 2 are exchanged.  A lane of a 32x32x16 MFMA
+// accumulator owns sequence indices {0-3, 8-11} (lanes 0-31) or {4-7, 12-15} (lanes
+// 32-63) of such a group, so with this order its 8 values pair with one contiguous
+// 16-byte run of the transposed operand.
+__host__ __device__ inline int perm16(int p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
+
+template <bool QUANT, bool OUT_F16>
+__global__ __launch_bounds__(256) void prep_kernel(
+    const uint16_t* __restrict__ x, int L, int Lp, int D,
+    uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint16_t* __restrict__ xf_pub,
+    uint16_t* __restrict__ xr, uint16_t* __restrict__ xt)
+{
+    __shared__ uint16_t tile[64][128 + 2];
+    const int bh = blockIdx.y;
+    const int l0 = blockIdx.x * 64;
+    const int nb = D / 16;                       // 16-element blocks per row
+    const size_t in_base = (size_t)bh * L * D;
+
+    for (int blk = threadIdx.x; blk < 64 * nb; blk += 256) {
+        const int row = blk / nb, cb = blk % nb;
+        const int l = l0 + row;
+        float v[16];
+        if (l < L) {
+            const uint4v* src = reinterpret_cast<const uint4v*>(x + in_base + (size_t)l * D + cb * 16);
+            uint4v a = src[0], b = src[1];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[2 * i]         = __uint_as_float(a[i] << 16);
+                v[2 * i + 1]     = __uint_as_float(a[i] & 0xFFFF0000u);
+                v[8 + 2 * i]     = __uint_as_float(b[i] << 16);
+                v[8 + 2 * i + 1] = __uint_as_float(b[i] & 0xFFFF0000u);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = 0.0f;
+        }
+
+        float xf[16];
+        if (QUANT) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
+            const float s = block_scale_exact(amax);
+            uint32_t clo = 0, chi = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t sign = __float_as_uint(v[i]) >> 31;
+                float q = 0.0f;
+                if (s > 0.0f) {
+                    // IEEE division then RNE to the E2M1 grid == RNE of the real quotient:
+                    // |x| has 8 significant bits and s has 4, so a quotient that is not on
+                    // a rounding boundary is at least 2^-9 (relative) away from it.
+                    float r = fabsf(v[i]) / s;
+                    r = r < 6.0f ? r : 6.0f;
+                    q = rne_e2m1_grid(r);
+                }
+                const uint32_t code = (sign << 3) | e2m1_index_of(q);
+                if (i < 8) clo |= code << (4 * i); else chi |= code << (4 * (i - 8));
+                const float d = q * s;                   // exact: <= 6 significant bits
+                xf[i] = sign ? -d : d;
+            }
+            if (l < L) {
+                if (codes) {
+                    uint2v c2; c2[0] = clo; c2[1] = chi;
+                    *reinterpret_cast<uint2v*>(codes + ((size_t)bh * L + l) * (D / 2) + cb * 8) = c2;
+                }
+                if (scales) scales[((size_t)bh * L + l) * nb + cb] = (uint8_t)e4m3_byte_of(s);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) xf[i] = v[i];
+        }
+
+        if (xf_pub && l < L) {                           // public bf16 copy, un-padded
+            uint4v o0, o1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                o0[i] = pack_bf16x2_rne(xf[2 * i], xf[2 * i + 1]);
+                o1[i] = pack_bf16x2_rne(xf[8 + 2 * i], xf[8 + 2 * i + 1]);
+            }
+            uint4v* dst = reinterpret_cast<uint4v*>(xf_pub + in_base + (size_t)l * D + cb * 16);
+            dst[0] = o0; dst[1] = o1;
+        }
+        // workspace copies: fp16 or bf16; both hold s*c exactly
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            w[i] = OUT_F16 ? pack_f16x2(xf[2 * i], xf[2 * i + 1]) : pack_bf16x2_rne(xf[2 * i], xf[2 * i + 1]);
+        if (xr) {                                        // row-major, rows padded to Lp with zeros
+            uint4v o0, o1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { o0[i] = w[i]; o1[i] = w[4 + i]; }
+            uint4v* dst = reinterpret_cast<uint4v*>(xr + ((size_t)bh * Lp + l) * D + cb * 16);
+            dst[0] = o0; dst[1] = o1;
+        }
+        if (xt) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                tile[row][cb * 16 + 2 * i]     = (uint16_t)(w[i] & 0xFFFFu);
+                tile[row][cb * 16 + 2 * i + 1] = (uint16_t)(w[i] >> 16);
+            }
+        }
+    }
+    if (xt) {
+        __syncthreads();
+        // transposed copy [bh][c][Lp]: 8 positions (16 bytes) per store
+        for (int ch = threadIdx.x; ch < D * 8; ch += 256) {
+            const int c = ch >> 3, kc = ch & 7;
+            uint4v o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int p0 = kc * 8 + 2 * j, p1 = p0 + 1;
+                const int r0 = (p0 & ~15) | perm16(p0 & 15), r1 = (p1 & ~15) | perm16(p1 & 15);
+                o[j] = (uint32_t)tile[r0][c] | ((uint32_t)tile[r1][c] << 16);
+            }
+            *reinterpret_cast<uint4v*>(xt + ((size_t)bh * D + c) * Lp + l0 + kc * 8) = o;
+        }
+    }
+}
+
+template <bool QUANT, bool OUT_F16>
+static int launch_prep_t(const void* x, int BH, int L, int D, uint8_t* codes, uint8_t* scales,
+                         void* xf_pub, void* xr, void* xt, hipStream_t st)
+{
+    const int Lp = round_up(L, kRowPad);
+    dim3 grid(Lp / 64, BH);
+    hipLaunchKernelGGL((prep_kernel<QUANT, OUT_F16>), grid, dim3(256), 0, st,
+                       (const uint16_t*)x, L, Lp, D, codes, scales, (uint16_t*)xf_pub,
+                       (uint16_t*)xr, (uint16_t*)xt);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_prep(const void* x, int BH, int L, int D, bool quant, bool out_f16,
+                uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st)
+{
+    if (quant) return out_f16 ? launch_prep_t<true, true>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st)
+                              : launch_prep_t<true, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st);
+    return launch_prep_t<false, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st);
+}
+
+}  // namespace aq
