@@ -1,0 +1,64 @@
+"""attnqat_bwd against the oracle (Alg. 3): GPU forward -> GPU backward vs oracle forward -> oracle backward."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from tests.gpu_util import f32, host, max_abs, random_inputs, rel_l2, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3     # rel-L2 per tensor; the bf16 rounding of the outputs alone is about 1.7e-3
+
+
+def _run(B, Hq, Hkv, L, d, causal, seed, **kw):
+    import paper_2603_00040_amd as aq
+    x = random_inputs(B, Hq, Hkv, L, d, seed, **kw)
+    q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
+    o, lse, ohp = aq.attnqat_fwd(q, k, v, causal)
+    dq, dk, dv = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
+    torch.cuda.synchronize()
+    fq, fk, fv, fdo = (f32(x[n]) for n in ("q", "k", "v", "do"))
+    rf = oracle.fwd(fq, fk, fv, causal, aq.block_k())
+    rb = oracle.bwd(fq, fk, fv, fdo, rf["L"], rf["Op"], causal)
+    r = {n: (rel_l2(host(t), rb[n], zero_rms=1e-2), max_abs(host(t), rb[n])) for n, t in (("dQ", dq), ("dK", dk), ("dV", dv))}
+    print(f"bwd B{B} Hq{Hq} Hkv{Hkv} L{L} d{d} causal{int(causal)}: " +
+          " ".join(f"{n} rel {a:.2e} max {b:.2e}" for n, (a, b) in r.items()), flush=True)
+    for n, (a, _) in r.items():
+        assert a <= TOL, (n, a)
+    # determinism: no atomics anywhere, a second call returns the same bits
+    dq2, dk2, dv2 = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
+    torch.cuda.synchronize()
+    assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
+
+
+def test_tiny_ref_config():
+    _run(1, 2, 2, 256, 64, False, seed=0)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("L", [1, 31, 64, 129, 300])
+def test_ragged_lengths_d128_gqa(L, causal):
+    _run(2, 4, 2, L, 128, causal, seed=200 + L, k_chan=4)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_d64_heavy_tails(causal):
+    _run(1, 3, 1, 333, 64, causal, seed=9, dist="t3", scale=0.5, tok_mod=50)
+
+
+def test_backward_with_oracle_forward_state():
+    """Feeding the oracle's L and O' (instead of the GPU forward's) isolates the backward."""
+    import paper_2603_00040_amd as aq
+    B, Hq, Hkv, L, d, causal = 1, 4, 2, 200, 128, True
+    x = random_inputs(B, Hq, Hkv, L, d, seed=31)
+    q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
+    fq, fk, fv, fdo = (f32(x[n]) for n in ("q", "k", "v", "do"))
+    rf = oracle.fwd(fq, fk, fv, causal, aq.block_k())
+    rb = oracle.bwd(fq, fk, fv, fdo, rf["L"], rf["Op"], causal)
+    lse = torch.from_numpy(rf["L"].astype(np.float32)).cuda()
+    ohp = torch.from_numpy(rf["Op"].astype(np.float32)).cuda()
+    dq, dk, dv = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
+    torch.cuda.synchronize()
+    for n, t in (("dQ", dq), ("dK", dk), ("dV", dv)):
+        assert rel_l2(host(t), rb[n]) <= TOL, n
