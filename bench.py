@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the Attn-QAT hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of seeded synthetic input that is
+already resident in HBM: the Q/K/V quantization passes, the training forward (Alg. 2) and
+the backward (Alg. 3) for a training workload, or quantization + inference forward
+(Alg. 1) for an inference workload.  Prints ONE JSON line.
+
+FLOP convention (model FLOPs): forward 4*B*Hq*L^2*d, backward 10*B*Hq*L^2*d, halved under
+a causal mask.  The roofline entry prices the dominant kernel by its ALGORITHMIC MFMA
+work (fwd_train 6, fwd_infer 4, bwd_dq 6, bwd_dkdv 8 times B*Hq*L^2*d; the extra low-order
+dS products and nothing else are overhead) against the dense 16-bit MFMA peak.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16 MFMA
+KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="dit720p_train",
+                    help="one of: tiny_ref dit480p_infer llm4k_gqa dit720p_train llm32k_gqa")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(heads shard across GPUs without communication, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2603_00040_amd as aq
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    w = W.by_name(args.workload)
+    train = w.passes == "fwd+bwd"
+    t0 = time.time()
+    x = W.make_inputs(w, with_do=train)
+    gen_s = time.time() - t0
+    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    do = dev(x["do"]) if train else None
+    B, Hq, Hkv, L, d = w.B, w.Hq, w.Hkv, w.L, w.d
+
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, L), dtype=torch.float32, device="cuda")
+    if train:
+        ohp = torch.empty((B, Hq, L, d), dtype=torch.float32, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws_bytes = max(aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d), aq.workspace_bytes(aq.WS_BWD, B, Hq, Hkv, L, d))
+    else:
+        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER, B, Hq, Hkv, L, d)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def fwd():
+        if train:
+            aq.attnqat_fwd(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
+        else:
+            aq.attnqat_fwd_infer(q, k, v, w.causal, workspace=ws, out=(o, lse))
+
+    def bwd():
+        aq.attnqat_bwd(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
+
+    def step():
+        fwd()
+        if train:
+            bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    aq.profile_enable(True)
+    kern_ms = {}
+    nprof = max(1, min(args.steps, 3))
+    for _ in range(nprof):
+        fwd(); torch.cuda.synchronize()
+        for name, ms in aq.profile_read():
+            kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
+        if train:
+            bwd(); torch.cuda.synchronize()
+            for name, ms in aq.profile_read():
+                kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
+    aq.profile_enable(False)
+
+    pair_flops = B * Hq * float(L) ** 2 * d * (0.5 if w.causal else 1.0)
+    step_flops = w.fwd_flops + (w.bwd_flops if train else 0.0)
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+    fwd_ms = kern_ms.get("prep_qkv", 0.0) + kern_ms.get("fwd_train", 0.0) + kern_ms.get("fwd_infer", 0.0)
+    dom = max((n for n in kern_ms if n in KERNEL_GEMMS), key=lambda n: kern_ms[n])
+    achieved = KERNEL_GEMMS[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel_ms": round(kern_ms[dom], 3),
+                "per_kernel": {n: {"ms": round(ms, 3),
+                                   "tflops": round(KERNEL_GEMMS[n] * pair_flops / (ms * 1e-3) / 1e12, 2)
+                                   if n in KERNEL_GEMMS else None} for n, ms in kern_ms.items()}}
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k())
+
+    out = {
+        "metric": "FP4-attention fwd+bwd TFLOPS (1 MI355X)" if train else "FP4-attention fwd TFLOPS (1 MI355X)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16/bf16 MFMA operands (exact NVFP4 values), fp32 accumulate and softmax",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
+                   "passes": w.passes, "block_k": aq.block_k(), "seed": w.seed},
+        "fwd_tflops": round(w.fwd_flops / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
+        "fwd_ms": round(fwd_ms, 3),
+        "frac_of_mfma_peak_model_flops": round(value / MFMA_PEAK_TFLOPS, 4),
+        "input_gen_s": round(gen_s, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w, x, train, target_s, block_k):
+    """Time the oracle (as it stands) on a bounded sample of the same workload: forward of
+    sampled query rows and, for training workloads, dQ of the same rows."""
+    import numpy as np
+
+    import oracle
+    import workloads as W
+    rng = np.random.default_rng(12345)
+    # one head keeps the host copies small; rows are spread over the whole sequence
+    b, h = 0, 0
+    hk = h // (w.Hq // w.Hkv)
+    f = {n: W.bf16_bits_to_f32(x[n][b:b + 1, (h if n in ("q", "do") else hk):(h if n in ("q", "do") else hk) + 1])
+         for n in x}
+    per_row = (4.0 + (6.0 if train else 0.0)) * w.L * w.d * (0.5 if w.causal else 1.0)
+
+    def run(n):
+        rows = np.sort(rng.choice(w.L, size=min(n, w.L), replace=False)).astype(np.int64)
+        t0 = time.perf_counter()
+        r = oracle.fwd(f["q"], f["k"], f["v"], w.causal, block_k, rows=rows)
+        if train:
+            oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal)
+        return rows.size, time.perf_counter() - t0
+
+    n0, t_pilot = run(32)
+    n = int(max(32, min(w.L, n0 * target_s / max(t_pilot, 1e-3))))
+    n, t = run(n)
+    return {"value": round(n * per_row / t / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{n} query rows of head (0,0), all {w.L} keys: oracle forward"
+                      + (" + oracle dQ (model FLOPs 4+6 per row-key-d; the dK/dV products are not in the sample)"
+                         if train else " (model FLOPs 4 per row-key-d)")
+                      + f", {t:.1f} s, includes phi of that head's Q/K/V"}
+
+
+if __name__ == "__main__":
+    main()

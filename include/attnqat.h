@@ -122,6 +122,19 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         void* o, float* lse, int row0, float* p_dump,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement hook (the kernels of Alg. 1-3 are enqueued back to back by one call, so a
+ * caller cannot bracket a single kernel with its own events).  While enabled, every entry
+ * point records a HIP event on `stream` before its first kernel and after each kernel; the
+ * events are created on first use and kept until the process ends (the one exception to
+ * "nothing is allocated").  attnqat_profile_read() must follow a synchronisation of that
+ * stream; it returns the number of kernels of the most recent call and fills ms[i] with
+ * the time between consecutive events and names[i] (may be NULL) with a static label.
+ * Not thread safe; off by default.
+ */
+int attnqat_profile_enable(int on);
+int attnqat_profile_read(int max_entries, float* ms, const char** names);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,8 @@ _SIGNATURES = {
     "attnqat_strerror": (ctypes.c_char_p, [_i]),
     "attnqat_debug_fwd_p": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
                                  _vp, _sz, _vp]),
+    "attnqat_profile_enable": (_i, [_i]),
+    "attnqat_profile_read": (_i, [_i, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -167,3 +169,17 @@ def attnqat_debug_fwd_p(q, k, v, causal: bool, row0: int):
     _check(lib().attnqat_debug_fwd_p(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                      _ptr(o), _ptr(lse), row0, _ptr(p), _ptr(ws), nb, _stream()))
     return o, lse, p
+
+
+def profile_enable(on: bool):
+    _check(lib().attnqat_profile_enable(int(on)))
+
+
+def profile_read():
+    """[(kernel label, milliseconds)] of the most recent call; synchronise the stream first."""
+    ms = (ctypes.c_float * 16)()
+    names = (ctypes.c_char_p * 16)()
+    n = lib().attnqat_profile_read(16, ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(names, ctypes.c_void_p))
+    if n < 0:
+        _check(n)
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]

@@ -15,6 +15,33 @@ struct Carver {
     void* take(size_t bytes) { void* p = base ? base + off : nullptr; off += align_up(bytes); return p; }
 };
 
+// Optional per-kernel timing: HIP events recorded on the launch stream after every kernel.
+struct Prof {
+    bool on = false;
+    bool created = false;
+    int n = 0;
+    hipEvent_t ev[16];
+    const char* name[16];
+} g_prof;
+
+void prof_begin(hipStream_t st)
+{
+    if (!g_prof.on) return;
+    if (!g_prof.created) {
+        for (auto& e : g_prof.ev) if (hipEventCreate(&e) != hipSuccess) { g_prof.on = false; return; }
+        g_prof.created = true;
+    }
+    g_prof.n = 0;
+    g_prof.name[0] = "begin";
+    (void)hipEventRecord(g_prof.ev[g_prof.n++], st);
+}
+void prof_mark(const char* name, hipStream_t st)
+{
+    if (!g_prof.on || g_prof.n >= 16) return;
+    g_prof.name[g_prof.n] = name;
+    (void)hipEventRecord(g_prof.ev[g_prof.n++], st);
+}
+
 int check_dims(int B, int Hq, int Hkv, int L, int d, int dtype)
 {
     if (B < 1 || Hq < 1 || Hkv < 1 || L < 1) return ATTNQAT_EINVAL;
@@ -65,12 +92,15 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
     FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d);
     if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
     // Alg. 1 line "phi(Q), phi(K), phi(V)" / Alg. 2 line "Q^F, K^F, V^F"
     if (launch_prep(q, B * Hq, L, d, true, true, nullptr, nullptr, nullptr, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(k, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, w.kh, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(v, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_qkv", st);
     if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, o, lse, o_hp, dump_row0, p_dump, st))
         return ATTNQAT_ELAUNCH;
+    prof_mark(train ? "fwd_train" : "fwd_infer", st);
     return ATTNQAT_OK;
 }
 
@@ -110,9 +140,29 @@ int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
     if (!x || (!codes && !scales && !xf)) return ATTNQAT_EINVAL;
     int rc = check_dims(B, H, H, L, d, dtype);
     if (rc) return rc;
+    prof_begin((hipStream_t)stream);
     if (launch_prep(x, B * H, L, d, true, false, codes, scales, xf, nullptr, nullptr, (hipStream_t)stream))
         return ATTNQAT_ELAUNCH;
+    prof_mark("quantize", (hipStream_t)stream);
     return ATTNQAT_OK;
+}
+
+int attnqat_profile_enable(int on)
+{
+    g_prof.on = on != 0;
+    g_prof.n = 0;
+    return ATTNQAT_OK;
+}
+
+int attnqat_profile_read(int max_entries, float* ms, const char** names)
+{
+    if (!ms || max_entries < 1) return ATTNQAT_EINVAL;
+    int n = 0;
+    for (int i = 1; i < g_prof.n && n < max_entries; ++i, ++n) {
+        if (hipEventElapsedTime(&ms[n], g_prof.ev[i - 1], g_prof.ev[i]) != hipSuccess) return ATTNQAT_ELAUNCH;
+        if (names) names[n] = g_prof.name[i];
+    }
+    return n;
 }
 
 int attnqat_fwd(const void* q, const void* k, const void* v,
@@ -159,16 +209,21 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
     BwdWs w = carve_bwd(workspace, B, Hq, Hkv, L, d);
     if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
     // Q^F, K^F, V^F again (bit-identical to the forward's), plus transposed copies
     if (launch_prep(q, B * Hq, L, d, true, false, nullptr, nullptr, nullptr, w.qb, w.qt, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(k, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.kb, w.kt, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(v, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, w.dot, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_qkvdo", st);
     if (launch_delta(d_o, o_hp, B * Hq, L, d, w.delta, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("delta", st);
     if (launch_bwd_dq(w.qb, w.kb, w.vb, w.kt, w.dob, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dq, st))
         return ATTNQAT_ELAUNCH;
+    prof_mark("bwd_dq", st);
     if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.qt, w.dob, w.dot, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
         return ATTNQAT_ELAUNCH;
+    prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;
 }
 

@@ -1,0 +1,41 @@
+"""The C-ABI library loads on a machine without a GPU and exports every declared symbol."""
+import ctypes
+import os
+import re
+
+import paper_2603_00040_amd as aq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "attnqat.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(attnqat_\w+)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    L = ctypes.CDLL(aq.LIB_PATH)
+    names = _declared()
+    assert {"attnqat_quantize", "attnqat_fwd", "attnqat_bwd", "attnqat_fwd_infer"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(aq.EXPORTS) == names          # the binding covers the same names
+
+
+def test_host_side_queries_need_no_gpu():
+    assert aq.block_k() == 64
+    assert aq.lib().attnqat_strerror(aq.ESHAPE).decode().startswith("unsupported shape")
+    # workspace: three fp16 copies padded to 128 rows (forward), eight bf16 copies + D (backward)
+    B, Hq, Hkv, L, d = 1, 4, 2, 300, 128
+    Lp = 384
+    assert aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d) == (Hq + 2 * Hkv) * Lp * d * 2
+    assert aq.workspace_bytes(aq.WS_BWD, B, Hq, Hkv, L, d) == (4 * Hq + 3 * Hkv) * Lp * d * 2 + Hq * Lp * 4
+    assert aq.workspace_bytes(aq.WS_FWD, B, Hq, 3, L, d) == 0
+    assert aq.workspace_bytes(99, B, Hq, Hkv, L, d) == 0
+
+
+def test_argument_validation_happens_before_any_gpu_call():
+    f = aq.lib().attnqat_fwd_infer
+    assert f(None, None, None, 1, 2, 2, 64, 128, 0, 0, None, None, None, 0, None) == aq.EINVAL
+    assert aq.lib().attnqat_quantize(None, 1, 1, 16, 64, 0, None, None, None, None) == aq.EINVAL
