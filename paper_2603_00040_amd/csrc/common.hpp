@@ -76,7 +76,47 @@ __device__ inline float block_scale_exact(float amax) {
 }
 
 // ---- cross-lane: combine the two 32-lane halves of a wave -------------------
-__device__ inline float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
-__device__ inline float xhalf_sum(float x) { return x + __shfl_xor(x, 32); }
+// v_permlane32_swap(a, b) exchanges a[32..63] with b[0..31]: called with (x, x) it returns
+// {x.lo, x.lo} and {x.hi, x.hi}, so one swap plus one ALU op reduces over the halves.
+__device__ inline float xhalf_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float xhalf_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// ---- phi^-1(phi(.)) of two P values with the hardware FP4 converts ------------
+// v_cvt_scalef32_pk_fp4_f32 rounds to E2M1 with ties-to-even and saturates at 6 (checked
+// against the threshold definition on the device, including +-3 ulp around every tie).
+// r0, r1 = p * (1/s);  returns the fp16 pair (s*c0, s*c1), exact in fp16.
+__device__ inline uint32_t fq_pair_f16(float r0, float r1, uint32_t s_f16x2) {
+    const uint32_t codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, r0, r1, 1.0f, 0);
+    const half2v c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 0);
+    const half2v s = __builtin_bit_cast(half2v, s_f16x2);
+    return __builtin_bit_cast(uint32_t, c * s);
+}
+// The same, returning the two dequantized values as fp32 (for bf16 consumers).
+__device__ inline void fq_pair_f32(float r0, float r1, float s, float& o0, float& o1) {
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const uint32_t codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, r0, r1, 1.0f, 0);
+    const float2v c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
+    o0 = c[0] * s; o1 = c[1] * s;
+}
+
+// ---- LDS tiles filled by direct global->LDS loads ------------------------------
+// global_load_lds_dwordx4 writes lane i's 16 bytes to (wave-uniform LDS base) + 16*i, so a
+// tile row cannot be padded; bank conflicts are avoided by an XOR swizzle of the 16-byte
+// chunk index instead.  CH = chunks per row (16: 256-byte rows, 8: 128-byte rows).
+template <int CH>
+__device__ inline int swz(int row, int chunk) {
+    return CH == 16 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
+}
+// One wave copies 1 KiB: LDS chunk slot (wave-uniform slot0 + lane) <- its global source.
+__device__ inline void async_copy16(const void* gsrc, void* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
 
 }  // namespace aq

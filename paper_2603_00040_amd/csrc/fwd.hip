@@ -2,7 +2,8 @@
 //
 // Work split: a workgroup of 4 waves owns 128 query rows of one head; each wave owns 32
 // of them.  Key tiles of B_k = 64 keys are visited in increasing order; K and V^T tiles
-// are staged through LDS (double buffered) and shared by the four waves.
+// are copied global->LDS directly (global_load_lds, double buffered, XOR-swizzled rows)
+// and shared by the four waves.
 //
 // MFMA shapes (v_mfma_f32_32x32x16_f16, fp32 accumulate).  All operands are the
 // dequantized NVFP4 values s*c, which fp16 represents exactly, so the products are those
@@ -22,12 +23,12 @@ namespace aq {
 
 template <int D>
 struct FwdSmem {
-    half_t k[2][64][D + 8];      // K tile, row = key; +16 B pad: conflict-free 16 B reads
-    half_t v[2][D][64 + 8];      // V^T tile, row = d
+    half_t k[2][64 * D];      // K tile [key][d], 16-byte chunks XOR-swizzled inside a row
+    half_t v[2][D * 64];      // V^T tile [d][key], likewise
 };
 
 template <int D, bool TRAIN, bool CAUSAL, bool DUMP>
-__global__ __launch_bounds__(256) void fwd_kernel(
+__global__ __launch_bounds__(256, 2) void fwd_kernel(
     const half_t* __restrict__ Qh, const half_t* __restrict__ Kh, const half_t* __restrict__ Vt,
     uint16_t* __restrict__ O, float* __restrict__ lse, float* __restrict__ Ohp,
     int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */, int dump_row0, float* __restrict__ pdump)
@@ -35,7 +36,8 @@ __global__ __launch_bounds__(256) void fwd_kernel(
     constexpr int DS = D / 16;      // contraction steps of S
     constexpr int MB = D / 32;      // 32-row blocks of O^T
     constexpr int KCH = D / 8;      // 16-byte chunks per K row
-    constexpr int NLD = (64 * KCH) / 256;   // chunks per thread per tile (K and V^T alike)
+    constexpr int KLD = KCH / 4;    // 1 KiB wave-loads per wave for the K tile
+    constexpr int VLD = D / 32;     // ... for the V^T tile
     extern __shared__ __align__(16) unsigned char smem_raw[];
     FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
 
@@ -47,9 +49,6 @@ __global__ __launch_bounds__(256) void fwd_kernel(
     const int bhkv = b * (Hq / G) + h / G;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
     const int q_row = qt * 128 + wave * 32 + ln;
-
-    const half_t* Kbase = Kh + (size_t)bhkv * Lp * D;
-    const half_t* Vbase = Vt + (size_t)bhkv * D * Lp;
 
     // Q^F operand: this lane's query row, d-slots 16*ds + 8*hf .. +7
     half8 qreg[DS];
@@ -63,23 +62,24 @@ __global__ __launch_bounds__(256) void fwd_kernel(
     const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;     // tiles this workgroup visits
     const int wave_qmax = qt * 128 + wave * 32 + 31;
 
-    uint4v kld[NLD], vld[NLD];
-    auto gload = [&](int j) {
-        const int k0 = j * 64;
+    // per-lane global sources of the direct-to-LDS tile loads (advance by one tile per step)
+    const half_t* ksrc[KLD];
+    const half_t* vsrc[VLD];
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int ch = tid + 256 * i;
-            kld[i] = *reinterpret_cast<const uint4v*>(Kbase + (size_t)(k0 + ch / KCH) * D + 8 * (ch % KCH));
-            vld[i] = *reinterpret_cast<const uint4v*>(Vbase + (size_t)(ch / 8) * Lp + k0 + 8 * (ch % 8));
-        }
-    };
-    auto sstore = [&](int buf) {
+    for (int i = 0; i < KLD; ++i) {
+        const int slot = 64 * (wave * KLD + i) + lane, r = slot / KCH, pc = slot % KCH;
+        ksrc[i] = Kh + ((size_t)bhkv * Lp + r) * D + 8 * swz<KCH>(r, pc);
+    }
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int ch = tid + 256 * i;
-            *reinterpret_cast<uint4v*>(&sm.k[buf][ch / KCH][8 * (ch % KCH)]) = kld[i];
-            *reinterpret_cast<uint4v*>(&sm.v[buf][ch / 8][8 * (ch % 8)]) = vld[i];
-        }
+    for (int i = 0; i < VLD; ++i) {
+        const int slot = 64 * (wave * VLD + i) + lane, r = slot / 8, pc = slot % 8;
+        vsrc[i] = Vt + ((size_t)bhkv * D + r) * Lp + 8 * swz<8>(r, pc);
+    }
+    auto issue_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < KLD; ++i) { async_copy16(ksrc[i], &sm.k[buf][512 * (wave * KLD + i)]); ksrc[i] += 64 * D; }
+#pragma unroll
+        for (int i = 0; i < VLD; ++i) { async_copy16(vsrc[i], &sm.v[buf][512 * (wave * VLD + i)]); vsrc[i] += 64; }
     };
 
     floatx16 o[MB], op[TRAIN ? MB : 1];
@@ -90,28 +90,27 @@ __global__ __launch_bounds__(256) void fwd_kernel(
     }
     float m = -INFINITY, lsum = 0.0f;     // lsum: this half-wave's part of l (same alpha in both halves)
 
-    gload(0);
-    sstore(0);
+    issue_tile(0);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     for (int j = 0; j < nkt; ++j) {
         const int buf = j & 1;
         const int k0 = j * 64;
-        if (j + 1 < nkt) gload(j + 1);
+        if (j + 1 < nkt) issue_tile(buf ^ 1);                    // lands while this tile is consumed
         const bool active = !CAUSAL || k0 <= wave_qmax;          // wave-uniform
 
-        floatx16 s[2];
-        uint32_t pq[2][8], pu[TRAIN ? 2 : 1][8];                 // packed fp16 P-tilde^F / P-tilde
-        float alpha = 1.0f;
         if (active) {
             // ---- S^T = K^F Q^F^T
+            floatx16 s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
+                const int r = 32 * kb + ln;
 #pragma unroll
                 for (int ds = 0; ds < DS; ++ds) {
-                    const half8 a = *reinterpret_cast<const half8*>(&sm.k[buf][32 * kb + ln][16 * ds + 8 * hf]);
+                    const half8 a = *reinterpret_cast<const half8*>(&sm.k[buf][(r * KCH + swz<KCH>(r, 2 * ds + hf)) * 8]);
                     s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[ds], s[kb], 0, 0, 0);
                 }
             }
@@ -128,14 +127,12 @@ __global__ __launch_bounds__(256) void fwd_kernel(
                     }
             }
             // ---- online softmax (Alg. 2: m_new, alpha, P-tilde, l)
-            float mt = -INFINITY;
+            float mt = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[kb][i]);
+            for (int i = 1; i < 16; ++i) mt = fmaxf(mt, fmaxf(s[0][i], s[1][i]));
             mt = xhalf_max(mt);
             const float mnew = fmaxf(m, mt);
-            alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
+            const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
             const float ms = mnew * c;
             m = mnew;
             float rs = 0.0f;
@@ -147,68 +144,61 @@ __global__ __launch_bounds__(256) void fwd_kernel(
                     rs += s[kb][i];
                 }
             lsum = lsum * alpha + rs;                           // un-quantized P-tilde
-            // ---- phi^-1(phi(P-tilde)): groups of 16 keys = registers 8g..8g+7 of both halves
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int g = 0; g < 2; ++g) {
-                    float amax = 0.0f;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, s[kb][8 * g + i]);
-                    amax = xhalf_max(amax);
-                    const float sc = rne_e4m3_grid(amax * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
-                    const float inv = sc > 0.0f ? __builtin_amdgcn_rcpf(sc) : 0.0f;
-                    float pf[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        pf[i] = rne_e2m1_grid(fminf(s[kb][8 * g + i] * inv, 6.0f)) * sc;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        pq[kb][4 * g + i] = pack_f16x2(pf[2 * i], pf[2 * i + 1]);
-                        if constexpr (TRAIN) pu[kb][4 * g + i] = pack_f16x2(s[kb][8 * g + 2 * i], s[kb][8 * g + 2 * i + 1]);
-                    }
-                    if constexpr (DUMP) {
-                        if (q_row >= dump_row0 && q_row < dump_row0 + 128 && q_row < L) {
-#pragma unroll
-                            for (int i = 0; i < 8; ++i) {
-                                const int key = k0 + 32 * kb + 16 * g + 8 * (i >> 2) + 4 * hf + (i & 3);
-                                if (key < L)
-                                    pdump[((size_t)bh * 128 + (q_row - dump_row0)) * L + key] = pf[i];
-                            }
-                        }
-                    }
-                }
-        }
-        // stage the next tile while this one is still being consumed
-        if (j + 1 < nkt) sstore(buf ^ 1);
-
-        if (active) {
-            // ---- rescale, exact no-op when no row of this wave moved its maximum
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+            // ---- rescale: exact no-op unless some row of this wave moved its maximum (rare
+            // after the first tiles), so it lives on the cold path
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0, 0)) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) { o[mb][i] *= alpha; if constexpr (TRAIN) op[mb][i] *= alpha; }
             }
-            // ---- O^T += V^F^T P-tilde^F^T ; O'^T += V^F^T P-tilde^T
+            // ---- per 16 keys: phi^-1(phi(P-tilde)), then O^T += V^F^T P-tilde^F^T and
+            //      O'^T += V^F^T P-tilde^T.  Keys of a group = registers 8g..8g+7 of both halves.
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 const int kb = ks >> 1, g = ks & 1;
-                uint4v bq; bq[0] = pq[kb][4 * g]; bq[1] = pq[kb][4 * g + 1]; bq[2] = pq[kb][4 * g + 2]; bq[3] = pq[kb][4 * g + 3];
-                const half8 bqh = __builtin_bit_cast(half8, bq);
-                half8 buh;
-                if constexpr (TRAIN) {
-                    uint4v bu; bu[0] = pu[kb][4 * g]; bu[1] = pu[kb][4 * g + 1]; bu[2] = pu[kb][4 * g + 2]; bu[3] = pu[kb][4 * g + 3];
-                    buh = __builtin_bit_cast(half8, bu);
+                float amax = s[kb][8 * g];
+#pragma unroll
+                for (int i = 1; i < 8; ++i) amax = fmaxf(amax, s[kb][8 * g + i]);
+                amax = xhalf_max(amax);
+                const float sc = rne_e4m3_grid(amax * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
+                const float inv = sc > 0.0f ? __builtin_amdgcn_rcpf(sc) : 0.0f;
+                const uint32_t sc2 = pack_f16x2(sc, sc);
+                uint4v bq, bu;
+                float pfv[DUMP ? 8 : 1];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p0 = s[kb][8 * g + 2 * i], p1 = s[kb][8 * g + 2 * i + 1];
+                    const uint32_t w = fq_pair_f16(p0 * inv, p1 * inv, sc2);
+                    bq[i] = w;
+                    if constexpr (TRAIN) bu[i] = pack_f16x2(p0, p1);
+                    if constexpr (DUMP) {
+                        const half2v pr = __builtin_bit_cast(half2v, w);
+                        pfv[2 * i] = (float)pr[0]; pfv[2 * i + 1] = (float)pr[1];
+                    }
                 }
+                if constexpr (DUMP) {
+                    if (q_row >= dump_row0 && q_row < dump_row0 + 128 && q_row < L) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const int key = k0 + 32 * kb + 16 * g + 8 * (i >> 2) + 4 * hf + (i & 3);
+                            if (key < L)
+                                pdump[((size_t)bh * 128 + (q_row - dump_row0)) * L + key] = pfv[i];
+                        }
+                    }
+                }
+                const half8 bqh = __builtin_bit_cast(half8, bq);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    const half8 a = *reinterpret_cast<const half8*>(&sm.v[buf][32 * mb + ln][16 * ks + 8 * hf]);
+                    const int r = 32 * mb + ln;
+                    const half8 a = *reinterpret_cast<const half8*>(&sm.v[buf][(r * 8 + swz<8>(r, 2 * ks + hf)) * 8]);
                     o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bqh, o[mb], 0, 0, 0);
-                    if constexpr (TRAIN) op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, buh, op[mb], 0, 0, 0);
+                    if constexpr (TRAIN)
+                        op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, __builtin_bit_cast(half8, bu), op[mb], 0, 0, 0);
                 }
             }
         }
+        __builtin_amdgcn_s_waitcnt(0);        // this wave's part of the next tile is in LDS
         __syncthreads();
     }
 
