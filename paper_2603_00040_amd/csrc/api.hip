@@ -67,16 +67,15 @@ FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     return w;
 }
 
-// Workspace of the backward: bf16 copies (dO is not exactly representable in fp16).
-struct BwdWs { void *qb, *kb, *vb, *kt, *qt, *dob, *dot; float* delta; size_t bytes; };
+// Workspace of the backward: bf16 row-major copies (dO is not exactly representable in fp16) and D.
+struct BwdWs { void *qb, *kb, *vb, *dob; float* delta; size_t bytes; };
 BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
 {
     const size_t Lp = round_up(L, kRowPad);
     Carver c{(unsigned char*)ws, 0};
     BwdWs w;
     const size_t nq = (size_t)B * Hq * Lp * d * 2, nk = (size_t)B * Hkv * Lp * d * 2;
-    w.qb = c.take(nq); w.kb = c.take(nk); w.vb = c.take(nk);
-    w.kt = c.take(nk); w.qt = c.take(nq); w.dob = c.take(nq); w.dot = c.take(nq);
+    w.qb = c.take(nq); w.kb = c.take(nk); w.vb = c.take(nk); w.dob = c.take(nq);
     w.delta = (float*)c.take((size_t)B * Hq * Lp * 4);
     w.bytes = c.off;
     return w;
@@ -210,18 +209,18 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
     if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
-    // Q^F, K^F, V^F again (bit-identical to the forward's), plus transposed copies
-    if (launch_prep(q, B * Hq, L, d, true, false, nullptr, nullptr, nullptr, w.qb, w.qt, st)) return ATTNQAT_ELAUNCH;
-    if (launch_prep(k, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.kb, w.kt, st)) return ATTNQAT_ELAUNCH;
+    // Q^F, K^F, V^F again (bit-identical to the forward's) and a zero-padded copy of dO
+    if (launch_prep(q, B * Hq, L, d, true, false, nullptr, nullptr, nullptr, w.qb, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(k, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.kb, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(v, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, w.dot, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
     if (launch_delta(d_o, o_hp, B * Hq, L, d, w.delta, st)) return ATTNQAT_ELAUNCH;
     prof_mark("delta", st);
-    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.kt, w.dob, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dq, st))
+    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dq, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
-    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.qt, w.dob, w.dot, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
+    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;

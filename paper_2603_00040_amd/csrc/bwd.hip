@@ -14,7 +14,10 @@
 //
 // As in the forward, S and dP are computed transposed ([key, query]) so that a lane owns
 // one query row: L_i, D_i are per-lane scalars and the 16-key blocks of phi(P) are
-// register reductions plus one exchange between the 32-lane halves.
+// register reductions plus one exchange between the 32-lane halves.  Tiles are copied
+// global->LDS directly (XOR-swizzled rows); operands that a product needs transposed
+// (K^T for dQ; Q and dO column-wise, P^F^T and dS^T for dK/dV) are read from the row-major
+// tiles with the LDS transpose read, so no transposed copy exists anywhere.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -74,19 +77,18 @@ int launch_delta(const void* d_o, const float* o_hp, int BHq, int L, int D, floa
 // ------------------------------------------------------------------ dQ pass
 template <int D>
 struct DqSmem {
-    uint16_t k[2][64][D + 8];       // K^F tile, row = key
-    uint16_t v[2][64][D + 8];       // V^F tile, row = key
-    uint16_t kt[2][D][64 + 8];      // K^F^T tile, row = d, keys permuted inside groups of 16
+    uint16_t k[2][64 * D];       // K^F tile [key][d], swizzled
+    uint16_t v[2][64 * D];       // V^F tile [key][d], swizzled
 };
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void bwd_dq_kernel(
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
-    const uint16_t* __restrict__ Kt, const uint16_t* __restrict__ dOb,
+    const uint16_t* __restrict__ dOb,
     const float* __restrict__ lse, const float* __restrict__ delta, uint16_t* __restrict__ dQ,
     int L, int Lp, int Hq, int G, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */)
 {
-    constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, NLD = (64 * KCH) / 256;
+    constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, KLD = KCH / 4;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
 
@@ -98,10 +100,6 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
     const int bhkv = b * (Hq / G) + h / G;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
     const int q_row = qt * 128 + wave * 32 + ln;
-
-    const uint16_t* Kbase = Kb + (size_t)bhkv * Lp * D;
-    const uint16_t* Vbase = Vb + (size_t)bhkv * Lp * D;
-    const uint16_t* Ktbase = Kt + (size_t)bhkv * D * Lp;
 
     uint4v qreg[DS], doreg[DS];
     {
@@ -119,24 +117,19 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
     const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;
     const int wave_qmax = qt * 128 + wave * 32 + 31;
 
-    uint4v kld[NLD], vld[NLD], tld[NLD];
-    auto gload = [&](int j) {
-        const int k0 = j * 64;
+    const uint16_t* ksrc[KLD];
+    const uint16_t* vsrc[KLD];
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int ch = tid + 256 * i;
-            kld[i] = *reinterpret_cast<const uint4v*>(Kbase + (size_t)(k0 + ch / KCH) * D + 8 * (ch % KCH));
-            vld[i] = *reinterpret_cast<const uint4v*>(Vbase + (size_t)(k0 + ch / KCH) * D + 8 * (ch % KCH));
-            tld[i] = *reinterpret_cast<const uint4v*>(Ktbase + (size_t)(ch / 8) * Lp + k0 + 8 * (ch % 8));
-        }
-    };
-    auto sstore = [&](int buf) {
+    for (int i = 0; i < KLD; ++i) {
+        const int slot = 64 * (wave * KLD + i) + lane, r = slot / KCH, pc = slot % KCH;
+        const size_t off = ((size_t)bhkv * Lp + r) * D + 8 * swz<KCH>(r, pc);
+        ksrc[i] = Kb + off; vsrc[i] = Vb + off;
+    }
+    auto issue_tile = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int ch = tid + 256 * i;
-            *reinterpret_cast<uint4v*>(&sm.k[buf][ch / KCH][8 * (ch % KCH)]) = kld[i];
-            *reinterpret_cast<uint4v*>(&sm.v[buf][ch / KCH][8 * (ch % KCH)]) = vld[i];
-            *reinterpret_cast<uint4v*>(&sm.kt[buf][ch / 8][8 * (ch % 8)]) = tld[i];
+        for (int i = 0; i < KLD; ++i) {
+            async_copy16(ksrc[i], &sm.k[buf][512 * (wave * KLD + i)]); ksrc[i] += 64 * D;
+            async_copy16(vsrc[i], &sm.v[buf][512 * (wave * KLD + i)]); vsrc[i] += 64 * D;
         }
     };
 
@@ -146,27 +139,29 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
 
-    gload(0);
-    sstore(0);
+    // lane roles of the transpose reads: r = lane in its group of 16, grp = which 16 columns
+    const int tr_r = lane & 15, tr_grp = (lane >> 4) & 1;
+
+    issue_tile(0);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     for (int j = 0; j < nkt; ++j) {
         const int buf = j & 1, k0 = j * 64;
-        if (j + 1 < nkt) gload(j + 1);
+        if (j + 1 < nkt) issue_tile(buf ^ 1);
         const bool active = !CAUSAL || k0 <= wave_qmax;
-        uint32_t dsh[2][8], dsl[2][8];
         if (active) {
             floatx16 s[2], dp[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { s[kb][i] = 0.0f; dp[kb][i] = 0.0f; }
+                const int r = 32 * kb + ln;
 #pragma unroll
                 for (int ds = 0; ds < DS; ++ds) {
-                    const uint4v ak = *reinterpret_cast<const uint4v*>(&sm.k[buf][32 * kb + ln][16 * ds + 8 * hf]);
-                    s[kb] = mfma_bf16(ak, qreg[ds], s[kb]);                  // S^T = K^F Q^F^T
-                    const uint4v av = *reinterpret_cast<const uint4v*>(&sm.v[buf][32 * kb + ln][16 * ds + 8 * hf]);
-                    dp[kb] = mfma_bf16(av, doreg[ds], dp[kb]);              // dP^T = V^F dO^T
+                    const int e = (r * KCH + swz<KCH>(r, 2 * ds + hf)) * 8;
+                    s[kb] = mfma_bf16(*reinterpret_cast<const uint4v*>(&sm.k[buf][e]), qreg[ds], s[kb]);     // S^T = K^F Q^F^T
+                    dp[kb] = mfma_bf16(*reinterpret_cast<const uint4v*>(&sm.v[buf][e]), doreg[ds], dp[kb]);  // dP^T = V^F dO^T
                 }
             }
             const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > qt * 128 + wave * 32);
@@ -183,30 +178,29 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
                     s[kb][i] = p * (dp[kb][i] - Dq) * rs;                          // dS, from the fp32 P
                 }
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint32_t hi = pack_bf16x2(s[kb][2 * i], s[kb][2 * i + 1]);
-                    dsh[kb][i] = hi;
-                    dsl[kb][i] = pack_bf16x2(s[kb][2 * i] - bf16_lo_f32(hi), s[kb][2 * i + 1] - bf16_hi_f32(hi));
-                }
-        }
-        if (j + 1 < nkt) sstore(buf ^ 1);
-        if (active) {
-#pragma unroll
             for (int ks = 0; ks < 4; ++ks) {                                       // dQ^T += K^F^T dS^T
                 const int kb = ks >> 1, g = ks & 1;
-                uint4v bh_, bl_;
+                uint4v bhi, blo;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { bh_[i] = dsh[kb][4 * g + i]; bl_[i] = dsl[kb][4 * g + i]; }
+                for (int i = 0; i < 4; ++i) {
+                    const float d0 = s[kb][8 * g + 2 * i], d1 = s[kb][8 * g + 2 * i + 1];
+                    const uint32_t hi = pack_bf16x2(d0, d1);
+                    bhi[i] = hi;
+                    blo[i] = pack_bf16x2(d0 - bf16_lo_f32(hi), d1 - bf16_hi_f32(hi));
+                }
+                const int key_a = 16 * ks + 4 * hf + (tr_r >> 2);                 // slots 0-3; +8: slots 4-7
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    const uint4v a = *reinterpret_cast<const uint4v*>(&sm.kt[buf][32 * mb + ln][16 * ks + 8 * hf]);
-                    acc[mb] = mfma_bf16(a, bh_, acc[mb]);
-                    acc[mb] = mfma_bf16(a, bl_, acc[mb]);
+                    const int col = 32 * mb + 16 * tr_grp + 4 * (tr_r & 3);
+                    const uint2v a0 = lds_read_tr16(&sm.k[buf][swz_elem<KCH>(key_a, col)]);
+                    const uint2v a1 = lds_read_tr16(&sm.k[buf][swz_elem<KCH>(key_a + 8, col)]);
+                    uint4v a; a[0] = a0[0]; a[1] = a0[1]; a[2] = a1[0]; a[3] = a1[1];
+                    acc[mb] = mfma_bf16(a, bhi, acc[mb]);
+                    acc[mb] = mfma_bf16(a, blo, acc[mb]);
                 }
             }
         }
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
 
@@ -225,7 +219,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
 }
 
 template <int D, bool CAUSAL>
-static int launch_dq_t(const void* qb, const void* kb, const void* vb, const void* kt, const void* dob,
+static int launch_dq_t(const void* qb, const void* kb, const void* vb, const void* dob,
                        const float* lse, const float* delta, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
@@ -235,45 +229,45 @@ static int launch_dq_t(const void* qb, const void* kb, const void* vb, const voi
         return -1;
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
-                       (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb, (const uint16_t*)kt,
+                       (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
                        (const uint16_t*)dob, lse, delta, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv,
                        1.4426950408889634f * rs, rs);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* kt, const void* dob,
+int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
                   const float* lse, const float* delta,
                   int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dq_t<128, true>(qb, kb, vb, kt, dob, lse, delta, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<128, false>(qb, kb, vb, kt, dob, lse, delta, B, Hq, Hkv, L, dq, st);
-    if (D == 64)  return causal ? launch_dq_t<64, true>(qb, kb, vb, kt, dob, lse, delta, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<64, false>(qb, kb, vb, kt, dob, lse, delta, B, Hq, Hkv, L, dq, st);
+    if (D == 128) return causal ? launch_dq_t<128, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st)
+                                : launch_dq_t<128, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st);
+    if (D == 64)  return causal ? launch_dq_t<64, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st)
+                                : launch_dq_t<64, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st);
     return -1;
 }
 
 // ------------------------------------------------------------------ dK/dV pass
 // A workgroup owns 128 keys of one kv head (32 per wave, held in registers as MFMA A
 // operands) and walks over the query rows of every query head of the group in tiles of 32.
+constexpr int kTPad = 36;            // row length (elements) of the per-wave [query][key] staging tiles
+
 template <int D>
 struct DkvSmem {
-    uint16_t q[2][32][D + 8];        // Q^F rows       (B operand of S^T)
-    uint16_t g[2][32][D + 8];        // dO rows        (B operand of dP^T)
-    uint16_t qt[2][D][32 + 8];       // Q^F^T          (B operand of dK), queries permuted in 16s
-    uint16_t gt[2][D][32 + 8];       // dO^T           (B operand of dV)
-    uint16_t t[4][3][32][32 + 8];    // per wave: P^F^T, dS_hi^T, dS_lo^T as [key][query] (A operands)
+    uint16_t q[2][32 * D];           // Q^F rows [query][d], swizzled
+    uint16_t g[2][32 * D];           // dO rows  [query][d], swizzled
+    uint16_t t[4][3][32 * kTPad];    // per wave: P^F, dS_hi, dS_lo as [query][key]
 };
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void bwd_dkdv_kernel(
+__global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
-    const uint16_t* __restrict__ Qt, const uint16_t* __restrict__ dOb, const uint16_t* __restrict__ dOt,
+    const uint16_t* __restrict__ dOb,
     const float* __restrict__ lse, const float* __restrict__ delta,
     uint16_t* __restrict__ dK, uint16_t* __restrict__ dV,
     int L, int Lp, int Hq, int G, float c, float rs)
 {
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
-    constexpr int NLD = (32 * KCH) / 256;            // 16-byte chunks per thread per tile
+    constexpr int TLD = KCH / 8;                     // 1 KiB wave-loads per wave per tile (32 rows)
     extern __shared__ __align__(16) unsigned char smem_raw[];
     DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
 
@@ -309,43 +303,44 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
     const int per_head = nq32 - qt_first;
     const int niter = per_head > 0 ? per_head * G : 0;
 
-    uint4v ql[NLD], gl[NLD], qtl[NLD], gtl[NLD];
-    auto gload = [&](int it) {
+    // direct-to-LDS sources: a tile is 32 rows = 32*KCH chunks = KCH/2 wave-loads, TLD per wave
+    // (TLD = 2 for d = 128; for d = 64 only waves 0 and 1 load, one each)
+    constexpr int NWL = (32 * KCH) / 64;             // wave-loads per tile
+    int slot_r[TLD > 0 ? TLD : 1], slot_c[TLD > 0 ? TLD : 1];
+    constexpr int PER_WAVE = NWL >= 4 ? NWL / 4 : 1;
+    const bool loader = NWL >= 4 || wave < NWL;
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int slot = 64 * (wave * PER_WAVE + i) + lane;
+        slot_r[i] = slot / KCH; slot_c[i] = swz<KCH>(slot / KCH, slot % KCH);
+    }
+    auto issue_tile = [&](int it, int buf) {
         const int g = it / per_head, q0 = (qt_first + it % per_head) * 32;
         const size_t bh = (size_t)b * Hq + hk * G + g;
+        if (loader) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int ch = tid + 256 * i;
-            const size_t ro = (bh * Lp + q0 + ch / KCH) * D + 8 * (ch % KCH);
-            ql[i] = *reinterpret_cast<const uint4v*>(Qb + ro);
-            gl[i] = *reinterpret_cast<const uint4v*>(dOb + ro);
-            const size_t to = (bh * D + ch / 4) * Lp + q0 + 8 * (ch % 4);
-            qtl[i] = *reinterpret_cast<const uint4v*>(Qt + to);
-            gtl[i] = *reinterpret_cast<const uint4v*>(dOt + to);
-        }
-    };
-    auto sstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int ch = tid + 256 * i;
-            *reinterpret_cast<uint4v*>(&sm.q[buf][ch / KCH][8 * (ch % KCH)]) = ql[i];
-            *reinterpret_cast<uint4v*>(&sm.g[buf][ch / KCH][8 * (ch % KCH)]) = gl[i];
-            *reinterpret_cast<uint4v*>(&sm.qt[buf][ch / 4][8 * (ch % 4)]) = qtl[i];
-            *reinterpret_cast<uint4v*>(&sm.gt[buf][ch / 4][8 * (ch % 4)]) = gtl[i];
+            for (int i = 0; i < PER_WAVE; ++i) {
+                const size_t off = (bh * Lp + q0 + slot_r[i]) * D + 8 * slot_c[i];
+                async_copy16(Qb + off, &sm.q[buf][512 * (wave * PER_WAVE + i)]);
+                async_copy16(dOb + off, &sm.g[buf][512 * (wave * PER_WAVE + i)]);
+            }
         }
     };
 
-    if (niter > 0) { gload(0); sstore(0); }
+    if (niter > 0) issue_tile(0, 0);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    // column of query ln inside a transposed tile: quads 1 and 2 of every 16 exchanged
-    const int qcol = (ln & 16) | (ln & 3) | ((ln & 4) << 1) | ((ln & 8) >> 1);
+    const int tr_r = lane & 15, tr_grp = (lane >> 4) & 1;
+    uint16_t* tp = &sm.t[wave][0][0];
+    uint16_t* th = &sm.t[wave][1][0];
+    uint16_t* tl = &sm.t[wave][2][0];
 
     for (int it = 0; it < niter; ++it) {
         const int buf = it & 1;
         const int g = it / per_head, q0 = (qt_first + it % per_head) * 32;
         const size_t bh = (size_t)b * Hq + hk * G + g;
-        if (it + 1 < niter) gload(it + 1);
+        if (it + 1 < niter) issue_tile(it + 1, buf ^ 1);
         const bool active = !CAUSAL || q0 + 31 >= key0_w;          // wave-uniform
         if (active) {
             const int q_row = q0 + ln;
@@ -356,46 +351,48 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
             for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds) {
-                const uint4v bq = *reinterpret_cast<const uint4v*>(&sm.q[buf][ln][16 * ds + 8 * hf]);
-                s = mfma_bf16(kreg[ds], bq, s);                        // S^T = K^F Q^F^T
-                const uint4v bg = *reinterpret_cast<const uint4v*>(&sm.g[buf][ln][16 * ds + 8 * hf]);
-                dp = mfma_bf16(vreg[ds], bg, dp);                      // dP^T = V^F dO^T
+                const int e = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
+                s = mfma_bf16(kreg[ds], *reinterpret_cast<const uint4v*>(&sm.q[buf][e]), s);     // S^T = K^F Q^F^T
+                dp = mfma_bf16(vreg[ds], *reinterpret_cast<const uint4v*>(&sm.g[buf][e]), dp);   // dP^T = V^F dO^T
             }
-            // P = exp(S - L_i), masked keys (beyond L, or after the query) are 0
+            // P = exp(S - L_i); masked keys (beyond L, or after the query) are 0
+            const bool need_mask = (key0_w + 32 > L) || (CAUSAL && key0_w + 31 > q0);
             const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int key = key0_w + 8 * (i >> 2) + 4 * hf + (i & 3);
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[i], c, -Ls));
-                s[i] = key > klim ? 0.0f : p;
+                float p = __builtin_amdgcn_exp2f(fmaf(s[i], c, -Ls));
+                if (need_mask) {
+                    const int key = key0_w + 8 * (i >> 2) + 4 * hf + (i & 3);
+                    if (key > klim) p = 0.0f;
+                }
+                s[i] = p;
             }
-            uint16_t* tp = &sm.t[wave][0][0][0];
-            uint16_t* th = &sm.t[wave][1][0][0];
-            uint16_t* tl = &sm.t[wave][2][0][0];
 #pragma unroll
             for (int gq = 0; gq < 2; ++gq) {                           // phi^-1(phi(P)) per 16 keys
-                float amax = 0.0f;
+                float amax = s[8 * gq];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) amax = fmaxf(amax, s[8 * gq + i]);
+                for (int i = 1; i < 8; ++i) amax = fmaxf(amax, s[8 * gq + i]);
                 amax = xhalf_max(amax);
                 const float sc = rne_e4m3_grid(amax * (1.0f / 6.0f));
                 const float inv = sc > 0.0f ? __builtin_amdgcn_rcpf(sc) : 0.0f;
 #pragma unroll
-                for (int i = 0; i < 8; i += 2) {
-                    const int r0 = 8 * gq + i;
-                    const float pf0 = rne_e2m1_grid(fminf(s[r0] * inv, 6.0f)) * sc;
-                    const float pf1 = rne_e2m1_grid(fminf(s[r0 + 1] * inv, 6.0f)) * sc;
-                    const float ds0 = s[r0] * (dp[r0] - Dq) * rs;       // dS from the fp32 P
-                    const float ds1 = s[r0 + 1] * (dp[r0 + 1] - Dq) * rs;
-                    const uint32_t wp = pack_bf16x2(pf0, pf1);
-                    const uint32_t wh = pack_bf16x2(ds0, ds1);
-                    const uint32_t wl = pack_bf16x2(ds0 - bf16_lo_f32(wh), ds1 - bf16_hi_f32(wh));
-                    // register r <-> key row 8*(r>>2) + 4*hf + (r&3) of this wave's 32 keys
-                    const int kr0 = 8 * (r0 >> 2) + 4 * hf + (r0 & 3);
-                    const int o0 = kr0 * 40 + qcol, o1 = o0 + 40;
-                    tp[o0] = (uint16_t)wp; tp[o1] = (uint16_t)(wp >> 16);
-                    th[o0] = (uint16_t)wh; th[o1] = (uint16_t)(wh >> 16);
-                    tl[o0] = (uint16_t)wl; tl[o1] = (uint16_t)(wl >> 16);
+                for (int t4 = 0; t4 < 2; ++t4) {                       // 4 consecutive keys per store
+                    const int r0 = 8 * gq + 4 * t4;
+                    float pf[4], dsv[4];
+                    fq_pair_f32(s[r0] * inv, s[r0 + 1] * inv, sc, pf[0], pf[1]);
+                    fq_pair_f32(s[r0 + 2] * inv, s[r0 + 3] * inv, sc, pf[2], pf[3]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dsv[e] = s[r0 + e] * (dp[r0 + e] - Dq) * rs;   // dS from the fp32 P
+                    uint2v wp, wh, wl;
+                    wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
+                    wh[0] = pack_bf16x2(dsv[0], dsv[1]); wh[1] = pack_bf16x2(dsv[2], dsv[3]);
+                    wl[0] = pack_bf16x2(dsv[0] - bf16_lo_f32(wh[0]), dsv[1] - bf16_hi_f32(wh[0]));
+                    wl[1] = pack_bf16x2(dsv[2] - bf16_lo_f32(wh[1]), dsv[3] - bf16_hi_f32(wh[1]));
+                    // registers r0..r0+3 <-> keys 8*(r0>>2) + 4*hf + 0..3 of this wave's 32 keys
+                    const int o = ln * kTPad + 8 * (r0 >> 2) + 4 * hf;
+                    *reinterpret_cast<uint2v*>(tp + o) = wp;
+                    *reinterpret_cast<uint2v*>(th + o) = wh;
+                    *reinterpret_cast<uint2v*>(tl + o) = wl;
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -403,21 +400,35 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {                           // 16 queries per step
-                const uint4v ap = *reinterpret_cast<const uint4v*>(&sm.t[wave][0][ln][16 * ks + 8 * hf]);
-                const uint4v ah = *reinterpret_cast<const uint4v*>(&sm.t[wave][1][ln][16 * ks + 8 * hf]);
-                const uint4v al = *reinterpret_cast<const uint4v*>(&sm.t[wave][2][ln][16 * ks + 8 * hf]);
+                // contraction slots 0-3: queries 16*ks + 8*hf + 0..3, slots 4-7: the next four
+                const int qa = 16 * ks + 8 * hf + (tr_r >> 2);
+                const int ta = qa * kTPad + 16 * tr_grp + 4 * (tr_r & 3);
+                uint4v ap, ah, al;
+                {
+                    const uint2v p0 = lds_read_tr16(tp + ta), p1 = lds_read_tr16(tp + ta + 4 * kTPad);
+                    const uint2v h0 = lds_read_tr16(th + ta), h1 = lds_read_tr16(th + ta + 4 * kTPad);
+                    const uint2v l0 = lds_read_tr16(tl + ta), l1 = lds_read_tr16(tl + ta + 4 * kTPad);
+                    ap[0] = p0[0]; ap[1] = p0[1]; ap[2] = p1[0]; ap[3] = p1[1];
+                    ah[0] = h0[0]; ah[1] = h0[1]; ah[2] = h1[0]; ah[3] = h1[1];
+                    al[0] = l0[0]; al[1] = l0[1]; al[2] = l1[0]; al[3] = l1[1];
+                }
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const uint4v bg = *reinterpret_cast<const uint4v*>(&sm.gt[buf][32 * nb + ln][16 * ks + 8 * hf]);
+                    const int col = 32 * nb + 16 * tr_grp + 4 * (tr_r & 3);
+                    const uint2v g0 = lds_read_tr16(&sm.g[buf][swz_elem<KCH>(qa, col)]);
+                    const uint2v g1 = lds_read_tr16(&sm.g[buf][swz_elem<KCH>(qa + 4, col)]);
+                    uint4v bg; bg[0] = g0[0]; bg[1] = g0[1]; bg[2] = g1[0]; bg[3] = g1[1];
                     dv[nb] = mfma_bf16(ap, bg, dv[nb]);                // dV += P^F^T dO
-                    const uint4v bq = *reinterpret_cast<const uint4v*>(&sm.qt[buf][32 * nb + ln][16 * ks + 8 * hf]);
+                    const uint2v q0_ = lds_read_tr16(&sm.q[buf][swz_elem<KCH>(qa, col)]);
+                    const uint2v q1_ = lds_read_tr16(&sm.q[buf][swz_elem<KCH>(qa + 4, col)]);
+                    uint4v bq; bq[0] = q0_[0]; bq[1] = q0_[1]; bq[2] = q1_[0]; bq[3] = q1_[1];
                     dk[nb] = mfma_bf16(ah, bq, dk[nb]);                // dK += dS^T Q^F
                     dk[nb] = mfma_bf16(al, bq, dk[nb]);
                 }
             }
             __builtin_amdgcn_wave_barrier();
         }
-        if (it + 1 < niter) sstore(buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
 
@@ -436,8 +447,8 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
 }
 
 template <int D, bool CAUSAL>
-static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* qt, const void* dob,
-                         const void* dot, const float* lse, const float* delta,
+static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
+                         const float* lse, const float* delta,
                          int B, int Hq, int Hkv, int L, void* dk, void* dv, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
@@ -447,20 +458,20 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
         return -1;
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
-                       (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb, (const uint16_t*)qt,
-                       (const uint16_t*)dob, (const uint16_t*)dot, lse, delta, (uint16_t*)dk, (uint16_t*)dv,
+                       (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
+                       (const uint16_t*)dob, lse, delta, (uint16_t*)dk, (uint16_t*)dv,
                        L, Lp, Hq, Hq / Hkv, 1.4426950408889634f * rs, rs);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* qt, const void* dob,
-                    const void* dot, const float* lse, const float* delta,
+int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
+                    const float* lse, const float* delta,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, qt, dob, dot, lse, delta, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<128, false>(qb, kb, vb, qt, dob, dot, lse, delta, B, Hq, Hkv, L, dk, dv, st);
-    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, qt, dob, dot, lse, delta, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<64, false>(qb, kb, vb, qt, dob, dot, lse, delta, B, Hq, Hkv, L, dk, dv, st);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st)
+                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st);
+    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st)
+                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st);
     return -1;
 }
 

@@ -109,9 +109,28 @@ __device__ inline void fq_pair_f32(float r0, float r1, float s, float& o0, float
 // global_load_lds_dwordx4 writes lane i's 16 bytes to (wave-uniform LDS base) + 16*i, so a
 // tile row cannot be padded; bank conflicts are avoided by an XOR swizzle of the 16-byte
 // chunk index instead.  CH = chunks per row (16: 256-byte rows, 8: 128-byte rows).
+// The 16-chunk key is row with its two 2-bit fields exchanged: 16 consecutive rows still get
+// 16 distinct keys (conflict-free 16-byte column reads), and 4 consecutive rows land in 4
+// different 64-byte groups (which the row-walking transpose reads below want).
 template <int CH>
 __device__ inline int swz(int row, int chunk) {
-    return CH == 16 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
+    return CH == 16 ? (chunk ^ (((row & 3) << 2) | ((row >> 2) & 3))) : (chunk ^ ((row >> 1) & 7));
+}
+// Element (row, col) of a swizzled tile with CH chunks of 8 halves per row.
+template <int CH>
+__device__ inline int swz_elem(int row, int col) {
+    return (row * CH + swz<CH>(row, col >> 3)) * 8 + (col & 7);
+}
+
+// ds_read_b64_tr_b16: the 16 lanes of a group each pass the address of 4 consecutive 16-bit
+// elements; lane i of the group receives element (i & 3) of the runs of lanes
+// i/4, 4 + i/4, 8 + i/4, 12 + i/4.  With lane r pointing at X[k0 + r/4][n0 + 4*(r%4) ..],
+// lane i therefore gets X[k0 .. k0+3][n0 + i]: a column of a row-major tile, i.e. the MFMA
+// operand of the transposed matrix without a transposed copy.
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ inline uint2v lds_read_tr16(const uint16_t* p) {
+    const short4v r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
+    return __builtin_bit_cast(uint2v, r);
 }
 // One wave copies 1 KiB: LDS chunk slot (wave-uniform slot0 + lane) <- its global source.
 __device__ inline void async_copy16(const void* gsrc, void* lds_wave_base) {

@@ -22,13 +22,13 @@ int launch_fwd(const void* qh, const void* kh, const void* vt,
 int launch_delta(const void* d_o, const float* o_hp, int BHq, int L, int D, float* delta, hipStream_t st);
 
 // Alg. 3, query-stationary pass: dQ.
-int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* kt, const void* dob,
+int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
                   const float* lse, const float* delta,
                   int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st);
 
 // Alg. 3, key-stationary pass: dK, dV (summed over the query heads of a group).
-int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* qt, const void* dob,
-                    const void* dot, const float* lse, const float* delta,
+int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
+                    const float* lse, const float* delta,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st);
 
 }  // namespace aq
