@@ -63,6 +63,9 @@ def _load():
     L.oracle_bwd_dkdv_keys.restype = _i
     L.oracle_bwd_dkdv_keys.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
                                        _i, _i, _l, _vp, _vp, _vp, _vp, _vp, _vp]
+    L.oracle_bwd_rows_dkdv.restype = _i
+    L.oracle_bwd_rows_dkdv.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
+                                       _l, _vp, _vp, _vp, _vp, _vp]
     L.oracle_num_threads.restype = _i
     _lib = L
     return L
@@ -223,3 +226,22 @@ def bwd_dkdv_keys(q, k, v, do, b, hk, keys, Lse_grp, Op_grp, causal: bool,
     if rc:
         raise ValueError(f"oracle_bwd_dkdv_keys failed ({rc})")
     return (dK, dV, P) if dump_p else (dK, dV)
+
+
+def bwd_rows_dkdv(q, k, v, do, rows, Lse_rows, Op_rows, causal: bool,
+                  quant_qkv: bool = True, quant_p: bool = True, scale_mode: int = 0):
+    """dK, dV of Alg. 3 with the sums over query rows restricted to ``rows`` (flat ids), for
+    all keys.  Equals the full backward when dO is zero outside the listed rows (dS and
+    dV are linear in dO).  Returns (dK, dV) float64 [B,Hkv,L,d]."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    qf, kf, vf = _prep_qkv(q, k, v, quant_qkv, scale_mode)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    do, Lse_rows, Op_rows = _f32(do), _f64(Lse_rows), _f64(Op_rows)
+    dK = np.empty((B, Hkv, L, d)); dV = np.empty((B, Hkv, L, d))
+    rc = _load().oracle_bwd_rows_dkdv(_p(qf), _p(kf), _p(vf), _p(do), B, Hq, Hkv, L, d,
+                                      int(causal), int(quant_p), scale_mode,
+                                      rows.size, _p(rows), _p(Lse_rows), _p(Op_rows), _p(dK), _p(dV))
+    if rc:
+        raise ValueError(f"oracle_bwd_rows_dkdv failed ({rc})")
+    return dK, dV

@@ -393,6 +393,51 @@ int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, cons
     return 0;
 }
 
+/* dK and dV contributions of a LIST of query rows, for all keys (Alg. 3 with the outer
+ * sums restricted to the listed rows).  Because dP, D and therefore dS, and dV = P^F^T dO,
+ * are linear in dO, this equals the full backward whenever dO is zero outside the list.
+ * rows: flat ids; Lse_rows[nrows], Op_rows[nrows,d] belong to the list.
+ * dK, dV [B,Hkv,L,d] are overwritten. */
+int oracle_bwd_rows_dkdv(const float* qf, const float* kf, const float* vf, const float* dO,
+                         int B, int Hq, int Hkv, long L, int d, int causal,
+                         int quant_p, int scale_mode,
+                         long nrows, const long* rows,
+                         const double* Lse_rows, const double* Op_rows,
+                         double* dK, double* dV)
+{
+    if (!rows || Hq % Hkv) return -1;
+    const int G = Hq / Hkv;
+    const double rs = 1.0 / sqrt((double)d);
+    memset(dK, 0, sizeof(double) * (size_t)B * Hkv * L * d);
+    memset(dV, 0, sizeof(double) * (size_t)B * Hkv * L * d);
+    for (long n = 0; n < nrows; ++n) {              /* rows one after another ... */
+        long rid = rows[n]; long i = rid % L; long bh = rid / L;
+        int h = (int)(bh % Hq), b = (int)(bh / Hq);
+        long u = (long)b * Hkv + h / G;
+        const float* kh = kf + u * L * d; const float* vh = vf + u * L * d;
+        const float* qrow = qf + rid * d; const float* dorow = dO + rid * d;
+        double D = 0.0;
+        for (int c = 0; c < d; ++c) D += (double)dorow[c] * Op_rows[n * d + c];
+        long kend = causal ? i + 1 : L;
+        long nblk = (kend + 15) / 16;
+        #pragma omp parallel for schedule(static)   /* ... key blocks in parallel: disjoint dK/dV rows */
+        for (long kb = 0; kb < nblk; ++kb) {
+            long k0 = kb * 16;
+            double P[16], Pf[16], dS[16];
+            int nv = nvis_of(k0, kend);
+            bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, d, rs, quant_p, scale_mode, P, Pf, dS);
+            for (int k = 0; k < nv; ++k) {
+                long kr = (u * L + k0 + k) * d;
+                for (int c = 0; c < d; ++c) {
+                    dV[kr + c] += Pf[k] * (double)dorow[c];
+                    dK[kr + c] += dS[k] * (double)qrow[c];
+                }
+            }
+        }
+    }
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -1,0 +1,151 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot run these problems whole, so each check is one it can do exactly:
+  * O, L, O' and dQ on seeded sampled query rows (rows are independent given all K, V);
+  * dK and dV on ALL keys of the selected kv heads, by running the GPU backward with a dO
+    that is zero outside the sampled rows: dP, D, dS and dV = P^F^T dO are linear in dO, so
+    the oracle only has to visit the sampled rows, while the kernel still walks every
+    (query tile, key tile) pair of the full problem; heads without sampled rows must come
+    back exactly zero;
+  * the dequantized P-tilde^F of one 128-row query tile, element by element (flip count);
+  * codes and scales of complete Q/K/V tensors, bit exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from tests.gpu_util import f32, host, max_abs, rel_l2, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL, FLIP_BAR = 2e-3, 1e-4
+
+
+def _selection(w):
+    """kv heads to check (first and last), their query heads, and sampled rows per query head."""
+    G = w.Hq // w.Hkv
+    kv = sorted({0, w.Hkv - 1})
+    b = w.B - 1
+    qheads = [hk * G + g for hk in kv for g in range(G)]
+    rng = np.random.default_rng(1000 + w.seed)
+    nrand = 6 if len(qheads) <= 4 else 2
+    rows = []
+    for h in qheads:
+        fixed = [0, 1, w.L - 1, w.L - 2, (w.L // 128) * 128 - 1, (w.L // 128) * 128]
+        extra = rng.integers(0, w.L, nrand).tolist()
+        rows.append(sorted({r for r in fixed + extra if 0 <= r < w.L}))
+    return b, kv, qheads, rows
+
+
+def _sub(x, b, kv, qheads):
+    """The sub-problem (B=1) made of the selected heads, as float32 for the oracle."""
+    s = {"q": f32(x["q"][b:b + 1, qheads]), "k": f32(x["k"][b:b + 1, kv]), "v": f32(x["v"][b:b + 1, kv])}
+    if "do" in x:
+        s["do"] = f32(x["do"][b:b + 1, qheads])
+    return s
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_full_size(cfg):
+    import paper_2603_00040_amd as aq
+    w = W.CONFIGS[cfg]
+    train = w.passes == "fwd+bwd"
+    print(f"\n[{w.name}] generating inputs", flush=True)
+    x = W.make_inputs(w, with_do=train)
+    q, k, v = to_dev(x["q"]), to_dev(x["k"]), to_dev(x["v"])
+    b, kv, qheads, rows = _selection(w)
+    L, d, Bk = w.L, w.d, aq.block_k()
+    sub = _sub(x, b, kv, qheads)
+    flat = np.asarray([hi * L + r for hi, rs in enumerate(rows) for r in rs], dtype=np.int64)
+    gi = [(b, h, r) for h, rs in zip(qheads, rows) for r in rs]                # (b, h, row) on the GPU side
+    pick = lambda t: torch.stack([t[bb, hh, rr] for bb, hh, rr in gi])
+
+    # ---- forward
+    print(f"[{w.name}] GPU forward", flush=True)
+    if train:
+        o, lse, ohp = aq.attnqat_fwd(q, k, v, w.causal)
+    else:
+        o, lse = aq.attnqat_fwd_infer(q, k, v, w.causal)
+    torch.cuda.synchronize()
+    print(f"[{w.name}] oracle forward on {flat.size} rows", flush=True)
+    rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, rows=flat)
+    eO = rel_l2(host(pick(o)), rf["O"]); eL = max_abs(host(pick(lse)), rf["L"])
+    print(f"[{w.name}] O rel-L2 {eO:.2e} max-abs {max_abs(host(pick(o)), rf['O']):.2e}  L max-abs {eL:.2e}", flush=True)
+    assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
+    if train:
+        eOp = rel_l2(host(pick(ohp)), rf["Op"])
+        print(f"[{w.name}] O' rel-L2 {eOp:.2e}", flush=True)
+        assert eOp <= 2e-4
+
+    # ---- P-tilde^F of one query tile of the selected heads
+    row0 = ((L // 2) // 128) * 128
+    _, _, p = aq.attnqat_debug_fwd_p(q, k, v, w.causal, row0)
+    torch.cuda.synchronize()
+    nrow = min(128, L - row0)
+    hsel = list(range(len(qheads)))[:2]
+    prow = np.asarray([hi * L + row0 + i for hi in hsel for i in range(nrow)], dtype=np.int64)
+    rp = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, rows=prow, dump_p=True)
+    got = torch.stack([p[b, qheads[hi], :nrow] for hi in hsel]).cpu().numpy().reshape(-1, L)
+    flips = int((got != rp["P"]).sum())
+    print(f"[{w.name}] P-tilde^F flips {flips} of {got.size} ({flips / got.size:.2e})", flush=True)
+    assert flips / got.size < FLIP_BAR
+    del p
+
+    # ---- codes and scales of whole tensors
+    for name in (("k", "v") if cfg == 3 else ("q", "k", "v")):
+        t = {"q": q, "k": k, "v": v}[name]
+        codes, scales, _ = aq.attnqat_quantize(t, want_xf=False)
+        torch.cuda.synchronize()
+        pc, ps, _ = oracle.phi(f32(x[name]))
+        gc, gs = codes.cpu().numpy(), scales.cpu().numpy()
+        canon = lambda c: np.where((c & 7) == 0, c & 0xF0, c) & np.where((c & 0x70) == 0, 0x0F, 0xFF)
+        nbad_s = int((gs != ps).sum()); nbad_c = int((canon(gc) != canon(pc)).sum())
+        print(f"[{w.name}] phi({name}): {gs.size} scales, {nbad_s} differ; {gc.size} code bytes, {nbad_c} differ", flush=True)
+        assert nbad_s == 0 and nbad_c == 0
+        del codes, scales, pc, ps, gc, gs
+    if not train:
+        return
+
+    # ---- backward: dQ on the sampled rows (full dO)
+    do = to_dev(x["do"])
+    print(f"[{w.name}] GPU backward (dense dO)", flush=True)
+    dq, dk, dv = aq.attnqat_bwd(q, k, v, do, lse, ohp, w.causal)
+    torch.cuda.synchronize()
+    rdq = oracle.bwd_dq_rows(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
+    eQ = rel_l2(host(pick(dq)), rdq)
+    print(f"[{w.name}] dQ rel-L2 {eQ:.2e} max-abs {max_abs(host(pick(dq)), rdq):.2e}", flush=True)
+    assert eQ <= TOL
+    # Eq. 5: sum_i dQ_i . Q^F_i = sum_k dK_k . K^F_k (both equal sum_ik dS_ik S_ik sqrt(d)) ties the
+    # dense dK of EVERY head to dQ at any size
+    _, _, qf = aq.attnqat_quantize(q, want_codes=False)
+    _, _, kf = aq.attnqat_quantize(k, want_codes=False)
+    G = w.Hq // w.Hkv
+    lhs = (dq.float() * qf.float()).sum((2, 3)).double().view(w.B, w.Hkv, G).sum(-1)
+    rhs = (dk.float() * kf.float()).sum((2, 3)).double()
+    scale = (dq.float().abs() * qf.float().abs()).sum((2, 3)).double().view(w.B, w.Hkv, G).sum(-1)
+    ident = float(((lhs - rhs).abs() / scale).max())
+    print(f"[{w.name}] max |sum dQ.Q - sum dK.K| / sum |dQ||Q| over heads = {ident:.2e}", flush=True)
+    assert ident < 2e-3
+    del dq, dk, dv, qf, kf
+
+    # ---- backward with dO zero outside the sampled rows: dK, dV on all keys
+    dos = torch.zeros_like(do)
+    for bb, hh, rr in gi:
+        dos[bb, hh, rr] = do[bb, hh, rr]
+    print(f"[{w.name}] GPU backward (sparse dO)", flush=True)
+    _, dk, dv = aq.attnqat_bwd(q, k, v, dos, lse, ohp, w.causal)
+    torch.cuda.synchronize()
+    rdk, rdv = oracle.bwd_rows_dkdv(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
+    gk = host(dk[b, kv]); gv = host(dv[b, kv])
+    eK, eV = rel_l2(gk, rdk[0]), rel_l2(gv, rdv[0], zero_rms=1e-6)
+    nzv = float((rdv[0] != 0).mean())
+    print(f"[{w.name}] dK rel-L2 {eK:.2e} max-abs {max_abs(gk, rdk[0]):.2e}  dV rel-L2 {eV:.2e} "
+          f"max-abs {max_abs(gv, rdv[0]):.2e} (oracle dV non-zero fraction {nzv:.3f})", flush=True)
+    assert eK <= TOL and eV <= TOL
+    other = [hk for hk in range(w.Hkv) if hk not in kv]
+    if other:
+        assert not dk[:, other].any() and not dv[:, other].any()
+    if w.B > 1:
+        assert not dk[:b].any() and not dv[:b].any()

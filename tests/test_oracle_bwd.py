@@ -120,3 +120,18 @@ def test_sampled_entry_points_match_full(causal):
     assert np.allclose(dv, g["dV"][b, hk, keys], rtol=0, atol=1e-12)
     # P = 1 quantizes to 6 * RNE_E4M3(1/6) = 6 * 0.171875 = 1.03125
     assert P.shape == (5, 2, 50) and P.max() <= 1.03125
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_rows_restricted_dkdv_equals_full_backward_with_sparse_dO(causal):
+    q, k, v = _rand(1, 4, 2, 70, 32, seed=40)
+    do = _bf(np.random.default_rng(41).standard_normal(q.shape).astype(np.float32))
+    rows = oracle.flat_rows(1, 4, 70, [(0, 0, 0), (0, 1, 69), (0, 3, 35), (0, 2, 16), (0, 2, 17)])
+    sparse = np.zeros_like(do).reshape(-1, 32)
+    sparse[rows] = do.reshape(-1, 32)[rows]
+    sparse = sparse.reshape(do.shape)
+    f, g = _oracle_fwd_bwd(q, k, v, sparse, causal)
+    fr = oracle.fwd(q, k, v, causal, 64, rows=rows)
+    dk, dv = oracle.bwd_rows_dkdv(q, k, v, do, rows, fr["L"], fr["Op"], causal)
+    assert np.allclose(dk, g["dK"], rtol=0, atol=1e-12) and np.allclose(dv, g["dV"], rtol=0, atol=1e-12)
+    assert np.abs(g["dK"]).max() > 1e-3
