@@ -18,6 +18,10 @@
 // global->LDS directly (XOR-swizzled rows); operands that a product needs transposed
 // (K^T for dQ; Q and dO column-wise, P^F^T and dS^T for dK/dV) are read from the row-major
 // tiles with the LDS transpose read, so no transposed copy exists anywhere.
+//
+// LDS reads are the scarce resource of these loops (one wave sustains about one 1 KiB read
+// per 40 cycles, latency ~130 cycles), so every operand read is issued a few MFMAs ahead of
+// its consumer and the scheduling groups pin that order.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -35,6 +39,7 @@ __device__ inline float bf16_hi_f32(uint32_t w) { return __uint_as_float(w & 0xF
 __device__ inline floatx16 mfma_bf16(uint4v a, uint4v b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
+__device__ inline uint4v join(uint2v a, uint2v b) { uint4v r; r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1]; return r; }
 
 // ------------------------------------------------------------------ delta
 template <int D>
@@ -111,7 +116,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         }
     }
     const float Ls = (q_row < L ? lse[(size_t)bh * L + q_row] : 0.0f) * 1.4426950408889634f;
-    const float Dq = delta[(size_t)bh * Lp + q_row];
+    const float Dqs = delta[(size_t)bh * Lp + q_row] * rs;          // D_i / sqrt(d)
 
     const int nkt_all = (L + 63) / 64;
     const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;
@@ -125,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         const size_t off = ((size_t)bhkv * Lp + r) * D + 8 * swz<KCH>(r, pc);
         ksrc[i] = Kb + off; vsrc[i] = Vb + off;
     }
-    auto issue_tile = [&](int buf) {
+    auto issue_tile = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < KLD; ++i) {
             async_copy16(ksrc[i], &sm.k[buf][512 * (wave * KLD + i)]); ksrc[i] += 64 * D;
@@ -133,14 +138,26 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         }
     };
 
+    // LDS element offsets (buffer 0).  Row blocks of 32 (kb) and key steps of 16 (ks) add
+    // compile-time constants: they do not change a row's swizzle key.
+    //   koff[ds]    16-byte operand reads of K and V rows: row ln, d-slots 16*ds + 8*hf
+    //   toff[mb][v] transpose reads of K^T: lane r of a group of 16 points at key 4*hf + r/4 + 8*v,
+    //               columns 32*mb + 16*grp + 4*(r%4); the lane receives column 32*mb + ln of 4 keys
+    const int tr_r = lane & 15, tr_grp = (lane >> 4) & 1;
+    int koff[DS], toff[MB][2];
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) koff[ds] = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 2; ++v)
+            toff[mb][v] = swz_elem<KCH>(4 * hf + (tr_r >> 2) + 8 * v, 32 * mb + 16 * tr_grp + 4 * (tr_r & 3));
+
     floatx16 acc[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
-
-    // lane roles of the transpose reads: r = lane in its group of 16, grp = which 16 columns
-    const int tr_r = lane & 15, tr_grp = (lane >> 4) & 1;
 
     issue_tile(0);
     __builtin_amdgcn_s_waitcnt(0);
@@ -151,52 +168,74 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         if (j + 1 < nkt) issue_tile(buf ^ 1);
         const bool active = !CAUSAL || k0 <= wave_qmax;
         if (active) {
+            const uint16_t* kt_ = &sm.k[buf][0];
+            const uint16_t* vt_ = &sm.v[buf][0];
             floatx16 s[2], dp[2];
+            {   // S^T = K^F Q^F^T and dP^T = V^F dO^T: 4*DS steps, step i: ds = i/4, kb = (i/2)%2, K or V = i%2
+                constexpr int NST = 4 * DS, RING = 6;
+                auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
+                    const uint16_t* base = (i & 1) ? vt_ : kt_;
+                    return *reinterpret_cast<const uint4v*>(base + koff[i >> 2] + ((i >> 1) & 1) * (32 * D));
+                };
+                uint4v ring[RING];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+                for (int i = 0; i < RING; ++i) ring[i] = opnd(i);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) { s[kb][i] = 0.0f; dp[kb][i] = 0.0f; }
-                const int r = 32 * kb + ln;
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int ds = 0; ds < DS; ++ds) {
-                    const int e = (r * KCH + swz<KCH>(r, 2 * ds + hf)) * 8;
-                    s[kb] = mfma_bf16(*reinterpret_cast<const uint4v*>(&sm.k[buf][e]), qreg[ds], s[kb]);     // S^T = K^F Q^F^T
-                    dp[kb] = mfma_bf16(*reinterpret_cast<const uint4v*>(&sm.v[buf][e]), doreg[ds], dp[kb]);  // dP^T = V^F dO^T
+                    for (int i = 0; i < 16; ++i) { s[kb][i] = 0.0f; dp[kb][i] = 0.0f; }
+#pragma unroll
+                for (int i = 0; i < NST; ++i) {
+                    const uint4v a = ring[i % RING];
+                    if (i + RING < NST) ring[i % RING] = opnd(i + RING);
+                    const int kb = (i >> 1) & 1, ds = i >> 2;
+                    if (i & 1) dp[kb] = mfma_bf16(a, doreg[ds], dp[kb]);
+                    else       s[kb] = mfma_bf16(a, qreg[ds], s[kb]);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
+#pragma unroll
+                for (int i = 0; i < NST; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (i + RING < NST) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
             }
+            // masked keys (beyond L, or after the query): S = -inf so that P = 0
             const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > qt * 128 + wave * 32);
-            const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
+            if (need_mask) {
+                const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float p = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, -Ls));     // P = exp(S - L_i)
-                    if (need_mask) {
+                    for (int i = 0; i < 16; ++i) {
                         const int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * hf + (i & 3);
-                        if (key > klim) p = 0.0f;
+                        if (key > klim) s[kb][i] = -INFINITY;
                     }
-                    s[kb][i] = p * (dp[kb][i] - Dq) * rs;                          // dS, from the fp32 P
-                }
+            }
+            // dQ^T += K^F^T dS^T, 16 keys per step; the K^T operands of a step are read (transposed)
+            // before that step's dS is computed, so their latency hides behind the VALU work
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {                                       // dQ^T += K^F^T dS^T
+            for (int ks = 0; ks < 4; ++ks) {
                 const int kb = ks >> 1, g = ks & 1;
+                uint4v at[MB];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    at[mb] = join(lds_read_tr16(kt_ + toff[mb][0] + ks * (16 * D)), lds_read_tr16(kt_ + toff[mb][1] + ks * (16 * D)));
                 uint4v bhi, blo;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float d0 = s[kb][8 * g + 2 * i], d1 = s[kb][8 * g + 2 * i + 1];
+                    const int r0 = 8 * g + 2 * i;
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][r0], c, -Ls));           // P = exp(S - L_i)
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][r0 + 1], c, -Ls));
+                    const float d0 = p0 * fmaf(dp[kb][r0], rs, -Dqs);                         // dS = P (dP - D_i)/sqrt(d)
+                    const float d1 = p1 * fmaf(dp[kb][r0 + 1], rs, -Dqs);
                     const uint32_t hi = pack_bf16x2(d0, d1);
                     bhi[i] = hi;
                     blo[i] = pack_bf16x2(d0 - bf16_lo_f32(hi), d1 - bf16_hi_f32(hi));
                 }
-                const int key_a = 16 * ks + 4 * hf + (tr_r >> 2);                 // slots 0-3; +8: slots 4-7
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    const int col = 32 * mb + 16 * tr_grp + 4 * (tr_r & 3);
-                    const uint2v a0 = lds_read_tr16(&sm.k[buf][swz_elem<KCH>(key_a, col)]);
-                    const uint2v a1 = lds_read_tr16(&sm.k[buf][swz_elem<KCH>(key_a + 8, col)]);
-                    uint4v a; a[0] = a0[0]; a[1] = a0[1]; a[2] = a1[0]; a[3] = a1[1];
-                    acc[mb] = mfma_bf16(a, bhi, acc[mb]);
-                    acc[mb] = mfma_bf16(a, blo, acc[mb]);
+                    acc[mb] = mfma_bf16(at[mb], bhi, acc[mb]);
+                    acc[mb] = mfma_bf16(at[mb], blo, acc[mb]);
                 }
             }
         }
@@ -267,7 +306,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     int L, int Lp, int Hq, int G, float c, float rs)
 {
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
-    constexpr int TLD = KCH / 8;                     // 1 KiB wave-loads per wave per tile (32 rows)
+    constexpr int NWL = (32 * KCH) / 64;             // 1 KiB wave-loads per tile of 32 rows
+    constexpr int PER_WAVE = NWL >= 4 ? NWL / 4 : 1;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
 
@@ -278,12 +318,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const int b = bhkv / Hkv, hk = bhkv % Hkv;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
     const int key0_w = kt_ * 128 + wave * 32;       // this wave's first key
-    const int key_row = key0_w + ln;
 
     // K^F, V^F rows of this lane's key: A operands (row = key, d-slots 16*ds + 8*hf)
     uint4v kreg[DS], vreg[DS];
     {
-        const size_t off = ((size_t)bhkv * Lp + key_row) * D + 8 * hf;
+        const size_t off = ((size_t)bhkv * Lp + key0_w + ln) * D + 8 * hf;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
             kreg[ds] = *reinterpret_cast<const uint4v*>(Kb + off + 16 * ds);
@@ -297,76 +336,116 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) { dk[nb][i] = 0.0f; dv[nb][i] = 0.0f; }
 
-    // query tiles of 32 rows; under a causal mask only rows >= the workgroup's first key matter
+    // query tiles of 32 rows, query heads of the group one after another; under a causal mask
+    // only rows >= the workgroup's first key matter
     const int nq32 = (L + 31) / 32;
     const int qt_first = CAUSAL ? (kt_ * 128) / 32 : 0;
     const int per_head = nq32 - qt_first;
     const int niter = per_head > 0 ? per_head * G : 0;
+    const size_t bh0 = (size_t)b * Hq + hk * G;      // first query head of the group
 
-    // direct-to-LDS sources: a tile is 32 rows = 32*KCH chunks = KCH/2 wave-loads, TLD per wave
-    // (TLD = 2 for d = 128; for d = 64 only waves 0 and 1 load, one each)
-    constexpr int NWL = (32 * KCH) / 64;             // wave-loads per tile
-    int slot_r[TLD > 0 ? TLD : 1], slot_c[TLD > 0 ? TLD : 1];
-    constexpr int PER_WAVE = NWL >= 4 ? NWL / 4 : 1;
+    // direct-to-LDS loads: this wave's chunk slots and their (row, swizzled chunk)
     const bool loader = NWL >= 4 || wave < NWL;
+    int slot_off[PER_WAVE];
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
         const int slot = 64 * (wave * PER_WAVE + i) + lane;
-        slot_r[i] = slot / KCH; slot_c[i] = swz<KCH>(slot / KCH, slot % KCH);
+        slot_off[i] = (slot / KCH) * D + 8 * swz<KCH>(slot / KCH, slot % KCH);
     }
-    auto issue_tile = [&](int it, int buf) {
-        const int g = it / per_head, q0 = (qt_first + it % per_head) * 32;
-        const size_t bh = (size_t)b * Hq + hk * G + g;
+    // (head, tile) walk without divisions: state of the NEXT tile to load and of the current tile
+    int ld_g = 0, ld_t = 0;                          // next tile to issue: head index in group, tile in head
+    auto issue_next = [&](int buf) __attribute__((always_inline)) {
+        const size_t row0 = (bh0 + ld_g) * Lp + (size_t)(qt_first + ld_t) * 32;
         if (loader) {
 #pragma unroll
             for (int i = 0; i < PER_WAVE; ++i) {
-                const size_t off = (bh * Lp + q0 + slot_r[i]) * D + 8 * slot_c[i];
-                async_copy16(Qb + off, &sm.q[buf][512 * (wave * PER_WAVE + i)]);
-                async_copy16(dOb + off, &sm.g[buf][512 * (wave * PER_WAVE + i)]);
+                async_copy16(Qb + row0 * D + slot_off[i], &sm.q[buf][512 * (wave * PER_WAVE + i)]);
+                async_copy16(dOb + row0 * D + slot_off[i], &sm.g[buf][512 * (wave * PER_WAVE + i)]);
             }
         }
+        if (++ld_t == per_head) { ld_t = 0; ++ld_g; }
+    };
+    // L_i and D_i of this lane's query row of a tile (clamped rows carry P = anything, dO = 0)
+    auto row_scalars = [&](int g, int t, float& Ls, float& Dqs) __attribute__((always_inline)) {
+        const int q_row = (qt_first + t) * 32 + ln;
+        Ls = (q_row < L ? lse[(bh0 + g) * L + q_row] : 0.0f) * 1.4426950408889634f;
+        Dqs = delta[(bh0 + g) * Lp + q_row] * rs;
     };
 
-    if (niter > 0) issue_tile(0, 0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-
+    // LDS element offsets (buffer 0)
+    //   qoff[ds]    16-byte reads of Q / dO rows: row ln, d-slots 16*ds + 8*hf
+    //   goff[nb][v] transpose reads of Q / dO columns: lane r of a group of 16 points at query
+    //               8*hf + r/4 + 4*v, columns 32*nb + 16*grp + 4*(r%4)
     const int tr_r = lane & 15, tr_grp = (lane >> 4) & 1;
+    int qoff[DS], goff[NB][2];
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) qoff[ds] = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 2; ++v)
+            goff[nb][v] = swz_elem<KCH>(8 * hf + (tr_r >> 2) + 4 * v, 32 * nb + 16 * tr_grp + 4 * (tr_r & 3));
+    const int tw_off = ln * kTPad + 4 * hf;                                    // staging tile: this lane's writes
+    const int ta_off = (8 * hf + (tr_r >> 2)) * kTPad + 16 * tr_grp + 4 * (tr_r & 3);   // ... and transpose reads
     uint16_t* tp = &sm.t[wave][0][0];
     uint16_t* th = &sm.t[wave][1][0];
     uint16_t* tl = &sm.t[wave][2][0];
 
+    float Ls_n = 0.0f, Dqs_n = 0.0f;
+    if (niter > 0) { issue_next(0); row_scalars(0, 0, Ls_n, Dqs_n); }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    int cur_g = 0, cur_t = 0;
     for (int it = 0; it < niter; ++it) {
         const int buf = it & 1;
-        const int g = it / per_head, q0 = (qt_first + it % per_head) * 32;
-        const size_t bh = (size_t)b * Hq + hk * G + g;
-        if (it + 1 < niter) issue_tile(it + 1, buf ^ 1);
+        const int q0 = (qt_first + cur_t) * 32;
+        const float Ls = Ls_n, Dqs = Dqs_n;
+        // next tile: start its copy and fetch its row scalars now, they are needed one iteration later
+        int nx_g = cur_g, nx_t = cur_t + 1;
+        if (nx_t == per_head) { nx_t = 0; ++nx_g; }
+        if (it + 1 < niter) { issue_next(buf ^ 1); row_scalars(nx_g, nx_t, Ls_n, Dqs_n); }
         const bool active = !CAUSAL || q0 + 31 >= key0_w;          // wave-uniform
         if (active) {
-            const int q_row = q0 + ln;
-            const float Ls = (q_row < L ? lse[bh * L + q_row] : 0.0f) * 1.4426950408889634f;
-            const float Dq = delta[bh * Lp + q_row];
+            const uint16_t* qt_ = &sm.q[buf][0];
+            const uint16_t* gt_ = &sm.g[buf][0];
             floatx16 s, dp;
+            {   // S^T = K^F Q^F^T, dP^T = V^F dO^T: 2*DS steps, step i: ds = i/2, Q or dO = i%2
+                constexpr int NST = 2 * DS, RING = 4;
+                auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
+                    return *reinterpret_cast<const uint4v*>(((i & 1) ? gt_ : qt_) + qoff[i >> 1]);
+                };
+                uint4v ring[RING];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
+                for (int i = 0; i < RING; ++i) ring[i] = opnd(i);
 #pragma unroll
-            for (int ds = 0; ds < DS; ++ds) {
-                const int e = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
-                s = mfma_bf16(kreg[ds], *reinterpret_cast<const uint4v*>(&sm.q[buf][e]), s);     // S^T = K^F Q^F^T
-                dp = mfma_bf16(vreg[ds], *reinterpret_cast<const uint4v*>(&sm.g[buf][e]), dp);   // dP^T = V^F dO^T
-            }
-            // P = exp(S - L_i); masked keys (beyond L, or after the query) are 0
-            const bool need_mask = (key0_w + 32 > L) || (CAUSAL && key0_w + 31 > q0);
-            const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
+                for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float p = __builtin_amdgcn_exp2f(fmaf(s[i], c, -Ls));
-                if (need_mask) {
-                    const int key = key0_w + 8 * (i >> 2) + 4 * hf + (i & 3);
-                    if (key > klim) p = 0.0f;
+                for (int i = 0; i < NST; ++i) {
+                    const uint4v bq = ring[i % RING];
+                    if (i + RING < NST) ring[i % RING] = opnd(i + RING);
+                    if (i & 1) dp = mfma_bf16(vreg[i >> 1], bq, dp);
+                    else       s = mfma_bf16(kreg[i >> 1], bq, s);
                 }
-                s[i] = p;
+                __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
+#pragma unroll
+                for (int i = 0; i < NST; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (i + RING < NST) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
             }
+            // masked keys (beyond L, or after the query): S = -inf so that P = 0
+            const bool need_mask = (key0_w + 32 > L) || (CAUSAL && key0_w + 31 > q0);
+            if (need_mask) {
+                const int klim = CAUSAL ? min(L - 1, q0 + ln) : L - 1;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = key0_w + 8 * (i >> 2) + 4 * hf + (i & 3);
+                    if (key > klim) s[i] = -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c, -Ls));    // P = exp(S - L_i)
 #pragma unroll
             for (int gq = 0; gq < 2; ++gq) {                           // phi^-1(phi(P)) per 16 keys
                 float amax = s[8 * gq];
@@ -382,14 +461,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                     fq_pair_f32(s[r0] * inv, s[r0 + 1] * inv, sc, pf[0], pf[1]);
                     fq_pair_f32(s[r0 + 2] * inv, s[r0 + 3] * inv, sc, pf[2], pf[3]);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) dsv[e] = s[r0 + e] * (dp[r0 + e] - Dq) * rs;   // dS from the fp32 P
+                    for (int e = 0; e < 4; ++e) dsv[e] = s[r0 + e] * fmaf(dp[r0 + e], rs, -Dqs);   // dS from the fp32 P
                     uint2v wp, wh, wl;
                     wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
                     wh[0] = pack_bf16x2(dsv[0], dsv[1]); wh[1] = pack_bf16x2(dsv[2], dsv[3]);
                     wl[0] = pack_bf16x2(dsv[0] - bf16_lo_f32(wh[0]), dsv[1] - bf16_hi_f32(wh[0]));
                     wl[1] = pack_bf16x2(dsv[2] - bf16_lo_f32(wh[1]), dsv[3] - bf16_hi_f32(wh[1]));
                     // registers r0..r0+3 <-> keys 8*(r0>>2) + 4*hf + 0..3 of this wave's 32 keys
-                    const int o = ln * kTPad + 8 * (r0 >> 2) + 4 * hf;
+                    const int o = tw_off + 8 * (r0 >> 2);
                     *reinterpret_cast<uint2v*>(tp + o) = wp;
                     *reinterpret_cast<uint2v*>(th + o) = wh;
                     *reinterpret_cast<uint2v*>(tl + o) = wl;
@@ -401,33 +480,22 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {                           // 16 queries per step
                 // contraction slots 0-3: queries 16*ks + 8*hf + 0..3, slots 4-7: the next four
-                const int qa = 16 * ks + 8 * hf + (tr_r >> 2);
-                const int ta = qa * kTPad + 16 * tr_grp + 4 * (tr_r & 3);
-                uint4v ap, ah, al;
-                {
-                    const uint2v p0 = lds_read_tr16(tp + ta), p1 = lds_read_tr16(tp + ta + 4 * kTPad);
-                    const uint2v h0 = lds_read_tr16(th + ta), h1 = lds_read_tr16(th + ta + 4 * kTPad);
-                    const uint2v l0 = lds_read_tr16(tl + ta), l1 = lds_read_tr16(tl + ta + 4 * kTPad);
-                    ap[0] = p0[0]; ap[1] = p0[1]; ap[2] = p1[0]; ap[3] = p1[1];
-                    ah[0] = h0[0]; ah[1] = h0[1]; ah[2] = h1[0]; ah[3] = h1[1];
-                    al[0] = l0[0]; al[1] = l0[1]; al[2] = l1[0]; al[3] = l1[1];
-                }
+                const int ta = ta_off + ks * (16 * kTPad);
+                const uint4v ap = join(lds_read_tr16(tp + ta), lds_read_tr16(tp + ta + 4 * kTPad));
+                const uint4v ah = join(lds_read_tr16(th + ta), lds_read_tr16(th + ta + 4 * kTPad));
+                const uint4v al = join(lds_read_tr16(tl + ta), lds_read_tr16(tl + ta + 4 * kTPad));
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const int col = 32 * nb + 16 * tr_grp + 4 * (tr_r & 3);
-                    const uint2v g0 = lds_read_tr16(&sm.g[buf][swz_elem<KCH>(qa, col)]);
-                    const uint2v g1 = lds_read_tr16(&sm.g[buf][swz_elem<KCH>(qa + 4, col)]);
-                    uint4v bg; bg[0] = g0[0]; bg[1] = g0[1]; bg[2] = g1[0]; bg[3] = g1[1];
+                    const uint4v bg = join(lds_read_tr16(gt_ + goff[nb][0] + ks * (16 * D)), lds_read_tr16(gt_ + goff[nb][1] + ks * (16 * D)));
+                    const uint4v bq = join(lds_read_tr16(qt_ + goff[nb][0] + ks * (16 * D)), lds_read_tr16(qt_ + goff[nb][1] + ks * (16 * D)));
                     dv[nb] = mfma_bf16(ap, bg, dv[nb]);                // dV += P^F^T dO
-                    const uint2v q0_ = lds_read_tr16(&sm.q[buf][swz_elem<KCH>(qa, col)]);
-                    const uint2v q1_ = lds_read_tr16(&sm.q[buf][swz_elem<KCH>(qa + 4, col)]);
-                    uint4v bq; bq[0] = q0_[0]; bq[1] = q0_[1]; bq[2] = q1_[0]; bq[3] = q1_[1];
                     dk[nb] = mfma_bf16(ah, bq, dk[nb]);                // dK += dS^T Q^F
                     dk[nb] = mfma_bf16(al, bq, dk[nb]);
                 }
             }
             __builtin_amdgcn_wave_barrier();
         }
+        cur_g = nx_g; cur_t = nx_t;
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }

@@ -62,6 +62,14 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
     const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;     // tiles this workgroup visits
     const int wave_qmax = qt * 128 + wave * 32 + 31;
 
+    // LDS element offsets of this lane's operand reads (buffer 0, row block 0); the row blocks
+    // kb / mb add compile-time constants because a row's swizzle key survives adding 32 rows.
+    int koff[DS], voff[4];
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) koff[ds] = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) voff[ks] = (ln * 8 + swz<8>(ln, 2 * ks + hf)) * 8;
+
     // per-lane global sources of the direct-to-LDS tile loads (advance by one tile per step)
     const half_t* ksrc[KLD];
     const half_t* vsrc[VLD];
@@ -101,17 +109,33 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
         const bool active = !CAUSAL || k0 <= wave_qmax;          // wave-uniform
 
         if (active) {
-            // ---- S^T = K^F Q^F^T
+            // ---- S^T = K^F Q^F^T.  A wave sustains about one 1 KiB LDS read per 40 cycles and the
+            // read latency is ~130 cycles, so the K operands are read RING steps ahead of the MFMA
+            // that consumes them (the scheduling groups below keep the compiler from sinking them).
             floatx16 s[2];
+            {
+                const half_t* kt_ = &sm.k[buf][0];
+                constexpr int NS = 2 * DS, RING = 6;
+                half8 ring[RING];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+                for (int i = 0; i < RING; ++i)
+                    ring[i] = *reinterpret_cast<const half8*>(kt_ + koff[i >> 1] + (i & 1) * (32 * D));
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
-                const int r = 32 * kb + ln;
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int ds = 0; ds < DS; ++ds) {
-                    const half8 a = *reinterpret_cast<const half8*>(&sm.k[buf][(r * KCH + swz<KCH>(r, 2 * ds + hf)) * 8]);
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[ds], s[kb], 0, 0, 0);
+                    for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {                  // step i: ds = i / 2, kb = i % 2
+                    const half8 a = ring[i % RING];
+                    if (i + RING < NS)
+                        ring[i % RING] = *reinterpret_cast<const half8*>(kt_ + koff[(i + RING) >> 1] + ((i + RING) & 1) * (32 * D));
+                    s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[i >> 1], s[i & 1], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (i + RING < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
             }
             // ---- mask: keys beyond L, and keys after the query when causal
@@ -157,6 +181,10 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 const int kb = ks >> 1, g = ks & 1;
+                half8 av[MB];                                   // this step's V^F^T operands, in flight during phi
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    av[mb] = *reinterpret_cast<const half8*>(&sm.v[buf][voff[ks] + mb * (32 * 64)]);
                 float amax = s[kb][8 * g];
 #pragma unroll
                 for (int i = 1; i < 8; ++i) amax = fmaxf(amax, s[kb][8 * g + i]);
@@ -190,11 +218,9 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
                 const half8 bqh = __builtin_bit_cast(half8, bq);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    const int r = 32 * mb + ln;
-                    const half8 a = *reinterpret_cast<const half8*>(&sm.v[buf][(r * 8 + swz<8>(r, 2 * ks + hf)) * 8]);
-                    o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bqh, o[mb], 0, 0, 0);
+                    o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], bqh, o[mb], 0, 0, 0);
                     if constexpr (TRAIN)
-                        op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, __builtin_bit_cast(half8, bu), op[mb], 0, 0, 0);
+                        op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], __builtin_bit_cast(half8, bu), op[mb], 0, 0, 0);
                 }
             }
         }
