@@ -22,6 +22,9 @@ sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16 MFMA
 KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}
+# HBM-side bytes per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
+# measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
+MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 151.0e9, "bwd_dq": 361.1e9, "bwd_dkdv": 210.2e9}}
 
 
 def main():
@@ -112,7 +115,8 @@ def main():
     dom = max((n for n in kern_ms if n in KERNEL_GEMMS), key=lambda n: kern_ms[n])
     achieved = KERNEL_GEMMS[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
                 "kernel_ms": round(kern_ms[dom], 3),
                 "per_kernel": {n: {"ms": round(ms, 3),
                                    "tflops": round(KERNEL_GEMMS[n] * pair_flops / (ms * 1e-3) / 1e12, 2)
