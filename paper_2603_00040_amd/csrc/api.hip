@@ -67,8 +67,8 @@ FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     return w;
 }
 
-// Workspace of the backward: bf16 row-major copies (dO is not exactly representable in fp16) and D.
-struct BwdWs { void *qb, *kb, *vb, *dob; float* delta; size_t bytes; };
+// Workspace of the backward: bf16 row-major copies (dO is not exactly representable in fp16) and the per-row {L, D} pairs.
+struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; size_t bytes; };
 BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
 {
     const size_t Lp = round_up(L, kRowPad);
@@ -76,7 +76,7 @@ BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     BwdWs w;
     const size_t nq = (size_t)B * Hq * Lp * d * 2, nk = (size_t)B * Hkv * Lp * d * 2;
     w.qb = c.take(nq); w.kb = c.take(nk); w.vb = c.take(nk); w.dob = c.take(nq);
-    w.delta = (float*)c.take((size_t)B * Hq * Lp * 4);
+    w.rowstat = (float*)c.take((size_t)B * Hq * Lp * 8);
     w.bytes = c.off;
     return w;
 }
@@ -215,12 +215,12 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
     if (launch_prep(v, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
-    if (launch_delta(d_o, o_hp, B * Hq, L, d, w.delta, st)) return ATTNQAT_ELAUNCH;
+    if (launch_delta(d_o, o_hp, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
     prof_mark("delta", st);
-    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dq, st))
+    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, B, Hq, Hkv, L, d, causal != 0, dq, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
-    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, lse, w.delta, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
+    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;

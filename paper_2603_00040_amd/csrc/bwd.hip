@@ -41,10 +41,13 @@ __device__ inline floatx16 mfma_bf16(uint4v a, uint4v b, floatx16 c) {
 }
 __device__ inline uint4v join(uint2v a, uint2v b) { uint4v r; r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1]; return r; }
 
-// ------------------------------------------------------------------ delta
+// ------------------------------------------------------------------ per-row statistics
+// rowstat[bh*Lp + l] = { L_l * log2(e), D_l / sqrt(d) } with D = rowsum(dO o O'); rows l >= L
+// (padding) hold {0, 0}.  Both attention passes read them as they are.
 template <int D>
 __global__ __launch_bounds__(256) void delta_kernel(const uint16_t* __restrict__ dO, const float* __restrict__ Ohp,
-                                                    int L, int Lp, long nrows_p, float* __restrict__ delta)
+                                                    const float* __restrict__ lse,
+                                                    int L, int Lp, long nrows_p, float rs, float2* __restrict__ rowstat)
 {
     constexpr int TPR = D / 8;                 // threads per row
     const long r = (long)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;    // padded row id: bh*Lp + l
@@ -65,17 +68,18 @@ __global__ __launch_bounds__(256) void delta_kernel(const uint16_t* __restrict__
     }
 #pragma unroll
     for (int w = TPR / 2; w >= 1; w >>= 1) acc += __shfl_xor(acc, w);
-    if (c == 0) delta[r] = acc;
+    if (c == 0) rowstat[r] = make_float2(l < L ? lse[(size_t)bh * L + l] * 1.4426950408889634f : 0.0f, acc * rs);
 }
 
-int launch_delta(const void* d_o, const float* o_hp, int BHq, int L, int D, float* delta, hipStream_t st)
+int launch_delta(const void* d_o, const float* o_hp, const float* lse, int BHq, int L, int D, float* rowstat, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const long nrows_p = (long)BHq * Lp;
     const int rpb = 256 / (D / 8);
     const unsigned grid = (unsigned)((nrows_p + rpb - 1) / rpb);
-    if (D == 128) hipLaunchKernelGGL(delta_kernel<128>, dim3(grid), dim3(256), 0, st, (const uint16_t*)d_o, o_hp, L, Lp, nrows_p, delta);
-    else          hipLaunchKernelGGL(delta_kernel<64>, dim3(grid), dim3(256), 0, st, (const uint16_t*)d_o, o_hp, L, Lp, nrows_p, delta);
+    const float rs = 1.0f / sqrtf((float)D);
+    if (D == 128) hipLaunchKernelGGL(delta_kernel<128>, dim3(grid), dim3(256), 0, st, (const uint16_t*)d_o, o_hp, lse, L, Lp, nrows_p, rs, (float2*)rowstat);
+    else          hipLaunchKernelGGL(delta_kernel<64>, dim3(grid), dim3(256), 0, st, (const uint16_t*)d_o, o_hp, lse, L, Lp, nrows_p, rs, (float2*)rowstat);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -90,7 +94,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb,
-    const float* __restrict__ lse, const float* __restrict__ delta, uint16_t* __restrict__ dQ,
+    const float2* __restrict__ rowstat, uint16_t* __restrict__ dQ,
     int L, int Lp, int Hq, int G, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */)
 {
     constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, KLD = KCH / 4;
@@ -115,8 +119,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
             doreg[ds] = *reinterpret_cast<const uint4v*>(dOb + off + 16 * ds);
         }
     }
-    const float Ls = (q_row < L ? lse[(size_t)bh * L + q_row] : 0.0f) * 1.4426950408889634f;
-    const float Dqs = delta[(size_t)bh * Lp + q_row] * rs;          // D_i / sqrt(d)
+    const float2 st_ = rowstat[(size_t)bh * Lp + q_row];
+    const float Ls = st_.x, Dqs = st_.y;                             // L_i log2(e), D_i / sqrt(d)
 
     const int nkt_all = (L + 63) / 64;
     const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
             }
             // masked keys (beyond L, or after the query): S = -inf so that P = 0
             const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > qt * 128 + wave * 32);
-            if (need_mask) {
+            if (__builtin_expect(need_mask, 0)) {
                 const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
 
 template <int D, bool CAUSAL>
 static int launch_dq_t(const void* qb, const void* kb, const void* vb, const void* dob,
-                       const float* lse, const float* delta, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st)
+                       const float* rowstat, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DqSmem<D>);
@@ -269,19 +273,19 @@ static int launch_dq_t(const void* qb, const void* kb, const void* vb, const voi
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
-                       (const uint16_t*)dob, lse, delta, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv,
+                       (const uint16_t*)dob, (const float2*)rowstat, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv,
                        1.4426950408889634f * rs, rs);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
-                  const float* lse, const float* delta,
+                  const float* rowstat,
                   int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dq_t<128, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<128, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st);
-    if (D == 64)  return causal ? launch_dq_t<64, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<64, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dq, st);
+    if (D == 128) return causal ? launch_dq_t<128, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st)
+                                : launch_dq_t<128, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st);
+    if (D == 64)  return causal ? launch_dq_t<64, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st)
+                                : launch_dq_t<64, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st);
     return -1;
 }
 
@@ -300,8 +304,7 @@ struct DkvSmem {
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
-    const uint16_t* __restrict__ dOb,
-    const float* __restrict__ lse, const float* __restrict__ delta,
+    const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat,
     uint16_t* __restrict__ dK, uint16_t* __restrict__ dV,
     int L, int Lp, int Hq, int G, float c, float rs)
 {
@@ -365,34 +368,28 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
         }
         if (++ld_t == per_head) { ld_t = 0; ++ld_g; }
     };
-    // L_i and D_i of this lane's query row of a tile (clamped rows carry P = anything, dO = 0)
-    auto row_scalars = [&](int g, int t, float& Ls, float& Dqs) __attribute__((always_inline)) {
-        const int q_row = (qt_first + t) * 32 + ln;
-        Ls = (q_row < L ? lse[(bh0 + g) * L + q_row] : 0.0f) * 1.4426950408889634f;
-        Dqs = delta[(bh0 + g) * Lp + q_row] * rs;
-    };
 
-    // LDS element offsets (buffer 0)
-    //   qoff[ds]    16-byte reads of Q / dO rows: row ln, d-slots 16*ds + 8*hf
-    //   goff[nb][v] transpose reads of Q / dO columns: lane r of a group of 16 points at query
-    //               8*hf + r/4 + 4*v, columns 32*nb + 16*grp + 4*(r%4)
+    // LDS byte offsets.  A row of a tile is D*2 bytes = KCH 16-byte chunks and chunk c of row r sits
+    // at chunk c ^ key(r), so an offset is (per-lane constant) XOR (compile-time constant):
+    //   operand reads of Q / dO rows (row ln, d-slots 16*ds + 8*hf):   a_rd ^ (ds << 5)
+    //   transpose reads of Q / dO columns (lane r of a group of 16 points at query
+    //   8*hf + r/4 + 4*v, columns 32*nb + 16*grp + 4*(r%4)):           g_rd[v] ^ (nb << 6)
+    // 16 more rows, the other buffer and the dO tile are constant byte distances.
+    constexpr int kRowB = 2 * D, kBufB = 32 * kRowB, kGB = 2 * kBufB;
     const int tr_r = lane & 15, tr_grp = (lane >> 4) & 1;
-    int qoff[DS], goff[NB][2];
+    const int a_rd = 2 * swz_elem<KCH>(ln, 8 * hf);
+    int g_rd[2];
 #pragma unroll
-    for (int ds = 0; ds < DS; ++ds) qoff[ds] = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 2; ++v)
-            goff[nb][v] = swz_elem<KCH>(8 * hf + (tr_r >> 2) + 4 * v, 32 * nb + 16 * tr_grp + 4 * (tr_r & 3));
+    for (int v = 0; v < 2; ++v) g_rd[v] = 2 * swz_elem<KCH>(8 * hf + (tr_r >> 2) + 4 * v, 16 * tr_grp + 4 * (tr_r & 3));
     const int tw_off = ln * kTPad + 4 * hf;                                    // staging tile: this lane's writes
     const int ta_off = (8 * hf + (tr_r >> 2)) * kTPad + 16 * tr_grp + 4 * (tr_r & 3);   // ... and transpose reads
     uint16_t* tp = &sm.t[wave][0][0];
     uint16_t* th = &sm.t[wave][1][0];
     uint16_t* tl = &sm.t[wave][2][0];
 
-    float Ls_n = 0.0f, Dqs_n = 0.0f;
-    if (niter > 0) { issue_next(0); row_scalars(0, 0, Ls_n, Dqs_n); }
+    // {L_i log2(e), D_i / sqrt(d)} of this lane's query row of the next tile
+    float2 st_n = make_float2(0.0f, 0.0f);
+    if (niter > 0) { issue_next(0); st_n = rowstat[bh0 * Lp + (size_t)qt_first * 32 + ln]; }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -400,20 +397,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     for (int it = 0; it < niter; ++it) {
         const int buf = it & 1;
         const int q0 = (qt_first + cur_t) * 32;
-        const float Ls = Ls_n, Dqs = Dqs_n;
+        const float Ls = st_n.x, Dqs = st_n.y;
         // next tile: start its copy and fetch its row scalars now, they are needed one iteration later
         int nx_g = cur_g, nx_t = cur_t + 1;
         if (nx_t == per_head) { nx_t = 0; ++nx_g; }
-        if (it + 1 < niter) { issue_next(buf ^ 1); row_scalars(nx_g, nx_t, Ls_n, Dqs_n); }
+        if (it + 1 < niter) {
+            issue_next(buf ^ 1);
+            st_n = rowstat[(bh0 + nx_g) * Lp + (size_t)(qt_first + nx_t) * 32 + ln];
+        }
         const bool active = !CAUSAL || q0 + 31 >= key0_w;          // wave-uniform
         if (active) {
-            const uint16_t* qt_ = &sm.q[buf][0];
-            const uint16_t* gt_ = &sm.g[buf][0];
+            // Q^F tile of this iteration (dO is kGB further).  The per-lane offsets are made opaque once
+            // per iteration: otherwise the compiler hoists every (offset ^ constant) out of the loop and
+            // pays for it with a dozen registers that this kernel does not have.
+            const unsigned char* tile = smem_raw;
+            int a_it = a_rd + buf * kBufB, g_it0 = g_rd[0] + buf * kBufB, g_it1 = g_rd[1] + buf * kBufB;
+            asm volatile("" : "+v"(a_it), "+v"(g_it0), "+v"(g_it1));
             floatx16 s, dp;
             {   // S^T = K^F Q^F^T, dP^T = V^F dO^T: 2*DS steps, step i: ds = i/2, Q or dO = i%2
-                constexpr int NST = 2 * DS, RING = 4;
+                constexpr int NST = 2 * DS, RING = 3;
                 auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
-                    return *reinterpret_cast<const uint4v*>(((i & 1) ? gt_ : qt_) + qoff[i >> 1]);
+                    return lds_read16(tile + (a_it ^ ((i >> 1) << 5)) + (i & 1) * kGB);
                 };
                 uint4v ring[RING];
 #pragma unroll
@@ -436,7 +440,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             }
             // masked keys (beyond L, or after the query): S = -inf so that P = 0
             const bool need_mask = (key0_w + 32 > L) || (CAUSAL && key0_w + 31 > q0);
-            if (need_mask) {
+            if (__builtin_expect(need_mask, 0)) {
                 const int klim = CAUSAL ? min(L - 1, q0 + ln) : L - 1;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
@@ -486,8 +490,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 const uint4v al = join(lds_read_tr16(tl + ta), lds_read_tr16(tl + ta + 4 * kTPad));
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const uint4v bg = join(lds_read_tr16(gt_ + goff[nb][0] + ks * (16 * D)), lds_read_tr16(gt_ + goff[nb][1] + ks * (16 * D)));
-                    const uint4v bq = join(lds_read_tr16(qt_ + goff[nb][0] + ks * (16 * D)), lds_read_tr16(qt_ + goff[nb][1] + ks * (16 * D)));
+                    const int o0 = (g_it0 ^ (nb << 6)) + ks * (16 * kRowB), o1 = (g_it1 ^ (nb << 6)) + ks * (16 * kRowB);
+                    const uint4v bg = join(lds_read_tr16b(tile + o0 + kGB), lds_read_tr16b(tile + o1 + kGB));
+                    const uint4v bq = join(lds_read_tr16b(tile + o0), lds_read_tr16b(tile + o1));
                     dv[nb] = mfma_bf16(ap, bg, dv[nb]);                // dV += P^F^T dO
                     dk[nb] = mfma_bf16(ah, bq, dk[nb]);                // dK += dS^T Q^F
                     dk[nb] = mfma_bf16(al, bq, dk[nb]);
@@ -516,7 +521,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 
 template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
-                         const float* lse, const float* delta,
+                         const float* rowstat,
                          int B, int Hq, int Hkv, int L, void* dk, void* dv, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
@@ -527,19 +532,19 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
-                       (const uint16_t*)dob, lse, delta, (uint16_t*)dk, (uint16_t*)dv,
+                       (const uint16_t*)dob, (const float2*)rowstat, (uint16_t*)dk, (uint16_t*)dv,
                        L, Lp, Hq, Hq / Hkv, 1.4426950408889634f * rs, rs);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
-                    const float* lse, const float* delta,
+                    const float* rowstat,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st);
-    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, lse, delta, B, Hq, Hkv, L, dk, dv, st);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st)
+                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st);
+    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st)
+                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st);
     return -1;
 }
 

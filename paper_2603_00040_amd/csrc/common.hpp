@@ -132,6 +132,11 @@ __device__ inline uint2v lds_read_tr16(const uint16_t* p) {
     const short4v r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
     return __builtin_bit_cast(uint2v, r);
 }
+__device__ inline uint2v lds_read_tr16b(const unsigned char* p) { return lds_read_tr16(reinterpret_cast<const uint16_t*>(p)); }
+// Plain 16-byte LDS read at a byte address.
+__device__ inline uint4v lds_read16(const unsigned char* p) {
+    return *(const __attribute__((address_space(3))) uint4v*)p;
+}
 // One wave copies 1 KiB: LDS chunk slot (wave-uniform slot0 + lane) <- its global source.
 __device__ inline void async_copy16(const void* gsrc, void* lds_wave_base) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,

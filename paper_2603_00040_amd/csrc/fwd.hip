@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
             }
             // ---- mask: keys beyond L, and keys after the query when causal
             const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > qt * 128 + wave * 32);
-            if (need_mask) {
+            if (__builtin_expect(need_mask, 0)) {
                 const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)

@@ -18,17 +18,18 @@ int launch_fwd(const void* qh, const void* kh, const void* vt,
                int B, int Hq, int Hkv, int L, int D, bool causal, bool train,
                void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st);
 
-// D = rowsum(dO o O') (Alg. 3, first line).  d_o bf16, o_hp fp32, [rows, D]; delta [BHq, Lp].
-int launch_delta(const void* d_o, const float* o_hp, int BHq, int L, int D, float* delta, hipStream_t st);
+// Per-row statistics of the backward: rowstat [BHq, Lp, 2] = {L log2(e), D / sqrt(d)} with
+// D = rowsum(dO o O') (Alg. 3, first line); padding rows hold zeros.  d_o bf16, o_hp fp32, [rows, D].
+int launch_delta(const void* d_o, const float* o_hp, const float* lse, int BHq, int L, int D, float* rowstat, hipStream_t st);
 
 // Alg. 3, query-stationary pass: dQ.
 int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
-                  const float* lse, const float* delta,
+                  const float* rowstat,
                   int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st);
 
 // Alg. 3, key-stationary pass: dK, dV (summed over the query heads of a group).
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
-                    const float* lse, const float* delta,
+                    const float* rowstat,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st);
 
 }  // namespace aq
