@@ -22,6 +22,7 @@
 // LDS reads are the scarce resource of these loops (one wave sustains about one 1 KiB read
 // per 40 cycles, latency ~130 cycles), so every operand read is issued a few MFMAs ahead of
 // its consumer and the scheduling groups pin that order.
+#include <type_traits>
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -164,6 +165,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
 
     issue_tile(0);
+    // Q, dO and the row scalars must have arrived BEFORE the loop: a load still pending at loop entry
+    // makes the compiler wait for all vector-memory traffic at the first product of every iteration,
+    // i.e. for the tile prefetch it has just issued.
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(qreg[ds]), "+v"(doreg[ds]));
+    asm volatile("" :: "v"(Ls), "v"(Dqs));
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -390,6 +397,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     // {L_i log2(e), D_i / sqrt(d)} of this lane's query row of the next tile
     float2 st_n = make_float2(0.0f, 0.0f);
     if (niter > 0) { issue_next(0); st_n = rowstat[bh0 * Lp + (size_t)qt_first * 32 + ln]; }
+    // every load of the prologue must have arrived before the loop (see the dQ pass)
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(kreg[ds]), "+v"(vreg[ds]));
+    asm volatile("" : "+v"(st_n.x), "+v"(st_n.y));
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -450,6 +461,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c, -Ls));    // P = exp(S - L_i)
+            bool nz = false;
 #pragma unroll
             for (int gq = 0; gq < 2; ++gq) {                           // phi^-1(phi(P)) per 16 keys
                 float amax = s[8 * gq];
@@ -458,6 +470,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 amax = xhalf_max(amax);
                 const float sc = rne_e4m3_grid(amax * (1.0f / 6.0f));
                 const float inv = sc > 0.0f ? __builtin_amdgcn_rcpf(sc) : 0.0f;
+                nz = nz || sc > 0.0f;
 #pragma unroll
                 for (int t4 = 0; t4 < 2; ++t4) {                       // 4 consecutive keys per store
                     const int r0 = 8 * gq + 4 * t4;
@@ -481,21 +494,53 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {                           // 16 queries per step
-                // contraction slots 0-3: queries 16*ks + 8*hf + 0..3, slots 4-7: the next four
+            // dK += dS^T Q^F (hi and lo), then dV += P^F^T dO, each in 2*NB steps: step j covers queries
+            // 16*(j/NB) .. +15 (contraction slots 0-3: queries 16*ks + 8*hf + 0..3, slots 4-7: the next
+            // four) and columns 32*(j%NB) .. +31.  The operands of step j+1 are read while step j multiplies.
+            constexpr int NSTEP = 2 * NB;
+            auto rd_b = [&](int j, int extra) __attribute__((always_inline)) -> uint4v {
+                const int nb = j % NB, ks = j / NB;
+                return join(lds_read_tr16b(tile + (g_it0 ^ (nb << 6)) + ks * (16 * kRowB) + extra),
+                            lds_read_tr16b(tile + (g_it1 ^ (nb << 6)) + ks * (16 * kRowB) + extra));
+            };
+            auto rd_t = [&](const uint16_t* t, int ks) __attribute__((always_inline)) -> uint4v {
                 const int ta = ta_off + ks * (16 * kTPad);
-                const uint4v ap = join(lds_read_tr16(tp + ta), lds_read_tr16(tp + ta + 4 * kTPad));
-                const uint4v ah = join(lds_read_tr16(th + ta), lds_read_tr16(th + ta + 4 * kTPad));
-                const uint4v al = join(lds_read_tr16(tl + ta), lds_read_tr16(tl + ta + 4 * kTPad));
+                return join(lds_read_tr16(t + ta), lds_read_tr16(t + ta + 4 * kTPad));
+            };
+            {
+                uint4v ah = rd_t(th, 0), al = rd_t(tl, 0), bq[2];
+                bq[0] = rd_b(0, 0);
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int o0 = (g_it0 ^ (nb << 6)) + ks * (16 * kRowB), o1 = (g_it1 ^ (nb << 6)) + ks * (16 * kRowB);
-                    const uint4v bg = join(lds_read_tr16b(tile + o0 + kGB), lds_read_tr16b(tile + o1 + kGB));
-                    const uint4v bq = join(lds_read_tr16b(tile + o0), lds_read_tr16b(tile + o1));
-                    dv[nb] = mfma_bf16(ap, bg, dv[nb]);                // dV += P^F^T dO
-                    dk[nb] = mfma_bf16(ah, bq, dk[nb]);                // dK += dS^T Q^F
-                    dk[nb] = mfma_bf16(al, bq, dk[nb]);
+                for (int j = 0; j < NSTEP; ++j) {
+                    const int nb = j % NB;
+                    if (j + 1 < NSTEP) bq[(j + 1) & 1] = rd_b(j + 1, 0);
+                    uint4v ah_n, al_n;
+                    if (j == NB - 1) { ah_n = rd_t(th, 1); al_n = rd_t(tl, 1); }
+                    dk[nb] = mfma_bf16(ah, bq[j & 1], dk[nb]);
+                    dk[nb] = mfma_bf16(al, bq[j & 1], dk[nb]);
+                    if (j == NB - 1) { ah = ah_n; al = al_n; }
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, 4 + 2, 0);
+#pragma unroll
+                for (int j = 0; j < NSTEP; ++j) {
+                    if (j + 1 < NSTEP) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    if (j == NB - 1) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                }
+            }
+            // If every block scale of this 32x32 tile rounded to 0 (max P <= 6 * 2^-10: the usual case
+            // for long rows), P^F is identically 0 and the dV products add nothing.  Wave-uniform, exact.
+            if (__builtin_amdgcn_ballot_w64(nz) != 0) {
+                uint4v ap = rd_t(tp, 0), bg[2];
+                bg[0] = rd_b(0, kGB);
+#pragma unroll
+                for (int j = 0; j < NSTEP; ++j) {
+                    const int nb = j % NB;
+                    if (j + 1 < NSTEP) bg[(j + 1) & 1] = rd_b(j + 1, kGB);
+                    uint4v ap_n;
+                    if (j == NB - 1) ap_n = rd_t(tp, 1);
+                    dv[nb] = mfma_bf16(ap, bg[j & 1], dv[nb]);
+                    if (j == NB - 1) ap = ap_n;
                 }
             }
             __builtin_amdgcn_wave_barrier();
@@ -503,6 +548,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
         cur_g = nx_g; cur_t = nx_t;
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        asm volatile("" : "+v"(st_n.x), "+v"(st_n.y));     // the next tile's row scalars are consumed here, not earlier
     }
 
     // accumulators: row = key 8*(i>>2) + 4*hf + (i&3) of the wave, column d = 32*nb + ln

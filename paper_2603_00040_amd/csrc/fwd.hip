@@ -99,6 +99,11 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
     float m = -INFINITY, lsum = 0.0f;     // lsum: this half-wave's part of l (same alpha in both halves)
 
     issue_tile(0);
+    // The Q registers must have arrived BEFORE the loop: a load still pending at loop entry makes the
+    // compiler wait for all vector-memory traffic at the first product of every iteration, i.e. for
+    // the tile prefetch it has just issued.
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(qreg[ds]));
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
