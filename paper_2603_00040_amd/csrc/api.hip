@@ -67,8 +67,9 @@ FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     return w;
 }
 
-// Workspace of the backward: bf16 row-major copies (dO is not exactly representable in fp16) and the per-row {L, D} pairs.
-struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; size_t bytes; };
+// Workspace of the backward: row-major copies (Q^F, K^F fp16; V^F and dO bf16: dO is not exactly
+// representable in fp16), the per-row {L, D} pairs and the partial maxima that bound |dS|.
+struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; float* bounds; size_t bytes; };
 BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
 {
     const size_t Lp = round_up(L, kRowPad);
@@ -77,6 +78,7 @@ BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     const size_t nq = (size_t)B * Hq * Lp * d * 2, nk = (size_t)B * Hkv * Lp * d * 2;
     w.qb = c.take(nq); w.kb = c.take(nk); w.vb = c.take(nk); w.dob = c.take(nq);
     w.rowstat = (float*)c.take((size_t)B * Hq * Lp * 8);
+    w.bounds = (float*)c.take((size_t)3 * B * Hq * 64 * 4);
     w.bytes = c.off;
     return w;
 }
@@ -210,17 +212,18 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
     // Q^F, K^F, V^F again (bit-identical to the forward's) and a zero-padded copy of dO
-    if (launch_prep(q, B * Hq, L, d, true, false, nullptr, nullptr, nullptr, w.qb, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_prep(k, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.kb, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(q, B * Hq, L, d, true, true, nullptr, nullptr, nullptr, w.qb, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_prep(k, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, w.kb, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(v, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
     if (launch_delta(d_o, o_hp, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
+    if (launch_bounds(w.vb, w.dob, w.rowstat, B * Hkv, B * Hq, L, d, w.bounds, st)) return ATTNQAT_ELAUNCH;
     prof_mark("delta", st);
-    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, B, Hq, Hkv, L, d, causal != 0, dq, st))
+    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dq, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
-    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
+    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;

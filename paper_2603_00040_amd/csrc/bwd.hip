@@ -1,5 +1,6 @@
-// Backward of Attn-QAT on gfx950 (Alg. 3), as three kernels:
-//   delta      D = rowsum(dO o O')                        (first line of Alg. 3; HBM bound)
+// Backward of Attn-QAT on gfx950 (Alg. 3), as four kernels:
+//   delta      D = rowsum(dO o O') and the per-row {L, D} pairs   (first line of Alg. 3; HBM bound)
+//   bounds     per-head maxima of |dO_i|, |V^F_j| and |D_i|: they bound |dS|   (HBM bound)
 //   bwd_dq     query-stationary: S, P, dP, dS, dQ += dS K^F
 //   bwd_dkdv   key-stationary:   S, P, P^F, dP, dS, dV += P^F^T dO, dK += dS^T Q^F
 // The paper's single loop nest accumulates dQ across key tiles; here dQ gets its own pass
@@ -7,10 +8,16 @@
 // two-pass form of the Triton tutorial kernel the paper extends), which keeps every
 // output deterministic.
 //
-// MFMA: v_mfma_f32_32x32x16_bf16.  Q^F, K^F, V^F and P^F are exact in bf16 and dO is bf16
-// input, so S, dP and dV see exact operands.  dS is fp32: it enters its two products as a
-// bf16 pair hi + lo (hi = RNE(dS), lo = RNE(dS - hi)), which keeps 16 significant bits;
-// a single bf16 would by itself cost about 1.7e-3 relative L2 in dQ and dK.
+// MFMA: v_mfma_f32_32x32x16_{f16,bf16}.  Q^F, K^F, V^F and P^F are exact in both 16-bit
+// formats and dO is bf16 input, so S (fp16 operands), dP and dV (bf16 operands) see exact
+// operands.  dS is fp32 and the only rounded operand: it enters its two products (with K^F
+// and with Q^F, both fp16) as fp16, 11 significant bits, after multiplication by a power of
+// two chosen from an upper bound of |dS| so that nothing overflows and the values that matter
+// stay clear of the subnormals:
+//     |dS_ij| = P_ij |dP_ij - D_i| / sqrt(d) <= (|dO_i| max_j |V^F_j| + |D_i|) / sqrt(d)
+// (P <= 1, Cauchy-Schwarz).  The dQ pass scales per query row, the dK/dV pass per kv head; the
+// accumulators are divided by the same power of two at the end.  A single bf16 (8 bits)
+// would by itself cost about 1.7e-3 relative L2 in dQ and dK.
 //
 // As in the forward, S and dP are computed transposed ([key, query]) so that a lane owns
 // one query row: L_i, D_i are per-lane scalars and the 16-key blocks of phi(P) are
@@ -39,6 +46,17 @@ __device__ inline float bf16_hi_f32(uint32_t w) { return __uint_as_float(w & 0xF
 
 __device__ inline floatx16 mfma_bf16(uint4v a, uint4v b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ inline floatx16 mfma_f16(uint4v a, uint4v b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+}
+// Largest power of two <= kDsTop / bound (bound >= 0), kept inside [2^-60, 2^60]: the factor that dS
+// is multiplied by before it is rounded to fp16.
+constexpr float kDsTop = 49152.0f;
+__device__ inline float ds_scale_for(float bound) {
+    float t = kDsTop / fmaxf(bound, 1e-30f);
+    t = fminf(fmaxf(t, 8.7e-19f), 1.15e18f);
+    return __uint_as_float(__float_as_uint(t) & 0x7F800000u);
 }
 __device__ inline uint4v join(uint2v a, uint2v b) { uint4v r; r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1]; return r; }
 
@@ -84,19 +102,89 @@ int launch_delta(const void* d_o, const float* o_hp, const float* lse, int BHq, 
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// ------------------------------------------------------------------ bounds of |dS|
+// part[(which*NH + head)*kBoundParts + chunk]: maxima over the chunk's rows of
+//   which 0: |V^F_j|_2 (kv heads)   1: |dO_i|_2 (query heads)   2: |D_i|/sqrt(d) (query heads)
+// No atomics and no initialisation: the consumers reduce the kBoundParts partial maxima.
+constexpr int kBoundParts = 64;
+
+template <int D>
+__global__ __launch_bounds__(256) void bounds_kernel(const uint16_t* __restrict__ Vb, const uint16_t* __restrict__ dOb,
+                                                     const float2* __restrict__ rowstat, int Lp, int NHkv, int NHq,
+                                                     float* __restrict__ part)
+{
+    constexpr int TPR = D / 8, RPP = 256 / TPR;      // threads per row, rows per pass
+    __shared__ float red[2][4];
+    const int head = blockIdx.y, chunk = blockIdx.x;
+    const bool is_v = head < NHkv;
+    const int h = is_v ? head : head - NHkv;
+    const uint16_t* src = (is_v ? Vb : dOb) + (size_t)h * Lp * D;
+    const int rows_per = (Lp + kBoundParts - 1) / kBoundParts;
+    const int r_begin = chunk * rows_per, r_end = min(Lp, r_begin + rows_per);
+    const int c = threadIdx.x % TPR;
+    float nmax = 0.0f, dmax = 0.0f;
+    for (int r = r_begin + threadIdx.x / TPR; r < r_end; r += RPP) {
+        const uint4v g = *reinterpret_cast<const uint4v*>(src + (size_t)r * D + 8 * c);
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float lo = bf16_lo_f32(g[i]), hi = bf16_hi_f32(g[i]);
+            acc = fmaf(lo, lo, fmaf(hi, hi, acc));
+        }
+#pragma unroll
+        for (int w = TPR / 2; w >= 1; w >>= 1) acc += __shfl_xor(acc, w);
+        nmax = fmaxf(nmax, acc);
+        if (!is_v && c == 0) dmax = fmaxf(dmax, fabsf(rowstat[(size_t)h * Lp + r].y));
+    }
+#pragma unroll
+    for (int w = 32; w >= 1; w >>= 1) { nmax = fmaxf(nmax, __shfl_xor(nmax, w)); dmax = fmaxf(dmax, __shfl_xor(dmax, w)); }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = nmax; red[1][threadIdx.x >> 6] = dmax; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        nmax = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+        dmax = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+        const float nrm = sqrtf(nmax) * 1.0001f;     // rounded up a little: it is an upper bound
+        if (is_v) part[(size_t)h * kBoundParts + chunk] = nrm;
+        else {
+            part[((size_t)NHq + h) * kBoundParts + chunk] = nrm;
+            part[((size_t)2 * NHq + h) * kBoundParts + chunk] = dmax;
+        }
+    }
+}
+
+// One of the three maxima of a head: every lane gets the maximum of the head's partial values.
+__device__ inline float bound_of(const float* __restrict__ part, int NHq, int which, int head) {
+    float v = part[((size_t)which * NHq + head) * kBoundParts + (threadIdx.x & 63)];
+#pragma unroll
+    for (int w = 32; w >= 1; w >>= 1) v = fmaxf(v, __shfl_xor(v, w));
+    return v;
+}
+
+int launch_bounds(const void* vb, const void* dob, const float* rowstat, int BHkv, int BHq, int L, int D,
+                  float* part, hipStream_t st)
+{
+    const int Lp = round_up(L, kRowPad);
+    dim3 grid(kBoundParts, BHkv + BHq);
+    if (D == 128) hipLaunchKernelGGL(bounds_kernel<128>, grid, dim3(256), 0, st, (const uint16_t*)vb, (const uint16_t*)dob,
+                                     (const float2*)rowstat, Lp, BHkv, BHq, part);
+    else          hipLaunchKernelGGL(bounds_kernel<64>, grid, dim3(256), 0, st, (const uint16_t*)vb, (const uint16_t*)dob,
+                                     (const float2*)rowstat, Lp, BHkv, BHq, part);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 // ------------------------------------------------------------------ dQ pass
 template <int D>
 struct DqSmem {
-    uint16_t k[2][64 * D];       // K^F tile [key][d], swizzled
-    uint16_t v[2][64 * D];       // V^F tile [key][d], swizzled
+    uint16_t k[2][64 * D];       // K^F tile [key][d], fp16, swizzled
+    uint16_t v[2][64 * D];       // V^F tile [key][d], bf16, swizzled
 };
 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb,
-    const float2* __restrict__ rowstat, uint16_t* __restrict__ dQ,
-    int L, int Lp, int Hq, int G, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */)
+    const float2* __restrict__ rowstat, const float* __restrict__ bound_part, uint16_t* __restrict__ dQ,
+    int L, int Lp, int Hq, int G, int NHq, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */)
 {
     constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, KLD = KCH / 4;
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -121,7 +209,24 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         }
     }
     const float2 st_ = rowstat[(size_t)bh * Lp + q_row];
-    const float Ls = st_.x, Dqs = st_.y;                             // L_i log2(e), D_i / sqrt(d)
+    const float Ls = st_.x;                                          // L_i log2(e)
+    // dS of this row goes to fp16 after multiplication by ds_scale = 2^k, k from the bound
+    // (|dO_i| max_j |V^F_j| + |D_i|) / sqrt(d) >= |dS_ij|; rs_s and Dq_s carry the factor.
+    float ds_scale;
+    {
+        float n2 = 0.0f;
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float lo = bf16_lo_f32(doreg[ds][i]), hi = bf16_hi_f32(doreg[ds][i]);
+                n2 = fmaf(lo, lo, fmaf(hi, hi, n2));
+            }
+        n2 = xhalf_sum(n2);
+        const float vmax = bound_of(bound_part, NHq, 0, bhkv);
+        ds_scale = ds_scale_for((sqrtf(n2) * 1.0001f * vmax) * rs + fabsf(st_.y));
+    }
+    const float rs_s = rs * ds_scale, Dq_s = st_.y * ds_scale;        // D_i / sqrt(d), scaled
 
     const int nkt_all = (L + 63) / 64;
     const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;
@@ -170,7 +275,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     // i.e. for the tile prefetch it has just issued.
 #pragma unroll
     for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(qreg[ds]), "+v"(doreg[ds]));
-    asm volatile("" :: "v"(Ls), "v"(Dqs));
+    asm volatile("" :: "v"(Ls), "v"(rs_s), "v"(Dq_s));
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -201,7 +306,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
                     if (i + RING < NST) ring[i % RING] = opnd(i + RING);
                     const int kb = (i >> 1) & 1, ds = i >> 2;
                     if (i & 1) dp[kb] = mfma_bf16(a, doreg[ds], dp[kb]);
-                    else       s[kb] = mfma_bf16(a, qreg[ds], s[kb]);
+                    else       s[kb] = mfma_f16(a, qreg[ds], s[kb]);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
 #pragma unroll
@@ -231,23 +336,17 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
                     at[mb] = join(lds_read_tr16(kt_ + toff[mb][0] + ks * (16 * D)), lds_read_tr16(kt_ + toff[mb][1] + ks * (16 * D)));
-                uint4v bhi, blo;
+                uint4v bds;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int r0 = 8 * g + 2 * i;
                     const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][r0], c, -Ls));           // P = exp(S - L_i)
                     const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][r0 + 1], c, -Ls));
-                    const float d0 = p0 * fmaf(dp[kb][r0], rs, -Dqs);                         // dS = P (dP - D_i)/sqrt(d)
-                    const float d1 = p1 * fmaf(dp[kb][r0 + 1], rs, -Dqs);
-                    const uint32_t hi = pack_bf16x2(d0, d1);
-                    bhi[i] = hi;
-                    blo[i] = pack_bf16x2(d0 - bf16_lo_f32(hi), d1 - bf16_hi_f32(hi));
+                    // dS = P (dP - D_i)/sqrt(d), times ds_scale, to fp16
+                    bds[i] = pack_f16x2(p0 * fmaf(dp[kb][r0], rs_s, -Dq_s), p1 * fmaf(dp[kb][r0 + 1], rs_s, -Dq_s));
                 }
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    acc[mb] = mfma_bf16(at[mb], bhi, acc[mb]);
-                    acc[mb] = mfma_bf16(at[mb], blo, acc[mb]);
-                }
+                for (int mb = 0; mb < MB; ++mb) acc[mb] = mfma_f16(at[mb], bds, acc[mb]);
             }
         }
         __builtin_amdgcn_s_waitcnt(0);
@@ -256,13 +355,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
 
     if (q_row < L) {
         const size_t row = (size_t)bh * L + q_row;
+        const float un = rs / rs_s;                                  // 1 / ds_scale, exact: a power of two
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 uint2v w;
-                w[0] = pack_bf16x2(acc[mb][4 * t], acc[mb][4 * t + 1]);
-                w[1] = pack_bf16x2(acc[mb][4 * t + 2], acc[mb][4 * t + 3]);
+                w[0] = pack_bf16x2(acc[mb][4 * t] * un, acc[mb][4 * t + 1] * un);
+                w[1] = pack_bf16x2(acc[mb][4 * t + 2] * un, acc[mb][4 * t + 3] * un);
                 *reinterpret_cast<uint2v*>(dQ + row * D + 32 * mb + 8 * t + 4 * hf) = w;
             }
     }
@@ -270,7 +370,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
 
 template <int D, bool CAUSAL>
 static int launch_dq_t(const void* qb, const void* kb, const void* vb, const void* dob,
-                       const float* rowstat, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st)
+                       const float* rowstat, const float* bound_part, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DqSmem<D>);
@@ -280,19 +380,19 @@ static int launch_dq_t(const void* qb, const void* kb, const void* vb, const voi
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
-                       (const uint16_t*)dob, (const float2*)rowstat, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv,
+                       (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv, B * Hq,
                        1.4426950408889634f * rs, rs);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
-                  const float* rowstat,
+                  const float* rowstat, const float* bound_part,
                   int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dq_t<128, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<128, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st);
-    if (D == 64)  return causal ? launch_dq_t<64, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<64, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dq, st);
+    if (D == 128) return causal ? launch_dq_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st)
+                                : launch_dq_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st);
+    if (D == 64)  return causal ? launch_dq_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st)
+                                : launch_dq_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st);
     return -1;
 }
 
@@ -303,17 +403,17 @@ constexpr int kTPad = 36;            // row length (elements) of the per-wave [q
 
 template <int D>
 struct DkvSmem {
-    uint16_t q[2][32 * D];           // Q^F rows [query][d], swizzled
-    uint16_t g[2][32 * D];           // dO rows  [query][d], swizzled
-    uint16_t t[4][3][32 * kTPad];    // per wave: P^F, dS_hi, dS_lo as [query][key]
+    uint16_t q[2][32 * D];           // Q^F rows [query][d], fp16, swizzled
+    uint16_t g[2][32 * D];           // dO rows  [query][d], bf16, swizzled
+    uint16_t t[4][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
 };
 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
-    const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat,
+    const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
     uint16_t* __restrict__ dK, uint16_t* __restrict__ dV,
-    int L, int Lp, int Hq, int G, float c, float rs)
+    int L, int Lp, int Hq, int G, int NHq, float c, float rs)
 {
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
     constexpr int NWL = (32 * KCH) / 64;             // 1 KiB wave-loads per tile of 32 rows
@@ -354,6 +454,19 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const int niter = per_head > 0 ? per_head * G : 0;
     const size_t bh0 = (size_t)b * Hq + hk * G;      // first query head of the group
 
+    // dS goes to fp16 after multiplication by ds_scale = 2^k, one k for the kv head, from the bound
+    // (max_i |dO_i| max_j |V^F_j| + max_i |D_i|) / sqrt(d) >= |dS_ij| over the query heads of the group
+    float ds_scale;
+    {
+        float domax = 0.0f, dmax = 0.0f;
+        for (int g = 0; g < G; ++g) {
+            domax = fmaxf(domax, bound_of(bound_part, NHq, 1, (int)bh0 + g));
+            dmax = fmaxf(dmax, bound_of(bound_part, NHq, 2, (int)bh0 + g));
+        }
+        ds_scale = ds_scale_for(domax * bound_of(bound_part, NHq, 0, bhkv) * rs + dmax);
+    }
+    const float rs_s = rs * ds_scale;
+
     // direct-to-LDS loads: this wave's chunk slots and their (row, swizzled chunk)
     const bool loader = NWL >= 4 || wave < NWL;
     int slot_off[PER_WAVE];
@@ -392,7 +505,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const int ta_off = (8 * hf + (tr_r >> 2)) * kTPad + 16 * tr_grp + 4 * (tr_r & 3);   // ... and transpose reads
     uint16_t* tp = &sm.t[wave][0][0];
     uint16_t* th = &sm.t[wave][1][0];
-    uint16_t* tl = &sm.t[wave][2][0];
 
     // {L_i log2(e), D_i / sqrt(d)} of this lane's query row of the next tile
     float2 st_n = make_float2(0.0f, 0.0f);
@@ -408,7 +520,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     for (int it = 0; it < niter; ++it) {
         const int buf = it & 1;
         const int q0 = (qt_first + cur_t) * 32;
-        const float Ls = st_n.x, Dqs = st_n.y;
+        const float Ls = st_n.x, Dq_s = st_n.y * (rs_s / rs);
         // next tile: start its copy and fetch its row scalars now, they are needed one iteration later
         int nx_g = cur_g, nx_t = cur_t + 1;
         if (nx_t == per_head) { nx_t = 0; ++nx_g; }
@@ -440,7 +552,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                     const uint4v bq = ring[i % RING];
                     if (i + RING < NST) ring[i % RING] = opnd(i + RING);
                     if (i & 1) dp = mfma_bf16(vreg[i >> 1], bq, dp);
-                    else       s = mfma_bf16(kreg[i >> 1], bq, s);
+                    else       s = mfma_f16(kreg[i >> 1], bq, s);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
 #pragma unroll
@@ -478,23 +590,20 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                     fq_pair_f32(s[r0] * inv, s[r0 + 1] * inv, sc, pf[0], pf[1]);
                     fq_pair_f32(s[r0 + 2] * inv, s[r0 + 3] * inv, sc, pf[2], pf[3]);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) dsv[e] = s[r0 + e] * fmaf(dp[r0 + e], rs, -Dqs);   // dS from the fp32 P
-                    uint2v wp, wh, wl;
+                    for (int e = 0; e < 4; ++e) dsv[e] = s[r0 + e] * fmaf(dp[r0 + e], rs_s, -Dq_s);   // dS from the fp32 P, scaled
+                    uint2v wp, wh;
                     wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
-                    wh[0] = pack_bf16x2(dsv[0], dsv[1]); wh[1] = pack_bf16x2(dsv[2], dsv[3]);
-                    wl[0] = pack_bf16x2(dsv[0] - bf16_lo_f32(wh[0]), dsv[1] - bf16_hi_f32(wh[0]));
-                    wl[1] = pack_bf16x2(dsv[2] - bf16_lo_f32(wh[1]), dsv[3] - bf16_hi_f32(wh[1]));
+                    wh[0] = pack_f16x2(dsv[0], dsv[1]); wh[1] = pack_f16x2(dsv[2], dsv[3]);
                     // registers r0..r0+3 <-> keys 8*(r0>>2) + 4*hf + 0..3 of this wave's 32 keys
                     const int o = tw_off + 8 * (r0 >> 2);
                     *reinterpret_cast<uint2v*>(tp + o) = wp;
                     *reinterpret_cast<uint2v*>(th + o) = wh;
-                    *reinterpret_cast<uint2v*>(tl + o) = wl;
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            // dK += dS^T Q^F (hi and lo), then dV += P^F^T dO, each in 2*NB steps: step j covers queries
+            // dK += dS^T Q^F, then dV += P^F^T dO, each in 2*NB steps: step j covers queries
             // 16*(j/NB) .. +15 (contraction slots 0-3: queries 16*ks + 8*hf + 0..3, slots 4-7: the next
             // four) and columns 32*(j%NB) .. +31.  The operands of step j+1 are read while step j multiplies.
             constexpr int NSTEP = 2 * NB;
@@ -508,24 +617,23 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 return join(lds_read_tr16(t + ta), lds_read_tr16(t + ta + 4 * kTPad));
             };
             {
-                uint4v ah = rd_t(th, 0), al = rd_t(tl, 0), bq[2];
+                uint4v ah = rd_t(th, 0), bq[2];
                 bq[0] = rd_b(0, 0);
 #pragma unroll
                 for (int j = 0; j < NSTEP; ++j) {
                     const int nb = j % NB;
                     if (j + 1 < NSTEP) bq[(j + 1) & 1] = rd_b(j + 1, 0);
-                    uint4v ah_n, al_n;
-                    if (j == NB - 1) { ah_n = rd_t(th, 1); al_n = rd_t(tl, 1); }
-                    dk[nb] = mfma_bf16(ah, bq[j & 1], dk[nb]);
-                    dk[nb] = mfma_bf16(al, bq[j & 1], dk[nb]);
-                    if (j == NB - 1) { ah = ah_n; al = al_n; }
+                    uint4v ah_n;
+                    if (j == NB - 1) ah_n = rd_t(th, 1);
+                    dk[nb] = mfma_f16(ah, bq[j & 1], dk[nb]);
+                    if (j == NB - 1) ah = ah_n;
                 }
-                __builtin_amdgcn_sched_group_barrier(0x100, 4 + 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 + 2, 0);
 #pragma unroll
                 for (int j = 0; j < NSTEP; ++j) {
                     if (j + 1 < NSTEP) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                    if (j == NB - 1) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    if (j == NB - 1) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 }
             }
             // If every block scale of this 32x32 tile rounded to 0 (max P <= 6 * 2^-10: the usual case
@@ -559,7 +667,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             const int key = key0_w + 8 * (i >> 2) + 4 * hf + (i & 3);
             if (key < L) {
                 const size_t o = ((size_t)bhkv * L + key) * D + 32 * nb + ln;
-                dK[o] = f32_to_bf16_rne(dk[nb][i]);
+                dK[o] = f32_to_bf16_rne(dk[nb][i] * (rs / rs_s));            // / ds_scale, exact: a power of two
                 dV[o] = f32_to_bf16_rne(dv[nb][i]);
             }
         }
@@ -567,7 +675,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 
 template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
-                         const float* rowstat,
+                         const float* rowstat, const float* bound_part,
                          int B, int Hq, int Hkv, int L, void* dk, void* dv, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
@@ -578,19 +686,19 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
-                       (const uint16_t*)dob, (const float2*)rowstat, (uint16_t*)dk, (uint16_t*)dv,
-                       L, Lp, Hq, Hq / Hkv, 1.4426950408889634f * rs, rs);
+                       (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv,
+                       L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs, rs);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
-                    const float* rowstat,
+                    const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st);
-    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, B, Hq, Hkv, L, dk, dv, st);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st)
+                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st);
+    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st)
+                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st);
     return -1;
 }
 

@@ -22,14 +22,19 @@ int launch_fwd(const void* qh, const void* kh, const void* vt,
 // D = rowsum(dO o O') (Alg. 3, first line); padding rows hold zeros.  d_o bf16, o_hp fp32, [rows, D].
 int launch_delta(const void* d_o, const float* o_hp, const float* lse, int BHq, int L, int D, float* rowstat, hipStream_t st);
 
-// Alg. 3, query-stationary pass: dQ.
+// Per-head bounds that limit |dS| (partial maxima of |V^F_j|, |dO_i|, |D_i|/sqrt(d)): part holds
+// 3 * BHq * 64 floats.  vb, dob: bf16 row-major copies padded to Lp rows.
+int launch_bounds(const void* vb, const void* dob, const float* rowstat, int BHkv, int BHq, int L, int D,
+                  float* part, hipStream_t st);
+
+// Alg. 3, query-stationary pass: dQ.  qh, kh: fp16 copies; vb, dob: bf16 copies.
 int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
-                  const float* rowstat,
+                  const float* rowstat, const float* bound_part,
                   int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st);
 
 // Alg. 3, key-stationary pass: dK, dV (summed over the query heads of a group).
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
-                    const float* rowstat,
+                    const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st);
 
 }  // namespace aq
