@@ -4,6 +4,7 @@ import pytest
 import torch
 
 import oracle
+import workloads as W
 from tests.gpu_util import f32, host, max_abs, random_inputs, rel_l2, to_dev
 
 pytestmark = pytest.mark.gpu
@@ -62,3 +63,39 @@ def test_backward_with_oracle_forward_state():
     torch.cuda.synchronize()
     for n, t in (("dQ", dq), ("dK", dk), ("dV", dv)):
         assert rel_l2(host(t), rb[n]) <= TOL, n
+
+
+@pytest.mark.parametrize("log2_scale", [-40, 0, 30])
+def test_do_dynamic_range(log2_scale):
+    """dS is rounded to fp16 after a power-of-two scaling taken from a bound of |dS| (per query row
+    for dQ, per kv head for dK): rows of dO that differ by 2^30 in magnitude, all-zero rows, an
+    all-zero head and a very small or very large overall scale must not cost accuracy."""
+    import paper_2603_00040_amd as aq
+    B, Hq, Hkv, L, d, causal = 1, 4, 2, 300, 128, False
+    x = random_inputs(B, Hq, Hkv, L, d, seed=77, k_chan=4)
+    fdo = f32(x["do"])
+    row_exp = ((np.arange(L) * 7) % 31) - 20                       # 2^-20 .. 2^10, exact in bf16
+    fdo = fdo * np.exp2(row_exp + log2_scale)[None, None, :, None]
+    fdo[:, :, ::17] = 0.0                                          # zero rows
+    fdo[:, 3] = 0.0                                                # a zero head
+    do_bits = W.f32_to_bf16_bits(fdo.astype(np.float32))
+    assert np.array_equal(f32(do_bits), fdo.astype(np.float32))    # the scaling stayed exact
+    q, k, v, do = to_dev(x["q"]), to_dev(x["k"]), to_dev(x["v"]), to_dev(do_bits)
+    o, lse, ohp = aq.attnqat_fwd(q, k, v, causal)
+    dq, dk, dv = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
+    torch.cuda.synchronize()
+    fq, fk, fv = f32(x["q"]), f32(x["k"]), f32(x["v"])
+    rf = oracle.fwd(fq, fk, fv, causal, aq.block_k())
+    rb = oracle.bwd(fq, fk, fv, fdo.astype(np.float32), rf["L"], rf["Op"], causal)
+    for n, t in (("dK", dk), ("dV", dv)):
+        e = rel_l2(host(t), rb[n])
+        print(f"scale 2^{log2_scale}: {n} rel-L2 {e:.2e}", flush=True)
+        assert e <= TOL, (n, e)
+    # dQ row by row: every row carries its own scale, so every row must be accurate on its own
+    gq, rq = host(dq), rb["dQ"]
+    num = np.linalg.norm(gq - rq, axis=-1); den = np.linalg.norm(rq, axis=-1)
+    zero = den == 0
+    assert np.all(gq[zero] == 0)
+    worst = float((num[~zero] / den[~zero]).max())
+    print(f"scale 2^{log2_scale}: dQ worst row rel-L2 {worst:.2e} over {int((~zero).sum())} rows", flush=True)
+    assert worst <= 4e-3
