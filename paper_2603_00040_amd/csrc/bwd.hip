@@ -196,7 +196,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     if (CAUSAL) qt = nqt - 1 - qt;
     const int b = bh / Hq, h = bh % Hq;
     const int bhkv = b * (Hq / G) + h / G;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: LDS destinations and branches use it
     const int q_row = qt * 128 + wave * 32 + ln;
 
     uint4v qreg[DS], doreg[DS];
@@ -232,19 +233,20 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;
     const int wave_qmax = qt * 128 + wave * 32 + 31;
 
-    const uint16_t* ksrc[KLD];
-    const uint16_t* vsrc[KLD];
+    // direct-to-LDS tile loads: wave-uniform tile base + this lane's byte offset inside the tile
+    uint32_t kv_ld[KLD];
 #pragma unroll
     for (int i = 0; i < KLD; ++i) {
         const int slot = 64 * (wave * KLD + i) + lane, r = slot / KCH, pc = slot % KCH;
-        const size_t off = ((size_t)bhkv * Lp + r) * D + 8 * swz<KCH>(r, pc);
-        ksrc[i] = Kb + off; vsrc[i] = Vb + off;
+        kv_ld[i] = 2u * (uint32_t)(r * D + 8 * swz<KCH>(r, pc));
     }
-    auto issue_tile = [&](int buf) __attribute__((always_inline)) {
+    const uint16_t* k_head = Kb + (size_t)bhkv * Lp * D;
+    const uint16_t* v_head = Vb + (size_t)bhkv * Lp * D;
+    auto issue_tile = [&](int buf, int jt) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < KLD; ++i) {
-            async_copy16(ksrc[i], &sm.k[buf][512 * (wave * KLD + i)]); ksrc[i] += 64 * D;
-            async_copy16(vsrc[i], &sm.v[buf][512 * (wave * KLD + i)]); vsrc[i] += 64 * D;
+            async_copy16(k_head + (size_t)jt * (64 * D), kv_ld[i], &sm.k[buf][512 * (wave * KLD + i)]);
+            async_copy16(v_head + (size_t)jt * (64 * D), kv_ld[i], &sm.v[buf][512 * (wave * KLD + i)]);
         }
     };
 
@@ -269,7 +271,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
 
-    issue_tile(0);
+    issue_tile(0, 0);
     // Q, dO and the row scalars must have arrived BEFORE the loop: a load still pending at loop entry
     // makes the compiler wait for all vector-memory traffic at the first product of every iteration,
     // i.e. for the tile prefetch it has just issued.
@@ -281,7 +283,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
 
     for (int j = 0; j < nkt; ++j) {
         const int buf = j & 1, k0 = j * 64;
-        if (j + 1 < nkt) issue_tile(buf ^ 1);
+        if (j + 1 < nkt) issue_tile(buf ^ 1, j + 1);
         const bool active = !CAUSAL || k0 <= wave_qmax;
         if (active) {
             const uint16_t* kt_ = &sm.k[buf][0];
@@ -426,7 +428,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const int kt_ = blockIdx.x % nkt;               // key tiles in increasing order: under a causal
     const int Hkv = Hq / G;                         // mask the first tiles see the most queries
     const int b = bhkv / Hkv, hk = bhkv % Hkv;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: LDS destinations and branches use it
     const int key0_w = kt_ * 128 + wave * 32;       // this wave's first key
 
     // K^F, V^F rows of this lane's key: A operands (row = key, d-slots 16*ds + 8*hf)
@@ -469,11 +472,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 
     // direct-to-LDS loads: this wave's chunk slots and their (row, swizzled chunk)
     const bool loader = NWL >= 4 || wave < NWL;
-    int slot_off[PER_WAVE];
+    uint32_t slot_off[PER_WAVE];                     // this lane's byte offset inside a tile's source rows
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
         const int slot = 64 * (wave * PER_WAVE + i) + lane;
-        slot_off[i] = (slot / KCH) * D + 8 * swz<KCH>(slot / KCH, slot % KCH);
+        slot_off[i] = 2u * (uint32_t)((slot / KCH) * D + 8 * swz<KCH>(slot / KCH, slot % KCH));
     }
     // (head, tile) walk without divisions: state of the NEXT tile to load and of the current tile
     int ld_g = 0, ld_t = 0;                          // next tile to issue: head index in group, tile in head
@@ -482,8 +485,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
         if (loader) {
 #pragma unroll
             for (int i = 0; i < PER_WAVE; ++i) {
-                async_copy16(Qb + row0 * D + slot_off[i], &sm.q[buf][512 * (wave * PER_WAVE + i)]);
-                async_copy16(dOb + row0 * D + slot_off[i], &sm.g[buf][512 * (wave * PER_WAVE + i)]);
+                async_copy16(Qb + row0 * D, slot_off[i], &sm.q[buf][512 * (wave * PER_WAVE + i)]);
+                async_copy16(dOb + row0 * D, slot_off[i], &sm.g[buf][512 * (wave * PER_WAVE + i)]);
             }
         }
         if (++ld_t == per_head) { ld_t = 0; ++ld_g; }

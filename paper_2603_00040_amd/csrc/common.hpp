@@ -87,6 +87,11 @@ __device__ inline float xhalf_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// max(a, b) written as median(a, b, +inf): fmaxf() on values the compiler cannot prove quiet (MFMA
+// results) costs a canonicalizing v_max per operand, the median has no such requirement and the
+// compiler folds chains of it into v_max3.  No NaN reaches these reductions.
+__device__ inline float max_nc(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_inff()); }
+
 // ---- phi^-1(phi(.)) of two P values with the hardware FP4 converts ------------
 // v_cvt_scalef32_pk_fp4_f32 rounds to E2M1 with ties-to-even and saturates at 6 (checked
 // against the threshold definition on the device, including +-3 ulp around every tie).
@@ -96,6 +101,20 @@ __device__ inline uint32_t fq_pair_f16(float r0, float r1, uint32_t s_f16x2) {
     const half2v c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 0);
     const half2v s = __builtin_bit_cast(half2v, s_f16x2);
     return __builtin_bit_cast(uint32_t, c * s);
+}
+// Eight values at once: the four converts fill one register of codes byte by byte (one
+// zero-initialisation instead of four).  r[i] = p[i] * (1/s); out[j] = fp16 pair (s*c[2j], s*c[2j+1]).
+__device__ inline void fq_oct_f16(const float (&r)[8], uint32_t s_f16x2, uint32_t (&out)[4]) {
+    uint32_t codes = 0u;
+    codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, r[0], r[1], 1.0f, 0);
+    codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, r[2], r[3], 1.0f, 1);
+    codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, r[4], r[5], 1.0f, 2);
+    codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, r[6], r[7], 1.0f, 3);
+    const half2v s = __builtin_bit_cast(half2v, s_f16x2);
+    out[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 0) * s);
+    out[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 1) * s);
+    out[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 2) * s);
+    out[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 3) * s);
 }
 // The same, returning the two dequantized values as fp32 (for bf16 consumers).
 __device__ inline void fq_pair_f32(float r0, float r1, float s, float& o0, float& o1) {
@@ -138,9 +157,19 @@ __device__ inline uint4v lds_read16(const unsigned char* p) {
     return *(const __attribute__((address_space(3))) uint4v*)p;
 }
 // One wave copies 1 KiB: LDS chunk slot (wave-uniform slot0 + lane) <- its global source.
-__device__ inline void async_copy16(const void* gsrc, void* lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
-                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+// Inline assembly on purpose.  The compiler files global_load_lds under FLAT accesses that may
+// touch both memories, and while one is pending it turns every LDS wait of the wave into "wait
+// for everything": the operand prefetch of the attention loops would drain at each product.
+// Written this way the copy is invisible to the compiler's counters, so callers wait with
+// s_waitcnt vmcnt(0) themselves before the barrier that publishes the tile (vector-memory
+// loads return in order, so the compiler's own waits stay valid, if conservative).
+// gbase: wave-uniform global address; voff: this lane's byte offset from it (< 4 GiB);
+// lds_wave_base: wave-uniform LDS pointer.
+__device__ inline void async_copy16(const void* gbase, uint32_t voff, void* lds_wave_base) {
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(gbase), "s"(lds) : "memory");
 }
 
 }  // namespace aq

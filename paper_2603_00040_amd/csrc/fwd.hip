@@ -47,7 +47,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
     if (CAUSAL) qt = nqt - 1 - qt;                       // longest rows first
     const int b = bh / Hq, h = bh % Hq;
     const int bhkv = b * (Hq / G) + h / G;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: LDS destinations and branches use it
     const int q_row = qt * 128 + wave * 32 + ln;
 
     // Q^F operand: this lane's query row, d-slots 16*ds + 8*hf .. +7
@@ -64,30 +65,30 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
 
     // LDS element offsets of this lane's operand reads (buffer 0, row block 0); the row blocks
     // kb / mb add compile-time constants because a row's swizzle key survives adding 32 rows.
-    int koff[DS], voff[4];
-#pragma unroll
-    for (int ds = 0; ds < DS; ++ds) koff[ds] = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) voff[ks] = (ln * 8 + swz<8>(ln, 2 * ks + hf)) * 8;
+    // Chunk c of row r sits at chunk c ^ key(r), so an operand's byte offset is (per-lane constant) XOR
+    // (compile-time constant): K rows  k_rd ^ (ds << 5),  V^T rows  v_rd ^ (ks << 5).
+    const int k_rd = 2 * swz_elem<KCH>(ln, 8 * hf);
+    const int v_rd = 2 * swz_elem<8>(ln, 8 * hf);
 
-    // per-lane global sources of the direct-to-LDS tile loads (advance by one tile per step)
-    const half_t* ksrc[KLD];
-    const half_t* vsrc[VLD];
+    // direct-to-LDS tile loads: wave-uniform tile base + this lane's byte offset inside the tile
+    uint32_t k_ld[KLD], v_ld[VLD];
 #pragma unroll
     for (int i = 0; i < KLD; ++i) {
         const int slot = 64 * (wave * KLD + i) + lane, r = slot / KCH, pc = slot % KCH;
-        ksrc[i] = Kh + ((size_t)bhkv * Lp + r) * D + 8 * swz<KCH>(r, pc);
+        k_ld[i] = 2u * (uint32_t)(r * D + 8 * swz<KCH>(r, pc));
     }
 #pragma unroll
     for (int i = 0; i < VLD; ++i) {
         const int slot = 64 * (wave * VLD + i) + lane, r = slot / 8, pc = slot % 8;
-        vsrc[i] = Vt + ((size_t)bhkv * D + r) * Lp + 8 * swz<8>(r, pc);
+        v_ld[i] = 2u * ((uint32_t)r * (uint32_t)Lp + 8u * (uint32_t)swz<8>(r, pc));
     }
-    auto issue_tile = [&](int buf) {
+    const half_t* k_head = Kh + (size_t)bhkv * Lp * D;      // [key][d]
+    const half_t* v_head = Vt + (size_t)bhkv * D * Lp;      // [d][key]
+    auto issue_tile = [&](int buf, int jt) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < KLD; ++i) { async_copy16(ksrc[i], &sm.k[buf][512 * (wave * KLD + i)]); ksrc[i] += 64 * D; }
+        for (int i = 0; i < KLD; ++i) async_copy16(k_head + (size_t)jt * (64 * D), k_ld[i], &sm.k[buf][512 * (wave * KLD + i)]);
 #pragma unroll
-        for (int i = 0; i < VLD; ++i) { async_copy16(vsrc[i], &sm.v[buf][512 * (wave * VLD + i)]); vsrc[i] += 64; }
+        for (int i = 0; i < VLD; ++i) async_copy16(v_head + (size_t)jt * 64, v_ld[i], &sm.v[buf][512 * (wave * VLD + i)]);
     };
 
     floatx16 o[MB], op[TRAIN ? MB : 1];
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
     }
     float m = -INFINITY, lsum = 0.0f;     // lsum: this half-wave's part of l (same alpha in both halves)
 
-    issue_tile(0);
+    issue_tile(0, 0);
     // The Q registers must have arrived BEFORE the loop: a load still pending at loop entry makes the
     // compiler wait for all vector-memory traffic at the first product of every iteration, i.e. for
     // the tile prefetch it has just issued.
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
     for (int j = 0; j < nkt; ++j) {
         const int buf = j & 1;
         const int k0 = j * 64;
-        if (j + 1 < nkt) issue_tile(buf ^ 1);                    // lands while this tile is consumed
+        if (j + 1 < nkt) issue_tile(buf ^ 1, j + 1);                    // lands while this tile is consumed
         const bool active = !CAUSAL || k0 <= wave_qmax;          // wave-uniform
 
         if (active) {
@@ -119,12 +120,19 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
             // that consumes them (the scheduling groups below keep the compiler from sinking them).
             floatx16 s[2];
             {
-                const half_t* kt_ = &sm.k[buf][0];
+                // per-lane offset of this tile, opaque to the compiler: it would otherwise hoist every
+                // (offset ^ constant) out of the loop and pay for it with registers
+                int k_it = k_rd + buf * (int)sizeof(sm.k[0]);
+                asm volatile("" : "+v"(k_it));
+                const unsigned char* kbase = reinterpret_cast<const unsigned char*>(&sm.k[0][0]);
+                auto k_opnd = [&](int i) __attribute__((always_inline)) -> half8 {
+                    return __builtin_bit_cast(half8, lds_read16(kbase + (k_it ^ ((i >> 1) << 5)) + (i & 1) * (32 * D * 2)));
+                };
                 constexpr int NS = 2 * DS, RING = 6;
                 half8 ring[RING];
 #pragma unroll
                 for (int i = 0; i < RING; ++i)
-                    ring[i] = *reinterpret_cast<const half8*>(kt_ + koff[i >> 1] + (i & 1) * (32 * D));
+                    ring[i] = k_opnd(i);
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -133,7 +141,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
                 for (int i = 0; i < NS; ++i) {                  // step i: ds = i / 2, kb = i % 2
                     const half8 a = ring[i % RING];
                     if (i + RING < NS)
-                        ring[i % RING] = *reinterpret_cast<const half8*>(kt_ + koff[(i + RING) >> 1] + ((i + RING) & 1) * (32 * D));
+                        ring[i % RING] = k_opnd(i + RING);
                     s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qreg[i >> 1], s[i & 1], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
@@ -156,9 +164,9 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
                     }
             }
             // ---- online softmax (Alg. 2: m_new, alpha, P-tilde, l)
-            float mt = fmaxf(s[0][0], s[1][0]);
+            float mt = max_nc(s[0][0], s[1][0]);
 #pragma unroll
-            for (int i = 1; i < 16; ++i) mt = fmaxf(mt, fmaxf(s[0][i], s[1][i]));
+            for (int i = 1; i < 16; ++i) mt = max_nc(max_nc(mt, s[0][i]), s[1][i]);
             mt = xhalf_max(mt);
             const float mnew = fmaxf(m, mt);
             const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
@@ -183,13 +191,16 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
             }
             // ---- per 16 keys: phi^-1(phi(P-tilde)), then O^T += V^F^T P-tilde^F^T and
             //      O'^T += V^F^T P-tilde^T.  Keys of a group = registers 8g..8g+7 of both halves.
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const int kb = ks >> 1, g = ks & 1;
-                half8 av[MB];                                   // this step's V^F^T operands, in flight during phi
+            int v_it = v_rd + buf * (int)sizeof(sm.v[0]);
+            asm volatile("" : "+v"(v_it));
+            const unsigned char* vbase = reinterpret_cast<const unsigned char*>(&sm.v[0][0]);
+            auto load_v = [&](int ks, half8 (&av)[MB]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
-                    av[mb] = *reinterpret_cast<const half8*>(&sm.v[buf][voff[ks] + mb * (32 * 64)]);
+                    av[mb] = __builtin_bit_cast(half8, lds_read16(vbase + (v_it ^ (ks << 5)) + mb * (32 * 64 * 2)));
+            };
+            auto quantize = [&](int ks, uint4v& bq, uint4v& bu) __attribute__((always_inline)) {
+                const int kb = ks >> 1, g = ks & 1;
                 float amax = s[kb][8 * g];
 #pragma unroll
                 for (int i = 1; i < 8; ++i) amax = fmaxf(amax, s[kb][8 * g + i]);
@@ -197,16 +208,18 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
                 const float sc = rne_e4m3_grid(amax * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
                 const float inv = sc > 0.0f ? __builtin_amdgcn_rcpf(sc) : 0.0f;
                 const uint32_t sc2 = pack_f16x2(sc, sc);
-                uint4v bq, bu;
                 float pfv[DUMP ? 8 : 1];
+                float r[8];
+                uint32_t w[4];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = s[kb][8 * g + i] * inv;
+                fq_oct_f16(r, sc2, w);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float p0 = s[kb][8 * g + 2 * i], p1 = s[kb][8 * g + 2 * i + 1];
-                    const uint32_t w = fq_pair_f16(p0 * inv, p1 * inv, sc2);
-                    bq[i] = w;
-                    if constexpr (TRAIN) bu[i] = pack_f16x2(p0, p1);
+                    bq[i] = w[i];
+                    if constexpr (TRAIN) bu[i] = pack_f16x2(s[kb][8 * g + 2 * i], s[kb][8 * g + 2 * i + 1]);
                     if constexpr (DUMP) {
-                        const half2v pr = __builtin_bit_cast(half2v, w);
+                        const half2v pr = __builtin_bit_cast(half2v, w[i]);
                         pfv[2 * i] = (float)pr[0]; pfv[2 * i + 1] = (float)pr[1];
                     }
                 }
@@ -220,6 +233,13 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
                         }
                     }
                 }
+            };
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                half8 av[MB];                                   // this step's V^F^T operands, in flight during phi
+                uint4v bq, bu;
+                load_v(ks, av);
+                quantize(ks, bq, bu);
                 const half8 bqh = __builtin_bit_cast(half8, bq);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
