@@ -576,32 +576,30 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c, -Ls));    // P = exp(S - L_i)
+            // block scales of phi(P): one per 16 keys = registers 8*gq .. 8*gq+7 of both halves
+            float sc[2], inv[2];
             bool nz = false;
 #pragma unroll
-            for (int gq = 0; gq < 2; ++gq) {                           // phi^-1(phi(P)) per 16 keys
+            for (int gq = 0; gq < 2; ++gq) {
                 float amax = s[8 * gq];
 #pragma unroll
                 for (int i = 1; i < 8; ++i) amax = fmaxf(amax, s[8 * gq + i]);
                 amax = xhalf_max(amax);
-                const float sc = rne_e4m3_grid(amax * (1.0f / 6.0f));
-                const float inv = sc > 0.0f ? __builtin_amdgcn_rcpf(sc) : 0.0f;
-                nz = nz || sc > 0.0f;
+                sc[gq] = rne_e4m3_grid(amax * (1.0f / 6.0f));
+                inv[gq] = sc[gq] > 0.0f ? __builtin_amdgcn_rcpf(sc[gq]) : 0.0f;
+                nz = nz || sc[gq] > 0.0f;
+            }
+            // dS = P (dP - D_i)/sqrt(d) from the fp32 P, scaled, as fp16, staged as [query][key]
 #pragma unroll
-                for (int t4 = 0; t4 < 2; ++t4) {                       // 4 consecutive keys per store
-                    const int r0 = 8 * gq + 4 * t4;
-                    float pf[4], dsv[4];
-                    fq_pair_f32(s[r0] * inv, s[r0 + 1] * inv, sc, pf[0], pf[1]);
-                    fq_pair_f32(s[r0 + 2] * inv, s[r0 + 3] * inv, sc, pf[2], pf[3]);
+            for (int t4 = 0; t4 < 4; ++t4) {                           // 4 consecutive keys per store
+                const int r0 = 4 * t4;
+                float dsv[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) dsv[e] = s[r0 + e] * fmaf(dp[r0 + e], rs_s, -Dq_s);   // dS from the fp32 P, scaled
-                    uint2v wp, wh;
-                    wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
-                    wh[0] = pack_f16x2(dsv[0], dsv[1]); wh[1] = pack_f16x2(dsv[2], dsv[3]);
-                    // registers r0..r0+3 <-> keys 8*(r0>>2) + 4*hf + 0..3 of this wave's 32 keys
-                    const int o = tw_off + 8 * (r0 >> 2);
-                    *reinterpret_cast<uint2v*>(tp + o) = wp;
-                    *reinterpret_cast<uint2v*>(th + o) = wh;
-                }
+                for (int e = 0; e < 4; ++e) dsv[e] = s[r0 + e] * fmaf(dp[r0 + e], rs_s, -Dq_s);
+                uint2v wh;
+                wh[0] = pack_f16x2(dsv[0], dsv[1]); wh[1] = pack_f16x2(dsv[2], dsv[3]);
+                // registers r0..r0+3 <-> keys 8*(r0>>2) + 4*hf + 0..3 of this wave's 32 keys
+                *reinterpret_cast<uint2v*>(th + tw_off + 8 * (r0 >> 2)) = wh;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -640,8 +638,23 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 }
             }
             // If every block scale of this 32x32 tile rounded to 0 (max P <= 6 * 2^-10: the usual case
-            // for long rows), P^F is identically 0 and the dV products add nothing.  Wave-uniform, exact.
+            // for long rows), P^F is identically 0: quantizing it, staging it and the dV products are
+            // skipped.  Wave-uniform, exact.
             if (__builtin_amdgcn_ballot_w64(nz) != 0) {
+                // P^F = phi^-1(phi(P)), staged as [query][key]
+#pragma unroll
+                for (int t4 = 0; t4 < 4; ++t4) {
+                    const int r0 = 4 * t4, gq = t4 >> 1;
+                    float pf[4];
+                    fq_pair_f32(s[r0] * inv[gq], s[r0 + 1] * inv[gq], sc[gq], pf[0], pf[1]);
+                    fq_pair_f32(s[r0 + 2] * inv[gq], s[r0 + 3] * inv[gq], sc[gq], pf[2], pf[3]);
+                    uint2v wp;
+                    wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
+                    *reinterpret_cast<uint2v*>(tp + tw_off + 8 * (r0 >> 2)) = wp;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 uint4v ap = rd_t(tp, 0), bg[2];
                 bg[0] = rd_b(0, kGB);
 #pragma unroll
