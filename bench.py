@@ -7,9 +7,10 @@ the backward (Alg. 3) for a training workload, or quantization + inference forwa
 (Alg. 1) for an inference workload.  Prints ONE JSON line.
 
 FLOP convention (model FLOPs): forward 4*B*Hq*L^2*d, backward 10*B*Hq*L^2*d, halved under
-a causal mask.  The roofline entry prices the dominant kernel by its ALGORITHMIC MFMA
-work (fwd_train 6, fwd_infer 4, bwd_dq 6, bwd_dkdv 8 times B*Hq*L^2*d; the extra low-order
-dS products and nothing else are overhead) against the dense 16-bit MFMA peak.
+a causal mask.  The roofline entry prices the dominant kernel by the MFMA work it EXECUTES
+(fwd_train 6, fwd_infer 4, bwd_dq 6 times B*Hq*L^2*d; bwd_dkdv 6 + 2f, where f is the
+measured fraction of 32x32 tiles whose P^F is non-zero: the dV product of the other tiles is
+skipped, exactly, and is not counted) against the dense 16-bit MFMA peak.
 """
 import argparse
 import json
@@ -21,7 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16 MFMA
-KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}
+KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
 # HBM-side bytes per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
 # measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
 MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 151.0e9, "bwd_dq": 361.1e9, "bwd_dkdv": 210.2e9}}
@@ -107,20 +108,33 @@ def main():
             for name, ms in aq.profile_read():
                 kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
     aq.profile_enable(False)
+    pf_frac = None
+    if train:
+        # how many 32x32 tiles of the dK/dV pass had a non-zero P^F (the others skip the dV products, exactly)
+        counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+        aq.debug_dkdv_tile_counts(counts)
+        bwd(); torch.cuda.synchronize()
+        aq.debug_dkdv_tile_counts(None)
+        visited, nonzero = (int(c) for c in counts.cpu())
+        pf_frac = nonzero / max(visited, 1)
 
     pair_flops = B * Hq * float(L) ** 2 * d * (0.5 if w.causal else 1.0)
     step_flops = w.fwd_flops + (w.bwd_flops if train else 0.0)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
     fwd_ms = kern_ms.get("prep_qkv", 0.0) + kern_ms.get("fwd_train", 0.0) + kern_ms.get("fwd_infer", 0.0)
-    dom = max((n for n in kern_ms if n in KERNEL_GEMMS), key=lambda n: kern_ms[n])
-    achieved = KERNEL_GEMMS[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
+    gemms = dict(KERNEL_GEMMS)
+    if pf_frac is not None:
+        gemms["bwd_dkdv"] = 6.0 + 2.0 * pf_frac
+    dom = max((n for n in kern_ms if n in gemms), key=lambda n: kern_ms[n])
+    achieved = gemms[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
                 "kernel_ms": round(kern_ms[dom], 3),
+                "dkdv_tiles_with_nonzero_pf": None if pf_frac is None else round(pf_frac, 6),
                 "per_kernel": {n: {"ms": round(ms, 3),
-                                   "tflops": round(KERNEL_GEMMS[n] * pair_flops / (ms * 1e-3) / 1e12, 2)
-                                   if n in KERNEL_GEMMS else None} for n, ms in kern_ms.items()}}
+                                   "tflops": round(gemms[n] * pair_flops / (ms * 1e-3) / 1e12, 2)
+                                   if n in gemms else None} for n, ms in kern_ms.items()}}
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -167,8 +181,12 @@ def cpu_baseline(w, x, train, target_s, block_k):
             oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal)
         return rows.size, time.perf_counter() - t0
 
-    n0, t_pilot = run(32)
-    n = int(max(32, min(w.L, n0 * target_s / max(t_pilot, 1e-3))))
+    # two pilots separate the fixed cost (phi of the head's Q/K/V) from the cost per row
+    n1, t1 = run(16)
+    n2, t2 = run(min(w.L, 1024))
+    per = max((t2 - t1) / max(n2 - n1, 1), 1e-5)
+    fixed = max(t1 - per * n1, 0.0)
+    n = int(max(48, min(w.L, (target_s - fixed) / per)))
     n, t = run(n)
     return {"value": round(n * per_row / t / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle",

@@ -135,6 +135,16 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
 int attnqat_profile_enable(int on);
 int attnqat_profile_read(int max_entries, float* ms, const char** names);
 
+/*
+ * Measurement hook for the dK/dV pass of attnqat_bwd.  That pass skips the work on P^F
+ * (quantizing it and dV += P^F^T dO) for every 32-query x 32-key tile whose P^F is all zero,
+ * which is exact; how often that happens depends on the data.  While `counts` (device,
+ * 2 x uint64, zeroed by the caller) is non-NULL, every later attnqat_bwd adds to counts[0]
+ * the number of tiles the pass visited and to counts[1] the number with a non-zero P^F.
+ * Pass NULL to switch it off (the default).  Not thread safe.
+ */
+int attnqat_debug_dkdv_tile_counts(unsigned long long* counts);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ _SIGNATURES = {
     "attnqat_strerror": (ctypes.c_char_p, [_i]),
     "attnqat_debug_fwd_p": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
                                  _vp, _sz, _vp]),
+    "attnqat_debug_dkdv_tile_counts": (_i, [_vp]),
     "attnqat_profile_enable": (_i, [_i]),
     "attnqat_profile_read": (_i, [_i, _vp, _vp]),
 }
@@ -169,6 +170,11 @@ def attnqat_debug_fwd_p(q, k, v, causal: bool, row0: int):
     _check(lib().attnqat_debug_fwd_p(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                      _ptr(o), _ptr(lse), row0, _ptr(p), _ptr(ws), nb, _stream()))
     return o, lse, p
+
+
+def debug_dkdv_tile_counts(counts):
+    """counts: zeroed int64 CUDA tensor of 2 elements (tiles visited, tiles with non-zero P^F) or None."""
+    _check(lib().attnqat_debug_dkdv_tile_counts(_ptr(counts) if counts is not None else None))
 
 
 def profile_enable(on: bool):

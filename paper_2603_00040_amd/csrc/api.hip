@@ -148,6 +148,14 @@ int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
     return ATTNQAT_OK;
 }
 
+static unsigned long long* g_dkdv_counts = nullptr;
+
+int attnqat_debug_dkdv_tile_counts(unsigned long long* counts)
+{
+    g_dkdv_counts = counts;
+    return ATTNQAT_OK;
+}
+
 int attnqat_profile_enable(int on)
 {
     g_prof.on = on != 0;
@@ -223,7 +231,7 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
     if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dq, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
-    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv, st))
+    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv, g_dkdv_counts, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;

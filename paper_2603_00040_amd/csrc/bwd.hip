@@ -410,11 +410,11 @@ struct DkvSmem {
     uint16_t t[4][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
 };
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
-    uint16_t* __restrict__ dK, uint16_t* __restrict__ dV,
+    uint16_t* __restrict__ dK, uint16_t* __restrict__ dV, unsigned long long* __restrict__ tile_counts,
     int L, int Lp, int Hq, int G, int NHq, float c, float rs)
 {
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
@@ -520,6 +520,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     __syncthreads();
 
     int cur_g = 0, cur_t = 0;
+    unsigned n_tiles = 0, n_pf_tiles = 0;            // measurement only (wave-uniform)
     for (int it = 0; it < niter; ++it) {
         const int buf = it & 1;
         const int q0 = (qt_first + cur_t) * 32;
@@ -640,7 +641,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             // If every block scale of this 32x32 tile rounded to 0 (max P <= 6 * 2^-10: the usual case
             // for long rows), P^F is identically 0: quantizing it, staging it and the dV products are
             // skipped.  Wave-uniform, exact.
+            if constexpr (COUNT) ++n_tiles;
             if (__builtin_amdgcn_ballot_w64(nz) != 0) {
+                if constexpr (COUNT) ++n_pf_tiles;
                 // P^F = phi^-1(phi(P)), staged as [query][key]
 #pragma unroll
                 for (int t4 = 0; t4 < 4; ++t4) {
@@ -675,6 +678,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
         asm volatile("" : "+v"(st_n.x), "+v"(st_n.y));     // the next tile's row scalars are consumed here, not earlier
     }
 
+    if (COUNT && lane == 0) {
+        atomicAdd(&tile_counts[0], (unsigned long long)n_tiles);
+        atomicAdd(&tile_counts[1], (unsigned long long)n_pf_tiles);
+    }
+
     // accumulators: row = key 8*(i>>2) + 4*hf + (i&3) of the wave, column d = 32*nb + ln
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -692,29 +700,30 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
-                         int B, int Hq, int Hkv, int L, void* dk, void* dv, hipStream_t st)
+                         int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DkvSmem<D>);
-    auto kern = bwd_dkdv_kernel<D, CAUSAL>;
+    auto kern = tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true> : bwd_dkdv_kernel<D, CAUSAL, false>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
         return -1;
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
-                       (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv,
+                       (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv, tile_counts,
                        L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs, rs);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
-                    int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st)
+                    int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
+                    unsigned long long* tile_counts, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st);
-    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st)
-                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, st);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st)
+                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st);
+    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st)
+                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st);
     return -1;
 }
 

@@ -35,6 +35,7 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 // Alg. 3, key-stationary pass: dK, dV (summed over the query heads of a group).
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
-                    int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv, hipStream_t st);
+                    int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
+                    unsigned long long* tile_counts /* may be null */, hipStream_t st);
 
 }  // namespace aq
