@@ -99,3 +99,34 @@ def test_do_dynamic_range(log2_scale):
     worst = float((num[~zero] / den[~zero]).max())
     print(f"scale 2^{log2_scale}: dQ worst row rel-L2 {worst:.2e} over {int((~zero).sum())} rows", flush=True)
     assert worst <= 4e-3
+
+
+def test_dkdv_tile_count_hook():
+    """The measurement variant of the dK/dV pass counts the tiles it visits and those with a non-zero
+    P^F, and returns the same bits as the production variant."""
+    import paper_2603_00040_amd as aq
+    B, Hq, Hkv, L, d = 1, 2, 2, 256, 64
+    x = random_inputs(B, Hq, Hkv, L, d, seed=5)
+    q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
+    o, lse, ohp = aq.attnqat_fwd(q, k, v, False)
+    ref = aq.attnqat_bwd(q, k, v, do, lse, ohp, False)
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    aq.debug_dkdv_tile_counts(counts)
+    try:
+        got = aq.attnqat_bwd(q, k, v, do, lse, ohp, False)
+        torch.cuda.synchronize()
+    finally:
+        aq.debug_dkdv_tile_counts(None)
+    visited, nonzero = (int(c) for c in counts.cpu())
+    assert visited == B * Hq * (L // 32) ** 2
+    # P^F of a 32x32 tile is non-zero iff some P of it exceeds 6 * 2^-10 ... checked against the oracle's P
+    rf = oracle.fwd(f32(x["q"]), f32(x["k"]), f32(x["v"]), False, aq.block_k())
+    qf, kf = oracle.fake_quant(f32(x["q"])), oracle.fake_quant(f32(x["k"]))
+    s = np.einsum("bhid,bhjd->bhij", qf.astype(np.float64), kf.astype(np.float64)) / np.sqrt(d)
+    p = np.exp(s - rf["L"][..., None])
+    blk = p.reshape(B, Hq, L // 32, 32, L // 16, 16).max(-1)          # per query row and 16-key block
+    # scale of a block = RNE_E4M3(max/6) > 0 iff max/6 > 2^-10 (half the smallest subnormal 2^-9, ties to even -> 0)
+    tile_nz = (blk > 6.0 * 2.0 ** -10).reshape(B, Hq, L // 32, 32, L // 32, 2).any(axis=(3, 5))
+    assert nonzero == int(tile_nz.sum())
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
