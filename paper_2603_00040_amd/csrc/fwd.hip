@@ -164,22 +164,27 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
                     }
             }
             // ---- online softmax (Alg. 2: m_new, alpha, P-tilde, l)
-            float mt = max_nc(s[0][0], s[1][0]);
+            // (four interleaved chains each: a single chain of 32 dependent max / add instructions would
+            // run at the instruction latency, not at the issue rate)
+            float mp[4];
 #pragma unroll
-            for (int i = 1; i < 16; ++i) mt = max_nc(max_nc(mt, s[0][i]), s[1][i]);
-            mt = xhalf_max(mt);
+            for (int j = 0; j < 4; ++j) mp[j] = max_nc(s[0][j], s[1][j]);
+#pragma unroll
+            for (int i = 4; i < 16; ++i) mp[i & 3] = max_nc(max_nc(mp[i & 3], s[0][i]), s[1][i]);
+            const float mt = xhalf_max(max_nc(max_nc(mp[0], mp[1]), max_nc(mp[2], mp[3])));
             const float mnew = fmaxf(m, mt);
             const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
             const float ms = mnew * c;
             m = mnew;
-            float rs = 0.0f;
+            float rp[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, -ms));
-                    rs += s[kb][i];
+                    rp[i & 3] += s[kb][i];
                 }
+            const float rs = (rp[0] + rp[1]) + (rp[2] + rp[3]);
             lsum = lsum * alpha + rs;                           // un-quantized P-tilde
             // ---- rescale: exact no-op unless some row of this wave moved its maximum (rare
             // after the first tiles), so it lives on the cold path
@@ -189,6 +194,24 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
 #pragma unroll
                     for (int i = 0; i < 16; ++i) { o[mb][i] *= alpha; if constexpr (TRAIN) op[mb][i] *= alpha; }
             }
+            // ---- block scales of phi(P-tilde) for the four 16-key groups of the tile, as four independent
+            // chains (max tree, exchange between the halves, E4M3 rounding, reciprocal): computed one after
+            // the other they would sit on the critical path of every step below.
+            float bsc[4], binv[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const floatx16& sv = s[ks >> 1];
+                const int b0 = 8 * (ks & 1);
+                const float a0 = fmaxf(fmaxf(sv[b0], sv[b0 + 1]), sv[b0 + 2]);
+                const float a1 = fmaxf(fmaxf(sv[b0 + 3], sv[b0 + 4]), sv[b0 + 5]);
+                bsc[ks] = fmaxf(fmaxf(a0, a1), fmaxf(sv[b0 + 6], sv[b0 + 7]));
+            }
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bsc[ks] = xhalf_max(bsc[ks]);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bsc[ks] = rne_e4m3_grid(bsc[ks] * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) binv[ks] = bsc[ks] > 0.0f ? __builtin_amdgcn_rcpf(bsc[ks]) : 0.0f;
             // ---- per 16 keys: phi^-1(phi(P-tilde)), then O^T += V^F^T P-tilde^F^T and
             //      O'^T += V^F^T P-tilde^T.  Keys of a group = registers 8g..8g+7 of both halves.
             int v_it = v_rd + buf * (int)sizeof(sm.v[0]);
@@ -201,12 +224,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
             };
             auto quantize = [&](int ks, uint4v& bq, uint4v& bu) __attribute__((always_inline)) {
                 const int kb = ks >> 1, g = ks & 1;
-                float amax = s[kb][8 * g];
-#pragma unroll
-                for (int i = 1; i < 8; ++i) amax = fmaxf(amax, s[kb][8 * g + i]);
-                amax = xhalf_max(amax);
-                const float sc = rne_e4m3_grid(amax * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
-                const float inv = sc > 0.0f ? __builtin_amdgcn_rcpf(sc) : 0.0f;
+                const float sc = bsc[ks], inv = binv[ks];
                 const uint32_t sc2 = pack_f16x2(sc, sc);
                 float pfv[DUMP ? 8 : 1];
                 float r[8];
@@ -234,19 +252,77 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(
                     }
                 }
             };
+            if constexpr (DUMP) {
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                half8 av[MB];                                   // this step's V^F^T operands, in flight during phi
-                uint4v bq, bu;
-                load_v(ks, av);
-                quantize(ks, bq, bu);
-                const half8 bqh = __builtin_bit_cast(half8, bq);
+                for (int ks = 0; ks < 4; ++ks) {
+                    half8 av[MB];
+                    uint4v bq, bu;
+                    load_v(ks, av);
+                    quantize(ks, bq, bu);
+                    const half8 bqh = __builtin_bit_cast(half8, bq);
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], bqh, o[mb], 0, 0, 0);
-                    if constexpr (TRAIN)
-                        op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], __builtin_bit_cast(half8, bu), op[mb], 0, 0, 0);
+                    for (int mb = 0; mb < MB; ++mb) {
+                        o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], bqh, o[mb], 0, 0, 0);
+                        if constexpr (TRAIN)
+                            op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], __builtin_bit_cast(half8, bu), op[mb], 0, 0, 0);
+                    }
                 }
+            } else {
+                // A wave issues in order: a block of MFMAs followed by a block of vector instructions leaves
+                // the vector ALU idle while the MFMAs queue up and the matrix pipe idle afterwards.  So the
+                // quantization of step ks+1 is cut into four parts of a few instructions that follow the
+                // products of step ks (scheduling fences keep the compiler from regrouping them); a V^T
+                // operand register is reloaded for step ks+1 as soon as its last product of step ks has issued.
+                struct QState { uint32_t c01, c23; };
+                auto q_part = [&](int ks, int c, QState& st, uint4v& bq, uint4v& bu) __attribute__((always_inline)) {
+                    const int b0 = 8 * (ks & 1);
+                    const floatx16& sv = s[ks >> 1];
+                    const float inv = binv[ks];
+                    if (c == 0) {
+                        st.c01 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, sv[b0] * inv, sv[b0 + 1] * inv, 1.0f, 0);
+                        st.c23 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, sv[b0 + 4] * inv, sv[b0 + 5] * inv, 1.0f, 0);
+                    } else if (c == 1) {
+                        st.c01 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(st.c01, sv[b0 + 2] * inv, sv[b0 + 3] * inv, 1.0f, 1);
+                        st.c23 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(st.c23, sv[b0 + 6] * inv, sv[b0 + 7] * inv, 1.0f, 1);
+                    } else if (c == 2) {
+                        const half2v sc2 = __builtin_bit_cast(half2v, pack_f16x2(bsc[ks], bsc[ks]));
+                        bq[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(st.c01, 1.0f, 0) * sc2);
+                        bq[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(st.c01, 1.0f, 1) * sc2);
+                        bq[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(st.c23, 1.0f, 0) * sc2);
+                        bq[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(st.c23, 1.0f, 1) * sc2);
+                    } else if constexpr (TRAIN) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) bu[i] = pack_f16x2(sv[b0 + 2 * i], sv[b0 + 2 * i + 1]);
+                    }
+                };
+                half8 av[MB];
+                uint4v bq[2], bu[2];
+                QState st;
+                load_v(0, av);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) q_part(0, c, st, bq[0], bu[0]);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const int cur = ks & 1, nxt = cur ^ 1;
+                    const half8 bqh = __builtin_bit_cast(half8, bq[cur]);
+                    const half8 buh = __builtin_bit_cast(half8, bu[cur]);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        // the four parts of step ks+1 are spread over the MB operands of step ks
+                        __builtin_amdgcn_sched_barrier(0);
+                        o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], bqh, o[mb], 0, 0, 0);
+                        if constexpr (TRAIN) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], buh, op[mb], 0, 0, 0);
+                        }
+                        if (ks < 3) {
+#pragma unroll
+                            for (int c = (4 * mb) / MB; c < (4 * (mb + 1)) / MB; ++c) q_part(ks + 1, c, st, bq[nxt], bu[nxt]);
+                        }
+                        if (ks < 3) av[mb] = __builtin_bit_cast(half8, lds_read16(vbase + (v_it ^ ((ks + 1) << 5)) + mb * (32 * 64 * 2)));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         __builtin_amdgcn_s_waitcnt(0);        // this wave's part of the next tile is in LDS
