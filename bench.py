@@ -23,9 +23,9 @@ sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16 MFMA
 KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
-# HBM-side bytes per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
+# Bytes beyond L2 per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
 # measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
-MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 151.0e9, "bwd_dq": 361.1e9, "bwd_dkdv": 210.2e9}}
+MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 35.5e9, "bwd_dq": 205.2e9, "bwd_dkdv": 737.4e9}}
 
 
 def main():
