@@ -1,9 +1,10 @@
 // Fused forward of Attn-QAT on gfx950: Alg. 1 (inference) and Alg. 2 (training).
 //
-// Work split: a workgroup of 4 waves owns 128 query rows of one head; each wave owns 32
+// Work split: a workgroup of 8 waves owns 256 query rows of one head; each wave owns 32
 // of them.  Key tiles of B_k = 64 keys are visited in increasing order; K and V^T tiles
 // are copied global->LDS directly (global_load_lds, double buffered, XOR-swizzled rows)
-// and shared by the four waves.
+// and shared by the eight waves.  Waves 0-3 and waves 4-7 run half an iteration apart
+// (vector phase / matrix phase, separated by barriers).
 //
 // MFMA shapes (v_mfma_f32_32x32x16_f16, fp32 accumulate).  All operands are the
 // dequantized NVFP4 values s*c, which fp16 represents exactly, so the products are those
@@ -155,9 +156,12 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     if (late) __builtin_amdgcn_s_barrier();              // one phase behind from here on
 
     // Two phases per key tile, separated by barriers; waves 0-3 are in the vector phase while waves
-    // 4-7 are in the matrix phase and vice versa, so every SIMD always holds one wave of each kind:
+    // 4-7 are in the matrix phase and vice versa, so every SIMD holds one wave of each kind:
     //   vector phase j:  mask, online softmax, block scales of phi(P-tilde)         (no MFMA, no LDS)
     //   matrix phase j:  O, O' += V^F^T P(j) with the FP4 round trip of P-tilde in between;  S(j+1)
+    // (The MFMAs of one wave do not overlap with the vector instructions of ANOTHER wave on this
+    // hardware, only with its own; what this arrangement buys, measured, is that the matrix stream
+    // runs at raised priority against a pure vector stream and that a tile copy serves 256 rows.)
     // Tile traffic: K(j+2) and V(j+1) are requested at the start of matrix phase j into the buffers
     // whose last readers (matrix phase j-1 of either group) are two barriers back.
     // ---- vector phase of one key tile: mask, online softmax, block scales of phi(P-tilde)  (no MFMA, no LDS)
