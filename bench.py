@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--workload", default="dit720p_train",
                     help="one of: tiny_ref dit480p_infer llm4k_gqa dit720p_train llm32k_gqa")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
+    ap.add_argument("--ablation", type=int, default=0,
+                    help="backward ablation bit set of Sec. 4.2 (1: D from the bf16 O, 2: dV from the un-quantized P); "
+                         "0 = the method itself")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -78,7 +81,10 @@ def main():
             aq.attnqat_fwd_infer(q, k, v, w.causal, workspace=ws, out=(o, lse))
 
     def bwd():
-        aq.attnqat_bwd(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
+        if args.ablation:
+            aq.attnqat_bwd_ablation(q, k, v, do, lse, ohp, o, w.causal, args.ablation, workspace=ws, out=(dq, dk, dv))
+        else:
+            aq.attnqat_bwd(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
 
     def step():
         fwd()
@@ -109,7 +115,9 @@ def main():
                 kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
     aq.profile_enable(False)
     pf_frac = None
-    if train:
+    if train and args.ablation & 2:
+        pf_frac = 1.0                    # the un-quantized P is never skipped
+    elif train:
         # how many 32x32 tiles of the dK/dV pass had a non-zero P^F (the others skip the dV products, exactly)
         counts = torch.zeros(2, dtype=torch.int64, device="cuda")
         aq.debug_dkdv_tile_counts(counts)
@@ -147,7 +155,7 @@ def main():
         "vs_baseline": None, "dtype": "f16/bf16 MFMA operands (exact NVFP4 values), fp32 accumulate and softmax",
         "data": "synthetic",
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
-                   "passes": w.passes, "block_k": aq.block_k(), "seed": w.seed},
+                   "passes": w.passes, "block_k": aq.block_k(), "seed": w.seed, "bwd_ablation": args.ablation},
         "fwd_tflops": round(w.fwd_flops / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
         "fwd_ms": round(fwd_ms, 3),
         "frac_of_mfma_peak_model_flops": round(value / MFMA_PEAK_TFLOPS, 4),

@@ -102,6 +102,25 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
                 void* dq, void* dk, void* dv,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The two backward ablations of Sec. 4.2 (Table 2, Exp. 7 and Exp. 8; the failure modes that
+ * Sec. 3.3 explains), as switches of the same backward.  `ablation` is a bit set:
+ *   ATTNQAT_ABL_D_FROM_O       D = rowsum(dO o O) with the forward's low-precision output `o`
+ *                              ([B,Hq,L,d] bf16, device, read) instead of O'; o_hp is ignored.
+ *   ATTNQAT_ABL_P_UNQUANTIZED  dV += P^T dO with the recomputed fp32 P instead of
+ *                              phi^-1(phi(P)) (P enters the product as a bf16 hi + lo pair).
+ * 0 computes exactly what attnqat_bwd computes.  Other arguments, workspace, errors: as attnqat_bwd
+ * (workspace size ATTNQAT_WS_BWD); `o` may be NULL unless ATTNQAT_ABL_D_FROM_O is set, o_hp may be
+ * NULL if it is.
+ */
+#define ATTNQAT_ABL_D_FROM_O        1
+#define ATTNQAT_ABL_P_UNQUANTIZED   2
+int attnqat_bwd_ablation(const void* q, const void* k, const void* v, const void* d_o,
+                         const float* lse, const float* o_hp, const void* o,
+                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int ablation,
+                         void* dq, void* dk, void* dv,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace the call named by `which` (ATTNQAT_WS_*) needs; 0 for bad arguments. */
 size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d);
 

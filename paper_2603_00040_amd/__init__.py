@@ -26,6 +26,8 @@ _SIGNATURES = {
     "attnqat_fwd_infer": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                          _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_bwd_ablation": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
+                                  _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "attnqat_block_k": (_i, []),
     "attnqat_strerror": (ctypes.c_char_p, [_i]),
@@ -156,6 +158,35 @@ def attnqat_bwd(q, k, v, d_o, lse, o_hp, causal: bool, workspace=None, out=None)
     _check(lib().attnqat_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(o_hp),
                              B, Hq, Hkv, L, d, int(causal), BF16,
                              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), nb, _stream()))
+    return dq, dk, dv
+
+
+ABL_D_FROM_O, ABL_P_UNQUANTIZED = 1, 2
+
+
+def attnqat_bwd_ablation(q, k, v, d_o, lse, o_hp, o, causal: bool, ablation: int, workspace=None, out=None):
+    """Alg. 3 with the ablations of Sec. 4.2 switched on by the bit set ``ablation``
+    (ABL_D_FROM_O: D from the bf16 output ``o``; ABL_P_UNQUANTIZED: dV from the fp32 P).
+    Returns (dq, dk, dv) bf16."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (d_o, "d_o")):
+        _dev_bf16(t, n)
+    if ablation & ABL_D_FROM_O:
+        _dev_bf16(o, "o")
+    elif not (o_hp.dtype == torch.float32 and o_hp.is_contiguous()):
+        raise AttnQatError("o_hp must be a contiguous fp32 tensor")
+    if not (lse.dtype == torch.float32 and lse.is_contiguous()):
+        raise AttnQatError("lse must be a contiguous fp32 tensor")
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    else:
+        dq, dk, dv = out
+    ws, nb = _workspace(WS_BWD, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_bwd_ablation(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse),
+                                      _ptr(o_hp) if o_hp is not None else None, _ptr(o) if o is not None else None,
+                                      B, Hq, Hkv, L, d, int(causal), BF16, int(ablation),
+                                      _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), nb, _stream()))
     return dq, dk, dv
 
 

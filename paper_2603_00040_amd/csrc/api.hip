@@ -206,13 +206,13 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                       workspace, workspace_bytes, stream);
 }
 
-int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
-                const float* lse, const float* o_hp,
-                int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
-                void* dq, void* dk, void* dv,
-                void* workspace, size_t workspace_bytes, void* stream)
+static int bwd_common(const void* q, const void* k, const void* v, const void* d_o,
+                      const float* lse, const void* o_acc, bool o_is_bf16, bool p_quant,
+                      int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                      void* dq, void* dk, void* dv,
+                      void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!q || !k || !v || !d_o || !lse || !o_hp || !dq || !dk || !dv) return ATTNQAT_EINVAL;
+    if (!q || !k || !v || !d_o || !lse || !o_acc || !dq || !dk || !dv) return ATTNQAT_EINVAL;
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
     BwdWs w = carve_bwd(workspace, B, Hq, Hkv, L, d);
@@ -225,16 +225,39 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
     if (launch_prep(v, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
-    if (launch_delta(d_o, o_hp, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
+    if (launch_delta(d_o, o_acc, o_is_bf16, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
     if (launch_bounds(w.vb, w.dob, w.rowstat, B * Hkv, B * Hq, L, d, w.bounds, st)) return ATTNQAT_ELAUNCH;
     prof_mark("delta", st);
     if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dq, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
-    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv, g_dkdv_counts, st))
+    if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv,
+                        g_dkdv_counts, p_quant, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;
+}
+
+int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
+                const float* lse, const float* o_hp,
+                int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                void* dq, void* dk, void* dv,
+                void* workspace, size_t workspace_bytes, void* stream)
+{
+    return bwd_common(q, k, v, d_o, lse, o_hp, false, true, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
+                      workspace, workspace_bytes, stream);
+}
+
+int attnqat_bwd_ablation(const void* q, const void* k, const void* v, const void* d_o,
+                         const float* lse, const float* o_hp, const void* o,
+                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int ablation,
+                         void* dq, void* dk, void* dv,
+                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (ablation & ~(ATTNQAT_ABL_D_FROM_O | ATTNQAT_ABL_P_UNQUANTIZED)) return ATTNQAT_EINVAL;
+    const bool low = (ablation & ATTNQAT_ABL_D_FROM_O) != 0;
+    return bwd_common(q, k, v, d_o, lse, low ? o : (const void*)o_hp, low, !(ablation & ATTNQAT_ABL_P_UNQUANTIZED),
+                      B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -63,8 +63,8 @@ __device__ inline uint4v join(uint2v a, uint2v b) { uint4v r; r[0] = a[0]; r[1] 
 // ------------------------------------------------------------------ per-row statistics
 // rowstat[bh*Lp + l] = { L_l * log2(e), D_l / sqrt(d) } with D = rowsum(dO o O'); rows l >= L
 // (padding) hold {0, 0}.  Both attention passes read them as they are.
-template <int D>
-__global__ __launch_bounds__(256) void delta_kernel(const uint16_t* __restrict__ dO, const float* __restrict__ Ohp,
+template <int D, bool LOWP /* ablation: O' is given as bf16 */>
+__global__ __launch_bounds__(256) void delta_kernel(const uint16_t* __restrict__ dO, const void* __restrict__ Ohp_,
                                                     const float* __restrict__ lse,
                                                     int L, int Lp, long nrows_p, float rs, float2* __restrict__ rowstat)
 {
@@ -77,8 +77,16 @@ __global__ __launch_bounds__(256) void delta_kernel(const uint16_t* __restrict__
     if (l < L) {
         const size_t off = ((size_t)bh * L + l) * D + 8 * c;
         const uint4v g = *reinterpret_cast<const uint4v*>(dO + off);
-        const floatx4 o0 = *reinterpret_cast<const floatx4*>(Ohp + off);
-        const floatx4 o1 = *reinterpret_cast<const floatx4*>(Ohp + off + 4);
+        floatx4 o0, o1;
+        if constexpr (LOWP) {
+            const uint4v w = *reinterpret_cast<const uint4v*>(static_cast<const uint16_t*>(Ohp_) + off);
+            o0[0] = bf16_lo_f32(w[0]); o0[1] = bf16_hi_f32(w[0]); o0[2] = bf16_lo_f32(w[1]); o0[3] = bf16_hi_f32(w[1]);
+            o1[0] = bf16_lo_f32(w[2]); o1[1] = bf16_hi_f32(w[2]); o1[2] = bf16_lo_f32(w[3]); o1[3] = bf16_hi_f32(w[3]);
+        } else {
+            const float* Ohp = static_cast<const float*>(Ohp_);
+            o0 = *reinterpret_cast<const floatx4*>(Ohp + off);
+            o1 = *reinterpret_cast<const floatx4*>(Ohp + off + 4);
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             acc += bf16_lo_f32(g[i]) * o0[2 * i] + bf16_hi_f32(g[i]) * o0[2 * i + 1];
@@ -90,15 +98,19 @@ __global__ __launch_bounds__(256) void delta_kernel(const uint16_t* __restrict__
     if (c == 0) rowstat[r] = make_float2(l < L ? lse[(size_t)bh * L + l] * 1.4426950408889634f : 0.0f, acc * rs);
 }
 
-int launch_delta(const void* d_o, const float* o_hp, const float* lse, int BHq, int L, int D, float* rowstat, hipStream_t st)
+int launch_delta(const void* d_o, const void* o_acc, bool o_is_bf16, const float* lse, int BHq, int L, int D,
+                 float* rowstat, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const long nrows_p = (long)BHq * Lp;
     const int rpb = 256 / (D / 8);
     const unsigned grid = (unsigned)((nrows_p + rpb - 1) / rpb);
     const float rs = 1.0f / sqrtf((float)D);
-    if (D == 128) hipLaunchKernelGGL(delta_kernel<128>, dim3(grid), dim3(256), 0, st, (const uint16_t*)d_o, o_hp, lse, L, Lp, nrows_p, rs, (float2*)rowstat);
-    else          hipLaunchKernelGGL(delta_kernel<64>, dim3(grid), dim3(256), 0, st, (const uint16_t*)d_o, o_hp, lse, L, Lp, nrows_p, rs, (float2*)rowstat);
+    auto go = [&](auto kern) {
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st, (const uint16_t*)d_o, o_acc, lse, L, Lp, nrows_p, rs, (float2*)rowstat);
+    };
+    if (D == 128) { if (o_is_bf16) go(delta_kernel<128, true>); else go(delta_kernel<128, false>); }
+    else          { if (o_is_bf16) go(delta_kernel<64, true>);  else go(delta_kernel<64, false>); }
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -410,7 +422,7 @@ struct DkvSmem {
     uint16_t t[4][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
 };
 
-template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */>
+template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */, bool PQUANT /* false: ablation, dV from the fp32 P */>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
@@ -642,32 +654,46 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             // for long rows), P^F is identically 0: quantizing it, staging it and the dV products are
             // skipped.  Wave-uniform, exact.
             if constexpr (COUNT) ++n_tiles;
-            if (__builtin_amdgcn_ballot_w64(nz) != 0) {
+            if (!PQUANT || __builtin_amdgcn_ballot_w64(nz) != 0) {
                 if constexpr (COUNT) ++n_pf_tiles;
-                // P^F = phi^-1(phi(P)), staged as [query][key]
+                // P^F = phi^-1(phi(P)), staged as [query][key].  Ablation (Sec. 4.2, "no fake quantization of P in
+                // the backward"): the fp32 P itself, in two passes as a bf16 hi + lo pair.
 #pragma unroll
-                for (int t4 = 0; t4 < 4; ++t4) {
-                    const int r0 = 4 * t4, gq = t4 >> 1;
-                    float pf[4];
-                    fq_pair_f32(s[r0] * inv[gq], s[r0 + 1] * inv[gq], sc[gq], pf[0], pf[1]);
-                    fq_pair_f32(s[r0 + 2] * inv[gq], s[r0 + 3] * inv[gq], sc[gq], pf[2], pf[3]);
-                    uint2v wp;
-                    wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
-                    *reinterpret_cast<uint2v*>(tp + tw_off + 8 * (r0 >> 2)) = wp;
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                uint4v ap = rd_t(tp, 0), bg[2];
-                bg[0] = rd_b(0, kGB);
+                for (int pass = 0; pass < (PQUANT ? 1 : 2); ++pass) {
 #pragma unroll
-                for (int j = 0; j < NSTEP; ++j) {
-                    const int nb = j % NB;
-                    if (j + 1 < NSTEP) bg[(j + 1) & 1] = rd_b(j + 1, kGB);
-                    uint4v ap_n;
-                    if (j == NB - 1) ap_n = rd_t(tp, 1);
-                    dv[nb] = mfma_bf16(ap, bg[j & 1], dv[nb]);
-                    if (j == NB - 1) ap = ap_n;
+                    for (int t4 = 0; t4 < 4; ++t4) {
+                        const int r0 = 4 * t4, gq = t4 >> 1;
+                        float pf[4];
+                        if constexpr (PQUANT) {
+                            fq_pair_f32(s[r0] * inv[gq], s[r0 + 1] * inv[gq], sc[gq], pf[0], pf[1]);
+                            fq_pair_f32(s[r0 + 2] * inv[gq], s[r0 + 3] * inv[gq], sc[gq], pf[2], pf[3]);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float hi = __uint_as_float((uint32_t)f32_to_bf16_rne(s[r0 + e]) << 16);
+                                pf[e] = pass == 0 ? hi : s[r0 + e] - hi;
+                            }
+                        }
+                        uint2v wp;
+                        wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
+                        *reinterpret_cast<uint2v*>(tp + tw_off + 8 * (r0 >> 2)) = wp;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    uint4v ap = rd_t(tp, 0), bg[2];
+                    bg[0] = rd_b(0, kGB);
+#pragma unroll
+                    for (int j = 0; j < NSTEP; ++j) {
+                        const int nb = j % NB;
+                        if (j + 1 < NSTEP) bg[(j + 1) & 1] = rd_b(j + 1, kGB);
+                        uint4v ap_n;
+                        if (j == NB - 1) ap_n = rd_t(tp, 1);
+                        dv[nb] = mfma_bf16(ap, bg[j & 1], dv[nb]);
+                        if (j == NB - 1) ap = ap_n;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
                 }
             }
             __builtin_amdgcn_wave_barrier();
@@ -700,11 +726,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
-                         int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts, hipStream_t st)
+                         int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts,
+                         bool p_quant, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DkvSmem<D>);
-    auto kern = tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true> : bwd_dkdv_kernel<D, CAUSAL, false>;
+    auto kern = !p_quant ? bwd_dkdv_kernel<D, CAUSAL, false, false>
+              : tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true, true> : bwd_dkdv_kernel<D, CAUSAL, false, true>;
+    if (!p_quant) tile_counts = nullptr;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
         return -1;
     const float rs = 1.0f / sqrtf((float)D);
@@ -718,12 +747,12 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
-                    unsigned long long* tile_counts, hipStream_t st)
+                    unsigned long long* tile_counts, bool p_quant, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st)
-                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st);
-    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st)
-                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, st);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st)
+                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st);
+    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st)
+                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st);
     return -1;
 }
 

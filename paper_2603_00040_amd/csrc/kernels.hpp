@@ -20,7 +20,9 @@ int launch_fwd(const void* qh, const void* kh, const void* vt,
 
 // Per-row statistics of the backward: rowstat [BHq, Lp, 2] = {L log2(e), D / sqrt(d)} with
 // D = rowsum(dO o O') (Alg. 3, first line); padding rows hold zeros.  d_o bf16, o_hp fp32, [rows, D].
-int launch_delta(const void* d_o, const float* o_hp, const float* lse, int BHq, int L, int D, float* rowstat, hipStream_t st);
+// o_acc: O' fp32, or (ablation) the bf16 O when o_is_bf16.
+int launch_delta(const void* d_o, const void* o_acc, bool o_is_bf16, const float* lse, int BHq, int L, int D,
+                 float* rowstat, hipStream_t st);
 
 // Per-head bounds that limit |dS| (partial maxima of |V^F_j|, |dO_i|, |D_i|/sqrt(d)): part holds
 // 3 * BHq * 64 floats.  vb, dob: bf16 row-major copies padded to Lp rows.
@@ -36,6 +38,6 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
-                    unsigned long long* tile_counts /* may be null */, hipStream_t st);
+                    unsigned long long* tile_counts /* may be null */, bool p_quant /* false: ablation */, hipStream_t st);
 
 }  // namespace aq

@@ -50,5 +50,5 @@ def test_forward_kernels_do_not_spill():
 def test_backward_kernels_do_not_spill():
     k = _resources("bwd.hip")
     _check(k, r"bwd_dq_kernelILi(64|128)ELb[01]E", 4)
-    # bwd_dkdv_kernel<D, CAUSAL, COUNT>: the measurement variant (COUNT = true) is exempt
-    _check(k, r"bwd_dkdv_kernelILi(64|128)ELb[01]ELb0E", 4)
+    # bwd_dkdv_kernel<D, CAUSAL, COUNT, PQUANT>: the measurement (COUNT) and ablation (!PQUANT) variants are exempt
+    _check(k, r"bwd_dkdv_kernelILi(64|128)ELb[01]ELb0ELb1E", 4)
