@@ -54,6 +54,13 @@ def _load():
     L.oracle_fwd_rows.restype = _i
     L.oracle_fwd_rows.argtypes = [_vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i, _i,
                                   _l, _vp, _vp, _vp, _vp, _vp]
+    L.oracle_e8m0_from_amax.restype = _i
+    L.oracle_e8m0_from_amax.argtypes = [_d]
+    L.oracle_phi_mx.restype = _i
+    L.oracle_phi_mx.argtypes = [_vp, _l, _l, _vp, _vp, _vp]
+    L.oracle_fwd_rows_mx.restype = _i
+    L.oracle_fwd_rows_mx.argtypes = [_vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
+                                     _l, _vp, _vp, _vp, _vp, _vp]
     L.oracle_bwd.restype = _i
     L.oracle_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
                              _vp, _vp, _vp]
@@ -127,6 +134,60 @@ def phi(x, scale_mode: int = 0):
 def fake_quant(x, scale_mode: int = 0):
     """phi^-1(phi(x)) along the last axis."""
     return phi(x, scale_mode)[2]
+
+
+# ---------------------------------------------------------------- MX format
+
+def e8m0_from_amax(amax: float) -> int:
+    """E8M0 byte of the smallest power of two s >= 2^-126 with 6 s >= amax."""
+    return _load().oracle_e8m0_from_amax(float(amax))
+
+
+def phi_mx(x):
+    """MX phi and phi^-1 along the last axis in blocks of 32 (a short last block is zero padded).
+
+    Returns (packed codes uint8 [..., nb*16], E8M0 scale bytes uint8 [..., nb],
+    dequantized float32 [..., n]) with nb = ceil(n/32)."""
+    x = _f32(x)
+    n = x.shape[-1]
+    nb = (n + 31) // 32
+    rows = x.size // n
+    packed = np.empty(x.shape[:-1] + (nb * 16,), np.uint8)
+    scales = np.empty(x.shape[:-1] + (nb,), np.uint8)
+    xf = np.empty_like(x)
+    rc = _load().oracle_phi_mx(_p(x), rows, n, _p(packed), _p(scales), _p(xf))
+    if rc:
+        raise ValueError(f"oracle_phi_mx failed ({rc})")
+    return packed, scales, xf
+
+
+def fake_quant_mx(x, axis: int = -1):
+    """MX phi^-1(phi(x)) with the blocks of 32 running along `axis`."""
+    xt = np.ascontiguousarray(np.moveaxis(_f32(x), axis, -1))
+    return np.ascontiguousarray(np.moveaxis(phi_mx(xt)[2], -1, axis))
+
+
+def fwd_mx(q, k, v, causal: bool, Bk: int, quant_p: bool = True, rows=None, dump_p: bool = False):
+    """Alg. 1 in the MX format: Q^F, K^F blocked along d, V^F and P-tilde^F along the keys.
+    Same arguments and outputs as fwd() (Op is the un-quantized-P output of Alg. 2)."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    qf, kf, vf = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx(v, axis=-2)
+    if rows is None:
+        n, shp, rp = B * Hq * L, (B, Hq, L), None
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        n, shp, rp = rows.size, (rows.size,), rows
+    O = np.empty(shp + (d,)); Op = np.empty(shp + (d,)); Lse = np.empty(shp)
+    P = np.empty((n, L), np.float32) if dump_p else None
+    rc = _load().oracle_fwd_rows_mx(_p(qf), _p(kf), _p(vf), B, Hq, Hkv, L, d, int(causal), Bk,
+                                    int(quant_p), n, _p(rp), _p(O), _p(Op), _p(Lse), _p(P))
+    if rc:
+        raise ValueError(f"oracle_fwd_rows_mx failed ({rc})")
+    out = {"O": O, "Op": Op, "L": Lse}
+    if dump_p:
+        out["P"] = P
+    return out
 
 
 # ---------------------------------------------------------------- attention

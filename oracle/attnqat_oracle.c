@@ -29,6 +29,15 @@
  *   - key tiles of Bk keys are visited in increasing order; the running max
  *     used for quantizing P-tilde is the max over all tiles seen so far.
  *
+ * MX variant (the OCP microscaling format named in Sec. 3.1 next to NVFP4: E2M1
+ * elements, 32 per block, power-of-two E8M0 scale), same algorithms with
+ *   - the block scale is the smallest power of two s with 6 s >= max|X| (the
+ *     E8M0 counterpart of Eq. 1's s = max|X|/6: no element saturates), not below
+ *     2^-126; a block of zeros gets 2^-126,
+ *   - Q and K in blocks of 32 along d, P-tilde and V in blocks of 32 along the
+ *     keys (aligned to absolute key indices that are multiples of 32), so that
+ *     both products contract over the blocked axis.
+ *
  * Parity status: every exported function below is pinned by the CPU tests
  * (format tables, closed forms, library attention with phi off, an independent
  * row-wise transcription with phi on, autograd of the unrolled STE graph).
@@ -129,6 +138,56 @@ int oracle_phi(const float* x, long nrows, int d, int scale_mode,
     return 0;
 }
 
+/* ---------------------------------------------------------------- MX format */
+
+/* E8M0 byte (value 2^(byte-127)) of the smallest power of two s >= 2^-126 with 6 s >= amax.
+ * 6 * 2^e is exact in fp64, so the comparison is that of the real numbers. */
+int oracle_e8m0_from_amax(double amax)
+{
+    int e = -126;
+    while (e < 127 && ldexp(6.0, e) < amax) ++e;
+    return e + 127;
+}
+
+/* phi then phi^-1 on one MX block of n <= 32 values. */
+static void phi_mx_block(const double* x, int n, uint8_t* code, uint8_t* scale_byte, double* xf)
+{
+    double amax = 0.0;
+    for (int i = 0; i < n; ++i) { double a = fabs(x[i]); if (a > amax) amax = a; }
+    int sb = oracle_e8m0_from_amax(amax);
+    double s = ldexp(1.0, sb - 127);
+    for (int i = 0; i < n; ++i) {
+        int sign = signbit(x[i]) ? 8 : 0;
+        int mag = oracle_e2m1_round(fabs(x[i]), s);
+        if (code) code[i] = (uint8_t)(sign | mag);
+        if (xf) xf[i] = (sign ? -1.0 : 1.0) * s * E2M1[mag];
+    }
+    if (scale_byte) *scale_byte = (uint8_t)sb;
+}
+
+/* MX phi over the last axis of x[nrows, n] in blocks of 32 (the last block may be short and is
+ * padded with zeros).  With nb = ceil(n/32): packed[nrows, nb*16] (element 2k in bits 3:0),
+ * scales[nrows, nb] E8M0 bytes, xf[nrows, n].  Any output may be NULL. */
+int oracle_phi_mx(const float* x, long nrows, long n, uint8_t* packed, uint8_t* scales, float* xf)
+{
+    if (!x || n < 1) return -1;
+    const long nb = (n + 31) / 32;
+    #pragma omp parallel for schedule(static)
+    for (long r = 0; r < nrows; ++r) {
+        for (long b = 0; b < nb; ++b) {
+            double xb[32], xfb[32]; uint8_t code[32], sb;
+            const int m = (int)((n - b * 32 < 32) ? n - b * 32 : 32);
+            for (int i = 0; i < 32; ++i) { xb[i] = i < m ? (double)x[r * n + b * 32 + i] : 0.0; }
+            phi_mx_block(xb, 32, code, &sb, xfb);
+            if (packed) for (int i = 0; i < 32; i += 2)
+                packed[(r * nb + b) * 16 + i / 2] = (uint8_t)(code[i] | (code[i + 1] << 4));
+            if (scales) scales[r * nb + b] = sb;
+            if (xf) for (int i = 0; i < m; ++i) xf[r * n + b * 32 + i] = (float)xfb[i];
+        }
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------ forward */
 
 static double dot(const float* a, const float* b, int d)
@@ -147,13 +206,14 @@ static double dot(const float* a, const float* b, int d)
  * Pdump[nrows, L] (optional) receives the dequantized P-tilde^F of each key as it
  * entered the O update (0 for masked keys).
  */
-int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
+static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                     int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
-                    int quant_p, int scale_mode,
+                    int quant_p, int scale_mode, int mx,
                     long nrows, const long* rows,
                     double* O, double* Op, double* Lse, float* Pdump)
 {
-    if (!qf || !kf || !vf || Hq % Hkv || Bk < 16 || Bk % 16 || d < 1) return -1;
+    const int pb = mx ? 32 : 16;               /* keys per P block */
+    if (!qf || !kf || !vf || Hq % Hkv || Bk < pb || Bk % pb || d < 1) return -1;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     if (!rows) nrows = (long)B * Hq * L;
@@ -196,8 +256,10 @@ int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
                 }
                 for (int k = nk; k < Bk; ++k) Pt[k] = 0.0;      /* masked keys */
                 if (quant_p) {
-                    for (int k = 0; k < nk; k += 16)
-                        phi_block(Pt + k, 16, scale_mode, NULL, NULL, NULL, Pf + k);
+                    for (int k = 0; k < nk; k += pb) {
+                        if (mx) phi_mx_block(Pt + k, pb, NULL, NULL, Pf + k);
+                        else    phi_block(Pt + k, pb, scale_mode, NULL, NULL, NULL, Pf + k);
+                    }
                 } else {
                     for (int k = 0; k < nk; ++k) Pf[k] = Pt[k];
                 }
@@ -223,6 +285,27 @@ int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
         free(S); free(Pt); free(Pf); free(o); free(op);
     }
     return err ? -2 : 0;
+}
+
+int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
+                    int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
+                    int quant_p, int scale_mode,
+                    long nrows, const long* rows,
+                    double* O, double* Op, double* Lse, float* Pdump)
+{
+    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode, 0,
+                         nrows, rows, O, Op, Lse, Pdump);
+}
+
+/* The same recurrence with P-tilde quantized in MX blocks of 32 keys (qf, kf, vf: the MX
+ * fake-quantized tensors, V blocked along the keys). */
+int oracle_fwd_rows_mx(const float* qf, const float* kf, const float* vf,
+                       int B, int Hq, int Hkv, long L, int d, int causal, int Bk, int quant_p,
+                       long nrows, const long* rows,
+                       double* O, double* Op, double* Lse, float* Pdump)
+{
+    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, 0, 1,
+                         nrows, rows, O, Op, Lse, Pdump);
 }
 
 /* ----------------------------------------------------------------- backward */

@@ -7,6 +7,9 @@ Two implementations of phi (Eq. 1, Eq. 2 with an E4M3 block scale):
   * ``fake_quant_np``: vectorised numpy; the E4M3 grid comes from torch's own
     float8_e4m3fn decoder (a library table), decisions by ``searchsorted``.
 and a row-at-a-time numpy transcription of the training forward (Alg. 2).
+
+For the MX variant (E2M1, blocks of 32, power-of-two scale): ``phi_mx_block_exact`` on
+rationals and ``fake_quant_mx_np``, whose scale exponent comes from ``numpy.frexp``.
 """
 from fractions import Fraction
 
@@ -94,9 +97,65 @@ def fake_quant_np(x, axis=-1):
     return np.moveaxis(out, -1, axis)
 
 
-def attn_fwd_rowwise_np(qf, kf, vf, causal, Bk, quant_p=True):
+def phi_mx_block_exact(xs):
+    """xs: list of python floats (<=32).  Returns (codes, scale exponent, dequantized Fractions).
+    The scale is the smallest power of two s >= 2^-126 with 6 s >= max|x|, found on rationals
+    from the bit lengths of numerator and denominator."""
+    fx = [Fraction(float(x)) for x in xs]
+    amax = max(abs(f) for f in fx) if fx else Fraction(0)
+    if amax == 0:
+        e = -126
+    else:
+        t = amax / 6                                   # want the smallest e with 2^e >= t
+        e = t.numerator.bit_length() - t.denominator.bit_length()      # 2^(e-1) < t < 2^(e+1)
+        if Fraction(2) ** (e - 1) >= t:
+            e -= 1
+        elif Fraction(2) ** e < t:
+            e += 1
+        e = max(e, -126)
+    s = Fraction(2) ** e
+    codes, deq = [], []
+    for x, f in zip(xs, fx):
+        sign = 8 if np.signbit(np.float64(x)) else 0
+        mag = nearest_even_index(abs(f) / s, E2M1)
+        codes.append(sign | mag)
+        deq.append((-1 if sign else 1) * s * E2M1[mag])
+    return codes, e, deq
+
+
+def fake_quant_mx_np(x, axis=-1):
+    """MX phi^-1(phi(x)) in float64 along ``axis`` in aligned blocks of 32 (zero padded).
+    With amax = m 2^x, m in [0.5, 1) (frexp): 6 * 2^e >= amax first holds at e = x - 3 for
+    m <= 0.75 and at e = x - 2 above."""
+    x = np.moveaxis(np.asarray(x, dtype=np.float64), axis, -1)
+    n = x.shape[-1]
+    pad = (-n) % 32
+    xp = np.concatenate([x, np.zeros(x.shape[:-1] + (pad,))], axis=-1) if pad else x
+    blk = xp.reshape(xp.shape[:-1] + (-1, 32))
+    amax = np.abs(blk).max(axis=-1)
+    m, ex = np.frexp(amax)
+    e = np.where(amax > 0, ex - 3 + (m > 0.75), -126)
+    e = np.maximum(e, -126)
+    s = np.ldexp(1.0, e)[..., None]
+    vals = np.array([0, .5, 1, 1.5, 2, 3, 4, 6.0])
+    r = np.abs(blk) / s                                    # exact: division by a power of two
+    lo = np.floor(r * 2) / 2                               # E2M1 grid is a subset of the half-integers
+    idx = np.searchsorted(vals, np.minimum(r, 6.0), side="right") - 1      # largest grid value <= r
+    up = np.minimum(idx + 1, 7)
+    dlo, dup = r - vals[idx], vals[up] - r
+    pick_up = (dup < dlo) | ((dup == dlo) & (up % 2 == 0) & (up != idx))
+    mag = np.where(pick_up, up, idx)
+    del lo
+    out = np.sign(blk) * s * vals[mag]
+    out = out.reshape(xp.shape)[..., :n]
+    return np.moveaxis(out, -1, axis)
+
+
+def attn_fwd_rowwise_np(qf, kf, vf, causal, Bk, quant_p=True, fq=None):
     """Alg. 2, one query row at a time, numpy float64; inputs already fake-quantized.
-    qf [L,d], kf/vf [L,d] (one head).  Returns O, O', Lse."""
+    qf [L,d], kf/vf [L,d] (one head).  fq: the fake-quantizer of P-tilde (default: NVFP4).
+    Returns O, O', Lse."""
+    fq = fq or fake_quant_np
     L, d = qf.shape
     O = np.zeros((L, d)); Op = np.zeros((L, d)); Lse = np.zeros(L)
     for i in range(L):
@@ -109,7 +168,7 @@ def attn_fwd_rowwise_np(qf, kf, vf, causal, Bk, quant_p=True):
             mnew = max(m, s.max())
             alpha = 0.0 if m == -np.inf else np.exp(m - mnew)
             pt = np.exp(s - mnew).astype(np.float32).astype(np.float64)
-            pf = fake_quant_np(pt) if quant_p else pt      # blocks start at k0 (multiple of 16)
+            pf = fq(pt) if quant_p else pt                 # blocks start at k0 (a multiple of the block)
             l = alpha * l + pt.sum()
             o = alpha * o + pf @ vf[k0:k1]
             op = alpha * op + pt @ vf[k0:k1]

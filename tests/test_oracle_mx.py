@@ -1,0 +1,195 @@
+"""Pins of the oracle's MX variant (E2M1 elements, blocks of 32, power-of-two E8M0 scale).
+
+The format is the OCP microscaling FP4 named in Sec. 3.1 beside NVFP4; the scale rule is
+the power-of-two counterpart of Eq. 1: the smallest 2^e with 6 * 2^e >= max|X|.  Pinned by
+closed forms, an exact-rational twin, a numpy twin whose exponent comes from frexp, exact
+invariants of a power-of-two scale, and for the forward the same pins as the NVFP4 path
+(textbook attention with phi(P) off, an independent row-wise transcription with it on).
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from tests import indep
+
+
+def _bf16(x):
+    u = np.asarray(x, np.float32).view(np.uint32)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.view(np.float32)
+
+
+def _rand(B, Hq, Hkv, L, d, seed, outlier=False):
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((B, Hq, L, d)); k = rng.standard_normal((B, Hkv, L, d)); v = rng.standard_normal((B, Hkv, L, d))
+    if outlier:
+        k[..., 3] *= 6.0; q[..., 3] *= 2.0
+    return _bf16(q), _bf16(k), _bf16(v)
+
+
+def test_e8m0_hand_cases():
+    # 6 * 2^e >= amax first holds at: amax = 6 -> e = 0; just above 6 -> 1; 3 -> -1; just above 3 -> 0;
+    # 1 -> -2 (6/4 = 1.5 >= 1 > 0.75); 0.75 -> -3; 0 -> the floor -126
+    cases = [(6.0, 0), (np.nextafter(6.0, 7.0), 1), (3.0, -1), (np.nextafter(3.0, 4.0), 0), (1.0, -2), (0.75, -3),
+             (0.0, -126), (448.0, 7), (2.0 ** -140, -126), (6 * 2.0 ** 100, 100), (3.3e38, 126)]
+    for amax, e in cases:
+        assert oracle.e8m0_from_amax(amax) == e + 127, (amax, e)
+
+
+def test_e8m0_matches_log2_closed_form_on_every_bf16_amax():
+    # every positive finite bf16 value as a block maximum; ceil(log2(amax/6)) evaluated without rounding
+    # issues through frexp: amax = m 2^x, m in [0.5, 1): e = x - 3 if m <= 0.75 else x - 2
+    u = (np.arange(0x0080, 0x7F80, dtype=np.uint32) << 16).view(np.float32).astype(np.float64)
+    m, x = np.frexp(u)
+    want = np.maximum(x - 3 + (m > 0.75), -126) + 127
+    got = np.array([oracle.e8m0_from_amax(a) for a in u])
+    assert np.array_equal(got, want)
+    s = np.ldexp(1.0, got - 127)
+    big = got > 1
+    assert (6 * s >= u).all() and (6 * (s[big] / 2) < u[big]).all()       # smallest such power of two
+
+
+def test_phi_mx_matches_exact_rational_twin():
+    rng = np.random.default_rng(5)
+    for t in range(300):
+        scale = 2.0 ** rng.integers(-20, 20)
+        blk = _bf16(rng.standard_normal(32) * scale * (10.0 if t % 7 == 0 else 1.0))
+        if t % 5 == 0:
+            blk[rng.integers(0, 32, 8)] = 0.0
+        packed, sb, xf = oracle.phi_mx(blk[None, :])
+        codes, e, deq = indep.phi_mx_block_exact([float(v) for v in blk])
+        got = [(int(packed[0, i // 2]) >> (4 * (i % 2))) & 15 for i in range(32)]
+        assert sb[0, 0] == e + 127
+        # -0.0 and +0.0 of a zero magnitude are the same number
+        assert all(g == c or ((g & 7) == 0 and (c & 7) == 0) for g, c in zip(got, codes))
+        assert np.array_equal(xf[0].astype(np.float64), np.array([float(v) for v in deq]))
+
+
+def test_phi_mx_numpy_twin_on_gaussian_rows_and_both_axes():
+    rng = np.random.default_rng(6)
+    x = _bf16(rng.standard_normal((3, 70, 96)) * np.exp(rng.standard_normal((3, 70, 1))))
+    assert np.array_equal(oracle.fake_quant_mx(x).astype(np.float64), indep.fake_quant_mx_np(x))
+    # blocks along the second-to-last axis (how V is blocked), with a short last block (70 = 2*32 + 6)
+    assert np.array_equal(oracle.fake_quant_mx(x, axis=-2).astype(np.float64), indep.fake_quant_mx_np(x, axis=-2))
+    # and the two axes differ
+    assert not np.array_equal(oracle.fake_quant_mx(x), oracle.fake_quant_mx(x, axis=-2))
+
+
+def test_phi_mx_invariants():
+    rng = np.random.default_rng(7)
+    x = _bf16(rng.standard_normal((64, 128)))
+    packed, sb, xf = oracle.phi_mx(x)
+    s = np.ldexp(1.0, sb.astype(np.int64) - 127)
+    blk = x.reshape(64, 4, 32).astype(np.float64); q = xf.reshape(64, 4, 32).astype(np.float64)
+    # no element saturates, so the error is at most half the largest grid gap (2 s) ...
+    assert (np.abs(blk - q) <= s[..., None]).all()
+    # ... the maximum lands on 4 or 6 times the scale (amax / s in (3, 6]: at least 3, and 3 < amax/s rounds to >= 3)
+    top = np.abs(q).max(-1) / s
+    assert np.isin(top, [3.0, 4.0, 6.0]).all() and (top >= 3).all()
+    # exact homogeneity under powers of two: same codes, shifted scale byte
+    for kexp in (-9, 5):
+        p2, sb2, xf2 = oracle.phi_mx(x * 2.0 ** kexp)
+        assert np.array_equal(p2, packed) and np.array_equal(sb2.astype(int), sb.astype(int) + kexp)
+        assert np.array_equal(xf2, xf * np.float32(2.0 ** kexp))
+    # idempotent: quantized values are representable with the same or a finer scale
+    assert np.array_equal(oracle.phi_mx(xf)[2], xf)
+    # sign symmetry
+    assert np.array_equal(oracle.phi_mx(-x)[2], -xf)
+
+
+def test_phi_mx_round_trip_of_every_code_and_packing():
+    vals = np.array([0, .5, 1, 1.5, 2, 3, 4, 6.0])
+    codes = np.arange(32) % 16
+    blk = np.where(codes & 8, -1.0, 1.0) * vals[codes & 7]
+    for e in (-30, 0, 17):
+        packed, sb, xf = oracle.phi_mx((blk * 2.0 ** e)[None, :].astype(np.float32))
+        assert sb[0, 0] == 127 + e
+        got = np.array([(int(packed[0, i // 2]) >> (4 * (i % 2))) & 15 for i in range(32)])
+        assert np.array_equal(got & 7, codes & 7)
+        nz = (codes & 7) != 0
+        assert np.array_equal(got[nz], codes[nz])
+        assert np.array_equal(xf[0], (blk * 2.0 ** e).astype(np.float32))
+    # a block of zeros: the floor scale, all codes zero
+    packed, sb, xf = oracle.phi_mx(np.zeros((1, 32), np.float32))
+    assert sb[0, 0] == 1 and not packed.any() and not xf.any()
+
+
+def test_e2m1_ties_go_to_even_under_a_power_of_two_scale():
+    # midpoints of the grid times the scale; a 6 in the block pins the scale at 2^e
+    mids = [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0]
+    even = [0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0]
+    for e in (-3, 0, 4):
+        blk = np.zeros(32, np.float32); blk[0] = 6.0 * 2.0 ** e
+        blk[1:8] = np.array(mids) * 2.0 ** e
+        xf = oracle.phi_mx(blk[None, :])[2][0]
+        assert np.array_equal(xf[1:8], np.array(even, np.float32) * np.float32(2.0 ** e))
+
+
+def _textbook(q, k, v, causal):
+    d = q.shape[-1]
+    s = q @ np.swapaxes(k, -1, -2) / math.sqrt(d)
+    if causal:
+        L = s.shape[-1]
+        s = np.where(np.tril(np.ones((L, L), bool)), s, -np.inf)
+    m = s.max(-1, keepdims=True)
+    p = np.exp(s - m)
+    return p @ v / p.sum(-1, keepdims=True), (m + np.log(p.sum(-1, keepdims=True)))[..., 0]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Bk", [32, 64])
+def test_mx_forward_with_phi_p_off_is_textbook_attention_of_the_mx_inputs(causal, Bk):
+    q, k, v = _rand(1, 2, 2, 150, 64, seed=21)
+    r = oracle.fwd_mx(q, k, v, causal, Bk, quant_p=False)
+    qf = indep.fake_quant_mx_np(q); kf = indep.fake_quant_mx_np(k); vf = indep.fake_quant_mx_np(v, axis=-2)
+    O, L = _textbook(qf, kf, vf, causal)
+    assert np.allclose(r["O"], O, rtol=0, atol=1e-6)          # fp32 rounding of P-tilde
+    assert np.allclose(r["L"], L, rtol=0, atol=1e-6)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Bk", [32, 64])
+def test_mx_forward_matches_independent_rowwise_transcription(causal, Bk):
+    q, k, v = _rand(1, 2, 1, 200, 32, seed=22, outlier=True)
+    r = oracle.fwd_mx(q, k, v, causal, Bk)
+    qf = indep.fake_quant_mx_np(q); kf = indep.fake_quant_mx_np(k); vf = indep.fake_quant_mx_np(v, axis=-2)
+    for h in range(2):
+        O, Op, L = indep.attn_fwd_rowwise_np(qf[0, h], kf[0, 0], vf[0, 0], causal, Bk, fq=indep.fake_quant_mx_np)
+        assert np.allclose(r["O"][0, h], O, rtol=0, atol=1e-12)
+        assert np.allclose(r["Op"][0, h], Op, rtol=0, atol=1e-12)
+        assert np.allclose(r["L"][0, h], L, rtol=0, atol=1e-12)
+
+
+def test_mx_single_tile_closed_form_and_row_subset():
+    q, k, v = _rand(1, 2, 2, 48, 32, seed=23)
+    r = oracle.fwd_mx(q, k, v, False, 64)
+    qf = indep.fake_quant_mx_np(q); kf = indep.fake_quant_mx_np(k); vf = indep.fake_quant_mx_np(v, axis=-2)
+    for h in range(2):
+        s = qf[0, h] @ kf[0, h].T / np.sqrt(32)
+        pt = np.exp(s - s.max(-1, keepdims=True)).astype(np.float32).astype(np.float64)
+        o = indep.fake_quant_mx_np(pt) @ vf[0, h] / pt.sum(-1, keepdims=True)
+        assert np.allclose(r["O"][0, h], o, rtol=0, atol=1e-12)
+    rows = oracle.flat_rows(1, 2, 48, [(0, 1, 47), (0, 0, 3)])
+    sub = oracle.fwd_mx(q, k, v, False, 64, rows=rows, dump_p=True)
+    assert np.array_equal(sub["O"][0], r["O"][0, 1, 47]) and np.array_equal(sub["O"][1], r["O"][0, 0, 3])
+    # every dumped P-tilde^F value is (an E2M1 value) * 2^e with one e per block of 32 keys
+    p = sub["P"][0].astype(np.float64)
+    vals = np.array([0, .5, 1, 1.5, 2, 3, 4, 6.0])
+    for b0 in (0, 32):
+        blk = p[b0:b0 + 32]
+        ok = False
+        for e in range(-40, 4):
+            if np.isin(blk / 2.0 ** e, vals).all():
+                ok = True
+        assert ok
+
+
+def test_mx_and_nvfp4_forward_differ_at_quantization_noise_level():
+    q, k, v = _rand(1, 1, 1, 256, 64, seed=24)
+    a = oracle.fwd(q, k, v, False, 64)["O"]; b = oracle.fwd_mx(q, k, v, False, 64)["O"]
+    ref, _ = _textbook(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), False)
+    ea = np.linalg.norm(a - ref) / np.linalg.norm(ref); eb = np.linalg.norm(b - ref) / np.linalg.norm(ref)
+    assert 1e-2 < ea < 0.5 and 1e-2 < eb < 0.5
+    assert eb > 0.8 * ea        # coarser blocks and power-of-two scales do not beat NVFP4 by a margin
