@@ -50,6 +50,7 @@ extern "C" {
 #define ATTNQAT_WS_FWD              0   /* attnqat_fwd                                 */
 #define ATTNQAT_WS_FWD_INFER        1   /* attnqat_fwd_infer                           */
 #define ATTNQAT_WS_BWD              2   /* attnqat_bwd                                 */
+#define ATTNQAT_WS_FWD_INFER_MX     3   /* attnqat_fwd_infer_mx                        */
 
 /*
  * phi of Eq. 1 (Sec. 3.1) along d: for every 16 consecutive elements
@@ -140,6 +141,35 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                         void* o, float* lse, int row0, float* p_dump,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * MX variant of phi: the OCP microscaling FP4 format that Sec. 3.1 names beside NVFP4
+ * (E2M1 elements, 32 per block, one power-of-two E8M0 scale), with the power-of-two
+ * counterpart of Eq. 1 as the scale rule:
+ *   scale = the smallest 2^e, e >= -126, with 6 * 2^e >= max|x|   (byte e + 127; no element saturates)
+ *   code  = sign | RNE_E2M1(|x| / scale)
+ * axis 0: blocks of 32 along d (how Q and K are blocked)
+ *   codes [B,H,L,d/2] bytes (element 2k in bits 3:0), scales [B,H,L,d/32] E8M0 bytes
+ * axis 1: blocks of 32 along the sequence, aligned to multiples of 32 and zero padded (how V is
+ *   blocked, so that P.V contracts over the blocked axis); with Lc = L rounded up to 32
+ *   codes [B,H,d,Lc/2] bytes (position 2k in bits 3:0), scales [B,H,d,Lc/32] E8M0 bytes
+ * x [B,H,L,d] bf16 (device, read); xf optional [B,H,L,d] bf16: phi^-1(phi(x)); any output may be
+ * NULL, not all three.
+ */
+int attnqat_quantize_mx(const void* x, int B, int H, int L, int d, int dtype, int axis,
+                        uint8_t* codes, uint8_t* scales, void* xf, void* stream);
+
+/*
+ * Inference forward, Alg. 1, in the MX format: Q^F, K^F blocked along d, V^F and P-tilde^F along
+ * the keys (P blocks of 32 keys aligned to multiples of 32; key tiles of attnqat_block_k() keys
+ * as in attnqat_fwd_infer).  Both products run on the scaled FP4 matrix instruction of gfx950 on
+ * the codes and scale bytes themselves (Eq. 3: FP4MM), nothing is dequantized.
+ * Arguments as attnqat_fwd_infer; workspace size: ATTNQAT_WS_FWD_INFER_MX.
+ */
+int attnqat_fwd_infer_mx(const void* q, const void* k, const void* v,
+                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                         void* o, float* lse,
+                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement hook (the kernels of Alg. 1-3 are enqueued back to back by one call, so a

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libattnqat.so")
 
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4, -5
 BF16 = 0
-WS_FWD, WS_FWD_INFER, WS_BWD = 0, 1, 2
+WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX = 0, 1, 2, 3
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _SIGNATURES = {
@@ -28,6 +28,8 @@ _SIGNATURES = {
                          _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_ablation": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
                                   _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_quantize_mx": (_i, [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "attnqat_fwd_infer_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "attnqat_block_k": (_i, []),
     "attnqat_strerror": (ctypes.c_char_p, [_i]),
@@ -138,6 +140,41 @@ def attnqat_fwd_infer(q, k, v, causal: bool, workspace=None, out=None):
     ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, workspace)
     _check(lib().attnqat_fwd_infer(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                    _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
+    return o, lse
+
+
+def attnqat_quantize_mx(x, axis: int = 0, want_codes=True, want_xf=True):
+    """MX phi (E2M1, blocks of 32, E8M0 scale) along d (axis 0) or along the sequence (axis 1).
+    Returns (codes u8, scales u8, xf bf16): axis 0 [B,H,L,d/2], [B,H,L,d/32]; axis 1 [B,H,d,Lc/2],
+    [B,H,d,Lc/32] with Lc = L rounded up to 32."""
+    _dev_bf16(x, "x")
+    B, H, L, d = x.shape
+    if axis == 0:
+        cshape, sshape = (B, H, L, d // 2), (B, H, L, d // 32)
+    else:
+        Lc = (L + 31) // 32 * 32
+        cshape, sshape = (B, H, d, Lc // 2), (B, H, d, Lc // 32)
+    codes = torch.empty(cshape, dtype=torch.uint8, device=x.device) if want_codes else None
+    scales = torch.empty(sshape, dtype=torch.uint8, device=x.device) if want_codes else None
+    xf = torch.empty_like(x) if want_xf else None
+    _check(lib().attnqat_quantize_mx(_ptr(x), B, H, L, d, BF16, int(axis), _ptr(codes), _ptr(scales), _ptr(xf), _stream()))
+    return codes, scales, xf
+
+
+def attnqat_fwd_infer_mx(q, k, v, causal: bool, workspace=None, out=None):
+    """Alg. 1 in the MX format on the scaled FP4 MFMA.  Returns (o bf16, lse fp32)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    ws, nb = _workspace(WS_FWD_INFER_MX, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_fwd_infer_mx(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+                                      _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
     return o, lse
 
 

@@ -83,6 +83,19 @@ BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     return w;
 }
 
+// Workspace of the MX forward: Q operand codes and scale dwords, and the 64-key kv records.
+struct MxWs { unsigned char *qops, *qsc, *kv; size_t bytes; };
+MxWs carve_mx(void* ws, int B, int Hq, int Hkv, int L, int d)
+{
+    Carver c{(unsigned char*)ws, 0};
+    MxWs w;
+    w.qops = (unsigned char*)c.take(mx_qops_bytes(B * Hq, L, d));
+    w.qsc = (unsigned char*)c.take(mx_qsc_bytes(B * Hq, L));
+    w.kv = (unsigned char*)c.take(mx_kv_bytes(B * Hkv, L, d));
+    w.bytes = c.off;
+    return w;
+}
+
 int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int Hkv, int L, int d,
                int causal, int dtype, bool train, void* o, float* lse, float* o_hp,
                int dump_row0, float* p_dump, void* workspace, size_t workspace_bytes, void* stream)
@@ -131,6 +144,7 @@ size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d)
     case ATTNQAT_WS_FWD:
     case ATTNQAT_WS_FWD_INFER: return carve_fwd(nullptr, B, Hq, Hkv, L, d).bytes;
     case ATTNQAT_WS_BWD:       return carve_bwd(nullptr, B, Hq, Hkv, L, d).bytes;
+    case ATTNQAT_WS_FWD_INFER_MX: return carve_mx(nullptr, B, Hq, Hkv, L, d).bytes;
     default:                   return 0;
     }
 }
@@ -145,6 +159,40 @@ int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
     if (launch_prep(x, B * H, L, d, true, false, codes, scales, xf, nullptr, nullptr, (hipStream_t)stream))
         return ATTNQAT_ELAUNCH;
     prof_mark("quantize", (hipStream_t)stream);
+    return ATTNQAT_OK;
+}
+
+int attnqat_quantize_mx(const void* x, int B, int H, int L, int d, int dtype, int axis,
+                        uint8_t* codes, uint8_t* scales, void* xf, void* stream)
+{
+    if (!x || (!codes && !scales && !xf) || (axis != 0 && axis != 1)) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, H, H, L, d, dtype);
+    if (rc) return rc;
+    prof_begin((hipStream_t)stream);
+    if (launch_mx_quant(x, B * H, L, d, axis, 0, codes, scales, xf, (hipStream_t)stream)) return ATTNQAT_ELAUNCH;
+    prof_mark("quantize_mx", (hipStream_t)stream);
+    return ATTNQAT_OK;
+}
+
+int attnqat_fwd_infer_mx(const void* q, const void* k, const void* v,
+                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                         void* o, float* lse,
+                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    MxWs w = carve_mx(workspace, B, Hq, Hkv, L, d);
+    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    // Alg. 1 first line, in the MX format: phi(Q), phi(K) along d, phi(V) along the keys
+    if (launch_mx_quant(q, B * Hq, L, d, 0, 1, w.qops, w.qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(k, B * Hkv, L, d, 0, 2, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(v, B * Hkv, L, d, 1, 2, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_qkv_mx", st);
+    if (launch_fwd_mx(w.qops, w.qsc, w.kv, B, Hq, Hkv, L, d, causal != 0, o, lse, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("fwd_infer_mx", st);
     return ATTNQAT_OK;
 }
 

@@ -156,6 +156,9 @@ __device__ inline uint2v lds_read_tr16b(const unsigned char* p) { return lds_rea
 __device__ inline uint4v lds_read16(const unsigned char* p) {
     return *(const __attribute__((address_space(3))) uint4v*)p;
 }
+__device__ inline uint32_t lds_read4(const unsigned char* p) {
+    return *(const __attribute__((address_space(3))) uint32_t*)p;
+}
 // One wave copies 1 KiB: LDS chunk slot (wave-uniform slot0 + lane) <- its global source.
 // Inline assembly on purpose.  The compiler files global_load_lds under FLAT accesses that may
 // touch both memories, and while one is pending it turns every LDS wait of the wave into "wait

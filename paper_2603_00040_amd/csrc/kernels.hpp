@@ -40,4 +40,18 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
                     unsigned long long* tile_counts /* may be null */, bool p_quant /* false: ablation */, hipStream_t st);
 
+// ---- MX variant (E2M1, blocks of 32, E8M0 scale; mx.hip) ----
+// phi with the blocks along d (axis 0) or along the sequence (axis 1).  x [BH, L, D] bf16.
+//   mode 0: public layout (codes, scales, optional bf16 xf, see attnqat.h)
+//   mode 1: Q operands of the scaled MFMA (axis 0 only): codes -> operand array, scales -> scale dwords
+//   mode 2: the K part (axis 0) or the V part (axis 1) of the 64-key kv records at `codes`
+int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode,
+                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st);
+size_t mx_kv_bytes(int BHkv, int L, int D);
+size_t mx_qops_bytes(int BHq, int L, int D);
+size_t mx_qsc_bytes(int BHq, int L);
+// Alg. 1 on the arrays made by launch_mx_quant (modes 1 and 2).
+int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
+                  void* o, float* lse, hipStream_t st);
+
 }  // namespace aq

@@ -1,0 +1,422 @@
+// MX variant of the quantizer and of the inference forward (Alg. 1) on the scaled FP4 MFMA of gfx950.
+//
+// Format (the OCP microscaling FP4 that Sec. 3.1 names beside NVFP4): E2M1 elements in blocks of 32
+// with one power-of-two E8M0 scale, the smallest 2^e (e >= -126) with 6 * 2^e >= max|X|: the
+// power-of-two counterpart of Eq. 1, no element saturates.  Q and K are blocked along d, P-tilde and
+// V along the keys, so both products of Alg. 1 contract over the blocked axis and run on
+// v_mfma_scale_f32_32x32x64_f8f6f4 with the FP4 codes and the scale bytes as they are: there is no
+// dequantization anywhere, and phi(P-tilde) is one exponent extraction plus the hardware converts.
+//
+// Operand layout of that instruction with FP4 on both sides (checked on the device against a
+// scalar evaluation): lane l holds row (A) or column (B) l % 32 and the 32 contraction indices
+// 32 * (l / 32) .. + 31 as 32 nibbles in 4 registers, low nibble first, plus one scale byte for
+// exactly those 32 indices: one MX block per lane.
+//
+//   S^T[key, query]  = K codes (A, from LDS) x Q codes (B, registers), contraction over d
+//   O^T[d, query]   += V^T codes (A, from LDS) x P-tilde codes (B, registers), contraction over keys
+//
+// The rows of the two S^T products of a 64-key tile are assigned to keys so that the 32 accumulator
+// registers of a lane are the 32 consecutive keys 32 * (lane / 32) .. + 31 of the tile: one P block,
+// whose maximum, scale and codes never leave the lane, and whose 4 code registers already are the
+// B operand of the P.V product.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace aq {
+
+typedef int int8v __attribute__((ext_vector_type(8)));
+
+// E8M0 byte of the smallest power of two s >= 2^-126 with 6 s >= amax (amax >= 0, finite).
+// With amax = m 2^x, 1 <= m < 2:  6 * 2^(x-2) = 1.5 * 2^x covers m <= 1.5, else one more.
+__device__ inline uint32_t e8m0_of_amax(float amax) {
+    const uint32_t b = (__float_as_uint(amax) + 0x003FFFFFu) >> 23;      // biased exponent, +1 if mantissa > 1.5
+    return b > 3u ? b - 2u : 1u;
+}
+__device__ inline float e8m0_as_f32(uint32_t byte) { return __uint_as_float(byte << 23); }   // byte >= 1
+
+// 32 values -> 4 registers of E2M1 codes (value i in nibble i), RNE on v / scale, saturating.
+__device__ inline uint4v mx_codes32(const float (&v)[32], float scale) {
+    uint4v c;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        uint32_t r = 0u;
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * w + 0], v[8 * w + 1], scale, 0);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * w + 2], v[8 * w + 3], scale, 1);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * w + 4], v[8 * w + 5], scale, 2);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * w + 6], v[8 * w + 7], scale, 3);
+        c[w] = r;
+    }
+    return c;
+}
+
+__device__ inline float e2m1_value_of(uint32_t code) {
+    const uint32_t m = code & 7u;
+    const float v = m < 2u ? 0.5f * (float)m : __uint_as_float(((m >> 1) + 126u) << 23 | (m & 1u) << 22);
+    return (code & 8u) ? -v : v;
+}
+
+// Bytes of one 64-key record of a kv head: K operands, V^T operands, K scales, V scales.
+__host__ __device__ constexpr int mx_rec_bytes(int D) { return 2 * (D / 64) * 1024 + (D / 32) * 1024 + 512; }
+
+// Row of S^T product t (0/1) that holds key kk (0..63) of a tile, and the lane half that ends up owning it:
+// the accumulator register r of a lane in half h is row 8 (r/4) + 4 h + r % 4; key 32 h + 16 t + r goes there.
+__device__ inline int mx_srow_of_key(int kk) { const int w = kk & 15; return 8 * (w >> 2) + 4 * (kk >> 5) + (w & 3); }
+
+// ---------------------------------------------------------------------------------------------
+// phi along d (blocks of 32).  One thread per block.
+//   MODE 0: public layout   codes [rows, D/2], scales [rows, D/32], optional bf16 xf
+//   MODE 1: Q operands      ops [rows/32, D/64, 64 lanes, 16 B], sc [rows/32, 64 lanes] (byte ks)
+//   MODE 2: K part of the kv records
+template <int D, int MODE>
+__global__ __launch_bounds__(256) void mx_quant_d_kernel(
+    const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
+    uint16_t* __restrict__ xf)
+{
+    constexpr int NB = D / 32, KS = D / 64;
+    const int bh = blockIdx.y;
+    const int gid = blockIdx.x * 256 + threadIdx.x;
+    const int row = gid / NB, blk = gid % NB;
+    const int rows_out = MODE == 0 ? L : Lp;
+    if (row >= rows_out) return;
+    float v[32];
+    if (row < L) {
+        const uint4v* src = reinterpret_cast<const uint4v*>(x + ((size_t)bh * L + row) * D + blk * 32);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4v a = src[j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[8 * j + 2 * i]     = __uint_as_float(a[i] << 16);
+                v[8 * j + 2 * i + 1] = __uint_as_float(a[i] & 0xFFFF0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = 0.0f;
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(v[i]));
+    const uint32_t byte = e8m0_of_amax(amax);
+    const float s = e8m0_as_f32(byte);
+    const uint4v c = mx_codes32(v, s);
+    if (MODE == 0) {
+        if (codes) *reinterpret_cast<uint4v*>(codes + ((size_t)bh * L + row) * (D / 2) + blk * 16) = c;
+        if (scales) scales[((size_t)bh * L + row) * NB + blk] = (unsigned char)byte;
+        if (xf) {
+            uint4v o[4];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t w = c[i >> 2] >> (8 * (i & 3));
+                // code * 2^e: at most 2 significant bits, exact in bf16 whenever it is a normal number
+                const uint32_t lo = f32_to_bf16_rne(e2m1_value_of(w & 15u) * s), hi = f32_to_bf16_rne(e2m1_value_of((w >> 4) & 15u) * s);
+                o[i >> 2][i & 3] = lo | (hi << 16);
+            }
+            uint4v* dst = reinterpret_cast<uint4v*>(xf + ((size_t)bh * L + row) * D + blk * 32);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dst[j] = o[j];
+        }
+    } else if (MODE == 1) {
+        const int g = row >> 5, ks = blk >> 1, lane = (blk & 1) * 32 + (row & 31);
+        const size_t grp = (size_t)bh * (Lp / 32) + g;
+        *reinterpret_cast<uint4v*>(codes + ((grp * KS + ks) * 64 + lane) * 16) = c;
+        scales[(grp * 64 + lane) * 4 + ks] = (unsigned char)byte;
+        if (KS == 1) { scales[(grp * 64 + lane) * 4 + 1] = 1; }
+        if (ks == 0) { scales[(grp * 64 + lane) * 4 + 2] = 1; scales[(grp * 64 + lane) * 4 + 3] = 1; }
+    } else {
+        constexpr int REC = mx_rec_bytes(D), KOPS = 2 * KS * 1024, VOPS = NB * 1024;
+        const int tile = row >> 6, kk = row & 63, t = (kk >> 4) & 1;
+        const int ks = blk >> 1, lane = (blk & 1) * 32 + mx_srow_of_key(kk);
+        unsigned char* rec = codes + ((size_t)bh * (Lp / 64) + tile) * REC;
+        *reinterpret_cast<uint4v*>(rec + ((t * KS + ks) * 64 + lane) * 16) = c;
+        rec[KOPS + VOPS + lane * 4 + t * KS + ks] = (unsigned char)byte;
+        if (KS == 1 && t == 0) { rec[KOPS + VOPS + lane * 4 + 2] = 1; rec[KOPS + VOPS + lane * 4 + 3] = 1; }
+    }
+}
+
+// phi along the sequence axis (blocks of 32 positions, zero padded): how V is blocked.
+// One thread per (block of 32 positions, d index); x [BH, L, D].
+//   MODE 0: public layout  codes [BH, D, Lc/2], scales [BH, D, Lc/32] with Lc = round_up(L, 32); optional bf16 xf [BH, L, D]
+//   MODE 2: V part of the kv records
+template <int D, int MODE>
+__global__ __launch_bounds__(D) void mx_quant_l_kernel(
+    const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
+    uint16_t* __restrict__ xf)
+{
+    constexpr int KS = D / 64, MT = D / 32;
+    const int bh = blockIdx.y, kb = blockIdx.x, dd = threadIdx.x;
+    const uint16_t* src = x + (size_t)bh * L * D + dd;
+    float v[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const int l = kb * 32 + i;
+        v[i] = l < L ? bf16_to_f32(src[(size_t)l * D]) : 0.0f;
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(v[i]));
+    const uint32_t byte = e8m0_of_amax(amax);
+    const float s = e8m0_as_f32(byte);
+    const uint4v c = mx_codes32(v, s);
+    if (MODE == 0) {
+        const int Lc = round_up(L, 32);
+        if (codes) *reinterpret_cast<uint4v*>(codes + ((size_t)bh * D + dd) * (Lc / 2) + kb * 16) = c;
+        if (scales) scales[((size_t)bh * D + dd) * (Lc / 32) + kb] = (unsigned char)byte;
+        if (xf) {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const int l = kb * 32 + i;
+                const uint32_t code = (c[i >> 3] >> (4 * (i & 7))) & 15u;
+                if (l < L) xf[((size_t)bh * L + l) * D + dd] = f32_to_bf16_rne(e2m1_value_of(code) * s);
+            }
+        }
+    } else {
+        constexpr int REC = mx_rec_bytes(D), KOPS = 2 * KS * 1024, VOPS = MT * 1024;
+        const int tile = kb >> 1, lane = (kb & 1) * 32 + (dd & 31), mt = dd >> 5;
+        unsigned char* rec = codes + ((size_t)bh * (Lp / 64) + tile) * REC;
+        *reinterpret_cast<uint4v*>(rec + KOPS + (mt * 64 + lane) * 16) = c;
+        rec[KOPS + VOPS + 256 + lane * 4 + mt] = (unsigned char)byte;
+        if (MT == 2 && mt == 0) { rec[KOPS + VOPS + 256 + lane * 4 + 2] = 1; rec[KOPS + VOPS + 256 + lane * 4 + 3] = 1; }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Alg. 1 on the MX operands.  A workgroup of 4 waves owns 128 query rows of one head, a wave 32 of
+// them, a lane one row and one of the two 32-key blocks of every 64-key tile (B_k = 64).
+// kv records arrive in stages of two tiles, copied global->LDS directly into a ring of three stage
+// buffers; one barrier per stage.  The S^T products of tile j+1 are issued before the softmax of
+// tile j, so the matrix unit works under the wave's own vector instructions.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
+    const unsigned char* __restrict__ qops, const uint32_t* __restrict__ qsc, const unsigned char* __restrict__ kv,
+    uint16_t* __restrict__ O, float* __restrict__ lse, int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */)
+{
+    constexpr int KS = D / 64, MT = D / 32;
+    constexpr int KOPS = 2 * KS * 1024, VOPS = MT * 1024, REC = mx_rec_bytes(D), STAGE = 2 * REC, NCH = STAGE / 1024;
+    static_assert(STAGE % 1024 == 0, "a stage is a whole number of 1 KiB wave copies");
+    extern __shared__ __align__(16) unsigned char smem[];          // 3 stage buffers
+
+    const int nqt = Lp / 128;
+    const int bh = blockIdx.x / nqt;
+    int qt = blockIdx.x % nqt;
+    if (CAUSAL) qt = nqt - 1 - qt;                                 // longest rows first
+    const int b = bh / Hq, h = bh % Hq;
+    const int bhkv = b * (Hq / G) + h / G;
+    const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row0_w = qt * 128 + wave * 32;
+    const int q_row = row0_w + ln;
+    const int wave_qmax = row0_w + 31;
+
+    // Q operands of this lane: codes of its row for d-slots 64 ks + 32 hf .. + 31, scale bytes by ks
+    uint4v qop[KS];
+    const size_t grp = (size_t)bh * (Lp / 32) + (row0_w >> 5);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qop[ks] = *reinterpret_cast<const uint4v*>(qops + ((grp * KS + ks) * 64 + lane) * 16);
+    uint32_t qs = qsc[grp * 64 + lane];
+
+    const int nkt_all = (L + 63) / 64;
+    const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;   // tiles this workgroup visits
+    const int nst = (nkt + 1) / 2;
+    const unsigned char* kv_head = kv + (size_t)bhkv * (Lp / 64) * REC;
+    auto issue_stage = [&](int s) __attribute__((always_inline)) {
+        const unsigned char* src = kv_head + (size_t)s * STAGE;
+        unsigned char* dst = smem + (s % 3) * STAGE;
+        for (int i = wave; i < NCH; i += 4) async_copy16(src, (uint32_t)(i * 1024 + lane * 16), dst + i * 1024);
+    };
+    auto rec_of = [&](int j) __attribute__((always_inline)) -> const unsigned char* {
+        return smem + ((j >> 1) % 3) * STAGE + (j & 1) * REC;
+    };
+
+    floatx16 o[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[mt][i] = 0.0f;
+    float m = -INFINITY, lsum = 0.0f;
+
+    auto as8 = [](const uint4v& x) __attribute__((always_inline)) -> int8v {
+        int8v r = {(int)x[0], (int)x[1], (int)x[2], (int)x[3], 0, 0, 0, 0};
+        return r;
+    };
+    // S^T of one tile: product t covers keys {16 t .. 16 t + 15} of both 32-key blocks
+    auto scores = [&](const unsigned char* rec, floatx16 (&s)[2]) __attribute__((always_inline)) {
+        const uint32_t ksc = lds_read4(rec + KOPS + VOPS + lane * 4);
+        uint4v a[2][KS];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) a[t][ks] = lds_read16(rec + ((t * KS + ks) * 64 + lane) * 16);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[t][i] = 0.0f;
+        }
+        s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][0]), as8(qop[0]), s[0], 4, 4, 0, ksc, 0, qs);
+        s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][0]), as8(qop[0]), s[1], 4, 4, KS, ksc, 0, qs);
+        if constexpr (KS == 2) {
+            s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][1]), as8(qop[1]), s[0], 4, 4, 1, ksc, 1, qs);
+            s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][1]), as8(qop[1]), s[1], 4, 4, 3, ksc, 1, qs);
+        }
+    };
+    // online softmax of one tile (Alg. 1 inner loop), phi of this lane's P-tilde block, O += V^F^T P-tilde^F
+    auto softmax_pv = [&](int j, const unsigned char* rec, floatx16 (&s)[2]) __attribute__((always_inline)) {
+        const int k0 = j * 64;
+        const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > row0_w);
+        if (__builtin_expect(need_mask, 0)) {
+            const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (k0 + 32 * hf + 16 * t + i > klim) s[t][i] = -INFINITY;
+        }
+        float mp[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) mp[t] = max_nc(s[0][t], s[1][t]);
+#pragma unroll
+        for (int i = 4; i < 16; ++i) mp[i & 3] = max_nc(max_nc(mp[i & 3], s[0][i]), s[1][i]);
+        const float mown = max_nc(max_nc(mp[0], mp[1]), max_nc(mp[2], mp[3]));      // maximum of this lane's block
+        const float mnew = fmaxf(m, xhalf_max(mown));
+        const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
+        const float ms = mnew * c;
+        m = mnew;
+        float p[32];
+        float rp[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[16 * t + i] = __builtin_amdgcn_exp2f(fmaf(s[t][i], c, -ms));
+                rp[i & 3] += p[16 * t + i];
+            }
+        lsum = lsum * alpha + ((rp[0] + rp[1]) + (rp[2] + rp[3]));                  // un-quantized P-tilde
+        // block maximum of P-tilde: exp2 of the block's largest score, the same instructions on the same inputs
+        const float amax = __builtin_amdgcn_exp2f(fmaf(mown, c, -ms));
+        const uint32_t pbyte = e8m0_of_amax(amax);
+        const uint4v pc = mx_codes32(p, e8m0_as_f32(pbyte));
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0, 0)) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[mt][i] *= alpha;
+        }
+        const uint32_t vsc = lds_read4(rec + KOPS + VOPS + 256 + lane * 4);
+        uint4v va[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) va[mt] = lds_read16(rec + KOPS + (mt * 64 + lane) * 16);
+        const int8v pb = as8(pc);
+        o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[0]), pb, o[0], 4, 4, 0, vsc, 0, pbyte);
+        o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[1]), pb, o[1], 4, 4, 1, vsc, 0, pbyte);
+        if constexpr (MT == 4) {
+            o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[2]), pb, o[2], 4, 4, 2, vsc, 0, pbyte);
+            o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[3]), pb, o[3], 4, 4, 3, vsc, 0, pbyte);
+        }
+    };
+    auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || j * 64 <= wave_qmax; };
+    // One tile: at odd j the next stage becomes visible (and the buffer two stages back becomes free).
+    auto tile_step = [&](int j, floatx16 (&scur)[2], floatx16 (&snext)[2]) __attribute__((always_inline)) {
+        if (j & 1) {
+            __builtin_amdgcn_s_waitcnt(0);                 // this wave's part of stage (j+1)/2 is in LDS
+            __builtin_amdgcn_s_barrier();                  // ... everyone's is, and everyone is past tile j-1
+            if ((j >> 1) + 2 < nst) issue_stage((j >> 1) + 2);
+        }
+        if (j + 1 < nkt && wave_sees(j + 1)) scores(rec_of(j + 1), snext);
+        if (wave_sees(j)) softmax_pv(j, rec_of(j), scur);
+    };
+
+    issue_stage(0);
+    if (nst > 1) issue_stage(1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qop[ks]));
+    asm volatile("" : "+v"(qs));
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    floatx16 sa[2], sb[2];
+    scores(rec_of(0), sa);
+    for (int j = 0; j < nkt; j += 2) {
+        tile_step(j, sa, sb);
+        if (j + 1 < nkt) tile_step(j + 1, sb, sa);
+    }
+
+    // ---- epilogue: O /= l, L = m + log l
+    const float l = xhalf_sum(lsum);
+    const float inv_l = 1.0f / l;
+    if (q_row < L) {
+        const size_t row = (size_t)bh * L + q_row;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int d0 = 32 * mt + 8 * t + 4 * hf;
+                uint2v w;
+                w[0] = pack_bf16x2_rne(o[mt][4 * t] * inv_l, o[mt][4 * t + 1] * inv_l);
+                w[1] = pack_bf16x2_rne(o[mt][4 * t + 2] * inv_l, o[mt][4 * t + 3] * inv_l);
+                *reinterpret_cast<uint2v*>(O + row * D + d0) = w;
+            }
+        if (hf == 0) lse[row] = m * (c * 0.6931471805599453f) + logf(l);   // m is in raw q.k units
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int D>
+static int quant_d(const void* x, int BH, int L, int mode, unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
+{
+    const int Lp = round_up(L, kRowPad);
+    const int rows = mode == 0 ? L : Lp;
+    const dim3 grid((unsigned)(((size_t)rows * (D / 32) + 255) / 256), (unsigned)BH);
+    if (mode == 0)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 0>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    else if (mode == 1) hipLaunchKernelGGL((mx_quant_d_kernel<D, 1>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    else                hipLaunchKernelGGL((mx_quant_d_kernel<D, 2>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+template <int D>
+static int quant_l(const void* x, int BH, int L, int mode, unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
+{
+    const int Lp = round_up(L, kRowPad);
+    const int nblk = mode == 0 ? (L + 31) / 32 : Lp / 32;
+    const dim3 grid((unsigned)nblk, (unsigned)BH);
+    if (mode == 0) hipLaunchKernelGGL((mx_quant_l_kernel<D, 0>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    else           hipLaunchKernelGGL((mx_quant_l_kernel<D, 2>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode,
+                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
+{
+    if (BH > 65535) return -1;
+    if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, codes, scales, xf, st) : quant_d<64>(x, BH, L, mode, codes, scales, xf, st);
+    return D == 128 ? quant_l<128>(x, BH, L, mode, codes, scales, xf, st) : quant_l<64>(x, BH, L, mode, codes, scales, xf, st);
+}
+
+size_t mx_kv_bytes(int BHkv, int L, int D) { return (size_t)BHkv * (round_up(L, kRowPad) / 64) * mx_rec_bytes(D); }
+size_t mx_qops_bytes(int BHq, int L, int D) { return (size_t)BHq * round_up(L, kRowPad) * (D / 2); }
+size_t mx_qsc_bytes(int BHq, int L) { return (size_t)BHq * (round_up(L, kRowPad) / 32) * 64 * 4; }
+
+template <int D, bool CAUSAL>
+static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L,
+                           void* o, float* lse, hipStream_t st)
+{
+    const int Lp = round_up(L, kRowPad);
+    const size_t smem = 3 * 2 * (size_t)mx_rec_bytes(D);
+    auto kern = fwd_mx_kernel<D, CAUSAL>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)smem) != hipSuccess) return -1;
+    const float c = 1.4426950408889634f / sqrtf((float)D);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
+                       (const unsigned char*)qops, (const uint32_t*)qsc, (const unsigned char*)kv,
+                       (uint16_t*)o, lse, L, Lp, Hq, Hq / Hkv, c);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
+                  void* o, float* lse, hipStream_t st)
+{
+    if (D == 128) return causal ? launch_fwd_mx_t<128, true>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st)
+                                : launch_fwd_mx_t<128, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st);
+    if (D == 64)  return causal ? launch_fwd_mx_t<64, true>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st)
+                                : launch_fwd_mx_t<64, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st);
+    return -1;
+}
+
+}  // namespace aq
