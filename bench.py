@@ -22,7 +22,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16 MFMA
-KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
+MFMA_FP4_PEAK_TFLOPS = 10100.0     # MI355X dense FP4 MFMA (the MX variant's products)
+KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
 # Bytes beyond L2 per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
 # measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
 MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 35.5e9, "bwd_dq": 205.2e9, "bwd_dkdv": 737.4e9}}
@@ -39,6 +40,9 @@ def main():
     ap.add_argument("--ablation", type=int, default=0,
                     help="backward ablation bit set of Sec. 4.2 (1: D from the bf16 O, 2: dV from the un-quantized P); "
                          "0 = the method itself")
+    ap.add_argument("--format", default="nvfp4", choices=["nvfp4", "mx"],
+                    help="nvfp4: the paper's format (default).  mx: E2M1 blocks of 32 with E8M0 scales on the scaled "
+                         "FP4 MFMA; forward (Alg. 1) only, on the shape of --workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -55,7 +59,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     w = W.by_name(args.workload)
-    train = w.passes == "fwd+bwd"
+    mx = args.format == "mx"
+    train = w.passes == "fwd+bwd" and not mx
     t0 = time.time()
     x = W.make_inputs(w, with_do=train)
     gen_s = time.time() - t0
@@ -71,12 +76,14 @@ def main():
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         ws_bytes = max(aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d), aq.workspace_bytes(aq.WS_BWD, B, Hq, Hkv, L, d))
     else:
-        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER, B, Hq, Hkv, L, d)
+        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX if mx else aq.WS_FWD_INFER, B, Hq, Hkv, L, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
 
     def fwd():
         if train:
             aq.attnqat_fwd(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
+        elif mx:
+            aq.attnqat_fwd_infer_mx(q, k, v, w.causal, workspace=ws, out=(o, lse))
         else:
             aq.attnqat_fwd_infer(q, k, v, w.causal, workspace=ws, out=(o, lse))
 
@@ -129,14 +136,15 @@ def main():
     pair_flops = B * Hq * float(L) ** 2 * d * (0.5 if w.causal else 1.0)
     step_flops = w.fwd_flops + (w.bwd_flops if train else 0.0)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
-    fwd_ms = kern_ms.get("prep_qkv", 0.0) + kern_ms.get("fwd_train", 0.0) + kern_ms.get("fwd_infer", 0.0)
+    fwd_ms = sum(kern_ms.get(n, 0.0) for n in ("prep_qkv", "fwd_train", "fwd_infer", "prep_qkv_mx", "fwd_infer_mx"))
+    peak = MFMA_FP4_PEAK_TFLOPS if mx else MFMA_PEAK_TFLOPS
     gemms = dict(KERNEL_GEMMS)
     if pf_frac is not None:
         gemms["bwd_dkdv"] = 6.0 + 2.0 * pf_frac
     dom = max((n for n in kern_ms if n in gemms), key=lambda n: kern_ms[n])
     achieved = gemms[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
                 "kernel_ms": round(kern_ms[dom], 3),
                 "dkdv_tiles_with_nonzero_pf": None if pf_frac is None else round(pf_frac, 6),
@@ -146,19 +154,22 @@ def main():
 
     cpu = None
     if args.cpu_seconds > 0:
-        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k())
+        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx)
 
     out = {
         "metric": "FP4-attention fwd+bwd TFLOPS (1 MI355X)" if train else "FP4-attention fwd TFLOPS (1 MI355X)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16/bf16 MFMA operands (exact NVFP4 values), fp32 accumulate and softmax",
+        "vs_baseline": None,
+        "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if mx
+                 else "f16/bf16 MFMA operands (exact NVFP4 values), fp32 accumulate and softmax",
         "data": "synthetic",
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
-                   "passes": w.passes, "block_k": aq.block_k(), "seed": w.seed, "bwd_ablation": args.ablation},
+                   "passes": "fwd_infer" if mx else w.passes, "block_k": aq.block_k(), "seed": w.seed,
+                   "bwd_ablation": args.ablation, "format": args.format},
         "fwd_tflops": round(w.fwd_flops / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
         "fwd_ms": round(fwd_ms, 3),
-        "frac_of_mfma_peak_model_flops": round(value / MFMA_PEAK_TFLOPS, 4),
+        "frac_of_mfma_peak_model_flops": round(value / peak, 4),
         "input_gen_s": round(gen_s, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -166,7 +177,7 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, x, train, target_s, block_k):
+def cpu_baseline(w, x, train, target_s, block_k, mx=False):
     """Time the oracle (as it stands) on a bounded sample of the same workload: forward of
     sampled query rows and, for training workloads, dQ of the same rows."""
     import numpy as np
@@ -184,7 +195,7 @@ def cpu_baseline(w, x, train, target_s, block_k):
     def run(n):
         rows = np.sort(rng.choice(w.L, size=min(n, w.L), replace=False)).astype(np.int64)
         t0 = time.perf_counter()
-        r = oracle.fwd(f["q"], f["k"], f["v"], w.causal, block_k, rows=rows)
+        r = (oracle.fwd_mx if mx else oracle.fwd)(f["q"], f["k"], f["v"], w.causal, block_k, rows=rows)
         if train:
             oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal)
         return rows.size, time.perf_counter() - t0

@@ -149,3 +149,39 @@ def test_full_size(cfg):
         assert not dk[:, other].any() and not dv[:, other].any()
     if w.B > 1:
         assert not dk[:b].any() and not dv[:b].any()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_full_size_mx_forward(cfg):
+    """The MX forward (scaled FP4 MFMA) on the full shapes: O and L on sampled rows, and the MX codes and
+    scales of whole K (blocks along d) and V (blocks along the keys) tensors, bit exact."""
+    import paper_2603_00040_amd as aq
+    w = W.CONFIGS[cfg]
+    print(f"\n[{w.name}] generating inputs", flush=True)
+    x = W.make_inputs(w, with_do=False)
+    q, k, v = to_dev(x["q"]), to_dev(x["k"]), to_dev(x["v"])
+    b, kv, qheads, rows = _selection(w)
+    L, Bk = w.L, aq.block_k()
+    sub = _sub(x, b, kv, qheads)
+    flat = np.asarray([hi * L + r for hi, rs in enumerate(rows) for r in rs], dtype=np.int64)
+    gi = [(b, h, r) for h, rs in zip(qheads, rows) for r in rs]
+    pick = lambda t: torch.stack([t[bb, hh, rr] for bb, hh, rr in gi])
+    print(f"[{w.name}] GPU MX forward", flush=True)
+    o, lse = aq.attnqat_fwd_infer_mx(q, k, v, w.causal)
+    torch.cuda.synchronize()
+    print(f"[{w.name}] oracle MX forward on {flat.size} rows", flush=True)
+    rf = oracle.fwd_mx(sub["q"], sub["k"], sub["v"], w.causal, Bk, rows=flat)
+    eO = rel_l2(host(pick(o)), rf["O"]); eL = max_abs(host(pick(lse)), rf["L"])
+    print(f"[{w.name}] MX O rel-L2 {eO:.2e} max-abs {max_abs(host(pick(o)), rf['O']):.2e}  L max-abs {eL:.2e}", flush=True)
+    assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
+    canon = lambda c: np.where((c & 7) == 0, c & 0xF0, c) & np.where((c & 0x70) == 0, 0x0F, 0xFF)
+    for name, axis in (("k", 0), ("v", 1)):
+        t = {"k": k, "v": v}[name][b:b + 1, kv].contiguous()
+        codes, scales, _ = aq.attnqat_quantize_mx(t, axis=axis, want_xf=False)
+        torch.cuda.synchronize()
+        xs = sub[name] if axis == 0 else np.ascontiguousarray(np.swapaxes(sub[name], -1, -2))
+        pc, ps, _ = oracle.phi_mx(xs)
+        gc, gs = codes.cpu().numpy(), scales.cpu().numpy()
+        nbad_s = int((gs != ps).sum()); nbad_c = int((canon(gc) != canon(pc)).sum())
+        print(f"[{w.name}] MX phi({name}, axis {axis}): {gs.size} scales, {nbad_s} differ; {gc.size} code bytes, {nbad_c} differ", flush=True)
+        assert nbad_s == 0 and nbad_c == 0
