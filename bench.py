@@ -26,7 +26,8 @@ MFMA_FP4_PEAK_TFLOPS = 10100.0     # MI355X dense FP4 MFMA (the MX variant's pro
 KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
 # Bytes beyond L2 per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
 # measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
-MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 35.5e9, "bwd_dq": 205.2e9, "bwd_dkdv": 737.4e9}}
+MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 35.5e9, "bwd_dq": 205.2e9, "bwd_dkdv": 737.4e9},
+                          "dit480p_infer": {"fwd_infer_mx": 1.116e9}}       # profiles/dit480p_infer_mx_fwd_kernels.txt
 
 
 def main():
