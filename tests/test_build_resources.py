@@ -52,3 +52,8 @@ def test_backward_kernels_do_not_spill():
     _check(k, r"bwd_dq_kernelILi(64|128)ELb[01]E", 4)
     # bwd_dkdv_kernel<D, CAUSAL, COUNT, PQUANT>: the measurement (COUNT) and ablation (!PQUANT) variants are exempt
     _check(k, r"bwd_dkdv_kernelILi(64|128)ELb[01]ELb0ELb1E", 4)
+
+
+def test_mx_forward_kernels_do_not_spill():
+    k = _resources("mx.hip")
+    _check(k, r"fwd_mx_kernelILi(64|128)ELb[01]E", 4)
