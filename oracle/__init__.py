@@ -58,9 +58,6 @@ def _load():
     L.oracle_e8m0_from_amax.argtypes = [_d]
     L.oracle_phi_mx.restype = _i
     L.oracle_phi_mx.argtypes = [_vp, _l, _l, _vp, _vp, _vp]
-    L.oracle_fwd_rows_mx.restype = _i
-    L.oracle_fwd_rows_mx.argtypes = [_vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
-                                     _l, _vp, _vp, _vp, _vp, _vp]
     L.oracle_bwd.restype = _i
     L.oracle_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
                              _vp, _vp, _vp]
@@ -168,33 +165,21 @@ def fake_quant_mx(x, axis: int = -1):
 
 
 def fwd_mx(q, k, v, causal: bool, Bk: int, quant_p: bool = True, rows=None, dump_p: bool = False):
-    """Alg. 1 in the MX format: Q^F, K^F blocked along d, V^F and P-tilde^F along the keys.
-    Same arguments and outputs as fwd() (Op is the un-quantized-P output of Alg. 2)."""
-    B, Hq, L, d = q.shape
-    Hkv = k.shape[1]
-    qf, kf, vf = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx(v, axis=-2)
-    if rows is None:
-        n, shp, rp = B * Hq * L, (B, Hq, L), None
-    else:
-        rows = np.ascontiguousarray(rows, dtype=np.int64)
-        n, shp, rp = rows.size, (rows.size,), rows
-    O = np.empty(shp + (d,)); Op = np.empty(shp + (d,)); Lse = np.empty(shp)
-    P = np.empty((n, L), np.float32) if dump_p else None
-    rc = _load().oracle_fwd_rows_mx(_p(qf), _p(kf), _p(vf), B, Hq, Hkv, L, d, int(causal), Bk,
-                                    int(quant_p), n, _p(rp), _p(O), _p(Op), _p(Lse), _p(P))
-    if rc:
-        raise ValueError(f"oracle_fwd_rows_mx failed ({rc})")
-    out = {"O": O, "Op": Op, "L": Lse}
-    if dump_p:
-        out["P"] = P
-    return out
+    """Alg. 1 / Alg. 2 in the MX format: Q^F, K^F blocked along d, V^F and P-tilde^F along the keys.
+    Same outputs as fwd()."""
+    return fwd(q, k, v, causal, Bk, quant_p=quant_p, scale_mode=MX, rows=rows, dump_p=dump_p)
 
 
 # ---------------------------------------------------------------- attention
 
+MX = 2      # scale_mode of the MX format: E2M1 blocks of 32 with E8M0 scales, V and P blocked along the keys
+
+
 def _prep_qkv(q, k, v, quant_qkv, scale_mode):
     q, k, v = _f32(q), _f32(k), _f32(v)
-    if quant_qkv:      # Alg. 2 first line: Q^F, K^F, V^F
+    if quant_qkv and scale_mode == MX:
+        q, k, v = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx(v, axis=-2)
+    elif quant_qkv:    # Alg. 2 first line: Q^F, K^F, V^F
         q, k, v = fake_quant(q, scale_mode), fake_quant(k, scale_mode), fake_quant(v, scale_mode)
     return q, k, v
 

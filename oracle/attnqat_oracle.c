@@ -25,7 +25,8 @@
  *   - "round to the nearest FP4 value" is round-to-nearest-even on the real
  *     quotient |x|/s, saturating at 6.
  *   - P blocks are 16 consecutive keys aligned to absolute key indices that
- *     are multiples of 16; masked and out-of-range keys count as 0.
+ *     are multiples of 16 (32 and 32 in the MX format, scale_mode 2); masked and
+ *     out-of-range keys count as 0.
  *   - key tiles of Bk keys are visited in increasing order; the running max
  *     used for quantizing P-tilde is the max over all tiles seen so far.
  *
@@ -287,31 +288,26 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
     return err ? -2 : 0;
 }
 
+/* scale_mode 2: the MX format (qf, kf, vf are then the MX fake-quantized tensors, V blocked along
+ * the keys, and P-tilde is quantized in MX blocks of 32 keys). */
 int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
                     int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
                     int quant_p, int scale_mode,
                     long nrows, const long* rows,
                     double* O, double* Op, double* Lse, float* Pdump)
 {
-    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode, 0,
-                         nrows, rows, O, Op, Lse, Pdump);
-}
-
-/* The same recurrence with P-tilde quantized in MX blocks of 32 keys (qf, kf, vf: the MX
- * fake-quantized tensors, V blocked along the keys). */
-int oracle_fwd_rows_mx(const float* qf, const float* kf, const float* vf,
-                       int B, int Hq, int Hkv, long L, int d, int causal, int Bk, int quant_p,
-                       long nrows, const long* rows,
-                       double* O, double* Op, double* Lse, float* Pdump)
-{
-    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, 0, 1,
+    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode, scale_mode == 2,
                          nrows, rows, O, Op, Lse, Pdump);
 }
 
 /* ----------------------------------------------------------------- backward */
 
+/* Keys per P block: 16 (NVFP4), 32 in the MX format (scale_mode 2). */
+#define PB_MAX 32
+static int pb_of(int scale_mode) { return scale_mode == 2 ? 32 : 16; }
+
 /*
- * One query row against one aligned block of 16 keys [k0, k0+16): the inner
+ * One query row against one aligned block of pb keys [k0, k0+pb): the inner
  * statements of Alg. 3.  nvis = number of keys of the block the row may see
  * (the rest are masked: P = 0).  Returns P (fp32-rounded), P^F and dS.
  */
@@ -319,15 +315,17 @@ static void bwd_block(const float* qrow, const float* dorow, double lse, double 
                       const float* kh, const float* vh, long k0, int nvis, int d, double rs,
                       int quant_p, int scale_mode, double* P, double* Pf, double* dS)
 {
-    for (int k = 0; k < 16; ++k) {
+    const int pb = pb_of(scale_mode);
+    for (int k = 0; k < pb; ++k) {
         if (k < nvis) {
             double s = dot(qrow, kh + (k0 + k) * d, d) * rs;
             P[k] = (double)(float)exp(s - lse);
         } else P[k] = 0.0;
     }
-    if (quant_p) phi_block(P, 16, scale_mode, NULL, NULL, NULL, Pf);
-    else for (int k = 0; k < 16; ++k) Pf[k] = P[k];
-    for (int k = 0; k < 16; ++k) {
+    if (quant_p && scale_mode == 2) phi_mx_block(P, pb, NULL, NULL, Pf);
+    else if (quant_p) phi_block(P, pb, scale_mode, NULL, NULL, NULL, Pf);
+    else for (int k = 0; k < pb; ++k) Pf[k] = P[k];
+    for (int k = 0; k < pb; ++k) {
         if (k < nvis) {
             double dP = dot(dorow, vh + (k0 + k) * d, d);
             dS[k] = P[k] * (dP - D) * rs;        /* fp32 P, not P^F (Sec. 3.3) */
@@ -335,10 +333,10 @@ static void bwd_block(const float* qrow, const float* dorow, double lse, double 
     }
 }
 
-static int nvis_of(long k0, long kend)
+static int nvis_of(long k0, long kend, int pb)
 {
     long n = kend - k0;
-    return (int)(n < 0 ? 0 : (n > 16 ? 16 : n));
+    return (int)(n < 0 ? 0 : (n > pb ? pb : n));
 }
 
 /*
@@ -354,6 +352,7 @@ int oracle_bwd(const float* qf, const float* kf, const float* vf, const float* d
     if (!qf || !kf || !vf || !dO || !Lse || !Op || Hq % Hkv) return -1;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
+    const int pb = pb_of(scale_mode);
     memset(dQ, 0, sizeof(double) * (size_t)B * Hq * L * d);
     memset(dK, 0, sizeof(double) * (size_t)B * Hkv * L * d);
     memset(dV, 0, sizeof(double) * (size_t)B * Hkv * L * d);
@@ -370,9 +369,9 @@ int oracle_bwd(const float* qf, const float* kf, const float* vf, const float* d
                 double D = 0.0;                                   /* D = rowsum(dO o O') */
                 for (int c = 0; c < d; ++c) D += (double)dorow[c] * Op[rid * d + c];
                 long kend = causal ? i + 1 : L;
-                for (long k0 = 0; k0 < kend; k0 += 16) {
-                    double P[16], Pf[16], dS[16];
-                    int nv = nvis_of(k0, kend);
+                for (long k0 = 0; k0 < kend; k0 += pb) {
+                    double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
+                    int nv = nvis_of(k0, kend, pb);
                     bwd_block(qrow, dorow, Lse[rid], D, kh, vh, k0, nv, d, rs,
                               quant_p, scale_mode, P, Pf, dS);
                     for (int k = 0; k < nv; ++k) {
@@ -402,6 +401,7 @@ int oracle_bwd_dq_rows(const float* qf, const float* kf, const float* vf, const 
     (void)B;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
+    const int pb = pb_of(scale_mode);
     #pragma omp parallel for schedule(dynamic, 1)
     for (long n = 0; n < nrows; ++n) {
         long rid = rows[n]; long i = rid % L; long bh = rid / L;
@@ -413,9 +413,9 @@ int oracle_bwd_dq_rows(const float* qf, const float* kf, const float* vf, const 
         for (int c = 0; c < d; ++c) D += (double)dorow[c] * Op_rows[n * d + c];
         for (int c = 0; c < d; ++c) dQ_rows[n * d + c] = 0.0;
         long kend = causal ? i + 1 : L;
-        for (long k0 = 0; k0 < kend; k0 += 16) {
-            double P[16], Pf[16], dS[16];
-            int nv = nvis_of(k0, kend);
+        for (long k0 = 0; k0 < kend; k0 += pb) {
+            double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
+            int nv = nvis_of(k0, kend, pb);
             bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, d, rs,
                       quant_p, scale_mode, P, Pf, dS);
             for (int k = 0; k < nv; ++k)
@@ -439,6 +439,7 @@ int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, cons
     if (!keys || Hq % Hkv || b < 0 || b >= B || hk < 0 || hk >= Hkv) return -1;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
+    const int pb = pb_of(scale_mode);
     const float* kh = kf + ((long)b * Hkv + hk) * L * d;
     const float* vh = vf + ((long)b * Hkv + hk) * L * d;
     /* D for every query row of the group */
@@ -453,7 +454,7 @@ int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, cons
     }
     #pragma omp parallel for schedule(dynamic, 1)
     for (long n = 0; n < nkeys; ++n) {
-        long key = keys[n]; long k0 = key - key % 16; int kk = (int)(key - k0);
+        long key = keys[n]; long k0 = key - key % pb; int kk = (int)(key - k0);
         for (int c = 0; c < d; ++c) { dK_keys[n * d + c] = 0.0; dV_keys[n * d + c] = 0.0; }
         for (int g = 0; g < G; ++g) {
             for (long i = 0; i < L; ++i) {
@@ -461,9 +462,9 @@ int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, cons
                 if (Pf_dump) Pf_dump[(n * G + g) * L + i] = 0.0f;
                 if (key >= kend) continue;
                 long rid = ((long)b * Hq + hk * G + g) * L + i;
-                double P[16], Pf[16], dS[16];
+                double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
                 bwd_block(qf + rid * d, dO + rid * d, Lse_grp[g * L + i], Dg[g * L + i],
-                          kh, vh, k0, nvis_of(k0, kend), d, rs, quant_p, scale_mode, P, Pf, dS);
+                          kh, vh, k0, nvis_of(k0, kend, pb), d, rs, quant_p, scale_mode, P, Pf, dS);
                 for (int c = 0; c < d; ++c) {
                     dV_keys[n * d + c] += Pf[kk] * (double)dO[rid * d + c];
                     dK_keys[n * d + c] += dS[kk] * (double)qf[rid * d + c];
@@ -491,6 +492,7 @@ int oracle_bwd_rows_dkdv(const float* qf, const float* kf, const float* vf, cons
     if (!rows || Hq % Hkv) return -1;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
+    const int pb = pb_of(scale_mode);
     memset(dK, 0, sizeof(double) * (size_t)B * Hkv * L * d);
     memset(dV, 0, sizeof(double) * (size_t)B * Hkv * L * d);
     for (long n = 0; n < nrows; ++n) {              /* rows one after another ... */
@@ -502,12 +504,12 @@ int oracle_bwd_rows_dkdv(const float* qf, const float* kf, const float* vf, cons
         double D = 0.0;
         for (int c = 0; c < d; ++c) D += (double)dorow[c] * Op_rows[n * d + c];
         long kend = causal ? i + 1 : L;
-        long nblk = (kend + 15) / 16;
+        long nblk = (kend + pb - 1) / pb;
         #pragma omp parallel for schedule(static)   /* ... key blocks in parallel: disjoint dK/dV rows */
         for (long kb = 0; kb < nblk; ++kb) {
-            long k0 = kb * 16;
-            double P[16], Pf[16], dS[16];
-            int nv = nvis_of(k0, kend);
+            long k0 = kb * pb;
+            double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
+            int nv = nvis_of(k0, kend, pb);
             bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, d, rs, quant_p, scale_mode, P, Pf, dS);
             for (int k = 0; k < nv; ++k) {
                 long kr = (u * L + k0 + k) * d;

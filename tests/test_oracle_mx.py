@@ -193,3 +193,82 @@ def test_mx_and_nvfp4_forward_differ_at_quantization_noise_level():
     ea = np.linalg.norm(a - ref) / np.linalg.norm(ref); eb = np.linalg.norm(b - ref) / np.linalg.norm(ref)
     assert 1e-2 < ea < 0.5 and 1e-2 < eb < 0.5
     assert eb > 0.8 * ea        # coarser blocks and power-of-two scales do not beat NVFP4 by a margin
+
+
+# ---------------------------------------------------------------- backward (Alg. 3) in the MX format
+
+def _autograd_mx(q, k, v, do, causal):
+    """torch autograd (fp64) through the unrolled MX fake-quant graph, straight-through at every
+    phi^-1 phi: Q, K blocked along d, V and P blocked along the keys."""
+    import torch
+
+    def ste(x, axis):
+        fq = torch.from_numpy(indep.fake_quant_mx_np(x.detach().numpy(), axis=axis))
+        return x + (fq - x).detach()
+
+    q, k, v, do = (torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True) for a in (q, k, v, do))
+    G = q.shape[1] // k.shape[1]
+    qf, kf, vf = ste(q, -1), ste(k, -1), ste(v, -2)
+    kf = kf.repeat_interleave(G, dim=1); vf = vf.repeat_interleave(G, dim=1)
+    s = qf @ kf.transpose(-1, -2) / np.sqrt(q.shape[-1])
+    if causal:
+        L = q.shape[2]
+        s = s.masked_fill(torch.triu(torch.ones(L, L, dtype=torch.bool), 1), float("-inf"))
+    p = torch.softmax(s, -1)
+    p32 = p.detach().to(torch.float32).to(torch.float64)
+    pq = torch.from_numpy(indep.fake_quant_mx_np(p32.numpy(), axis=-1))
+    p = p + (pq - p).detach()
+    o = p @ vf
+    (o * do.detach()).sum().backward()
+    return q.grad.numpy(), k.grad.numpy(), v.grad.numpy()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_mx_backward_matches_autograd_of_unrolled_ste_graph(causal):
+    q, k, v = _rand(1, 4, 2, 80, 32, seed=31, outlier=True)        # 80 = 2 * 32 + 16: a short last block
+    do = _bf16(np.random.default_rng(131).standard_normal(q.shape))
+    f = oracle.fwd(q, k, v, causal, 32, scale_mode=oracle.MX)
+    g = oracle.bwd(q, k, v, do, f["L"], f["Op"], causal, scale_mode=oracle.MX)
+    dq, dk, dv = _autograd_mx(q, k, v, do, causal)
+    for name, a, b in (("dQ", g["dQ"], dq), ("dK", g["dK"], dk), ("dV", g["dV"], dv)):
+        assert np.allclose(a, b, rtol=0, atol=5e-6 * np.abs(b).max()), name
+    # and it is not the NVFP4 backward
+    g16 = oracle.bwd(q, k, v, do, f["L"], f["Op"], causal)
+    assert np.linalg.norm(g16["dV"] - g["dV"]) > 1e-3 * np.linalg.norm(g["dV"])
+
+
+def test_mx_dV_is_PF_transpose_dO_with_blocks_of_32_keys():
+    q, k, v = _rand(1, 2, 1, 96, 32, seed=32)
+    do = _bf16(np.random.default_rng(132).standard_normal(q.shape))
+    f = oracle.fwd(q, k, v, True, 64, scale_mode=oracle.MX)
+    g = oracle.bwd(q, k, v, do, f["L"], f["Op"], True, scale_mode=oracle.MX)
+    qf, kf = indep.fake_quant_mx_np(q), indep.fake_quant_mx_np(k)
+    dv = np.zeros((96, 32))
+    for h in range(2):
+        s = qf[0, h] @ kf[0, 0].T / np.sqrt(32)
+        s[np.triu(np.ones((96, 96), bool), 1)] = -np.inf
+        p = np.exp(s - f["L"][0, h][:, None]).astype(np.float32).astype(np.float64)
+        dv += indep.fake_quant_mx_np(p, axis=-1).T @ do[0, h]
+    assert np.allclose(g["dV"][0, 0], dv, rtol=0, atol=1e-10)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_mx_sampled_backward_entry_points_match_full(causal):
+    q, k, v = _rand(2, 4, 2, 70, 32, seed=33)
+    do = _bf16(np.random.default_rng(133).standard_normal(q.shape))
+    f = oracle.fwd(q, k, v, causal, 64, scale_mode=oracle.MX)
+    g = oracle.bwd(q, k, v, do, f["L"], f["Op"], causal, scale_mode=oracle.MX)
+    rows = oracle.flat_rows(2, 4, 70, [(0, 0, 0), (1, 3, 69), (0, 2, 33), (1, 1, 31), (1, 1, 32)])
+    fr = oracle.fwd(q, k, v, causal, 64, scale_mode=oracle.MX, rows=rows)
+    dq = oracle.bwd_dq_rows(q, k, v, do, rows, fr["L"], fr["Op"], causal, scale_mode=oracle.MX)
+    assert np.allclose(dq, g["dQ"].reshape(-1, 32)[rows], rtol=0, atol=1e-12)
+    keys = np.array([0, 31, 32, 47, 64, 69])
+    b, hk = 1, 1
+    dk, dv = oracle.bwd_dkdv_keys(q, k, v, do, b, hk, keys, f["L"][b, 2:4], f["Op"][b, 2:4], causal,
+                                  scale_mode=oracle.MX)
+    assert np.allclose(dk, g["dK"][b, hk, keys], rtol=0, atol=1e-12)
+    assert np.allclose(dv, g["dV"][b, hk, keys], rtol=0, atol=1e-12)
+    sparse = np.zeros_like(do).reshape(-1, 32); sparse[rows] = do.reshape(-1, 32)[rows]
+    gs = oracle.bwd(q, k, v, sparse.reshape(do.shape), f["L"], f["Op"], causal, scale_mode=oracle.MX)
+    dk2, dv2 = oracle.bwd_rows_dkdv(q, k, v, do, rows, fr["L"], fr["Op"], causal, scale_mode=oracle.MX)
+    assert np.allclose(dk2, gs["dK"], rtol=0, atol=1e-12) and np.allclose(dv2, gs["dV"], rtol=0, atol=1e-12)
