@@ -51,6 +51,8 @@ extern "C" {
 #define ATTNQAT_WS_FWD_INFER        1   /* attnqat_fwd_infer                           */
 #define ATTNQAT_WS_BWD              2   /* attnqat_bwd                                 */
 #define ATTNQAT_WS_FWD_INFER_MX     3   /* attnqat_fwd_infer_mx                        */
+#define ATTNQAT_WS_FWD_MX           4   /* attnqat_fwd_mx, attnqat_debug_fwd_p_mx      */
+#define ATTNQAT_WS_BWD_MX           5   /* attnqat_bwd_mx                              */
 
 /*
  * phi of Eq. 1 (Sec. 3.1) along d: for every 16 consecutive elements
@@ -134,8 +136,10 @@ const char* attnqat_strerror(int code);
 /*
  * Test hook: attnqat_fwd_infer that also writes the dequantized P-tilde^F that
  * entered the O update, for the 128 query rows [row0, row0+128) of every head
- * (row0 a multiple of 128): p_dump [B,Hq,128,L] fp32 (device, written; rows
- * beyond L and masked keys get 0).
+ * (row0 a multiple of 128): p_dump [B,Hq,128,L] fp32 (device).  The caller
+ * zeroes it: key tiles that no row of a 32-row group can see under the causal
+ * mask are skipped and not written, nor are rows beyond L; masked keys inside
+ * a visited tile get 0.
  */
 int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
@@ -170,6 +174,31 @@ int attnqat_fwd_infer_mx(const void* q, const void* k, const void* v,
                          int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                          void* o, float* lse,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Training forward (Alg. 2) and backward (Alg. 3) in the MX format, for training against
+ * attnqat_fwd_infer_mx: the same quantizers (Q^F, K^F blocked along d; V^F, P-tilde^F and the
+ * backward's recomputed P^F in blocks of 32 keys; power-of-two scales), O' from the un-quantized
+ * P-tilde, D from O', dS from the fp32 P.  These two run on the 16-bit matrix instructions with the
+ * dequantized values (Eq. 4), which are the numbers the FP4 instruction multiplies (Eq. 3): O and lse
+ * agree with attnqat_fwd_infer_mx up to fp32 summation order, except that dequantized values below
+ * the fp16 range (2^-24; P-tilde^F far below the row maximum, elements of all-tiny Q/K/V blocks)
+ * are flushed here.  Arguments as attnqat_fwd / attnqat_bwd; workspace sizes ATTNQAT_WS_FWD_MX and
+ * ATTNQAT_WS_BWD_MX.  attnqat_debug_fwd_p_mx is attnqat_debug_fwd_p for this forward.
+ */
+int attnqat_fwd_mx(const void* q, const void* k, const void* v,
+                   int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                   void* o, float* lse, float* o_hp,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int attnqat_bwd_mx(const void* q, const void* k, const void* v, const void* d_o,
+                   const float* lse, const float* o_hp,
+                   int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                   void* dq, void* dk, void* dv,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int attnqat_debug_fwd_p_mx(const void* q, const void* k, const void* v,
+                           int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                           void* o, float* lse, int row0, float* p_dump,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement hook (the kernels of Alg. 1-3 are enqueued back to back by one call, so a

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libattnqat.so")
 
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4, -5
 BF16 = 0
-WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX = 0, 1, 2, 3
+WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX, WS_FWD_MX, WS_BWD_MX = 0, 1, 2, 3, 4, 5
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _SIGNATURES = {
@@ -30,6 +30,11 @@ _SIGNATURES = {
                                   _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_quantize_mx": (_i, [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "attnqat_fwd_infer_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
+                            _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_debug_fwd_p_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
+                                    _vp, _sz, _vp]),
     "attnqat_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "attnqat_block_k": (_i, []),
     "attnqat_strerror": (ctypes.c_char_p, [_i]),
@@ -108,7 +113,17 @@ def attnqat_quantize(x, want_codes=True, want_xf=True):
     return codes, scales, xf
 
 
-def attnqat_fwd(q, k, v, causal: bool, workspace=None, out=None):
+def attnqat_fwd_mx(q, k, v, causal: bool, workspace=None, out=None):
+    """Alg. 2 in the MX format (16-bit matrix path).  Returns (o bf16, lse fp32 [B,Hq,L], o_hp fp32)."""
+    return attnqat_fwd(q, k, v, causal, workspace, out, _mx=True)
+
+
+def attnqat_bwd_mx(q, k, v, d_o, lse, o_hp, causal: bool, workspace=None, out=None):
+    """Alg. 3 in the MX format.  Returns (dq, dk, dv) bf16."""
+    return attnqat_bwd(q, k, v, d_o, lse, o_hp, causal, workspace, out, _mx=True)
+
+
+def attnqat_fwd(q, k, v, causal: bool, workspace=None, out=None, _mx=False):
     """Alg. 2.  Returns (o bf16, lse fp32 [B,Hq,L], o_hp fp32)."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _dev_bf16(t, n)
@@ -120,8 +135,8 @@ def attnqat_fwd(q, k, v, causal: bool, workspace=None, out=None):
         o_hp = torch.empty((B, Hq, L, d), dtype=torch.float32, device=q.device)
     else:
         o, lse, o_hp = out
-    ws, nb = _workspace(WS_FWD, B, Hq, Hkv, L, d, workspace)
-    _check(lib().attnqat_fwd(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+    ws, nb = _workspace(WS_FWD_MX if _mx else WS_FWD, B, Hq, Hkv, L, d, workspace)
+    _check((lib().attnqat_fwd_mx if _mx else lib().attnqat_fwd)(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                              _ptr(o), _ptr(lse), _ptr(o_hp), _ptr(ws), nb, _stream()))
     return o, lse, o_hp
 
@@ -178,7 +193,7 @@ def attnqat_fwd_infer_mx(q, k, v, causal: bool, workspace=None, out=None):
     return o, lse
 
 
-def attnqat_bwd(q, k, v, d_o, lse, o_hp, causal: bool, workspace=None, out=None):
+def attnqat_bwd(q, k, v, d_o, lse, o_hp, causal: bool, workspace=None, out=None, _mx=False):
     """Alg. 3.  Returns (dq, dk, dv) bf16."""
     for t, n in ((q, "q"), (k, "k"), (v, "v"), (d_o, "d_o")):
         _dev_bf16(t, n)
@@ -191,8 +206,8 @@ def attnqat_bwd(q, k, v, d_o, lse, o_hp, causal: bool, workspace=None, out=None)
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     else:
         dq, dk, dv = out
-    ws, nb = _workspace(WS_BWD, B, Hq, Hkv, L, d, workspace)
-    _check(lib().attnqat_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(o_hp),
+    ws, nb = _workspace(WS_BWD_MX if _mx else WS_BWD, B, Hq, Hkv, L, d, workspace)
+    _check((lib().attnqat_bwd_mx if _mx else lib().attnqat_bwd)(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(o_hp),
                              B, Hq, Hkv, L, d, int(causal), BF16,
                              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), nb, _stream()))
     return dq, dk, dv
@@ -227,15 +242,20 @@ def attnqat_bwd_ablation(q, k, v, d_o, lse, o_hp, o, causal: bool, ablation: int
     return dq, dk, dv
 
 
-def attnqat_debug_fwd_p(q, k, v, causal: bool, row0: int):
+def attnqat_debug_fwd_p_mx(q, k, v, causal: bool, row0: int):
+    """attnqat_debug_fwd_p for the MX forward of attnqat_fwd_mx."""
+    return attnqat_debug_fwd_p(q, k, v, causal, row0, _mx=True)
+
+
+def attnqat_debug_fwd_p(q, k, v, causal: bool, row0: int, _mx=False):
     """Test hook: (o, lse, P-tilde^F fp32 [B,Hq,128,L]) for query rows [row0, row0+128)."""
     B, Hq, L, d = q.shape
     Hkv = k.shape[1]
     o = torch.empty_like(q)
     lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
-    p = torch.empty((B, Hq, 128, L), dtype=torch.float32, device=q.device)
-    ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, None)
-    _check(lib().attnqat_debug_fwd_p(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+    p = torch.zeros((B, Hq, 128, L), dtype=torch.float32, device=q.device)    # skipped (masked) tiles are not written
+    ws, nb = _workspace(WS_FWD_MX if _mx else WS_FWD_INFER, B, Hq, Hkv, L, d, None)
+    _check((lib().attnqat_debug_fwd_p_mx if _mx else lib().attnqat_debug_fwd_p)(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                      _ptr(o), _ptr(lse), row0, _ptr(p), _ptr(ws), nb, _stream()))
     return o, lse, p
 

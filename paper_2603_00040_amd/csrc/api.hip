@@ -54,8 +54,8 @@ int check_dims(int B, int Hq, int Hkv, int L, int d, int dtype)
 }
 
 // Workspace of the forward: fp16 Q^F, K^F (row-major) and V^F^T.
-struct FwdWs { void *qh, *kh, *vt; size_t bytes; };
-FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d)
+struct FwdWs { void *qh, *kh, *vt, *tmp; size_t bytes; };
+FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 {
     const size_t Lp = round_up(L, kRowPad);
     Carver c{(unsigned char*)ws, 0};
@@ -63,14 +63,15 @@ FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     w.qh = c.take((size_t)B * Hq * Lp * d * 2);
     w.kh = c.take((size_t)B * Hkv * Lp * d * 2);
     w.vt = c.take((size_t)B * Hkv * Lp * d * 2);
+    w.tmp = mx ? c.take((size_t)B * Hq * L * d * 2) : nullptr;      // MX: the dequantized bf16 tensor before its layout copy
     w.bytes = c.off;
     return w;
 }
 
 // Workspace of the backward: row-major copies (Q^F, K^F fp16; V^F and dO bf16: dO is not exactly
 // representable in fp16), the per-row {L, D} pairs and the partial maxima that bound |dS|.
-struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; float* bounds; size_t bytes; };
-BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
+struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; float* bounds; void* tmp; size_t bytes; };
+BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 {
     const size_t Lp = round_up(L, kRowPad);
     Carver c{(unsigned char*)ws, 0};
@@ -79,6 +80,7 @@ BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d)
     w.qb = c.take(nq); w.kb = c.take(nk); w.vb = c.take(nk); w.dob = c.take(nq);
     w.rowstat = (float*)c.take((size_t)B * Hq * Lp * 8);
     w.bounds = (float*)c.take((size_t)3 * B * Hq * 64 * 4);
+    w.tmp = mx ? c.take((size_t)B * Hq * L * d * 2) : nullptr;
     w.bytes = c.off;
     return w;
 }
@@ -96,23 +98,33 @@ MxWs carve_mx(void* ws, int B, int Hq, int Hkv, int L, int d)
     return w;
 }
 
+// phi of one input tensor and its layout copies (xr row-major, xt transposed; either may be null).
+// NVFP4: one fused kernel.  MX: the MX fake-quantizer writes the dequantized bf16 tensor to tmp (blocks along d,
+// or along the sequence for V), then the layout copy runs without quantizing.
+int quant_copy(const void* x, int BH, int L, int d, bool mx, int mx_axis, bool out_f16, void* xr, void* xt, void* tmp, hipStream_t st)
+{
+    if (!mx) return launch_prep(x, BH, L, d, true, out_f16, nullptr, nullptr, nullptr, xr, xt, st);
+    if (launch_mx_quant(x, BH, L, d, mx_axis, 0, nullptr, nullptr, tmp, st)) return -1;
+    return launch_prep(tmp, BH, L, d, false, out_f16, nullptr, nullptr, nullptr, xr, xt, st);
+}
+
 int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int Hkv, int L, int d,
-               int causal, int dtype, bool train, void* o, float* lse, float* o_hp,
+               int causal, int dtype, bool train, bool mx, void* o, float* lse, float* o_hp,
                int dump_row0, float* p_dump, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!q || !k || !v || !o || !lse || (train && !o_hp)) return ATTNQAT_EINVAL;
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
-    FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d);
+    FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d, mx);
     if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
     // Alg. 1 line "phi(Q), phi(K), phi(V)" / Alg. 2 line "Q^F, K^F, V^F"
-    if (launch_prep(q, B * Hq, L, d, true, true, nullptr, nullptr, nullptr, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_prep(k, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, w.kh, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_prep(v, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
+    if (quant_copy(q, B * Hq, L, d, mx, 0, true, w.qh, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kh, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    if (quant_copy(v, B * Hkv, L, d, mx, 1, true, nullptr, w.vt, w.tmp, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkv", st);
-    if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, o, lse, o_hp, dump_row0, p_dump, st))
+    if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, mx, o, lse, o_hp, dump_row0, p_dump, st))
         return ATTNQAT_ELAUNCH;
     prof_mark(train ? "fwd_train" : "fwd_infer", st);
     return ATTNQAT_OK;
@@ -145,6 +157,8 @@ size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d)
     case ATTNQAT_WS_FWD_INFER: return carve_fwd(nullptr, B, Hq, Hkv, L, d).bytes;
     case ATTNQAT_WS_BWD:       return carve_bwd(nullptr, B, Hq, Hkv, L, d).bytes;
     case ATTNQAT_WS_FWD_INFER_MX: return carve_mx(nullptr, B, Hq, Hkv, L, d).bytes;
+    case ATTNQAT_WS_FWD_MX:    return carve_fwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
+    case ATTNQAT_WS_BWD_MX:    return carve_bwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
     default:                   return 0;
     }
 }
@@ -227,7 +241,7 @@ int attnqat_fwd(const void* q, const void* k, const void* v,
                 void* o, float* lse, float* o_hp,
                 void* workspace, size_t workspace_bytes, void* stream)
 {
-    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, true, o, lse, o_hp, 0, nullptr,
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, true, false, o, lse, o_hp, 0, nullptr,
                       workspace, workspace_bytes, stream);
 }
 
@@ -236,7 +250,7 @@ int attnqat_fwd_infer(const void* q, const void* k, const void* v,
                       void* o, float* lse,
                       void* workspace, size_t workspace_bytes, void* stream)
 {
-    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, o, lse, nullptr, 0, nullptr,
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, false, o, lse, nullptr, 0, nullptr,
                       workspace, workspace_bytes, stream);
 }
 
@@ -250,12 +264,31 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
     if (rc) return rc;
     if (hipMemsetAsync(p_dump, 0, (size_t)B * Hq * 128 * L * sizeof(float), (hipStream_t)stream) != hipSuccess)
         return ATTNQAT_ELAUNCH;
-    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, o, lse, nullptr, row0, p_dump,
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, false, o, lse, nullptr, row0, p_dump,
+                      workspace, workspace_bytes, stream);
+}
+
+int attnqat_fwd_mx(const void* q, const void* k, const void* v,
+                   int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                   void* o, float* lse, float* o_hp,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, true, true, o, lse, o_hp, 0, nullptr,
+                      workspace, workspace_bytes, stream);
+}
+
+int attnqat_debug_fwd_p_mx(const void* q, const void* k, const void* v,
+                           int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                           void* o, float* lse, int row0, float* p_dump,
+                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!p_dump || row0 < 0 || row0 % 128 != 0) return ATTNQAT_EINVAL;
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, true, o, lse, nullptr, row0, p_dump,
                       workspace, workspace_bytes, stream);
 }
 
 static int bwd_common(const void* q, const void* k, const void* v, const void* d_o,
-                      const float* lse, const void* o_acc, bool o_is_bf16, bool p_quant,
+                      const float* lse, const void* o_acc, bool o_is_bf16, int p_quant /* 0 none, 1 NVFP4, 2 MX */,
                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                       void* dq, void* dk, void* dv,
                       void* workspace, size_t workspace_bytes, void* stream)
@@ -263,14 +296,15 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
     if (!q || !k || !v || !d_o || !lse || !o_acc || !dq || !dk || !dv) return ATTNQAT_EINVAL;
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
-    BwdWs w = carve_bwd(workspace, B, Hq, Hkv, L, d);
+    const bool mx = p_quant == 2;
+    BwdWs w = carve_bwd(workspace, B, Hq, Hkv, L, d, mx);
     if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
     // Q^F, K^F, V^F again (bit-identical to the forward's) and a zero-padded copy of dO
-    if (launch_prep(q, B * Hq, L, d, true, true, nullptr, nullptr, nullptr, w.qb, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_prep(k, B * Hkv, L, d, true, true, nullptr, nullptr, nullptr, w.kb, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_prep(v, B * Hkv, L, d, true, false, nullptr, nullptr, nullptr, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (quant_copy(q, B * Hq, L, d, mx, 0, true, w.qb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    if (quant_copy(v, B * Hkv, L, d, mx, 1, false, w.vb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
     if (launch_delta(d_o, o_acc, o_is_bf16, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
@@ -292,7 +326,17 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
                 void* dq, void* dk, void* dv,
                 void* workspace, size_t workspace_bytes, void* stream)
 {
-    return bwd_common(q, k, v, d_o, lse, o_hp, false, true, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
+    return bwd_common(q, k, v, d_o, lse, o_hp, false, 1, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
+                      workspace, workspace_bytes, stream);
+}
+
+int attnqat_bwd_mx(const void* q, const void* k, const void* v, const void* d_o,
+                   const float* lse, const float* o_hp,
+                   int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                   void* dq, void* dk, void* dv,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    return bwd_common(q, k, v, d_o, lse, o_hp, false, 2, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
                       workspace, workspace_bytes, stream);
 }
 
@@ -304,7 +348,7 @@ int attnqat_bwd_ablation(const void* q, const void* k, const void* v, const void
 {
     if (ablation & ~(ATTNQAT_ABL_D_FROM_O | ATTNQAT_ABL_P_UNQUANTIZED)) return ATTNQAT_EINVAL;
     const bool low = (ablation & ATTNQAT_ABL_D_FROM_O) != 0;
-    return bwd_common(q, k, v, d_o, lse, low ? o : (const void*)o_hp, low, !(ablation & ATTNQAT_ABL_P_UNQUANTIZED),
+    return bwd_common(q, k, v, d_o, lse, low ? o : (const void*)o_hp, low, (ablation & ATTNQAT_ABL_P_UNQUANTIZED) ? 0 : 1,
                       B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv, workspace, workspace_bytes, stream);
 }
 

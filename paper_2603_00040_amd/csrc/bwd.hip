@@ -422,7 +422,8 @@ struct DkvSmem {
     uint16_t t[4][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
 };
 
-template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */, bool PQUANT /* false: ablation, dV from the fp32 P */>
+template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */,
+          int PQ /* phi(P): 0 none (ablation: dV from the fp32 P), 1 NVFP4, 2 MX */>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
@@ -590,8 +591,20 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c, -Ls));    // P = exp(S - L_i)
             // block scales of phi(P): one per 16 keys = registers 8*gq .. 8*gq+7 of both halves
+            constexpr bool PQUANT = PQ != 0;
             float sc[2], inv[2];
             bool nz = false;
+            if constexpr (PQ == 2) {
+                // MX format: this wave's 32 keys are one block with a power-of-two scale
+                float a4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) a4[t] = fmaxf(fmaxf(s[t], s[4 + t]), fmaxf(s[8 + t], s[12 + t]));
+                const float amax = xhalf_max(fmaxf(fmaxf(a4[0], a4[1]), fmaxf(a4[2], a4[3])));
+                const uint32_t byte = e8m0_of_amax(amax);
+                sc[0] = sc[1] = e8m0_as_f32(byte);
+                inv[0] = inv[1] = e8m0_inverse_as_f32(byte);
+                nz = amax > 0.0f;
+            } else
 #pragma unroll
             for (int gq = 0; gq < 2; ++gq) {
                 float amax = s[8 * gq];
@@ -727,13 +740,14 @@ template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
                          int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts,
-                         bool p_quant, hipStream_t st)
+                         int p_quant, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DkvSmem<D>);
-    auto kern = !p_quant ? bwd_dkdv_kernel<D, CAUSAL, false, false>
-              : tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true, true> : bwd_dkdv_kernel<D, CAUSAL, false, true>;
-    if (!p_quant) tile_counts = nullptr;
+    auto kern = p_quant == 0 ? bwd_dkdv_kernel<D, CAUSAL, false, 0>
+              : p_quant == 2 ? bwd_dkdv_kernel<D, CAUSAL, false, 2>
+              : tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true, 1> : bwd_dkdv_kernel<D, CAUSAL, false, 1>;
+    if (p_quant != 1) tile_counts = nullptr;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
         return -1;
     const float rs = 1.0f / sqrtf((float)D);
@@ -747,7 +761,7 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
-                    unsigned long long* tile_counts, bool p_quant, hipStream_t st)
+                    unsigned long long* tile_counts, int p_quant, hipStream_t st)
 {
     if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st)
                                 : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st);

@@ -75,6 +75,16 @@ __device__ inline float block_scale_exact(float amax) {
     return rne_e4m3_grid(v);
 }
 
+// ---- MX format (E2M1 blocks of 32, power-of-two E8M0 scale) -------------------
+// E8M0 byte of the smallest power of two s >= 2^-126 with 6 s >= amax (amax >= 0, finite).
+// With amax = m 2^x, 1 <= m < 2:  6 * 2^(x-2) = 1.5 * 2^x covers m <= 1.5, else one more.
+__device__ inline uint32_t e8m0_of_amax(float amax) {
+    const uint32_t b = (__float_as_uint(amax) + 0x003FFFFFu) >> 23;      // biased exponent, +1 if mantissa > 1.5
+    return b > 3u ? b - 2u : 1u;
+}
+__device__ inline float e8m0_as_f32(uint32_t byte) { return __uint_as_float(byte << 23); }            // 1 <= byte <= 254
+__device__ inline float e8m0_inverse_as_f32(uint32_t byte) { return __uint_as_float((254u - byte) << 23); }   // 1 <= byte <= 253
+
 // ---- cross-lane: combine the two 32-lane halves of a wave -------------------
 // v_permlane32_swap(a, b) exchanges a[32..63] with b[0..31]: called with (x, x) it returns
 // {x.lo, x.lo} and {x.hi, x.hi}, so one swap plus one ALU op reduces over the halves.

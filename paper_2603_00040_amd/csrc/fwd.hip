@@ -28,7 +28,7 @@ struct FwdSmem {
     half_t v[2][D * 64];      // V^T tile [d][key], likewise
 };
 
-template <int D, bool TRAIN, bool CAUSAL, bool DUMP>
+template <int D, bool TRAIN, bool CAUSAL, bool DUMP, bool MXP>
 __global__ __launch_bounds__(512, 2) void fwd_kernel(
     const half_t* __restrict__ Qh, const half_t* __restrict__ Kh, const half_t* __restrict__ Vt,
     uint16_t* __restrict__ O, float* __restrict__ lse, float* __restrict__ Ohp,
@@ -208,6 +208,21 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { o[mb][i] *= alpha; if constexpr (TRAIN) op[mb][i] *= alpha; }
         }
+        if constexpr (MXP) {
+            // MX format: one power-of-two scale per 32 keys = all 16 registers of s[kb] in both halves;
+            // the two 16-key groups of a block share it
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const floatx16& sv = s[kb];
+                float a4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) a4[t] = fmaxf(fmaxf(sv[t], sv[4 + t]), fmaxf(sv[8 + t], sv[12 + t]));
+                const uint32_t byte = e8m0_of_amax(xhalf_max(fmaxf(fmaxf(a4[0], a4[1]), fmaxf(a4[2], a4[3]))));
+                bsc[2 * kb] = bsc[2 * kb + 1] = e8m0_as_f32(byte);
+                binv[2 * kb] = binv[2 * kb + 1] = e8m0_inverse_as_f32(byte);
+            }
+            return;
+        }
         // block scales of phi(P-tilde) for the four 16-key groups of the tile (keys of a group =
         // registers 8g..8g+7 of both halves), as four independent chains
 #pragma unroll
@@ -373,14 +388,14 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     }
 }
 
-template <int D, bool TRAIN, bool CAUSAL, bool DUMP>
+template <int D, bool TRAIN, bool CAUSAL, bool DUMP, bool MXP>
 static int launch_t(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int L,
                     void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int nqt = (Lp + 255) / 256;
     const size_t smem = sizeof(FwdSmem<D>);
-    auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP>;
+    auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP, MXP>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)smem) != hipSuccess) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
@@ -390,29 +405,31 @@ static int launch_t(const void* qh, const void* kh, const void* vt, int B, int H
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-template <int D>
+template <int D, bool MXP>
 static int launch_d(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int L,
                     bool causal, bool train, void* o, float* lse, float* o_hp,
                     int dump_row0, float* p_dump, hipStream_t st)
 {
     if (p_dump) {
-        return causal ? launch_t<D, false, true, true>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st)
-                      : launch_t<D, false, false, true>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st);
+        return causal ? launch_t<D, false, true, true, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st)
+                      : launch_t<D, false, false, true, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st);
     }
     if (train) {
-        return causal ? launch_t<D, true, true, false>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
-                      : launch_t<D, true, false, false>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+        return causal ? launch_t<D, true, true, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
+                      : launch_t<D, true, false, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
     }
-    return causal ? launch_t<D, false, true, false>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
-                  : launch_t<D, false, false, false>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+    return causal ? launch_t<D, false, true, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
+                  : launch_t<D, false, false, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
 }
 
 int launch_fwd(const void* qh, const void* kh, const void* vt,
-               int B, int Hq, int Hkv, int L, int D, bool causal, bool train,
+               int B, int Hq, int Hkv, int L, int D, bool causal, bool train, bool mx_p,
                void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st)
 {
-    if (D == 128) return launch_d<128>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st);
-    if (D == 64)  return launch_d<64>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st);
+    if (D == 128) return mx_p ? launch_d<128, true>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st)
+                              : launch_d<128, false>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st);
+    if (D == 64)  return mx_p ? launch_d<64, true>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st)
+                              : launch_d<64, false>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st);
     return -1;
 }
 

@@ -14,8 +14,9 @@ int launch_prep(const void* x, int BH, int L, int D, bool quant, bool out_f16,
                 uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st);
 
 // Alg. 1 (train=false) / Alg. 2 (train=true) on fp16 copies made by launch_prep.
+// mx_p: phi(P-tilde) in the MX format (blocks of 32 keys, power-of-two scale) instead of NVFP4.
 int launch_fwd(const void* qh, const void* kh, const void* vt,
-               int B, int Hq, int Hkv, int L, int D, bool causal, bool train,
+               int B, int Hq, int Hkv, int L, int D, bool causal, bool train, bool mx_p,
                void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st);
 
 // Per-row statistics of the backward: rowstat [BHq, Lp, 2] = {L log2(e), D / sqrt(d)} with
@@ -38,7 +39,8 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
-                    unsigned long long* tile_counts /* may be null */, bool p_quant /* false: ablation */, hipStream_t st);
+                    unsigned long long* tile_counts /* may be null */,
+                    int p_quant /* phi(P): 0 none (ablation), 1 NVFP4, 2 MX */, hipStream_t st);
 
 // ---- MX variant (E2M1, blocks of 32, E8M0 scale; mx.hip) ----
 // phi with the blocks along d (axis 0) or along the sequence (axis 1).  x [BH, L, D] bf16.

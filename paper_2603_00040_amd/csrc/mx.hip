@@ -26,14 +26,6 @@ namespace aq {
 
 typedef int int8v __attribute__((ext_vector_type(8)));
 
-// E8M0 byte of the smallest power of two s >= 2^-126 with 6 s >= amax (amax >= 0, finite).
-// With amax = m 2^x, 1 <= m < 2:  6 * 2^(x-2) = 1.5 * 2^x covers m <= 1.5, else one more.
-__device__ inline uint32_t e8m0_of_amax(float amax) {
-    const uint32_t b = (__float_as_uint(amax) + 0x003FFFFFu) >> 23;      // biased exponent, +1 if mantissa > 1.5
-    return b > 3u ? b - 2u : 1u;
-}
-__device__ inline float e8m0_as_f32(uint32_t byte) { return __uint_as_float(byte << 23); }   // byte >= 1
-
 // 32 values -> 4 registers of E2M1 codes (value i in nibble i), RNE on v / scale, saturating.
 __device__ inline uint4v mx_codes32(const float (&v)[32], float scale) {
     uint4v c;

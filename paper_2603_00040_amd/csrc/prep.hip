@@ -148,7 +148,8 @@ int launch_prep(const void* x, int BH, int L, int D, bool quant, bool out_f16,
 {
     if (quant) return out_f16 ? launch_prep_t<true, true>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st)
                               : launch_prep_t<true, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st);
-    return launch_prep_t<false, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st);
+    return out_f16 ? launch_prep_t<false, true>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st)
+                   : launch_prep_t<false, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st);
 }
 
 }  // namespace aq

@@ -126,3 +126,68 @@ def test_fwd_mx_argument_errors():
     assert L.attnqat_fwd_infer_mx(*args(qp=None)) == aq.EINVAL
     assert L.attnqat_quantize_mx(q.data_ptr(), 1, 2, 64, 128, 0, 2, o.data_ptr(), None, None, None) == aq.EINVAL
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- training forward and backward in the MX format
+
+FLIP_BAR = 1e-4       # fraction of P-tilde^F elements that may differ from the oracle's
+F16_FLUSH = 2.0 ** -25   # the 16-bit path holds P-tilde^F in fp16: below 2^-24 a value is rounded to a multiple of 2^-24
+
+
+def _run_train(B, Hq, Hkv, L, d, causal, seed, **kw):
+    import paper_2603_00040_amd as aq
+    x = random_inputs(B, Hq, Hkv, L, d, seed, **kw)
+    q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
+    o, lse, ohp = aq.attnqat_fwd_mx(q, k, v, causal)
+    oi, lsei = aq.attnqat_fwd_infer_mx(q, k, v, causal)
+    dq, dk, dv = aq.attnqat_bwd_mx(q, k, v, do, lse, ohp, causal)
+    torch.cuda.synchronize()
+    fq, fk, fv, fdo = (f32(x[n]) for n in ("q", "k", "v", "do"))
+    rf = oracle.fwd(fq, fk, fv, causal, aq.block_k(), scale_mode=oracle.MX)
+    rb = oracle.bwd(fq, fk, fv, fdo, rf["L"], rf["Op"], causal, scale_mode=oracle.MX)
+    r = {"O": rel_l2(host(o), rf["O"]), "Op": rel_l2(host(ohp), rf["Op"]), "L": max_abs(host(lse), rf["L"])}
+    r.update({n: rel_l2(host(t), rb[n], zero_rms=1e-2) for n, t in (("dQ", dq), ("dK", dk), ("dV", dv))})
+    # Eq. 3 == Eq. 4: the FP4-instruction forward and the 16-bit forward compute the same O and L
+    r["O_vs_fp4_path"] = max_abs(host(o), host(oi)); r["L_vs_fp4_path"] = max_abs(host(lse), host(lsei))
+    print(f"mx train B{B} Hq{Hq} Hkv{Hkv} L{L} d{d} causal{int(causal)}: " + " ".join(f"{n} {a:.2e}" for n, a in r.items()), flush=True)
+    assert r["O"] <= TOL and r["Op"] <= 2e-4 and r["L"] <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
+    for n in ("dQ", "dK", "dV"):
+        assert r[n] <= TOL, (n, r[n])
+    scale = max(1.0, float(np.abs(rf["O"]).max()))
+    assert r["O_vs_fp4_path"] <= 2.0 ** -7 * scale and r["L_vs_fp4_path"] <= 1e-4       # one bf16 rounding step of O apart at most
+
+
+def test_mx_train_tiny_ref_config():
+    _run_train(1, 2, 2, 256, 64, False, seed=0)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("L", [1, 31, 64, 129, 300])
+def test_mx_train_ragged_lengths_d128_gqa(L, causal):
+    _run_train(2, 4, 2, L, 128, causal, seed=300 + L, k_chan=4)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_mx_train_d64_heavy_tails(causal):
+    _run_train(1, 3, 1, 333, 64, causal, seed=9, dist="t3", scale=0.5, tok_mod=50)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_mx_P_code_flips(causal):
+    """The dequantized P-tilde^F entering the O update of attnqat_fwd_mx, element by element."""
+    import paper_2603_00040_amd as aq
+    B, Hq, Hkv, L, d = 1, 2, 1, 640, 128
+    x = random_inputs(B, Hq, Hkv, L, d, seed=11, k_chan=4)
+    q, k, v = (to_dev(x[n]) for n in "qkv")
+    bad = tot = 0
+    for row0 in (0, 512):
+        _, _, p = aq.attnqat_debug_fwd_p_mx(q, k, v, causal, row0)
+        torch.cuda.synchronize()
+        nrow = min(128, L - row0)
+        rows = oracle.flat_rows(B, Hq, L, [(0, h, row0 + i) for h in range(Hq) for i in range(nrow)])
+        ref = oracle.fwd(f32(x["q"]), f32(x["k"]), f32(x["v"]), causal, aq.block_k(), scale_mode=oracle.MX,
+                         rows=rows, dump_p=True)
+        got = p.cpu().numpy()[0, :, :nrow].reshape(-1, L)
+        bad += int((np.abs(got.astype(np.float64) - ref["P"]) > F16_FLUSH).sum()); tot += got.size
+    print(f"MX P flips causal{int(causal)}: {bad} of {tot} ({bad / tot:.2e})", flush=True)
+    assert bad / tot < FLIP_BAR
