@@ -42,8 +42,10 @@ def main():
                     help="backward ablation bit set of Sec. 4.2 (1: D from the bf16 O, 2: dV from the un-quantized P); "
                          "0 = the method itself")
     ap.add_argument("--format", default="nvfp4", choices=["nvfp4", "mx"],
-                    help="nvfp4: the paper's format (default).  mx: E2M1 blocks of 32 with E8M0 scales on the scaled "
-                         "FP4 MFMA; forward (Alg. 1) only, on the shape of --workload")
+                    help="nvfp4: the paper's format (default).  mx: E2M1 blocks of 32 with E8M0 scales: the inference "
+                         "forward runs on the scaled FP4 MFMA, the training forward and the backward on the 16-bit path")
+    ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
+                    help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -61,7 +63,7 @@ def main():
         sys.exit(3)
     w = W.by_name(args.workload)
     mx = args.format == "mx"
-    train = w.passes == "fwd+bwd" and not mx
+    train = w.passes == "fwd+bwd" and args.passes == "auto"
     t0 = time.time()
     x = W.make_inputs(w, with_do=train)
     gen_s = time.time() - t0
@@ -75,14 +77,15 @@ def main():
     if train:
         ohp = torch.empty((B, Hq, L, d), dtype=torch.float32, device="cuda")
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-        ws_bytes = max(aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d), aq.workspace_bytes(aq.WS_BWD, B, Hq, Hkv, L, d))
+        ws_bytes = max(aq.workspace_bytes(aq.WS_FWD_MX if mx else aq.WS_FWD, B, Hq, Hkv, L, d),
+                       aq.workspace_bytes(aq.WS_BWD_MX if mx else aq.WS_BWD, B, Hq, Hkv, L, d))
     else:
         ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX if mx else aq.WS_FWD_INFER, B, Hq, Hkv, L, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
 
     def fwd():
         if train:
-            aq.attnqat_fwd(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
+            (aq.attnqat_fwd_mx if mx else aq.attnqat_fwd)(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
         elif mx:
             aq.attnqat_fwd_infer_mx(q, k, v, w.causal, workspace=ws, out=(o, lse))
         else:
@@ -92,7 +95,7 @@ def main():
         if args.ablation:
             aq.attnqat_bwd_ablation(q, k, v, do, lse, ohp, o, w.causal, args.ablation, workspace=ws, out=(dq, dk, dv))
         else:
-            aq.attnqat_bwd(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
+            (aq.attnqat_bwd_mx if mx else aq.attnqat_bwd)(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
 
     def step():
         fwd()
@@ -123,8 +126,8 @@ def main():
                 kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
     aq.profile_enable(False)
     pf_frac = None
-    if train and args.ablation & 2:
-        pf_frac = 1.0                    # the un-quantized P is never skipped
+    if train and (args.ablation & 2 or mx):
+        pf_frac = 1.0                    # the un-quantized P is never skipped; an MX P^F tile is zero only if P itself is
     elif train:
         # how many 32x32 tiles of the dK/dV pass had a non-zero P^F (the others skip the dV products, exactly)
         counts = torch.zeros(2, dtype=torch.int64, device="cuda")
@@ -138,7 +141,7 @@ def main():
     step_flops = w.fwd_flops + (w.bwd_flops if train else 0.0)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
     fwd_ms = sum(kern_ms.get(n, 0.0) for n in ("prep_qkv", "fwd_train", "fwd_infer", "prep_qkv_mx", "fwd_infer_mx"))
-    peak = MFMA_FP4_PEAK_TFLOPS if mx else MFMA_PEAK_TFLOPS
+    peak = MFMA_FP4_PEAK_TFLOPS if (mx and not train) else MFMA_PEAK_TFLOPS
     gemms = dict(KERNEL_GEMMS)
     if pf_frac is not None:
         gemms["bwd_dkdv"] = 6.0 + 2.0 * pf_frac
@@ -146,7 +149,7 @@ def main():
     achieved = gemms[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom) if (not mx or dom == "fwd_infer_mx") else None,
                 "kernel_ms": round(kern_ms[dom], 3),
                 "dkdv_tiles_with_nonzero_pf": None if pf_frac is None else round(pf_frac, 6),
                 "per_kernel": {n: {"ms": round(ms, 3),
@@ -162,11 +165,11 @@ def main():
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if mx
-                 else "f16/bf16 MFMA operands (exact NVFP4 values), fp32 accumulate and softmax",
+        "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if (mx and not train)
+                 else "f16/bf16 MFMA operands (exact %s values), fp32 accumulate and softmax" % ("MXFP4" if mx else "NVFP4"),
         "data": "synthetic",
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
-                   "passes": "fwd_infer" if mx else w.passes, "block_k": aq.block_k(), "seed": w.seed,
+                   "passes": w.passes if train else "fwd_infer", "block_k": aq.block_k(), "seed": w.seed,
                    "bwd_ablation": args.ablation, "format": args.format},
         "fwd_tflops": round(w.fwd_flops / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
         "fwd_ms": round(fwd_ms, 3),
@@ -196,9 +199,10 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False):
     def run(n):
         rows = np.sort(rng.choice(w.L, size=min(n, w.L), replace=False)).astype(np.int64)
         t0 = time.perf_counter()
-        r = (oracle.fwd_mx if mx else oracle.fwd)(f["q"], f["k"], f["v"], w.causal, block_k, rows=rows)
+        sm = oracle.MX if mx else 0
+        r = oracle.fwd(f["q"], f["k"], f["v"], w.causal, block_k, scale_mode=sm, rows=rows)
         if train:
-            oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal)
+            oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal, scale_mode=sm)
         return rows.size, time.perf_counter() - t0
 
     # two pilots separate the fixed cost (phi of the head's Q/K/V) from the cost per row

@@ -185,3 +185,49 @@ def test_full_size_mx_forward(cfg):
         nbad_s = int((gs != ps).sum()); nbad_c = int((canon(gc) != canon(pc)).sum())
         print(f"[{w.name}] MX phi({name}, axis {axis}): {gs.size} scales, {nbad_s} differ; {gc.size} code bytes, {nbad_c} differ", flush=True)
         assert nbad_s == 0 and nbad_c == 0
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_full_size_mx_training(cfg):
+    """attnqat_fwd_mx + attnqat_bwd_mx on the full training shapes: O, O', L and dQ on sampled rows; dK and dV
+    on all keys of the selected kv heads through a dO that is zero outside the sampled rows (as above)."""
+    import paper_2603_00040_amd as aq
+    w = W.CONFIGS[cfg]
+    print(f"\n[{w.name}] generating inputs", flush=True)
+    x = W.make_inputs(w, with_do=True)
+    q, k, v, do = to_dev(x["q"]), to_dev(x["k"]), to_dev(x["v"]), to_dev(x["do"])
+    b, kv, qheads, rows = _selection(w)
+    L, Bk, MX = w.L, aq.block_k(), oracle.MX
+    sub = _sub(x, b, kv, qheads)
+    flat = np.asarray([hi * L + r for hi, rs in enumerate(rows) for r in rs], dtype=np.int64)
+    gi = [(b, h, r) for h, rs in zip(qheads, rows) for r in rs]
+    pick = lambda t: torch.stack([t[bb, hh, rr] for bb, hh, rr in gi])
+    print(f"[{w.name}] GPU MX training forward", flush=True)
+    o, lse, ohp = aq.attnqat_fwd_mx(q, k, v, w.causal)
+    torch.cuda.synchronize()
+    rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, scale_mode=MX, rows=flat)
+    eO = rel_l2(host(pick(o)), rf["O"]); eOp = rel_l2(host(pick(ohp)), rf["Op"]); eL = max_abs(host(pick(lse)), rf["L"])
+    print(f"[{w.name}] MX train O rel-L2 {eO:.2e}  O' rel-L2 {eOp:.2e}  L max-abs {eL:.2e}", flush=True)
+    assert eO <= TOL and eOp <= 2e-4 and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
+    print(f"[{w.name}] GPU MX backward (dense dO)", flush=True)
+    dq, dk, dv = aq.attnqat_bwd_mx(q, k, v, do, lse, ohp, w.causal)
+    torch.cuda.synchronize()
+    rdq = oracle.bwd_dq_rows(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal, scale_mode=MX)
+    eQ = rel_l2(host(pick(dq)), rdq)
+    print(f"[{w.name}] MX dQ rel-L2 {eQ:.2e}", flush=True)
+    assert eQ <= TOL
+    del dq, dk, dv
+    dos = torch.zeros_like(do)
+    for bb, hh, rr in gi:
+        dos[bb, hh, rr] = do[bb, hh, rr]
+    print(f"[{w.name}] GPU MX backward (sparse dO)", flush=True)
+    _, dk, dv = aq.attnqat_bwd_mx(q, k, v, dos, lse, ohp, w.causal)
+    torch.cuda.synchronize()
+    rdk, rdv = oracle.bwd_rows_dkdv(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal, scale_mode=MX)
+    gk = host(dk[b, kv]); gv = host(dv[b, kv])
+    eK, eV = rel_l2(gk, rdk[0]), rel_l2(gv, rdv[0], zero_rms=1e-6)
+    print(f"[{w.name}] MX dK rel-L2 {eK:.2e}  dV rel-L2 {eV:.2e} (oracle dV non-zero fraction {float((rdv[0] != 0).mean()):.3f})", flush=True)
+    assert eK <= TOL and eV <= TOL
+    other = [hk for hk in range(w.Hkv) if hk not in kv]
+    if other:
+        assert not dk[:, other].any() and not dv[:, other].any()
