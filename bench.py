@@ -26,6 +26,9 @@ MFMA_FP4_PEAK_TFLOPS = 10100.0     # MI355X dense FP4 MFMA (the MX variant's pro
 KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
 # Bytes beyond L2 per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
 # measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
+# Sec. 4.4: peak forward throughput on B200 (NVFP4 QK + FP8 PV) at b=1, s=32768, h=32, d=128.  Another machine and
+# another recipe: context for the forward on that shape, not a target.
+PAPER_FWD_TFLOPS = {"paper_peak_fwd_shape": 2026.0}
 MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 35.5e9, "bwd_dq": 205.2e9, "bwd_dkdv": 737.4e9},
                           "dit480p_infer": {"fwd_infer_mx": 1.116e9}}       # profiles/dit480p_infer_mx_fwd_kernels.txt
 
@@ -36,7 +39,8 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="dit720p_train",
-                    help="one of: tiny_ref dit480p_infer llm4k_gqa dit720p_train llm32k_gqa")
+                    help="one of: tiny_ref dit480p_infer llm4k_gqa dit720p_train llm32k_gqa; or paper_peak_fwd_shape "
+                         "(context only: the shape of the paper's peak forward figure)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     ap.add_argument("--ablation", type=int, default=0,
                     help="backward ablation bit set of Sec. 4.2 (1: D from the bf16 O, 2: dV from the un-quantized P); "
@@ -164,7 +168,7 @@ def main():
         "metric": "FP4-attention fwd+bwd TFLOPS (1 MI355X)" if train else "FP4-attention fwd TFLOPS (1 MI355X)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None,
+        "vs_baseline": round(value / PAPER_FWD_TFLOPS[w.name], 4) if (w.name in PAPER_FWD_TFLOPS and not train) else None,
         "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if (mx and not train)
                  else "f16/bf16 MFMA operands (exact %s values), fp32 accumulate and softmax" % ("MXFP4" if mx else "NVFP4"),
         "data": "synthetic",

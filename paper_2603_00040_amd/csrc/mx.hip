@@ -1,4 +1,5 @@
 // MX variant of the quantizer and of the inference forward (Alg. 1) on the scaled FP4 MFMA of gfx950.
+// (The MX training forward and backward are variants of the 16-bit kernels in fwd.hip and bwd.hip.)
 //
 // Format (the OCP microscaling FP4 that Sec. 3.1 names beside NVFP4): E2M1 elements in blocks of 32
 // with one power-of-two E8M0 scale, the smallest 2^e (e >= -126) with 6 * 2^e >= max|X|: the
