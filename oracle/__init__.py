@@ -58,6 +58,12 @@ def _load():
     L.oracle_e8m0_from_amax.argtypes = [_d]
     L.oracle_phi_mx.restype = _i
     L.oracle_phi_mx.argtypes = [_vp, _l, _l, _vp, _vp, _vp]
+    L.oracle_e8m0_from_amax_fp8.restype = _i
+    L.oracle_e8m0_from_amax_fp8.argtypes = [_d]
+    L.oracle_e4m3_round.restype = _i
+    L.oracle_e4m3_round.argtypes = [_d, _d]
+    L.oracle_phi_mx8.restype = _i
+    L.oracle_phi_mx8.argtypes = [_vp, _l, _l, _vp, _vp, _vp]
     L.oracle_bwd.restype = _i
     L.oracle_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
                              _vp, _vp, _vp]
@@ -164,6 +170,38 @@ def fake_quant_mx(x, axis: int = -1):
     return np.ascontiguousarray(np.moveaxis(phi_mx(xt)[2], -1, axis))
 
 
+def e8m0_from_amax_fp8(amax: float) -> int:
+    """E8M0 byte of the smallest power of two s >= 2^-126 with 448 s >= amax."""
+    return _load().oracle_e8m0_from_amax_fp8(float(amax))
+
+
+def e4m3_round(ax: float, s: float) -> int:
+    """E4M3 byte of RNE_E4M3(ax/s), ax >= 0, saturating at 448."""
+    return _load().oracle_e4m3_round(float(ax), float(s))
+
+
+def phi_mx8(x):
+    """MXFP8 phi and phi^-1 (E4M3 elements, blocks of 32 along the last axis, E8M0 scale).
+    Returns (E4M3 bytes uint8 [..., nb*32], E8M0 scale bytes uint8 [..., nb], dequantized float32 [..., n])."""
+    x = _f32(x)
+    n = x.shape[-1]
+    nb = (n + 31) // 32
+    rows = x.size // n
+    codes = np.empty(x.shape[:-1] + (nb * 32,), np.uint8)
+    scales = np.empty(x.shape[:-1] + (nb,), np.uint8)
+    xf = np.empty_like(x)
+    rc = _load().oracle_phi_mx8(_p(x), rows, n, _p(codes), _p(scales), _p(xf))
+    if rc:
+        raise ValueError(f"oracle_phi_mx8 failed ({rc})")
+    return codes, scales, xf
+
+
+def fake_quant_mx8(x, axis: int = -1):
+    """MXFP8 phi^-1(phi(x)) with the blocks of 32 running along `axis`."""
+    xt = np.ascontiguousarray(np.moveaxis(_f32(x), axis, -1))
+    return np.ascontiguousarray(np.moveaxis(phi_mx8(xt)[2], -1, axis))
+
+
 def fwd_mx(q, k, v, causal: bool, Bk: int, quant_p: bool = True, rows=None, dump_p: bool = False):
     """Alg. 1 / Alg. 2 in the MX format: Q^F, K^F blocked along d, V^F and P-tilde^F along the keys.
     Same outputs as fwd()."""
@@ -173,12 +211,15 @@ def fwd_mx(q, k, v, causal: bool, Bk: int, quant_p: bool = True, rows=None, dump
 # ---------------------------------------------------------------- attention
 
 MX = 2      # scale_mode of the MX format: E2M1 blocks of 32 with E8M0 scales, V and P blocked along the keys
+MX_FP8PV = 3    # mixed recipe: Q, K as in MX (FP4), V and P in MXFP8 (E4M3 elements, same blocks and scale format)
 
 
 def _prep_qkv(q, k, v, quant_qkv, scale_mode):
     q, k, v = _f32(q), _f32(k), _f32(v)
     if quant_qkv and scale_mode == MX:
         q, k, v = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx(v, axis=-2)
+    elif quant_qkv and scale_mode == MX_FP8PV:
+        q, k, v = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx8(v, axis=-2)
     elif quant_qkv:    # Alg. 2 first line: Q^F, K^F, V^F
         q, k, v = fake_quant(q, scale_mode), fake_quant(k, scale_mode), fake_quant(v, scale_mode)
     return q, k, v

@@ -189,6 +189,67 @@ int oracle_phi_mx(const float* x, long nrows, long n, uint8_t* packed, uint8_t* 
     return 0;
 }
 
+/* MXFP8 (E4M3 elements, 32 per block, E8M0 scale): the element format of the mixed recipe that keeps
+ * FP4 for Q K^T and uses FP8 for P V (Sec. 3.4; scale_mode 3).  Same scale rule with E4M3's largest
+ * value in place of 6: the smallest power of two s >= 2^-126 with 448 s >= max|X|. */
+int oracle_e8m0_from_amax_fp8(double amax)
+{
+    int e = -126;
+    while (e < 127 && ldexp(448.0, e) < amax) ++e;
+    return e + 127;
+}
+
+/* Byte (sign clear) of RNE_E4M3(ax / s), ax >= 0, s a power of two, saturating at 448 (0x7E).
+ * Decided on ax against midpoint * s, exact in fp64. */
+int oracle_e4m3_round(double ax, double s)
+{
+    int lo = 0, hi = 0x7E;                      /* largest i with value(i) * s <= ax */
+    while (lo < hi) {
+        int mid = (lo + hi + 1) / 2;
+        if (oracle_e4m3_value(mid) * s <= ax) lo = mid; else hi = mid - 1;
+    }
+    if (lo == 0x7E) return lo;
+    double m = 0.5 * (oracle_e4m3_value(lo) + oracle_e4m3_value(lo + 1)) * s;
+    if (ax > m || (ax == m && (lo & 1))) return lo + 1;
+    return lo;
+}
+
+static void phi_mx8_block(const double* x, int n, uint8_t* code, uint8_t* scale_byte, double* xf)
+{
+    double amax = 0.0;
+    for (int i = 0; i < n; ++i) { double a = fabs(x[i]); if (a > amax) amax = a; }
+    int sb = oracle_e8m0_from_amax_fp8(amax);
+    double s = ldexp(1.0, sb - 127);
+    for (int i = 0; i < n; ++i) {
+        int sign = signbit(x[i]) ? 0x80 : 0;
+        int mag = oracle_e4m3_round(fabs(x[i]), s);
+        if (code) code[i] = (uint8_t)(sign | mag);
+        if (xf) xf[i] = (sign ? -1.0 : 1.0) * s * oracle_e4m3_value(mag);
+    }
+    if (scale_byte) *scale_byte = (uint8_t)sb;
+}
+
+/* MXFP8 phi over the last axis of x[nrows, n] in blocks of 32 (a short last block is zero padded).
+ * With nb = ceil(n/32): codes[nrows, nb*32] E4M3 bytes, scales[nrows, nb] E8M0 bytes, xf[nrows, n]. */
+int oracle_phi_mx8(const float* x, long nrows, long n, uint8_t* codes, uint8_t* scales, float* xf)
+{
+    if (!x || n < 1) return -1;
+    const long nb = (n + 31) / 32;
+    #pragma omp parallel for schedule(static)
+    for (long r = 0; r < nrows; ++r) {
+        for (long b = 0; b < nb; ++b) {
+            double xb[32], xfb[32]; uint8_t code[32], sb;
+            const int m = (int)((n - b * 32 < 32) ? n - b * 32 : 32);
+            for (int i = 0; i < 32; ++i) { xb[i] = i < m ? (double)x[r * n + b * 32 + i] : 0.0; }
+            phi_mx8_block(xb, 32, code, &sb, xfb);
+            if (codes) for (int i = 0; i < 32; ++i) codes[(r * nb + b) * 32 + i] = code[i];
+            if (scales) scales[r * nb + b] = sb;
+            if (xf) for (int i = 0; i < m; ++i) xf[r * n + b * 32 + i] = (float)xfb[i];
+        }
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------ forward */
 
 static double dot(const float* a, const float* b, int d)
@@ -258,7 +319,8 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                 for (int k = nk; k < Bk; ++k) Pt[k] = 0.0;      /* masked keys */
                 if (quant_p) {
                     for (int k = 0; k < nk; k += pb) {
-                        if (mx) phi_mx_block(Pt + k, pb, NULL, NULL, Pf + k);
+                        if (mx == 2) phi_mx8_block(Pt + k, pb, NULL, NULL, Pf + k);
+                        else if (mx) phi_mx_block(Pt + k, pb, NULL, NULL, Pf + k);
                         else    phi_block(Pt + k, pb, scale_mode, NULL, NULL, NULL, Pf + k);
                     }
                 } else {
@@ -289,22 +351,24 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
 }
 
 /* scale_mode 2: the MX format (qf, kf, vf are then the MX fake-quantized tensors, V blocked along
- * the keys, and P-tilde is quantized in MX blocks of 32 keys). */
+ * the keys, and P-tilde is quantized in MX blocks of 32 keys).  scale_mode 3: the same with MXFP8
+ * (E4M3 elements) for P-tilde (and, in the caller's vf, for V). */
 int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
                     int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
                     int quant_p, int scale_mode,
                     long nrows, const long* rows,
                     double* O, double* Op, double* Lse, float* Pdump)
 {
-    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode, scale_mode == 2,
+    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode,
+                         scale_mode == 2 ? 1 : scale_mode == 3 ? 2 : 0,
                          nrows, rows, O, Op, Lse, Pdump);
 }
 
 /* ----------------------------------------------------------------- backward */
 
-/* Keys per P block: 16 (NVFP4), 32 in the MX format (scale_mode 2). */
+/* Keys per P block: 16 (NVFP4), 32 in the MX formats (scale_mode 2 and 3). */
 #define PB_MAX 32
-static int pb_of(int scale_mode) { return scale_mode == 2 ? 32 : 16; }
+static int pb_of(int scale_mode) { return scale_mode >= 2 ? 32 : 16; }
 
 /*
  * One query row against one aligned block of pb keys [k0, k0+pb): the inner
@@ -322,7 +386,8 @@ static void bwd_block(const float* qrow, const float* dorow, double lse, double 
             P[k] = (double)(float)exp(s - lse);
         } else P[k] = 0.0;
     }
-    if (quant_p && scale_mode == 2) phi_mx_block(P, pb, NULL, NULL, Pf);
+    if (quant_p && scale_mode == 3) phi_mx8_block(P, pb, NULL, NULL, Pf);
+    else if (quant_p && scale_mode == 2) phi_mx_block(P, pb, NULL, NULL, Pf);
     else if (quant_p) phi_block(P, pb, scale_mode, NULL, NULL, NULL, Pf);
     else for (int k = 0; k < pb; ++k) Pf[k] = P[k];
     for (int k = 0; k < pb; ++k) {

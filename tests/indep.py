@@ -151,6 +151,27 @@ def fake_quant_mx_np(x, axis=-1):
     return np.moveaxis(out, -1, axis)
 
 
+def fake_quant_mx8_np(x, axis=-1):
+    """MXFP8 phi^-1(phi(x)) in float64 along ``axis`` (E4M3 elements, aligned blocks of 32, zero padded).
+    Scale: with amax = m 2^x, m in [0.5, 1) (frexp) and 448 = 0.875 * 2^9, 448 * 2^e >= amax first holds at
+    e = x - 9 for m <= 0.875 and at e = x - 8 above.  Elements: torch's own float32 -> float8_e4m3fn cast
+    (round to nearest even) of the exactly scaled values, which never exceed 448."""
+    x = np.moveaxis(np.asarray(x, dtype=np.float64), axis, -1)
+    n = x.shape[-1]
+    pad = (-n) % 32
+    xp = np.concatenate([x, np.zeros(x.shape[:-1] + (pad,))], axis=-1) if pad else x
+    blk = xp.reshape(xp.shape[:-1] + (-1, 32))
+    amax = np.abs(blk).max(axis=-1)
+    m, ex = np.frexp(amax)
+    e = np.where(amax > 0, ex - 9 + (m > 0.875), -126)
+    e = np.maximum(e, -126)
+    s = np.ldexp(1.0, e)[..., None]
+    r = (blk / s).astype(np.float32)                       # exact: power-of-two scaling of fp32 inputs, |r| <= 448
+    q = torch.from_numpy(np.ascontiguousarray(r)).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    out = (q * s).reshape(xp.shape)[..., :n]
+    return np.moveaxis(out, -1, axis)
+
+
 def attn_fwd_rowwise_np(qf, kf, vf, causal, Bk, quant_p=True, fq=None):
     """Alg. 2, one query row at a time, numpy float64; inputs already fake-quantized.
     qf [L,d], kf/vf [L,d] (one head).  fq: the fake-quantizer of P-tilde (default: NVFP4).

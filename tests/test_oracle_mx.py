@@ -272,3 +272,73 @@ def test_mx_sampled_backward_entry_points_match_full(causal):
     gs = oracle.bwd(q, k, v, sparse.reshape(do.shape), f["L"], f["Op"], causal, scale_mode=oracle.MX)
     dk2, dv2 = oracle.bwd_rows_dkdv(q, k, v, do, rows, fr["L"], fr["Op"], causal, scale_mode=oracle.MX)
     assert np.allclose(dk2, gs["dK"], rtol=0, atol=1e-12) and np.allclose(dv2, gs["dV"], rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- mixed recipe: FP4 Q K^T, MXFP8 (E4M3) P and V
+
+def test_fp8_scale_rule_hand_cases():
+    # 448 * 2^e >= amax first holds at: 448 -> 0; just above -> 1; 1 -> -8 (1.75 >= 1 > 0.875); 0.875 -> -9; 0 -> floor
+    for amax, e in [(448.0, 0), (np.nextafter(448.0, 500.0), 1), (1.0, -8), (0.875, -9), (np.nextafter(0.875, 1.0), -8),
+                    (0.0, -126), (3e38, 120)]:
+        assert oracle.e8m0_from_amax_fp8(amax) == e + 127, (amax, e)
+
+
+def test_e4m3_rounding_matches_torch_cast_including_ties():
+    import torch
+    rng = np.random.default_rng(40)
+    grid = np.array([oracle.e4m3_value(b) for b in range(0x7F)])
+    mids = 0.5 * (grid[:-1] + grid[1:])
+    near = np.concatenate([np.nextafter(mids.astype(np.float32), np.float32(0)), mids.astype(np.float32),
+                           np.nextafter(mids.astype(np.float32), np.float32(500))])
+    vals = np.concatenate([grid, near, rng.uniform(0, 448, 4000), rng.uniform(0, 0.05, 2000)]).astype(np.float32)
+    want = torch.from_numpy(vals).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    for sexp in (0, -7, 5):
+        s = 2.0 ** sexp
+        got = np.array([oracle.e4m3_round(float(v) * s, s) for v in vals])
+        assert np.array_equal(got, want)
+    assert oracle.e4m3_round(1000.0, 1.0) == 0x7E           # saturates at 448
+
+
+def test_phi_mx8_numpy_twin_invariants_and_bytes():
+    rng = np.random.default_rng(41)
+    x = _bf16(rng.standard_normal((3, 70, 96)) * np.exp(rng.standard_normal((3, 70, 1))))
+    assert np.array_equal(oracle.fake_quant_mx8(x).astype(np.float64), indep.fake_quant_mx8_np(x))
+    assert np.array_equal(oracle.fake_quant_mx8(x, axis=-2).astype(np.float64), indep.fake_quant_mx8_np(x, axis=-2))
+    codes, sb, xf = oracle.phi_mx8(x)
+    s = np.ldexp(1.0, sb.astype(np.int64) - 127)
+    blk = x.reshape(3, 70, 3, 32).astype(np.float64); q = xf.reshape(3, 70, 3, 32).astype(np.float64)
+    # no saturation: the block maximum is in (224, 448] scale units and lands on 224 .. 448; normal elements are within 2^-4 relative
+    top = np.abs(q).max(-1) / s
+    assert (top >= 224).all() and (top <= 448).all()
+    normal = np.abs(blk) >= s[..., None] * 2.0 ** -6
+    assert (np.abs(blk - q)[normal] <= np.abs(blk)[normal] * 2.0 ** -4).all()
+    # the bytes decode to the dequantized values
+    dec = np.array([oracle.e4m3_value(b) for b in range(0x7F)])
+    cb = codes.reshape(3, 70, 3, 32)
+    val = np.where(cb & 0x80, -1.0, 1.0) * dec[cb & 0x7F] * s[..., None]
+    assert np.array_equal(val, q)
+    # exact homogeneity under powers of two, idempotence
+    c2, sb2, xf2 = oracle.phi_mx8(x * 2.0 ** -5)
+    assert np.array_equal(c2, codes) and np.array_equal(sb2.astype(int), sb.astype(int) - 5)
+    assert np.array_equal(oracle.phi_mx8(xf)[2], xf)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_fp8pv_forward_matches_textbook_and_rowwise_transcription(causal):
+    q, k, v = _rand(1, 2, 1, 200, 32, seed=42, outlier=True)
+    qf = indep.fake_quant_mx_np(q); kf = indep.fake_quant_mx_np(k); vf = indep.fake_quant_mx8_np(v, axis=-2)
+    r0 = oracle.fwd(q, k, v, causal, 64, quant_p=False, scale_mode=oracle.MX_FP8PV)
+    O, L = _textbook(qf, np.repeat(kf, 2, 1), np.repeat(vf, 2, 1), causal)
+    assert np.allclose(r0["O"], O, rtol=0, atol=1e-6) and np.allclose(r0["L"], L, rtol=0, atol=1e-6)
+    r = oracle.fwd(q, k, v, causal, 64, scale_mode=oracle.MX_FP8PV)
+    for h in range(2):
+        O, Op, L = indep.attn_fwd_rowwise_np(qf[0, h], kf[0, 0], vf[0, 0], causal, 64, fq=indep.fake_quant_mx8_np)
+        assert np.allclose(r["O"][0, h], O, rtol=0, atol=1e-12)
+        assert np.allclose(r["Op"][0, h], Op, rtol=0, atol=1e-12)
+        assert np.allclose(r["L"][0, h], L, rtol=0, atol=1e-12)
+    # FP8 for P and V is closer to the un-quantized-P output than FP4 is
+    r4 = oracle.fwd(q, k, v, causal, 64, scale_mode=oracle.MX)
+    e8 = np.linalg.norm(r["O"] - r0["O"]) / np.linalg.norm(r0["O"])
+    r40 = oracle.fwd(q, k, v, causal, 64, quant_p=False, scale_mode=oracle.MX)
+    e4 = np.linalg.norm(r4["O"] - r40["O"]) / np.linalg.norm(r40["O"])
+    assert e8 < 0.5 * e4
