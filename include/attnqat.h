@@ -53,6 +53,7 @@ extern "C" {
 #define ATTNQAT_WS_FWD_INFER_MX     3   /* attnqat_fwd_infer_mx                        */
 #define ATTNQAT_WS_FWD_MX           4   /* attnqat_fwd_mx, attnqat_debug_fwd_p_mx      */
 #define ATTNQAT_WS_BWD_MX           5   /* attnqat_bwd_mx                              */
+#define ATTNQAT_WS_FWD_INFER_MX_FP8PV 6 /* attnqat_fwd_infer_mx_fp8pv                  */
 
 /*
  * phi of Eq. 1 (Sec. 3.1) along d: for every 16 consecutive elements
@@ -174,6 +175,24 @@ int attnqat_fwd_infer_mx(const void* q, const void* k, const void* v,
                          int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                          void* o, float* lse,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Mixed recipe of Sec. 3.4 (FP4 for Q K^T, FP8 for P V) in MX terms: Q^F, K^F as in attnqat_fwd_infer_mx;
+ * V^F and P-tilde^F in MXFP8: E4M3 elements (OCP: bias 7, subnormals, largest value 448), the same blocks
+ * of 32 keys and E8M0 scales, scale = the smallest 2^e, e >= -126, with 448 * 2^e >= max|x| (nothing
+ * saturates), element = sign | RNE_E4M3(|x| / scale).  P.V runs on the same scaled matrix instruction with
+ * FP8 operands, at half the FP4 rate.  Arguments as attnqat_fwd_infer; workspace ATTNQAT_WS_FWD_INFER_MX_FP8PV.
+ *
+ * attnqat_quantize_mxfp8: that quantizer for a whole tensor, blocks along the sequence only (axis must be 1):
+ *   codes [B,H,d,Lc] E4M3 bytes (Lc = L rounded up to 32, zero padded), scales [B,H,d,Lc/32] E8M0 bytes,
+ *   xf optional [B,H,L,d] bf16 (values with more than 8 significant bits are rounded to bf16).
+ */
+int attnqat_quantize_mxfp8(const void* x, int B, int H, int L, int d, int dtype, int axis,
+                           uint8_t* codes, uint8_t* scales, void* xf, void* stream);
+int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
+                               int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                               void* o, float* lse,
+                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Training forward (Alg. 2) and backward (Alg. 3) in the MX format, for training against

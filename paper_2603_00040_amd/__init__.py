@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libattnqat.so")
 
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4, -5
 BF16 = 0
-WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX, WS_FWD_MX, WS_BWD_MX = 0, 1, 2, 3, 4, 5
+WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX, WS_FWD_MX, WS_BWD_MX, WS_FWD_INFER_MX_FP8PV = 0, 1, 2, 3, 4, 5, 6
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _SIGNATURES = {
@@ -30,6 +30,8 @@ _SIGNATURES = {
                                   _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_quantize_mx": (_i, [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "attnqat_fwd_infer_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_quantize_mxfp8": (_i, [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "attnqat_fwd_infer_mx_fp8pv": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                             _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -176,7 +178,25 @@ def attnqat_quantize_mx(x, axis: int = 0, want_codes=True, want_xf=True):
     return codes, scales, xf
 
 
-def attnqat_fwd_infer_mx(q, k, v, causal: bool, workspace=None, out=None):
+def attnqat_quantize_mxfp8(x, want_codes=True, want_xf=True):
+    """MXFP8 phi (E4M3 elements, blocks of 32 along the sequence, E8M0 scale): how V is held in the mixed recipe.
+    Returns (codes u8 [B,H,d,Lc], scales u8 [B,H,d,Lc/32], xf bf16) with Lc = L rounded up to 32."""
+    _dev_bf16(x, "x")
+    B, H, L, d = x.shape
+    Lc = (L + 31) // 32 * 32
+    codes = torch.empty((B, H, d, Lc), dtype=torch.uint8, device=x.device) if want_codes else None
+    scales = torch.empty((B, H, d, Lc // 32), dtype=torch.uint8, device=x.device) if want_codes else None
+    xf = torch.empty_like(x) if want_xf else None
+    _check(lib().attnqat_quantize_mxfp8(_ptr(x), B, H, L, d, BF16, 1, _ptr(codes), _ptr(scales), _ptr(xf), _stream()))
+    return codes, scales, xf
+
+
+def attnqat_fwd_infer_mx_fp8pv(q, k, v, causal: bool, workspace=None, out=None):
+    """Alg. 1, mixed recipe: FP4 (MX) Q K^T, MXFP8 P V.  Returns (o bf16, lse fp32)."""
+    return attnqat_fwd_infer_mx(q, k, v, causal, workspace, out, _fp8pv=True)
+
+
+def attnqat_fwd_infer_mx(q, k, v, causal: bool, workspace=None, out=None, _fp8pv=False):
     """Alg. 1 in the MX format on the scaled FP4 MFMA.  Returns (o bf16, lse fp32)."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _dev_bf16(t, n)
@@ -187,8 +207,8 @@ def attnqat_fwd_infer_mx(q, k, v, causal: bool, workspace=None, out=None):
         lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
     else:
         o, lse = out
-    ws, nb = _workspace(WS_FWD_INFER_MX, B, Hq, Hkv, L, d, workspace)
-    _check(lib().attnqat_fwd_infer_mx(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+    ws, nb = _workspace(WS_FWD_INFER_MX_FP8PV if _fp8pv else WS_FWD_INFER_MX, B, Hq, Hkv, L, d, workspace)
+    _check((lib().attnqat_fwd_infer_mx_fp8pv if _fp8pv else lib().attnqat_fwd_infer_mx)(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                       _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
     return o, lse
 

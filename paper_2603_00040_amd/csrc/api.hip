@@ -87,13 +87,13 @@ BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 
 // Workspace of the MX forward: Q operand codes and scale dwords, and the 64-key kv records.
 struct MxWs { unsigned char *qops, *qsc, *kv; size_t bytes; };
-MxWs carve_mx(void* ws, int B, int Hq, int Hkv, int L, int d)
+MxWs carve_mx(void* ws, int B, int Hq, int Hkv, int L, int d, bool fp8v = false)
 {
     Carver c{(unsigned char*)ws, 0};
     MxWs w;
     w.qops = (unsigned char*)c.take(mx_qops_bytes(B * Hq, L, d));
     w.qsc = (unsigned char*)c.take(mx_qsc_bytes(B * Hq, L));
-    w.kv = (unsigned char*)c.take(mx_kv_bytes(B * Hkv, L, d));
+    w.kv = (unsigned char*)c.take(mx_kv_bytes(B * Hkv, L, d, fp8v));
     w.bytes = c.off;
     return w;
 }
@@ -104,7 +104,7 @@ MxWs carve_mx(void* ws, int B, int Hq, int Hkv, int L, int d)
 int quant_copy(const void* x, int BH, int L, int d, bool mx, int mx_axis, bool out_f16, void* xr, void* xt, void* tmp, hipStream_t st)
 {
     if (!mx) return launch_prep(x, BH, L, d, true, out_f16, nullptr, nullptr, nullptr, xr, xt, st);
-    if (launch_mx_quant(x, BH, L, d, mx_axis, 0, nullptr, nullptr, tmp, st)) return -1;
+    if (launch_mx_quant(x, BH, L, d, mx_axis, 0, false, nullptr, nullptr, tmp, st)) return -1;
     return launch_prep(tmp, BH, L, d, false, out_f16, nullptr, nullptr, nullptr, xr, xt, st);
 }
 
@@ -157,6 +157,7 @@ size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d)
     case ATTNQAT_WS_FWD_INFER: return carve_fwd(nullptr, B, Hq, Hkv, L, d).bytes;
     case ATTNQAT_WS_BWD:       return carve_bwd(nullptr, B, Hq, Hkv, L, d).bytes;
     case ATTNQAT_WS_FWD_INFER_MX: return carve_mx(nullptr, B, Hq, Hkv, L, d).bytes;
+    case ATTNQAT_WS_FWD_INFER_MX_FP8PV: return carve_mx(nullptr, B, Hq, Hkv, L, d, true).bytes;
     case ATTNQAT_WS_FWD_MX:    return carve_fwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
     case ATTNQAT_WS_BWD_MX:    return carve_bwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
     default:                   return 0;
@@ -176,15 +177,48 @@ int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
     return ATTNQAT_OK;
 }
 
-int attnqat_quantize_mx(const void* x, int B, int H, int L, int d, int dtype, int axis,
-                        uint8_t* codes, uint8_t* scales, void* xf, void* stream)
+static int quantize_mx_common(const void* x, int B, int H, int L, int d, int dtype, int axis, bool fp8,
+                              uint8_t* codes, uint8_t* scales, void* xf, void* stream)
 {
-    if (!x || (!codes && !scales && !xf) || (axis != 0 && axis != 1)) return ATTNQAT_EINVAL;
+    if (!x || (!codes && !scales && !xf) || (axis != 0 && axis != 1) || (fp8 && axis != 1)) return ATTNQAT_EINVAL;
     int rc = check_dims(B, H, H, L, d, dtype);
     if (rc) return rc;
     prof_begin((hipStream_t)stream);
-    if (launch_mx_quant(x, B * H, L, d, axis, 0, codes, scales, xf, (hipStream_t)stream)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(x, B * H, L, d, axis, 0, fp8, codes, scales, xf, (hipStream_t)stream)) return ATTNQAT_ELAUNCH;
     prof_mark("quantize_mx", (hipStream_t)stream);
+    return ATTNQAT_OK;
+}
+
+int attnqat_quantize_mx(const void* x, int B, int H, int L, int d, int dtype, int axis,
+                        uint8_t* codes, uint8_t* scales, void* xf, void* stream)
+{
+    return quantize_mx_common(x, B, H, L, d, dtype, axis, false, codes, scales, xf, stream);
+}
+
+int attnqat_quantize_mxfp8(const void* x, int B, int H, int L, int d, int dtype, int axis,
+                           uint8_t* codes, uint8_t* scales, void* xf, void* stream)
+{
+    return quantize_mx_common(x, B, H, L, d, dtype, axis, true, codes, scales, xf, stream);
+}
+
+static int fwd_infer_mx_common(const void* q, const void* k, const void* v,
+                               int B, int Hq, int Hkv, int L, int d, int causal, int dtype, bool fp8pv,
+                               void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    MxWs w = carve_mx(workspace, B, Hq, Hkv, L, d, fp8pv);
+    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    // Alg. 1 first line, in the MX format: phi(Q), phi(K) along d, phi(V) along the keys (E4M3 elements in the mixed recipe)
+    if (launch_mx_quant(q, B * Hq, L, d, 0, 1, false, w.qops, w.qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(k, B * Hkv, L, d, 0, 2, fp8pv, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(v, B * Hkv, L, d, 1, 2, fp8pv, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_qkv_mx", st);
+    if (launch_fwd_mx(w.qops, w.qsc, w.kv, B, Hq, Hkv, L, d, causal != 0, fp8pv, o, lse, st)) return ATTNQAT_ELAUNCH;
+    prof_mark(fp8pv ? "fwd_infer_mx_fp8pv" : "fwd_infer_mx", st);
     return ATTNQAT_OK;
 }
 
@@ -193,21 +227,15 @@ int attnqat_fwd_infer_mx(const void* q, const void* k, const void* v,
                          void* o, float* lse,
                          void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!q || !k || !v || !o || !lse) return ATTNQAT_EINVAL;
-    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
-    if (rc) return rc;
-    MxWs w = carve_mx(workspace, B, Hq, Hkv, L, d);
-    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    prof_begin(st);
-    // Alg. 1 first line, in the MX format: phi(Q), phi(K) along d, phi(V) along the keys
-    if (launch_mx_quant(q, B * Hq, L, d, 0, 1, w.qops, w.qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_mx_quant(k, B * Hkv, L, d, 0, 2, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_mx_quant(v, B * Hkv, L, d, 1, 2, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
-    prof_mark("prep_qkv_mx", st);
-    if (launch_fwd_mx(w.qops, w.qsc, w.kv, B, Hq, Hkv, L, d, causal != 0, o, lse, st)) return ATTNQAT_ELAUNCH;
-    prof_mark("fwd_infer_mx", st);
-    return ATTNQAT_OK;
+    return fwd_infer_mx_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, o, lse, workspace, workspace_bytes, stream);
+}
+
+int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
+                               int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                               void* o, float* lse,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_infer_mx_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, true, o, lse, workspace, workspace_bytes, stream);
 }
 
 static unsigned long long* g_dkdv_counts = nullptr;

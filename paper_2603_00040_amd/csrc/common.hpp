@@ -82,6 +82,11 @@ __device__ inline uint32_t e8m0_of_amax(float amax) {
     const uint32_t b = (__float_as_uint(amax) + 0x003FFFFFu) >> 23;      // biased exponent, +1 if mantissa > 1.5
     return b > 3u ? b - 2u : 1u;
 }
+// The same for E4M3 elements: the smallest power of two s >= 2^-126 with 448 s >= amax (448 = 1.75 * 2^8).
+__device__ inline uint32_t e8m0_of_amax_fp8(float amax) {
+    const uint32_t b = (__float_as_uint(amax) + 0x001FFFFFu) >> 23;      // biased exponent, +1 if mantissa > 1.75
+    return b > 9u ? b - 8u : 1u;
+}
 __device__ inline float e8m0_as_f32(uint32_t byte) { return __uint_as_float(byte << 23); }            // 1 <= byte <= 254
 __device__ inline float e8m0_inverse_as_f32(uint32_t byte) { return __uint_as_float((254u - byte) << 23); }   // 1 <= byte <= 253
 

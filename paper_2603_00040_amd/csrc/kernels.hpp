@@ -47,13 +47,14 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
 //   mode 0: public layout (codes, scales, optional bf16 xf, see attnqat.h)
 //   mode 1: Q operands of the scaled MFMA (axis 0 only): codes -> operand array, scales -> scale dwords
 //   mode 2: the K part (axis 0) or the V part (axis 1) of the 64-key kv records at `codes`
-int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode,
+// fp8: E4M3 elements instead of E2M1 (axis 1 only); with axis 0 and mode 2 it selects the record layout whose V part is FP8.
+int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
                     unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st);
-size_t mx_kv_bytes(int BHkv, int L, int D);
+size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v);
 size_t mx_qops_bytes(int BHq, int L, int D);
 size_t mx_qsc_bytes(int BHq, int L);
-// Alg. 1 on the arrays made by launch_mx_quant (modes 1 and 2).
-int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
+// Alg. 1 on the arrays made by launch_mx_quant (modes 1 and 2).  fp8pv: P-tilde and V in MXFP8 (mixed recipe).
+int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal, bool fp8pv,
                   void* o, float* lse, hipStream_t st);
 
 }  // namespace aq

@@ -16,6 +16,12 @@
 //   S^T[key, query]  = K codes (A, from LDS) x Q codes (B, registers), contraction over d
 //   O^T[d, query]   += V^T codes (A, from LDS) x P-tilde codes (B, registers), contraction over keys
 //
+// Mixed recipe (Sec. 3.4: FP4 for Q K^T, FP8 for P V): the FP8PV variants keep Q and K in MXFP4 and hold V and
+// P-tilde in MXFP8 (E4M3 elements, the same blocks of 32 keys and E8M0 scales; scale = smallest 2^e with
+// 448 * 2^e >= max|X|).  The P.V product then runs the same instruction with FP8 operands, whose layout differs
+// (measured): the 32 bytes of lane l are contraction indices 16 (l/32) .. + 15 and 32 + 16 (l/32) .. + 15, and the
+// scale of indices 32 b .. + 31 comes from lane l % 32 + 32 b.
+//
 // The rows of the two S^T products of a 64-key tile are assigned to keys so that the 32 accumulator
 // registers of a lane are the 32 consecutive keys 32 * (lane / 32) .. + 31 of the tile: one P block,
 // whose maximum, scale and codes never leave the lane, and whose 4 code registers already are the
@@ -49,7 +55,24 @@ __device__ inline float e2m1_value_of(uint32_t code) {
 }
 
 // Bytes of one 64-key record of a kv head: K operands, V^T operands, K scales, V scales.
-__host__ __device__ constexpr int mx_rec_bytes(int D) { return 2 * (D / 64) * 1024 + (D / 32) * 1024 + 512; }
+__host__ __device__ constexpr int mx_rec_bytes(int D, bool fp8v = false) { return 2 * (D / 64) * 1024 + (D / 32) * (fp8v ? 2048 : 1024) + 512; }
+
+// 32 values -> 8 registers of E4M3 bytes (value i in byte i), RNE on v / scale; |v| / scale <= 448 by the scale rule.
+typedef short short2v __attribute__((ext_vector_type(2)));
+__device__ inline void mx_codes32_fp8(const float (&v)[32], float scale, uint32_t (&c)[8]) {
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+        short2v r = {0, 0};
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, v[4 * w + 0], v[4 * w + 1], scale, false);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, v[4 * w + 2], v[4 * w + 3], scale, true);
+        c[w] = __builtin_bit_cast(uint32_t, r);
+    }
+}
+__device__ inline float e4m3_value_of(uint32_t byte) {
+    const uint32_t e = (byte >> 3) & 15u, m = byte & 7u;
+    const float v = e == 0u ? (float)m * 0.001953125f : __uint_as_float((e + 120u) << 23 | m << 20);
+    return (byte & 0x80u) ? -v : v;
+}
 
 // Row of S^T product t (0/1) that holds key kk (0..63) of a tile, and the lane half that ends up owning it:
 // the accumulator register r of a lane in half h is row 8 (r/4) + 4 h + r % 4; key 32 h + 16 t + r goes there.
@@ -60,7 +83,7 @@ __device__ inline int mx_srow_of_key(int kk) { const int w = kk & 15; return 8 *
 //   MODE 0: public layout   codes [rows, D/2], scales [rows, D/32], optional bf16 xf
 //   MODE 1: Q operands      ops [rows/32, D/64, 64 lanes, 16 B], sc [rows/32, 64 lanes] (byte ks)
 //   MODE 2: K part of the kv records
-template <int D, int MODE>
+template <int D, int MODE, bool FP8V = false /* MODE 2: records whose V part is FP8 */>
 __global__ __launch_bounds__(256) void mx_quant_d_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
     uint16_t* __restrict__ xf)
@@ -117,7 +140,7 @@ __global__ __launch_bounds__(256) void mx_quant_d_kernel(
         if (KS == 1) { scales[(grp * 64 + lane) * 4 + 1] = 1; }
         if (ks == 0) { scales[(grp * 64 + lane) * 4 + 2] = 1; scales[(grp * 64 + lane) * 4 + 3] = 1; }
     } else {
-        constexpr int REC = mx_rec_bytes(D), KOPS = 2 * KS * 1024, VOPS = NB * 1024;
+        constexpr int REC = mx_rec_bytes(D, FP8V), KOPS = 2 * KS * 1024, VOPS = NB * (FP8V ? 2048 : 1024);
         const int tile = row >> 6, kk = row & 63, t = (kk >> 4) & 1;
         const int ks = blk >> 1, lane = (blk & 1) * 32 + mx_srow_of_key(kk);
         unsigned char* rec = codes + ((size_t)bh * (Lp / 64) + tile) * REC;
@@ -128,10 +151,11 @@ __global__ __launch_bounds__(256) void mx_quant_d_kernel(
 }
 
 // phi along the sequence axis (blocks of 32 positions, zero padded): how V is blocked.
-// One thread per (block of 32 positions, d index); x [BH, L, D].
-//   MODE 0: public layout  codes [BH, D, Lc/2], scales [BH, D, Lc/32] with Lc = round_up(L, 32); optional bf16 xf [BH, L, D]
-//   MODE 2: V part of the kv records
-template <int D, int MODE>
+// One thread per (block of 32 positions, d index); x [BH, L, D].  FP8: E4M3 elements (one byte each) instead of E2M1.
+//   MODE 0: public layout  codes [BH, D, Lc/2] (FP8: [BH, D, Lc]), scales [BH, D, Lc/32] with Lc = round_up(L, 32);
+//           optional bf16 xf [BH, L, D]
+//   MODE 2: V part of the kv records (FP8: two 1 KiB halves per d-block, bytes 0-15 and 16-31 of every lane)
+template <int D, int MODE, bool FP8>
 __global__ __launch_bounds__(D) void mx_quant_l_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
     uint16_t* __restrict__ xf)
@@ -148,26 +172,50 @@ __global__ __launch_bounds__(D) void mx_quant_l_kernel(
     float amax = 0.0f;
 #pragma unroll
     for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(v[i]));
-    const uint32_t byte = e8m0_of_amax(amax);
+    const uint32_t byte = FP8 ? e8m0_of_amax_fp8(amax) : e8m0_of_amax(amax);
     const float s = e8m0_as_f32(byte);
-    const uint4v c = mx_codes32(v, s);
+    uint32_t c[8];
+    if constexpr (FP8) {
+        mx_codes32_fp8(v, s, c);
+    } else {
+        const uint4v c4 = mx_codes32(v, s);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { c[i] = c4[i]; c[4 + i] = 0u; }
+    }
+    constexpr int NW = FP8 ? 8 : 4;                 // code registers per block
     if (MODE == 0) {
         const int Lc = round_up(L, 32);
-        if (codes) *reinterpret_cast<uint4v*>(codes + ((size_t)bh * D + dd) * (Lc / 2) + kb * 16) = c;
+        if (codes) {
+            uint4v* dst = reinterpret_cast<uint4v*>(codes + (((size_t)bh * D + dd) * (Lc / 32) + kb) * (4 * NW));
+#pragma unroll
+            for (int i = 0; i < NW / 4; ++i) { uint4v o; o[0] = c[4 * i]; o[1] = c[4 * i + 1]; o[2] = c[4 * i + 2]; o[3] = c[4 * i + 3]; dst[i] = o; }
+        }
         if (scales) scales[((size_t)bh * D + dd) * (Lc / 32) + kb] = (unsigned char)byte;
         if (xf) {
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
                 const int l = kb * 32 + i;
-                const uint32_t code = (c[i >> 3] >> (4 * (i & 7))) & 15u;
-                if (l < L) xf[((size_t)bh * L + l) * D + dd] = f32_to_bf16_rne(e2m1_value_of(code) * s);
+                const float val = FP8 ? e4m3_value_of((c[i >> 2] >> (8 * (i & 3))) & 255u) : e2m1_value_of((c[i >> 3] >> (4 * (i & 7))) & 15u);
+                if (l < L) xf[((size_t)bh * L + l) * D + dd] = f32_to_bf16_rne(val * s);
             }
         }
     } else {
-        constexpr int REC = mx_rec_bytes(D), KOPS = 2 * KS * 1024, VOPS = MT * 1024;
+        constexpr int REC = mx_rec_bytes(D, FP8), KOPS = 2 * KS * 1024, VOPS = MT * (FP8 ? 2048 : 1024);
         const int tile = kb >> 1, lane = (kb & 1) * 32 + (dd & 31), mt = dd >> 5;
         unsigned char* rec = codes + ((size_t)bh * (Lp / 64) + tile) * REC;
-        *reinterpret_cast<uint4v*>(rec + KOPS + (mt * 64 + lane) * 16) = c;
+        if constexpr (FP8) {
+            // FP8 operands: registers 0-3 of lane (row, h) are contraction indices 16 h .. + 15, registers 4-7 are
+            // 32 + 16 h .. + 15, and the scale of indices 32 b .. + 31 is taken from lane (row, b): the two halves of
+            // this block of 32 keys go to the two lane halves, in the register group of the block
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                uint4v o; o[0] = c[4 * i]; o[1] = c[4 * i + 1]; o[2] = c[4 * i + 2]; o[3] = c[4 * i + 3];
+                *reinterpret_cast<uint4v*>(rec + KOPS + ((mt * 2 + (kb & 1)) * 64 + i * 32 + (dd & 31)) * 16) = o;
+            }
+        } else {
+            uint4v o; o[0] = c[0]; o[1] = c[1]; o[2] = c[2]; o[3] = c[3];
+            *reinterpret_cast<uint4v*>(rec + KOPS + (mt * 64 + lane) * 16) = o;
+        }
         rec[KOPS + VOPS + 256 + lane * 4 + mt] = (unsigned char)byte;
         if (MT == 2 && mt == 0) { rec[KOPS + VOPS + 256 + lane * 4 + 2] = 1; rec[KOPS + VOPS + 256 + lane * 4 + 3] = 1; }
     }
@@ -179,13 +227,13 @@ __global__ __launch_bounds__(D) void mx_quant_l_kernel(
 // kv records arrive in stages of two tiles, copied global->LDS directly into a ring of three stage
 // buffers; one barrier per stage.  The S^T products of tile j+1 are issued before the softmax of
 // tile j, so the matrix unit works under the wave's own vector instructions.
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool FP8PV>
 __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     const unsigned char* __restrict__ qops, const uint32_t* __restrict__ qsc, const unsigned char* __restrict__ kv,
     uint16_t* __restrict__ O, float* __restrict__ lse, int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */)
 {
     constexpr int KS = D / 64, MT = D / 32;
-    constexpr int KOPS = 2 * KS * 1024, VOPS = MT * 1024, REC = mx_rec_bytes(D), STAGE = 2 * REC, NCH = STAGE / 1024;
+    constexpr int KOPS = 2 * KS * 1024, VOPS = MT * (FP8PV ? 2048 : 1024), REC = mx_rec_bytes(D, FP8PV), STAGE = 2 * REC, NCH = STAGE / 1024;
     static_assert(STAGE % 1024 == 0, "a stage is a whole number of 1 KiB wave copies");
     extern __shared__ __align__(16) unsigned char smem[];          // 3 stage buffers
 
@@ -286,8 +334,24 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
         lsum = lsum * alpha + ((rp[0] + rp[1]) + (rp[2] + rp[3]));                  // un-quantized P-tilde
         // block maximum of P-tilde: exp2 of the block's largest score, the same instructions on the same inputs
         const float amax = __builtin_amdgcn_exp2f(fmaf(mown, c, -ms));
-        const uint32_t pbyte = e8m0_of_amax(amax);
-        const uint4v pc = mx_codes32(p, e8m0_as_f32(pbyte));
+        const uint32_t pbyte = FP8PV ? e8m0_of_amax_fp8(amax) : e8m0_of_amax(amax);
+        uint32_t pc[8];
+        if constexpr (FP8PV) {
+            // E4M3 bytes of this lane's block, then the exchange that the FP8 operand layout asks for: registers 0-3 of
+            // lane (row, h) hold keys 16 h .. + 15 of the tile and registers 4-7 keys 32 + 16 h .. + 15, so the lower
+            // half-wave hands the second half of its block to the upper one and takes the first half of the upper's
+            uint32_t own[8];
+            mx_codes32_fp8(p, e8m0_as_f32(pbyte), own);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                auto r = __builtin_amdgcn_permlane32_swap(own[i], own[4 + i], false, false);
+                pc[i] = r[0]; pc[4 + i] = r[1];
+            }
+        } else {
+            const uint4v c4 = mx_codes32(p, e8m0_as_f32(pbyte));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { pc[i] = c4[i]; pc[4 + i] = 0u; }
+        }
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0, 0)) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -295,15 +359,30 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
                 for (int i = 0; i < 16; ++i) o[mt][i] *= alpha;
         }
         const uint32_t vsc = lds_read4(rec + KOPS + VOPS + 256 + lane * 4);
-        uint4v va[MT];
+        const int8v pb = {(int)pc[0], (int)pc[1], (int)pc[2], (int)pc[3], (int)pc[4], (int)pc[5], (int)pc[6], (int)pc[7]};
+        if constexpr (FP8PV) {
+            int8v va[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) va[mt] = lds_read16(rec + KOPS + (mt * 64 + lane) * 16);
-        const int8v pb = as8(pc);
-        o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[0]), pb, o[0], 4, 4, 0, vsc, 0, pbyte);
-        o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[1]), pb, o[1], 4, 4, 1, vsc, 0, pbyte);
-        if constexpr (MT == 4) {
-            o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[2]), pb, o[2], 4, 4, 2, vsc, 0, pbyte);
-            o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[3]), pb, o[3], 4, 4, 3, vsc, 0, pbyte);
+            for (int mt = 0; mt < MT; ++mt) {
+                const uint4v lo = lds_read16(rec + KOPS + ((2 * mt) * 64 + lane) * 16), hi = lds_read16(rec + KOPS + ((2 * mt + 1) * 64 + lane) * 16);
+                va[mt] = int8v{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            }
+            o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va[0], pb, o[0], 0, 0, 0, vsc, 0, pbyte);
+            o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va[1], pb, o[1], 0, 0, 1, vsc, 0, pbyte);
+            if constexpr (MT == 4) {
+                o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va[2], pb, o[2], 0, 0, 2, vsc, 0, pbyte);
+                o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va[3], pb, o[3], 0, 0, 3, vsc, 0, pbyte);
+            }
+        } else {
+            uint4v va[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) va[mt] = lds_read16(rec + KOPS + (mt * 64 + lane) * 16);
+            o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[0]), pb, o[0], 4, 4, 0, vsc, 0, pbyte);
+            o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[1]), pb, o[1], 4, 4, 1, vsc, 0, pbyte);
+            if constexpr (MT == 4) {
+                o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[2]), pb, o[2], 4, 4, 2, vsc, 0, pbyte);
+                o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[3]), pb, o[3], 4, 4, 3, vsc, 0, pbyte);
+            }
         }
     };
     auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || j * 64 <= wave_qmax; };
@@ -353,46 +432,48 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
 
 // ---------------------------------------------------------------------------------------------
 template <int D>
-static int quant_d(const void* x, int BH, int L, int mode, unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
+static int quant_d(const void* x, int BH, int L, int mode, bool fp8v, unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int rows = mode == 0 ? L : Lp;
     const dim3 grid((unsigned)(((size_t)rows * (D / 32) + 255) / 256), (unsigned)BH);
     if (mode == 0)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 0>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
     else if (mode == 1) hipLaunchKernelGGL((mx_quant_d_kernel<D, 1>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    else if (fp8v)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 2, true>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
     else                hipLaunchKernelGGL((mx_quant_d_kernel<D, 2>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
-template <int D>
+template <int D, bool FP8>
 static int quant_l(const void* x, int BH, int L, int mode, unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int nblk = mode == 0 ? (L + 31) / 32 : Lp / 32;
     const dim3 grid((unsigned)nblk, (unsigned)BH);
-    if (mode == 0) hipLaunchKernelGGL((mx_quant_l_kernel<D, 0>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
-    else           hipLaunchKernelGGL((mx_quant_l_kernel<D, 2>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    if (mode == 0) hipLaunchKernelGGL((mx_quant_l_kernel<D, 0, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    else           hipLaunchKernelGGL((mx_quant_l_kernel<D, 2, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode,
+int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
                     unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
 {
-    if (BH > 65535) return -1;
-    if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, codes, scales, xf, st) : quant_d<64>(x, BH, L, mode, codes, scales, xf, st);
-    return D == 128 ? quant_l<128>(x, BH, L, mode, codes, scales, xf, st) : quant_l<64>(x, BH, L, mode, codes, scales, xf, st);
+    if (BH > 65535 || (axis == 0 && fp8 && mode != 2)) return -1;
+    if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, fp8, codes, scales, xf, st) : quant_d<64>(x, BH, L, mode, fp8, codes, scales, xf, st);
+    if (fp8) return D == 128 ? quant_l<128, true>(x, BH, L, mode, codes, scales, xf, st) : quant_l<64, true>(x, BH, L, mode, codes, scales, xf, st);
+    return D == 128 ? quant_l<128, false>(x, BH, L, mode, codes, scales, xf, st) : quant_l<64, false>(x, BH, L, mode, codes, scales, xf, st);
 }
 
-size_t mx_kv_bytes(int BHkv, int L, int D) { return (size_t)BHkv * (round_up(L, kRowPad) / 64) * mx_rec_bytes(D); }
+size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v) { return (size_t)BHkv * (round_up(L, kRowPad) / 64) * mx_rec_bytes(D, fp8v); }
 size_t mx_qops_bytes(int BHq, int L, int D) { return (size_t)BHq * round_up(L, kRowPad) * (D / 2); }
 size_t mx_qsc_bytes(int BHq, int L) { return (size_t)BHq * (round_up(L, kRowPad) / 32) * 64 * 4; }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool FP8PV>
 static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L,
                            void* o, float* lse, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
-    const size_t smem = 3 * 2 * (size_t)mx_rec_bytes(D);
-    auto kern = fwd_mx_kernel<D, CAUSAL>;
+    const size_t smem = 3 * 2 * (size_t)mx_rec_bytes(D, FP8PV);
+    auto kern = fwd_mx_kernel<D, CAUSAL, FP8PV>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)smem) != hipSuccess) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
@@ -401,14 +482,21 @@ static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, in
                        (uint16_t*)o, lse, L, Lp, Hq, Hq / Hkv, c);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
+template <int D, bool FP8PV>
+static int launch_fwd_mx_d(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, bool causal,
+                           void* o, float* lse, hipStream_t st)
+{
+    return causal ? launch_fwd_mx_t<D, true, FP8PV>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st)
+                  : launch_fwd_mx_t<D, false, FP8PV>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st);
+}
 
-int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
+int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal, bool fp8pv,
                   void* o, float* lse, hipStream_t st)
 {
-    if (D == 128) return causal ? launch_fwd_mx_t<128, true>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st)
-                                : launch_fwd_mx_t<128, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st);
-    if (D == 64)  return causal ? launch_fwd_mx_t<64, true>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st)
-                                : launch_fwd_mx_t<64, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st);
+    if (D == 128) return fp8pv ? launch_fwd_mx_d<128, true>(qops, qsc, kv, B, Hq, Hkv, L, causal, o, lse, st)
+                               : launch_fwd_mx_d<128, false>(qops, qsc, kv, B, Hq, Hkv, L, causal, o, lse, st);
+    if (D == 64)  return fp8pv ? launch_fwd_mx_d<64, true>(qops, qsc, kv, B, Hq, Hkv, L, causal, o, lse, st)
+                               : launch_fwd_mx_d<64, false>(qops, qsc, kv, B, Hq, Hkv, L, causal, o, lse, st);
     return -1;
 }
 

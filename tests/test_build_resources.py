@@ -56,4 +56,5 @@ def test_backward_kernels_do_not_spill():
 
 def test_mx_forward_kernels_do_not_spill():
     k = _resources("mx.hip")
-    _check(k, r"fwd_mx_kernelILi(64|128)ELb[01]E", 4)
+    # fwd_mx_kernel<D, CAUSAL, FP8PV>
+    _check(k, r"fwd_mx_kernelILi(64|128)ELb[01]ELb[01]E", 8)

@@ -191,3 +191,66 @@ def test_mx_P_code_flips(causal):
         bad += int((np.abs(got.astype(np.float64) - ref["P"]) > F16_FLUSH).sum()); tot += got.size
     print(f"MX P flips causal{int(causal)}: {bad} of {tot} ({bad / tot:.2e})", flush=True)
     assert bad / tot < FLIP_BAR
+
+
+# ---------------------------------------------------------------- mixed recipe: FP4 Q K^T, MXFP8 P V
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_quantize_mxfp8_bit_exact(d):
+    import paper_2603_00040_amd as aq
+    rng = np.random.default_rng(50)
+    allb = np.arange(1 << 16, dtype=np.uint16)
+    allb = allb[(allb & 0x7F80) != 0x7F80]
+    L = 300
+    n = 2 * L * d
+    bits = rng.choice(allb, size=n).astype(np.uint16)
+    base = rng.integers(90, 160, size=n // 32).repeat(32).astype(np.uint16)
+    bits = (bits & 0x807F) | ((base + rng.integers(0, 6, size=n).astype(np.uint16)) << 7)
+    x = bits.reshape(1, 2, L, d)
+    # a 448 pins the scale at 1: E4M3 midpoints (ties) and their bf16 neighbours below it; maxima around 1.75 * 2^x
+    tie = np.zeros(32, np.float32)
+    tie[:12] = [448.0, 0.0009765625, 0.0029296875, 17.0, 19.0, 208.0, 240.0, 416.0, -17.0, -19.0, -208.0, -416.0]
+    x[0, 0, :32, 0] = W.f32_to_bf16_bits(tie)
+    for i, top in enumerate((1.7421875, 1.75, 1.7578125)):
+        col = np.zeros(32, np.float32); col[0] = top; col[1:6] = [0.1, 0.3, 0.7, 1.1, 1.6]
+        x[0, 0, :32, 1 + i] = W.f32_to_bf16_bits(col)
+    x = np.ascontiguousarray(x)
+    codes, scales, xf = aq.attnqat_quantize_mxfp8(to_dev(x))
+    torch.cuda.synchronize()
+    xs = np.ascontiguousarray(np.swapaxes(W.bf16_bits_to_f32(x), -1, -2))
+    pc, ps, pxf = oracle.phi_mx8(xs)
+    gc, gs = codes.cpu().numpy(), scales.cpu().numpy()
+    assert gc.shape == pc.shape and gs.shape == ps.shape
+    assert np.array_equal(gs, ps), f"{(gs != ps).sum()} scale bytes differ"
+    canon = lambda c: np.where((c & 0x7F) == 0, 0, c)                  # -0 and +0 are the same value
+    assert np.array_equal(canon(gc), canon(pc)), f"{(canon(gc) != canon(pc)).sum()} code bytes differ"
+    # the bf16 copy rounds 4-bit-significand values times a power of two: exact
+    want = np.ascontiguousarray(np.swapaxes(pxf, -1, -2))
+    assert np.array_equal(xf.to(torch.float32).cpu().numpy(), want)
+
+
+def _run_fp8pv(B, Hq, Hkv, L, d, causal, seed, **kw):
+    import paper_2603_00040_amd as aq
+    x = random_inputs(B, Hq, Hkv, L, d, seed, **kw)
+    q, k, v = (to_dev(x[n]) for n in "qkv")
+    o, lse = aq.attnqat_fwd_infer_mx_fp8pv(q, k, v, causal)
+    torch.cuda.synchronize()
+    ref = oracle.fwd(f32(x["q"]), f32(x["k"]), f32(x["v"]), causal, aq.block_k(), scale_mode=oracle.MX_FP8PV)
+    r = {"O": rel_l2(host(o), ref["O"]), "L": max_abs(host(lse), ref["L"]), "Omax": max_abs(host(o), ref["O"])}
+    print(f"fwd_mx_fp8pv B{B} Hq{Hq} Hkv{Hkv} L{L} d{d} causal{int(causal)}: {r}", flush=True)
+    assert r["O"] <= TOL and r["L"] <= 2e-5 * max(1.0, np.abs(ref["L"]).max())
+
+
+def test_fp8pv_tiny_ref_config():
+    _run_fp8pv(1, 2, 2, 256, 64, False, seed=0)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("L", [1, 31, 65, 300, 520])
+def test_fp8pv_ragged_lengths_d128_gqa(L, causal):
+    _run_fp8pv(2, 4, 2, L, 128, causal, seed=400 + L, k_chan=4)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_fp8pv_d64_heavy_tails(causal):
+    _run_fp8pv(1, 3, 1, 333, 64, causal, seed=7, dist="t3", scale=0.5, tok_mod=50)
