@@ -23,7 +23,8 @@ sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16 MFMA
 MFMA_FP4_PEAK_TFLOPS = 10100.0     # MI355X dense FP4 MFMA (the MX variant's products)
-KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
+MFMA_FP8_PEAK_TFLOPS = 5000.0      # MI355X dense FP8 MFMA (P V of the mixed recipe)
+KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "fwd_infer_mx_fp8pv": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
 # Bytes beyond L2 per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
 # measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
 # Sec. 4.4: peak forward throughput on B200 (NVFP4 QK + FP8 PV) at b=1, s=32768, h=32, d=128.  Another machine and
@@ -45,9 +46,10 @@ def main():
     ap.add_argument("--ablation", type=int, default=0,
                     help="backward ablation bit set of Sec. 4.2 (1: D from the bf16 O, 2: dV from the un-quantized P); "
                          "0 = the method itself")
-    ap.add_argument("--format", default="nvfp4", choices=["nvfp4", "mx"],
+    ap.add_argument("--format", default="nvfp4", choices=["nvfp4", "mx", "mx_fp8pv"],
                     help="nvfp4: the paper's format (default).  mx: E2M1 blocks of 32 with E8M0 scales: the inference "
-                         "forward runs on the scaled FP4 MFMA, the training forward and the backward on the 16-bit path")
+                         "forward runs on the scaled FP4 MFMA, the training forward and the backward on the 16-bit path.  "
+                         "mx_fp8pv: the mixed recipe (FP4 Q K^T, MXFP8 P V), inference forward only")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     args = ap.parse_args()
@@ -66,8 +68,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     w = W.by_name(args.workload)
-    mx = args.format == "mx"
-    train = w.passes == "fwd+bwd" and args.passes == "auto"
+    fp8pv = args.format == "mx_fp8pv"
+    mx = args.format == "mx" or fp8pv
+    train = w.passes == "fwd+bwd" and args.passes == "auto" and not fp8pv
     t0 = time.time()
     x = W.make_inputs(w, with_do=train)
     gen_s = time.time() - t0
@@ -84,12 +87,15 @@ def main():
         ws_bytes = max(aq.workspace_bytes(aq.WS_FWD_MX if mx else aq.WS_FWD, B, Hq, Hkv, L, d),
                        aq.workspace_bytes(aq.WS_BWD_MX if mx else aq.WS_BWD, B, Hq, Hkv, L, d))
     else:
-        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX if mx else aq.WS_FWD_INFER, B, Hq, Hkv, L, d)
+        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX_FP8PV if fp8pv else aq.WS_FWD_INFER_MX if mx else aq.WS_FWD_INFER,
+                                      B, Hq, Hkv, L, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
 
     def fwd():
         if train:
             (aq.attnqat_fwd_mx if mx else aq.attnqat_fwd)(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
+        elif fp8pv:
+            aq.attnqat_fwd_infer_mx_fp8pv(q, k, v, w.causal, workspace=ws, out=(o, lse))
         elif mx:
             aq.attnqat_fwd_infer_mx(q, k, v, w.causal, workspace=ws, out=(o, lse))
         else:
@@ -144,8 +150,10 @@ def main():
     pair_flops = B * Hq * float(L) ** 2 * d * (0.5 if w.causal else 1.0)
     step_flops = w.fwd_flops + (w.bwd_flops if train else 0.0)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
-    fwd_ms = sum(kern_ms.get(n, 0.0) for n in ("prep_qkv", "fwd_train", "fwd_infer", "prep_qkv_mx", "fwd_infer_mx"))
+    fwd_ms = sum(kern_ms.get(n, 0.0) for n in ("prep_qkv", "fwd_train", "fwd_infer", "prep_qkv_mx", "fwd_infer_mx", "fwd_infer_mx_fp8pv"))
     peak = MFMA_FP4_PEAK_TFLOPS if (mx and not train) else MFMA_PEAK_TFLOPS
+    if fp8pv:      # half of the products at the FP4 rate, half at the FP8 rate
+        peak = round(2.0 / (1.0 / MFMA_FP4_PEAK_TFLOPS + 1.0 / MFMA_FP8_PEAK_TFLOPS), 1)
     gemms = dict(KERNEL_GEMMS)
     if pf_frac is not None:
         gemms["bwd_dkdv"] = 6.0 + 2.0 * pf_frac
@@ -162,14 +170,15 @@ def main():
 
     cpu = None
     if args.cpu_seconds > 0:
-        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx)
+        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx, fp8pv)
 
     out = {
         "metric": "FP4-attention fwd+bwd TFLOPS (1 MI355X)" if train else "FP4-attention fwd TFLOPS (1 MI355X)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": round(value / PAPER_FWD_TFLOPS[w.name], 4) if (w.name in PAPER_FWD_TFLOPS and not train) else None,
-        "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if (mx and not train)
+        "dtype": "fp4 Q K^T, fp8 (E4M3) P V MFMA operands with E8M0 block scales, fp32 accumulate and softmax" if fp8pv
+                 else "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if (mx and not train)
                  else "f16/bf16 MFMA operands (exact %s values), fp32 accumulate and softmax" % ("MXFP4" if mx else "NVFP4"),
         "data": "synthetic",
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
@@ -185,7 +194,7 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, x, train, target_s, block_k, mx=False):
+def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False):
     """Time the oracle (as it stands) on a bounded sample of the same workload: forward of
     sampled query rows and, for training workloads, dQ of the same rows."""
     import numpy as np
@@ -203,7 +212,7 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False):
     def run(n):
         rows = np.sort(rng.choice(w.L, size=min(n, w.L), replace=False)).astype(np.int64)
         t0 = time.perf_counter()
-        sm = oracle.MX if mx else 0
+        sm = oracle.MX_FP8PV if fp8pv else oracle.MX if mx else 0
         r = oracle.fwd(f["q"], f["k"], f["v"], w.causal, block_k, scale_mode=sm, rows=rows)
         if train:
             oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal, scale_mode=sm)

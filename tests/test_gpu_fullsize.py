@@ -151,10 +151,11 @@ def test_full_size(cfg):
         assert not dk[:b].any() and not dv[:b].any()
 
 
+@pytest.mark.parametrize("fp8pv", [False, True])
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4])
-def test_full_size_mx_forward(cfg):
-    """The MX forward (scaled FP4 MFMA) on the full shapes: O and L on sampled rows, and the MX codes and
-    scales of whole K (blocks along d) and V (blocks along the keys) tensors, bit exact."""
+def test_full_size_mx_forward(cfg, fp8pv):
+    """The MX forward (scaled FP4 MFMA; fp8pv: the mixed recipe with MXFP8 P and V) on the full shapes: O and L on
+    sampled rows, and the MX codes and scales of whole K (blocks along d) and V (blocks along the keys) tensors, bit exact."""
     import paper_2603_00040_amd as aq
     w = W.CONFIGS[cfg]
     print(f"\n[{w.name}] generating inputs", flush=True)
@@ -167,20 +168,22 @@ def test_full_size_mx_forward(cfg):
     gi = [(b, h, r) for h, rs in zip(qheads, rows) for r in rs]
     pick = lambda t: torch.stack([t[bb, hh, rr] for bb, hh, rr in gi])
     print(f"[{w.name}] GPU MX forward", flush=True)
-    o, lse = aq.attnqat_fwd_infer_mx(q, k, v, w.causal)
+    o, lse = (aq.attnqat_fwd_infer_mx_fp8pv if fp8pv else aq.attnqat_fwd_infer_mx)(q, k, v, w.causal)
     torch.cuda.synchronize()
     print(f"[{w.name}] oracle MX forward on {flat.size} rows", flush=True)
-    rf = oracle.fwd_mx(sub["q"], sub["k"], sub["v"], w.causal, Bk, rows=flat)
+    rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, scale_mode=oracle.MX_FP8PV if fp8pv else oracle.MX, rows=flat)
     eO = rel_l2(host(pick(o)), rf["O"]); eL = max_abs(host(pick(lse)), rf["L"])
     print(f"[{w.name}] MX O rel-L2 {eO:.2e} max-abs {max_abs(host(pick(o)), rf['O']):.2e}  L max-abs {eL:.2e}", flush=True)
     assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
     canon = lambda c: np.where((c & 7) == 0, c & 0xF0, c) & np.where((c & 0x70) == 0, 0x0F, 0xFF)
-    for name, axis in (("k", 0), ("v", 1)):
+    if fp8pv:
+        canon = lambda c: np.where((c & 0x7F) == 0, 0, c)
+    for name, axis in ((("v", 1),) if fp8pv else (("k", 0), ("v", 1))):
         t = {"k": k, "v": v}[name][b:b + 1, kv].contiguous()
-        codes, scales, _ = aq.attnqat_quantize_mx(t, axis=axis, want_xf=False)
+        codes, scales, _ = aq.attnqat_quantize_mxfp8(t, want_xf=False) if fp8pv else aq.attnqat_quantize_mx(t, axis=axis, want_xf=False)
         torch.cuda.synchronize()
         xs = sub[name] if axis == 0 else np.ascontiguousarray(np.swapaxes(sub[name], -1, -2))
-        pc, ps, _ = oracle.phi_mx(xs)
+        pc, ps, _ = oracle.phi_mx8(xs) if fp8pv else oracle.phi_mx(xs)
         gc, gs = codes.cpu().numpy(), scales.cpu().numpy()
         nbad_s = int((gs != ps).sum()); nbad_c = int((canon(gc) != canon(pc)).sum())
         print(f"[{w.name}] MX phi({name}, axis {axis}): {gs.size} scales, {nbad_s} differ; {gc.size} code bytes, {nbad_c} differ", flush=True)
