@@ -208,6 +208,19 @@ def fwd_mx(q, k, v, causal: bool, Bk: int, quant_p: bool = True, rows=None, dump
     return fwd(q, k, v, causal, Bk, quant_p=quant_p, scale_mode=MX, rows=rows, dump_p=dump_p)
 
 
+# ---------------------------------------------------------------- K smoothing
+
+def smooth_k(k):
+    """K minus its mean over the tokens, per (batch, kv head, channel): the K smoothing of SageAttention that
+    Sec. 3.1 describes and Sec. 4.2 switches on inside QAT.  S changes by a per-query constant, which softmax
+    ignores, and the centred K quantizes better.  Mean = fp64 sum / L rounded to fp32; the subtraction is an fp32
+    subtraction.  Callers pass the result to fwd()/bwd() in place of K.  Gradient: dK = dK' - mean_j(dK'_j), and
+    sum_j dK'_j = sum_i rowsum(dS_i) Q^F_i = 0 because D comes from O' (Sec. 3.3), so dK = dK'."""
+    k = _f32(k)
+    mean = (k.astype(np.float64).sum(axis=-2, keepdims=True) / k.shape[-2]).astype(np.float32)
+    return k - mean
+
+
 # ---------------------------------------------------------------- attention
 
 MX = 2      # scale_mode of the MX format: E2M1 blocks of 32 with E8M0 scales, V and P blocked along the keys
