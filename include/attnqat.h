@@ -148,6 +148,30 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The NVFP4 forward and backward with options that Sec. 4.2 studies inside QAT (SageAttention's heuristics):
+ *   ATTNQAT_OPT_SMOOTH_K   K smoothing (Sec. 3.1): phi is applied to K minus its mean over the tokens, per
+ *                          (batch, kv head, channel).  S changes by a per-query constant that softmax ignores
+ *                          (lse moves by q . mean(K) / sqrt(d)); the centred K quantizes better.  The mean is the
+ *                          fp64 sum / L rounded to fp32, the subtraction an fp32 subtraction.  dK is the gradient
+ *                          with respect to the centred K, which equals the gradient with respect to K because
+ *                          rowsum(dS) = 0 when D comes from O' (Sec. 3.3).
+ * attnqat_fwd_opt: o_hp != NULL selects the training forward (Alg. 2), NULL the inference forward (Alg. 1).
+ * attnqat_bwd_opt must be given the same options as the forward whose lse and o_hp it consumes.
+ * options = 0 is attnqat_fwd / attnqat_fwd_infer / attnqat_bwd; unknown bits: ATTNQAT_EINVAL.
+ * Workspace sizes: ATTNQAT_WS_FWD and ATTNQAT_WS_BWD.
+ */
+#define ATTNQAT_OPT_SMOOTH_K        1
+int attnqat_fwd_opt(const void* q, const void* k, const void* v,
+                    int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
+                    void* o, float* lse, float* o_hp,
+                    void* workspace, size_t workspace_bytes, void* stream);
+int attnqat_bwd_opt(const void* q, const void* k, const void* v, const void* d_o,
+                    const float* lse, const float* o_hp,
+                    int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
+                    void* dq, void* dk, void* dv,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * MX variant of phi: the OCP microscaling FP4 format that Sec. 3.1 names beside NVFP4
  * (E2M1 elements, 32 per block, one power-of-two E8M0 scale), with the power-of-two
  * counterpart of Eq. 1 as the scale rule:

@@ -32,6 +32,9 @@ _SIGNATURES = {
     "attnqat_fwd_infer_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_quantize_mxfp8": (_i, [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "attnqat_fwd_infer_mx_fp8pv": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_fwd_opt": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_bwd_opt": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
+                             _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                             _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -113,6 +116,44 @@ def attnqat_quantize(x, want_codes=True, want_xf=True):
     xf = torch.empty_like(x) if want_xf else None
     _check(lib().attnqat_quantize(_ptr(x), B, H, L, d, BF16, _ptr(codes), _ptr(scales), _ptr(xf), _stream()))
     return codes, scales, xf
+
+
+OPT_SMOOTH_K = 1
+
+
+def attnqat_fwd_opt(q, k, v, causal: bool, options: int, train: bool = True, workspace=None, out=None):
+    """Alg. 2 (train) or Alg. 1 with the option bits of Sec. 4.2 (OPT_SMOOTH_K).  Returns (o, lse, o_hp or None)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+        o_hp = torch.empty((B, Hq, L, d), dtype=torch.float32, device=q.device) if train else None
+    else:
+        o, lse, o_hp = out
+    ws, nb = _workspace(WS_FWD, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_fwd_opt(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16, int(options),
+                                 _ptr(o), _ptr(lse), _ptr(o_hp), _ptr(ws), nb, _stream()))
+    return o, lse, o_hp
+
+
+def attnqat_bwd_opt(q, k, v, d_o, lse, o_hp, causal: bool, options: int, workspace=None, out=None):
+    """Alg. 3 with the same option bits as the forward.  Returns (dq, dk, dv) bf16."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (d_o, "d_o")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    else:
+        dq, dk, dv = out
+    ws, nb = _workspace(WS_BWD, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_bwd_opt(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(o_hp),
+                                 B, Hq, Hkv, L, d, int(causal), BF16, int(options),
+                                 _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), nb, _stream()))
+    return dq, dk, dv
 
 
 def attnqat_fwd_mx(q, k, v, causal: bool, workspace=None, out=None):

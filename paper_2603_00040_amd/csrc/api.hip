@@ -54,7 +54,7 @@ int check_dims(int B, int Hq, int Hkv, int L, int d, int dtype)
 }
 
 // Workspace of the forward: fp16 Q^F, K^F (row-major) and V^F^T.
-struct FwdWs { void *qh, *kh, *vt, *tmp; size_t bytes; };
+struct FwdWs { void *qh, *kh, *vt, *tmp; double* kpart; float* kmean; size_t bytes; };
 FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 {
     const size_t Lp = round_up(L, kRowPad);
@@ -64,13 +64,15 @@ FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
     w.kh = c.take((size_t)B * Hkv * Lp * d * 2);
     w.vt = c.take((size_t)B * Hkv * Lp * d * 2);
     w.tmp = mx ? c.take((size_t)B * Hq * L * d * 2) : nullptr;      // MX: the dequantized bf16 tensor before its layout copy
+    w.kpart = (double*)c.take(colmean_scratch_bytes(B * Hkv, d));  // K smoothing: partial sums and the token mean of K
+    w.kmean = (float*)c.take((size_t)B * Hkv * d * 4);
     w.bytes = c.off;
     return w;
 }
 
 // Workspace of the backward: row-major copies (Q^F, K^F fp16; V^F and dO bf16: dO is not exactly
 // representable in fp16), the per-row {L, D} pairs and the partial maxima that bound |dS|.
-struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; float* bounds; void* tmp; size_t bytes; };
+struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; float* bounds; void* tmp; double* kpart; float* kmean; size_t bytes; };
 BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 {
     const size_t Lp = round_up(L, kRowPad);
@@ -81,6 +83,8 @@ BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
     w.rowstat = (float*)c.take((size_t)B * Hq * Lp * 8);
     w.bounds = (float*)c.take((size_t)3 * B * Hq * 64 * 4);
     w.tmp = mx ? c.take((size_t)B * Hq * L * d * 2) : nullptr;
+    w.kpart = (double*)c.take(colmean_scratch_bytes(B * Hkv, d));
+    w.kmean = (float*)c.take((size_t)B * Hkv * d * 4);
     w.bytes = c.off;
     return w;
 }
@@ -101,18 +105,20 @@ MxWs carve_mx(void* ws, int B, int Hq, int Hkv, int L, int d, bool fp8v = false)
 // phi of one input tensor and its layout copies (xr row-major, xt transposed; either may be null).
 // NVFP4: one fused kernel.  MX: the MX fake-quantizer writes the dequantized bf16 tensor to tmp (blocks along d,
 // or along the sequence for V), then the layout copy runs without quantizing.
-int quant_copy(const void* x, int BH, int L, int d, bool mx, int mx_axis, bool out_f16, void* xr, void* xt, void* tmp, hipStream_t st)
+int quant_copy(const void* x, int BH, int L, int d, bool mx, int mx_axis, bool out_f16, void* xr, void* xt, void* tmp, hipStream_t st,
+               const float* sub = nullptr)
 {
-    if (!mx) return launch_prep(x, BH, L, d, true, out_f16, nullptr, nullptr, nullptr, xr, xt, st);
+    if (!mx) return launch_prep(x, BH, L, d, true, out_f16, nullptr, nullptr, nullptr, xr, xt, st, sub);
     if (launch_mx_quant(x, BH, L, d, mx_axis, 0, false, nullptr, nullptr, tmp, st)) return -1;
     return launch_prep(tmp, BH, L, d, false, out_f16, nullptr, nullptr, nullptr, xr, xt, st);
 }
 
 int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int Hkv, int L, int d,
                int causal, int dtype, bool train, bool mx, void* o, float* lse, float* o_hp,
-               int dump_row0, float* p_dump, void* workspace, size_t workspace_bytes, void* stream)
+               int dump_row0, float* p_dump, void* workspace, size_t workspace_bytes, void* stream, int options = 0)
 {
     if (!q || !k || !v || !o || !lse || (train && !o_hp)) return ATTNQAT_EINVAL;
+    if ((options & ~ATTNQAT_OPT_SMOOTH_K) || (options && mx)) return ATTNQAT_EINVAL;
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
     FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d, mx);
@@ -121,7 +127,12 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
     prof_begin(st);
     // Alg. 1 line "phi(Q), phi(K), phi(V)" / Alg. 2 line "Q^F, K^F, V^F"
     if (quant_copy(q, B * Hq, L, d, mx, 0, true, w.qh, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
-    if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kh, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    const float* kmean = nullptr;
+    if (options & ATTNQAT_OPT_SMOOTH_K) {          // K minus its token mean (Sec. 3.1), then phi
+        if (launch_colmean(k, B * Hkv, L, d, w.kpart, w.kmean, st)) return ATTNQAT_ELAUNCH;
+        kmean = w.kmean;
+    }
+    if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kh, nullptr, w.tmp, st, kmean)) return ATTNQAT_ELAUNCH;
     if (quant_copy(v, B * Hkv, L, d, mx, 1, true, nullptr, w.vt, w.tmp, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkv", st);
     if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, mx, o, lse, o_hp, dump_row0, p_dump, st))
@@ -296,6 +307,15 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                       workspace, workspace_bytes, stream);
 }
 
+int attnqat_fwd_opt(const void* q, const void* k, const void* v,
+                    int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
+                    void* o, float* lse, float* o_hp,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, o_hp != nullptr, false, o, lse, o_hp, 0, nullptr,
+                      workspace, workspace_bytes, stream, options);
+}
+
 int attnqat_fwd_mx(const void* q, const void* k, const void* v,
                    int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                    void* o, float* lse, float* o_hp,
@@ -319,9 +339,10 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
                       const float* lse, const void* o_acc, bool o_is_bf16, int p_quant /* 0 none, 1 NVFP4, 2 MX */,
                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                       void* dq, void* dk, void* dv,
-                      void* workspace, size_t workspace_bytes, void* stream)
+                      void* workspace, size_t workspace_bytes, void* stream, int options = 0)
 {
     if (!q || !k || !v || !d_o || !lse || !o_acc || !dq || !dk || !dv) return ATTNQAT_EINVAL;
+    if ((options & ~ATTNQAT_OPT_SMOOTH_K) || (options && p_quant == 2)) return ATTNQAT_EINVAL;
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
     const bool mx = p_quant == 2;
@@ -331,7 +352,12 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
     prof_begin(st);
     // Q^F, K^F, V^F again (bit-identical to the forward's) and a zero-padded copy of dO
     if (quant_copy(q, B * Hq, L, d, mx, 0, true, w.qb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
-    if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    const float* kmean = nullptr;
+    if (options & ATTNQAT_OPT_SMOOTH_K) {          // the same centred K as the forward (deterministic mean)
+        if (launch_colmean(k, B * Hkv, L, d, w.kpart, w.kmean, st)) return ATTNQAT_ELAUNCH;
+        kmean = w.kmean;
+    }
+    if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kb, nullptr, w.tmp, st, kmean)) return ATTNQAT_ELAUNCH;
     if (quant_copy(v, B * Hkv, L, d, mx, 1, false, w.vb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
@@ -356,6 +382,16 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
 {
     return bwd_common(q, k, v, d_o, lse, o_hp, false, 1, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
                       workspace, workspace_bytes, stream);
+}
+
+int attnqat_bwd_opt(const void* q, const void* k, const void* v, const void* d_o,
+                    const float* lse, const float* o_hp,
+                    int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
+                    void* dq, void* dk, void* dv,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return bwd_common(q, k, v, d_o, lse, o_hp, false, 1, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
+                      workspace, workspace_bytes, stream, options);
 }
 
 int attnqat_bwd_mx(const void* q, const void* k, const void* v, const void* d_o,

@@ -10,8 +10,15 @@ namespace aq {
 //   xr [BH, Lp, D]: dequantized rows, zero padded to Lp = round_up(L, 128)
 //   xt [BH, D, Lp]: the same, transposed, sequence positions permuted inside groups of 16
 //   quant=false copies x unchanged (bf16 only).  out_f16 selects fp16 for xr/xt.
+//   sub (optional) [BH, D] fp32: subtracted from every row before phi (K smoothing: the token mean of each channel)
 int launch_prep(const void* x, int BH, int L, int D, bool quant, bool out_f16,
-                uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st);
+                uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st,
+                const float* sub = nullptr);
+
+// Token mean of every channel of x [BH, L, D] bf16 -> mean [BH, D] fp32 (fp64 sums in a fixed order).
+// scratch: colmean_scratch_bytes() bytes.
+size_t colmean_scratch_bytes(int BH, int D);
+int launch_colmean(const void* x, int BH, int L, int D, double* scratch, float* mean, hipStream_t st);
 
 // Alg. 1 (train=false) / Alg. 2 (train=true) on fp16 copies made by launch_prep.
 // mx_p: phi(P-tilde) in the MX format (blocks of 32 keys, power-of-two scale) instead of NVFP4.

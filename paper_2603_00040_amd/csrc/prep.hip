@@ -21,7 +21,7 @@ template <bool QUANT, bool OUT_F16>
 __global__ __launch_bounds__(256) void prep_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, int D,
     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint16_t* __restrict__ xf_pub,
-    uint16_t* __restrict__ xr, uint16_t* __restrict__ xt)
+    uint16_t* __restrict__ xr, uint16_t* __restrict__ xt, const float* __restrict__ sub)
 {
     __shared__ uint16_t tile[64][128 + 2];
     const int bh = blockIdx.y;
@@ -42,6 +42,13 @@ __global__ __launch_bounds__(256) void prep_kernel(
                 v[2 * i + 1]     = __uint_as_float(a[i] & 0xFFFF0000u);
                 v[8 + 2 * i]     = __uint_as_float(b[i] << 16);
                 v[8 + 2 * i + 1] = __uint_as_float(b[i] & 0xFFFF0000u);
+            }
+            if (sub) {                      // K smoothing: minus the token mean of the channel, an fp32 subtraction.
+                // The inputs of phi then have 24 significant bits: the two "IEEE division == real quotient" arguments
+                // below hold up to a double rounding that can move a value sitting within 2^-24 of a rounding boundary.
+                const float* sp = sub + (size_t)bh * D + cb * 16;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] -= sp[i];
             }
         } else {
 #pragma unroll
@@ -131,25 +138,68 @@ __global__ __launch_bounds__(256) void prep_kernel(
     }
 }
 
+// Token mean of every channel, for K smoothing: fp64 partial sums of NCHUNK row ranges, then their sum in a fixed
+// order, divided by L and rounded to fp32.  Deterministic; x [BH, L, D] bf16.
+constexpr int kMeanChunks = 32;
+template <int D>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const uint16_t* __restrict__ x, int L, double* __restrict__ part)
+{
+    constexpr int NS = 256 / D;                       // row slices per block
+    __shared__ double red[256];
+    const int bh = blockIdx.y, ch = blockIdx.x, c = threadIdx.x % D, sl = threadIdx.x / D;
+    const int per = (L + kMeanChunks - 1) / kMeanChunks;
+    const int r0 = ch * per, r1 = min(L, r0 + per);
+    const uint16_t* src = x + (size_t)bh * L * D + c;
+    double acc = 0.0;
+    for (int r = r0 + sl; r < r1; r += NS) acc += (double)bf16_to_f32(src[(size_t)r * D]);
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (sl == 0) {
+        double t = red[c];
+#pragma unroll
+        for (int i = 1; i < NS; ++i) t += red[i * D + c];
+        part[((size_t)bh * kMeanChunks + ch) * D + c] = t;
+    }
+}
+__global__ void colmean_kernel(const double* __restrict__ part, int L, int D, float* __restrict__ mean)
+{
+    const int bh = blockIdx.x, c = threadIdx.x;
+    double t = 0.0;
+    for (int ch = 0; ch < kMeanChunks; ++ch) t += part[((size_t)bh * kMeanChunks + ch) * D + c];
+    mean[(size_t)bh * D + c] = (float)(t / (double)L);
+}
+
+size_t colmean_scratch_bytes(int BH, int D) { return (size_t)BH * kMeanChunks * D * sizeof(double); }
+
+int launch_colmean(const void* x, int BH, int L, int D, double* scratch, float* mean, hipStream_t st)
+{
+    if (BH > 65535 || (D != 64 && D != 128)) return -1;
+    if (D == 128) hipLaunchKernelGGL((colsum_partial_kernel<128>), dim3(kMeanChunks, BH), dim3(256), 0, st, (const uint16_t*)x, L, scratch);
+    else          hipLaunchKernelGGL((colsum_partial_kernel<64>), dim3(kMeanChunks, BH), dim3(256), 0, st, (const uint16_t*)x, L, scratch);
+    if (hipGetLastError() != hipSuccess) return -1;
+    hipLaunchKernelGGL(colmean_kernel, dim3(BH), dim3(D), 0, st, (const double*)scratch, L, D, mean);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <bool QUANT, bool OUT_F16>
 static int launch_prep_t(const void* x, int BH, int L, int D, uint8_t* codes, uint8_t* scales,
-                         void* xf_pub, void* xr, void* xt, hipStream_t st)
+                         void* xf_pub, void* xr, void* xt, const float* sub, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     dim3 grid(Lp / 64, BH);
     hipLaunchKernelGGL((prep_kernel<QUANT, OUT_F16>), grid, dim3(256), 0, st,
                        (const uint16_t*)x, L, Lp, D, codes, scales, (uint16_t*)xf_pub,
-                       (uint16_t*)xr, (uint16_t*)xt);
+                       (uint16_t*)xr, (uint16_t*)xt, sub);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_prep(const void* x, int BH, int L, int D, bool quant, bool out_f16,
-                uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st)
+                uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st, const float* sub)
 {
-    if (quant) return out_f16 ? launch_prep_t<true, true>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st)
-                              : launch_prep_t<true, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st);
-    return out_f16 ? launch_prep_t<false, true>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st)
-                   : launch_prep_t<false, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, st);
+    if (quant) return out_f16 ? launch_prep_t<true, true>(x, BH, L, D, codes, scales, xf_pub, xr, xt, sub, st)
+                              : launch_prep_t<true, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, sub, st);
+    return out_f16 ? launch_prep_t<false, true>(x, BH, L, D, codes, scales, xf_pub, xr, xt, sub, st)
+                   : launch_prep_t<false, false>(x, BH, L, D, codes, scales, xf_pub, xr, xt, sub, st);
 }
 
 }  // namespace aq

@@ -27,11 +27,15 @@ def test_host_side_queries_need_no_gpu():
     assert aq.block_k() == 64
     assert aq.lib().attnqat_strerror(aq.ESHAPE).decode().startswith("unsupported shape")
     # workspace: three fp16 copies padded to 128 rows (forward); Q, K, V, dO copies, the per-row {L, D}
-    # pairs and 3 x 64 partial maxima per query head that bound |dS| (backward)
+    # pairs and 3 x 64 partial maxima per query head that bound |dS| (backward); both end with the scratch of
+    # the K smoothing option: 32 fp64 partial column sums and the fp32 column mean per kv head
     B, Hq, Hkv, L, d = 1, 4, 2, 300, 128
     Lp = 384
-    assert aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d) == (Hq + 2 * Hkv) * Lp * d * 2
-    assert aq.workspace_bytes(aq.WS_BWD, B, Hq, Hkv, L, d) == (2 * Hq + 2 * Hkv) * Lp * d * 2 + Hq * Lp * 8 + 3 * Hq * 64 * 4
+    ksm = Hkv * 32 * d * 8 + Hkv * d * 4
+    assert aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d) == (Hq + 2 * Hkv) * Lp * d * 2 + ksm
+    assert aq.workspace_bytes(aq.WS_BWD, B, Hq, Hkv, L, d) == (2 * Hq + 2 * Hkv) * Lp * d * 2 + Hq * Lp * 8 + 3 * Hq * 64 * 4 + ksm
+    # the MX training path adds the dequantized bf16 tensor that the MX fake-quantizer hands to the layout copy
+    assert aq.workspace_bytes(aq.WS_FWD_MX, B, Hq, Hkv, L, d) == aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d) + Hq * L * d * 2
     assert aq.workspace_bytes(aq.WS_FWD, B, Hq, 3, L, d) == 0
     assert aq.workspace_bytes(99, B, Hq, Hkv, L, d) == 0
 
