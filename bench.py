@@ -50,9 +50,14 @@ def main():
                     help="nvfp4: the paper's format (default).  mx: E2M1 blocks of 32 with E8M0 scales: the inference "
                          "forward runs on the scaled FP4 MFMA, the training forward and the backward on the 16-bit path.  "
                          "mx_fp8pv: the mixed recipe (FP4 Q K^T, MXFP8 P V), inference forward only")
+    ap.add_argument("--smooth-k", action="store_true",
+                    help="K smoothing option of Sec. 4.2 (nvfp4 format only): phi on K minus its token mean")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     args = ap.parse_args()
+    if args.smooth_k and (args.format != "nvfp4" or args.ablation):
+        print("bench.py: --smooth-k goes with --format nvfp4 and no ablation", file=sys.stderr)
+        sys.exit(2)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(heads shard across GPUs without communication, see DESIGN.md)", file=sys.stderr)
@@ -87,12 +92,14 @@ def main():
         ws_bytes = max(aq.workspace_bytes(aq.WS_FWD_MX if mx else aq.WS_FWD, B, Hq, Hkv, L, d),
                        aq.workspace_bytes(aq.WS_BWD_MX if mx else aq.WS_BWD, B, Hq, Hkv, L, d))
     else:
-        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX_FP8PV if fp8pv else aq.WS_FWD_INFER_MX if mx else aq.WS_FWD_INFER,
+        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX_FP8PV if fp8pv else aq.WS_FWD_INFER_MX if mx else aq.WS_FWD,
                                       B, Hq, Hkv, L, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
 
     def fwd():
-        if train:
+        if args.smooth_k:
+            aq.attnqat_fwd_opt(q, k, v, w.causal, aq.OPT_SMOOTH_K, train=train, workspace=ws, out=(o, lse, ohp if train else None))
+        elif train:
             (aq.attnqat_fwd_mx if mx else aq.attnqat_fwd)(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
         elif fp8pv:
             aq.attnqat_fwd_infer_mx_fp8pv(q, k, v, w.causal, workspace=ws, out=(o, lse))
@@ -102,7 +109,9 @@ def main():
             aq.attnqat_fwd_infer(q, k, v, w.causal, workspace=ws, out=(o, lse))
 
     def bwd():
-        if args.ablation:
+        if args.smooth_k:
+            aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, aq.OPT_SMOOTH_K, workspace=ws, out=(dq, dk, dv))
+        elif args.ablation:
             aq.attnqat_bwd_ablation(q, k, v, do, lse, ohp, o, w.causal, args.ablation, workspace=ws, out=(dq, dk, dv))
         else:
             (aq.attnqat_bwd_mx if mx else aq.attnqat_bwd)(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
@@ -170,7 +179,7 @@ def main():
 
     cpu = None
     if args.cpu_seconds > 0:
-        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx, fp8pv)
+        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k)
 
     out = {
         "metric": "FP4-attention fwd+bwd TFLOPS (1 MI355X)" if train else "FP4-attention fwd TFLOPS (1 MI355X)",
@@ -183,7 +192,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
                    "passes": w.passes if train else "fwd_infer", "block_k": aq.block_k(), "seed": w.seed,
-                   "bwd_ablation": args.ablation, "format": args.format},
+                   "bwd_ablation": args.ablation, "format": args.format, "smooth_k": bool(args.smooth_k)},
         "fwd_tflops": round(w.fwd_flops / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
         "fwd_ms": round(fwd_ms, 3),
         "frac_of_mfma_peak_model_flops": round(value / peak, 4),
@@ -194,7 +203,7 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False):
+def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False):
     """Time the oracle (as it stands) on a bounded sample of the same workload: forward of
     sampled query rows and, for training workloads, dQ of the same rows."""
     import numpy as np
@@ -207,6 +216,8 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False):
     hk = h // (w.Hq // w.Hkv)
     f = {n: W.bf16_bits_to_f32(x[n][b:b + 1, (h if n in ("q", "do") else hk):(h if n in ("q", "do") else hk) + 1])
          for n in x}
+    if smooth_k:
+        f["k"] = oracle.smooth_k(f["k"])
     per_row = (4.0 + (6.0 if train else 0.0)) * w.L * w.d * (0.5 if w.causal else 1.0)
 
     def run(n):

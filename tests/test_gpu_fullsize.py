@@ -234,3 +234,43 @@ def test_full_size_mx_training(cfg):
     other = [hk for hk in range(w.Hkv) if hk not in kv]
     if other:
         assert not dk[:, other].any() and not dv[:, other].any()
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_full_size_k_smoothing(cfg):
+    """ATTNQAT_OPT_SMOOTH_K on the two LLM shapes (K has outlier channels): O, O', L and dQ on sampled rows against
+    the oracle run on the centred K; dK, dV through a dO that is zero outside the sampled rows."""
+    import paper_2603_00040_amd as aq
+    w = W.CONFIGS[cfg]
+    print(f"\n[{w.name}] generating inputs", flush=True)
+    x = W.make_inputs(w, with_do=True)
+    q, k, v, do = to_dev(x["q"]), to_dev(x["k"]), to_dev(x["v"]), to_dev(x["do"])
+    b, kv, qheads, rows = _selection(w)
+    L, Bk = w.L, aq.block_k()
+    sub = _sub(x, b, kv, qheads)
+    sub["k"] = oracle.smooth_k(sub["k"])
+    flat = np.asarray([hi * L + r for hi, rs in enumerate(rows) for r in rs], dtype=np.int64)
+    gi = [(b, h, r) for h, rs in zip(qheads, rows) for r in rs]
+    pick = lambda t: torch.stack([t[bb, hh, rr] for bb, hh, rr in gi])
+    o, lse, ohp = aq.attnqat_fwd_opt(q, k, v, w.causal, aq.OPT_SMOOTH_K)
+    torch.cuda.synchronize()
+    rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, rows=flat)
+    eO = rel_l2(host(pick(o)), rf["O"]); eOp = rel_l2(host(pick(ohp)), rf["Op"]); eL = max_abs(host(pick(lse)), rf["L"])
+    print(f"[{w.name}] smooth-K O rel-L2 {eO:.2e}  O' rel-L2 {eOp:.2e}  L max-abs {eL:.2e}", flush=True)
+    assert eO <= TOL and eOp <= 2e-4 and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
+    dq, _, _ = aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, aq.OPT_SMOOTH_K)
+    torch.cuda.synchronize()
+    rdq = oracle.bwd_dq_rows(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
+    eQ = rel_l2(host(pick(dq)), rdq)
+    print(f"[{w.name}] smooth-K dQ rel-L2 {eQ:.2e}", flush=True)
+    assert eQ <= TOL
+    del dq
+    dos = torch.zeros_like(do)
+    for bb, hh, rr in gi:
+        dos[bb, hh, rr] = do[bb, hh, rr]
+    _, dk, dv = aq.attnqat_bwd_opt(q, k, v, dos, lse, ohp, w.causal, aq.OPT_SMOOTH_K)
+    torch.cuda.synchronize()
+    rdk, rdv = oracle.bwd_rows_dkdv(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
+    eK, eV = rel_l2(host(dk[b, kv]), rdk[0]), rel_l2(host(dv[b, kv]), rdv[0], zero_rms=1e-6)
+    print(f"[{w.name}] smooth-K dK rel-L2 {eK:.2e}  dV rel-L2 {eV:.2e}", flush=True)
+    assert eK <= TOL and eV <= TOL
