@@ -30,7 +30,7 @@ KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "fwd_in
 # Sec. 4.4: peak forward throughput on B200 (NVFP4 QK + FP8 PV) at b=1, s=32768, h=32, d=128.  Another machine and
 # another recipe: context for the forward on that shape, not a target.
 PAPER_FWD_TFLOPS = {"paper_peak_fwd_shape": 2026.0}
-MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 35.5e9, "bwd_dq": 205.2e9, "bwd_dkdv": 737.4e9},
+MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 20.0e9, "bwd_dq": 33.0e9, "bwd_dkdv": 707.4e9},
                           "dit480p_infer": {"fwd_infer_mx": 1.116e9}}       # profiles/dit480p_infer_mx_fwd_kernels.txt
 
 

@@ -203,8 +203,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
 
     const int nqt = Lp / 128;
-    const int bh = blockIdx.x / nqt;
-    int qt = blockIdx.x % nqt;
+    int bh, qt;
+    head_tile_of_block(blockIdx.x, gridDim.x / nqt, nqt, bh, qt);
     if (CAUSAL) qt = nqt - 1 - qt;
     const int b = bh / Hq, h = bh % Hq;
     const int bhkv = b * (Hq / G) + h / G;
@@ -437,8 +437,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
 
     const int nkt = Lp / 128;
-    const int bhkv = blockIdx.x / nkt;
-    const int kt_ = blockIdx.x % nkt;               // key tiles in increasing order: under a causal
+    int bhkv, kt_;
+    head_tile_of_block(blockIdx.x, gridDim.x / nkt, nkt, bhkv, kt_);    // key tiles in increasing order: under a causal
     const int Hkv = Hq / G;                         // mask the first tiles see the most queries
     const int b = bhkv / Hkv, hk = bhkv % Hkv;
     const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;

@@ -190,4 +190,20 @@ __device__ inline void async_copy16(const void* gbase, uint32_t voff, void* lds_
                  :: "v"(voff), "s"(gbase), "s"(lds) : "memory");
 }
 
+// ---- workgroup -> (head, tile) with heads pinned to XCDs ----------------------
+// The dispatcher hands workgroup i to XCD i % 8, and every XCD has its own L2.  All workgroups of a head stream the
+// same K/V (or Q/dO) tiles, so a head is kept on one XCD: XCD x works through heads x, x + 8, ... one after another
+// and its L2 sees one stream at a time instead of eight.  Needs nheads % 8 == 0 (then every XCD gets the same
+// number of workgroups and the map is a bijection); otherwise the plain head-major order is kept.
+__device__ inline void head_tile_of_block(int block, int nheads, int per_head, int& head, int& tile) {
+    if ((nheads & 7) == 0) {
+        const int xcd = block & 7, slot = block >> 3;
+        head = xcd + 8 * (slot / per_head);
+        tile = slot % per_head;
+    } else {
+        head = block / per_head;
+        tile = block % per_head;
+    }
+}
+
 }  // namespace aq

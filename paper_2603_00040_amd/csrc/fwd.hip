@@ -43,8 +43,8 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
 
     const int nqt = (Lp + 255) / 256;
-    const int bh = blockIdx.x / nqt;
-    int qt = blockIdx.x % nqt;
+    int bh, qt;
+    head_tile_of_block(blockIdx.x, gridDim.x / nqt, nqt, bh, qt);
     if (CAUSAL) qt = nqt - 1 - qt;                       // longest rows first
     const int b = bh / Hq, h = bh % Hq;
     const int bhkv = b * (Hq / G) + h / G;

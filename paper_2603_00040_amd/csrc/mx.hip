@@ -238,8 +238,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     extern __shared__ __align__(16) unsigned char smem[];          // 3 stage buffers
 
     const int nqt = Lp / 128;
-    const int bh = blockIdx.x / nqt;
-    int qt = blockIdx.x % nqt;
+    int bh, qt;
+    head_tile_of_block(blockIdx.x, gridDim.x / nqt, nqt, bh, qt);
     if (CAUSAL) qt = nqt - 1 - qt;                                 // longest rows first
     const int b = bh / Hq, h = bh % Hq;
     const int bhkv = b * (Hq / G) + h / G;
