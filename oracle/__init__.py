@@ -64,6 +64,8 @@ def _load():
     L.oracle_e4m3_round.argtypes = [_d, _d]
     L.oracle_phi_mx8.restype = _i
     L.oracle_phi_mx8.argtypes = [_vp, _l, _l, _vp, _vp, _vp]
+    L.oracle_two_level_s1.restype = _d
+    L.oracle_two_level_s1.argtypes = [_d]
     L.oracle_bwd.restype = _i
     L.oracle_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
                              _vp, _vp, _vp]
@@ -210,6 +212,11 @@ def fwd_mx(q, k, v, causal: bool, Bk: int, quant_p: bool = True, rows=None, dump
 
 # ---------------------------------------------------------------- K smoothing
 
+def two_level_s1(rowmax: float) -> float:
+    """Row factor of the two-level quantization of P: the smallest power of two s1 with 2688 s1 >= max(rowmax, 2^-24)."""
+    return _load().oracle_two_level_s1(float(rowmax))
+
+
 def smooth_k(k):
     """K minus its mean over the tokens, per (batch, kv head, channel): the K smoothing of SageAttention that
     Sec. 3.1 describes and Sec. 4.2 switches on inside QAT.  S changes by a per-query constant, which softmax
@@ -224,6 +231,7 @@ def smooth_k(k):
 # ---------------------------------------------------------------- attention
 
 MX = 2      # scale_mode of the MX format: E2M1 blocks of 32 with E8M0 scales, V and P blocked along the keys
+TWO_LEVEL_P = 4  # NVFP4 with SageAttention3's two-level quantization of P (row factor, then blocks of 16); Bk = 64
 MX_FP8PV = 3    # mixed recipe: Q, K as in MX (FP4), V and P in MXFP8 (E4M3 elements, same blocks and scale format)
 
 
@@ -233,8 +241,9 @@ def _prep_qkv(q, k, v, quant_qkv, scale_mode):
         q, k, v = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx(v, axis=-2)
     elif quant_qkv and scale_mode == MX_FP8PV:
         q, k, v = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx8(v, axis=-2)
-    elif quant_qkv:    # Alg. 2 first line: Q^F, K^F, V^F
-        q, k, v = fake_quant(q, scale_mode), fake_quant(k, scale_mode), fake_quant(v, scale_mode)
+    elif quant_qkv:    # Alg. 2 first line: Q^F, K^F, V^F (the two-level option only concerns P)
+        sm = 0 if scale_mode == TWO_LEVEL_P else scale_mode
+        q, k, v = fake_quant(q, sm), fake_quant(k, sm), fake_quant(v, sm)
     return q, k, v
 
 

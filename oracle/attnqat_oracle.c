@@ -250,6 +250,38 @@ int oracle_phi_mx8(const float* x, long nrows, long n, uint8_t* codes, uint8_t* 
     return 0;
 }
 
+/* ------------------------------------------------- two-level quantization of P */
+
+/* SageAttention3's two-level scheme as Sec. 3.1 describes it and Sec. 4.2 switches on inside QAT
+ * (scale_mode 4): every row of a P tile is first rescaled so that its maximum lands just below
+ * 448 * 6 (the largest block scale times the largest element), then quantized as usual in NVFP4
+ * blocks of 16.  Readings: a "row" is the 64 keys of one key tile (TWO_LEVEL_SPAN, the key tile
+ * of the forward; the backward uses the same aligned groups); the row factor is rounded up to a
+ * power of two, s1 = the smallest 2^k with 2688 * 2^k >= max(rowmax, 2^-24), so that the rescale
+ * is exact in every number format involved (the row maximum lands in (1344, 2688]) and rows
+ * without any mass do not produce unbounded factors. */
+#define TWO_LEVEL_SPAN 64
+static double two_level_s1(double rowmax)
+{
+    double base = rowmax > ldexp(1.0, -24) ? rowmax : ldexp(1.0, -24);
+    int k = -60;
+    while (ldexp(2688.0, k) < base) ++k;
+    return ldexp(1.0, k);
+}
+double oracle_two_level_s1(double rowmax) { return two_level_s1(rowmax); }
+
+/* phi^-1(phi(.)) of n (a multiple of 16, <= 64) values of one row of a P tile with the two levels. */
+static void phi_two_level(const double* P, int n, double* Pf)
+{
+    double rmax = 0.0;
+    for (int k = 0; k < n; ++k) if (P[k] > rmax) rmax = P[k];
+    const double s1 = two_level_s1(rmax);
+    double P2[TWO_LEVEL_SPAN], Pf2[TWO_LEVEL_SPAN];
+    for (int k = 0; k < n; ++k) P2[k] = P[k] / s1;                 /* exact: a power of two */
+    for (int k = 0; k < n; k += 16) phi_block(P2 + k, 16, 0, NULL, NULL, NULL, Pf2 + k);
+    for (int k = 0; k < n; ++k) Pf[k] = s1 * Pf2[k];
+}
+
 /* ------------------------------------------------------------------ forward */
 
 static double dot(const float* a, const float* b, int d)
@@ -274,8 +306,9 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                     long nrows, const long* rows,
                     double* O, double* Op, double* Lse, float* Pdump)
 {
-    const int pb = mx ? 32 : 16;               /* keys per P block */
+    const int pb = (mx == 1 || mx == 2) ? 32 : 16;               /* keys per P block */
     if (!qf || !kf || !vf || Hq % Hkv || Bk < pb || Bk % pb || d < 1) return -1;
+    if (mx == 3 && Bk != TWO_LEVEL_SPAN) return -1;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     if (!rows) nrows = (long)B * Hq * L;
@@ -317,7 +350,9 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                     rowsum += Pt[k];
                 }
                 for (int k = nk; k < Bk; ++k) Pt[k] = 0.0;      /* masked keys */
-                if (quant_p) {
+                if (quant_p && mx == 3) {
+                    phi_two_level(Pt, Bk, Pf);                  /* the whole tile row, masked keys are 0 */
+                } else if (quant_p) {
                     for (int k = 0; k < nk; k += pb) {
                         if (mx == 2) phi_mx8_block(Pt + k, pb, NULL, NULL, Pf + k);
                         else if (mx) phi_mx_block(Pt + k, pb, NULL, NULL, Pf + k);
@@ -352,7 +387,8 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
 
 /* scale_mode 2: the MX format (qf, kf, vf are then the MX fake-quantized tensors, V blocked along
  * the keys, and P-tilde is quantized in MX blocks of 32 keys).  scale_mode 3: the same with MXFP8
- * (E4M3 elements) for P-tilde (and, in the caller's vf, for V). */
+ * (E4M3 elements) for P-tilde (and, in the caller's vf, for V).  scale_mode 4: NVFP4 with the
+ * two-level quantization of P-tilde (Bk must be 64). */
 int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
                     int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
                     int quant_p, int scale_mode,
@@ -360,7 +396,7 @@ int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
                     double* O, double* Op, double* Lse, float* Pdump)
 {
     return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode,
-                         scale_mode == 2 ? 1 : scale_mode == 3 ? 2 : 0,
+                         scale_mode == 2 ? 1 : scale_mode == 3 ? 2 : scale_mode == 4 ? 3 : 0,
                          nrows, rows, O, Op, Lse, Pdump);
 }
 
@@ -368,15 +404,29 @@ int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
 
 /* Keys per P block: 16 (NVFP4), 32 in the MX formats (scale_mode 2 and 3). */
 #define PB_MAX 32
-static int pb_of(int scale_mode) { return scale_mode >= 2 ? 32 : 16; }
+static int pb_of(int scale_mode) { return (scale_mode == 2 || scale_mode == 3) ? 32 : 16; }
 
 /*
  * One query row against one aligned block of pb keys [k0, k0+pb): the inner
  * statements of Alg. 3.  nvis = number of keys of the block the row may see
- * (the rest are masked: P = 0).  Returns P (fp32-rounded), P^F and dS.
+ * (the rest are masked: P = 0), kend = end of the row's visible keys.  Returns P (fp32-rounded),
+ * P^F and dS.
  */
+/* Two-level P in the backward: the row factor of the aligned group of 64 keys that holds block k0
+ * (keys >= kend are masked: P = 0). */
+static double span_s1(const float* qrow, double lse, const float* kh, long k0, long kend, int d, double rs)
+{
+    long s0 = k0 - k0 % TWO_LEVEL_SPAN;
+    double rmax = 0.0;
+    for (long k = s0; k < s0 + TWO_LEVEL_SPAN && k < kend; ++k) {
+        double p = (double)(float)exp(dot(qrow, kh + k * d, d) * rs - lse);
+        if (p > rmax) rmax = p;
+    }
+    return two_level_s1(rmax);
+}
+
 static void bwd_block(const float* qrow, const float* dorow, double lse, double D,
-                      const float* kh, const float* vh, long k0, int nvis, int d, double rs,
+                      const float* kh, const float* vh, long k0, int nvis, long kend, int d, double rs,
                       int quant_p, int scale_mode, double* P, double* Pf, double* dS)
 {
     const int pb = pb_of(scale_mode);
@@ -386,7 +436,14 @@ static void bwd_block(const float* qrow, const float* dorow, double lse, double 
             P[k] = (double)(float)exp(s - lse);
         } else P[k] = 0.0;
     }
-    if (quant_p && scale_mode == 3) phi_mx8_block(P, pb, NULL, NULL, Pf);
+    if (quant_p && scale_mode == 4) {
+        const double s1 = span_s1(qrow, lse, kh, k0, kend, d, rs);
+        double P2[16], Pf2[16];
+        for (int k = 0; k < 16; ++k) P2[k] = P[k] / s1;
+        phi_block(P2, 16, 0, NULL, NULL, NULL, Pf2);
+        for (int k = 0; k < 16; ++k) Pf[k] = s1 * Pf2[k];
+    }
+    else if (quant_p && scale_mode == 3) phi_mx8_block(P, pb, NULL, NULL, Pf);
     else if (quant_p && scale_mode == 2) phi_mx_block(P, pb, NULL, NULL, Pf);
     else if (quant_p) phi_block(P, pb, scale_mode, NULL, NULL, NULL, Pf);
     else for (int k = 0; k < pb; ++k) Pf[k] = P[k];
@@ -437,7 +494,7 @@ int oracle_bwd(const float* qf, const float* kf, const float* vf, const float* d
                 for (long k0 = 0; k0 < kend; k0 += pb) {
                     double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
                     int nv = nvis_of(k0, kend, pb);
-                    bwd_block(qrow, dorow, Lse[rid], D, kh, vh, k0, nv, d, rs,
+                    bwd_block(qrow, dorow, Lse[rid], D, kh, vh, k0, nv, kend, d, rs,
                               quant_p, scale_mode, P, Pf, dS);
                     for (int k = 0; k < nv; ++k) {
                         long kr = (u * L + k0 + k) * d;
@@ -481,7 +538,7 @@ int oracle_bwd_dq_rows(const float* qf, const float* kf, const float* vf, const 
         for (long k0 = 0; k0 < kend; k0 += pb) {
             double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
             int nv = nvis_of(k0, kend, pb);
-            bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, d, rs,
+            bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, kend, d, rs,
                       quant_p, scale_mode, P, Pf, dS);
             for (int k = 0; k < nv; ++k)
                 for (int c = 0; c < d; ++c)
@@ -529,7 +586,7 @@ int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, cons
                 long rid = ((long)b * Hq + hk * G + g) * L + i;
                 double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
                 bwd_block(qf + rid * d, dO + rid * d, Lse_grp[g * L + i], Dg[g * L + i],
-                          kh, vh, k0, nvis_of(k0, kend, pb), d, rs, quant_p, scale_mode, P, Pf, dS);
+                          kh, vh, k0, nvis_of(k0, kend, pb), kend, d, rs, quant_p, scale_mode, P, Pf, dS);
                 for (int c = 0; c < d; ++c) {
                     dV_keys[n * d + c] += Pf[kk] * (double)dO[rid * d + c];
                     dK_keys[n * d + c] += dS[kk] * (double)qf[rid * d + c];
@@ -575,7 +632,7 @@ int oracle_bwd_rows_dkdv(const float* qf, const float* kf, const float* vf, cons
             long k0 = kb * pb;
             double P[PB_MAX], Pf[PB_MAX], dS[PB_MAX];
             int nv = nvis_of(k0, kend, pb);
-            bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, d, rs, quant_p, scale_mode, P, Pf, dS);
+            bwd_block(qrow, dorow, Lse_rows[n], D, kh, vh, k0, nv, kend, d, rs, quant_p, scale_mode, P, Pf, dS);
             for (int k = 0; k < nv; ++k) {
                 long kr = (u * L + k0 + k) * d;
                 for (int c = 0; c < d; ++c) {
