@@ -52,12 +52,15 @@ def main():
                          "mx_fp8pv: the mixed recipe (FP4 Q K^T, MXFP8 P V), inference forward only")
     ap.add_argument("--smooth-k", action="store_true",
                     help="K smoothing option of Sec. 4.2 (nvfp4 format only): phi on K minus its token mean")
+    ap.add_argument("--two-level-p", action="store_true",
+                    help="two-level quantization of P, the other option of Sec. 4.2 (nvfp4 format only)")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     args = ap.parse_args()
-    if args.smooth_k and (args.format != "nvfp4" or args.ablation):
-        print("bench.py: --smooth-k goes with --format nvfp4 and no ablation", file=sys.stderr)
+    if (args.smooth_k or args.two_level_p) and (args.format != "nvfp4" or args.ablation):
+        print("bench.py: --smooth-k and --two-level-p go with --format nvfp4 and no ablation", file=sys.stderr)
         sys.exit(2)
+    opts = (1 if args.smooth_k else 0) | (2 if args.two_level_p else 0)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(heads shard across GPUs without communication, see DESIGN.md)", file=sys.stderr)
@@ -97,8 +100,8 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
 
     def fwd():
-        if args.smooth_k:
-            aq.attnqat_fwd_opt(q, k, v, w.causal, aq.OPT_SMOOTH_K, train=train, workspace=ws, out=(o, lse, ohp if train else None))
+        if opts:
+            aq.attnqat_fwd_opt(q, k, v, w.causal, opts, train=train, workspace=ws, out=(o, lse, ohp if train else None))
         elif train:
             (aq.attnqat_fwd_mx if mx else aq.attnqat_fwd)(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
         elif fp8pv:
@@ -109,8 +112,8 @@ def main():
             aq.attnqat_fwd_infer(q, k, v, w.causal, workspace=ws, out=(o, lse))
 
     def bwd():
-        if args.smooth_k:
-            aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, aq.OPT_SMOOTH_K, workspace=ws, out=(dq, dk, dv))
+        if opts:
+            aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, opts, workspace=ws, out=(dq, dk, dv))
         elif args.ablation:
             aq.attnqat_bwd_ablation(q, k, v, do, lse, ohp, o, w.causal, args.ablation, workspace=ws, out=(dq, dk, dv))
         else:
@@ -145,7 +148,7 @@ def main():
                 kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
     aq.profile_enable(False)
     pf_frac = None
-    if train and (args.ablation & 2 or mx):
+    if train and (args.ablation & 2 or mx or args.two_level_p):
         pf_frac = 1.0                    # the un-quantized P is never skipped; an MX P^F tile is zero only if P itself is
     elif train:
         # how many 32x32 tiles of the dK/dV pass had a non-zero P^F (the others skip the dV products, exactly)
@@ -179,7 +182,7 @@ def main():
 
     cpu = None
     if args.cpu_seconds > 0:
-        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k)
+        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k, args.two_level_p)
 
     out = {
         "metric": "FP4-attention fwd+bwd TFLOPS (1 MI355X)" if train else "FP4-attention fwd TFLOPS (1 MI355X)",
@@ -192,7 +195,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
                    "passes": w.passes if train else "fwd_infer", "block_k": aq.block_k(), "seed": w.seed,
-                   "bwd_ablation": args.ablation, "format": args.format, "smooth_k": bool(args.smooth_k)},
+                   "bwd_ablation": args.ablation, "format": args.format, "smooth_k": bool(args.smooth_k), "two_level_p": bool(args.two_level_p)},
         "fwd_tflops": round(w.fwd_flops / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
         "fwd_ms": round(fwd_ms, 3),
         "frac_of_mfma_peak_model_flops": round(value / peak, 4),
@@ -203,7 +206,7 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False):
+def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False, two_level=False):
     """Time the oracle (as it stands) on a bounded sample of the same workload: forward of
     sampled query rows and, for training workloads, dQ of the same rows."""
     import numpy as np
@@ -223,7 +226,7 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k
     def run(n):
         rows = np.sort(rng.choice(w.L, size=min(n, w.L), replace=False)).astype(np.int64)
         t0 = time.perf_counter()
-        sm = oracle.MX_FP8PV if fp8pv else oracle.MX if mx else 0
+        sm = oracle.MX_FP8PV if fp8pv else oracle.MX if mx else oracle.TWO_LEVEL_P if two_level else 0
         r = oracle.fwd(f["q"], f["k"], f["v"], w.causal, block_k, scale_mode=sm, rows=rows)
         if train:
             oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal, scale_mode=sm)

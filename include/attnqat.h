@@ -155,12 +155,18 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
  *                          fp64 sum / L rounded to fp32, the subtraction an fp32 subtraction.  dK is the gradient
  *                          with respect to the centred K, which equals the gradient with respect to K because
  *                          rowsum(dS) = 0 when D comes from O' (Sec. 3.3).
+ *   ATTNQAT_OPT_TWO_LEVEL_P  two-level quantization of P (Sec. 3.1): every row of a 64-key tile of P-tilde (forward)
+ *                          or P (backward, the same aligned groups of 64 keys) is divided by s1, the smallest power
+ *                          of two with 448 * 6 * s1 >= max(row maximum, 2^-24), quantized in NVFP4 blocks of 16 and
+ *                          multiplied back, so that blocks far below the row maximum of the whole sequence keep
+ *                          their values instead of under-flowing the E4M3 scale.  Only P^F changes (O, dV).
  * attnqat_fwd_opt: o_hp != NULL selects the training forward (Alg. 2), NULL the inference forward (Alg. 1).
  * attnqat_bwd_opt must be given the same options as the forward whose lse and o_hp it consumes.
  * options = 0 is attnqat_fwd / attnqat_fwd_infer / attnqat_bwd; unknown bits: ATTNQAT_EINVAL.
  * Workspace sizes: ATTNQAT_WS_FWD and ATTNQAT_WS_BWD.
  */
 #define ATTNQAT_OPT_SMOOTH_K        1
+#define ATTNQAT_OPT_TWO_LEVEL_P     2
 int attnqat_fwd_opt(const void* q, const void* k, const void* v,
                     int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
                     void* o, float* lse, float* o_hp,
@@ -170,6 +176,12 @@ int attnqat_bwd_opt(const void* q, const void* k, const void* v, const void* d_o
                     int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
                     void* dq, void* dk, void* dv,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* attnqat_debug_fwd_p with the option bits of attnqat_fwd_opt (workspace ATTNQAT_WS_FWD). */
+int attnqat_debug_fwd_p_opt(const void* q, const void* k, const void* v,
+                            int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
+                            void* o, float* lse, int row0, float* p_dump,
+                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * MX variant of phi: the OCP microscaling FP4 format that Sec. 3.1 names beside NVFP4

@@ -255,12 +255,15 @@ int oracle_phi_mx8(const float* x, long nrows, long n, uint8_t* codes, uint8_t* 
 /* SageAttention3's two-level scheme as Sec. 3.1 describes it and Sec. 4.2 switches on inside QAT
  * (scale_mode 4): every row of a P tile is first rescaled so that its maximum lands just below
  * 448 * 6 (the largest block scale times the largest element), then quantized as usual in NVFP4
- * blocks of 16.  Readings: a "row" is the 64 keys of one key tile (TWO_LEVEL_SPAN, the key tile
- * of the forward; the backward uses the same aligned groups); the row factor is rounded up to a
+ * blocks of 16.  Readings: a "row" is a row of the P tile of the pass: the 64 keys of one key tile
+ * in the forward (TWO_LEVEL_SPAN = B_k), aligned groups of 32 keys in the backward
+ * (TWO_LEVEL_SPAN_BWD, the width of the backward's P tiles; SageAttention3 is inference only and
+ * fixes nothing there); the row factor is rounded up to a
  * power of two, s1 = the smallest 2^k with 2688 * 2^k >= max(rowmax, 2^-24), so that the rescale
  * is exact in every number format involved (the row maximum lands in (1344, 2688]) and rows
  * without any mass do not produce unbounded factors. */
 #define TWO_LEVEL_SPAN 64
+#define TWO_LEVEL_SPAN_BWD 32
 static double two_level_s1(double rowmax)
 {
     double base = rowmax > ldexp(1.0, -24) ? rowmax : ldexp(1.0, -24);
@@ -412,13 +415,13 @@ static int pb_of(int scale_mode) { return (scale_mode == 2 || scale_mode == 3) ?
  * (the rest are masked: P = 0), kend = end of the row's visible keys.  Returns P (fp32-rounded),
  * P^F and dS.
  */
-/* Two-level P in the backward: the row factor of the aligned group of 64 keys that holds block k0
- * (keys >= kend are masked: P = 0). */
+/* Two-level P in the backward: the row factor of the aligned group of TWO_LEVEL_SPAN_BWD keys that
+ * holds block k0 (keys >= kend are masked: P = 0). */
 static double span_s1(const float* qrow, double lse, const float* kh, long k0, long kend, int d, double rs)
 {
-    long s0 = k0 - k0 % TWO_LEVEL_SPAN;
+    long s0 = k0 - k0 % TWO_LEVEL_SPAN_BWD;
     double rmax = 0.0;
-    for (long k = s0; k < s0 + TWO_LEVEL_SPAN && k < kend; ++k) {
+    for (long k = s0; k < s0 + TWO_LEVEL_SPAN_BWD && k < kend; ++k) {
         double p = (double)(float)exp(dot(qrow, kh + k * d, d) * rs - lse);
         if (p > rmax) rmax = p;
     }

@@ -35,6 +35,8 @@ _SIGNATURES = {
     "attnqat_fwd_opt": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_opt": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
                              _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_debug_fwd_p_opt": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
+                                     _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                             _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -118,7 +120,20 @@ def attnqat_quantize(x, want_codes=True, want_xf=True):
     return codes, scales, xf
 
 
-OPT_SMOOTH_K = 1
+OPT_SMOOTH_K, OPT_TWO_LEVEL_P = 1, 2
+
+
+def attnqat_debug_fwd_p_opt(q, k, v, causal: bool, row0: int, options: int):
+    """attnqat_debug_fwd_p with the option bits of attnqat_fwd_opt."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+    p = torch.zeros((B, Hq, 128, L), dtype=torch.float32, device=q.device)
+    ws, nb = _workspace(WS_FWD, B, Hq, Hkv, L, d, None)
+    _check(lib().attnqat_debug_fwd_p_opt(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16, int(options),
+                                         _ptr(o), _ptr(lse), row0, _ptr(p), _ptr(ws), nb, _stream()))
+    return o, lse, p
 
 
 def attnqat_fwd_opt(q, k, v, causal: bool, options: int, train: bool = True, workspace=None, out=None):

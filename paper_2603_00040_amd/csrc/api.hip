@@ -118,7 +118,7 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
                int dump_row0, float* p_dump, void* workspace, size_t workspace_bytes, void* stream, int options = 0)
 {
     if (!q || !k || !v || !o || !lse || (train && !o_hp)) return ATTNQAT_EINVAL;
-    if ((options & ~ATTNQAT_OPT_SMOOTH_K) || (options && mx)) return ATTNQAT_EINVAL;
+    if ((options & ~(ATTNQAT_OPT_SMOOTH_K | ATTNQAT_OPT_TWO_LEVEL_P)) || (options && mx)) return ATTNQAT_EINVAL;
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
     FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d, mx);
@@ -135,7 +135,8 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
     if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kh, nullptr, w.tmp, st, kmean)) return ATTNQAT_ELAUNCH;
     if (quant_copy(v, B * Hkv, L, d, mx, 1, true, nullptr, w.vt, w.tmp, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkv", st);
-    if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, mx, o, lse, o_hp, dump_row0, p_dump, st))
+    const int p_quant = mx ? 1 : (options & ATTNQAT_OPT_TWO_LEVEL_P) ? 2 : 0;
+    if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, p_quant, o, lse, o_hp, dump_row0, p_dump, st))
         return ATTNQAT_ELAUNCH;
     prof_mark(train ? "fwd_train" : "fwd_infer", st);
     return ATTNQAT_OK;
@@ -316,6 +317,16 @@ int attnqat_fwd_opt(const void* q, const void* k, const void* v,
                       workspace, workspace_bytes, stream, options);
 }
 
+int attnqat_debug_fwd_p_opt(const void* q, const void* k, const void* v,
+                            int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
+                            void* o, float* lse, int row0, float* p_dump,
+                            void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!p_dump || row0 < 0 || row0 % 128 != 0) return ATTNQAT_EINVAL;
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, false, o, lse, nullptr, row0, p_dump,
+                      workspace, workspace_bytes, stream, options);
+}
+
 int attnqat_fwd_mx(const void* q, const void* k, const void* v,
                    int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                    void* o, float* lse, float* o_hp,
@@ -336,13 +347,14 @@ int attnqat_debug_fwd_p_mx(const void* q, const void* k, const void* v,
 }
 
 static int bwd_common(const void* q, const void* k, const void* v, const void* d_o,
-                      const float* lse, const void* o_acc, bool o_is_bf16, int p_quant /* 0 none, 1 NVFP4, 2 MX */,
+                      const float* lse, const void* o_acc, bool o_is_bf16, int p_quant /* 0 none, 1 NVFP4, 2 MX; 3 (two-level) is set from the options */,
                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                       void* dq, void* dk, void* dv,
                       void* workspace, size_t workspace_bytes, void* stream, int options = 0)
 {
     if (!q || !k || !v || !d_o || !lse || !o_acc || !dq || !dk || !dv) return ATTNQAT_EINVAL;
-    if ((options & ~ATTNQAT_OPT_SMOOTH_K) || (options && p_quant == 2)) return ATTNQAT_EINVAL;
+    if ((options & ~(ATTNQAT_OPT_SMOOTH_K | ATTNQAT_OPT_TWO_LEVEL_P)) || (options && p_quant != 1)) return ATTNQAT_EINVAL;
+    if (options & ATTNQAT_OPT_TWO_LEVEL_P) p_quant = 3;
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
     const bool mx = p_quant == 2;

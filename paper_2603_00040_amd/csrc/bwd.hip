@@ -423,7 +423,7 @@ struct DkvSmem {
 };
 
 template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */,
-          int PQ /* phi(P): 0 none (ablation: dV from the fp32 P), 1 NVFP4, 2 MX */>
+          int PQ /* phi(P): 0 none (ablation: dV from the fp32 P), 1 NVFP4, 2 MX, 3 NVFP4 after the two-level row factor */>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
@@ -604,16 +604,33 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 sc[0] = sc[1] = e8m0_as_f32(byte);
                 inv[0] = inv[1] = e8m0_inverse_as_f32(byte);
                 nz = amax > 0.0f;
-            } else
+            } else {
+                // Two-level quantization of P (PQ == 3): a row of this wave's tile (32 aligned keys) is divided by s1,
+                // the smallest power of two with 2688 s1 >= max(row maximum, 2^-24), before the NVFP4 blocks
+                float s1 = 1.0f, inv1 = 1.0f;
+                float amax[2];
 #pragma unroll
-            for (int gq = 0; gq < 2; ++gq) {
-                float amax = s[8 * gq];
+                for (int gq = 0; gq < 2; ++gq) {
+                    amax[gq] = s[8 * gq];
 #pragma unroll
-                for (int i = 1; i < 8; ++i) amax = fmaxf(amax, s[8 * gq + i]);
-                amax = xhalf_max(amax);
-                sc[gq] = rne_e4m3_grid(amax * (1.0f / 6.0f));
-                inv[gq] = sc[gq] > 0.0f ? __builtin_amdgcn_rcpf(sc[gq]) : 0.0f;
-                nz = nz || sc[gq] > 0.0f;
+                    for (int i = 1; i < 8; ++i) amax[gq] = fmaxf(amax[gq], s[8 * gq + i]);
+                    amax[gq] = xhalf_max(amax[gq]);
+                }
+                if constexpr (PQ == 3) {
+                    const float base = fmaxf(fmaxf(amax[0], amax[1]), 5.9604644775390625e-08f);
+                    const uint32_t e1 = ((__float_as_uint(base) + 0x0057FFFFu) >> 23) - 11u;      // 2688 = 1.3125 * 2^11
+                    s1 = __uint_as_float(e1 << 23);
+                    inv1 = __uint_as_float((254u - e1) << 23);
+                }
+#pragma unroll
+                for (int gq = 0; gq < 2; ++gq) {
+                    const float s2 = rne_e4m3_grid((amax[gq] * inv1) * (1.0f / 6.0f));
+                    // P^F = (s1 s2) * code and the code is RNE(P / (s1 s2)): from here on the product of the two levels
+                    // stands in for the block scale (a power of two times an E4M3 value: still exact in bf16)
+                    sc[gq] = s2 * s1;
+                    inv[gq] = s2 > 0.0f ? __builtin_amdgcn_rcpf(s2) * inv1 : 0.0f;
+                    nz = nz || s2 > 0.0f;
+                }
             }
             // dS = P (dP - D_i)/sqrt(d) from the fp32 P, scaled, as fp16, staged as [query][key]
 #pragma unroll
@@ -746,6 +763,7 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
     const size_t smem = sizeof(DkvSmem<D>);
     auto kern = p_quant == 0 ? bwd_dkdv_kernel<D, CAUSAL, false, 0>
               : p_quant == 2 ? bwd_dkdv_kernel<D, CAUSAL, false, 2>
+              : p_quant == 3 ? bwd_dkdv_kernel<D, CAUSAL, false, 3>
               : tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true, 1> : bwd_dkdv_kernel<D, CAUSAL, false, 1>;
     if (p_quant != 1) tile_counts = nullptr;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)

@@ -28,7 +28,7 @@ struct FwdSmem {
     half_t v[2][D * 64];      // V^T tile [d][key], likewise
 };
 
-template <int D, bool TRAIN, bool CAUSAL, bool DUMP, bool MXP>
+template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ /* phi(P-tilde): 0 NVFP4, 1 MX, 2 NVFP4 with the two-level row factor */>
 __global__ __launch_bounds__(512, 2) void fwd_kernel(
     const half_t* __restrict__ Qh, const half_t* __restrict__ Kh, const half_t* __restrict__ Vt,
     uint16_t* __restrict__ O, float* __restrict__ lse, float* __restrict__ Ohp,
@@ -105,6 +105,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         for (int i = 0; i < 16; ++i) { o[mb][i] = 0.0f; if constexpr (TRAIN) op[mb][i] = 0.0f; }
     }
     float m = -INFINITY, lsum = 0.0f;     // lsum: this half-wave's part of l (same alpha in both halves)
+    float s1_prev = 1.0f, s1_cur = 1.0f;  // two-level P-tilde: the row factor O is currently expressed in, and this tile's
     floatx16 s[2];                        // S^T of the current tile, then P-tilde
 #pragma unroll
     for (int i = 0; i < 16; ++i) { s[0][i] = 0.0f; s[1][i] = 0.0f; }
@@ -202,13 +203,38 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         lsum = lsum * alpha + ((rp[0] + rp[1]) + (rp[2] + rp[3]));          // un-quantized P-tilde
         // rescale: exact no-op unless some row of this wave moved its maximum (rare after the
         // first tiles), so it lives on the cold path
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0, 0)) {
+        float inv1 = 1.0f;
+        if constexpr (PQ == 2) {
+            // Two-level quantization of P-tilde (Sec. 3.1): the row of this tile is divided by s1, the smallest power
+            // of two with 2688 s1 >= max(row maximum, 2^-24), before the NVFP4 blocks.  The row maximum is exp2 of the
+            // tile's largest score, the same instructions on the same inputs as that element's P-tilde.
+            // O is kept in units of the current s1 (its products use P-tilde / s1, which fp16 holds exactly whatever
+            // the magnitude of the row), so it is re-based on every tile; O' only needs alpha.
+            const float base = fmaxf(__builtin_amdgcn_exp2f(fmaf(mt, c, -ms)), 5.9604644775390625e-08f);
+            const uint32_t e1 = ((__float_as_uint(base) + 0x0057FFFFu) >> 23) - 11u;      // 2688 = 1.3125 * 2^11
+            s1_cur = __uint_as_float(e1 << 23);
+            inv1 = __uint_as_float((254u - e1) << 23);
+            const float f = alpha * s1_prev * inv1;
+            s1_prev = s1_cur;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[mb][i] *= f;
+            if constexpr (TRAIN) {
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0, 0)) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) op[mb][i] *= alpha;
+                }
+            }
+        } else if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0, 0)) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { o[mb][i] *= alpha; if constexpr (TRAIN) op[mb][i] *= alpha; }
         }
-        if constexpr (MXP) {
+        if constexpr (PQ == 1) {
             // MX format: one power-of-two scale per 32 keys = all 16 registers of s[kb] in both halves;
             // the two 16-key groups of a block share it
 #pragma unroll
@@ -235,10 +261,11 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) bsc[ks] = xhalf_max(bsc[ks]);
+        // (two-level: the block maxima of P-tilde / s1 are at most 2688 (1 + 2^-23), whose sixth rounds to 448, the largest scale)
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) bsc[ks] = rne_e4m3_grid(bsc[ks] * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
+        for (int ks = 0; ks < 4; ++ks) bsc[ks] = rne_e4m3_grid((bsc[ks] * inv1) * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) binv[ks] = bsc[ks] > 0.0f ? __builtin_amdgcn_rcpf(bsc[ks]) : 0.0f;
+        for (int ks = 0; ks < 4; ++ks) binv[ks] = bsc[ks] > 0.0f ? __builtin_amdgcn_rcpf(bsc[ks]) * inv1 : 0.0f;
     };
     // ---- matrix phase of one key tile: O, O' += V^F^T P with the FP4 round trip of P-tilde in between
     auto matrix_phase = [&](int j, const float (&bsc)[4], const float (&binv)[4]) __attribute__((always_inline)) {
@@ -279,7 +306,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
                         for (int i = 0; i < 8; ++i) {
                             const int key = k0 + 32 * (ks >> 1) + 16 * (ks & 1) + 8 * (i >> 2) + 4 * hf + (i & 3);
                             if (key < L)
-                                pdump[((size_t)bh * 128 + (q_row - dump_row0)) * L + key] = pfv[i];
+                                pdump[((size_t)bh * 128 + (q_row - dump_row0)) * L + key] = PQ == 2 ? pfv[i] * s1_cur : pfv[i];
                         }
                     }
                 }
@@ -366,6 +393,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     // ---- epilogue: O /= l, O' /= l, L = m + log l
     const float l = xhalf_sum(lsum);
     const float inv_l = 1.0f / l;
+    const float inv_lo = PQ == 2 ? s1_prev * inv_l : inv_l;      // O leaves the units of the last row factor
     if (q_row < L) {
         const size_t row = (size_t)bh * L + q_row;
 #pragma unroll
@@ -374,8 +402,8 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
             for (int t = 0; t < 4; ++t) {
                 const int d0 = 32 * mb + 8 * t + 4 * hf;
                 uint2v w;
-                w[0] = pack_bf16x2_rne(o[mb][4 * t] * inv_l, o[mb][4 * t + 1] * inv_l);
-                w[1] = pack_bf16x2_rne(o[mb][4 * t + 2] * inv_l, o[mb][4 * t + 3] * inv_l);
+                w[0] = pack_bf16x2_rne(o[mb][4 * t] * inv_lo, o[mb][4 * t + 1] * inv_lo);
+                w[1] = pack_bf16x2_rne(o[mb][4 * t + 2] * inv_lo, o[mb][4 * t + 3] * inv_lo);
                 *reinterpret_cast<uint2v*>(O + row * D + d0) = w;
                 if constexpr (TRAIN) {
                     floatx4 f;
@@ -388,14 +416,14 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     }
 }
 
-template <int D, bool TRAIN, bool CAUSAL, bool DUMP, bool MXP>
+template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ>
 static int launch_t(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int L,
                     void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int nqt = (Lp + 255) / 256;
     const size_t smem = sizeof(FwdSmem<D>);
-    auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP, MXP>;
+    auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP, PQ>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)smem) != hipSuccess) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
@@ -405,31 +433,31 @@ static int launch_t(const void* qh, const void* kh, const void* vt, int B, int H
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-template <int D, bool MXP>
+template <int D, int PQ>
 static int launch_d(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int L,
                     bool causal, bool train, void* o, float* lse, float* o_hp,
                     int dump_row0, float* p_dump, hipStream_t st)
 {
     if (p_dump) {
-        return causal ? launch_t<D, false, true, true, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st)
-                      : launch_t<D, false, false, true, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st);
+        return causal ? launch_t<D, false, true, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st)
+                      : launch_t<D, false, false, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st);
     }
     if (train) {
-        return causal ? launch_t<D, true, true, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
-                      : launch_t<D, true, false, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+        return causal ? launch_t<D, true, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
+                      : launch_t<D, true, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
     }
-    return causal ? launch_t<D, false, true, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
-                  : launch_t<D, false, false, false, MXP>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+    return causal ? launch_t<D, false, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
+                  : launch_t<D, false, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
 }
 
 int launch_fwd(const void* qh, const void* kh, const void* vt,
-               int B, int Hq, int Hkv, int L, int D, bool causal, bool train, bool mx_p,
+               int B, int Hq, int Hkv, int L, int D, bool causal, bool train, int p_quant,
                void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st)
 {
-    if (D == 128) return mx_p ? launch_d<128, true>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st)
-                              : launch_d<128, false>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st);
-    if (D == 64)  return mx_p ? launch_d<64, true>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st)
-                              : launch_d<64, false>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st);
+#define AQ_FWD(DD, PQ) launch_d<DD, PQ>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st)
+    if (D == 128) return p_quant == 1 ? AQ_FWD(128, 1) : p_quant == 2 ? AQ_FWD(128, 2) : AQ_FWD(128, 0);
+    if (D == 64)  return p_quant == 1 ? AQ_FWD(64, 1) : p_quant == 2 ? AQ_FWD(64, 2) : AQ_FWD(64, 0);
+#undef AQ_FWD
     return -1;
 }
 

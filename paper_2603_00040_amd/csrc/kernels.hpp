@@ -21,9 +21,10 @@ size_t colmean_scratch_bytes(int BH, int D);
 int launch_colmean(const void* x, int BH, int L, int D, double* scratch, float* mean, hipStream_t st);
 
 // Alg. 1 (train=false) / Alg. 2 (train=true) on fp16 copies made by launch_prep.
-// mx_p: phi(P-tilde) in the MX format (blocks of 32 keys, power-of-two scale) instead of NVFP4.
+// p_quant: phi(P-tilde) 0 NVFP4; 1 in the MX format (blocks of 32 keys, power-of-two scale); 2 NVFP4 after the
+// two-level row factor (every 64-key tile row divided by a power of two that brings its maximum just below 448 * 6).
 int launch_fwd(const void* qh, const void* kh, const void* vt,
-               int B, int Hq, int Hkv, int L, int D, bool causal, bool train, bool mx_p,
+               int B, int Hq, int Hkv, int L, int D, bool causal, bool train, int p_quant,
                void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st);
 
 // Per-row statistics of the backward: rowstat [BHq, Lp, 2] = {L log2(e), D / sqrt(d)} with
@@ -47,7 +48,7 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
                     const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
                     unsigned long long* tile_counts /* may be null */,
-                    int p_quant /* phi(P): 0 none (ablation), 1 NVFP4, 2 MX */, hipStream_t st);
+                    int p_quant /* phi(P): 0 none (ablation), 1 NVFP4, 2 MX, 3 NVFP4 with the two-level row factor */, hipStream_t st);
 
 // ---- MX variant (E2M1, blocks of 32, E8M0 scale; mx.hip) ----
 // phi with the blocks along d (axis 0) or along the sequence (axis 1).  x [BH, L, D] bf16.

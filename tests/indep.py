@@ -172,16 +172,16 @@ def fake_quant_mx8_np(x, axis=-1):
     return np.moveaxis(out, -1, axis)
 
 
-def fake_quant_two_level_np(p, axis=-1):
-    """Two-level quantization of P along ``axis`` (values >= 0): aligned groups of 64 are divided by a power-of-two
+def fake_quant_two_level_np(p, axis=-1, span=64):
+    """Two-level quantization of P along ``axis`` (values >= 0): aligned groups of ``span`` are divided by a power-of-two
     row factor s1 = smallest 2^k with 2688 * 2^k >= max(group max, 2^-24), NVFP4-quantized in blocks of 16, and
     multiplied back.  With base = m 2^x, m in [0.5, 1) (frexp) and 2688 = 0.65625 * 2^12: k = x - 12 for
     m <= 0.65625, else x - 11."""
     x = np.moveaxis(np.asarray(p, dtype=np.float64), axis, -1)
     n = x.shape[-1]
-    pad = (-n) % 64
+    pad = (-n) % span
     xp = np.concatenate([x, np.zeros(x.shape[:-1] + (pad,))], axis=-1) if pad else x
-    grp = xp.reshape(xp.shape[:-1] + (-1, 64))
+    grp = xp.reshape(xp.shape[:-1] + (-1, span))
     base = np.maximum(grp.max(axis=-1), 2.0 ** -24)
     m, ex = np.frexp(base)
     s1 = np.ldexp(1.0, ex - 12 + (m > 0.65625))[..., None]

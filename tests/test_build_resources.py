@@ -43,15 +43,15 @@ def _check(kernels, pattern, expect_count):
 
 def test_forward_kernels_do_not_spill():
     k = _resources("fwd.hip")
-    # fwd_kernel<D, TRAIN, CAUSAL, DUMP, MXP>: every production variant (DUMP = false), d = 64 and 128, both formats of phi(P)
-    _check(k, r"fwd_kernelILi(64|128)ELb[01]ELb[01]ELb0ELb[01]E", 16)
+    # fwd_kernel<D, TRAIN, CAUSAL, DUMP, PQ>: every production variant (DUMP = false), d = 64 and 128, the three forms of phi(P)
+    _check(k, r"fwd_kernelILi(64|128)ELb[01]ELb[01]ELb0ELi[012]E", 24)
 
 
 def test_backward_kernels_do_not_spill():
     k = _resources("bwd.hip")
     _check(k, r"bwd_dq_kernelILi(64|128)ELb[01]E", 4)
     # bwd_dkdv_kernel<D, CAUSAL, COUNT, PQ>: the measurement (COUNT) and ablation (PQ = 0) variants are exempt
-    _check(k, r"bwd_dkdv_kernelILi(64|128)ELb[01]ELb0ELi[12]E", 8)
+    _check(k, r"bwd_dkdv_kernelILi(64|128)ELb[01]ELb0ELi[123]E", 12)
 
 
 def test_mx_forward_kernels_do_not_spill():

@@ -236,41 +236,44 @@ def test_full_size_mx_training(cfg):
         assert not dk[:, other].any() and not dv[:, other].any()
 
 
-@pytest.mark.parametrize("cfg", [2, 4])
-def test_full_size_k_smoothing(cfg):
-    """ATTNQAT_OPT_SMOOTH_K on the two LLM shapes (K has outlier channels): O, O', L and dQ on sampled rows against
-    the oracle run on the centred K; dK, dV through a dO that is zero outside the sampled rows."""
+@pytest.mark.parametrize("cfg,opts", [(2, 1), (4, 1), (3, 2), (2, 3)])
+def test_full_size_options(cfg, opts):
+    """The option bits of attnqat_fwd_opt / attnqat_bwd_opt (1: K smoothing, 2: two-level quantization of P) on full
+    shapes: O, O', L and dQ on sampled rows against the oracle with the same options; dK, dV through a dO that is zero
+    outside the sampled rows."""
     import paper_2603_00040_amd as aq
     w = W.CONFIGS[cfg]
-    print(f"\n[{w.name}] generating inputs", flush=True)
+    print(f"\n[{w.name}] options {opts}: generating inputs", flush=True)
     x = W.make_inputs(w, with_do=True)
     q, k, v, do = to_dev(x["q"]), to_dev(x["k"]), to_dev(x["v"]), to_dev(x["do"])
     b, kv, qheads, rows = _selection(w)
     L, Bk = w.L, aq.block_k()
+    sm = oracle.TWO_LEVEL_P if opts & aq.OPT_TWO_LEVEL_P else 0
     sub = _sub(x, b, kv, qheads)
-    sub["k"] = oracle.smooth_k(sub["k"])
+    if opts & aq.OPT_SMOOTH_K:
+        sub["k"] = oracle.smooth_k(sub["k"])
     flat = np.asarray([hi * L + r for hi, rs in enumerate(rows) for r in rs], dtype=np.int64)
     gi = [(b, h, r) for h, rs in zip(qheads, rows) for r in rs]
     pick = lambda t: torch.stack([t[bb, hh, rr] for bb, hh, rr in gi])
-    o, lse, ohp = aq.attnqat_fwd_opt(q, k, v, w.causal, aq.OPT_SMOOTH_K)
+    o, lse, ohp = aq.attnqat_fwd_opt(q, k, v, w.causal, opts)
     torch.cuda.synchronize()
-    rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, rows=flat)
+    rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, scale_mode=sm, rows=flat)
     eO = rel_l2(host(pick(o)), rf["O"]); eOp = rel_l2(host(pick(ohp)), rf["Op"]); eL = max_abs(host(pick(lse)), rf["L"])
-    print(f"[{w.name}] smooth-K O rel-L2 {eO:.2e}  O' rel-L2 {eOp:.2e}  L max-abs {eL:.2e}", flush=True)
+    print(f"[{w.name}] options {opts}: O rel-L2 {eO:.2e}  O' rel-L2 {eOp:.2e}  L max-abs {eL:.2e}", flush=True)
     assert eO <= TOL and eOp <= 2e-4 and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
-    dq, _, _ = aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, aq.OPT_SMOOTH_K)
+    dq, _, _ = aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, opts)
     torch.cuda.synchronize()
-    rdq = oracle.bwd_dq_rows(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
+    rdq = oracle.bwd_dq_rows(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal, scale_mode=sm)
     eQ = rel_l2(host(pick(dq)), rdq)
-    print(f"[{w.name}] smooth-K dQ rel-L2 {eQ:.2e}", flush=True)
+    print(f"[{w.name}] options {opts}: dQ rel-L2 {eQ:.2e}", flush=True)
     assert eQ <= TOL
     del dq
     dos = torch.zeros_like(do)
     for bb, hh, rr in gi:
         dos[bb, hh, rr] = do[bb, hh, rr]
-    _, dk, dv = aq.attnqat_bwd_opt(q, k, v, dos, lse, ohp, w.causal, aq.OPT_SMOOTH_K)
+    _, dk, dv = aq.attnqat_bwd_opt(q, k, v, dos, lse, ohp, w.causal, opts)
     torch.cuda.synchronize()
-    rdk, rdv = oracle.bwd_rows_dkdv(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
+    rdk, rdv = oracle.bwd_rows_dkdv(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal, scale_mode=sm)
     eK, eV = rel_l2(host(dk[b, kv]), rdk[0]), rel_l2(host(dv[b, kv]), rdv[0], zero_rms=1e-6)
-    print(f"[{w.name}] smooth-K dK rel-L2 {eK:.2e}  dV rel-L2 {eV:.2e}", flush=True)
+    print(f"[{w.name}] options {opts}: dK rel-L2 {eK:.2e}  dV rel-L2 {eV:.2e} (oracle dV non-zero fraction {float((rdv[0] != 0).mean()):.3f})", flush=True)
     assert eK <= TOL and eV <= TOL

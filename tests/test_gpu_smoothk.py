@@ -76,5 +76,5 @@ def test_smoothk_option_errors():
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     call = lambda opt: L_.attnqat_fwd_opt(q.data_ptr(), q.data_ptr(), q.data_ptr(), 1, 2, 2, 64, 128, 0, 0, opt,
                                          o.data_ptr(), lse.data_ptr(), None, ws.data_ptr(), need, None)
-    assert call(0) == aq.OK and call(1) == aq.OK and call(2) == aq.EINVAL and call(-1) == aq.EINVAL
+    assert call(0) == aq.OK and call(1) == aq.OK and call(2) == aq.OK and call(4) == aq.EINVAL and call(-1) == aq.EINVAL
     torch.cuda.synchronize()
