@@ -54,6 +54,7 @@ extern "C" {
 #define ATTNQAT_WS_FWD_MX           4   /* attnqat_fwd_mx, attnqat_debug_fwd_p_mx      */
 #define ATTNQAT_WS_BWD_MX           5   /* attnqat_bwd_mx                              */
 #define ATTNQAT_WS_FWD_INFER_MX_FP8PV 6 /* attnqat_fwd_infer_mx_fp8pv                  */
+#define ATTNQAT_WS_FWD_INFER_MX_PAGED 7 /* attnqat_fwd_infer_mx_paged (L = queries per sequence) */
 
 /*
  * phi of Eq. 1 (Sec. 3.1) along d: for every 16 consecutive elements
@@ -229,6 +230,33 @@ int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
                                int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                                void* o, float* lse,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Serving: an FP4 KV cache in pages, and Alg. 1 over it for sequences of different lengths (the variable-length /
+ * paged setting that Sec. 6 leaves as future work; format and forward as attnqat_fwd_infer_mx).
+ *
+ * The cache is caller-owned device memory of num_pages * attnqat_kv_cache_page_bytes(Hkv, d) bytes.  A page holds
+ * 128 consecutive positions of ONE sequence for all Hkv heads, as MX codes and scale bytes in the order the matrix
+ * instruction reads them (K blocked along d, V in blocks of 32 positions), so the scale factors travel with their
+ * page and a page table is all a reader needs.
+ *
+ * attnqat_kv_cache_write_mx quantizes k, v [1,Hkv,L,d] bf16 (positions 0..L-1 of one sequence, L >= 1) into the pages
+ * page_ids[0 .. ceil(L/128)-1] (device int32; each entry in [0, num_pages)); a last page that is not full is zero
+ * padded.  A sequence that grows is written again from position 0 of its last page on (V scales cover 32 positions:
+ * a block that gains positions must be re-quantized), i.e. k, v must start at a multiple of 128 of the sequence.
+ *
+ * attnqat_fwd_infer_mx_paged: q [B,Hq,Lq,d] bf16 holds the LAST Lq positions of every sequence; sequence b has
+ * kv_lens[b] >= Lq keys (device int32 [B]) in the pages page_table[b*max_pages + 0 ..] (device int32 [B,max_pages],
+ * max_pages >= ceil(max kv_len / 128)).  causal != 0: query i sees keys 0 .. kv_lens[b] - Lq + i (chunked prefill;
+ * Lq = 1 is a decode step).  o [B,Hq,Lq,d] bf16, lse [B,Hq,Lq] fp32.  Page ids outside [0, num_pages) are clamped
+ * (wrong result, no out-of-bounds access); a sequence with kv_lens[b] = 0 gets o = 0.
+ */
+size_t attnqat_kv_cache_page_bytes(int Hkv, int d);
+int attnqat_kv_cache_write_mx(const void* k, const void* v, int Hkv, int L, int d, int dtype,
+                              void* cache, const int* page_ids, void* stream);
+int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
+                               const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                               void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Training forward (Alg. 2) and backward (Alg. 3) in the MX format, for training against

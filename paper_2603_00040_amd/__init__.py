@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libattnqat.so")
 
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4, -5
 BF16 = 0
-WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX, WS_FWD_MX, WS_BWD_MX, WS_FWD_INFER_MX_FP8PV = 0, 1, 2, 3, 4, 5, 6
+(WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX, WS_FWD_MX, WS_BWD_MX, WS_FWD_INFER_MX_FP8PV,
+ WS_FWD_INFER_MX_PAGED) = 0, 1, 2, 3, 4, 5, 6, 7
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _SIGNATURES = {
@@ -37,6 +38,9 @@ _SIGNATURES = {
                              _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_debug_fwd_p_opt": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
                                      _vp, _sz, _vp]),
+    "attnqat_kv_cache_page_bytes": (_sz, [_i, _i]),
+    "attnqat_kv_cache_write_mx": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "attnqat_fwd_infer_mx_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                             _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -121,6 +125,44 @@ def attnqat_quantize(x, want_codes=True, want_xf=True):
 
 
 OPT_SMOOTH_K, OPT_TWO_LEVEL_P = 1, 2
+
+
+def kv_cache_page_bytes(Hkv: int, d: int) -> int:
+    return lib().attnqat_kv_cache_page_bytes(Hkv, d)
+
+
+def attnqat_kv_cache_write_mx(k, v, cache, page_ids):
+    """Quantize one sequence's k, v [1,Hkv,L,d] bf16 into the pages ``page_ids`` (int32 CUDA tensor) of the FP4 KV
+    ``cache`` (uint8 CUDA tensor of num_pages * kv_cache_page_bytes(Hkv, d) bytes)."""
+    _dev_bf16(k, "k"); _dev_bf16(v, "v")
+    _, Hkv, L, d = k.shape
+    if k.shape[0] != 1 or v.shape != k.shape:
+        raise AttnQatError("k and v must be [1,Hkv,L,d] of one sequence")
+    if not (page_ids.is_cuda and page_ids.dtype == torch.int32 and page_ids.is_contiguous() and page_ids.numel() >= (L + 127) // 128):
+        raise AttnQatError("page_ids must be a contiguous int32 CUDA tensor with ceil(L/128) entries")
+    _check(lib().attnqat_kv_cache_write_mx(_ptr(k), _ptr(v), Hkv, L, d, BF16, _ptr(cache), _ptr(page_ids), _stream()))
+
+
+def attnqat_fwd_infer_mx_paged(q, cache, num_pages, page_table, kv_lens, Hkv, causal: bool, workspace=None, out=None):
+    """Alg. 1 (MX, FP4 matrix instruction) over a paged FP4 KV cache.  q [B,Hq,Lq,d]: the last Lq positions of every
+    sequence; page_table int32 [B,max_pages]; kv_lens int32 [B].  Returns (o bf16, lse fp32)."""
+    _dev_bf16(q, "q")
+    B, Hq, Lq, d = q.shape
+    for t, n in ((page_table, "page_table"), (kv_lens, "kv_lens")):
+        if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+            raise AttnQatError(f"{n} must be a contiguous int32 CUDA tensor")
+    if page_table.dim() != 2 or page_table.shape[0] != B or kv_lens.numel() != B:
+        raise AttnQatError("page_table must be [B,max_pages] and kv_lens [B]")
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    ws, nb = _workspace(WS_FWD_INFER_MX_PAGED, B, Hq, Hkv, Lq, d, workspace)
+    _check(lib().attnqat_fwd_infer_mx_paged(_ptr(q), B, Hq, Hkv, Lq, d, int(causal), BF16, _ptr(cache), int(num_pages),
+                                            _ptr(page_table), page_table.shape[1], _ptr(kv_lens),
+                                            _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
+    return o, lse
 
 
 def attnqat_debug_fwd_p_opt(q, k, v, causal: bool, row0: int, options: int):

@@ -170,6 +170,11 @@ size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d)
     case ATTNQAT_WS_BWD:       return carve_bwd(nullptr, B, Hq, Hkv, L, d).bytes;
     case ATTNQAT_WS_FWD_INFER_MX: return carve_mx(nullptr, B, Hq, Hkv, L, d).bytes;
     case ATTNQAT_WS_FWD_INFER_MX_FP8PV: return carve_mx(nullptr, B, Hq, Hkv, L, d, true).bytes;
+    case ATTNQAT_WS_FWD_INFER_MX_PAGED: {          // L = the number of query positions per sequence
+        Carver c{nullptr, 0};
+        c.take(mx_qops_bytes(B * Hq, L, d)); c.take(mx_qsc_bytes(B * Hq, L));
+        return c.off;
+    }
     case ATTNQAT_WS_FWD_MX:    return carve_fwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
     case ATTNQAT_WS_BWD_MX:    return carve_bwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
     default:                   return 0;
@@ -248,6 +253,47 @@ int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
                                void* workspace, size_t workspace_bytes, void* stream)
 {
     return fwd_infer_mx_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, true, o, lse, workspace, workspace_bytes, stream);
+}
+
+size_t attnqat_kv_cache_page_bytes(int Hkv, int d)
+{
+    if (Hkv < 1 || (d != 64 && d != 128)) return 0;
+    return (size_t)Hkv * mx_page_bytes(d);
+}
+
+int attnqat_kv_cache_write_mx(const void* k, const void* v, int Hkv, int L, int d, int dtype,
+                              void* cache, const int* page_ids, void* stream)
+{
+    if (!k || !v || !cache || !page_ids) return ATTNQAT_EINVAL;
+    int rc = check_dims(1, Hkv, Hkv, L, d, dtype);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    if (launch_mx_quant(k, Hkv, L, d, 0, 2, false, (unsigned char*)cache, nullptr, nullptr, st, page_ids)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(v, Hkv, L, d, 1, 2, false, (unsigned char*)cache, nullptr, nullptr, st, page_ids)) return ATTNQAT_ELAUNCH;
+    prof_mark("kv_cache_write_mx", st);
+    return ATTNQAT_OK;
+}
+
+int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
+                               const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                               void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !cache || !page_table || !kv_lens || !o || !lse || num_pages < 1 || max_pages < 1) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, Lq, d, dtype);
+    if (rc) return rc;
+    Carver c{(unsigned char*)workspace, 0};
+    unsigned char* qops = (unsigned char*)c.take(mx_qops_bytes(B * Hq, Lq, d));
+    unsigned char* qsc = (unsigned char*)c.take(mx_qsc_bytes(B * Hq, Lq));
+    if (!workspace || workspace_bytes < c.off) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    if (launch_mx_quant(q, B * Hq, Lq, d, 0, 1, false, qops, qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_q_mx", st);
+    if (launch_fwd_mx_paged(qops, qsc, cache, B, Hq, Hkv, Lq, d, causal != 0, page_table, kv_lens, max_pages, num_pages, o, lse, st))
+        return ATTNQAT_ELAUNCH;
+    prof_mark("fwd_infer_mx_paged", st);
+    return ATTNQAT_OK;
 }
 
 static unsigned long long* g_dkdv_counts = nullptr;

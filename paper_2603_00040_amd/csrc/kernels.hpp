@@ -56,13 +56,20 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
 //   mode 1: Q operands of the scaled MFMA (axis 0 only): codes -> operand array, scales -> scale dwords
 //   mode 2: the K part (axis 0) or the V part (axis 1) of the 64-key kv records at `codes`
 // fp8: E4M3 elements instead of E2M1 (axis 1 only); with axis 0 and mode 2 it selects the record layout whose V part is FP8.
+// page_ids (mode 2, FP4 only; device int32, one entry per 128 positions): the records go into the pages of a KV cache
+// laid out [page][kv head][2 records] instead of one after another; BH then is the number of kv heads of ONE sequence.
 int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
-                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st);
+                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids = nullptr);
 size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v);
 size_t mx_qops_bytes(int BHq, int L, int D);
 size_t mx_qsc_bytes(int BHq, int L);
 // Alg. 1 on the arrays made by launch_mx_quant (modes 1 and 2).  fp8pv: P-tilde and V in MXFP8 (mixed recipe).
 int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal, bool fp8pv,
                   void* o, float* lse, hipStream_t st);
+
+// The same forward on a paged KV cache: q has Lq positions per sequence, the last Lq of a sequence of kv_lens[b] keys.
+size_t mx_page_bytes(int D);
+int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, int B, int Hq, int Hkv, int Lq, int D, bool causal,
+                        const int* page_table, const int* kv_lens, int max_pages, int num_pages, void* o, float* lse, hipStream_t st);
 
 }  // namespace aq

@@ -74,6 +74,13 @@ __device__ inline float e4m3_value_of(uint32_t byte) {
     return (byte & 0x80u) ? -v : v;
 }
 
+// Where the 64-key record `tile` of kv head `head` lives.  Contiguous: records of a head one after another.  Paged (a
+// KV cache): a page holds two records (128 keys) of every kv head, page_ids[tile / 2] names the page of this sequence.
+__device__ inline unsigned char* mx_record_of(unsigned char* base, const int* page_ids, int head, int nheads, int Lp, int tile, int rec_bytes) {
+    if (page_ids) return base + (((size_t)page_ids[tile >> 1] * nheads + head) * 2 + (tile & 1)) * rec_bytes;
+    return base + ((size_t)head * (Lp / 64) + tile) * rec_bytes;
+}
+
 // Row of S^T product t (0/1) that holds key kk (0..63) of a tile, and the lane half that ends up owning it:
 // the accumulator register r of a lane in half h is row 8 (r/4) + 4 h + r % 4; key 32 h + 16 t + r goes there.
 __device__ inline int mx_srow_of_key(int kk) { const int w = kk & 15; return 8 * (w >> 2) + 4 * (kk >> 5) + (w & 3); }
@@ -86,7 +93,7 @@ __device__ inline int mx_srow_of_key(int kk) { const int w = kk & 15; return 8 *
 template <int D, int MODE, bool FP8V = false /* MODE 2: records whose V part is FP8 */>
 __global__ __launch_bounds__(256) void mx_quant_d_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
-    uint16_t* __restrict__ xf)
+    uint16_t* __restrict__ xf, const int* __restrict__ page_ids)
 {
     constexpr int NB = D / 32, KS = D / 64;
     const int bh = blockIdx.y;
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(256) void mx_quant_d_kernel(
         constexpr int REC = mx_rec_bytes(D, FP8V), KOPS = 2 * KS * 1024, VOPS = NB * (FP8V ? 2048 : 1024);
         const int tile = row >> 6, kk = row & 63, t = (kk >> 4) & 1;
         const int ks = blk >> 1, lane = (blk & 1) * 32 + mx_srow_of_key(kk);
-        unsigned char* rec = codes + ((size_t)bh * (Lp / 64) + tile) * REC;
+        unsigned char* rec = mx_record_of(codes, page_ids, bh, (int)gridDim.y, Lp, tile, REC);
         *reinterpret_cast<uint4v*>(rec + ((t * KS + ks) * 64 + lane) * 16) = c;
         rec[KOPS + VOPS + lane * 4 + t * KS + ks] = (unsigned char)byte;
         if (KS == 1 && t == 0) { rec[KOPS + VOPS + lane * 4 + 2] = 1; rec[KOPS + VOPS + lane * 4 + 3] = 1; }
@@ -158,7 +165,7 @@ __global__ __launch_bounds__(256) void mx_quant_d_kernel(
 template <int D, int MODE, bool FP8>
 __global__ __launch_bounds__(D) void mx_quant_l_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
-    uint16_t* __restrict__ xf)
+    uint16_t* __restrict__ xf, const int* __restrict__ page_ids)
 {
     constexpr int KS = D / 64, MT = D / 32;
     const int bh = blockIdx.y, kb = blockIdx.x, dd = threadIdx.x;
@@ -202,7 +209,7 @@ __global__ __launch_bounds__(D) void mx_quant_l_kernel(
     } else {
         constexpr int REC = mx_rec_bytes(D, FP8), KOPS = 2 * KS * 1024, VOPS = MT * (FP8 ? 2048 : 1024);
         const int tile = kb >> 1, lane = (kb & 1) * 32 + (dd & 31), mt = dd >> 5;
-        unsigned char* rec = codes + ((size_t)bh * (Lp / 64) + tile) * REC;
+        unsigned char* rec = mx_record_of(codes, page_ids, bh, (int)gridDim.y, Lp, tile, REC);
         if constexpr (FP8) {
             // FP8 operands: registers 0-3 of lane (row, h) are contraction indices 16 h .. + 15, registers 4-7 are
             // 32 + 16 h .. + 15, and the scale of indices 32 b .. + 31 is taken from lane (row, b): the two halves of
@@ -227,10 +234,14 @@ __global__ __launch_bounds__(D) void mx_quant_l_kernel(
 // kv records arrive in stages of two tiles, copied global->LDS directly into a ring of three stage
 // buffers; one barrier per stage.  The S^T products of tile j+1 are issued before the softmax of
 // tile j, so the matrix unit works under the wave's own vector instructions.
-template <int D, bool CAUSAL, bool FP8PV>
+// PAGED: the kv records come from a KV cache (pages of 128 keys = one stage per kv head, located through
+// page_table [B, max_pages]), every sequence has its own number of keys kv_lens[b] >= L, and the L queries are the
+// LAST L positions of the sequence: under the causal mask query i sees keys 0 .. kv_len - L + i.
+template <int D, bool CAUSAL, bool FP8PV, bool PAGED>
 __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     const unsigned char* __restrict__ qops, const uint32_t* __restrict__ qsc, const unsigned char* __restrict__ kv,
-    uint16_t* __restrict__ O, float* __restrict__ lse, int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */)
+    uint16_t* __restrict__ O, float* __restrict__ lse, int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */,
+    const int* __restrict__ page_table, const int* __restrict__ kv_lens, int max_pages, int num_pages)
 {
     constexpr int KS = D / 64, MT = D / 32;
     constexpr int KOPS = 2 * KS * 1024, VOPS = MT * (FP8PV ? 2048 : 1024), REC = mx_rec_bytes(D, FP8PV), STAGE = 2 * REC, NCH = STAGE / 1024;
@@ -256,12 +267,20 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     for (int ks = 0; ks < KS; ++ks) qop[ks] = *reinterpret_cast<const uint4v*>(qops + ((grp * KS + ks) * 64 + lane) * 16);
     uint32_t qs = qsc[grp * 64 + lane];
 
-    const int nkt_all = (L + 63) / 64;
-    const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;   // tiles this workgroup visits
+    const int Lk = PAGED ? __builtin_amdgcn_readfirstlane(kv_lens[b]) : L;      // keys of this sequence
+    const int koff = PAGED ? Lk - L : 0;                           // key index of query 0's diagonal
+    const int nkt_all = PAGED ? min((Lk + 63) / 64, 2 * max_pages) : (Lk + 63) / 64;   // never past the page table
+    const int nkt = CAUSAL ? min((koff + qt * 128 + 128 + 63) / 64, nkt_all) : nkt_all;   // tiles this workgroup visits
     const int nst = (nkt + 1) / 2;
     const unsigned char* kv_head = kv + (size_t)bhkv * (Lp / 64) * REC;
+    const int Hkv = Hq / G;
     auto issue_stage = [&](int s) __attribute__((always_inline)) {
         const unsigned char* src = kv_head + (size_t)s * STAGE;
+        if constexpr (PAGED) {
+            int page = __builtin_amdgcn_readfirstlane(page_table[(size_t)b * max_pages + s]);
+            page = min(max(page, 0), num_pages - 1);               // a bad table entry reads a wrong page, never outside the cache
+            src = kv + ((size_t)page * Hkv + (h / G)) * STAGE;
+        }
         unsigned char* dst = smem + (s % 3) * STAGE;
         for (int i = wave; i < NCH; i += 4) async_copy16(src, (uint32_t)(i * 1024 + lane * 16), dst + i * 1024);
     };
@@ -303,9 +322,9 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     // online softmax of one tile (Alg. 1 inner loop), phi of this lane's P-tilde block, O += V^F^T P-tilde^F
     auto softmax_pv = [&](int j, const unsigned char* rec, floatx16 (&s)[2]) __attribute__((always_inline)) {
         const int k0 = j * 64;
-        const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > row0_w);
+        const bool need_mask = (k0 + 64 > Lk) || (CAUSAL && k0 + 63 > koff + row0_w);
         if (__builtin_expect(need_mask, 0)) {
-            const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
+            const int klim = CAUSAL ? min(Lk - 1, koff + q_row) : Lk - 1;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -385,7 +404,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
             }
         }
     };
-    auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || j * 64 <= wave_qmax; };
+    auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || j * 64 <= koff + wave_qmax; };
     // One tile: at odd j the next stage becomes visible (and the buffer two stages back becomes free).
     auto tile_step = [&](int j, floatx16 (&scur)[2], floatx16 (&snext)[2]) __attribute__((always_inline)) {
         if (j & 1) {
@@ -413,7 +432,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
 
     // ---- epilogue: O /= l, L = m + log l
     const float l = xhalf_sum(lsum);
-    const float inv_l = 1.0f / l;
+    const float inv_l = (PAGED && !(l > 0.0f)) ? 0.0f : 1.0f / l;         // a sequence without keys: O = 0, L = -inf
     if (q_row < L) {
         const size_t row = (size_t)bh * L + q_row;
 #pragma unroll
@@ -432,62 +451,65 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
 
 // ---------------------------------------------------------------------------------------------
 template <int D>
-static int quant_d(const void* x, int BH, int L, int mode, bool fp8v, unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
+static int quant_d(const void* x, int BH, int L, int mode, bool fp8v, unsigned char* codes, unsigned char* scales, void* xf,
+                   const int* page_ids, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int rows = mode == 0 ? L : Lp;
     const dim3 grid((unsigned)(((size_t)rows * (D / 32) + 255) / 256), (unsigned)BH);
-    if (mode == 0)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 0>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
-    else if (mode == 1) hipLaunchKernelGGL((mx_quant_d_kernel<D, 1>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
-    else if (fp8v)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 2, true>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
-    else                hipLaunchKernelGGL((mx_quant_d_kernel<D, 2>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    if (mode == 0)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 0>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
+    else if (mode == 1) hipLaunchKernelGGL((mx_quant_d_kernel<D, 1>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
+    else if (fp8v)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 2, true>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
+    else                hipLaunchKernelGGL((mx_quant_d_kernel<D, 2>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 template <int D, bool FP8>
-static int quant_l(const void* x, int BH, int L, int mode, unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
+static int quant_l(const void* x, int BH, int L, int mode, unsigned char* codes, unsigned char* scales, void* xf,
+                   const int* page_ids, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int nblk = mode == 0 ? (L + 31) / 32 : Lp / 32;
     const dim3 grid((unsigned)nblk, (unsigned)BH);
-    if (mode == 0) hipLaunchKernelGGL((mx_quant_l_kernel<D, 0, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
-    else           hipLaunchKernelGGL((mx_quant_l_kernel<D, 2, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf);
+    if (mode == 0) hipLaunchKernelGGL((mx_quant_l_kernel<D, 0, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
+    else           hipLaunchKernelGGL((mx_quant_l_kernel<D, 2, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
-                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st)
+                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids)
 {
-    if (BH > 65535 || (axis == 0 && fp8 && mode != 2)) return -1;
-    if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, fp8, codes, scales, xf, st) : quant_d<64>(x, BH, L, mode, fp8, codes, scales, xf, st);
-    if (fp8) return D == 128 ? quant_l<128, true>(x, BH, L, mode, codes, scales, xf, st) : quant_l<64, true>(x, BH, L, mode, codes, scales, xf, st);
-    return D == 128 ? quant_l<128, false>(x, BH, L, mode, codes, scales, xf, st) : quant_l<64, false>(x, BH, L, mode, codes, scales, xf, st);
+    if (BH > 65535 || (axis == 0 && fp8 && mode != 2) || (page_ids && (mode != 2 || fp8))) return -1;
+    if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, st) : quant_d<64>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, st);
+    if (fp8) return D == 128 ? quant_l<128, true>(x, BH, L, mode, codes, scales, xf, page_ids, st) : quant_l<64, true>(x, BH, L, mode, codes, scales, xf, page_ids, st);
+    return D == 128 ? quant_l<128, false>(x, BH, L, mode, codes, scales, xf, page_ids, st) : quant_l<64, false>(x, BH, L, mode, codes, scales, xf, page_ids, st);
 }
 
 size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v) { return (size_t)BHkv * (round_up(L, kRowPad) / 64) * mx_rec_bytes(D, fp8v); }
 size_t mx_qops_bytes(int BHq, int L, int D) { return (size_t)BHq * round_up(L, kRowPad) * (D / 2); }
 size_t mx_qsc_bytes(int BHq, int L) { return (size_t)BHq * (round_up(L, kRowPad) / 32) * 64 * 4; }
+size_t mx_page_bytes(int D) { return 2 * (size_t)mx_rec_bytes(D, false); }
 
-template <int D, bool CAUSAL, bool FP8PV>
+template <int D, bool CAUSAL, bool FP8PV, bool PAGED>
 static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L,
-                           void* o, float* lse, hipStream_t st)
+                           void* o, float* lse, const int* page_table, const int* kv_lens, int max_pages, int num_pages, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = 3 * 2 * (size_t)mx_rec_bytes(D, FP8PV);
-    auto kern = fwd_mx_kernel<D, CAUSAL, FP8PV>;
+    auto kern = fwd_mx_kernel<D, CAUSAL, FP8PV, PAGED>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)smem) != hipSuccess) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
                        (const unsigned char*)qops, (const uint32_t*)qsc, (const unsigned char*)kv,
-                       (uint16_t*)o, lse, L, Lp, Hq, Hq / Hkv, c);
+                       (uint16_t*)o, lse, L, Lp, Hq, Hq / Hkv, c, page_table, kv_lens, max_pages, num_pages);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 template <int D, bool FP8PV>
 static int launch_fwd_mx_d(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, bool causal,
                            void* o, float* lse, hipStream_t st)
 {
-    return causal ? launch_fwd_mx_t<D, true, FP8PV>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st)
-                  : launch_fwd_mx_t<D, false, FP8PV>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, st);
+    return causal ? launch_fwd_mx_t<D, true, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, st)
+                  : launch_fwd_mx_t<D, false, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, st);
 }
 
 int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal, bool fp8pv,
@@ -497,6 +519,16 @@ int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int 
                                : launch_fwd_mx_d<128, false>(qops, qsc, kv, B, Hq, Hkv, L, causal, o, lse, st);
     if (D == 64)  return fp8pv ? launch_fwd_mx_d<64, true>(qops, qsc, kv, B, Hq, Hkv, L, causal, o, lse, st)
                                : launch_fwd_mx_d<64, false>(qops, qsc, kv, B, Hq, Hkv, L, causal, o, lse, st);
+    return -1;
+}
+
+int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, int B, int Hq, int Hkv, int Lq, int D, bool causal,
+                        const int* page_table, const int* kv_lens, int max_pages, int num_pages, void* o, float* lse, hipStream_t st)
+{
+#define AQ_PAGED(DD, CC) launch_fwd_mx_t<DD, CC, false, true>(qops, qsc, cache, B, Hq, Hkv, Lq, o, lse, page_table, kv_lens, max_pages, num_pages, st)
+    if (D == 128) return causal ? AQ_PAGED(128, true) : AQ_PAGED(128, false);
+    if (D == 64)  return causal ? AQ_PAGED(64, true) : AQ_PAGED(64, false);
+#undef AQ_PAGED
     return -1;
 }
 
