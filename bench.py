@@ -54,6 +54,9 @@ def main():
                     help="K smoothing option of Sec. 4.2 (nvfp4 format only): phi on K minus its token mean")
     ap.add_argument("--two-level-p", action="store_true",
                     help="two-level quantization of P, the other option of Sec. 4.2 (nvfp4 format only)")
+    ap.add_argument("--paged-lq", type=int, default=0,
+                    help="serving mode (not a benchmark configuration): the MX forward over a paged FP4 KV cache with this many "
+                         "query positions per sequence (1 = a decode step) for 32 sequences of 4k-16k keys, 32 query / 8 kv heads")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     args = ap.parse_args()
@@ -75,6 +78,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.paged_lq > 0:
+        return bench_paged(args, aq, torch, np)
     w = W.by_name(args.workload)
     fp8pv = args.format == "mx_fp8pv"
     mx = args.format == "mx" or fp8pv
@@ -204,6 +209,66 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
+
+
+def bench_paged(args, aq, torch, np):
+    """Serving shapes: 32 sequences with 4096..16384 keys (seeded), Hq = 32, Hkv = 8, d = 128, causal; the KV cache is
+    written once (untimed), a step is one attnqat_fwd_infer_mx_paged call over all sequences."""
+    B, Hq, Hkv, d, Lq = 32, 32, 8, 128, args.paged_lq
+    rng = np.random.default_rng(7)
+    kv_lens = rng.integers(4096, 16385, B).astype(np.int32)
+    kv_lens = np.maximum(kv_lens, Lq)
+    max_pages = int((kv_lens.max() + 127) // 128)
+    pages_of = [(int(n) + 127) // 128 for n in kv_lens]
+    num_pages = sum(pages_of)
+    perm = rng.permutation(num_pages).astype(np.int32)
+    table = np.zeros((B, max_pages), np.int32)
+    cache = torch.empty(num_pages * aq.kv_cache_page_bytes(Hkv, d), dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    nxt = 0
+    for b in range(B):
+        n = int(kv_lens[b])
+        table[b, :pages_of[b]] = perm[nxt:nxt + pages_of[b]]; nxt += pages_of[b]
+        k = torch.randn((1, Hkv, n, d), device="cuda", generator=g).to(torch.bfloat16)
+        v = torch.randn((1, Hkv, n, d), device="cuda", generator=g).to(torch.bfloat16)
+        aq.attnqat_kv_cache_write_mx(k, v, cache, torch.from_numpy(table[b, :pages_of[b]].copy()).cuda())
+    q = torch.randn((B, Hq, Lq, d), device="cuda", generator=g).to(torch.bfloat16)
+    tab, lens = torch.from_numpy(table).cuda(), torch.from_numpy(kv_lens).cuda()
+    o = torch.empty_like(q); lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device="cuda")
+    ws = torch.empty(aq.workspace_bytes(aq.WS_FWD_INFER_MX_PAGED, B, Hq, Hkv, Lq, d), dtype=torch.uint8, device="cuda")
+    step = lambda: aq.attnqat_fwd_infer_mx_paged(q, cache, num_pages, tab, lens, Hkv, True, workspace=ws, out=(o, lse))
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    aq.profile_enable(True)
+    step(); torch.cuda.synchronize()
+    kern = dict(aq.profile_read())
+    aq.profile_enable(False)
+    kms = kern["fwd_infer_mx_paged"]
+    # causal chunk: query i of the last Lq positions sees kv_len - Lq + i + 1 keys
+    pairs = float(sum(Hq * (Lq * (int(n) - Lq) + Lq * (Lq + 1) / 2) for n in kv_lens))
+    flops = 4.0 * pairs * d
+    cache_bytes = float(sum(pages_of)) * aq.kv_cache_page_bytes(Hkv, d)          # every page of every sequence, once
+    decode = Lq <= 16
+    roofline = ({"bound": "hbm", "kernel": "fwd_infer_mx_paged", "achieved": round(cache_bytes / (kms * 1e-3) / 1e9, 1), "peak": 8000.0,
+                 "unit": "GB/s", "frac": round(cache_bytes / (kms * 1e-3) / 8e12, 4), "traffic": None, "kernel_ms": round(kms, 3)}
+                if decode else
+                {"bound": "mfma", "kernel": "fwd_infer_mx_paged", "achieved": round(flops / (kms * 1e-3) / 1e12, 2), "peak": MFMA_FP4_PEAK_TFLOPS,
+                 "unit": "TFLOP/s", "frac": round(flops / (kms * 1e-3) / 1e12 / MFMA_FP4_PEAK_TFLOPS, 4), "traffic": None, "kernel_ms": round(kms, 3)})
+    print(json.dumps({
+        "metric": "FP4-attention fwd TFLOPS (1 MI355X)", "value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax", "data": "synthetic",
+        "config": {"workload": "serving_paged_kv (not a benchmark configuration)", "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "Lq": Lq,
+                   "kv_len_min": int(kv_lens.min()), "kv_len_max": int(kv_lens.max()), "kv_len_sum": int(kv_lens.sum()), "causal": True,
+                   "page_keys": 128, "cache_bytes": int(cache_bytes), "format": "mx"},
+        "tokens_per_s": round(B * Lq / (ms * 1e-3), 1), "per_kernel_ms": {k_: round(v_, 3) for k_, v_ in kern.items()},
+        "roofline": roofline, "cpu_baseline": None}), flush=True)
 
 
 def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False, two_level=False):
