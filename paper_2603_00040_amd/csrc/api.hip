@@ -282,15 +282,20 @@ int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, in
     if (!q || !cache || !page_table || !kv_lens || !o || !lse || num_pages < 1 || max_pages < 1) return ATTNQAT_EINVAL;
     int rc = check_dims(B, Hq, Hkv, Lq, d, dtype);
     if (rc) return rc;
+    // Grouped-query heads with few positions: q [B,Hq,Lq,d] is [B*Hkv, G*Lq, d] in memory, so the G query heads of a kv
+    // group are treated as one head with G*Lq rows: one tile and one pass over the pages instead of G.
+    const int G = Hq / Hkv;
+    const bool pack = G > 1 && G * Lq <= 128;
+    const int Hq_k = pack ? Hkv : Hq, Lq_k = pack ? G * Lq : Lq;
     Carver c{(unsigned char*)workspace, 0};
-    unsigned char* qops = (unsigned char*)c.take(mx_qops_bytes(B * Hq, Lq, d));
+    unsigned char* qops = (unsigned char*)c.take(mx_qops_bytes(B * Hq, Lq, d));      // sized for the unpacked case (the larger)
     unsigned char* qsc = (unsigned char*)c.take(mx_qsc_bytes(B * Hq, Lq));
     if (!workspace || workspace_bytes < c.off) return ATTNQAT_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
-    if (launch_mx_quant(q, B * Hq, Lq, d, 0, 1, false, qops, qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(q, B * Hq_k, Lq_k, d, 0, 1, false, qops, qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_q_mx", st);
-    if (launch_fwd_mx_paged(qops, qsc, cache, B, Hq, Hkv, Lq, d, causal != 0, page_table, kv_lens, max_pages, num_pages, o, lse, st))
+    if (launch_fwd_mx_paged(qops, qsc, cache, B, Hq_k, Hkv, Lq_k, d, causal != 0, page_table, kv_lens, max_pages, num_pages, Lq, o, lse, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("fwd_infer_mx_paged", st);
     return ATTNQAT_OK;

@@ -67,9 +67,11 @@ size_t mx_qsc_bytes(int BHq, int L);
 int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal, bool fp8pv,
                   void* o, float* lse, hipStream_t st);
 
-// The same forward on a paged KV cache: q has Lq positions per sequence, the last Lq of a sequence of kv_lens[b] keys.
+// The same forward on a paged KV cache: a head has Lq rows, positions kv_lens[b] - lq_inner .. of its sequence, repeated
+// Lq / lq_inner times when the query heads of a kv group are packed into one head (then Hq == Hkv).
 size_t mx_page_bytes(int D);
 int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, int B, int Hq, int Hkv, int Lq, int D, bool causal,
-                        const int* page_table, const int* kv_lens, int max_pages, int num_pages, void* o, float* lse, hipStream_t st);
+                        const int* page_table, const int* kv_lens, int max_pages, int num_pages, int lq_inner,
+                        void* o, float* lse, hipStream_t st);
 
 }  // namespace aq

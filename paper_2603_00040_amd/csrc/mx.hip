@@ -236,12 +236,15 @@ __global__ __launch_bounds__(D) void mx_quant_l_kernel(
 // tile j, so the matrix unit works under the wave's own vector instructions.
 // PAGED: the kv records come from a KV cache (pages of 128 keys = one stage per kv head, located through
 // page_table [B, max_pages]), every sequence has its own number of keys kv_lens[b] >= L, and the L queries are the
-// LAST L positions of the sequence: under the causal mask query i sees keys 0 .. kv_len - L + i.
+// LAST positions of the sequence.  lq_inner: the rows of a head are the G query heads of a kv group one after another,
+// lq_inner positions each (L = G * lq_inner; a kv head's queries are contiguous in [B,Hq,Lq,d], so grouped-query
+// heads with few positions share one tile and one pass over the pages); lq_inner == L: plain rows.  Under the causal
+// mask the query at position i of its head sees keys 0 .. kv_len - lq_inner + i.
 template <int D, bool CAUSAL, bool FP8PV, bool PAGED>
 __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     const unsigned char* __restrict__ qops, const uint32_t* __restrict__ qsc, const unsigned char* __restrict__ kv,
     uint16_t* __restrict__ O, float* __restrict__ lse, int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */,
-    const int* __restrict__ page_table, const int* __restrict__ kv_lens, int max_pages, int num_pages)
+    const int* __restrict__ page_table, const int* __restrict__ kv_lens, int max_pages, int num_pages, int lq_inner)
 {
     constexpr int KS = D / 64, MT = D / 32;
     constexpr int KOPS = 2 * KS * 1024, VOPS = MT * (FP8PV ? 2048 : 1024), REC = mx_rec_bytes(D, FP8PV), STAGE = 2 * REC, NCH = STAGE / 1024;
@@ -268,9 +271,10 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     uint32_t qs = qsc[grp * 64 + lane];
 
     const int Lk = PAGED ? __builtin_amdgcn_readfirstlane(kv_lens[b]) : L;      // keys of this sequence
-    const int koff = PAGED ? Lk - L : 0;                           // key index of query 0's diagonal
+    const int koff = PAGED ? Lk - lq_inner : 0;                    // key index of position 0's diagonal
+    const bool packed = PAGED && lq_inner != L;                    // several heads' positions in this tile
     const int nkt_all = PAGED ? min((Lk + 63) / 64, 2 * max_pages) : (Lk + 63) / 64;   // never past the page table
-    const int nkt = CAUSAL ? min((koff + qt * 128 + 128 + 63) / 64, nkt_all) : nkt_all;   // tiles this workgroup visits
+    const int nkt = (CAUSAL && !packed) ? min((koff + qt * 128 + 128 + 63) / 64, nkt_all) : nkt_all;   // tiles this workgroup visits
     const int nst = (nkt + 1) / 2;
     const unsigned char* kv_head = kv + (size_t)bhkv * (Lp / 64) * REC;
     const int Hkv = Hq / G;
@@ -322,9 +326,9 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     // online softmax of one tile (Alg. 1 inner loop), phi of this lane's P-tilde block, O += V^F^T P-tilde^F
     auto softmax_pv = [&](int j, const unsigned char* rec, floatx16 (&s)[2]) __attribute__((always_inline)) {
         const int k0 = j * 64;
-        const bool need_mask = (k0 + 64 > Lk) || (CAUSAL && k0 + 63 > koff + row0_w);
+        const bool need_mask = (k0 + 64 > Lk) || (CAUSAL && k0 + 63 > koff + (packed ? 0 : row0_w));
         if (__builtin_expect(need_mask, 0)) {
-            const int klim = CAUSAL ? min(Lk - 1, koff + q_row) : Lk - 1;
+            const int klim = CAUSAL ? min(Lk - 1, koff + (packed ? q_row % lq_inner : q_row)) : Lk - 1;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -404,7 +408,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
             }
         }
     };
-    auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || j * 64 <= koff + wave_qmax; };
+    auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || packed || j * 64 <= koff + wave_qmax; };
     // One tile: at odd j the next stage becomes visible (and the buffer two stages back becomes free).
     auto tile_step = [&](int j, floatx16 (&scur)[2], floatx16 (&snext)[2]) __attribute__((always_inline)) {
         if (j & 1) {
@@ -491,7 +495,8 @@ size_t mx_page_bytes(int D) { return 2 * (size_t)mx_rec_bytes(D, false); }
 
 template <int D, bool CAUSAL, bool FP8PV, bool PAGED>
 static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L,
-                           void* o, float* lse, const int* page_table, const int* kv_lens, int max_pages, int num_pages, hipStream_t st)
+                           void* o, float* lse, const int* page_table, const int* kv_lens, int max_pages, int num_pages, int lq_inner,
+                           hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = 3 * 2 * (size_t)mx_rec_bytes(D, FP8PV);
@@ -501,15 +506,15 @@ static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, in
     const float c = 1.4426950408889634f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
                        (const unsigned char*)qops, (const uint32_t*)qsc, (const unsigned char*)kv,
-                       (uint16_t*)o, lse, L, Lp, Hq, Hq / Hkv, c, page_table, kv_lens, max_pages, num_pages);
+                       (uint16_t*)o, lse, L, Lp, Hq, Hq / Hkv, c, page_table, kv_lens, max_pages, num_pages, lq_inner);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 template <int D, bool FP8PV>
 static int launch_fwd_mx_d(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, bool causal,
                            void* o, float* lse, hipStream_t st)
 {
-    return causal ? launch_fwd_mx_t<D, true, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, st)
-                  : launch_fwd_mx_t<D, false, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, st);
+    return causal ? launch_fwd_mx_t<D, true, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, L, st)
+                  : launch_fwd_mx_t<D, false, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, L, st);
 }
 
 int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal, bool fp8pv,
@@ -523,9 +528,10 @@ int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int 
 }
 
 int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, int B, int Hq, int Hkv, int Lq, int D, bool causal,
-                        const int* page_table, const int* kv_lens, int max_pages, int num_pages, void* o, float* lse, hipStream_t st)
+                        const int* page_table, const int* kv_lens, int max_pages, int num_pages, int lq_inner,
+                        void* o, float* lse, hipStream_t st)
 {
-#define AQ_PAGED(DD, CC) launch_fwd_mx_t<DD, CC, false, true>(qops, qsc, cache, B, Hq, Hkv, Lq, o, lse, page_table, kv_lens, max_pages, num_pages, st)
+#define AQ_PAGED(DD, CC) launch_fwd_mx_t<DD, CC, false, true>(qops, qsc, cache, B, Hq, Hkv, Lq, o, lse, page_table, kv_lens, max_pages, num_pages, lq_inner, st)
     if (D == 128) return causal ? AQ_PAGED(128, true) : AQ_PAGED(128, false);
     if (D == 64)  return causal ? AQ_PAGED(64, true) : AQ_PAGED(64, false);
 #undef AQ_PAGED

@@ -63,6 +63,13 @@ def test_paged_decode_step(causal):
     _run(4, 4, 128, [1, 33, 129, 640], 1, causal, seed=2)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Lq", [1, 5, 16, 100])
+def test_paged_grouped_query_heads_share_a_tile(Lq, causal):
+    # G = 8 query heads per kv head: G * Lq <= 128 packs them into one tile (Lq = 1, 5, 16), Lq = 100 does not
+    _run(16, 2, 128, [131, 64 + Lq, 700], Lq, causal, seed=10 + Lq, k_chan=4)
+
+
 def test_paged_whole_sequences_d64_gqa():
     _run(6, 2, 64, [200, 200, 200], 200, True, seed=3, dist="t3", scale=0.5)
 
