@@ -6,6 +6,15 @@
  * forward that also emits the high-precision output O' (Alg. 2) and the
  * backward that re-quantizes the recomputed P and takes D from O' (Alg. 3).
  *
+ * Beyond that core (each group is described where it is declared):
+ *   attnqat_bwd_ablation                the two backward ablations of Sec. 4.2
+ *   attnqat_fwd_opt, attnqat_bwd_opt    K smoothing and two-level quantization of P (Sec. 3.1 / 4.2) as option bits
+ *   attnqat_quantize_mx, attnqat_fwd_infer_mx, attnqat_fwd_mx, attnqat_bwd_mx
+ *                                       the same method in the MX format (E2M1 blocks of 32, E8M0 scales), whose
+ *                                       inference forward runs on the scaled FP4 matrix instruction
+ *   attnqat_quantize_mxfp8, attnqat_fwd_infer_mx_fp8pv   the mixed recipe: FP4 Q K^T, FP8 P V
+ *   attnqat_kv_cache_*, attnqat_fwd_infer_mx_paged       an FP4 KV cache in pages and the forward over it
+ *
  * Conventions shared by every entry point
  *   - Every data pointer is a caller-owned DEVICE pointer (HBM).  Nothing is
  *     allocated, freed or synchronised here: kernels are enqueued on `stream`
@@ -16,7 +25,7 @@
  *   - Tensors are contiguous, [B, H, L, d] with d innermost.  q/o/d_o/dq/o_hp
  *     have H = Hq heads; k/v/dk/dv have H = Hkv heads; Hq % Hkv == 0 and query
  *     head h reads kv head h / (Hq/Hkv) (grouped-query attention).
- *   - L is both the query and the key length.  d is 64 or 128.
+ *   - L is both the query and the key length (except in attnqat_fwd_infer_mx_paged).  d is 64 or 128.
  *   - dtype: ATTNQAT_BF16 (the only supported storage type of q,k,v,d_o and
  *     of o,dq,dk,dv).  lse is fp32, o_hp is fp32.
  *   - causal != 0: query i sees keys 0..i.
