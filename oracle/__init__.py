@@ -66,6 +66,9 @@ def _load():
     L.oracle_phi_mx8.argtypes = [_vp, _l, _l, _vp, _vp, _vp]
     L.oracle_two_level_s1.restype = _d
     L.oracle_two_level_s1.argtypes = [_d]
+    L.oracle_fwd_rows_masked.restype = _i
+    L.oracle_fwd_rows_masked.argtypes = [_vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i, _i,
+                                         _l, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i]
     L.oracle_bwd.restype = _i
     L.oracle_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _l, _i, _i, _i, _i,
                              _vp, _vp, _vp]
@@ -253,7 +256,7 @@ def flat_rows(B, Hq, L, rows):
 
 
 def fwd(q, k, v, causal: bool, Bk: int, quant_qkv: bool = True, quant_p: bool = True,
-        scale_mode: int = 0, rows=None, dump_p: bool = False):
+        scale_mode: int = 0, rows=None, dump_p: bool = False, block_mask=None, mask_block=(128, 128)):
     """Alg. 2 (training forward; Alg. 1's O and L are the same numbers).
 
     q [B,Hq,L,d], k/v [B,Hkv,L,d].  rows: None (all rows; outputs shaped
@@ -269,9 +272,18 @@ def fwd(q, k, v, causal: bool, Bk: int, quant_qkv: bool = True, quant_p: bool = 
         n, shp, rp = rows.size, (rows.size,), rows
     O = np.empty(shp + (d,)); Op = np.empty(shp + (d,)); Lse = np.empty(shp)
     P = np.empty((n, L), np.float32) if dump_p else None
-    rc = _load().oracle_fwd_rows(_p(qf), _p(kf), _p(vf), B, Hq, Hkv, L, d, int(causal), Bk,
-                                 int(quant_p), scale_mode, n, _p(rp),
-                                 _p(O), _p(Op), _p(Lse), _p(P))
+    if block_mask is None:
+        rc = _load().oracle_fwd_rows(_p(qf), _p(kf), _p(vf), B, Hq, Hkv, L, d, int(causal), Bk,
+                                     int(quant_p), scale_mode, n, _p(rp),
+                                     _p(O), _p(Op), _p(Lse), _p(P))
+    else:
+        # block-sparse attention: block_mask uint8 [B,Hq,ceil(L/bq),ceil(L/bk)], zero = the block is left out
+        bq, bk = mask_block
+        bm = np.ascontiguousarray(block_mask, dtype=np.uint8)
+        assert bm.shape == (B, Hq, (L + bq - 1) // bq, (L + bk - 1) // bk), bm.shape
+        rc = _load().oracle_fwd_rows_masked(_p(qf), _p(kf), _p(vf), B, Hq, Hkv, L, d, int(causal), Bk,
+                                            int(quant_p), scale_mode, n, _p(rp),
+                                            _p(O), _p(Op), _p(Lse), _p(P), _p(bm), bq, bk)
     if rc:
         raise ValueError(f"oracle_fwd_rows failed ({rc})")
     out = {"O": O, "Op": Op, "L": Lse}

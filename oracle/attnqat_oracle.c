@@ -307,8 +307,14 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                     int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
                     int quant_p, int scale_mode, int mx,
                     long nrows, const long* rows,
-                    double* O, double* Op, double* Lse, float* Pdump)
+                    double* O, double* Op, double* Lse, float* Pdump,
+                    const uint8_t* bmask, int mbq, int mbk)
 {
+    /* Block-sparse attention (the inference kernel of Sec. 3.4 supports it): bmask[B,Hq,ceil(L/mbq),ceil(L/mbk)],
+     * a zero byte removes the whole block of mbq queries x mbk keys (mbk a multiple of Bk): its key tiles are not
+     * visited.  A row with no key left gets O = 0 and L = -inf. */
+    if (bmask && (mbq < 1 || mbk < Bk || mbk % Bk)) return -1;
+    const long nqb = bmask ? (L + mbq - 1) / mbq : 0, nkb = bmask ? (L + mbk - 1) / mbk : 0;
     const int pb = (mx == 1 || mx == 2) ? 32 : 16;               /* keys per P block */
     if (!qf || !kf || !vf || Hq % Hkv || Bk < pb || Bk % pb || d < 1) return -1;
     if (mx == 3 && Bk != TWO_LEVEL_SPAN) return -1;
@@ -339,6 +345,7 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
             if (Pdump) for (long k = 0; k < L; ++k) Pdump[n * L + k] = 0.0f;
             long kend = causal ? i + 1 : L;           /* visible keys are [0, kend) */
             for (long k0 = 0; k0 < kend; k0 += Bk) {  /* tiles with no visible key change nothing */
+                if (bmask && !bmask[(((long)b * Hq + h) * nqb + i / mbq) * nkb + k0 / mbk]) continue;
                 int nk = (int)((kend - k0 < Bk) ? kend - k0 : Bk);
                 double mt = -INFINITY;
                 for (int k = 0; k < nk; ++k) {
@@ -377,10 +384,10 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                 }
             }
             for (int c = 0; c < d; ++c) {
-                if (O)  O[n * d + c]  = o[c] / l;
-                if (Op) Op[n * d + c] = op[c] / l;
+                if (O)  O[n * d + c]  = l > 0.0 ? o[c] / l : 0.0;
+                if (Op) Op[n * d + c] = l > 0.0 ? op[c] / l : 0.0;
             }
-            if (Lse) Lse[n] = m + log(l);
+            if (Lse) Lse[n] = l > 0.0 ? m + log(l) : -INFINITY;
         }
         }
         free(S); free(Pt); free(Pf); free(o); free(op);
@@ -400,7 +407,20 @@ int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
 {
     return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode,
                          scale_mode == 2 ? 1 : scale_mode == 3 ? 2 : scale_mode == 4 ? 3 : 0,
-                         nrows, rows, O, Op, Lse, Pdump);
+                         nrows, rows, O, Op, Lse, Pdump, NULL, 0, 0);
+}
+
+/* The same with a block mask (see fwd_rows_impl). */
+int oracle_fwd_rows_masked(const float* qf, const float* kf, const float* vf,
+                           int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
+                           int quant_p, int scale_mode,
+                           long nrows, const long* rows,
+                           double* O, double* Op, double* Lse, float* Pdump,
+                           const uint8_t* bmask, int mbq, int mbk)
+{
+    return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode,
+                         scale_mode == 2 ? 1 : scale_mode == 3 ? 2 : scale_mode == 4 ? 3 : 0,
+                         nrows, rows, O, Op, Lse, Pdump, bmask, mbq, mbk);
 }
 
 /* ----------------------------------------------------------------- backward */
