@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--paged-lq", type=int, default=0,
                     help="serving mode (not a benchmark configuration): the MX forward over a paged FP4 KV cache with this many "
                          "query positions per sequence (1 = a decode step) for 32 sequences of 4k-16k keys, 32 query / 8 kv heads")
+    ap.add_argument("--sparse-keep", type=float, default=0.0,
+                    help="block-sparse mode (not a benchmark configuration): the MX inference forward of the workload's shape "
+                         "under a seeded random mask of 128 x 128 blocks that keeps this fraction (plus every query block's own block)")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     args = ap.parse_args()
@@ -81,6 +84,8 @@ def main():
     if args.paged_lq > 0:
         return bench_paged(args, aq, torch, np)
     w = W.by_name(args.workload)
+    if args.sparse_keep > 0:
+        return bench_sparse(args, aq, torch, np, w, W)
     fp8pv = args.format == "mx_fp8pv"
     mx = args.format == "mx" or fp8pv
     train = w.passes == "fwd+bwd" and args.passes == "auto" and not fp8pv
@@ -269,6 +274,55 @@ def bench_paged(args, aq, torch, np):
                    "page_keys": 128, "cache_bytes": int(cache_bytes), "format": "mx"},
         "tokens_per_s": round(B * Lq / (ms * 1e-3), 1), "per_kernel_ms": {k_: round(v_, 3) for k_, v_ in kern.items()},
         "roofline": roofline, "cpu_baseline": None}), flush=True)
+
+
+def bench_sparse(args, aq, torch, np, w, W):
+    """Block-sparse MX forward on the workload's shape: a seeded random mask of 128 x 128 blocks; the flops counted are
+    those of the blocks kept (below the diagonal only, if causal)."""
+    B, Hq, Hkv, L, d = w.B, w.Hq, w.Hkv, w.L, w.d
+    x = W.make_inputs(w, with_do=False)
+    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    nb = (L + 127) // 128
+    rng = np.random.default_rng(w.seed)
+    bm = (rng.random((B, Hq, nb, nb)) < args.sparse_keep).astype(np.uint8)
+    bm[:, :, np.arange(nb), np.arange(nb)] = 1
+    if w.causal:
+        bm *= np.tril(np.ones((nb, nb), np.uint8))
+    edge = np.minimum(128, L - 128 * np.arange(nb)).astype(np.float64)              # rows / keys of every block
+    pairs = edge[:, None] * edge[None, :]
+    if w.causal:
+        pairs[np.arange(nb), np.arange(nb)] = edge * (edge + 1) / 2
+    kept_pairs = float((bm.astype(np.float64) * pairs).sum())
+    mask = torch.from_numpy(bm).cuda()
+    o = torch.empty_like(q); lse = torch.empty((B, Hq, L), dtype=torch.float32, device="cuda")
+    ws = torch.empty(aq.workspace_bytes(aq.WS_FWD_INFER_MX_SPARSE, B, Hq, Hkv, L, d), dtype=torch.uint8, device="cuda")
+    step = lambda: aq.attnqat_fwd_infer_mx_sparse(q, k, v, w.causal, mask, workspace=ws, out=(o, lse))
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    aq.profile_enable(True)
+    step(); torch.cuda.synchronize()
+    kern = dict(aq.profile_read())
+    aq.profile_enable(False)
+    kms = kern["fwd_infer_mx_sparse"]
+    flops = 4.0 * kept_pairs * d
+    print(json.dumps({
+        "metric": "FP4-attention fwd TFLOPS (1 MI355X)", "value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax", "data": "synthetic",
+        "config": {"workload": w.name + " under a random block mask (not a benchmark configuration)", "B": B, "Hq": Hq, "Hkv": Hkv, "L": L,
+                   "d": d, "causal": w.causal, "mask_block": [128, 128], "blocks_kept": round(float(bm.mean()), 4), "format": "mx"},
+        "per_kernel_ms": {k_: round(v_, 3) for k_, v_ in kern.items()},
+        "roofline": {"bound": "mfma", "kernel": "fwd_infer_mx_sparse", "achieved": round(flops / (kms * 1e-3) / 1e12, 2),
+                     "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(flops / (kms * 1e-3) / 1e12 / MFMA_FP4_PEAK_TFLOPS, 4),
+                     "traffic": None, "kernel_ms": round(kms, 3)},
+        "cpu_baseline": None}), flush=True)
 
 
 def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False, two_level=False):

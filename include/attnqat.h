@@ -14,6 +14,7 @@
  *                                       inference forward runs on the scaled FP4 matrix instruction
  *   attnqat_quantize_mxfp8, attnqat_fwd_infer_mx_fp8pv   the mixed recipe: FP4 Q K^T, FP8 P V
  *   attnqat_kv_cache_*, attnqat_fwd_infer_mx_paged       an FP4 KV cache in pages and the forward over it
+ *   attnqat_fwd_infer_mx_sparse                          block-sparse attention
  *
  * Conventions shared by every entry point
  *   - Every data pointer is a caller-owned DEVICE pointer (HBM).  Nothing is
@@ -64,6 +65,7 @@ extern "C" {
 #define ATTNQAT_WS_BWD_MX           5   /* attnqat_bwd_mx                              */
 #define ATTNQAT_WS_FWD_INFER_MX_FP8PV 6 /* attnqat_fwd_infer_mx_fp8pv                  */
 #define ATTNQAT_WS_FWD_INFER_MX_PAGED 7 /* attnqat_fwd_infer_mx_paged (L = queries per sequence) */
+#define ATTNQAT_WS_FWD_INFER_MX_SPARSE 8 /* attnqat_fwd_infer_mx_sparse                        */
 
 /*
  * phi of Eq. 1 (Sec. 3.1) along d: for every 16 consecutive elements
@@ -266,6 +268,18 @@ int attnqat_kv_cache_write_mx(const void* k, const void* v, int Hkv, int L, int 
 int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
                                const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
                                void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Block-sparse attention (Sec. 6: the paper's datacenter inference kernel supports it): attnqat_fwd_infer_mx with a
+ * block mask.  block_mask [B,Hq,nb,nb] bytes (device, read), nb = ceil(L/128): a zero byte removes the block of 128
+ * queries x 128 keys, i.e. those keys count as masked for those queries and their key tiles are not visited (the
+ * order of the remaining tiles, and with it the running maximum that P-tilde is quantized against, is unchanged).
+ * The causal flag still applies inside the blocks that are kept.  A query without any key left gets o = 0 and
+ * lse = -inf.  Workspace: ATTNQAT_WS_FWD_INFER_MX_SPARSE.
+ */
+int attnqat_fwd_infer_mx_sparse(const void* q, const void* k, const void* v,
+                                int B, int Hq, int Hkv, int L, int d, int causal, int dtype, const uint8_t* block_mask,
+                                void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Training forward (Alg. 2) and backward (Alg. 3) in the MX format, for training against

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libattnqat.so")
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4, -5
 BF16 = 0
 (WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX, WS_FWD_MX, WS_BWD_MX, WS_FWD_INFER_MX_FP8PV,
- WS_FWD_INFER_MX_PAGED) = 0, 1, 2, 3, 4, 5, 6, 7
+ WS_FWD_INFER_MX_PAGED, WS_FWD_INFER_MX_SPARSE) = 0, 1, 2, 3, 4, 5, 6, 7, 8
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _SIGNATURES = {
@@ -41,6 +41,7 @@ _SIGNATURES = {
     "attnqat_kv_cache_page_bytes": (_sz, [_i, _i]),
     "attnqat_kv_cache_write_mx": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp]),
     "attnqat_fwd_infer_mx_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_fwd_infer_mx_sparse": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                             _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -125,6 +126,28 @@ def attnqat_quantize(x, want_codes=True, want_xf=True):
 
 
 OPT_SMOOTH_K, OPT_TWO_LEVEL_P = 1, 2
+
+
+def attnqat_fwd_infer_mx_sparse(q, k, v, causal: bool, block_mask, workspace=None, out=None):
+    """Alg. 1 (MX, FP4 matrix instruction) with a block mask: uint8 CUDA tensor [B,Hq,nb,nb], nb = ceil(L/128), zero =
+    the 128 x 128 block is left out.  Returns (o bf16, lse fp32)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    nb = (L + 127) // 128
+    if not (block_mask.is_cuda and block_mask.dtype == torch.uint8 and block_mask.is_contiguous()
+            and tuple(block_mask.shape) == (B, Hq, nb, nb)):
+        raise AttnQatError("block_mask must be a contiguous uint8 CUDA tensor [B,Hq,ceil(L/128),ceil(L/128)]")
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    ws, nbytes = _workspace(WS_FWD_INFER_MX_SPARSE, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_fwd_infer_mx_sparse(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16, _ptr(block_mask),
+                                             _ptr(o), _ptr(lse), _ptr(ws), nbytes, _stream()))
+    return o, lse
 
 
 def kv_cache_page_bytes(Hkv: int, d: int) -> int:

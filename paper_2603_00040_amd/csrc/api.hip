@@ -175,6 +175,12 @@ size_t attnqat_workspace_bytes(int which, int B, int Hq, int Hkv, int L, int d)
         c.take(mx_qops_bytes(B * Hq, L, d)); c.take(mx_qsc_bytes(B * Hq, L));
         return c.off;
     }
+    case ATTNQAT_WS_FWD_INFER_MX_SPARSE: {
+        const size_t nb = round_up(L, kRowPad) / 128, nrows = (size_t)B * Hq * nb;
+        Carver c{nullptr, carve_mx(nullptr, B, Hq, Hkv, L, d, false).bytes};
+        c.take(nrows * nb * 4); c.take(nrows * 4);
+        return c.off;
+    }
     case ATTNQAT_WS_FWD_MX:    return carve_fwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
     case ATTNQAT_WS_BWD_MX:    return carve_bwd(nullptr, B, Hq, Hkv, L, d, true).bytes;
     default:                   return 0;
@@ -253,6 +259,30 @@ int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
                                void* workspace, size_t workspace_bytes, void* stream)
 {
     return fwd_infer_mx_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, true, o, lse, workspace, workspace_bytes, stream);
+}
+
+int attnqat_fwd_infer_mx_sparse(const void* q, const void* k, const void* v,
+                                int B, int Hq, int Hkv, int L, int d, int causal, int dtype, const uint8_t* block_mask,
+                                void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse || !block_mask) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    const size_t nb = round_up(L, kRowPad) / 128, nrows = (size_t)B * Hq * nb;
+    MxWs w = carve_mx(workspace, B, Hq, Hkv, L, d, false);
+    Carver c{(unsigned char*)workspace, w.bytes};
+    int* list = (int*)c.take(nrows * nb * 4);
+    int* cnt = (int*)c.take(nrows * 4);
+    if (!workspace || workspace_bytes < c.off) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    if (launch_mx_quant(q, B * Hq, L, d, 0, 1, false, w.qops, w.qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(k, B * Hkv, L, d, 0, 2, false, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(v, B * Hkv, L, d, 1, 2, false, w.kv, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_qkv_mx", st);
+    if (launch_fwd_mx_sparse(w.qops, w.qsc, w.kv, B, Hq, Hkv, L, d, causal != 0, block_mask, list, cnt, o, lse, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("fwd_infer_mx_sparse", st);
+    return ATTNQAT_OK;
 }
 
 size_t attnqat_kv_cache_page_bytes(int Hkv, int d)

@@ -74,4 +74,9 @@ int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, in
                         const int* page_table, const int* kv_lens, int max_pages, int num_pages, int lq_inner,
                         void* o, float* lse, hipStream_t st);
 
+// Block-sparse forward on contiguous kv records: block_mask [B*Hq*nb, nb] bytes with nb = ceil(L/128); list
+// ([B*Hq*nb, nb] int32) and cnt ([B*Hq*nb] int32) are scratch that the call fills.
+int launch_fwd_mx_sparse(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
+                         const unsigned char* block_mask, int* list, int* cnt, void* o, float* lse, hipStream_t st);
+
 }  // namespace aq

@@ -240,13 +240,18 @@ __global__ __launch_bounds__(D) void mx_quant_l_kernel(
 // lq_inner positions each (L = G * lq_inner; a kv head's queries are contiguous in [B,Hq,Lq,d], so grouped-query
 // heads with few positions share one tile and one pass over the pages); lq_inner == L: plain rows.  Under the causal
 // mask the query at position i of its head sees keys 0 .. kv_len - lq_inner + i.
-template <int D, bool CAUSAL, bool FP8PV, bool PAGED>
+//
+// KVM == 2, block-sparse attention on contiguous kv records: the workgroup visits only the 128-key blocks listed for its
+// 128 query rows (page_table then is the list [B*Hq*ceil(L/128), max_pages] of block indices in increasing order and
+// kv_lens the number of entries per row of that list); a row that ends up without any key gets O = 0 and L = -inf.
+template <int D, bool CAUSAL, bool FP8PV, int KVM /* 0 contiguous, 1 paged KV cache, 2 block-sparse */>
 __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     const unsigned char* __restrict__ qops, const uint32_t* __restrict__ qsc, const unsigned char* __restrict__ kv,
     uint16_t* __restrict__ O, float* __restrict__ lse, int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */,
     const int* __restrict__ page_table, const int* __restrict__ kv_lens, int max_pages, int num_pages, int lq_inner)
 {
     constexpr int KS = D / 64, MT = D / 32;
+    constexpr bool PAGED = KVM == 1, SPARSE = KVM == 2;
     constexpr int KOPS = 2 * KS * 1024, VOPS = MT * (FP8PV ? 2048 : 1024), REC = mx_rec_bytes(D, FP8PV), STAGE = 2 * REC, NCH = STAGE / 1024;
     static_assert(STAGE % 1024 == 0, "a stage is a whole number of 1 KiB wave copies");
     extern __shared__ __align__(16) unsigned char smem[];          // 3 stage buffers
@@ -274,12 +279,20 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     const int koff = PAGED ? Lk - lq_inner : 0;                    // key index of position 0's diagonal
     const bool packed = PAGED && lq_inner != L;                    // several heads' positions in this tile
     const int nkt_all = PAGED ? min((Lk + 63) / 64, 2 * max_pages) : (Lk + 63) / 64;   // never past the page table
-    const int nkt = (CAUSAL && !packed) ? min((koff + qt * 128 + 128 + 63) / 64, nkt_all) : nkt_all;   // tiles this workgroup visits
+    // block-sparse: the blocks of this workgroup's row of the list, and the first key of the block visited s-th
+    const int* blk_row = SPARSE ? page_table + ((size_t)bh * nqt + qt) * max_pages : nullptr;
+    const int nblk = SPARSE ? min(max(__builtin_amdgcn_readfirstlane(kv_lens[(size_t)bh * nqt + qt]), 0), max_pages) : 0;
+    auto blk_of = [&](int s) __attribute__((always_inline)) -> int {
+        return min(max(__builtin_amdgcn_readfirstlane(blk_row[s]), 0), Lp / 128 - 1);      // a bad entry reads a wrong block, never outside
+    };
+    const int nkt = SPARSE ? 2 * nblk
+                  : (CAUSAL && !packed) ? min((koff + qt * 128 + 128 + 63) / 64, nkt_all) : nkt_all;   // tiles this workgroup visits
     const int nst = (nkt + 1) / 2;
+    auto k0_of = [&](int j) __attribute__((always_inline)) -> int { return SPARSE ? blk_of(j >> 1) * 128 + (j & 1) * 64 : j * 64; };
     const unsigned char* kv_head = kv + (size_t)bhkv * (Lp / 64) * REC;
     const int Hkv = Hq / G;
     auto issue_stage = [&](int s) __attribute__((always_inline)) {
-        const unsigned char* src = kv_head + (size_t)s * STAGE;
+        const unsigned char* src = kv_head + (size_t)(SPARSE ? blk_of(s) : s) * STAGE;
         if constexpr (PAGED) {
             int page = __builtin_amdgcn_readfirstlane(page_table[(size_t)b * max_pages + s]);
             page = min(max(page, 0), num_pages - 1);               // a bad table entry reads a wrong page, never outside the cache
@@ -325,7 +338,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
     };
     // online softmax of one tile (Alg. 1 inner loop), phi of this lane's P-tilde block, O += V^F^T P-tilde^F
     auto softmax_pv = [&](int j, const unsigned char* rec, floatx16 (&s)[2]) __attribute__((always_inline)) {
-        const int k0 = j * 64;
+        const int k0 = k0_of(j);
         const bool need_mask = (k0 + 64 > Lk) || (CAUSAL && k0 + 63 > koff + (packed ? 0 : row0_w));
         if (__builtin_expect(need_mask, 0)) {
             const int klim = CAUSAL ? min(Lk - 1, koff + (packed ? q_row % lq_inner : q_row)) : Lk - 1;
@@ -342,8 +355,11 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
         for (int i = 4; i < 16; ++i) mp[i & 3] = max_nc(max_nc(mp[i & 3], s[0][i]), s[1][i]);
         const float mown = max_nc(max_nc(mp[0], mp[1]), max_nc(mp[2], mp[3]));      // maximum of this lane's block
         const float mnew = fmaxf(m, xhalf_max(mown));
-        const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
-        const float ms = mnew * c;
+        // (block-sparse: the first blocks a row meets may lie entirely in its causal future; until it has seen a key
+        //  its maximum is -inf, and a finite stand-in keeps the two expressions below free of inf - inf)
+        const float mref = (SPARSE && mnew == -INFINITY) ? 0.0f : mnew;
+        const float alpha = __builtin_amdgcn_exp2f((m - mref) * c);
+        const float ms = mref * c;
         m = mnew;
         float p[32];
         float rp[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -408,7 +424,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
             }
         }
     };
-    auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || packed || j * 64 <= koff + wave_qmax; };
+    auto wave_sees = [&](int j) __attribute__((always_inline)) -> bool { return !CAUSAL || packed || k0_of(j) <= koff + wave_qmax; };
     // One tile: at odd j the next stage becomes visible (and the buffer two stages back becomes free).
     auto tile_step = [&](int j, floatx16 (&scur)[2], floatx16 (&snext)[2]) __attribute__((always_inline)) {
         if (j & 1) {
@@ -436,7 +452,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
 
     // ---- epilogue: O /= l, L = m + log l
     const float l = xhalf_sum(lsum);
-    const float inv_l = (PAGED && !(l > 0.0f)) ? 0.0f : 1.0f / l;         // a sequence without keys: O = 0, L = -inf
+    const float inv_l = ((PAGED || SPARSE) && !(l > 0.0f)) ? 0.0f : 1.0f / l;         // a row without keys: O = 0, L = -inf
     if (q_row < L) {
         const size_t row = (size_t)bh * L + q_row;
 #pragma unroll
@@ -493,14 +509,14 @@ size_t mx_qops_bytes(int BHq, int L, int D) { return (size_t)BHq * round_up(L, k
 size_t mx_qsc_bytes(int BHq, int L) { return (size_t)BHq * (round_up(L, kRowPad) / 32) * 64 * 4; }
 size_t mx_page_bytes(int D) { return 2 * (size_t)mx_rec_bytes(D, false); }
 
-template <int D, bool CAUSAL, bool FP8PV, bool PAGED>
+template <int D, bool CAUSAL, bool FP8PV, int KVM>
 static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L,
                            void* o, float* lse, const int* page_table, const int* kv_lens, int max_pages, int num_pages, int lq_inner,
                            hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = 3 * 2 * (size_t)mx_rec_bytes(D, FP8PV);
-    auto kern = fwd_mx_kernel<D, CAUSAL, FP8PV, PAGED>;
+    auto kern = fwd_mx_kernel<D, CAUSAL, FP8PV, KVM>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)smem) != hipSuccess) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
@@ -513,8 +529,8 @@ template <int D, bool FP8PV>
 static int launch_fwd_mx_d(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, bool causal,
                            void* o, float* lse, hipStream_t st)
 {
-    return causal ? launch_fwd_mx_t<D, true, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, L, st)
-                  : launch_fwd_mx_t<D, false, FP8PV, false>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, L, st);
+    return causal ? launch_fwd_mx_t<D, true, FP8PV, 0>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, L, st)
+                  : launch_fwd_mx_t<D, false, FP8PV, 0>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, nullptr, nullptr, 0, 0, L, st);
 }
 
 int launch_fwd_mx(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal, bool fp8pv,
@@ -531,10 +547,35 @@ int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, in
                         const int* page_table, const int* kv_lens, int max_pages, int num_pages, int lq_inner,
                         void* o, float* lse, hipStream_t st)
 {
-#define AQ_PAGED(DD, CC) launch_fwd_mx_t<DD, CC, false, true>(qops, qsc, cache, B, Hq, Hkv, Lq, o, lse, page_table, kv_lens, max_pages, num_pages, lq_inner, st)
+#define AQ_PAGED(DD, CC) launch_fwd_mx_t<DD, CC, false, 1>(qops, qsc, cache, B, Hq, Hkv, Lq, o, lse, page_table, kv_lens, max_pages, num_pages, lq_inner, st)
     if (D == 128) return causal ? AQ_PAGED(128, true) : AQ_PAGED(128, false);
     if (D == 64)  return causal ? AQ_PAGED(64, true) : AQ_PAGED(64, false);
 #undef AQ_PAGED
+    return -1;
+}
+
+// Block lists of the block-sparse forward: row r = (b * Hq + h) * nqb + query block of mask [rows, nkb] (bytes, zero =
+// the block is left out) -> the indices of its non-zero key blocks in increasing order, and their number.
+__global__ void mx_block_list_kernel(const unsigned char* __restrict__ mask, int nrows, int nkb, int* __restrict__ list, int* __restrict__ cnt)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= nrows) return;
+    int n = 0;
+    for (int kb = 0; kb < nkb; ++kb)
+        if (mask[(size_t)r * nkb + kb]) list[(size_t)r * nkb + n++] = kb;
+    cnt[r] = n;
+}
+
+int launch_fwd_mx_sparse(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
+                         const unsigned char* block_mask, int* list, int* cnt, void* o, float* lse, hipStream_t st)
+{
+    const int nb = round_up(L, kRowPad) / 128, nrows = B * Hq * nb;
+    hipLaunchKernelGGL(mx_block_list_kernel, dim3((unsigned)((nrows + 127) / 128)), dim3(128), 0, st, block_mask, nrows, nb, list, cnt);
+    if (hipGetLastError() != hipSuccess) return -1;
+#define AQ_SPARSE(DD, CC) launch_fwd_mx_t<DD, CC, false, 2>(qops, qsc, kv, B, Hq, Hkv, L, o, lse, list, cnt, nb, 0, L, st)
+    if (D == 128) return causal ? AQ_SPARSE(128, true) : AQ_SPARSE(128, false);
+    if (D == 64)  return causal ? AQ_SPARSE(64, true) : AQ_SPARSE(64, false);
+#undef AQ_SPARSE
     return -1;
 }
 
