@@ -277,3 +277,81 @@ def test_full_size_options(cfg, opts):
     eK, eV = rel_l2(host(dk[b, kv]), rdk[0]), rel_l2(host(dv[b, kv]), rdv[0], zero_rms=1e-6)
     print(f"[{w.name}] options {opts}: dK rel-L2 {eK:.2e}  dV rel-L2 {eV:.2e} (oracle dV non-zero fraction {float((rdv[0] != 0).mean()):.3f})", flush=True)
     assert eK <= TOL and eV <= TOL
+
+
+@pytest.mark.parametrize("cfg", [1, 4])
+def test_full_size_block_sparse_forward(cfg):
+    """attnqat_fwd_infer_mx_sparse on the full inference shapes under a seeded random mask that keeps a quarter of the
+    128 x 128 blocks plus the diagonal (under the causal mask also blocks above the diagonal, which then hold no visible
+    key): O and L on sampled rows against the oracle's forward under the same mask."""
+    import paper_2603_00040_amd as aq
+    w = W.CONFIGS[cfg]
+    print(f"\n[{w.name}] generating inputs", flush=True)
+    x = W.make_inputs(w, with_do=False)
+    q, k, v = to_dev(x["q"]), to_dev(x["k"]), to_dev(x["v"])
+    b, kv, qheads, rows = _selection(w)
+    L, Bk = w.L, aq.block_k()
+    nb = (L + 127) // 128
+    bm = (np.random.default_rng(77 + w.seed).random((w.B, w.Hq, nb, nb)) < 0.25).astype(np.uint8)
+    bm[:, :, np.arange(nb), np.arange(nb)] = 1
+    sub = _sub(x, b, kv, qheads)
+    flat = np.asarray([hi * L + r for hi, rs in enumerate(rows) for r in rs], dtype=np.int64)
+    gi = [(b, h, r) for h, rs in zip(qheads, rows) for r in rs]
+    pick = lambda t: torch.stack([t[bb, hh, rr] for bb, hh, rr in gi])
+    print(f"[{w.name}] GPU block-sparse MX forward, {bm.mean():.3f} of the blocks kept", flush=True)
+    o, lse = aq.attnqat_fwd_infer_mx_sparse(q, k, v, w.causal, torch.from_numpy(bm).cuda())
+    torch.cuda.synchronize()
+    print(f"[{w.name}] oracle on {flat.size} rows", flush=True)
+    rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, scale_mode=oracle.MX, rows=flat,
+                    block_mask=np.ascontiguousarray(bm[b:b + 1, qheads]))
+    eO = rel_l2(host(pick(o)), rf["O"]); eL = max_abs(host(pick(lse)), rf["L"])
+    print(f"[{w.name}] sparse MX O rel-L2 {eO:.2e}  L max-abs {eL:.2e}", flush=True)
+    assert np.isfinite(rf["L"]).all()
+    assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
+
+
+@pytest.mark.parametrize("Lq", [1, 512])
+def test_full_size_paged_serving(Lq):
+    """attnqat_fwd_infer_mx_paged on the serving shape bench.py --paged-lq times (32 sequences of 4096..16384 keys, 32 query
+    and 8 kv heads, d = 128, causal, pages scattered over the cache): a decode step and a 512-query chunk; O and L of
+    sampled (sequence, head, position) against the oracle's MX forward of that sequence."""
+    import paper_2603_00040_amd as aq
+    B, Hq, Hkv, d = 32, 32, 8, 128
+    rng = np.random.default_rng(7)
+    kv_lens = np.maximum(rng.integers(4096, 16385, B), Lq).astype(np.int32)
+    pages_of = [(int(n) + 127) // 128 for n in kv_lens]
+    max_pages, num_pages = max(pages_of), sum(pages_of)
+    perm = rng.permutation(num_pages).astype(np.int32)
+    table = np.zeros((B, max_pages), np.int32)
+    cache = torch.empty(num_pages * aq.kv_cache_page_bytes(Hkv, d), dtype=torch.uint8, device="cuda")
+    cache.random_(0, 256)
+    check = sorted({0, B - 1, int(np.argmin(kv_lens)), int(np.argmax(kv_lens))})
+    kept, qb, nxt = {}, [], 0
+    print(f"\n[paged Lq={Lq}] writing {num_pages} pages", flush=True)
+    for bb in range(B):
+        n = int(kv_lens[bb])
+        table[bb, :pages_of[bb]] = perm[nxt:nxt + pages_of[bb]]; nxt += pages_of[bb]
+        kb = W.fill(1, Hkv, n, d, 500 + bb, W.TENSOR_K, "normal", 1.0, n_chan=4, chan_mult=20.0)
+        vb = W.fill(1, Hkv, n, d, 500 + bb, W.TENSOR_V, "normal", 1.0)
+        qf = W.fill(1, Hq, Lq, d, 500 + bb, W.TENSOR_Q, "normal", 1.0)
+        aq.attnqat_kv_cache_write_mx(to_dev(kb), to_dev(vb), cache, torch.from_numpy(table[bb, :pages_of[bb]].copy()).cuda())
+        qb.append(qf[0])
+        if bb in check:
+            kept[bb] = (kb, vb)
+    qall = np.ascontiguousarray(np.stack(qb))
+    o, lse = aq.attnqat_fwd_infer_mx_paged(to_dev(qall), cache, num_pages, torch.from_numpy(table).cuda(),
+                                           torch.from_numpy(kv_lens).cuda(), Hkv, True)
+    torch.cuda.synchronize()
+    assert not torch.isnan(o.float()).any() and not torch.isnan(lse).any()
+    pos = sorted({0, Lq - 1, Lq // 2, *np.random.default_rng(8).integers(0, Lq, 3).tolist()})
+    for bb in check:
+        n = int(kv_lens[bb])
+        kb, vb = kept[bb]
+        qf = np.zeros((1, Hq, n, d), np.float32)
+        qf[0, :, n - Lq:] = f32(qall[bb])
+        rows = oracle.flat_rows(1, Hq, n, [(0, h, n - Lq + i) for h in range(Hq) for i in pos])
+        ref = oracle.fwd(qf, f32(kb), f32(vb), True, aq.block_k(), scale_mode=oracle.MX, rows=rows)
+        got_o = host(o[bb][:, pos]).reshape(-1, d); got_l = host(lse[bb][:, pos]).reshape(-1)
+        eO = rel_l2(got_o, ref["O"]); eL = max_abs(got_l, ref["L"])
+        print(f"[paged Lq={Lq}] sequence {bb} ({n} keys): O rel-L2 {eO:.2e}  L max-abs {eL:.2e} on {rows.size} rows", flush=True)
+        assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(ref["L"]).max())
