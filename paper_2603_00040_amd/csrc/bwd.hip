@@ -604,7 +604,21 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 sc[0] = sc[1] = e8m0_as_f32(byte);
                 inv[0] = inv[1] = e8m0_inverse_as_f32(byte);
                 nz = amax > 0.0f;
-            } else {
+            } else if constexpr (PQ == 1) {
+                // Is any block scale of this tile non-zero?  A scale is RNE_E4M3(amax / 6), which is zero exactly when
+                // amax / 6 <= 2^-10 (half of the smallest subnormal, and the tie goes to the even neighbour, zero), and
+                // it grows with amax: some block has a non-zero scale iff some lane's largest P passes that test.  The
+                // scales themselves are only needed where the answer is yes (below).
+                float p4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) p4[t] = fmaxf(fmaxf(s[t], s[4 + t]), fmaxf(s[8 + t], s[12 + t]));
+                nz = fmaxf(fmaxf(p4[0], p4[1]), fmaxf(p4[2], p4[3])) * (1.0f / 6.0f) > 0.0009765625f;
+            } else if constexpr (PQ == 3) {
+                nz = true;       // decided with the scales below: after the row factor a tile is almost never all zero
+            }
+            // block scales of phi(P): one per 16 keys = registers 8*gq .. 8*gq+7 of both halves (NVFP4, with or without
+            // the row factor of the two-level form)
+            auto nvfp4_scales = [&]() __attribute__((always_inline)) {
                 // Two-level quantization of P (PQ == 3): a row of this wave's tile (32 aligned keys) is divided by s1,
                 // the smallest power of two with 2688 s1 >= max(row maximum, 2^-24), before the NVFP4 blocks
                 float s1 = 1.0f, inv1 = 1.0f;
@@ -622,6 +636,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                     s1 = __uint_as_float(e1 << 23);
                     inv1 = __uint_as_float((254u - e1) << 23);
                 }
+                bool any = false;
 #pragma unroll
                 for (int gq = 0; gq < 2; ++gq) {
                     const float s2 = rne_e4m3_grid((amax[gq] * inv1) * (1.0f / 6.0f));
@@ -629,9 +644,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                     // stands in for the block scale (a power of two times an E4M3 value: still exact in bf16)
                     sc[gq] = s2 * s1;
                     inv[gq] = s2 > 0.0f ? __builtin_amdgcn_rcpf(s2) * inv1 : 0.0f;
-                    nz = nz || s2 > 0.0f;
+                    any = any || s2 > 0.0f;
                 }
-            }
+                return any;
+            };
+            if constexpr (PQ == 3) nz = nvfp4_scales();
             // dS = P (dP - D_i)/sqrt(d) from the fp32 P, scaled, as fp16, staged as [query][key]
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4) {                           // 4 consecutive keys per store
@@ -686,6 +703,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             if constexpr (COUNT) ++n_tiles;
             if (!PQUANT || __builtin_amdgcn_ballot_w64(nz) != 0) {
                 if constexpr (COUNT) ++n_pf_tiles;
+                if constexpr (PQ == 1) nvfp4_scales();
                 // P^F = phi^-1(phi(P)), staged as [query][key].  Ablation (Sec. 4.2, "no fake quantization of P in
                 // the backward"): the fp32 P itself, in two passes as a bf16 hi + lo pair.
 #pragma unroll
