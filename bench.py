@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--sparse-keep", type=float, default=0.0,
                     help="block-sparse mode (not a benchmark configuration): the MX inference forward of the workload's shape "
                          "under a seeded random mask of 128 x 128 blocks that keeps this fraction (plus every query block's own block)")
+    ap.add_argument("--mfma-sustained", action="store_true",
+                    help="measurement only: the 16-bit MFMA rate and clock the part sustains with nothing else running "
+                         "(context for the roofline fractions, which are quoted against the published 2.5 PFLOP/s)")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     args = ap.parse_args()
@@ -81,6 +84,12 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.mfma_sustained:
+        tf, ghz = aq.attnqat_debug_mfma_burn()
+        print(json.dumps({"metric": "sustained v_mfma_f32_32x32x16_f16 rate, register operands, 2 waves per SIMD (1 MI355X)",
+                          "value": round(tf, 1), "unit": "TFLOP/s", "n_gpus": 1, "clock_ghz": round(ghz, 3),
+                          "published_peak": MFMA_PEAK_TFLOPS, "frac_of_published_peak": round(tf / MFMA_PEAK_TFLOPS, 4)}), flush=True)
+        return
     if args.paged_lq > 0:
         return bench_paged(args, aq, torch, np)
     w = W.by_name(args.workload)

@@ -320,6 +320,16 @@ int attnqat_profile_enable(int on);
 int attnqat_profile_read(int max_entries, float* ms, const char** names);
 
 /*
+ * Measurement kernel, not part of the attention path: the 16-bit MFMA rate this part sustains on its own.  `blocks`
+ * workgroups of 4 waves (2 workgroups per CU: 512 fill a 256-CU part once) each issue iters * 16 MFMAs
+ * (32x32x16, f16: 32768 flop each) per wave on non-trivial register operands.  out (device, blocks * 256 floats) takes
+ * the sums (ignored), clk (device, 2 * blocks uint64) per workgroup the shader clock cycles and the 100 MHz ticks its
+ * first wave spent in the loop: their ratio is the clock held under the load.  The caller times the launch.  Only
+ * enqueues.  blocks <= 65536, iters <= 2^22, else ATTNQAT_EINVAL.
+ */
+int attnqat_debug_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, void* stream);
+
+/*
  * Measurement hook for the dK/dV pass of attnqat_bwd.  That pass skips the work on P^F
  * (quantizing it and dV += P^F^T dO) for every 32-query x 32-key tile whose P^F is all zero,
  * which is exact; how often that happens depends on the data.  While `counts` (device,

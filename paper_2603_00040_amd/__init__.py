@@ -41,6 +41,7 @@ _SIGNATURES = {
     "attnqat_kv_cache_page_bytes": (_sz, [_i, _i]),
     "attnqat_kv_cache_write_mx": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp]),
     "attnqat_fwd_infer_mx_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_debug_mfma_burn": (_i, [_i, _i, _vp, _vp, _vp]),
     "attnqat_fwd_infer_mx_sparse": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
@@ -148,6 +149,26 @@ def attnqat_fwd_infer_mx_sparse(q, k, v, causal: bool, block_mask, workspace=Non
     _check(lib().attnqat_fwd_infer_mx_sparse(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16, _ptr(block_mask),
                                              _ptr(o), _ptr(lse), _ptr(ws), nbytes, _stream()))
     return o, lse
+
+
+def attnqat_debug_mfma_burn(rounds: int = 4, iters: int = 40000):
+    """The 16-bit MFMA rate the part sustains on its own and the clock it holds meanwhile: returns (TFLOP/s, GHz).
+    rounds: how many times the launch fills the chip (2 workgroups of 4 waves per CU)."""
+    ncu = torch.cuda.get_device_properties(0).multi_processor_count
+    blocks = 2 * ncu * rounds
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    clk = torch.zeros(2 * blocks, dtype=torch.int64, device="cuda")
+    _check(lib().attnqat_debug_mfma_burn(blocks, max(1, iters // 8), _ptr(out), _ptr(clk), _stream()))     # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _check(lib().attnqat_debug_mfma_burn(blocks, iters, _ptr(out), _ptr(clk), _stream()))
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    c = clk.cpu().numpy().reshape(blocks, 2).astype("float64")
+    flops = blocks * 4.0 * iters * 16.0 * 32768.0
+    return flops / (ms * 1e-3) / 1e12, float(c[:, 0].sum() / c[:, 1].sum()) * 0.1
 
 
 def kv_cache_page_bytes(Hkv: int, d: int) -> int:

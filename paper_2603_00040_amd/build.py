@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattnqat.so")
-SOURCES = ["prep.hip", "fwd.hip", "bwd.hip", "mx.hip", "api.hip"]
+SOURCES = ["prep.hip", "fwd.hip", "bwd.hip", "mx.hip", "probe.hip", "api.hip"]
 # -packed-fp32-ops off: plain fp32 VALU code only (packed fp32 forms are not trusted here)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

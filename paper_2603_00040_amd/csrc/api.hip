@@ -333,6 +333,12 @@ int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, in
 
 static unsigned long long* g_dkdv_counts = nullptr;
 
+int attnqat_debug_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, void* stream)
+{
+    if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 22) || !out || !clk) return ATTNQAT_EINVAL;
+    return launch_mfma_burn(blocks, iters, out, clk, (hipStream_t)stream) ? ATTNQAT_ELAUNCH : ATTNQAT_OK;
+}
+
 int attnqat_debug_dkdv_tile_counts(unsigned long long* counts)
 {
     g_dkdv_counts = counts;

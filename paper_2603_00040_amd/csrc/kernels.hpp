@@ -79,4 +79,8 @@ int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, in
 int launch_fwd_mx_sparse(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
                          const unsigned char* block_mask, int* list, int* cnt, void* o, float* lse, hipStream_t st);
 
+// Measurement only: `blocks` workgroups of 4 waves each run iters * 16 MFMAs (32x32x16, f16) per wave on register
+// operands; out [blocks * 256] floats, clk [2 * blocks] (shader cycles, 100 MHz ticks of wave 0 of every workgroup).
+int launch_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, hipStream_t st);
+
 }  // namespace aq

@@ -1,0 +1,54 @@
+// Measurement kernel, not part of the attention path: the rate at which this part sustains the 16-bit MFMA
+// (v_mfma_f32_32x32x16_f16) when nothing else runs, and the clock it holds while doing so.  The published peak
+// (2.5 PFLOP/s) is 1024 matrix pipes x 1024 flop per cycle x 2.4 GHz; under a matrix load the part lowers its clock,
+// so the rate that can be reached in practice is lower, and the attention kernels' figures are read against both.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace aq {
+
+typedef _Float16 probe_half8 __attribute__((ext_vector_type(8)));
+typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
+
+// 256 threads, 2 workgroups per CU: two waves per SIMD, each a chain of MFMAs on four accumulators with non-trivial
+// register operands.  clk[2*block] = shader clock cycles, clk[2*block + 1] = 100 MHz ticks, of wave 0's loop.
+__global__ __launch_bounds__(256, 2) void mfma_burn_kernel(float* __restrict__ out, unsigned long long* __restrict__ clk, int iters)
+{
+    probe_half8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (_Float16)(0.001f * (float)((int)threadIdx.x + i));
+        b[i] = (_Float16)(0.002f * (float)((int)threadIdx.x - i));
+    }
+    probe_floatx16 acc[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[k][i] = 0.0f;
+    const unsigned long long t0 = __builtin_readcyclecounter();
+    const unsigned long long r0 = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[k], 0, 0, 0);
+    }
+    const unsigned long long t1 = __builtin_readcyclecounter();
+    const unsigned long long r1 = __builtin_amdgcn_s_memrealtime();
+    float s = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[k][i];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+    if (threadIdx.x == 0) { clk[2 * blockIdx.x] = t1 - t0; clk[2 * blockIdx.x + 1] = r1 - r0; }
+}
+
+int launch_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, hipStream_t st)
+{
+    hipLaunchKernelGGL(mfma_burn_kernel, dim3((unsigned)blocks), dim3(256), 0, st, out, clk, iters);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // namespace aq
