@@ -182,12 +182,30 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         }
         // online softmax (Alg. 2: m_new, alpha, P-tilde, l).  Four interleaved chains each: a single
         // chain of 32 dependent max / add instructions would run at the instruction latency.
-        float mp[4];
+        // The maxima are taken on S: one per group of 16 keys (registers 8g..8g+7 of both halves), the tile's row
+        // maximum from those four.  exp2 of a group's largest score, by the same instructions on the same inputs as
+        // that element's P-tilde, then is the group's largest P-tilde, which the block scale of phi needs below.
+        float mt, gmax[4];
+        if constexpr (PQ == 1) {
+            float mp[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) mp[t] = max_nc(s[0][t], s[1][t]);
+            for (int t = 0; t < 4; ++t) mp[t] = max_nc(s[0][t], s[1][t]);
 #pragma unroll
-        for (int i = 4; i < 16; ++i) mp[i & 3] = max_nc(max_nc(mp[i & 3], s[0][i]), s[1][i]);
-        const float mt = xhalf_max(max_nc(max_nc(mp[0], mp[1]), max_nc(mp[2], mp[3])));
+            for (int i = 4; i < 16; ++i) mp[i & 3] = max_nc(max_nc(mp[i & 3], s[0][i]), s[1][i]);
+            mt = xhalf_max(max_nc(max_nc(mp[0], mp[1]), max_nc(mp[2], mp[3])));
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const floatx16& sv = s[ks >> 1];
+                const int b0 = 8 * (ks & 1);
+                const float a0 = max_nc(max_nc(sv[b0], sv[b0 + 1]), sv[b0 + 2]);
+                const float a1 = max_nc(max_nc(sv[b0 + 3], sv[b0 + 4]), sv[b0 + 5]);
+                gmax[ks] = max_nc(max_nc(a0, a1), max_nc(sv[b0 + 6], sv[b0 + 7]));
+            }
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) gmax[ks] = xhalf_max(gmax[ks]);
+            mt = max_nc(max_nc(gmax[0], gmax[1]), max_nc(gmax[2], gmax[3]));
+        }
         const float mnew = fmaxf(m, mt);
         const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
         const float ms = mnew * c;
@@ -252,15 +270,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         // block scales of phi(P-tilde) for the four 16-key groups of the tile (keys of a group =
         // registers 8g..8g+7 of both halves), as four independent chains
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const floatx16& sv = s[ks >> 1];
-            const int b0 = 8 * (ks & 1);
-            const float a0 = fmaxf(fmaxf(sv[b0], sv[b0 + 1]), sv[b0 + 2]);
-            const float a1 = fmaxf(fmaxf(sv[b0 + 3], sv[b0 + 4]), sv[b0 + 5]);
-            bsc[ks] = fmaxf(fmaxf(a0, a1), fmaxf(sv[b0 + 6], sv[b0 + 7]));
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) bsc[ks] = xhalf_max(bsc[ks]);
+        for (int ks = 0; ks < 4; ++ks) bsc[ks] = __builtin_amdgcn_exp2f(fmaf(gmax[ks], c, -ms));
         // (two-level: the block maxima of P-tilde / s1 are at most 2688 (1 + 2^-23), whose sixth rounds to 448, the largest scale)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) bsc[ks] = rne_e4m3_grid((bsc[ks] * inv1) * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
