@@ -31,6 +31,10 @@
 
 namespace aq {
 
+#ifndef AQ_DECODE_NP
+#define AQ_DECODE_NP 1     // pages per iteration of the decode kernel (4 waves per page)
+#endif
+
 typedef int int8v __attribute__((ext_vector_type(8)));
 
 // 32 values -> 4 registers of E2M1 codes (value i in nibble i), RNE on v / scale, saturating.
@@ -470,6 +474,256 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// Decode form of the paged forward: at most 32 query rows per (sequence, kv head) — one position, or a few, of the G
+// query heads of a group — against a long sequence.  fwd_mx_kernel would leave three of its four waves without rows
+// and walk the pages with one; here the waves of a workgroup share the KEYS: an iteration takes NP pages (a page: two
+// 64-key tiles), and wave w takes the product t = w % 2 of tile T = (w / 2) % 2 of page w / 4 of the iteration, i.e.
+// keys {32 hf + 16 t .. + 15} of that tile (16 of each of its two 32-key blocks), for all 32 rows.  What Alg. 1 makes
+// sequential is only the running maximum, and that needs no more than the waves' partial row maxima of S: they go
+// through LDS once per iteration, after which every wave knows the maximum after each of the 2 NP tiles and the largest
+// score of its two blocks (exp2 of it, by the same instructions as that element's P-tilde, is the block's amax, so both
+// waves of a block derive the same scale).  Each wave then quantizes its 16 keys per row against the maximum after ITS
+// tile, exactly as the tile order of Alg. 1 prescribes, and accumulates its own O and l against its own reference
+// maximum; the partial results are brought to the final maximum and added at the end.
+template <int D, bool CAUSAL, int NP /* pages per iteration: 4 NP waves */>
+__global__ __launch_bounds__(256 * NP, NP == 1 ? 2 : 1) void fwd_mx_decode_kernel(
+    const unsigned char* __restrict__ qops, const uint32_t* __restrict__ qsc, const unsigned char* __restrict__ kv,
+    uint16_t* __restrict__ O, float* __restrict__ lse, int L /* rows, <= 32 */, int Hq, int G, float c /* log2(e)/sqrt(d) */,
+    const int* __restrict__ page_table, const int* __restrict__ kv_lens, int max_pages, int num_pages, int lq_inner)
+{
+    constexpr int KS = D / 64, MT = D / 32, NW = 4 * NP;
+    constexpr int NIT = NP == 1 ? 4 : NP == 2 ? 3 : 2;   // iterations whose pages the LDS ring holds (NIT - 1 of them in flight)
+    constexpr int NR = NIT * NP;                     // ... in pages
+    constexpr int KOPS = 2 * KS * 1024, VOPS = MT * 1024, REC = mx_rec_bytes(D, false), STAGE = 2 * REC, NCH = STAGE / 1024;
+    constexpr int NV = MT * 16 + 1;                  // floats per lane in the final reduction
+    static_assert(STAGE % 1024 == 0 && NR * STAGE >= (NW / 2) * NV * 256, "the ring also holds the final reduction");
+    extern __shared__ __align__(16) unsigned char smem[];          // NR page buffers, then NW x 64 floats of partial maxima
+    float* xchg = reinterpret_cast<float*>(smem + NR * STAGE);
+
+    const int bh = blockIdx.x;
+    const int b = bh / Hq, h = bh % Hq;
+    const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int pi = wave >> 2, T = (wave >> 1) & 1, t = wave & 1;
+    const int q_row = ln;
+    const int Hkv = Hq / G;
+
+    // Q operands of row block 0 (rows 0..31 of this head's only tile; rows >= L are zero)
+    uint4v qop[KS];
+    const size_t grp = (size_t)bh * 4;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qop[ks] = *reinterpret_cast<const uint4v*>(qops + ((grp * KS + ks) * 64 + lane) * 16);
+    uint32_t qs = qsc[grp * 64 + lane];
+
+    const int Lk = __builtin_amdgcn_readfirstlane(kv_lens[b]);
+    const int koff = Lk - lq_inner;
+    const bool packed = lq_inner != L;
+    const int nst = min((Lk + 127) / 128, max_pages);              // pages of this sequence
+    const int nit = (nst + NP - 1) / NP;
+    const int klim = CAUSAL ? min(Lk - 1, koff + (packed ? q_row % lq_inner : q_row)) : Lk - 1;
+
+    // The pages of iteration it: NP * NCH copies of 1 KiB, dealt out to the waves in turn
+    auto issue_iter = [&](int it) __attribute__((always_inline)) {
+#pragma unroll
+        for (int pp = 0; pp < NP; ++pp) {
+            const int st = it * NP + pp;
+            if (st < nst) {
+                int page = __builtin_amdgcn_readfirstlane(page_table[(size_t)b * max_pages + st]);
+                page = min(max(page, 0), num_pages - 1);           // a bad table entry reads a wrong page, never outside the cache
+                const unsigned char* src = kv + ((size_t)page * Hkv + (h / G)) * STAGE;
+                unsigned char* dst = smem + (st % NR) * STAGE;
+                // copy g = pp * NCH + ch of the iteration goes to wave g mod NW
+                for (int ch = (wave + NW - (pp * NCH) % NW) % NW; ch < NCH; ch += NW)
+                    async_copy16(src, (uint32_t)(ch * 1024 + lane * 16), dst + ch * 1024);
+            }
+        }
+    };
+    // Wait until all but the copies of the `newer` most recent iterations have landed (vector-memory operations complete
+    // in order).  Only meaningful while those iterations are whole: a wave issues (NP * NCH) / NW copies per iteration,
+    // the first (NP * NCH) % NW waves one more.  s_waitcnt takes an immediate, hence the branches.
+    constexpr int CLO = (NP * NCH) / NW, NHI = (NP * NCH) % NW;
+    static_assert(NIT <= 4 && 2 * (CLO + 1) < 16, "at most two newer iterations in flight at a wait; the immediate below has 4 bits");
+    auto wait_all_but = [&](int newer) __attribute__((always_inline)) {
+#define AQ_VM(N) __builtin_amdgcn_s_waitcnt((N) | 0x70)
+        if (newer >= 2)      { if (wave < NHI) AQ_VM(2 * (CLO + 1)); else AQ_VM(2 * CLO); }
+        else if (newer == 1) { if (wave < NHI) AQ_VM(CLO + 1); else AQ_VM(CLO); }
+        else                 __builtin_amdgcn_s_waitcnt(0);
+#undef AQ_VM
+    };
+    auto as8 = [](const uint4v& x) __attribute__((always_inline)) -> int8v {
+        int8v r = {(int)x[0], (int)x[1], (int)x[2], (int)x[3], 0, 0, 0, 0};
+        return r;
+    };
+
+    floatx16 o[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[mt][i] = 0.0f;
+    float m_run = -INFINITY;         // maximum after the last iteration (the same in every wave)
+    float mref = -INFINITY;          // maximum this wave's O and l refer to (after its tile of its last iteration)
+    float lsum = 0.0f;
+
+    // Q must have arrived before the copies start: the wait for an ordinary load issued after them would wait for them too
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qop[ks]));
+    asm volatile("" : "+v"(qs));
+    __builtin_amdgcn_s_waitcnt(0);
+#pragma unroll
+    for (int i = 0; i < NIT - 1; ++i)
+        if (i < nit) issue_iter(i);
+
+    for (int it = 0; it < nit; ++it) {
+        // iteration it's pages are in LDS (the newer ones may be in flight if they are whole), everyone is past iteration it - 1
+        const int issued = min(nit, it + NIT - 1);                            // iterations issued so far
+        wait_all_but(issued * NP <= nst ? issued - 1 - it : 0);
+        __builtin_amdgcn_s_barrier();
+        if (it + NIT - 1 < nit) issue_iter(it + NIT - 1);                     // into the buffers of iteration it - 1
+        const int st = it * NP + pi;                                          // this wave's page
+        const bool valid = st < nst;                                          // (the last iteration may be short of pages)
+        const unsigned char* rec = smem + (st % NR) * STAGE + T * REC;
+        const int k0 = st * 128 + T * 64;
+        // S^T of this wave's 32 keys
+        floatx16 sv;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sv[i] = -INFINITY;
+        if (valid) {
+            const uint32_t ksc = lds_read4(rec + KOPS + VOPS + lane * 4);
+            uint4v a[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) a[ks] = lds_read16(rec + ((t * KS + ks) * 64 + lane) * 16);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sv[i] = 0.0f;
+            if (t == 0) {
+                sv = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0]), as8(qop[0]), sv, 4, 4, 0, ksc, 0, qs);
+                if constexpr (KS == 2) sv = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1]), as8(qop[1]), sv, 4, 4, 1, ksc, 1, qs);
+            } else {
+                sv = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0]), as8(qop[0]), sv, 4, 4, KS, ksc, 0, qs);
+                if constexpr (KS == 2) sv = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1]), as8(qop[1]), sv, 4, 4, 3, ksc, 1, qs);
+            }
+            const bool need_mask = (k0 + 64 > Lk) || (CAUSAL && k0 + 63 > koff);
+            if (need_mask) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (k0 + 32 * hf + 16 * t + i > klim) sv[i] = -INFINITY;
+            }
+        }
+        float pm[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pm[i] = max_nc(max_nc(sv[i], sv[4 + i]), max_nc(sv[8 + i], sv[12 + i]));
+        xchg[wave * 64 + lane] = max_nc(max_nc(pm[0], pm[1]), max_nc(pm[2], pm[3]));
+        // (fences, not __syncthreads(): the copies in flight are not to be waited for here)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        // maxima after each of the iteration's 2 NP tiles (tile tau: waves 2 tau and 2 tau + 1, both half-waves)
+        float mT = m_run, bm = -INFINITY, mt_run = m_run;
+#pragma unroll
+        for (int tau = 0; tau < 2 * NP; ++tau) {
+            const float x0 = xchg[(2 * tau) * 64 + lane], x1 = xchg[(2 * tau + 1) * 64 + lane];
+            const float y0 = xchg[(2 * tau) * 64 + (lane ^ 32)], y1 = xchg[(2 * tau + 1) * 64 + (lane ^ 32)];
+            mt_run = fmaxf(mt_run, max_nc(max_nc(x0, x1), max_nc(y0, y1)));
+            if (tau == 2 * pi + T) { mT = mt_run; bm = max_nc(x0, x1); }     // wave-uniform: this wave's tile, this lane's block
+        }
+        m_run = mt_run;
+        if (valid) {
+            const float alpha = __builtin_amdgcn_exp2f((mref - mT) * c);
+            const float ms = mT * c;
+            mref = mT;
+            float p[16];
+            float rp[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], c, -ms));
+                rp[i & 3] += p[i];
+            }
+            lsum = lsum * alpha + ((rp[0] + rp[1]) + (rp[2] + rp[3]));        // un-quantized P-tilde
+            const float amax = __builtin_amdgcn_exp2f(fmaf(bm, c, -ms));
+            const uint32_t pbyte = e8m0_of_amax(amax);
+            const float psc = e8m0_as_f32(pbyte);
+            uint32_t c0 = 0u, c1 = 0u;
+            c0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c0, p[0], p[1], psc, 0);
+            c0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c0, p[2], p[3], psc, 1);
+            c0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c0, p[4], p[5], psc, 2);
+            c0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c0, p[6], p[7], psc, 3);
+            c1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c1, p[8], p[9], psc, 0);
+            c1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c1, p[10], p[11], psc, 1);
+            c1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c1, p[12], p[13], psc, 2);
+            c1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c1, p[14], p[15], psc, 3);
+            // B operand of O^T += V^F^T P^T: this lane's k-slots are keys 32 hf + 0..31 of the tile, 8 to a register;
+            // the wave fills the 16 it has and leaves the other wave's at zero
+            const int8v pb = t ? int8v{0, 0, (int)c0, (int)c1, 0, 0, 0, 0} : int8v{(int)c0, (int)c1, 0, 0, 0, 0, 0, 0};
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[mt][i] *= alpha;
+            }
+            const uint32_t vsc = lds_read4(rec + KOPS + VOPS + 256 + lane * 4);
+            uint4v va[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) va[mt] = lds_read16(rec + KOPS + (mt * 64 + lane) * 16);
+            o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[0]), pb, o[0], 4, 4, 0, vsc, 0, pbyte);
+            o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[1]), pb, o[1], 4, 4, 1, vsc, 0, pbyte);
+            if constexpr (MT == 4) {
+                o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[2]), pb, o[2], 4, 4, 2, vsc, 0, pbyte);
+                o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(va[3]), pb, o[3], 4, 4, 3, vsc, 0, pbyte);
+            }
+        }
+        // (the partial maxima are read before the next iteration's barrier, which precedes the next writes)
+    }
+
+    // ---- the partial results, brought to the final maximum and added (a tree over the waves); O /= l, L = m + log l
+    const float f = (mref == m_run) ? 1.0f : __builtin_amdgcn_exp2f((mref - m_run) * c);      // (also covers -inf - -inf)
+    float l = xhalf_sum(lsum) * f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[mt][i] *= f;
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                                                          // everyone is done with the page buffers
+    float* red = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int step = NW / 2; step >= 1; step >>= 1) {
+        if (wave >= step && wave < 2 * step) {
+            float* dst = red + (size_t)(wave - step) * NV * 64;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64 + lane] = o[mt][i];
+            dst[(MT * 16) * 64 + lane] = l;
+        }
+        __syncthreads();
+        if (wave < step) {
+            const float* src = red + (size_t)wave * NV * 64;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[mt][i] += src[(mt * 16 + i) * 64 + lane];
+            l += src[(MT * 16) * 64 + lane];
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        const float inv_l = l > 0.0f ? 1.0f / l : 0.0f;                       // a sequence without keys: O = 0, L = -inf
+        if (q_row < L) {
+            const size_t row = (size_t)bh * L + q_row;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    const int d0 = 32 * mt + 8 * tt + 4 * hf;
+                    uint2v w;
+                    w[0] = pack_bf16x2_rne(o[mt][4 * tt] * inv_l, o[mt][4 * tt + 1] * inv_l);
+                    w[1] = pack_bf16x2_rne(o[mt][4 * tt + 2] * inv_l, o[mt][4 * tt + 3] * inv_l);
+                    *reinterpret_cast<uint2v*>(O + row * D + d0) = w;
+                }
+            if (hf == 0) lse[row] = m_run * (c * 0.6931471805599453f) + logf(l);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 template <int D>
 static int quant_d(const void* x, int BH, int L, int mode, bool fp8v, unsigned char* codes, unsigned char* scales, void* xf,
                    const int* page_ids, hipStream_t st)
@@ -547,6 +801,22 @@ int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, in
                         const int* page_table, const int* kv_lens, int max_pages, int num_pages, int lq_inner,
                         void* o, float* lse, hipStream_t st)
 {
+    if (Lq <= 32) {
+        // a step of decoding: the four waves of a workgroup share the keys of a page
+        const float c = 1.4426950408889634f / sqrtf((float)D);
+#define AQ_DECODE(DD, CC) do { \
+        constexpr int NP = AQ_DECODE_NP; \
+        constexpr size_t smem = (NP == 1 ? 4 : NP == 2 ? 3 : 2) * NP * 2 * (size_t)mx_rec_bytes(DD, false) + 4 * NP * 256; \
+        auto kern = fwd_mx_decode_kernel<DD, CC, NP>; \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) return -1; \
+        hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq)), dim3(256 * NP), smem, st, (const unsigned char*)qops, (const uint32_t*)qsc, \
+                           (const unsigned char*)cache, (uint16_t*)o, lse, Lq, Hq, Hq / Hkv, c, page_table, kv_lens, max_pages, num_pages, lq_inner); \
+        return hipGetLastError() == hipSuccess ? 0 : -1; } while (0)
+        if (D == 128) { if (causal) AQ_DECODE(128, true); else AQ_DECODE(128, false); }
+        if (D == 64)  { if (causal) AQ_DECODE(64, true); else AQ_DECODE(64, false); }
+#undef AQ_DECODE
+        return -1;
+    }
 #define AQ_PAGED(DD, CC) launch_fwd_mx_t<DD, CC, false, 1>(qops, qsc, cache, B, Hq, Hkv, Lq, o, lse, page_table, kv_lens, max_pages, num_pages, lq_inner, st)
     if (D == 128) return causal ? AQ_PAGED(128, true) : AQ_PAGED(128, false);
     if (D == 64)  return causal ? AQ_PAGED(64, true) : AQ_PAGED(64, false);

@@ -58,3 +58,5 @@ def test_mx_forward_kernels_do_not_spill():
     k = _resources("mx.hip")
     # fwd_mx_kernel<D, CAUSAL, FP8PV, KVM>: 8 contiguous variants, the 4 paged and the 4 block-sparse ones (FP4 only)
     _check(k, r"fwd_mx_kernelILi(64|128)ELb[01]ELb[01]ELi[012]E", 16)
+    # fwd_mx_decode_kernel<D, CAUSAL, NP = 1>: two workgroups per CU
+    _check(k, r"fwd_mx_decode_kernelILi(64|128)ELb[01]ELi1E", 4)

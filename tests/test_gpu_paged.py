@@ -64,6 +64,16 @@ def test_paged_decode_step(causal):
 
 
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+def test_paged_decode_kernel_shapes(d, causal):
+    # at most 32 rows per (sequence, kv head): the kernel whose waves share the keys of a page.  Lengths around the tile
+    # and page edges, one long enough for the copy ring to wrap several times; 7 positions without grouping (each row
+    # has its own causal limit), and 8 heads x 4 positions = exactly 32 packed rows
+    _run(2, 2, d, [64, 65, 128, 129, 2500], 7, causal, seed=40 + d, k_chan=4)
+    _run(16, 2, d, [4, 257, 1111], 4, causal, seed=41 + d)
+
+
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("Lq", [1, 5, 16, 100])
 def test_paged_grouped_query_heads_share_a_tile(Lq, causal):
     # G = 8 query heads per kv head: G * Lq <= 128 packs them into one tile (Lq = 1, 5, 16), Lq = 100 does not
