@@ -328,13 +328,10 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) a[t][ks] = lds_read16(rec + ((t * KS + ks) * 64 + lane) * 16);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[t][i] = 0.0f;
-        }
-        s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][0]), as8(qop[0]), s[0], 4, 4, 0, ksc, 0, qs);
-        s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][0]), as8(qop[0]), s[1], 4, 4, KS, ksc, 0, qs);
+        // (a constant zero accumulator is encoded in the instruction: no registers to clear)
+        const floatx16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][0]), as8(qop[0]), zero, 4, 4, 0, ksc, 0, qs);
+        s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][0]), as8(qop[0]), zero, 4, 4, KS, ksc, 0, qs);
         if constexpr (KS == 2) {
             s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][1]), as8(qop[1]), s[0], 4, 4, 1, ksc, 1, qs);
             s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][1]), as8(qop[1]), s[1], 4, 4, 3, ksc, 1, qs);
