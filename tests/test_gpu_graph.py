@@ -63,3 +63,37 @@ def test_graph_replay_of_training_step_and_mx_forward(causal):
             assert torch.equal(t, w), (rep, seed)
         assert not torch.isnan(lse).any()
     print(f"graph replays bit-identical to eager, causal={int(causal)}", flush=True)
+
+
+def test_two_streams_with_their_own_workspaces_do_not_interfere():
+    """The entry points keep no state between calls besides the caller's workspace: a training step on each of two
+    streams at once, different inputs, each with its own workspace, gives what each gives alone."""
+    import paper_2603_00040_amd as aq
+    B, Hq, Hkv, L, d = 1, 8, 4, 700, 128
+    sets = []
+    for seed in (11, 12):
+        x = random_inputs(B, Hq, Hkv, L, d, seed, k_chan=4)
+        t = {n: to_dev(x[n]) for n in ("q", "k", "v", "do")}
+        bufs = _bufs(aq, B, Hq, Hkv, L, d)
+        sets.append((t, bufs))
+
+    def step(t, bufs):
+        _, _, _, _, o, lse, ohp, dq, dk, dv, ws = bufs
+        aq.attnqat_fwd(t["q"], t["k"], t["v"], True, workspace=ws, out=(o, lse, ohp))
+        aq.attnqat_bwd(t["q"], t["k"], t["v"], t["do"], lse, ohp, True, workspace=ws, out=(dq, dk, dv))
+        return o, lse, ohp, dq, dk, dv
+
+    alone = []
+    for t, bufs in sets:
+        alone.append([r.clone() for r in step(t, bufs)])
+        torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for _ in range(3):
+        outs = []
+        for (t, bufs), st in zip(sets, streams):
+            with torch.cuda.stream(st):
+                outs.append(step(t, bufs))
+        torch.cuda.synchronize()
+        for got, want in zip(outs, alone):
+            for g_, w_ in zip(got, want):
+                assert torch.equal(g_, w_)
