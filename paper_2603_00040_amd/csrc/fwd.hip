@@ -210,13 +210,14 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
         const float ms = mnew * c;
         m = mnew;
-        float rp[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        float rp[4];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, -ms));
-                rp[i & 3] += s[kb][i];
+                if (kb == 0 && i < 4) rp[i] = s[kb][i];
+                else                  rp[i & 3] += s[kb][i];
             }
         lsum = lsum * alpha + ((rp[0] + rp[1]) + (rp[2] + rp[3]));          // un-quantized P-tilde
         // rescale: exact no-op unless some row of this wave moved its maximum (rare after the
@@ -272,10 +273,27 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) bsc[ks] = __builtin_amdgcn_exp2f(fmaf(gmax[ks], c, -ms));
         // (two-level: the block maxima of P-tilde / s1 are at most 2688 (1 + 2^-23), whose sixth rounds to 448, the largest scale)
+        if constexpr (PQ == 0) {
+            // RNE_E4M3(amax / 6) by the hardware conversion (OCP E4M3, round to nearest even, subnormals kept; two values
+            // per instruction) and back: the same values as rne_e4m3_grid in a quarter of the instructions.
+            // P-tilde <= 1: no saturation
+            typedef short short2v __attribute__((ext_vector_type(2)));
+            short2v pk = {0, 0};
+            pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, bsc[0] * (1.0f / 6.0f), bsc[1] * (1.0f / 6.0f), 1.0f, false);
+            pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, bsc[2] * (1.0f / 6.0f), bsc[3] * (1.0f / 6.0f), 1.0f, true);
+            const uint32_t w = __builtin_bit_cast(uint32_t, pk);
+            bsc[0] = __builtin_amdgcn_cvt_scalef32_f32_fp8(w, 1.0f, 0);
+            bsc[1] = __builtin_amdgcn_cvt_scalef32_f32_fp8(w, 1.0f, 1);
+            bsc[2] = __builtin_amdgcn_cvt_scalef32_f32_fp8(w, 1.0f, 2);
+            bsc[3] = __builtin_amdgcn_cvt_scalef32_f32_fp8(w, 1.0f, 3);
+        } else {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) bsc[ks] = rne_e4m3_grid((bsc[ks] * inv1) * (1.0f / 6.0f));   // P-tilde <= 1: no saturation
+            for (int ks = 0; ks < 4; ++ks) bsc[ks] = rne_e4m3_grid((bsc[ks] * inv1) * (1.0f / 6.0f));
+        }
+        // reciprocals.  A scale of 0: P^F is 0 whatever the codes are (the dequantization multiplies by the scale), so
+        // any finite factor serves; 512 = 1 / (smallest non-zero scale) keeps the quotients finite.
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) binv[ks] = bsc[ks] > 0.0f ? __builtin_amdgcn_rcpf(bsc[ks]) * inv1 : 0.0f;
+        for (int ks = 0; ks < 4; ++ks) binv[ks] = fminf(__builtin_amdgcn_rcpf(bsc[ks]), 512.0f) * inv1;
     };
     // ---- matrix phase of one key tile: O, O' += V^F^T P with the FP4 round trip of P-tilde in between
     auto matrix_phase = [&](int j, const float (&bsc)[4], const float (&binv)[4]) __attribute__((always_inline)) {
