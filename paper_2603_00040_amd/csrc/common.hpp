@@ -90,22 +90,30 @@ __device__ inline uint32_t e8m0_of_amax_fp8(float amax) {
 __device__ inline float e8m0_as_f32(uint32_t byte) { return __uint_as_float(byte << 23); }            // 1 <= byte <= 254
 __device__ inline float e8m0_inverse_as_f32(uint32_t byte) { return __uint_as_float((254u - byte) << 23); }   // 1 <= byte <= 253
 
+// max(a, b) written as median(a, b, +inf): fmaxf() on values the compiler cannot prove quiet (MFMA
+// results) costs a canonicalizing v_max per operand, the median has no such requirement and the
+// compiler folds chains of it into v_max3.  No NaN reaches these reductions.
+__device__ inline float max_nc(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_inff()); }
+// A lone two-input maximum still gets its operands canonicalized (v_max x, x, x twice) when they come out of an MFMA or a
+// cross-lane move; this one is the bare instruction.  Same precondition: no NaN.
+__device__ inline float max_raw(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // ---- cross-lane: combine the two 32-lane halves of a wave -------------------
 // v_permlane32_swap(a, b) exchanges a[32..63] with b[0..31]: called with (x, x) it returns
 // {x.lo, x.lo} and {x.hi, x.hi}, so one swap plus one ALU op reduces over the halves.
 __device__ inline float xhalf_max(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return max_raw(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ inline float xhalf_sum(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// max(a, b) written as median(a, b, +inf): fmaxf() on values the compiler cannot prove quiet (MFMA
-// results) costs a canonicalizing v_max per operand, the median has no such requirement and the
-// compiler folds chains of it into v_max3.  No NaN reaches these reductions.
-__device__ inline float max_nc(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_inff()); }
 
 // ---- phi^-1(phi(.)) of two P values with the hardware FP4 converts ------------
 // v_cvt_scalef32_pk_fp4_f32 rounds to E2M1 with ties-to-even and saturates at 6 (checked
@@ -170,6 +178,14 @@ __device__ inline uint2v lds_read_tr16b(const unsigned char* p) { return lds_rea
 // Plain 16-byte LDS read at a byte address.
 __device__ inline uint4v lds_read16(const unsigned char* p) {
     return *(const __attribute__((address_space(3))) uint4v*)p;
+}
+// The same at an LDS byte address held as an integer (tiles are 256-byte aligned, so an XOR of address bits 5..7 commutes
+// with adding the tile's base), and the integer address of an LDS object.
+__device__ inline uint4v lds_read16_at(uint32_t addr) {
+    return *(const __attribute__((address_space(3))) uint4v*)(uintptr_t)addr;
+}
+__device__ inline uint32_t lds_addr_of(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 __device__ inline uint32_t lds_read4(const unsigned char* p) {
     return *(const __attribute__((address_space(3))) uint32_t*)p;

@@ -116,10 +116,10 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     auto scores = [&](int buf) __attribute__((always_inline)) {
         // per-lane offset of this tile, opaque to the compiler: it would otherwise hoist every
         // (offset ^ constant) out of the loop and pay for it with registers
-        int k_it = k_rd + buf * (int)sizeof(sm.k[0]);
+        int k_it = k_rd + buf * (int)sizeof(sm.k[0]) + (int)lds_addr_of(kbase);
         asm volatile("" : "+v"(k_it));
         auto k_opnd = [&](int i) __attribute__((always_inline)) -> half8 {
-            return __builtin_bit_cast(half8, lds_read16(kbase + (k_it ^ ((i >> 1) << 5)) + (i & 1) * (32 * D * 2)));
+            return __builtin_bit_cast(half8, lds_read16_at((uint32_t)((k_it ^ ((i >> 1) << 5)) + (i & 1) * (32 * D * 2))));
         };
         constexpr int NS = 2 * DS, RING = 6;
         half8 ring[RING];
@@ -200,13 +200,13 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
                 const int b0 = 8 * (ks & 1);
                 const float a0 = max_nc(max_nc(sv[b0], sv[b0 + 1]), sv[b0 + 2]);
                 const float a1 = max_nc(max_nc(sv[b0 + 3], sv[b0 + 4]), sv[b0 + 5]);
-                gmax[ks] = max_nc(max_nc(a0, a1), max_nc(sv[b0 + 6], sv[b0 + 7]));
+                gmax[ks] = max_nc(max_nc(a0, a1), max_raw(sv[b0 + 6], sv[b0 + 7]));
             }
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) gmax[ks] = xhalf_max(gmax[ks]);
             mt = max_nc(max_nc(gmax[0], gmax[1]), max_nc(gmax[2], gmax[3]));
         }
-        const float mnew = fmaxf(m, mt);
+        const float mnew = max_nc(m, mt);
         const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
         const float ms = mnew * c;
         m = mnew;
@@ -300,7 +300,8 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         const int k0 = j * 64;
         (void)k0;
         // per 16 keys: phi^-1(phi(P-tilde)), then O^T += V^F^T P-tilde^F^T and O'^T += V^F^T P-tilde^T
-        int v_it = v_rd + (j & 1) * (int)sizeof(sm.v[0]);
+        // (an LDS address as an integer: pointer arithmetic on the dynamic LDS symbol costs an add per read)
+        int v_it = v_rd + (j & 1) * (int)sizeof(sm.v[0]) + (int)lds_addr_of(vbase);
         asm volatile("" : "+v"(v_it));
         struct QState { uint32_t c01, c23; };
         float pfv[DUMP ? 8 : 1];
@@ -310,8 +311,10 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
             const floatx16& sv = s[ks >> 1];
             const float inv = binv[ks];
             if (part == 0) {
-                st.c01 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, sv[b0] * inv, sv[b0 + 1] * inv, 1.0f, 0);
-                st.c23 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, sv[b0 + 4] * inv, sv[b0 + 5] * inv, 1.0f, 0);
+                // (the conversion replaces one byte of its first operand; bytes 2 and 3 of the code registers are never
+                //  read, so any register that is live anyway serves and none has to be cleared)
+                st.c01 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(__float_as_uint(inv), sv[b0] * inv, sv[b0 + 1] * inv, 1.0f, 0);
+                st.c23 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(__float_as_uint(inv), sv[b0 + 4] * inv, sv[b0 + 5] * inv, 1.0f, 0);
             } else if (part == 1) {
                 st.c01 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(st.c01, sv[b0 + 2] * inv, sv[b0 + 3] * inv, 1.0f, 1);
                 st.c23 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(st.c23, sv[b0 + 6] * inv, sv[b0 + 7] * inv, 1.0f, 1);
@@ -352,7 +355,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         QState st;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-            av[mb] = __builtin_bit_cast(half8, lds_read16(vbase + v_it + mb * (32 * 64 * 2)));
+            av[mb] = __builtin_bit_cast(half8, lds_read16_at((uint32_t)(v_it + mb * (32 * 64 * 2))));
 #pragma unroll
         for (int part = 0; part < 4; ++part) q_part(0, part, st, bq[0], bu[0]);
 #pragma unroll
@@ -371,7 +374,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
                 if (ks < 3) {
 #pragma unroll
                     for (int part = (4 * mb) / MB; part < (4 * (mb + 1)) / MB; ++part) q_part(ks + 1, part, st, bq[nxt], bu[nxt]);
-                    av[mb] = __builtin_bit_cast(half8, lds_read16(vbase + (v_it ^ ((ks + 1) << 5)) + mb * (32 * 64 * 2)));
+                    av[mb] = __builtin_bit_cast(half8, lds_read16_at((uint32_t)((v_it ^ ((ks + 1) << 5)) + mb * (32 * 64 * 2))));
                 }
             }
         }

@@ -355,7 +355,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
 #pragma unroll
         for (int i = 4; i < 16; ++i) mp[i & 3] = max_nc(max_nc(mp[i & 3], s[0][i]), s[1][i]);
         const float mown = max_nc(max_nc(mp[0], mp[1]), max_nc(mp[2], mp[3]));      // maximum of this lane's block
-        const float mnew = fmaxf(m, xhalf_max(mown));
+        const float mnew = max_nc(m, xhalf_max(mown));
         // (block-sparse: the first blocks a row meets may lie entirely in its causal future; until it has seen a key
         //  its maximum is -inf, and a finite stand-in keeps the two expressions below free of inf - inf)
         const float mref = (SPARSE && mnew == -INFINITY) ? 0.0f : mnew;
@@ -619,7 +619,7 @@ __global__ __launch_bounds__(256 * NP, NP == 1 ? 2 : 1) void fwd_mx_decode_kerne
         for (int tau = 0; tau < 2 * NP; ++tau) {
             const float x0 = xchg[(2 * tau) * 64 + lane], x1 = xchg[(2 * tau + 1) * 64 + lane];
             const float y0 = xchg[(2 * tau) * 64 + (lane ^ 32)], y1 = xchg[(2 * tau + 1) * 64 + (lane ^ 32)];
-            mt_run = fmaxf(mt_run, max_nc(max_nc(x0, x1), max_nc(y0, y1)));
+            mt_run = max_nc(mt_run, max_nc(max_nc(x0, x1), max_nc(y0, y1)));
             if (tau == 2 * pi + T) { mT = mt_run; bm = max_nc(x0, x1); }     // wave-uniform: this wave's tile, this lane's block
         }
         m_run = mt_run;
