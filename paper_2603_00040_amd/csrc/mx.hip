@@ -351,7 +351,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mx_kernel(
         }
         float mp[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) mp[t] = max_nc(s[0][t], s[1][t]);
+        for (int t = 0; t < 4; ++t) mp[t] = max_raw(s[0][t], s[1][t]);
 #pragma unroll
         for (int i = 4; i < 16; ++i) mp[i & 3] = max_nc(max_nc(mp[i & 3], s[0][i]), s[1][i]);
         const float mown = max_nc(max_nc(mp[0], mp[1]), max_nc(mp[2], mp[3]));      // maximum of this lane's block
@@ -607,7 +607,7 @@ __global__ __launch_bounds__(256 * NP, NP == 1 ? 2 : 1) void fwd_mx_decode_kerne
         }
         float pm[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pm[i] = max_nc(max_nc(sv[i], sv[4 + i]), max_nc(sv[8 + i], sv[12 + i]));
+        for (int i = 0; i < 4; ++i) pm[i] = max_nc(max_nc(sv[i], sv[4 + i]), max_raw(sv[8 + i], sv[12 + i]));
         xchg[wave * 64 + lane] = max_nc(max_nc(pm[0], pm[1]), max_nc(pm[2], pm[3]));
         // (fences, not __syncthreads(): the copies in flight are not to be waited for here)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
