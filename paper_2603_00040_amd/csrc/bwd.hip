@@ -433,7 +433,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
     constexpr int NWL = (32 * KCH) / 64;             // 1 KiB wave-loads per tile of 32 rows
     constexpr int PER_WAVE = NWL >= 4 ? NWL / 4 : 1;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
+    extern __shared__ __align__(256) unsigned char smem_raw[];   // XORs of address bits 5..7 below commute with adding this base
     DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
 
     const int nkt = Lp / 128;
@@ -517,10 +517,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     int g_rd[2];
 #pragma unroll
     for (int v = 0; v < 2; ++v) g_rd[v] = 2 * swz_elem<KCH>(8 * hf + (tr_r >> 2) + 4 * v, 16 * tr_grp + 4 * (tr_r & 3));
-    const int tw_off = ln * kTPad + 4 * hf;                                    // staging tile: this lane's writes
-    const int ta_off = (8 * hf + (tr_r >> 2)) * kTPad + 16 * tr_grp + 4 * (tr_r & 3);   // ... and transpose reads
-    uint16_t* tp = &sm.t[wave][0][0];
-    uint16_t* th = &sm.t[wave][1][0];
+    // staging tiles of this wave, as LDS byte addresses (integers: pointer arithmetic on the dynamic LDS symbol costs an
+    // add per access): this lane's writes and its transpose reads; the dS tile lies kTB bytes after the P^F tile
+    constexpr int kTB = 32 * kTPad * 2;
+    const uint32_t t_base = lds_addr_of(&sm.t[wave][0][0]);
+    const uint32_t tw_ad = t_base + 2u * (uint32_t)(ln * kTPad + 4 * hf);
+    const uint32_t ta_ad = t_base + 2u * (uint32_t)((8 * hf + (tr_r >> 2)) * kTPad + 16 * tr_grp + 4 * (tr_r & 3));
+    const int lds0 = (int)lds_addr_of(smem_raw);
 
     // {L_i log2(e), D_i / sqrt(d)} of this lane's query row of the next tile
     float2 st_n = make_float2(0.0f, 0.0f);
@@ -550,14 +553,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             // Q^F tile of this iteration (dO is kGB further).  The per-lane offsets are made opaque once
             // per iteration: otherwise the compiler hoists every (offset ^ constant) out of the loop and
             // pays for it with a dozen registers that this kernel does not have.
-            const unsigned char* tile = smem_raw;
-            int a_it = a_rd + buf * kBufB, g_it0 = g_rd[0] + buf * kBufB, g_it1 = g_rd[1] + buf * kBufB;
+            int a_it = a_rd + buf * kBufB + lds0, g_it0 = g_rd[0] + buf * kBufB + lds0, g_it1 = g_rd[1] + buf * kBufB + lds0;
             asm volatile("" : "+v"(a_it), "+v"(g_it0), "+v"(g_it1));
             floatx16 s, dp;
             {   // S^T = K^F Q^F^T, dP^T = V^F dO^T: 2*DS steps, step i: ds = i/2, Q or dO = i%2
                 constexpr int NST = 2 * DS, RING = 3;
                 auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
-                    return lds_read16(tile + (a_it ^ ((i >> 1) << 5)) + (i & 1) * kGB);
+                    return lds_read16_at((uint32_t)((a_it ^ ((i >> 1) << 5)) + (i & 1) * kGB));
                 };
                 uint4v ring[RING];
 #pragma unroll
@@ -659,7 +661,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 uint2v wh;
                 wh[0] = pack_f16x2(dsv[0], dsv[1]); wh[1] = pack_f16x2(dsv[2], dsv[3]);
                 // registers r0..r0+3 <-> keys 8*(r0>>2) + 4*hf + 0..3 of this wave's 32 keys
-                *reinterpret_cast<uint2v*>(th + tw_off + 8 * (r0 >> 2)) = wh;
+                lds_write8_at(tw_ad + (uint32_t)(kTB + 16 * (r0 >> 2)), wh);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -670,22 +672,22 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             constexpr int NSTEP = 2 * NB;
             auto rd_b = [&](int j, int extra) __attribute__((always_inline)) -> uint4v {
                 const int nb = j % NB, ks = j / NB;
-                return join(lds_read_tr16b(tile + (g_it0 ^ (nb << 6)) + ks * (16 * kRowB) + extra),
-                            lds_read_tr16b(tile + (g_it1 ^ (nb << 6)) + ks * (16 * kRowB) + extra));
+                return join(lds_read_tr16_at((uint32_t)((g_it0 ^ (nb << 6)) + ks * (16 * kRowB) + extra)),
+                            lds_read_tr16_at((uint32_t)((g_it1 ^ (nb << 6)) + ks * (16 * kRowB) + extra)));
             };
-            auto rd_t = [&](const uint16_t* t, int ks) __attribute__((always_inline)) -> uint4v {
-                const int ta = ta_off + ks * (16 * kTPad);
-                return join(lds_read_tr16(t + ta), lds_read_tr16(t + ta + 4 * kTPad));
+            auto rd_t = [&](int tb /* 0: P^F tile, kTB: dS tile */, int ks) __attribute__((always_inline)) -> uint4v {
+                const uint32_t ta = ta_ad + (uint32_t)(tb + ks * (16 * kTPad * 2));
+                return join(lds_read_tr16_at(ta), lds_read_tr16_at(ta + 4 * kTPad * 2));
             };
             {
-                uint4v ah = rd_t(th, 0), bq[2];
+                uint4v ah = rd_t(kTB, 0), bq[2];
                 bq[0] = rd_b(0, 0);
 #pragma unroll
                 for (int j = 0; j < NSTEP; ++j) {
                     const int nb = j % NB;
                     if (j + 1 < NSTEP) bq[(j + 1) & 1] = rd_b(j + 1, 0);
                     uint4v ah_n;
-                    if (j == NB - 1) ah_n = rd_t(th, 1);
+                    if (j == NB - 1) ah_n = rd_t(kTB, 1);
                     dk[nb] = mfma_f16(ah, bq[j & 1], dk[nb]);
                     if (j == NB - 1) ah = ah_n;
                 }
@@ -724,19 +726,19 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                         }
                         uint2v wp;
                         wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
-                        *reinterpret_cast<uint2v*>(tp + tw_off + 8 * (r0 >> 2)) = wp;
+                        lds_write8_at(tw_ad + (uint32_t)(16 * (r0 >> 2)), wp);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    uint4v ap = rd_t(tp, 0), bg[2];
+                    uint4v ap = rd_t(0, 0), bg[2];
                     bg[0] = rd_b(0, kGB);
 #pragma unroll
                     for (int j = 0; j < NSTEP; ++j) {
                         const int nb = j % NB;
                         if (j + 1 < NSTEP) bg[(j + 1) & 1] = rd_b(j + 1, kGB);
                         uint4v ap_n;
-                        if (j == NB - 1) ap_n = rd_t(tp, 1);
+                        if (j == NB - 1) ap_n = rd_t(0, 1);
                         dv[nb] = mfma_bf16(ap, bg[j & 1], dv[nb]);
                         if (j == NB - 1) ap = ap_n;
                     }

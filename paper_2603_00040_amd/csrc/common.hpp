@@ -184,6 +184,13 @@ __device__ inline uint4v lds_read16(const unsigned char* p) {
 __device__ inline uint4v lds_read16_at(uint32_t addr) {
     return *(const __attribute__((address_space(3))) uint4v*)(uintptr_t)addr;
 }
+__device__ inline uint2v lds_read_tr16_at(uint32_t addr) {
+    const short4v r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(uintptr_t)addr);
+    return __builtin_bit_cast(uint2v, r);
+}
+__device__ inline void lds_write8_at(uint32_t addr, uint2v v) {
+    *(__attribute__((address_space(3))) uint2v*)(uintptr_t)addr = v;
+}
 __device__ inline uint32_t lds_addr_of(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
