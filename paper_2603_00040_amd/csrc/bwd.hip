@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     int L, int Lp, int Hq, int G, int NHq, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */)
 {
     constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, KLD = KCH / 4;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
+    extern __shared__ __align__(256) unsigned char smem_raw[];
     DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
 
     const int nqt = Lp / 128;
@@ -268,14 +268,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     //   toff[mb][v] transpose reads of K^T: lane r of a group of 16 points at key 4*hf + r/4 + 8*v,
     //               columns 32*mb + 16*grp + 4*(r%4); the lane receives column 32*mb + ln of 4 keys
     const int tr_r = lane & 15, tr_grp = (lane >> 4) & 1;
-    int koff[DS], toff[MB][2];
+    // (LDS byte addresses inside buffer 0 of the K tile, as integers: with the buffer a compile-time constant in the loop
+    //  below, every read is this register plus an immediate)
+    const uint32_t k0_ad = lds_addr_of(&sm.k[0][0]);
+    uint32_t koff[DS], toff[MB][2];
 #pragma unroll
-    for (int ds = 0; ds < DS; ++ds) koff[ds] = (ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8;
+    for (int ds = 0; ds < DS; ++ds) koff[ds] = k0_ad + 2u * (uint32_t)((ln * KCH + swz<KCH>(ln, 2 * ds + hf)) * 8);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int v = 0; v < 2; ++v)
-            toff[mb][v] = swz_elem<KCH>(4 * hf + (tr_r >> 2) + 8 * v, 32 * mb + 16 * tr_grp + 4 * (tr_r & 3));
+            toff[mb][v] = k0_ad + 2u * (uint32_t)swz_elem<KCH>(4 * hf + (tr_r >> 2) + 8 * v, 32 * mb + 16 * tr_grp + 4 * (tr_r & 3));
+    constexpr uint32_t kTileB = 64 * D * 2, kVfromK = 2 * kTileB;      // bytes of a tile buffer; sm.v[b] lies kVfromK after sm.k[b]
 
     floatx16 acc[MB];
 #pragma unroll
@@ -293,19 +297,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    for (int j = 0; j < nkt; ++j) {
-        const int buf = j & 1, k0 = j * 64;
-        if (j + 1 < nkt) issue_tile(buf ^ 1, j + 1);
+    // one key tile; BUF = j mod 2 at compile time
+    auto tile = [&](auto buf_tag, int j) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        const int k0 = j * 64;
+        if (j + 1 < nkt) issue_tile(BUF ^ 1, j + 1);
         const bool active = !CAUSAL || k0 <= wave_qmax;
         if (active) {
-            const uint16_t* kt_ = &sm.k[buf][0];
-            const uint16_t* vt_ = &sm.v[buf][0];
             floatx16 s[2], dp[2];
             {   // S^T = K^F Q^F^T and dP^T = V^F dO^T: 4*DS steps, step i: ds = i/4, kb = (i/2)%2, K or V = i%2
                 constexpr int NST = 4 * DS, RING = 6;
                 auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
-                    const uint16_t* base = (i & 1) ? vt_ : kt_;
-                    return *reinterpret_cast<const uint4v*>(base + koff[i >> 2] + ((i >> 1) & 1) * (32 * D));
+                    return lds_read16_at(koff[i >> 2] + (uint32_t)(BUF * kTileB + (i & 1) * kVfromK + ((i >> 1) & 1) * (32 * D * 2)));
                 };
                 uint4v ring[RING];
 #pragma unroll
@@ -349,7 +352,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
                 uint4v at[MB];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
-                    at[mb] = join(lds_read_tr16(kt_ + toff[mb][0] + ks * (16 * D)), lds_read_tr16(kt_ + toff[mb][1] + ks * (16 * D)));
+                    at[mb] = join(lds_read_tr16_at(toff[mb][0] + (uint32_t)(BUF * kTileB + ks * (16 * D * 2))),
+                                  lds_read_tr16_at(toff[mb][1] + (uint32_t)(BUF * kTileB + ks * (16 * D * 2))));
                 uint4v bds;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -365,6 +369,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+    };
+    for (int j = 0; j < nkt; j += 2) {
+        tile(std::integral_constant<int, 0>{}, j);
+        if (j + 1 < nkt) tile(std::integral_constant<int, 1>{}, j + 1);
     }
 
     if (q_row < L) {
