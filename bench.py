@@ -199,6 +199,15 @@ def main():
                                    "tflops": round(gemms[n] * pair_flops / (ms * 1e-3) / 1e12, 2)
                                    if n in gemms else None} for n, ms in kern_ms.items()}}
 
+    # what this machine sustains on MFMAs alone (boxes of one pool differ by 10 % in the clock they hold under load)
+    try:
+        sus_tf, sus_ghz = aq.attnqat_debug_mfma_burn(rounds=2, iters=20000)
+        if peak == MFMA_PEAK_TFLOPS:
+            roofline["mfma_sustained_on_this_box"] = {"tflops": round(sus_tf, 1), "clock_ghz": round(sus_ghz, 3),
+                                                      "achieved_over_sustained": round(achieved / sus_tf, 4)}
+    except Exception as e:       # context only: never fails the run
+        roofline["mfma_sustained_on_this_box"] = {"error": str(e)}
+
     cpu = None
     if args.cpu_seconds > 0:
         cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k, args.two_level_p)
