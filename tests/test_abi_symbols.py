@@ -44,3 +44,10 @@ def test_argument_validation_happens_before_any_gpu_call():
     f = aq.lib().attnqat_fwd_infer
     assert f(None, None, None, 1, 2, 2, 64, 128, 0, 0, None, None, None, 0, None) == aq.EINVAL
     assert aq.lib().attnqat_quantize(None, 1, 1, 16, 64, 0, None, None, None, None) == aq.EINVAL
+    # every entry point that takes tensors rejects null pointers and bad sizes with a status, without touching a GPU
+    L = aq.lib()
+    assert L.attnqat_fwd_infer_mx(None, None, None, 1, 2, 2, 64, 128, 0, 0, None, None, None, 0, None) == aq.EINVAL
+    assert L.attnqat_fwd_infer_mx_sparse(None, None, None, 1, 2, 2, 64, 128, 0, 0, None, None, None, None, 0, None) == aq.EINVAL
+    assert L.attnqat_debug_mfma_burn(0, 1, None, None, None) == aq.EINVAL
+    assert L.attnqat_debug_mfma_burn(1, 1 << 23, None, None, None) == aq.EINVAL
+

@@ -97,3 +97,11 @@ def test_two_streams_with_their_own_workspaces_do_not_interfere():
         for got, want in zip(outs, alone):
             for g_, w_ in zip(got, want):
                 assert torch.equal(g_, w_)
+
+
+def test_mfma_sustained_probe_reports_a_plausible_rate_and_clock():
+    import paper_2603_00040_amd as aq
+    tf, ghz = aq.attnqat_debug_mfma_burn(rounds=1, iters=4000)
+    print(f"sustained MFMA probe: {tf:.0f} TFLOP/s at {ghz:.2f} GHz", flush=True)
+    assert 1.0 < ghz < 2.6          # the part's clock range
+    assert 800.0 < tf < 2600.0      # below the published 2.5 PFLOP/s, well above what a stalled launch would give
