@@ -39,7 +39,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     constexpr int KCH = D / 8;      // 16-byte chunks per K row
     constexpr int KLD = KCH / 8;    // 1 KiB wave-loads per wave for the K tile (8 waves)
     constexpr int VLD = D / 64;     // ... for the V^T tile
-    extern __shared__ __align__(16) unsigned char smem_raw[];
+    extern __shared__ __align__(256) unsigned char smem_raw[];   // the XORs of address bits 5..7 commute with adding this base
     FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
 
     const int nqt = (Lp + 255) / 256;
