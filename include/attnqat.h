@@ -54,6 +54,7 @@ extern "C" {
 #define ATTNQAT_EDTYPE             -3   /* dtype other than ATTNQAT_BF16              */
 #define ATTNQAT_EWORKSPACE         -4   /* workspace null or smaller than required    */
 #define ATTNQAT_ELAUNCH            -5   /* the HIP runtime refused a launch           */
+#define ATTNQAT_ESTATIC            -6   /* attnqat_fwd_infer_static: needs more than ATTNQAT_STATIC_SCRATCH_BYTES */
 
 #define ATTNQAT_BF16                0
 
@@ -102,6 +103,24 @@ int attnqat_fwd_infer(const void* q, const void* k, const void* v,
                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                       void* o, float* lse,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * attnqat_fwd_infer for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit for bit)
+ * as attnqat_fwd_infer, without the workspace: the scratch memory is a fixed array of ATTNQAT_STATIC_SCRATCH_BYTES
+ * inside the library's device image, which every GPU that the library runs on holds until the process ends.
+ *   - Problems with attnqat_workspace_bytes(ATTNQAT_WS_FWD_INFER, ...) > ATTNQAT_STATIC_SCRATCH_BYTES are refused with
+ *     ATTNQAT_ESTATIC and nothing is enqueued (e.g. B=1, Hq=8, Hkv=2, L=8192, d=128 needs 24.1 MiB and fits).
+ *   - Calls nothing that allocates or frees.  The first call on a device looks up the array's device address
+ *     (hipGetSymbolAddress, once per device, kept); make that first call outside a graph capture.
+ *   - All calls on one GPU share the one array: calls that may overlap on a GPU (different streams, different
+ *     threads) race on it.  Calls on one stream are ordered and safe.  Nothing needs clearing between calls: the
+ *     quantization pass rewrites every byte the forward reads.
+ */
+#define ATTNQAT_STATIC_SCRATCH_BYTES (32u << 20)
+int attnqat_fwd_infer_static(const void* q, const void* k, const void* v,
+                             int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                             void* o, float* lse, void* stream);
 
 /*
  * Backward, Alg. 3, with straight-through estimation (Eq. 5):

@@ -15,7 +15,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libattnqat.so")
 
-OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH, ESTATIC = 0, -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 32 << 20
 BF16 = 0
 (WS_FWD, WS_FWD_INFER, WS_BWD, WS_FWD_INFER_MX, WS_FWD_MX, WS_BWD_MX, WS_FWD_INFER_MX_FP8PV,
  WS_FWD_INFER_MX_PAGED, WS_FWD_INFER_MX_SPARSE) = 0, 1, 2, 3, 4, 5, 6, 7, 8
@@ -25,6 +26,7 @@ _SIGNATURES = {
     "attnqat_quantize": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "attnqat_fwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_infer": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_fwd_infer_static": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
     "attnqat_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                          _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_ablation": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
@@ -299,6 +301,19 @@ def attnqat_fwd_infer(q, k, v, causal: bool, workspace=None, out=None):
     ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, workspace)
     _check(lib().attnqat_fwd_infer(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                    _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
+    return o, lse
+
+
+def attnqat_fwd_infer_static(q, k, v, causal: bool, out):
+    """attnqat_fwd_infer on the library's static scratch array: allocates nothing, so the outputs (o bf16, lse fp32)
+    must be passed in.  Raises for problems that need more than STATIC_SCRATCH_BYTES of scratch."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    o, lse = out
+    _check(lib().attnqat_fwd_infer_static(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+                                          _ptr(o), _ptr(lse), _stream()))
     return o, lse
 
 

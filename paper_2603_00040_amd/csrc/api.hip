@@ -3,9 +3,35 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <atomic>
+#include <mutex>
+
 using namespace aq;
 
+// Scratch of attnqat_fwd_infer_static: the workspace of the inference forward as device memory that exists from the
+// moment the library is loaded on a GPU until the process ends, so that the entry point never has to allocate.  Every
+// GPU holds its own copy at its own address; in host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[ATTNQAT_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of `scratch` on the current GPU, looked up once per device (no allocation).  Null on failure.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+void* static_scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -157,6 +183,7 @@ const char* attnqat_strerror(int code)
     case ATTNQAT_EDTYPE:     return "unsupported dtype (only ATTNQAT_BF16)";
     case ATTNQAT_EWORKSPACE: return "workspace missing or too small (see attnqat_workspace_bytes)";
     case ATTNQAT_ELAUNCH:    return "kernel launch failed";
+    case ATTNQAT_ESTATIC:    return "problem needs more scratch than ATTNQAT_STATIC_SCRATCH_BYTES (use the entry point that takes a workspace)";
     default:                 return "unknown error code";
     }
 }
@@ -379,6 +406,23 @@ int attnqat_fwd_infer(const void* q, const void* k, const void* v,
 {
     return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, false, o, lse, nullptr, 0, nullptr,
                       workspace, workspace_bytes, stream);
+}
+
+int attnqat_fwd_infer_static(const void* q, const void* k, const void* v,
+                             int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                             void* o, float* lse, void* stream)
+{
+    if (!q || !k || !v || !o || !lse) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    const size_t need = carve_fwd(nullptr, B, Hq, Hkv, L, d).bytes;
+    if (need > (size_t)ATTNQAT_STATIC_SCRATCH_BYTES) return ATTNQAT_ESTATIC;
+    void* ws = static_scratch_of_current_device();       // the device address, never the array's name
+    if (!ws) return ATTNQAT_ELAUNCH;
+    // Nothing has to start at zero: the quantization pass writes every byte of the copies that the forward reads
+    // (padding rows included) before the forward runs, whatever an earlier call left behind.
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, false, o, lse, nullptr, 0, nullptr,
+                      ws, need, stream);
 }
 
 int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
