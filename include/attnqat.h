@@ -187,10 +187,12 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
  *                          with respect to the centred K, which equals the gradient with respect to K because
  *                          rowsum(dS) = 0 when D comes from O' (Sec. 3.3).
  *   ATTNQAT_OPT_TWO_LEVEL_P  two-level quantization of P (Sec. 3.1): every row of a 64-key tile of P-tilde (forward)
- *                          or P (backward, the same aligned groups of 64 keys) is divided by s1, the smallest power
- *                          of two with 448 * 6 * s1 >= max(row maximum, 2^-24), quantized in NVFP4 blocks of 16 and
- *                          multiplied back, so that blocks far below the row maximum of the whole sequence keep
- *                          their values instead of under-flowing the E4M3 scale.  Only P^F changes (O, dV).
+ *                          and every row of the same aligned groups of 64 keys (key indices 64 g .. 64 g + 63) of the
+ *                          recomputed P (backward) is divided by s1, the smallest power of two with
+ *                          448 * 6 * s1 >= max(maximum of the row over those 64 keys, 2^-24), quantized in NVFP4
+ *                          blocks of 16 and multiplied back, so that blocks far below the row maximum of the whole
+ *                          sequence keep their values instead of under-flowing the E4M3 scale.  Masked keys and keys
+ *                          beyond L count as 0.  Only P^F changes (O, dV).
  * attnqat_fwd_opt: o_hp != NULL selects the training forward (Alg. 2), NULL the inference forward (Alg. 1).
  * attnqat_bwd_opt must be given the same options as the forward whose lse and o_hp it consumes.
  * options = 0 is attnqat_fwd / attnqat_fwd_infer / attnqat_bwd; unknown bits: ATTNQAT_EINVAL.

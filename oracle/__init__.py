@@ -23,12 +23,27 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 E2M1_VALUES = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)
 
 
+_LIB_SAN = os.path.join(_HERE, "liboracle_san.so")
+# ATTNQAT_ORACLE_SANITIZED=1 (set by tests/test_oracle_sanitized.py for a child process that preloads the sanitizer
+# runtime) makes this module load the build with AddressSanitizer and UndefinedBehaviorSanitizer instead.
+_SANITIZED = os.environ.get("ATTNQAT_ORACLE_SANITIZED") == "1"
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  Plain -O2: no fast-math, no reassociation."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
     return _LIB
+
+
+def build_sanitized(force: bool = False) -> str:
+    """The same source with -fsanitize=address,undefined (any finding aborts the process).  Host code only."""
+    if force or not os.path.exists(_LIB_SAN) or os.path.getmtime(_LIB_SAN) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fopenmp", "-fsanitize=address,undefined",
+             "-fno-sanitize-recover=all", "-shared", "-fPIC", "-o", _LIB_SAN, _SRC, "-lm"])
+    return _LIB_SAN
 
 
 _lib = None
@@ -39,8 +54,7 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    build()
-    L = ctypes.CDLL(_LIB)
+    L = ctypes.CDLL(build_sanitized() if _SANITIZED else build())
     L.oracle_e2m1_value.restype = _d
     L.oracle_e2m1_value.argtypes = [_i]
     L.oracle_e4m3_value.restype = _d

@@ -255,15 +255,14 @@ int oracle_phi_mx8(const float* x, long nrows, long n, uint8_t* codes, uint8_t* 
 /* SageAttention3's two-level scheme as Sec. 3.1 describes it and Sec. 4.2 switches on inside QAT
  * (scale_mode 4): every row of a P tile is first rescaled so that its maximum lands just below
  * 448 * 6 (the largest block scale times the largest element), then quantized as usual in NVFP4
- * blocks of 16.  Readings: a "row" is a row of the P tile of the pass: the 64 keys of one key tile
- * in the forward (TWO_LEVEL_SPAN = B_k), aligned groups of 32 keys in the backward
- * (TWO_LEVEL_SPAN_BWD, the width of the backward's P tiles; SageAttention3 is inference only and
- * fixes nothing there); the row factor is rounded up to a
- * power of two, s1 = the smallest 2^k with 2688 * 2^k >= max(rowmax, 2^-24), so that the rescale
+ * blocks of 16.  Readings: a "row" is the 64 keys of one key tile (TWO_LEVEL_SPAN = B_k, the key
+ * tile of the forward); the backward applies the same operator to the same aligned groups of 64
+ * keys of the recomputed P (Sec. 2.3, "Matching the precision of P in the forward and backward
+ * passes": the recomputation goes through the quantizer the forward used); the row factor is
+ * rounded up to a power of two, s1 = the smallest 2^k with 2688 * 2^k >= max(rowmax, 2^-24), so that the rescale
  * is exact in every number format involved (the row maximum lands in (1344, 2688]) and rows
  * without any mass do not produce unbounded factors. */
 #define TWO_LEVEL_SPAN 64
-#define TWO_LEVEL_SPAN_BWD 32
 static double two_level_s1(double rowmax)
 {
     double base = rowmax > ldexp(1.0, -24) ? rowmax : ldexp(1.0, -24);
@@ -425,9 +424,10 @@ int oracle_fwd_rows_masked(const float* qf, const float* kf, const float* vf,
 
 /* ----------------------------------------------------------------- backward */
 
-/* Keys per P block: 16 (NVFP4), 32 in the MX formats (scale_mode 2 and 3). */
+/* Keys per P block: 16 (NVFP4), 32 in the MX format (scale_mode 2).  The mixed FP4/FP8 recipe (scale_mode 3) is an
+ * inference recipe and has no backward: the entry points below refuse it. */
 #define PB_MAX 32
-static int pb_of(int scale_mode) { return (scale_mode == 2 || scale_mode == 3) ? 32 : 16; }
+static int pb_of(int scale_mode) { return scale_mode == 2 ? 32 : 16; }
 
 /*
  * One query row against one aligned block of pb keys [k0, k0+pb): the inner
@@ -435,13 +435,13 @@ static int pb_of(int scale_mode) { return (scale_mode == 2 || scale_mode == 3) ?
  * (the rest are masked: P = 0), kend = end of the row's visible keys.  Returns P (fp32-rounded),
  * P^F and dS.
  */
-/* Two-level P in the backward: the row factor of the aligned group of TWO_LEVEL_SPAN_BWD keys that
- * holds block k0 (keys >= kend are masked: P = 0). */
+/* Two-level P in the backward: the row factor of the aligned group of TWO_LEVEL_SPAN keys (the forward's
+ * tile row) that holds block k0 (keys >= kend are masked: P = 0). */
 static double span_s1(const float* qrow, double lse, const float* kh, long k0, long kend, int d, double rs)
 {
-    long s0 = k0 - k0 % TWO_LEVEL_SPAN_BWD;
+    long s0 = k0 - k0 % TWO_LEVEL_SPAN;
     double rmax = 0.0;
-    for (long k = s0; k < s0 + TWO_LEVEL_SPAN_BWD && k < kend; ++k) {
+    for (long k = s0; k < s0 + TWO_LEVEL_SPAN && k < kend; ++k) {
         double p = (double)(float)exp(dot(qrow, kh + k * d, d) * rs - lse);
         if (p > rmax) rmax = p;
     }
@@ -466,7 +466,6 @@ static void bwd_block(const float* qrow, const float* dorow, double lse, double 
         phi_block(P2, 16, 0, NULL, NULL, NULL, Pf2);
         for (int k = 0; k < 16; ++k) Pf[k] = s1 * Pf2[k];
     }
-    else if (quant_p && scale_mode == 3) phi_mx8_block(P, pb, NULL, NULL, Pf);
     else if (quant_p && scale_mode == 2) phi_mx_block(P, pb, NULL, NULL, Pf);
     else if (quant_p) phi_block(P, pb, scale_mode, NULL, NULL, NULL, Pf);
     else for (int k = 0; k < pb; ++k) Pf[k] = P[k];
@@ -495,6 +494,7 @@ int oracle_bwd(const float* qf, const float* kf, const float* vf, const float* d
                double* dQ, double* dK, double* dV)
 {
     if (!qf || !kf || !vf || !dO || !Lse || !Op || Hq % Hkv) return -1;
+    if (scale_mode == 3) return -3;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     const int pb = pb_of(scale_mode);
@@ -543,6 +543,7 @@ int oracle_bwd_dq_rows(const float* qf, const float* kf, const float* vf, const 
                        const double* Lse_rows, const double* Op_rows, double* dQ_rows)
 {
     if (!rows || Hq % Hkv) return -1;
+    if (scale_mode == 3) return -3;
     (void)B;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
@@ -582,6 +583,7 @@ int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, cons
                          double* dK_keys, double* dV_keys, float* Pf_dump)
 {
     if (!keys || Hq % Hkv || b < 0 || b >= B || hk < 0 || hk >= Hkv) return -1;
+    if (scale_mode == 3) return -3;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     const int pb = pb_of(scale_mode);
@@ -635,6 +637,7 @@ int oracle_bwd_rows_dkdv(const float* qf, const float* kf, const float* vf, cons
                          double* dK, double* dV)
 {
     if (!rows || Hq % Hkv) return -1;
+    if (scale_mode == 3) return -3;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     const int pb = pb_of(scale_mode);

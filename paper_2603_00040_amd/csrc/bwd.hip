@@ -428,6 +428,7 @@ struct DkvSmem {
     uint16_t q[2][32 * D];           // Q^F rows [query][d], fp16, swizzled
     uint16_t g[2][32 * D];           // dO rows  [query][d], bf16, swizzled
     uint16_t t[4][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
+    float rmax[4][32];               // two-level P: per wave, the largest P of every query row over the wave's 32 keys
 };
 
 template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */,
@@ -556,7 +557,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             issue_next(buf ^ 1);
             st_n = rowstat[(bh0 + nx_g) * Lp + (size_t)(qt_first + nx_t) * 32 + ln];
         }
-        const bool active = !CAUSAL || q0 + 31 >= key0_w;          // wave-uniform
+        // wave-uniform.  With the two-level P every wave takes part in every tile: the exchange of the row maxima below
+        // contains a workgroup barrier, and a wave whose keys all lie after the tile's queries computes P = 0 throughout
+        // (which costs the first four query tiles of a workgroup some idle products and nothing else).
+        const bool active = PQ == 3 || !CAUSAL || q0 + 31 >= key0_w;
         if (active) {
             // Q^F tile of this iteration (dO is kGB further).  The per-lane offsets are made opaque once
             // per iteration: otherwise the compiler hoists every (offset ^ constant) out of the loop and
@@ -565,7 +569,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             asm volatile("" : "+v"(a_it), "+v"(g_it0), "+v"(g_it1));
             floatx16 s, dp;
             {   // S^T = K^F Q^F^T, dP^T = V^F dO^T: 2*DS steps, step i: ds = i/2, Q or dO = i%2
-                constexpr int NST = 2 * DS, RING = 3;
+                // (the two-level variant carries the exchanged row maximum and its LDS slot on top: its ring is one shorter)
+                constexpr int NST = 2 * DS, RING = PQ == 3 ? 2 : 3;
                 auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
                     return lds_read16_at((uint32_t)((a_it ^ ((i >> 1) << 5)) + (i & 1) * kGB));
                 };
@@ -623,14 +628,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
 #pragma unroll
                 for (int t = 0; t < 4; ++t) p4[t] = fmaxf(fmaxf(s[t], s[4 + t]), fmaxf(s[8 + t], s[12 + t]));
                 nz = fmaxf(fmaxf(p4[0], p4[1]), fmaxf(p4[2], p4[3])) * (1.0f / 6.0f) > 0.0009765625f;
-            } else if constexpr (PQ == 3) {
-                nz = true;       // decided with the scales below: after the row factor a tile is almost never all zero
+            }
+            // Two-level quantization of P (PQ == 3): the row factor belongs to an aligned group of 64 keys, the tile row
+            // of the forward, i.e. to this wave's 32 keys and those of its neighbour (waves 0|1 and 2|3 of the
+            // workgroup).  The two waves exchange their partial row maxima through LDS.
+            float pair_max = 0.0f;
+            if constexpr (PQ == 3) {
+                float p4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) p4[t] = fmaxf(fmaxf(s[t], s[4 + t]), fmaxf(s[8 + t], s[12 + t]));
+                const float own = xhalf_max(fmaxf(fmaxf(p4[0], p4[1]), fmaxf(p4[2], p4[3])));
+                // rmax[w][row] sits 128 w + 4 row bytes into a 256-byte aligned array: the neighbour's slot is address ^ 128
+                const uint32_t rm_ad = lds_addr_of(&sm.rmax[0][0]) + 128u * (uint32_t)wave + 4u * (uint32_t)ln;
+                *(__attribute__((address_space(3))) float*)(uintptr_t)rm_ad = own;      // both half-waves hold the same value
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                pair_max = fmaxf(own, *(const __attribute__((address_space(3))) float*)(uintptr_t)(rm_ad ^ 128u));
             }
             // block scales of phi(P): one per 16 keys = registers 8*gq .. 8*gq+7 of both halves (NVFP4, with or without
             // the row factor of the two-level form)
             auto nvfp4_scales = [&]() __attribute__((always_inline)) {
-                // Two-level quantization of P (PQ == 3): a row of this wave's tile (32 aligned keys) is divided by s1,
-                // the smallest power of two with 2688 s1 >= max(row maximum, 2^-24), before the NVFP4 blocks
+                // Two-level quantization of P (PQ == 3): the row of the aligned 64-key group is divided by s1, the
+                // smallest power of two with 2688 s1 >= max(row maximum of the group, 2^-24), before the NVFP4 blocks
                 float s1 = 1.0f, inv1 = 1.0f;
                 float amax[2];
 #pragma unroll
@@ -641,7 +659,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                     amax[gq] = xhalf_max(amax[gq]);
                 }
                 if constexpr (PQ == 3) {
-                    const float base = fmaxf(fmaxf(amax[0], amax[1]), 5.9604644775390625e-08f);
+                    const float base = fmaxf(pair_max, 5.9604644775390625e-08f);
                     const uint32_t e1 = ((__float_as_uint(base) + 0x0057FFFFu) >> 23) - 11u;      // 2688 = 1.3125 * 2^11
                     s1 = __uint_as_float(e1 << 23);
                     inv1 = __uint_as_float((254u - e1) << 23);
@@ -658,7 +676,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 }
                 return any;
             };
-            if constexpr (PQ == 3) nz = nvfp4_scales();
+            if constexpr (PQ == 3) nz = nvfp4_scales();      // after the row factor a tile is almost never all zero
             // dS = P (dP - D_i)/sqrt(d) from the fp32 P, scaled, as fp16, staged as [query][key]
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4) {                           // 4 consecutive keys per store

@@ -1,6 +1,7 @@
 """Pins of the oracle's two-level quantization of P (Sec. 3.1: each row of P is rescaled to [0, 448 * 6] before the
-NVFP4 blocks; an option inside QAT in Sec. 4.2).  Readings pinned here: rows are the 64 keys of a key tile in the
-forward and aligned groups of 32 keys in the backward, the row factor is the smallest power of two that keeps the row maximum below 448 * 6, with a floor of 2^-24 on that maximum."""
+NVFP4 blocks; an option inside QAT in Sec. 4.2).  Readings pinned here: rows are the 64 keys of a key tile, in the
+forward and (the same aligned groups of the recomputed P) in the backward; the row factor is the smallest power of two
+that keeps the row maximum below 448 * 6, with a floor of 2^-24 on that maximum."""
 import numpy as np
 import pytest
 import torch
@@ -70,7 +71,7 @@ def test_two_levels_keep_the_probabilities_that_plain_nvfp4_flushes():
 
 @pytest.mark.parametrize("causal", [False, True])
 def test_backward_matches_autograd_of_unrolled_ste_graph(causal):
-    q, k, v = _rand(1, 4, 2, 150, 32, seed=73, outlier=True)             # 150 = 4 * 32 + 22: a short last group
+    q, k, v = _rand(1, 4, 2, 150, 32, seed=73, outlier=True)             # 150 = 2 * 64 + 22: a short last group
     do = _bf(np.random.default_rng(74).standard_normal(q.shape))
     f = oracle.fwd(q, k, v, causal, 64, scale_mode=TL)
     g = oracle.bwd(q, k, v, do, f["L"], f["Op"], causal, scale_mode=TL)
@@ -85,8 +86,8 @@ def test_backward_matches_autograd_of_unrolled_ste_graph(causal):
     if causal:
         s = s.masked_fill(torch.triu(torch.ones(150, 150, dtype=torch.bool), 1), float("-inf"))
     p = torch.softmax(s, -1)
-    # the backward's P tiles are 32 keys wide: the row factor is taken per aligned group of 32 keys there
-    pq = torch.from_numpy(indep.fake_quant_two_level_np(p.detach().to(torch.float32).to(torch.float64).numpy(), axis=-1, span=32))
+    # the same operator as the forward: the row factor is taken per aligned group of 64 keys
+    pq = torch.from_numpy(indep.fake_quant_two_level_np(p.detach().to(torch.float32).to(torch.float64).numpy(), axis=-1))
     p = p + (pq - p).detach()
     ((p @ vf) * torch.from_numpy(do.astype(np.float64))).sum().backward()
     for name, a, b in (("dQ", g["dQ"], tq.grad.numpy()), ("dK", g["dK"], tk.grad.numpy()), ("dV", g["dV"], tv.grad.numpy())):
