@@ -677,6 +677,29 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 return any;
             };
             if constexpr (PQ == 3) nz = nvfp4_scales();      // after the row factor a tile is almost never all zero
+            // If every block scale of this 32x32 tile rounded to 0 (max P <= 6 * 2^-10: the usual case for long rows),
+            // P^F is identically 0: quantizing it, staging it and the dV products are skipped.  Wave-uniform, exact.
+            const bool with_pf = PQUANT && __builtin_amdgcn_ballot_w64(nz) != 0;
+            if constexpr (COUNT) { ++n_tiles; if (with_pf) ++n_pf_tiles; }
+            // P^F = phi^-1(phi(P)) as bf16, staged as [query][key] before dS is: both tiles are then in LDS when the
+            // products start, and the dV products of a tile that has them follow its dK products in one stream (a wave
+            // that quantized, staged and multiplied P^F only after its dK products kept the other three waiting at the
+            // tile barrier for the whole of that dependent chain).
+            if (with_pf) {
+                if constexpr (PQ == 1) nvfp4_scales();
+                if constexpr (PQUANT) {
+#pragma unroll
+                    for (int t4 = 0; t4 < 4; ++t4) {
+                        const int r0 = 4 * t4, gq = t4 >> 1;
+                        float pf[4];
+                        fq_pair_f32(s[r0] * inv[gq], s[r0 + 1] * inv[gq], sc[gq], pf[0], pf[1]);
+                        fq_pair_f32(s[r0 + 2] * inv[gq], s[r0 + 3] * inv[gq], sc[gq], pf[2], pf[3]);
+                        uint2v wp;
+                        wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
+                        lds_write8_at(tw_ad + (uint32_t)(16 * (r0 >> 2)), wp);
+                    }
+                }
+            }
             // dS = P (dP - D_i)/sqrt(d) from the fp32 P, scaled, as fp16, staged as [query][key]
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4) {                           // 4 consecutive keys per store
@@ -692,9 +715,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            // dK += dS^T Q^F, then dV += P^F^T dO, each in 2*NB steps: step j covers queries
-            // 16*(j/NB) .. +15 (contraction slots 0-3: queries 16*ks + 8*hf + 0..3, slots 4-7: the next
-            // four) and columns 32*(j%NB) .. +31.  The operands of step j+1 are read while step j multiplies.
+            // dK += dS^T Q^F (steps 0 .. NSTEP-1) and dV += P^F^T dO (steps NSTEP .. 2 NSTEP-1), NSTEP = 2*NB steps each:
+            // step j of a product covers queries 16*(j/NB) .. +15 (contraction slots 0-3: queries 16*ks + 8*hf + 0..3,
+            // slots 4-7: the next four) and columns 32*(j%NB) .. +31.  The operands of a step are read while the step
+            // before it multiplies.
             constexpr int NSTEP = 2 * NB;
             auto rd_b = [&](int j, int extra) __attribute__((always_inline)) -> uint4v {
                 const int nb = j % NB, ks = j / NB;
@@ -705,50 +729,54 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 const uint32_t ta = ta_ad + (uint32_t)(tb + ks * (16 * kTPad * 2));
                 return join(lds_read_tr16_at(ta), lds_read_tr16_at(ta + 4 * kTPad * 2));
             };
-            {
-                uint4v ah = rd_t(kTB, 0), bq[2];
-                bq[0] = rd_b(0, 0);
+            // steps [FIRST, LAST) of the stream
+            auto products = [&](auto first_tag, auto last_tag) __attribute__((always_inline)) {
+                constexpr int FIRST = decltype(first_tag)::value, LAST = decltype(last_tag)::value;
+                auto a_of = [&](int st) __attribute__((always_inline)) -> uint4v { return rd_t(st < NSTEP ? kTB : 0, (st % NSTEP) / NB); };
+                auto b_of = [&](int st) __attribute__((always_inline)) -> uint4v { return rd_b(st % NSTEP, st < NSTEP ? 0 : kGB); };
+                uint4v a = a_of(FIRST), b[2];
+                b[FIRST & 1] = b_of(FIRST);
 #pragma unroll
-                for (int j = 0; j < NSTEP; ++j) {
-                    const int nb = j % NB;
-                    if (j + 1 < NSTEP) bq[(j + 1) & 1] = rd_b(j + 1, 0);
-                    uint4v ah_n;
-                    if (j == NB - 1) ah_n = rd_t(kTB, 1);
-                    dk[nb] = mfma_f16(ah, bq[j & 1], dk[nb]);
-                    if (j == NB - 1) ah = ah_n;
+                for (int st = FIRST; st < LAST; ++st) {
+                    const int nb = st % NB;
+                    const bool new_a = st + 1 < LAST && (st + 1) % NB == 0;
+                    if (st + 1 < LAST) b[(st + 1) & 1] = b_of(st + 1);
+                    uint4v a_n;
+                    if (new_a) a_n = a_of(st + 1);
+                    if (st < NSTEP) dk[nb] = mfma_f16(a, b[st & 1], dk[nb]);
+                    else            dv[nb] = mfma_bf16(a, b[st & 1], dv[nb]);
+                    if (new_a) a = a_n;
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, 2 + 2, 0);
 #pragma unroll
-                for (int j = 0; j < NSTEP; ++j) {
-                    if (j + 1 < NSTEP) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                    if (j == NB - 1) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                for (int st = FIRST; st < LAST; ++st) {
+                    if (st + 1 < LAST) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    if (st + 1 < LAST && (st + 1) % NB == 0) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 }
-            }
-            // If every block scale of this 32x32 tile rounded to 0 (max P <= 6 * 2^-10: the usual case
-            // for long rows), P^F is identically 0: quantizing it, staging it and the dV products are
-            // skipped.  Wave-uniform, exact.
-            if constexpr (COUNT) ++n_tiles;
-            if (!PQUANT || __builtin_amdgcn_ballot_w64(nz) != 0) {
-                if constexpr (COUNT) ++n_pf_tiles;
-                if constexpr (PQ == 1) nvfp4_scales();
-                // P^F = phi^-1(phi(P)), staged as [query][key].  Ablation (Sec. 4.2, "no fake quantization of P in
-                // the backward"): the fp32 P itself, in two passes as a bf16 hi + lo pair.
+            };
+            typedef std::integral_constant<int, 0> I0;
+            typedef std::integral_constant<int, NSTEP> I1;
+            typedef std::integral_constant<int, 2 * NSTEP> I2;
+            if constexpr (PQUANT) {
+                // (two branches, each with its whole stream, would let the dV operand reads start under the dK products; the
+                //  compiler then shuffles the 256 accumulator registers between the branches and spills)
+                products(I0{}, I1{});
+                if (with_pf) products(I1{}, I2{});
+            } else {
+                // Ablation (Sec. 4.2, "no fake quantization of P in the backward"): dV from the fp32 P itself, which enters
+                // its product in two passes as a bf16 hi + lo pair
+                products(I0{}, I1{});
 #pragma unroll
-                for (int pass = 0; pass < (PQUANT ? 1 : 2); ++pass) {
+                for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
                     for (int t4 = 0; t4 < 4; ++t4) {
-                        const int r0 = 4 * t4, gq = t4 >> 1;
+                        const int r0 = 4 * t4;
                         float pf[4];
-                        if constexpr (PQUANT) {
-                            fq_pair_f32(s[r0] * inv[gq], s[r0 + 1] * inv[gq], sc[gq], pf[0], pf[1]);
-                            fq_pair_f32(s[r0 + 2] * inv[gq], s[r0 + 3] * inv[gq], sc[gq], pf[2], pf[3]);
-                        } else {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float hi = __uint_as_float((uint32_t)f32_to_bf16_rne(s[r0 + e]) << 16);
-                                pf[e] = pass == 0 ? hi : s[r0 + e] - hi;
-                            }
+                        for (int e = 0; e < 4; ++e) {
+                            const float hi = __uint_as_float((uint32_t)f32_to_bf16_rne(s[r0 + e]) << 16);
+                            pf[e] = pass == 0 ? hi : s[r0 + e] - hi;
                         }
                         uint2v wp;
                         wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
@@ -757,17 +785,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    uint4v ap = rd_t(0, 0), bg[2];
-                    bg[0] = rd_b(0, kGB);
-#pragma unroll
-                    for (int j = 0; j < NSTEP; ++j) {
-                        const int nb = j % NB;
-                        if (j + 1 < NSTEP) bg[(j + 1) & 1] = rd_b(j + 1, kGB);
-                        uint4v ap_n;
-                        if (j == NB - 1) ap_n = rd_t(0, 1);
-                        dv[nb] = mfma_bf16(ap, bg[j & 1], dv[nb]);
-                        if (j == NB - 1) ap = ap_n;
-                    }
+                    products(I1{}, I2{});
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                 }
