@@ -5,11 +5,12 @@ import torch
 
 import oracle
 import workloads as W
-from tests.gpu_util import f32, host, max_abs, random_inputs, rel_l2, to_dev
+from tests.gpu_util import check_bf16_output, f32, host, max_abs, random_inputs, rel_l2, to_dev
 
 pytestmark = pytest.mark.gpu
 
-TOL = 2e-3     # rel-L2 per tensor; the bf16 rounding of the outputs alone is about 1.7e-3
+TOL = 2e-3     # rel-L2 per tensor; the bf16 rounding of the outputs alone is about 1.7e-3 (check_bf16_output adds the
+               # bars that do not contain that rounding, and a bound on the largest element error)
 
 
 def _run(B, Hq, Hkv, L, d, causal, seed, **kw):
@@ -22,11 +23,9 @@ def _run(B, Hq, Hkv, L, d, causal, seed, **kw):
     fq, fk, fv, fdo = (f32(x[n]) for n in ("q", "k", "v", "do"))
     rf = oracle.fwd(fq, fk, fv, causal, aq.block_k())
     rb = oracle.bwd(fq, fk, fv, fdo, rf["L"], rf["Op"], causal)
-    r = {n: (rel_l2(host(t), rb[n], zero_rms=1e-2), max_abs(host(t), rb[n])) for n, t in (("dQ", dq), ("dK", dk), ("dV", dv))}
-    print(f"bwd B{B} Hq{Hq} Hkv{Hkv} L{L} d{d} causal{int(causal)}: " +
-          " ".join(f"{n} rel {a:.2e} max {b:.2e}" for n, (a, b) in r.items()), flush=True)
-    for n, (a, _) in r.items():
-        assert a <= TOL, (n, a)
+    print(f"bwd B{B} Hq{Hq} Hkv{Hkv} L{L} d{d} causal{int(causal)}:", flush=True)
+    for n, t in (("dQ", dq), ("dK", dk), ("dV", dv)):
+        check_bf16_output(n, host(t), rb[n], TOL, zero_rms=1e-2)
     # determinism: no atomics anywhere, a second call returns the same bits
     dq2, dk2, dv2 = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
     torch.cuda.synchronize()
@@ -62,7 +61,7 @@ def test_backward_with_oracle_forward_state():
     dq, dk, dv = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
     torch.cuda.synchronize()
     for n, t in (("dQ", dq), ("dK", dk), ("dV", dv)):
-        assert rel_l2(host(t), rb[n]) <= TOL, n
+        check_bf16_output(n, host(t), rb[n], TOL)
 
 
 @pytest.mark.parametrize("log2_scale", [-40, 0, 30])

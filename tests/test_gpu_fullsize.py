@@ -16,7 +16,7 @@ import torch
 
 import oracle
 import workloads as W
-from tests.gpu_util import f32, host, max_abs, rel_l2, to_dev
+from tests.gpu_util import check_bf16_output, f32, host, max_abs, rel_l2, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -71,9 +71,10 @@ def test_full_size(cfg):
     torch.cuda.synchronize()
     print(f"[{w.name}] oracle forward on {flat.size} rows", flush=True)
     rf = oracle.fwd(sub["q"], sub["k"], sub["v"], w.causal, Bk, rows=flat)
-    eO = rel_l2(host(pick(o)), rf["O"]); eL = max_abs(host(pick(lse)), rf["L"])
-    print(f"[{w.name}] O rel-L2 {eO:.2e} max-abs {max_abs(host(pick(o)), rf['O']):.2e}  L max-abs {eL:.2e}", flush=True)
-    assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
+    eL = max_abs(host(pick(lse)), rf["L"])
+    print(f"[{w.name}] L max-abs {eL:.2e}", flush=True)
+    check_bf16_output("O", host(pick(o)), rf["O"], TOL, label=f"[{w.name}] ")
+    assert eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
     if train:
         eOp = rel_l2(host(pick(ohp)), rf["Op"])
         print(f"[{w.name}] O' rel-L2 {eOp:.2e}", flush=True)
@@ -114,9 +115,7 @@ def test_full_size(cfg):
     dq, dk, dv = aq.attnqat_bwd(q, k, v, do, lse, ohp, w.causal)
     torch.cuda.synchronize()
     rdq = oracle.bwd_dq_rows(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
-    eQ = rel_l2(host(pick(dq)), rdq)
-    print(f"[{w.name}] dQ rel-L2 {eQ:.2e} max-abs {max_abs(host(pick(dq)), rdq):.2e}", flush=True)
-    assert eQ <= TOL
+    check_bf16_output("dQ", host(pick(dq)), rdq, TOL, label=f"[{w.name}] ")
     # Eq. 5: sum_i dQ_i . Q^F_i = sum_k dK_k . K^F_k (both equal sum_ik dS_ik S_ik sqrt(d)) ties the
     # dense dK of EVERY head to dQ at any size
     _, _, qf = aq.attnqat_quantize(q, want_codes=False)
@@ -139,11 +138,9 @@ def test_full_size(cfg):
     torch.cuda.synchronize()
     rdk, rdv = oracle.bwd_rows_dkdv(sub["q"], sub["k"], sub["v"], sub["do"], flat, rf["L"], rf["Op"], w.causal)
     gk = host(dk[b, kv]); gv = host(dv[b, kv])
-    eK, eV = rel_l2(gk, rdk[0]), rel_l2(gv, rdv[0], zero_rms=1e-6)
-    nzv = float((rdv[0] != 0).mean())
-    print(f"[{w.name}] dK rel-L2 {eK:.2e} max-abs {max_abs(gk, rdk[0]):.2e}  dV rel-L2 {eV:.2e} "
-          f"max-abs {max_abs(gv, rdv[0]):.2e} (oracle dV non-zero fraction {nzv:.3f})", flush=True)
-    assert eK <= TOL and eV <= TOL
+    print(f"[{w.name}] oracle dV non-zero fraction {float((rdv[0] != 0).mean()):.3f}", flush=True)
+    check_bf16_output("dK", gk, rdk[0], TOL, label=f"[{w.name}] ")
+    check_bf16_output("dV", gv, rdv[0], TOL, zero_rms=1e-6, label=f"[{w.name}] ")
     other = [hk for hk in range(w.Hkv) if hk not in kv]
     if other:
         assert not dk[:, other].any() and not dv[:, other].any()
