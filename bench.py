@@ -27,7 +27,7 @@ MFMA_FP8_PEAK_TFLOPS = 5000.0      # MI355X dense FP8 MFMA (P V of the mixed rec
 KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "fwd_infer_mx_fp8pv": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
 # Bytes beyond L2 per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
 # measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
-# Sec. 4.4: peak forward throughput on B200 (NVFP4 QK + FP8 PV) at b=1, s=32768, h=32, d=128.  Another machine and
+# Sec. 3.4: peak forward throughput on B200 (NVFP4 QK + FP8 PV) at b=1, s=32768, h=32, d=128.  Another machine and
 # another recipe: context for the forward on that shape, not a target.
 PAPER_FWD_TFLOPS = {"paper_peak_fwd_shape": 2026.0}
 MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 20.0e9, "bwd_dq": 33.0e9, "bwd_dkdv": 707.4e9},
@@ -44,16 +44,16 @@ def main():
                          "(context only: the shape of the paper's peak forward figure)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     ap.add_argument("--ablation", type=int, default=0,
-                    help="backward ablation bit set of Sec. 4.2 (1: D from the bf16 O, 2: dV from the un-quantized P); "
+                    help="backward ablation bit set of Sec. 3.2 (1: D from the bf16 O, 2: dV from the un-quantized P); "
                          "0 = the method itself")
     ap.add_argument("--format", default="nvfp4", choices=["nvfp4", "mx", "mx_fp8pv"],
                     help="nvfp4: the paper's format (default).  mx: E2M1 blocks of 32 with E8M0 scales: the inference "
                          "forward runs on the scaled FP4 MFMA, the training forward and the backward on the 16-bit path.  "
                          "mx_fp8pv: the mixed recipe (FP4 Q K^T, MXFP8 P V), inference forward only")
     ap.add_argument("--smooth-k", action="store_true",
-                    help="K smoothing option of Sec. 4.2 (nvfp4 format only): phi on K minus its token mean")
+                    help="K smoothing option of Sec. 3.2 (nvfp4 format only): phi on K minus its token mean")
     ap.add_argument("--two-level-p", action="store_true",
-                    help="two-level quantization of P, the other option of Sec. 4.2 (nvfp4 format only)")
+                    help="two-level quantization of P, the other option of Sec. 3.2 (nvfp4 format only)")
     ap.add_argument("--paged-lq", type=int, default=0,
                     help="serving mode (not a benchmark configuration): the MX forward over a paged FP4 KV cache with this many "
                          "query positions per sequence (1 = a decode step) for 32 sequences of 4k-16k keys, 32 query / 8 kv heads")
@@ -85,7 +85,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     if args.mfma_sustained:
-        tf, ghz = aq.attnqat_debug_mfma_burn()
+        from paper_2603_00040_amd import benchaux
+        tf, ghz = benchaux.mfma_sustained()
         print(json.dumps({"metric": "sustained v_mfma_f32_32x32x16_f16 rate, register operands, 2 waves per SIMD (1 MI355X)",
                           "value": round(tf, 1), "unit": "TFLOP/s", "n_gpus": 1, "clock_ghz": round(ghz, 3),
                           "published_peak": MFMA_PEAK_TFLOPS, "frac_of_published_peak": round(tf / MFMA_PEAK_TFLOPS, 4)}), flush=True)
@@ -201,7 +202,8 @@ def main():
 
     # what this machine sustains on MFMAs alone (boxes of one pool differ by 10 % in the clock they hold under load)
     try:
-        sus_tf, sus_ghz = aq.attnqat_debug_mfma_burn(rounds=2, iters=20000)
+        from paper_2603_00040_amd import benchaux
+        sus_tf, sus_ghz = benchaux.mfma_sustained(rounds=2, iters=20000)
         if peak == MFMA_PEAK_TFLOPS:
             roofline["mfma_sustained_on_this_box"] = {"tflops": round(sus_tf, 1), "clock_ghz": round(sus_ghz, 3),
                                                       "achieved_over_sustained": round(achieved / sus_tf, 4)}
@@ -247,15 +249,18 @@ def bench_paged(args, aq, torch, np):
     perm = rng.permutation(num_pages).astype(np.int32)
     table = np.zeros((B, max_pages), np.int32)
     cache = torch.empty(num_pages * aq.kv_cache_page_bytes(Hkv, d), dtype=torch.uint8, device="cuda")
-    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    import workloads as W
+    dev = lambda bits: torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
     nxt = 0
-    for b in range(B):
+    qb = []
+    for b in range(B):          # inputs from the seeded host generator, as everywhere else: N(0,1), K with 4 outlier channels x20
         n = int(kv_lens[b])
         table[b, :pages_of[b]] = perm[nxt:nxt + pages_of[b]]; nxt += pages_of[b]
-        k = torch.randn((1, Hkv, n, d), device="cuda", generator=g).to(torch.bfloat16)
-        v = torch.randn((1, Hkv, n, d), device="cuda", generator=g).to(torch.bfloat16)
-        aq.attnqat_kv_cache_write_mx(k, v, cache, torch.from_numpy(table[b, :pages_of[b]].copy()).cuda())
-    q = torch.randn((B, Hq, Lq, d), device="cuda", generator=g).to(torch.bfloat16)
+        k = dev(W.fill(1, Hkv, n, d, 500 + b, W.TENSOR_K, "normal", 1.0, n_chan=4, chan_mult=20.0))
+        v = dev(W.fill(1, Hkv, n, d, 500 + b, W.TENSOR_V, "normal", 1.0))
+        qb.append(W.fill(1, Hq, Lq, d, 500 + b, W.TENSOR_Q, "normal", 1.0)[0])
+        aq.attnqat_kv_cache_write_mx(k, v, cache, torch.from_numpy(table[b, :pages_of[b]].copy()).cuda(), num_pages)
+    q = dev(np.ascontiguousarray(np.stack(qb)))
     tab, lens = torch.from_numpy(table).cuda(), torch.from_numpy(kv_lens).cuda()
     o = torch.empty_like(q); lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device="cuda")
     ws = torch.empty(aq.workspace_bytes(aq.WS_FWD_INFER_MX_PAGED, B, Hq, Hkv, Lq, d), dtype=torch.uint8, device="cuda")

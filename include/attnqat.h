@@ -2,13 +2,13 @@
  * attnqat.h -- C ABI of the MI355X (gfx950) Attn-QAT hot path.
  *
  * NVFP4 fake-quantized attention: E2M1 elements with one E4M3 scale per 16
- * elements (Sec. 3.1, Eq. 1-2), the inference forward (Alg. 1), the training
+ * elements (Sec. 2.1, Eq. 1-2), the inference forward (Alg. 1), the training
  * forward that also emits the high-precision output O' (Alg. 2) and the
  * backward that re-quantizes the recomputed P and takes D from O' (Alg. 3).
  *
  * Beyond that core (each group is described where it is declared):
- *   attnqat_bwd_ablation                the two backward ablations of Sec. 4.2
- *   attnqat_fwd_opt, attnqat_bwd_opt    K smoothing and two-level quantization of P (Sec. 3.1 / 4.2) as option bits
+ *   attnqat_bwd_ablation                the two backward ablations of Sec. 3.2
+ *   attnqat_fwd_opt, attnqat_bwd_opt    K smoothing and two-level quantization of P (Sec. 2.1 / 4.2) as option bits
  *   attnqat_quantize_mx, attnqat_fwd_infer_mx, attnqat_fwd_mx, attnqat_bwd_mx
  *                                       the same method in the MX format (E2M1 blocks of 32, E8M0 scales), whose
  *                                       inference forward runs on the scaled FP4 matrix instruction
@@ -69,7 +69,7 @@ extern "C" {
 #define ATTNQAT_WS_FWD_INFER_MX_SPARSE 8 /* attnqat_fwd_infer_mx_sparse                        */
 
 /*
- * phi of Eq. 1 (Sec. 3.1) along d: for every 16 consecutive elements
+ * phi of Eq. 1 (Sec. 2.1) along d: for every 16 consecutive elements
  *   scale = RNE_E4M3(max|x| / 6)   (saturating at 448; a scale of 0 zeroes the block)
  *   code  = sign | RNE_E2M1(|x| / scale)   (ties to even, saturating at 6)
  * x       [B,H,L,d] bf16 (device, read)
@@ -138,8 +138,8 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The two backward ablations of Sec. 4.2 (Table 2, Exp. 7 and Exp. 8; the failure modes that
- * Sec. 3.3 explains), as switches of the same backward.  `ablation` is a bit set:
+ * The two backward ablations of Sec. 3.2 (Table 2, Exp. 7 and Exp. 8; the failure modes that
+ * Sec. 2.3 explains), as switches of the same backward.  `ablation` is a bit set:
  *   ATTNQAT_ABL_D_FROM_O       D = rowsum(dO o O) with the forward's low-precision output `o`
  *                              ([B,Hq,L,d] bf16, device, read) instead of O'; o_hp is ignored.
  *   ATTNQAT_ABL_P_UNQUANTIZED  dV += P^T dO with the recomputed fp32 P instead of
@@ -169,9 +169,9 @@ const char* attnqat_strerror(int code);
  * Test hook: attnqat_fwd_infer that also writes the dequantized P-tilde^F that
  * entered the O update, for the 128 query rows [row0, row0+128) of every head
  * (row0 a multiple of 128): p_dump [B,Hq,128,L] fp32 (device).  The caller
- * zeroes it: key tiles that no row of a 32-row group can see under the causal
- * mask are skipped and not written, nor are rows beyond L; masked keys inside
- * a visited tile get 0.
+ * zeroes it before the call (none of the three P hooks clears it): key tiles
+ * that no row of a 32-row group can see under the causal mask are skipped and
+ * not written, nor are rows beyond L; masked keys inside a visited tile get 0.
  */
 int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
@@ -179,14 +179,14 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The NVFP4 forward and backward with options that Sec. 4.2 studies inside QAT (SageAttention's heuristics):
- *   ATTNQAT_OPT_SMOOTH_K   K smoothing (Sec. 3.1): phi is applied to K minus its mean over the tokens, per
+ * The NVFP4 forward and backward with options that Sec. 3.2 studies inside QAT (SageAttention's heuristics):
+ *   ATTNQAT_OPT_SMOOTH_K   K smoothing (Sec. 2.1): phi is applied to K minus its mean over the tokens, per
  *                          (batch, kv head, channel).  S changes by a per-query constant that softmax ignores
  *                          (lse moves by q . mean(K) / sqrt(d)); the centred K quantizes better.  The mean is the
  *                          fp64 sum / L rounded to fp32, the subtraction an fp32 subtraction.  dK is the gradient
  *                          with respect to the centred K, which equals the gradient with respect to K because
- *                          rowsum(dS) = 0 when D comes from O' (Sec. 3.3).
- *   ATTNQAT_OPT_TWO_LEVEL_P  two-level quantization of P (Sec. 3.1): every row of a 64-key tile of P-tilde (forward)
+ *                          rowsum(dS) = 0 when D comes from O' (Sec. 2.3).
+ *   ATTNQAT_OPT_TWO_LEVEL_P  two-level quantization of P (Sec. 2.1): every row of a 64-key tile of P-tilde (forward)
  *                          and every row of the same aligned groups of 64 keys (key indices 64 g .. 64 g + 63) of the
  *                          recomputed P (backward) is divided by s1, the smallest power of two with
  *                          448 * 6 * s1 >= max(maximum of the row over those 64 keys, 2^-24), quantized in NVFP4
@@ -217,7 +217,7 @@ int attnqat_debug_fwd_p_opt(const void* q, const void* k, const void* v,
                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * MX variant of phi: the OCP microscaling FP4 format that Sec. 3.1 names beside NVFP4
+ * MX variant of phi: the OCP microscaling FP4 format that Sec. 2.1 names beside NVFP4
  * (E2M1 elements, 32 per block, one power-of-two E8M0 scale), with the power-of-two
  * counterpart of Eq. 1 as the scale rule:
  *   scale = the smallest 2^e, e >= -126, with 6 * 2^e >= max|x|   (byte e + 127; no element saturates)
@@ -246,7 +246,7 @@ int attnqat_fwd_infer_mx(const void* q, const void* k, const void* v,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Mixed recipe of Sec. 3.4 (FP4 for Q K^T, FP8 for P V) in MX terms: Q^F, K^F as in attnqat_fwd_infer_mx;
+ * Mixed recipe of Sec. 2.5 (FP4 for Q K^T, FP8 for P V) in MX terms: Q^F, K^F as in attnqat_fwd_infer_mx;
  * V^F and P-tilde^F in MXFP8: E4M3 elements (OCP: bias 7, subnormals, largest value 448), the same blocks
  * of 32 keys and E8M0 scales, scale = the smallest 2^e, e >= -126, with 448 * 2^e >= max|x| (nothing
  * saturates), element = sign | RNE_E4M3(|x| / scale).  P.V runs on the same scaled matrix instruction with
@@ -265,7 +265,7 @@ int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
 
 /*
  * Serving: an FP4 KV cache in pages, and Alg. 1 over it for sequences of different lengths (the variable-length /
- * paged setting that Sec. 6 leaves as future work; format and forward as attnqat_fwd_infer_mx).
+ * paged setting that Sec. 5 leaves as future work; format and forward as attnqat_fwd_infer_mx).
  *
  * The cache is caller-owned device memory of num_pages * attnqat_kv_cache_page_bytes(Hkv, d) bytes.  A page holds
  * 128 consecutive positions of ONE sequence for all Hkv heads, as MX codes and scale bytes in the order the matrix
@@ -273,9 +273,11 @@ int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
  * page and a page table is all a reader needs.
  *
  * attnqat_kv_cache_write_mx quantizes k, v [1,Hkv,L,d] bf16 (positions 0..L-1 of one sequence, L >= 1) into the pages
- * page_ids[0 .. ceil(L/128)-1] (device int32; each entry in [0, num_pages)); a last page that is not full is zero
- * padded.  A sequence that grows is written again from position 0 of its last page on (V scales cover 32 positions:
- * a block that gains positions must be re-quantized), i.e. k, v must start at a multiple of 128 of the sequence.
+ * page_ids[0 .. ceil(L/128)-1] (device int32) of a cache of num_pages pages; a last page that is not full is zero
+ * padded.  A page id outside [0, num_pages) is not written at all (the ids live on the device, so the call cannot
+ * refuse them; nothing outside the cache is touched).  A sequence that grows is written again from position 0 of its
+ * last page on (V scales cover 32 positions: a block that gains positions must be re-quantized), i.e. k, v must start
+ * at a multiple of 128 of the sequence.
  *
  * attnqat_fwd_infer_mx_paged: q [B,Hq,Lq,d] bf16 holds the LAST Lq positions of every sequence; sequence b has
  * kv_lens[b] >= Lq keys (device int32 [B]) in the pages page_table[b*max_pages + 0 ..] (device int32 [B,max_pages],
@@ -285,13 +287,13 @@ int attnqat_fwd_infer_mx_fp8pv(const void* q, const void* k, const void* v,
  */
 size_t attnqat_kv_cache_page_bytes(int Hkv, int d);
 int attnqat_kv_cache_write_mx(const void* k, const void* v, int Hkv, int L, int d, int dtype,
-                              void* cache, const int* page_ids, void* stream);
+                              void* cache, int num_pages, const int* page_ids, void* stream);
 int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
                                const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
                                void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Block-sparse attention (Sec. 6: the paper's datacenter inference kernel supports it): attnqat_fwd_infer_mx with a
+ * Block-sparse attention (Sec. 5: the paper's datacenter inference kernel supports it): attnqat_fwd_infer_mx with a
  * block mask.  block_mask [B,Hq,nb,nb] bytes (device, read), nb = ceil(L/128): a zero byte removes the block of 128
  * queries x 128 keys, i.e. those keys count as masked for those queries and their key tiles are not visited (the
  * order of the remaining tiles, and with it the running maximum that P-tilde is quantized against, is unchanged).
@@ -328,37 +330,27 @@ int attnqat_debug_fwd_p_mx(const void* q, const void* k, const void* v,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Measurement hook (the kernels of Alg. 1-3 are enqueued back to back by one call, so a
- * caller cannot bracket a single kernel with its own events).  While enabled, every entry
- * point records a HIP event on `stream` before its first kernel and after each kernel; the
- * events are created on first use and kept until the process ends (the one exception to
- * "nothing is allocated").  attnqat_profile_read() must follow a synchronisation of that
- * stream; it returns the number of kernels of the most recent call and fills ms[i] with
- * the time between consecutive events and names[i] (may be NULL) with a static label.
- * Not thread safe; off by default.
+ * Measurement hooks.  Their state is kept per stream: a setting made for one stream is seen only by entry points that are
+ * later called with that same stream argument (NULL, the default stream, is a stream of its own here), so calls on
+ * other streams and from other threads are not affected.  At most 16 streams can have a setting at a time
+ * (ATTNQAT_EINVAL beyond that); switching a setting off frees nothing but is always accepted.
+ *
+ * attnqat_profile_enable / attnqat_profile_read: the kernels of Alg. 1-3 are enqueued back to back by one call, so a
+ * caller cannot bracket a single kernel with its own events.  While enabled for `stream`, every entry point called on
+ * it records a HIP event before its first kernel and after each kernel; the events are created on first use and kept
+ * until the process ends (the one exception to "nothing is allocated").  attnqat_profile_read() must follow a
+ * synchronisation of that stream; it returns the number of kernels of the most recent call on it and fills ms[i] with the
+ * time between consecutive events and names[i] (may be NULL) with a static label.  Off by default.
+ *
+ * attnqat_debug_dkdv_tile_counts: the dK/dV pass of attnqat_bwd skips the work on P^F (quantizing it and
+ * dV += P^F^T dO) for every 32-query x 32-key tile whose P^F is all zero, which is exact; how often that happens depends
+ * on the data.  While `counts` (device, 2 x uint64, zeroed by the caller) is set for `stream`, every attnqat_bwd called
+ * on it adds to counts[0] the number of tiles the pass visited and to counts[1] the number with a non-zero P^F.
+ * NULL switches it off (the default).
  */
-int attnqat_profile_enable(int on);
-int attnqat_profile_read(int max_entries, float* ms, const char** names);
-
-/*
- * Measurement kernel, not part of the attention path: the 16-bit MFMA rate this part sustains on its own.  `blocks`
- * workgroups of 4 waves (2 workgroups per CU: 512 fill a 256-CU part once) each issue iters * 16 MFMAs
- * (32x32x16, f16: 32768 flop each) per wave on non-trivial register operands.  out (device, blocks * 256 floats) takes
- * the sums (ignored), clk (device, 2 * blocks uint64) per workgroup the shader clock cycles and the 100 MHz ticks its
- * first wave spent in the loop: their ratio is the clock held under the load.  The caller times the launch.  Only
- * enqueues.  blocks <= 65536, iters <= 2^22, else ATTNQAT_EINVAL.
- */
-int attnqat_debug_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, void* stream);
-
-/*
- * Measurement hook for the dK/dV pass of attnqat_bwd.  That pass skips the work on P^F
- * (quantizing it and dV += P^F^T dO) for every 32-query x 32-key tile whose P^F is all zero,
- * which is exact; how often that happens depends on the data.  While `counts` (device,
- * 2 x uint64, zeroed by the caller) is non-NULL, every later attnqat_bwd adds to counts[0]
- * the number of tiles the pass visited and to counts[1] the number with a non-zero P^F.
- * Pass NULL to switch it off (the default).  Not thread safe.
- */
-int attnqat_debug_dkdv_tile_counts(unsigned long long* counts);
+int attnqat_profile_enable(void* stream, int on);
+int attnqat_profile_read(void* stream, int max_entries, float* ms, const char** names);
+int attnqat_debug_dkdv_tile_counts(void* stream, unsigned long long* counts);
 
 #ifdef __cplusplus
 }

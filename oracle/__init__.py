@@ -236,10 +236,10 @@ def two_level_s1(rowmax: float) -> float:
 
 def smooth_k(k):
     """K minus its mean over the tokens, per (batch, kv head, channel): the K smoothing of SageAttention that
-    Sec. 3.1 describes and Sec. 4.2 switches on inside QAT.  S changes by a per-query constant, which softmax
+    Sec. 2.1 describes and Sec. 3.2 switches on inside QAT.  S changes by a per-query constant, which softmax
     ignores, and the centred K quantizes better.  Mean = fp64 sum / L rounded to fp32; the subtraction is an fp32
     subtraction.  Callers pass the result to fwd()/bwd() in place of K.  Gradient: dK = dK' - mean_j(dK'_j), and
-    sum_j dK'_j = sum_i rowsum(dS_i) Q^F_i = 0 because D comes from O' (Sec. 3.3), so dK = dK'."""
+    sum_j dK'_j = sum_i rowsum(dS_i) Q^F_i = 0 because D comes from O' (Sec. 2.3), so dK = dK'."""
     k = _f32(k)
     mean = (k.astype(np.float64).sum(axis=-2, keepdims=True) / k.shape[-2]).astype(np.float32)
     return k - mean

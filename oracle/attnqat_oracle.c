@@ -7,15 +7,15 @@
  *
  * Arithmetic: fp64 everywhere, except that the operand of every phi(P) is
  * first rounded to fp32 (the softmax is an fp32 quantity in the method,
- * Sec. 3.3 "High-precision O for the backward pass"), and phi's rounding
+ * Sec. 2.3 "High-precision O for the backward pass"), and phi's rounding
  * decisions are taken exactly on those fp32 values.
  *
  * What is implemented
- *   phi / phi^-1           Sec. 3.1 "NVFP4 and SageAttention3", Eq. 1 and Eq. 2
+ *   phi / phi^-1           Sec. 2.1 "NVFP4 and SageAttention3", Eq. 1 and Eq. 2
  *   forward (train+infer)  Alg. 2 "Attn-QAT Forward (Training)"; Alg. 1 is the
  *                          same recurrence without O' (Eq. 3 == Eq. 4)
  *   backward               Alg. 3 "Attn-QAT backward", with the two rules of
- *                          Sec. 3.3: P is re-quantized, D comes from O'
+ *                          Sec. 2.3: P is re-quantized, D comes from O'
  *
  * Readings of points the paper leaves open (all listed in the design notes):
  *   - the block scale is stored as E4M3 (OCP "fn": bias 7, subnormals, max
@@ -30,7 +30,7 @@
  *   - key tiles of Bk keys are visited in increasing order; the running max
  *     used for quantizing P-tilde is the max over all tiles seen so far.
  *
- * MX variant (the OCP microscaling format named in Sec. 3.1 next to NVFP4: E2M1
+ * MX variant (the OCP microscaling format named in Sec. 2.1 next to NVFP4: E2M1
  * elements, 32 per block, power-of-two E8M0 scale), same algorithms with
  *   - the block scale is the smallest power of two s with 6 s >= max|X| (the
  *     E8M0 counterpart of Eq. 1's s = max|X|/6: no element saturates), not below
@@ -190,7 +190,7 @@ int oracle_phi_mx(const float* x, long nrows, long n, uint8_t* packed, uint8_t* 
 }
 
 /* MXFP8 (E4M3 elements, 32 per block, E8M0 scale): the element format of the mixed recipe that keeps
- * FP4 for Q K^T and uses FP8 for P V (Sec. 3.4; scale_mode 3).  Same scale rule with E4M3's largest
+ * FP4 for Q K^T and uses FP8 for P V (Sec. 2.5; scale_mode 3).  Same scale rule with E4M3's largest
  * value in place of 6: the smallest power of two s >= 2^-126 with 448 s >= max|X|. */
 int oracle_e8m0_from_amax_fp8(double amax)
 {
@@ -252,7 +252,7 @@ int oracle_phi_mx8(const float* x, long nrows, long n, uint8_t* codes, uint8_t* 
 
 /* ------------------------------------------------- two-level quantization of P */
 
-/* SageAttention3's two-level scheme as Sec. 3.1 describes it and Sec. 4.2 switches on inside QAT
+/* SageAttention3's two-level scheme as Sec. 2.1 describes it and Sec. 3.2 switches on inside QAT
  * (scale_mode 4): every row of a P tile is first rescaled so that its maximum lands just below
  * 448 * 6 (the largest block scale times the largest element), then quantized as usual in NVFP4
  * blocks of 16.  Readings: a "row" is the 64 keys of one key tile (TWO_LEVEL_SPAN = B_k, the key
@@ -309,7 +309,7 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                     double* O, double* Op, double* Lse, float* Pdump,
                     const uint8_t* bmask, int mbq, int mbk)
 {
-    /* Block-sparse attention (the inference kernel of Sec. 3.4 supports it): bmask[B,Hq,ceil(L/mbq),ceil(L/mbk)],
+    /* Block-sparse attention (the datacenter inference kernel of Sec. 2.5 supports it, Sec. 5): bmask[B,Hq,ceil(L/mbq),ceil(L/mbk)],
      * a zero byte removes the whole block of mbq queries x mbk keys (mbk a multiple of Bk): its key tiles are not
      * visited.  A row with no key left gets O = 0 and L = -inf. */
     if (bmask && (mbq < 1 || mbk < Bk || mbk % Bk)) return -1;
@@ -472,7 +472,7 @@ static void bwd_block(const float* qrow, const float* dorow, double lse, double 
     for (int k = 0; k < pb; ++k) {
         if (k < nvis) {
             double dP = dot(dorow, vh + (k0 + k) * d, d);
-            dS[k] = P[k] * (dP - D) * rs;        /* fp32 P, not P^F (Sec. 3.3) */
+            dS[k] = P[k] * (dP - D) * rs;        /* fp32 P, not P^F (Sec. 2.3) */
         } else dS[k] = 0.0;
     }
 }

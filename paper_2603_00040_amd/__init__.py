@@ -41,9 +41,8 @@ _SIGNATURES = {
     "attnqat_debug_fwd_p_opt": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
                                      _vp, _sz, _vp]),
     "attnqat_kv_cache_page_bytes": (_sz, [_i, _i]),
-    "attnqat_kv_cache_write_mx": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "attnqat_kv_cache_write_mx": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _i, _vp, _vp]),
     "attnqat_fwd_infer_mx_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
-    "attnqat_debug_mfma_burn": (_i, [_i, _i, _vp, _vp, _vp]),
     "attnqat_fwd_infer_mx_sparse": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
@@ -55,9 +54,9 @@ _SIGNATURES = {
     "attnqat_strerror": (ctypes.c_char_p, [_i]),
     "attnqat_debug_fwd_p": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
                                  _vp, _sz, _vp]),
-    "attnqat_debug_dkdv_tile_counts": (_i, [_vp]),
-    "attnqat_profile_enable": (_i, [_i]),
-    "attnqat_profile_read": (_i, [_i, _vp, _vp]),
+    "attnqat_debug_dkdv_tile_counts": (_i, [_vp, _vp]),
+    "attnqat_profile_enable": (_i, [_vp, _i]),
+    "attnqat_profile_read": (_i, [_vp, _i, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -153,31 +152,11 @@ def attnqat_fwd_infer_mx_sparse(q, k, v, causal: bool, block_mask, workspace=Non
     return o, lse
 
 
-def attnqat_debug_mfma_burn(rounds: int = 4, iters: int = 40000):
-    """The 16-bit MFMA rate the part sustains on its own and the clock it holds meanwhile: returns (TFLOP/s, GHz).
-    rounds: how many times the launch fills the chip (2 workgroups of 4 waves per CU)."""
-    ncu = torch.cuda.get_device_properties(0).multi_processor_count
-    blocks = 2 * ncu * rounds
-    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
-    clk = torch.zeros(2 * blocks, dtype=torch.int64, device="cuda")
-    _check(lib().attnqat_debug_mfma_burn(blocks, max(1, iters // 8), _ptr(out), _ptr(clk), _stream()))     # warm-up
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    _check(lib().attnqat_debug_mfma_burn(blocks, iters, _ptr(out), _ptr(clk), _stream()))
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1)
-    c = clk.cpu().numpy().reshape(blocks, 2).astype("float64")
-    flops = blocks * 4.0 * iters * 16.0 * 32768.0
-    return flops / (ms * 1e-3) / 1e12, float(c[:, 0].sum() / c[:, 1].sum()) * 0.1
-
-
 def kv_cache_page_bytes(Hkv: int, d: int) -> int:
     return lib().attnqat_kv_cache_page_bytes(Hkv, d)
 
 
-def attnqat_kv_cache_write_mx(k, v, cache, page_ids):
+def attnqat_kv_cache_write_mx(k, v, cache, page_ids, num_pages=None):
     """Quantize one sequence's k, v [1,Hkv,L,d] bf16 into the pages ``page_ids`` (int32 CUDA tensor) of the FP4 KV
     ``cache`` (uint8 CUDA tensor of num_pages * kv_cache_page_bytes(Hkv, d) bytes)."""
     _dev_bf16(k, "k"); _dev_bf16(v, "v")
@@ -186,7 +165,9 @@ def attnqat_kv_cache_write_mx(k, v, cache, page_ids):
         raise AttnQatError("k and v must be [1,Hkv,L,d] of one sequence")
     if not (page_ids.is_cuda and page_ids.dtype == torch.int32 and page_ids.is_contiguous() and page_ids.numel() >= (L + 127) // 128):
         raise AttnQatError("page_ids must be a contiguous int32 CUDA tensor with ceil(L/128) entries")
-    _check(lib().attnqat_kv_cache_write_mx(_ptr(k), _ptr(v), Hkv, L, d, BF16, _ptr(cache), _ptr(page_ids), _stream()))
+    if num_pages is None:
+        num_pages = cache.numel() // kv_cache_page_bytes(Hkv, d)
+    _check(lib().attnqat_kv_cache_write_mx(_ptr(k), _ptr(v), Hkv, L, d, BF16, _ptr(cache), int(num_pages), _ptr(page_ids), _stream()))
 
 
 def attnqat_fwd_infer_mx_paged(q, cache, num_pages, page_table, kv_lens, Hkv, causal: bool, workspace=None, out=None):
@@ -225,7 +206,7 @@ def attnqat_debug_fwd_p_opt(q, k, v, causal: bool, row0: int, options: int):
 
 
 def attnqat_fwd_opt(q, k, v, causal: bool, options: int, train: bool = True, workspace=None, out=None):
-    """Alg. 2 (train) or Alg. 1 with the option bits of Sec. 4.2 (OPT_SMOOTH_K).  Returns (o, lse, o_hp or None)."""
+    """Alg. 2 (train) or Alg. 1 with the option bits of Sec. 3.2 (OPT_SMOOTH_K).  Returns (o, lse, o_hp or None)."""
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _dev_bf16(t, n)
     B, Hq, L, d = q.shape
@@ -394,7 +375,7 @@ ABL_D_FROM_O, ABL_P_UNQUANTIZED = 1, 2
 
 
 def attnqat_bwd_ablation(q, k, v, d_o, lse, o_hp, o, causal: bool, ablation: int, workspace=None, out=None):
-    """Alg. 3 with the ablations of Sec. 4.2 switched on by the bit set ``ablation``
+    """Alg. 3 with the ablations of Sec. 3.2 switched on by the bit set ``ablation``
     (ABL_D_FROM_O: D from the bf16 output ``o``; ABL_P_UNQUANTIZED: dV from the fp32 P).
     Returns (dq, dk, dv) bf16."""
     for t, n in ((q, "q"), (k, "k"), (v, "v"), (d_o, "d_o")):
@@ -438,19 +419,21 @@ def attnqat_debug_fwd_p(q, k, v, causal: bool, row0: int, _mx=False):
 
 
 def debug_dkdv_tile_counts(counts):
-    """counts: zeroed int64 CUDA tensor of 2 elements (tiles visited, tiles with non-zero P^F) or None."""
-    _check(lib().attnqat_debug_dkdv_tile_counts(_ptr(counts) if counts is not None else None))
+    """counts: zeroed int64 CUDA tensor of 2 elements (tiles visited, tiles with non-zero P^F) or None; applies to
+    attnqat_bwd calls on the current stream."""
+    _check(lib().attnqat_debug_dkdv_tile_counts(_stream(), _ptr(counts) if counts is not None else None))
 
 
 def profile_enable(on: bool):
-    _check(lib().attnqat_profile_enable(int(on)))
+    """Per-kernel timing of the calls made on the current stream."""
+    _check(lib().attnqat_profile_enable(_stream(), int(on)))
 
 
 def profile_read():
-    """[(kernel label, milliseconds)] of the most recent call; synchronise the stream first."""
+    """[(kernel label, milliseconds)] of the most recent call on the current stream; synchronise the stream first."""
     ms = (ctypes.c_float * 16)()
     names = (ctypes.c_char_p * 16)()
-    n = lib().attnqat_profile_read(16, ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(names, ctypes.c_void_p))
+    n = lib().attnqat_profile_read(_stream(), 16, ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(names, ctypes.c_void_p))
     if n < 0:
         _check(n)
     return [(names[i].decode(), float(ms[i])) for i in range(n)]

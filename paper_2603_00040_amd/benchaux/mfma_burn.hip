@@ -1,12 +1,11 @@
-// Measurement kernel, not part of the attention path: the rate at which this part sustains the 16-bit MFMA
+// Bench-only helper, built into its own library (libattnqat_benchaux.so): NOT part of the attention library or its ABI.
+// Measurement kernel: the rate at which this part sustains the 16-bit MFMA
 // (v_mfma_f32_32x32x16_f16) when nothing else runs, and the clock it holds while doing so.  The published peak
 // (2.5 PFLOP/s) is 1024 matrix pipes x 1024 flop per cycle x 2.4 GHz; under a matrix load the part lowers its clock,
 // so the rate that can be reached in practice is lower, and the attention kernels' figures are read against both.
 #include <hip/hip_runtime.h>
 
-#include "kernels.hpp"
-
-namespace aq {
+namespace {
 
 typedef _Float16 probe_half8 __attribute__((ext_vector_type(8)));
 typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
@@ -45,10 +44,15 @@ __global__ __launch_bounds__(256, 2) void mfma_burn_kernel(float* __restrict__ o
     if (threadIdx.x == 0) { clk[2 * blockIdx.x] = t1 - t0; clk[2 * blockIdx.x + 1] = r1 - r0; }
 }
 
-int launch_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, hipStream_t st)
-{
-    hipLaunchKernelGGL(mfma_burn_kernel, dim3((unsigned)blocks), dim3(256), 0, st, out, clk, iters);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
-}
+}  // namespace
 
-}  // namespace aq
+// `blocks` workgroups of 4 waves (2 workgroups per CU: 512 fill a 256-CU part once) each issue iters * 16 MFMAs
+// (32x32x16, f16: 32768 flop each) per wave.  out (device, blocks * 256 floats) takes the sums (ignored), clk (device,
+// 2 * blocks uint64) per workgroup the shader clock cycles and the 100 MHz ticks its first wave spent in the loop.
+// Only enqueues; the caller times the launch.  Returns 0, -1 for bad arguments, -5 if the launch failed.
+extern "C" int benchaux_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, void* stream)
+{
+    if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 22) || !out || !clk) return -1;
+    hipLaunchKernelGGL(mfma_burn_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, out, clk, iters);
+    return hipGetLastError() == hipSuccess ? 0 : -5;
+}

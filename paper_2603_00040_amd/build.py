@@ -10,7 +10,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattnqat.so")
-SOURCES = ["prep.hip", "fwd.hip", "bwd.hip", "mx.hip", "probe.hip", "api.hip"]
+SOURCES = ["prep.hip", "fwd.hip", "bwd.hip", "mx.hip", "api.hip"]
+# bench-only helper with its own library: measurement code stays out of the attention library and its ABI
+AUX_SRC = os.path.join(HERE, "benchaux", "mfma_burn.hip")
+AUX_LIB = os.path.join(HERE, "benchaux", "libattnqat_benchaux.so")
 # -packed-fp32-ops off: plain fp32 VALU code only (packed fp32 forms are not trusted here)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -45,6 +48,10 @@ def build(force: bool = False, verbose: bool = False, extra=()) -> str:
         objs = list(ex.map(compile_one, SOURCES))
     if force or _stale(LIB, objs):
         subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    if force or _stale(AUX_LIB, [AUX_SRC]):
+        r = subprocess.run(["hipcc", *FLAGS, "-shared", AUX_SRC, "-o", AUX_LIB], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {AUX_SRC}:\n{r.stderr}")
     return LIB
 
 

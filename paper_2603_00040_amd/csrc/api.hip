@@ -41,31 +41,68 @@ struct Carver {
     void* take(size_t bytes) { void* p = base ? base + off : nullptr; off += align_up(bytes); return p; }
 };
 
-// Optional per-kernel timing: HIP events recorded on the launch stream after every kernel.
-struct Prof {
-    bool on = false;
+// Measurement state, kept PER STREAM (a call only ever looks at the entry of the stream it enqueues on, so calls on
+// different streams, from different threads, do not see each other's settings): optional per-kernel timing with HIP
+// events recorded on the launch stream after every kernel, and the tile counters of the dK/dV pass.
+struct StreamDbg {
+    hipStream_t stream = nullptr;
+    bool used = false;
+    bool prof_on = false;
     bool created = false;
     int n = 0;
     hipEvent_t ev[16];
     const char* name[16];
-} g_prof;
+    unsigned long long* dkdv_counts = nullptr;
+};
+constexpr int kMaxDbgStreams = 16;
+StreamDbg g_dbg[kMaxDbgStreams];
+std::mutex g_dbg_mutex;
+std::atomic<int> g_dbg_active{0};          // entries with profiling on or a counter set: 0 = every call skips the table
+
+// The entry of a stream; with create, a free entry is taken for it.  Caller holds g_dbg_mutex.
+StreamDbg* dbg_entry(hipStream_t st, bool create)
+{
+    for (auto& e : g_dbg) if (e.used && e.stream == st) return &e;
+    if (!create) return nullptr;
+    for (auto& e : g_dbg) if (!e.used) { e.used = true; e.stream = st; return &e; }
+    return nullptr;
+}
+void dbg_recount()
+{
+    int n = 0;
+    for (auto& e : g_dbg) if (e.used && (e.prof_on || e.dkdv_counts)) ++n;
+    g_dbg_active.store(n, std::memory_order_release);
+}
 
 void prof_begin(hipStream_t st)
 {
-    if (!g_prof.on) return;
-    if (!g_prof.created) {
-        for (auto& e : g_prof.ev) if (hipEventCreate(&e) != hipSuccess) { g_prof.on = false; return; }
-        g_prof.created = true;
+    if (g_dbg_active.load(std::memory_order_acquire) == 0) return;
+    std::lock_guard<std::mutex> lock(g_dbg_mutex);
+    StreamDbg* e = dbg_entry(st, false);
+    if (!e || !e->prof_on) return;
+    if (!e->created) {
+        for (auto& v : e->ev) if (hipEventCreate(&v) != hipSuccess) { e->prof_on = false; dbg_recount(); return; }
+        e->created = true;
     }
-    g_prof.n = 0;
-    g_prof.name[0] = "begin";
-    (void)hipEventRecord(g_prof.ev[g_prof.n++], st);
+    e->n = 0;
+    e->name[0] = "begin";
+    (void)hipEventRecord(e->ev[e->n++], st);
 }
 void prof_mark(const char* name, hipStream_t st)
 {
-    if (!g_prof.on || g_prof.n >= 16) return;
-    g_prof.name[g_prof.n] = name;
-    (void)hipEventRecord(g_prof.ev[g_prof.n++], st);
+    if (g_dbg_active.load(std::memory_order_acquire) == 0) return;
+    std::lock_guard<std::mutex> lock(g_dbg_mutex);
+    StreamDbg* e = dbg_entry(st, false);
+    if (!e || !e->prof_on || e->n >= 16 || e->n == 0) return;
+    e->name[e->n] = name;
+    (void)hipEventRecord(e->ev[e->n++], st);
+}
+unsigned long long* dkdv_counts_of(hipStream_t st)
+{
+    if (g_dbg_active.load(std::memory_order_acquire) == 0) return nullptr;
+    std::lock_guard<std::mutex> lock(g_dbg_mutex);
+    StreamDbg* e = dbg_entry(st, false);
+    return e ? e->dkdv_counts : nullptr;
 }
 
 int check_dims(int B, int Hq, int Hkv, int L, int d, int dtype)
@@ -154,7 +191,7 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
     // Alg. 1 line "phi(Q), phi(K), phi(V)" / Alg. 2 line "Q^F, K^F, V^F"
     if (quant_copy(q, B * Hq, L, d, mx, 0, true, w.qh, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
     const float* kmean = nullptr;
-    if (options & ATTNQAT_OPT_SMOOTH_K) {          // K minus its token mean (Sec. 3.1), then phi
+    if (options & ATTNQAT_OPT_SMOOTH_K) {          // K minus its token mean (Sec. 2.1), then phi
         if (launch_colmean(k, B * Hkv, L, d, w.kpart, w.kmean, st)) return ATTNQAT_ELAUNCH;
         kmean = w.kmean;
     }
@@ -319,15 +356,15 @@ size_t attnqat_kv_cache_page_bytes(int Hkv, int d)
 }
 
 int attnqat_kv_cache_write_mx(const void* k, const void* v, int Hkv, int L, int d, int dtype,
-                              void* cache, const int* page_ids, void* stream)
+                              void* cache, int num_pages, const int* page_ids, void* stream)
 {
-    if (!k || !v || !cache || !page_ids) return ATTNQAT_EINVAL;
+    if (!k || !v || !cache || !page_ids || num_pages < 1) return ATTNQAT_EINVAL;
     int rc = check_dims(1, Hkv, Hkv, L, d, dtype);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
-    if (launch_mx_quant(k, Hkv, L, d, 0, 2, false, (unsigned char*)cache, nullptr, nullptr, st, page_ids)) return ATTNQAT_ELAUNCH;
-    if (launch_mx_quant(v, Hkv, L, d, 1, 2, false, (unsigned char*)cache, nullptr, nullptr, st, page_ids)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(k, Hkv, L, d, 0, 2, false, (unsigned char*)cache, nullptr, nullptr, st, page_ids, num_pages)) return ATTNQAT_ELAUNCH;
+    if (launch_mx_quant(v, Hkv, L, d, 1, 2, false, (unsigned char*)cache, nullptr, nullptr, st, page_ids, num_pages)) return ATTNQAT_ELAUNCH;
     prof_mark("kv_cache_write_mx", st);
     return ATTNQAT_OK;
 }
@@ -358,34 +395,37 @@ int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, in
     return ATTNQAT_OK;
 }
 
-static unsigned long long* g_dkdv_counts = nullptr;
-
-int attnqat_debug_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, void* stream)
+int attnqat_debug_dkdv_tile_counts(void* stream, unsigned long long* counts)
 {
-    if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 22) || !out || !clk) return ATTNQAT_EINVAL;
-    return launch_mfma_burn(blocks, iters, out, clk, (hipStream_t)stream) ? ATTNQAT_ELAUNCH : ATTNQAT_OK;
-}
-
-int attnqat_debug_dkdv_tile_counts(unsigned long long* counts)
-{
-    g_dkdv_counts = counts;
+    std::lock_guard<std::mutex> lock(g_dbg_mutex);
+    StreamDbg* e = dbg_entry((hipStream_t)stream, counts != nullptr);
+    if (!e) return counts ? ATTNQAT_EINVAL : ATTNQAT_OK;       // no free entry / nothing to switch off
+    e->dkdv_counts = counts;
+    dbg_recount();
     return ATTNQAT_OK;
 }
 
-int attnqat_profile_enable(int on)
+int attnqat_profile_enable(void* stream, int on)
 {
-    g_prof.on = on != 0;
-    g_prof.n = 0;
+    std::lock_guard<std::mutex> lock(g_dbg_mutex);
+    StreamDbg* e = dbg_entry((hipStream_t)stream, on != 0);
+    if (!e) return on ? ATTNQAT_EINVAL : ATTNQAT_OK;
+    e->prof_on = on != 0;
+    e->n = 0;
+    dbg_recount();
     return ATTNQAT_OK;
 }
 
-int attnqat_profile_read(int max_entries, float* ms, const char** names)
+int attnqat_profile_read(void* stream, int max_entries, float* ms, const char** names)
 {
     if (!ms || max_entries < 1) return ATTNQAT_EINVAL;
+    std::lock_guard<std::mutex> lock(g_dbg_mutex);
+    StreamDbg* e = dbg_entry((hipStream_t)stream, false);
+    if (!e) return 0;
     int n = 0;
-    for (int i = 1; i < g_prof.n && n < max_entries; ++i, ++n) {
-        if (hipEventElapsedTime(&ms[n], g_prof.ev[i - 1], g_prof.ev[i]) != hipSuccess) return ATTNQAT_ELAUNCH;
-        if (names) names[n] = g_prof.name[i];
+    for (int i = 1; i < e->n && n < max_entries; ++i, ++n) {
+        if (hipEventElapsedTime(&ms[n], e->ev[i - 1], e->ev[i]) != hipSuccess) return ATTNQAT_ELAUNCH;
+        if (names) names[n] = e->name[i];
     }
     return n;
 }
@@ -431,10 +471,6 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!p_dump || row0 < 0 || row0 % 128 != 0) return ATTNQAT_EINVAL;
-    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
-    if (rc) return rc;
-    if (hipMemsetAsync(p_dump, 0, (size_t)B * Hq * 128 * L * sizeof(float), (hipStream_t)stream) != hipSuccess)
-        return ATTNQAT_ELAUNCH;
     return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, false, o, lse, nullptr, row0, p_dump,
                       workspace, workspace_bytes, stream);
 }
@@ -511,7 +547,7 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
     if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv,
-                        g_dkdv_counts, p_quant, st))
+                        dkdv_counts_of(st), p_quant, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;

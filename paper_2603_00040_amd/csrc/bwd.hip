@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void bounds_kernel(const uint16_t* __restrict_
 {
     constexpr int TPR = D / 8, RPP = 256 / TPR;      // threads per row, rows per pass
     __shared__ float red[2][4];
-    const int head = blockIdx.y, chunk = blockIdx.x;
+    const int head = blockIdx.x / kBoundParts, chunk = blockIdx.x % kBoundParts;      // 1-D grid: no 65535 limit on the heads
     const bool is_v = head < NHkv;
     const int h = is_v ? head : head - NHkv;
     const uint16_t* src = (is_v ? Vb : dOb) + (size_t)h * Lp * D;
@@ -176,7 +176,7 @@ int launch_bounds(const void* vb, const void* dob, const float* rowstat, int BHk
                   float* part, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
-    dim3 grid(kBoundParts, BHkv + BHq);
+    dim3 grid((unsigned)kBoundParts * (unsigned)(BHkv + BHq));
     if (D == 128) hipLaunchKernelGGL(bounds_kernel<128>, grid, dim3(256), 0, st, (const uint16_t*)vb, (const uint16_t*)dob,
                                      (const float2*)rowstat, Lp, BHkv, BHq, part);
     else          hipLaunchKernelGGL(bounds_kernel<64>, grid, dim3(256), 0, st, (const uint16_t*)vb, (const uint16_t*)dob,
@@ -397,8 +397,8 @@ static int launch_dq_t(const void* qb, const void* kb, const void* vb, const voi
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DqSmem<D>);
     auto kern = bwd_dq_kernel<D, CAUSAL>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-        return -1;
+    static unsigned long long lds_set = 0;          // one per instantiation
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
@@ -764,7 +764,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 products(I0{}, I1{});
                 if (with_pf) products(I1{}, I2{});
             } else {
-                // Ablation (Sec. 4.2, "no fake quantization of P in the backward"): dV from the fp32 P itself, which enters
+                // Ablation (Sec. 3.2, "no fake quantization of P in the backward"): dV from the fp32 P itself, which enters
                 // its product in two passes as a bf16 hi + lo pair
                 products(I0{}, I1{});
 #pragma unroll
@@ -830,8 +830,9 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
               : p_quant == 3 ? bwd_dkdv_kernel<D, CAUSAL, false, 3>
               : tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true, 1> : bwd_dkdv_kernel<D, CAUSAL, false, 1>;
     if (p_quant != 1) tile_counts = nullptr;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-        return -1;
+    if (p_quant < 0 || p_quant > 3) return -1;
+    static unsigned long long lds_set[5] = {0, 0, 0, 0, 0};      // one per variant of this instantiation
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set[p_quant == 1 && tile_counts ? 4 : p_quant])) return -1;
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,

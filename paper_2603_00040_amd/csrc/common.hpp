@@ -1,5 +1,5 @@
 // Shared device helpers for the gfx950 Attn-QAT kernels: vector types, the
-// NVFP4 rounding primitives (Sec. 3.1, Eq. 1-2) and the MFMA operand layouts.
+// NVFP4 rounding primitives (Sec. 2.1, Eq. 1-2) and the MFMA operand layouts.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -227,6 +227,18 @@ __device__ inline void head_tile_of_block(int block, int nheads, int per_head, i
         head = block / per_head;
         tile = block % per_head;
     }
+}
+
+// Host side: raise a kernel's dynamic LDS limit once per kernel instantiation and device instead of on every launch.
+// `done` is a bit mask of devices (a static of the calling instantiation).  Returns false if the runtime refuses.
+inline bool ensure_dynamic_lds(const void* kernel, int bytes, unsigned long long& done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (__atomic_load_n(&done, __ATOMIC_ACQUIRE) & bit) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    __atomic_fetch_or(&done, bit, __ATOMIC_RELEASE);
+    return true;
 }
 
 }  // namespace aq

@@ -224,7 +224,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         // first tiles), so it lives on the cold path
         float inv1 = 1.0f;
         if constexpr (PQ == 2) {
-            // Two-level quantization of P-tilde (Sec. 3.1): the row of this tile is divided by s1, the smallest power
+            // Two-level quantization of P-tilde (Sec. 2.1): the row of this tile is divided by s1, the smallest power
             // of two with 2688 s1 >= max(row maximum, 2^-24), before the NVFP4 blocks.  The row maximum is exp2 of the
             // tile's largest score, the same instructions on the same inputs as that element's P-tilde.
             // O is kept in units of the current s1 (its products use P-tilde / s1, which fp16 holds exactly whatever
@@ -455,8 +455,8 @@ static int launch_t(const void* qh, const void* kh, const void* vt, int B, int H
     const int nqt = (Lp + 255) / 256;
     const size_t smem = sizeof(FwdSmem<D>);
     auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP, PQ>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)smem) != hipSuccess) return -1;
+    static unsigned long long lds_set = 0;          // one per instantiation
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * nqt)), dim3(512), smem, st,
                        (const half_t*)qh, (const half_t*)kh, (const half_t*)vt, (uint16_t*)o, lse, o_hp,

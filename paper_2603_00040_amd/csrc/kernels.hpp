@@ -58,8 +58,9 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
 // fp8: E4M3 elements instead of E2M1 (axis 1 only); with axis 0 and mode 2 it selects the record layout whose V part is FP8.
 // page_ids (mode 2, FP4 only; device int32, one entry per 128 positions): the records go into the pages of a KV cache
 // laid out [page][kv head][2 records] instead of one after another; BH then is the number of kv heads of ONE sequence.
+// Records whose page id lies outside [0, num_pages) are not written.
 int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
-                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids = nullptr);
+                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids = nullptr, int num_pages = 0);
 size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v);
 size_t mx_qops_bytes(int BHq, int L, int D);
 size_t mx_qsc_bytes(int BHq, int L);
@@ -78,9 +79,5 @@ int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, in
 // ([B*Hq*nb, nb] int32) and cnt ([B*Hq*nb] int32) are scratch that the call fills.
 int launch_fwd_mx_sparse(const void* qops, const void* qsc, const void* kv, int B, int Hq, int Hkv, int L, int D, bool causal,
                          const unsigned char* block_mask, int* list, int* cnt, void* o, float* lse, hipStream_t st);
-
-// Measurement only: `blocks` workgroups of 4 waves each run iters * 16 MFMAs (32x32x16, f16) per wave on register
-// operands; out [blocks * 256] floats, clk [2 * blocks] (shader cycles, 100 MHz ticks of wave 0 of every workgroup).
-int launch_mfma_burn(int blocks, int iters, float* out, unsigned long long* clk, hipStream_t st);
 
 }  // namespace aq

@@ -1,7 +1,7 @@
 // MX variant of the quantizer and of the inference forward (Alg. 1) on the scaled FP4 MFMA of gfx950.
 // (The MX training forward and backward are variants of the 16-bit kernels in fwd.hip and bwd.hip.)
 //
-// Format (the OCP microscaling FP4 that Sec. 3.1 names beside NVFP4): E2M1 elements in blocks of 32
+// Format (the OCP microscaling FP4 that Sec. 2.1 names beside NVFP4): E2M1 elements in blocks of 32
 // with one power-of-two E8M0 scale, the smallest 2^e (e >= -126) with 6 * 2^e >= max|X|: the
 // power-of-two counterpart of Eq. 1, no element saturates.  Q and K are blocked along d, P-tilde and
 // V along the keys, so both products of Alg. 1 contract over the blocked axis and run on
@@ -16,7 +16,7 @@
 //   S^T[key, query]  = K codes (A, from LDS) x Q codes (B, registers), contraction over d
 //   O^T[d, query]   += V^T codes (A, from LDS) x P-tilde codes (B, registers), contraction over keys
 //
-// Mixed recipe (Sec. 3.4: FP4 for Q K^T, FP8 for P V): the FP8PV variants keep Q and K in MXFP4 and hold V and
+// Mixed recipe (Sec. 2.5: FP4 for Q K^T, FP8 for P V): the FP8PV variants keep Q and K in MXFP4 and hold V and
 // P-tilde in MXFP8 (E4M3 elements, the same blocks of 32 keys and E8M0 scales; scale = smallest 2^e with
 // 448 * 2^e >= max|X|).  The P.V product then runs the same instruction with FP8 operands, whose layout differs
 // (measured): the 32 bytes of lane l are contraction indices 16 (l/32) .. + 15 and 32 + 16 (l/32) .. + 15, and the
@@ -80,8 +80,13 @@ __device__ inline float e4m3_value_of(uint32_t byte) {
 
 // Where the 64-key record `tile` of kv head `head` lives.  Contiguous: records of a head one after another.  Paged (a
 // KV cache): a page holds two records (128 keys) of every kv head, page_ids[tile / 2] names the page of this sequence.
-__device__ inline unsigned char* mx_record_of(unsigned char* base, const int* page_ids, int head, int nheads, int Lp, int tile, int rec_bytes) {
-    if (page_ids) return base + (((size_t)page_ids[tile >> 1] * nheads + head) * 2 + (tile & 1)) * rec_bytes;
+// A page id outside [0, num_pages) gives null: the writer leaves that record out instead of touching memory outside the cache.
+__device__ inline unsigned char* mx_record_of(unsigned char* base, const int* page_ids, int num_pages, int head, int nheads, int Lp, int tile, int rec_bytes) {
+    if (page_ids) {
+        const int page = page_ids[tile >> 1];
+        if (page < 0 || page >= num_pages) return nullptr;
+        return base + (((size_t)page * nheads + head) * 2 + (tile & 1)) * rec_bytes;
+    }
     return base + ((size_t)head * (Lp / 64) + tile) * rec_bytes;
 }
 
@@ -97,7 +102,7 @@ __device__ inline int mx_srow_of_key(int kk) { const int w = kk & 15; return 8 *
 template <int D, int MODE, bool FP8V = false /* MODE 2: records whose V part is FP8 */>
 __global__ __launch_bounds__(256) void mx_quant_d_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
-    uint16_t* __restrict__ xf, const int* __restrict__ page_ids)
+    uint16_t* __restrict__ xf, const int* __restrict__ page_ids, int num_pages)
 {
     constexpr int NB = D / 32, KS = D / 64;
     const int bh = blockIdx.y;
@@ -154,7 +159,8 @@ __global__ __launch_bounds__(256) void mx_quant_d_kernel(
         constexpr int REC = mx_rec_bytes(D, FP8V), KOPS = 2 * KS * 1024, VOPS = NB * (FP8V ? 2048 : 1024);
         const int tile = row >> 6, kk = row & 63, t = (kk >> 4) & 1;
         const int ks = blk >> 1, lane = (blk & 1) * 32 + mx_srow_of_key(kk);
-        unsigned char* rec = mx_record_of(codes, page_ids, bh, (int)gridDim.y, Lp, tile, REC);
+        unsigned char* rec = mx_record_of(codes, page_ids, num_pages, bh, (int)gridDim.y, Lp, tile, REC);
+        if (!rec) return;
         *reinterpret_cast<uint4v*>(rec + ((t * KS + ks) * 64 + lane) * 16) = c;
         rec[KOPS + VOPS + lane * 4 + t * KS + ks] = (unsigned char)byte;
         if (KS == 1 && t == 0) { rec[KOPS + VOPS + lane * 4 + 2] = 1; rec[KOPS + VOPS + lane * 4 + 3] = 1; }
@@ -169,7 +175,7 @@ __global__ __launch_bounds__(256) void mx_quant_d_kernel(
 template <int D, int MODE, bool FP8>
 __global__ __launch_bounds__(D) void mx_quant_l_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
-    uint16_t* __restrict__ xf, const int* __restrict__ page_ids)
+    uint16_t* __restrict__ xf, const int* __restrict__ page_ids, int num_pages)
 {
     constexpr int KS = D / 64, MT = D / 32;
     const int bh = blockIdx.y, kb = blockIdx.x, dd = threadIdx.x;
@@ -213,7 +219,8 @@ __global__ __launch_bounds__(D) void mx_quant_l_kernel(
     } else {
         constexpr int REC = mx_rec_bytes(D, FP8), KOPS = 2 * KS * 1024, VOPS = MT * (FP8 ? 2048 : 1024);
         const int tile = kb >> 1, lane = (kb & 1) * 32 + (dd & 31), mt = dd >> 5;
-        unsigned char* rec = mx_record_of(codes, page_ids, bh, (int)gridDim.y, Lp, tile, REC);
+        unsigned char* rec = mx_record_of(codes, page_ids, num_pages, bh, (int)gridDim.y, Lp, tile, REC);
+        if (!rec) return;
         if constexpr (FP8) {
             // FP8 operands: registers 0-3 of lane (row, h) are contraction indices 16 h .. + 15, registers 4-7 are
             // 32 + 16 h .. + 15, and the scale of indices 32 b .. + 31 is taken from lane (row, b): the two halves of
@@ -723,36 +730,36 @@ __global__ __launch_bounds__(256 * NP, NP == 1 ? 2 : 1) void fwd_mx_decode_kerne
 // ---------------------------------------------------------------------------------------------
 template <int D>
 static int quant_d(const void* x, int BH, int L, int mode, bool fp8v, unsigned char* codes, unsigned char* scales, void* xf,
-                   const int* page_ids, hipStream_t st)
+                   const int* page_ids, int num_pages, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int rows = mode == 0 ? L : Lp;
     const dim3 grid((unsigned)(((size_t)rows * (D / 32) + 255) / 256), (unsigned)BH);
-    if (mode == 0)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 0>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
-    else if (mode == 1) hipLaunchKernelGGL((mx_quant_d_kernel<D, 1>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
-    else if (fp8v)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 2, true>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
-    else                hipLaunchKernelGGL((mx_quant_d_kernel<D, 2>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
+    if (mode == 0)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 0>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
+    else if (mode == 1) hipLaunchKernelGGL((mx_quant_d_kernel<D, 1>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
+    else if (fp8v)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 2, true>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
+    else                hipLaunchKernelGGL((mx_quant_d_kernel<D, 2>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 template <int D, bool FP8>
 static int quant_l(const void* x, int BH, int L, int mode, unsigned char* codes, unsigned char* scales, void* xf,
-                   const int* page_ids, hipStream_t st)
+                   const int* page_ids, int num_pages, hipStream_t st)
 {
     const int Lp = round_up(L, kRowPad);
     const int nblk = mode == 0 ? (L + 31) / 32 : Lp / 32;
     const dim3 grid((unsigned)nblk, (unsigned)BH);
-    if (mode == 0) hipLaunchKernelGGL((mx_quant_l_kernel<D, 0, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
-    else           hipLaunchKernelGGL((mx_quant_l_kernel<D, 2, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids);
+    if (mode == 0) hipLaunchKernelGGL((mx_quant_l_kernel<D, 0, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
+    else           hipLaunchKernelGGL((mx_quant_l_kernel<D, 2, FP8>), grid, dim3(D), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
-                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids)
+                    unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids, int num_pages)
 {
     if (BH > 65535 || (axis == 0 && fp8 && mode != 2) || (page_ids && (mode != 2 || fp8))) return -1;
-    if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, st) : quant_d<64>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, st);
-    if (fp8) return D == 128 ? quant_l<128, true>(x, BH, L, mode, codes, scales, xf, page_ids, st) : quant_l<64, true>(x, BH, L, mode, codes, scales, xf, page_ids, st);
-    return D == 128 ? quant_l<128, false>(x, BH, L, mode, codes, scales, xf, page_ids, st) : quant_l<64, false>(x, BH, L, mode, codes, scales, xf, page_ids, st);
+    if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, num_pages, st) : quant_d<64>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, num_pages, st);
+    if (fp8) return D == 128 ? quant_l<128, true>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st) : quant_l<64, true>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st);
+    return D == 128 ? quant_l<128, false>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st) : quant_l<64, false>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st);
 }
 
 size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v) { return (size_t)BHkv * (round_up(L, kRowPad) / 64) * mx_rec_bytes(D, fp8v); }
@@ -768,8 +775,8 @@ static int launch_fwd_mx_t(const void* qops, const void* qsc, const void* kv, in
     const int Lp = round_up(L, kRowPad);
     const size_t smem = 3 * 2 * (size_t)mx_rec_bytes(D, FP8PV);
     auto kern = fwd_mx_kernel<D, CAUSAL, FP8PV, KVM>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)smem) != hipSuccess) return -1;
+    static unsigned long long lds_set = 0;          // one per instantiation
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
                        (const unsigned char*)qops, (const uint32_t*)qsc, (const unsigned char*)kv,
@@ -805,7 +812,8 @@ int launch_fwd_mx_paged(const void* qops, const void* qsc, const void* cache, in
         constexpr int NP = AQ_DECODE_NP; \
         constexpr size_t smem = (NP == 1 ? 4 : NP == 2 ? 3 : 2) * NP * 2 * (size_t)mx_rec_bytes(DD, false) + 4 * NP * 256; \
         auto kern = fwd_mx_decode_kernel<DD, CC, NP>; \
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) return -1; \
+        static unsigned long long lds_set = 0; \
+        if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1; \
         hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq)), dim3(256 * NP), smem, st, (const unsigned char*)qops, (const uint32_t*)qsc, \
                            (const unsigned char*)cache, (uint16_t*)o, lse, Lq, Hq, Hq / Hkv, c, page_table, kv_lens, max_pages, num_pages, lq_inner); \
         return hipGetLastError() == hipSuccess ? 0 : -1; } while (0)

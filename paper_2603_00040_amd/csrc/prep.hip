@@ -1,4 +1,4 @@
-// phi of Eq. 1 / Eq. 2 (Sec. 3.1) as a streaming kernel, plus the layout copies the
+// phi of Eq. 1 / Eq. 2 (Sec. 2.1) as a streaming kernel, plus the layout copies the
 // attention kernels read: the first line of Alg. 1 (phi(Q), phi(K), phi(V)) and of
 // Alg. 2 (Q^F, K^F, V^F).  HBM-bandwidth bound.
 //

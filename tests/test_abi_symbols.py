@@ -48,6 +48,8 @@ def test_argument_validation_happens_before_any_gpu_call():
     L = aq.lib()
     assert L.attnqat_fwd_infer_mx(None, None, None, 1, 2, 2, 64, 128, 0, 0, None, None, None, 0, None) == aq.EINVAL
     assert L.attnqat_fwd_infer_mx_sparse(None, None, None, 1, 2, 2, 64, 128, 0, 0, None, None, None, None, 0, None) == aq.EINVAL
-    assert L.attnqat_debug_mfma_burn(0, 1, None, None, None) == aq.EINVAL
-    assert L.attnqat_debug_mfma_burn(1, 1 << 23, None, None, None) == aq.EINVAL
+    assert L.attnqat_kv_cache_write_mx(None, None, 1, 1, 128, 0, None, 1, None, None) == aq.EINVAL
+    # the measurement hooks keep their state per stream: switching something off that was never on is accepted
+    assert L.attnqat_profile_enable(None, 0) == aq.OK and L.attnqat_debug_dkdv_tile_counts(None, None) == aq.OK
+    assert L.attnqat_profile_read(None, 0, None, None) == aq.EINVAL
 

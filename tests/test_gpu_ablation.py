@@ -1,4 +1,4 @@
-"""attnqat_bwd_ablation (Sec. 4.2, Exp. 7 and Exp. 8) against the oracle's switches."""
+"""attnqat_bwd_ablation (Sec. 3.2, Exp. 7 and Exp. 8) against the oracle's switches."""
 import numpy as np
 import pytest
 import torch

@@ -119,3 +119,15 @@ def test_paged_argument_errors_and_bad_page_ids():
     assert call(d=96) == aq.ESHAPE and call(hkv=3) == aq.ESHAPE and call(wsb=need - 1) == aq.EWORKSPACE
     assert aq.kv_cache_page_bytes(2, 128) == 2 * 2 * 8704 and aq.kv_cache_page_bytes(2, 96) == 0
     torch.cuda.synchronize()
+    # the writer: a page id outside the cache is left out (nothing outside the cache, and no other page, is touched)
+    x = random_inputs(1, Hkv, Hkv, 256, d, 9)
+    k, v = to_dev(x["k"]), to_dev(x["v"])
+    page = aq.kv_cache_page_bytes(Hkv, d)
+    guard = torch.full((4 * page,), 0xAB, dtype=torch.uint8, device="cuda")
+    cache2 = guard[page:3 * page]                       # two pages with a guard page on either side
+    aq.attnqat_kv_cache_write_mx(k, v, cache2, torch.tensor([1, 5], dtype=torch.int32, device="cuda"), num_pages=2)
+    aq.attnqat_kv_cache_write_mx(k, v, cache2, torch.tensor([-1, 2], dtype=torch.int32, device="cuda"), num_pages=2)
+    torch.cuda.synchronize()
+    g = guard.cpu()
+    assert bool((g[:2 * page] == 0xAB).all()) and bool((g[3 * page:] == 0xAB).all())      # guards and page 0 untouched
+    assert not bool((g[2 * page:3 * page] == 0xAB).all())                                   # page 1 was written

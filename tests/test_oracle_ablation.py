@@ -1,5 +1,5 @@
-"""The backward ablations of Sec. 4.2 (Exp. 7: D from the low-precision O; Exp. 8: no fake quantization
-of P in the backward) as the oracle computes them, pinned by what Sec. 3.3 says must and must not hold."""
+"""The backward ablations of Sec. 3.2 (Exp. 7: D from the low-precision O; Exp. 8: no fake quantization
+of P in the backward) as the oracle computes them, pinned by what Sec. 2.3 says must and must not hold."""
 import numpy as np
 
 import oracle

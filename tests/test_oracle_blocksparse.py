@@ -1,4 +1,4 @@
-"""Pins of the oracle's block-sparse forward (the inference kernel of Sec. 3.4 supports block-sparse attention):
+"""Pins of the oracle's block-sparse forward (the datacenter inference kernel of Sec. 2.5 supports block-sparse attention, Sec. 5):
 a zero byte of the block mask removes a block of queries x keys."""
 import numpy as np
 import pytest

@@ -66,7 +66,7 @@ def test_phi_on_matches_autograd_of_unrolled_ste_graph(causal, seed):
 
 
 def test_D_from_low_precision_O_breaks_the_identity():
-    """Eq. 7: rowsum(P o dP) = rowsum(dO o O') holds with O', not with O (Sec. 3.3)."""
+    """Eq. 7: rowsum(P o dP) = rowsum(dO o O') holds with O', not with O (Sec. 2.3)."""
     q, k, v = _rand(1, 2, 2, 64, 32, seed=24)
     do = _bf(np.random.default_rng(25).standard_normal(q.shape).astype(np.float32))
     f = oracle.fwd(q, k, v, False, 64)

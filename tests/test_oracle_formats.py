@@ -1,4 +1,4 @@
-"""Pins for the oracle's number formats and phi (Sec. 3.1, Eq. 1, Eq. 2).
+"""Pins for the oracle's number formats and phi (Sec. 2.1, Eq. 1, Eq. 2).
 
 Nothing here re-types the oracle's own formula: values come from the paper's
 stated constants (tests/golden), from torch's float8 decoder/caster, or from

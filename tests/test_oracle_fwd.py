@@ -44,7 +44,7 @@ def test_phi_off_is_textbook_attention_for_any_tile(causal, Bk):
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("Bk", [16, 64])
 def test_L_and_Oprime_ignore_P_quantization(causal, Bk):
-    """With phi on: L = logsumexp(Q^F K^F^T/sqrt d), O' = softmax(.) V^F (Alg. 2, Sec. 3.3)."""
+    """With phi on: L = logsumexp(Q^F K^F^T/sqrt d), O' = softmax(.) V^F (Alg. 2, Sec. 2.3)."""
     q, k, v = _rand(1, 4, 2, 150, 64, seed=11, outlier=True)
     r = oracle.fwd(q, k, v, causal, Bk)
     qf, kf, vf = (indep.fake_quant_np(a) for a in (q, k, v))

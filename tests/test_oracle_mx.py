@@ -1,6 +1,6 @@
 """Pins of the oracle's MX variant (E2M1 elements, blocks of 32, power-of-two E8M0 scale).
 
-The format is the OCP microscaling FP4 named in Sec. 3.1 beside NVFP4; the scale rule is
+The format is the OCP microscaling FP4 named in Sec. 2.1 beside NVFP4; the scale rule is
 the power-of-two counterpart of Eq. 1: the smallest 2^e with 6 * 2^e >= max|X|.  Pinned by
 closed forms, an exact-rational twin, a numpy twin whose exponent comes from frexp, exact
 invariants of a power-of-two scale, and for the forward the same pins as the NVFP4 path

@@ -1,4 +1,4 @@
-"""Pins of the oracle's K smoothing (Sec. 3.1: K minus its token mean; an option inside QAT in Sec. 4.2)."""
+"""Pins of the oracle's K smoothing (Sec. 2.1: K minus its token mean; an option inside QAT in Sec. 3.2)."""
 import numpy as np
 import pytest
 import torch

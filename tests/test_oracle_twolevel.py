@@ -1,5 +1,5 @@
-"""Pins of the oracle's two-level quantization of P (Sec. 3.1: each row of P is rescaled to [0, 448 * 6] before the
-NVFP4 blocks; an option inside QAT in Sec. 4.2).  Readings pinned here: rows are the 64 keys of a key tile, in the
+"""Pins of the oracle's two-level quantization of P (Sec. 2.1: each row of P is rescaled to [0, 448 * 6] before the
+NVFP4 blocks; an option inside QAT in Sec. 3.2).  Readings pinned here: rows are the 64 keys of a key tile, in the
 forward and (the same aligned groups of the recomputed P) in the backward; the row factor is the smallest power of two
 that keeps the row maximum below 448 * 6, with a floor of 2^-24 on that maximum."""
 import numpy as np
@@ -92,7 +92,7 @@ def test_backward_matches_autograd_of_unrolled_ste_graph(causal):
     ((p @ vf) * torch.from_numpy(do.astype(np.float64))).sum().backward()
     for name, a, b in (("dQ", g["dQ"], tq.grad.numpy()), ("dK", g["dK"], tk.grad.numpy()), ("dV", g["dV"], tv.grad.numpy())):
         assert np.allclose(a, b, rtol=0, atol=5e-6 * np.abs(b).max()), name
-    # only dV sees the quantizer of P (dS uses the fp32 P, Sec. 3.3)
+    # only dV sees the quantizer of P (dS uses the fp32 P, Sec. 2.3)
     g0 = oracle.bwd(q, k, v, do, f["L"], f["Op"], causal)
     assert np.array_equal(g0["dQ"], g["dQ"]) and np.array_equal(g0["dK"], g["dK"]) and not np.array_equal(g0["dV"], g["dV"])
 

@@ -5,7 +5,7 @@ is the one piece of code that both the CPU oracle's tests and the HIP path's
 tests/bench use.  Tensors come back as numpy ``uint16`` arrays holding bf16 bit
 patterns in ``[B, H, L, d]`` layout; ``bf16_bits_to_f32`` widens them exactly.
 
-Shapes follow the models the paper trains and serves (Sec. 4 "Experiments" and
+Shapes follow the models the paper trains and serves (Sec. 3 "Experiments" and
 the appendix "Detailed Training Setup"): Wan 2.1 1.3B at 480p (12 heads, d=128,
 21x30x52 latent tokens), Wan 2.1 14B at 720p (40 heads, 21x45x80 tokens), and
 GQA LLMs of the Qwen3-14B / Llama-3.1-70B class.  The paper's latents, prompts
@@ -87,7 +87,7 @@ CONFIGS = [
 ]
 
 
-# Not a benchmark configuration: the shape on which Sec. 4.4 quotes its peak forward throughput on B200
+# Not a benchmark configuration: the shape on which Sec. 3.4 quotes its peak forward throughput on B200
 # (b=1, s=32768, h=32, d=128), for a like-for-like context line of the inference forward.
 CONTEXT = [
     Workload("paper_peak_fwd_shape", 1, 32, 32, 32768, 128, False, 5, "normal", 1.0, passes="fwd_infer"),
