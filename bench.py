@@ -25,13 +25,188 @@ MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16 MFMA
 MFMA_FP4_PEAK_TFLOPS = 10100.0     # MI355X dense FP4 MFMA (the MX variant's products)
 MFMA_FP8_PEAK_TFLOPS = 5000.0      # MI355X dense FP8 MFMA (P V of the mixed recipe)
 KERNEL_GEMMS = {"fwd_train": 6.0, "fwd_infer": 4.0, "fwd_infer_mx": 4.0, "fwd_infer_mx_fp8pv": 4.0, "bwd_dq": 6.0, "bwd_dkdv": 8.0}   # bwd_dkdv: see main()
-# Bytes beyond L2 per launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel),
-# measured with rocprofv3 --pmc: profiles/hbm_traffic_dit720p_train.md
 # Sec. 3.4: peak forward throughput on B200 (NVFP4 QK + FP8 PV) at b=1, s=32768, h=32, d=128.  Another machine and
 # another recipe: context for the forward on that shape, not a target.
 PAPER_FWD_TFLOPS = {"paper_peak_fwd_shape": 2026.0}
-MEASURED_TRAFFIC_BYTES = {"dit720p_train": {"fwd_train": 20.0e9, "bwd_dq": 33.0e9, "bwd_dkdv": 707.4e9},
-                          "dit480p_infer": {"fwd_infer_mx": 1.116e9}}       # profiles/dit480p_infer_mx_fwd_kernels.txt
+# Bytes beyond L2 per launch of a kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy kernel).  NOT measured
+# by the run that prints them: they come from separate rocprofv3 --pmc runs of this same command, whose summaries (with
+# the commit they were taken at) are the files named here; a kernel that changed since then has no entry.
+def _traffic(gb, source):
+    return {"bytes": gb * 1e9, "source": source}
+
+
+TRAFFIC_BEYOND_L2 = {
+    "dit720p_train": {k: _traffic(v, "profiles/hbm_traffic_dit720p_train.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate runs; "
+                                     "kernels as of commit 63a7b2d)")
+                      for k, v in {"fwd_train": 20.0, "bwd_dq": 33.0, "bwd_dkdv": 707.4}.items()},
+    "dit480p_infer": {"fwd_infer_mx": _traffic(1.116, "profiles/dit480p_infer_mx_fwd_kernels.txt (kernels as of commit 63a7b2d)")},
+}
+
+
+HBM_PEAK_GBS = 8000.0              # MI355X HBM3E
+
+
+def hbm_kernel_report(kern_ms, w, train):
+    """Achieved GB/s of the bandwidth-bound kernels against the HBM peak.  Algorithmic bytes per element (d innermost):
+    a quantization pass reads 2 B (bf16) and writes 2 B (the fp16/bf16 workspace copy the attention kernels read);
+    delta reads dO (2 B) and O' (4 B) and, per row, L (4 B), and writes the {L, D} pair (8 B); bounds reads the V^F and dO
+    copies (2 B each) and the pairs."""
+    nq = float(w.B) * w.Hq * w.L * w.d
+    nkv = float(w.B) * w.Hkv * w.L * w.d
+    rows = float(w.B) * w.Hq * w.L
+    byts = {"prep_qkv": 4.0 * (nq + 2 * nkv), "prep_qkvdo": 4.0 * (2 * nq + 2 * nkv),
+            "delta": 6.0 * nq + 12.0 * rows, "bounds": 2.0 * (nq + nkv) + 8.0 * rows, "quantize": None}
+    out = {}
+    for name, b in byts.items():
+        if name in kern_ms and b:
+            gbs = b / (kern_ms[name] * 1e-3) / 1e9
+            out[name] = {"ms": round(kern_ms[name], 4), "algorithmic_bytes": int(b), "GB/s": round(gbs, 1),
+                         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    return out
+
+
+def measure(aq, torch, np, W, w, steps, warmup, fmt="nvfp4", opts=0, ablation=0, passes="auto", keep_inputs=False):
+    """Time `steps` passes of the whole path on workload w (inputs resident in HBM) and the kernels of one pass."""
+    fp8pv = fmt == "mx_fp8pv"
+    mx = fmt == "mx" or fp8pv
+    train = w.passes == "fwd+bwd" and passes == "auto" and not fp8pv
+    t0 = time.time()
+    x = W.make_inputs(w, with_do=train)
+    gen_s = time.time() - t0
+    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    do = dev(x["do"]) if train else None
+    B, Hq, Hkv, L, d = w.B, w.Hq, w.Hkv, w.L, w.d
+
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, L), dtype=torch.float32, device="cuda")
+    ohp = None
+    if train:
+        ohp = torch.empty((B, Hq, L, d), dtype=torch.float32, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws_bytes = max(aq.workspace_bytes(aq.WS_FWD_MX if mx else aq.WS_FWD, B, Hq, Hkv, L, d),
+                       aq.workspace_bytes(aq.WS_BWD_MX if mx else aq.WS_BWD, B, Hq, Hkv, L, d))
+    else:
+        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX_FP8PV if fp8pv else aq.WS_FWD_INFER_MX if mx else aq.WS_FWD,
+                                      B, Hq, Hkv, L, d)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def fwd():
+        if opts:
+            aq.attnqat_fwd_opt(q, k, v, w.causal, opts, train=train, workspace=ws, out=(o, lse, ohp if train else None))
+        elif train:
+            (aq.attnqat_fwd_mx if mx else aq.attnqat_fwd)(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
+        elif fp8pv:
+            aq.attnqat_fwd_infer_mx_fp8pv(q, k, v, w.causal, workspace=ws, out=(o, lse))
+        elif mx:
+            aq.attnqat_fwd_infer_mx(q, k, v, w.causal, workspace=ws, out=(o, lse))
+        else:
+            aq.attnqat_fwd_infer(q, k, v, w.causal, workspace=ws, out=(o, lse))
+
+    def bwd():
+        if opts:
+            aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, opts, workspace=ws, out=(dq, dk, dv))
+        elif ablation:
+            aq.attnqat_bwd_ablation(q, k, v, do, lse, ohp, o, w.causal, ablation, workspace=ws, out=(dq, dk, dv))
+        else:
+            (aq.attnqat_bwd_mx if mx else aq.attnqat_bwd)(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
+
+    def step():
+        fwd()
+        if train:
+            bwd()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    aq.profile_enable(True)
+    kern_ms = {}
+    nprof = max(1, min(steps, 3))
+    for _ in range(nprof):
+        fwd(); torch.cuda.synchronize()
+        for name, ms in aq.profile_read():
+            kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
+        if train:
+            bwd(); torch.cuda.synchronize()
+            for name, ms in aq.profile_read():
+                kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
+    if fmt == "nvfp4":
+        # the public quantizer on Q alone: 2 B read, 0.5 B of codes and 1/16 B of scale written per element
+        codes = torch.empty((B, Hq, L, d // 2), dtype=torch.uint8, device="cuda")
+        scales = torch.empty((B, Hq, L, d // 16), dtype=torch.uint8, device="cuda")
+        qms = 0.0
+        for _ in range(nprof + 1):
+            aq.lib().attnqat_quantize(q.data_ptr(), B, Hq, L, d, aq.BF16, codes.data_ptr(), scales.data_ptr(), None,
+                                      torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            qms = dict(aq.profile_read())["quantize"]          # the last (warm) call
+        del codes, scales
+    aq.profile_enable(False)
+    pf_frac = None
+    if train and (ablation & 2 or mx or opts & 2):
+        pf_frac = 1.0                    # the un-quantized P is never skipped; an MX P^F tile is zero only if P itself is
+    elif train:
+        # how many 32x32 tiles of the dK/dV pass had a non-zero P^F (the others skip the dV products, exactly)
+        counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+        aq.debug_dkdv_tile_counts(counts)
+        bwd(); torch.cuda.synchronize()
+        aq.debug_dkdv_tile_counts(None)
+        visited, nonzero = (int(c) for c in counts.cpu())
+        pf_frac = nonzero / max(visited, 1)
+
+    pair_flops = B * Hq * float(L) ** 2 * d * (0.5 if w.causal else 1.0)
+    step_flops = w.fwd_flops + (w.bwd_flops if train else 0.0)
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+    fwd_ms = sum(kern_ms.get(n, 0.0) for n in ("prep_qkv", "fwd_train", "fwd_infer", "prep_qkv_mx", "fwd_infer_mx", "fwd_infer_mx_fp8pv"))
+    peak = MFMA_FP4_PEAK_TFLOPS if (mx and not train) else MFMA_PEAK_TFLOPS
+    if fp8pv:      # half of the products at the FP4 rate, half at the FP8 rate
+        peak = round(2.0 / (1.0 / MFMA_FP4_PEAK_TFLOPS + 1.0 / MFMA_FP8_PEAK_TFLOPS), 1)
+    gemms = dict(KERNEL_GEMMS)
+    if pf_frac is not None:
+        gemms["bwd_dkdv"] = 6.0 + 2.0 * pf_frac
+    dom = max((n for n in kern_ms if n in gemms), key=lambda n: kern_ms[n])
+    achieved = gemms[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
+    traffic = TRAFFIC_BEYOND_L2.get(w.name, {}).get(dom) if (fmt == "nvfp4" and not opts and not ablation) or dom == "fwd_infer_mx" else None
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": traffic["bytes"] if traffic else None,
+                "traffic_source": traffic["source"] if traffic else None,
+                "kernel_ms": round(kern_ms[dom], 3),
+                "dkdv_tiles_with_nonzero_pf": None if pf_frac is None else round(pf_frac, 6),
+                "per_kernel": {n: {"ms": round(ms, 3),
+                                   "tflops": round(gemms[n] * pair_flops / (ms * 1e-3) / 1e12, 2)
+                                   if n in gemms else None} for n, ms in kern_ms.items()},
+                "hbm_bound_kernels": hbm_kernel_report(kern_ms, w, train)}
+    if fmt == "nvfp4":
+        qb = float(B) * Hq * L * d * (2.0 + 0.5 + 0.0625)
+        roofline["hbm_bound_kernels"]["quantize"] = {
+            "ms": round(qms, 4), "algorithmic_bytes": int(qb), "GB/s": round(qb / (qms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(qb / (qms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "what": "attnqat_quantize on Q: codes and scales out, no dequantized copy"}
+    res = {"train": train, "mx": mx, "fp8pv": fp8pv, "ms_per_step": ms_per_step, "value": value, "fwd_ms": fwd_ms, "peak": peak,
+           "achieved": achieved, "gen_s": gen_s, "roofline": roofline, "x": x if keep_inputs else None}
+    return res
+
+
+def per_config_entry(w, r):
+    """The short record of one benchmark configuration for the per_config array."""
+    rf = r["roofline"]
+    return {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "L": w.L, "d": w.d, "causal": w.causal,
+            "passes": w.passes if r["train"] else "fwd_infer", "ms_per_step": round(r["ms_per_step"], 3),
+            "fwd_tflops": round(w.fwd_flops / (r["fwd_ms"] * 1e-3) / 1e12, 2) if r["fwd_ms"] > 0 else None,
+            "fwd_bwd_tflops": round(r["value"], 2) if r["train"] else None,
+            "frac_of_mfma_peak_model_flops": round(r["value"] / r["peak"], 4),
+            "dominant_kernel": {"kernel": rf["kernel"], "ms": rf["kernel_ms"], "executed_tflops": rf["achieved"], "frac": rf["frac"]},
+            "dkdv_tiles_with_nonzero_pf": rf["dkdv_tiles_with_nonzero_pf"],
+            "kernel_ms": {n: v["ms"] for n, v in rf["per_kernel"].items()},
+            "hbm_bound_kernels": {n: {"GB/s": v["GB/s"], "frac_of_hbm_peak": v["frac_of_hbm_peak"]} for n, v in rf["hbm_bound_kernels"].items()}}
 
 
 def main():
@@ -65,6 +240,9 @@ def main():
                          "(context for the roofline fractions, which are quoted against the published 2.5 PFLOP/s)")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
+    ap.add_argument("--per-config", default="auto", choices=["auto", "on", "off"],
+                    help="also time the other four benchmark configurations for a few steps each and report them in per_config "
+                         "(auto: only in the default run, i.e. the headline workload in the paper's format without options)")
     args = ap.parse_args()
     if (args.smooth_k or args.two_level_p) and (args.format != "nvfp4" or args.ablation):
         print("bench.py: --smooth-k and --two-level-p go with --format nvfp4 and no ablation", file=sys.stderr)
@@ -96,109 +274,9 @@ def main():
     w = W.by_name(args.workload)
     if args.sparse_keep > 0:
         return bench_sparse(args, aq, torch, np, w, W)
-    fp8pv = args.format == "mx_fp8pv"
-    mx = args.format == "mx" or fp8pv
-    train = w.passes == "fwd+bwd" and args.passes == "auto" and not fp8pv
-    t0 = time.time()
-    x = W.make_inputs(w, with_do=train)
-    gen_s = time.time() - t0
-    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
-    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
-    do = dev(x["do"]) if train else None
-    B, Hq, Hkv, L, d = w.B, w.Hq, w.Hkv, w.L, w.d
 
-    o = torch.empty_like(q)
-    lse = torch.empty((B, Hq, L), dtype=torch.float32, device="cuda")
-    if train:
-        ohp = torch.empty((B, Hq, L, d), dtype=torch.float32, device="cuda")
-        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-        ws_bytes = max(aq.workspace_bytes(aq.WS_FWD_MX if mx else aq.WS_FWD, B, Hq, Hkv, L, d),
-                       aq.workspace_bytes(aq.WS_BWD_MX if mx else aq.WS_BWD, B, Hq, Hkv, L, d))
-    else:
-        ws_bytes = aq.workspace_bytes(aq.WS_FWD_INFER_MX_FP8PV if fp8pv else aq.WS_FWD_INFER_MX if mx else aq.WS_FWD,
-                                      B, Hq, Hkv, L, d)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-
-    def fwd():
-        if opts:
-            aq.attnqat_fwd_opt(q, k, v, w.causal, opts, train=train, workspace=ws, out=(o, lse, ohp if train else None))
-        elif train:
-            (aq.attnqat_fwd_mx if mx else aq.attnqat_fwd)(q, k, v, w.causal, workspace=ws, out=(o, lse, ohp))
-        elif fp8pv:
-            aq.attnqat_fwd_infer_mx_fp8pv(q, k, v, w.causal, workspace=ws, out=(o, lse))
-        elif mx:
-            aq.attnqat_fwd_infer_mx(q, k, v, w.causal, workspace=ws, out=(o, lse))
-        else:
-            aq.attnqat_fwd_infer(q, k, v, w.causal, workspace=ws, out=(o, lse))
-
-    def bwd():
-        if opts:
-            aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, w.causal, opts, workspace=ws, out=(dq, dk, dv))
-        elif args.ablation:
-            aq.attnqat_bwd_ablation(q, k, v, do, lse, ohp, o, w.causal, args.ablation, workspace=ws, out=(dq, dk, dv))
-        else:
-            (aq.attnqat_bwd_mx if mx else aq.attnqat_bwd)(q, k, v, do, lse, ohp, w.causal, workspace=ws, out=(dq, dk, dv))
-
-    def step():
-        fwd()
-        if train:
-            bwd()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-
-    # per-kernel durations: HIP events recorded by the library on the launch stream
-    aq.profile_enable(True)
-    kern_ms = {}
-    nprof = max(1, min(args.steps, 3))
-    for _ in range(nprof):
-        fwd(); torch.cuda.synchronize()
-        for name, ms in aq.profile_read():
-            kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
-        if train:
-            bwd(); torch.cuda.synchronize()
-            for name, ms in aq.profile_read():
-                kern_ms[name] = kern_ms.get(name, 0.0) + ms / nprof
-    aq.profile_enable(False)
-    pf_frac = None
-    if train and (args.ablation & 2 or mx or args.two_level_p):
-        pf_frac = 1.0                    # the un-quantized P is never skipped; an MX P^F tile is zero only if P itself is
-    elif train:
-        # how many 32x32 tiles of the dK/dV pass had a non-zero P^F (the others skip the dV products, exactly)
-        counts = torch.zeros(2, dtype=torch.int64, device="cuda")
-        aq.debug_dkdv_tile_counts(counts)
-        bwd(); torch.cuda.synchronize()
-        aq.debug_dkdv_tile_counts(None)
-        visited, nonzero = (int(c) for c in counts.cpu())
-        pf_frac = nonzero / max(visited, 1)
-
-    pair_flops = B * Hq * float(L) ** 2 * d * (0.5 if w.causal else 1.0)
-    step_flops = w.fwd_flops + (w.bwd_flops if train else 0.0)
-    value = step_flops / (ms_per_step * 1e-3) / 1e12
-    fwd_ms = sum(kern_ms.get(n, 0.0) for n in ("prep_qkv", "fwd_train", "fwd_infer", "prep_qkv_mx", "fwd_infer_mx", "fwd_infer_mx_fp8pv"))
-    peak = MFMA_FP4_PEAK_TFLOPS if (mx and not train) else MFMA_PEAK_TFLOPS
-    if fp8pv:      # half of the products at the FP4 rate, half at the FP8 rate
-        peak = round(2.0 / (1.0 / MFMA_FP4_PEAK_TFLOPS + 1.0 / MFMA_FP8_PEAK_TFLOPS), 1)
-    gemms = dict(KERNEL_GEMMS)
-    if pf_frac is not None:
-        gemms["bwd_dkdv"] = 6.0 + 2.0 * pf_frac
-    dom = max((n for n in kern_ms if n in gemms), key=lambda n: kern_ms[n])
-    achieved = gemms[dom] * pair_flops / (kern_ms[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom) if (not mx or dom == "fwd_infer_mx") else None,
-                "kernel_ms": round(kern_ms[dom], 3),
-                "dkdv_tiles_with_nonzero_pf": None if pf_frac is None else round(pf_frac, 6),
-                "per_kernel": {n: {"ms": round(ms, 3),
-                                   "tflops": round(gemms[n] * pair_flops / (ms * 1e-3) / 1e12, 2)
-                                   if n in gemms else None} for n, ms in kern_ms.items()}}
+    r = measure(aq, torch, np, W, w, args.steps, args.warmup, args.format, opts, args.ablation, args.passes, keep_inputs=True)
+    train, mx, fp8pv, value, peak, roofline = r["train"], r["mx"], r["fp8pv"], r["value"], r["peak"], r["roofline"]
 
     # what this machine sustains on MFMAs alone (boxes of one pool differ by 10 % in the clock they hold under load)
     try:
@@ -206,18 +284,33 @@ def main():
         sus_tf, sus_ghz = benchaux.mfma_sustained(rounds=2, iters=20000)
         if peak == MFMA_PEAK_TFLOPS:
             roofline["mfma_sustained_on_this_box"] = {"tflops": round(sus_tf, 1), "clock_ghz": round(sus_ghz, 3),
-                                                      "achieved_over_sustained": round(achieved / sus_tf, 4)}
+                                                      "achieved_over_sustained": round(r["achieved"] / sus_tf, 4)}
     except Exception as e:       # context only: never fails the run
         roofline["mfma_sustained_on_this_box"] = {"error": str(e)}
 
     cpu = None
     if args.cpu_seconds > 0:
-        cpu = cpu_baseline(w, x, train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k, args.two_level_p)
+        cpu = cpu_baseline(w, r["x"], train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k, args.two_level_p)
+    r["x"] = None
 
+    # the other benchmark configurations, a few steps each (the headline line above stays the one `value` refers to)
+    per_config = None
+    default_run = w.name == "dit720p_train" and args.format == "nvfp4" and not opts and not args.ablation and args.passes == "auto"
+    if args.per_config == "on" or (args.per_config == "auto" and default_run):
+        per_config = []
+        for wc in W.CONFIGS:
+            if wc.name == w.name:
+                per_config.append(per_config_entry(w, r))
+                continue
+            torch.cuda.empty_cache()
+            rc = measure(aq, torch, np, W, wc, 5 if wc.L <= 40000 else 2, 2 if wc.L <= 40000 else 1, args.format, opts, args.ablation, "auto")
+            per_config.append(per_config_entry(wc, rc))
+
+    B, Hq, Hkv, L, d = w.B, w.Hq, w.Hkv, w.L, w.d
     out = {
         "metric": "FP4-attention fwd+bwd TFLOPS (1 MI355X)" if train else "FP4-attention fwd TFLOPS (1 MI355X)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(r["ms_per_step"], 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": round(value / PAPER_FWD_TFLOPS[w.name], 4) if (w.name in PAPER_FWD_TFLOPS and not train) else None,
         "dtype": "fp4 Q K^T, fp8 (E4M3) P V MFMA operands with E8M0 block scales, fp32 accumulate and softmax" if fp8pv
                  else "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if (mx and not train)
@@ -226,12 +319,13 @@ def main():
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
                    "passes": w.passes if train else "fwd_infer", "block_k": aq.block_k(), "seed": w.seed,
                    "bwd_ablation": args.ablation, "format": args.format, "smooth_k": bool(args.smooth_k), "two_level_p": bool(args.two_level_p)},
-        "fwd_tflops": round(w.fwd_flops / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
-        "fwd_ms": round(fwd_ms, 3),
+        "fwd_tflops": round(w.fwd_flops / (r["fwd_ms"] * 1e-3) / 1e12, 2) if r["fwd_ms"] > 0 else None,
+        "fwd_ms": round(r["fwd_ms"], 3),
         "frac_of_mfma_peak_model_flops": round(value / peak, 4),
-        "input_gen_s": round(gen_s, 1),
+        "input_gen_s": round(r["gen_s"], 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "per_config": per_config,
     }
     print(json.dumps(out), flush=True)
 
@@ -349,8 +443,9 @@ def bench_sparse(args, aq, torch, np, w, W):
 
 
 def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False, two_level=False):
-    """Time the oracle (as it stands) on a bounded sample of the same workload: forward of
-    sampled query rows and, for training workloads, dQ of the same rows."""
+    """Time the oracle (as it stands) on a bounded sample of the same workload: the forward of sampled query rows and,
+    for training workloads, their dQ and their contributions to dK and dV over all keys (the whole of Alg. 3 for those
+    rows: 14 model FLOPs per row-key-d with the forward)."""
     import numpy as np
 
     import oracle
@@ -363,7 +458,7 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k
          for n in x}
     if smooth_k:
         f["k"] = oracle.smooth_k(f["k"])
-    per_row = (4.0 + (6.0 if train else 0.0)) * w.L * w.d * (0.5 if w.causal else 1.0)
+    per_row = (4.0 + (10.0 if train else 0.0)) * w.L * w.d * (0.5 if w.causal else 1.0)
 
     def run(n):
         rows = np.sort(rng.choice(w.L, size=min(n, w.L), replace=False)).astype(np.int64)
@@ -372,11 +467,12 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k
         r = oracle.fwd(f["q"], f["k"], f["v"], w.causal, block_k, scale_mode=sm, rows=rows)
         if train:
             oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal, scale_mode=sm)
+            oracle.bwd_rows_dkdv(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal, scale_mode=sm)
         return rows.size, time.perf_counter() - t0
 
     # two pilots separate the fixed cost (phi of the head's Q/K/V) from the cost per row
     n1, t1 = run(16)
-    n2, t2 = run(min(w.L, 1024))
+    n2, t2 = run(min(w.L, 512))
     per = max((t2 - t1) / max(n2 - n1, 1), 1e-5)
     fixed = max(t1 - per * n1, 0.0)
     n = int(max(48, min(w.L, (target_s - fixed) / per)))
@@ -384,7 +480,7 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k
     return {"value": round(n * per_row / t / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle",
             "sample": f"{n} query rows of head (0,0), all {w.L} keys: oracle forward"
-                      + (" + oracle dQ (model FLOPs 4+6 per row-key-d; the dK/dV products are not in the sample)"
+                      + (" + oracle dQ of those rows + their dK, dV contributions over all keys (model FLOPs 4+10 per row-key-d)"
                          if train else " (model FLOPs 4 per row-key-d)")
                       + f", {t:.1f} s, includes phi of that head's Q/K/V"}
 

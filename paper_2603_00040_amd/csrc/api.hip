@@ -541,8 +541,9 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
     if (launch_delta(d_o, o_acc, o_is_bf16, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
-    if (launch_bounds(w.vb, w.dob, w.rowstat, B * Hkv, B * Hq, L, d, w.bounds, st)) return ATTNQAT_ELAUNCH;
     prof_mark("delta", st);
+    if (launch_bounds(w.vb, w.dob, w.rowstat, B * Hkv, B * Hq, L, d, w.bounds, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("bounds", st);
     if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dq, st))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
