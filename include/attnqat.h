@@ -77,7 +77,8 @@ extern "C" {
  *         a code is sign<<3 | index into {0,.5,1,1.5,2,3,4,6}
  * scales  [B,H,L,d/16] E4M3 bytes (device, written)
  * xf      optional [B,H,L,d] bf16 (device, written): phi^-1(phi(x)) of Eq. 2; may be NULL
- * codes and scales may be NULL when only xf is wanted.
+ * codes and scales may be NULL when only xf is wanted.  Alignment (vector loads and stores): x and xf 16 bytes, codes 8,
+ * scales 4; otherwise ATTNQAT_EINVAL.
  */
 int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
                      uint8_t* codes, uint8_t* scales, void* xf, void* stream);

@@ -255,6 +255,7 @@ int attnqat_quantize(const void* x, int B, int H, int L, int d, int dtype,
                      uint8_t* codes, uint8_t* scales, void* xf, void* stream)
 {
     if (!x || (!codes && !scales && !xf)) return ATTNQAT_EINVAL;
+    if (((uintptr_t)x & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 3) || ((uintptr_t)xf & 15)) return ATTNQAT_EINVAL;
     int rc = check_dims(B, H, H, L, d, dtype);
     if (rc) return rc;
     prof_begin((hipStream_t)stream);

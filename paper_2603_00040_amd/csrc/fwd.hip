@@ -42,30 +42,27 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     extern __shared__ __align__(256) unsigned char smem_raw[];   // the XORs of address bits 5..7 commute with adding this base
     FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
 
+    // Work items: a tile of 256 query rows of one head.  Without a mask a workgroup takes one.  Under a causal mask tile qt
+    // visits 4 qt + 4 key tiles, so a workgroup takes a pair, tile nqt - 1 - p and then tile p: every workgroup then does
+    // the same amount of work (no tail of long tiles at the end of a head) and there are half as many workgroups, each of
+    // which costs the CU a fixed 20 - 30 us of start-up and wind-down that nothing overlaps at one workgroup per CU.
     const int nqt = (Lp + 255) / 256;
-    int bh, qt;
-    head_tile_of_block(blockIdx.x, gridDim.x / nqt, nqt, bh, qt);
-    if (CAUSAL) qt = nqt - 1 - qt;                       // longest rows first
+    const int per_head = CAUSAL ? (nqt + 1) / 2 : nqt;
+    int bh, qt0;
+    head_tile_of_block(blockIdx.x, gridDim.x / per_head, per_head, bh, qt0);
+    const int nitems = (CAUSAL && nqt - 1 - qt0 != qt0) ? 2 : 1;
     const int b = bh / Hq, h = bh % Hq;
     const int bhkv = b * (Hq / G) + h / G;
-    const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: LDS destinations and branches use it
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);        // scalar: LDS destinations and branches use it
     const bool late = wave >= 4;                         // the group that runs one phase behind
-    const int row0_w = qt * 256 + wave * 32;
-    const bool has_rows = row0_w < Lp;                   // false only in the last workgroup of a head
-    const int q_row = row0_w + ln;
-
-    // Q^F operand: this lane's query row, d-slots 16*ds + 8*hf .. +7
-    half8 qreg[DS];
-    {
-        const half_t* qp = Qh + ((size_t)bh * Lp + (has_rows ? q_row : 0)) * D + 8 * hf;
-#pragma unroll
-        for (int ds = 0; ds < DS; ++ds) qreg[ds] = *reinterpret_cast<const half8*>(qp + 16 * ds);
-    }
-
     const int nkt_all = (L + 63) / 64;
-    const int nkt = CAUSAL ? min(4 * qt + 4, nkt_all) : nkt_all;     // tiles this workgroup visits
-    const int wave_qmax = row0_w + 31;
+
+    for (int item = 0; item < nitems; ++item) {
+    // (the lane number is taken afresh for every item and made opaque: everything formed from it would otherwise be kept
+    //  in registers, or rather in scratch, across the key loop for the sake of the second item)
+    uint32_t lane_i = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(lane_i));
+    const int lane = (int)lane_i, ln = lane & 31, hf = lane >> 5;
 
     // Chunk c of row r sits at chunk c ^ key(r), so an operand's byte offset is (per-lane constant) XOR
     // (compile-time constant): K rows  k_rd ^ (ds << 5),  V^T rows  v_rd ^ (ks << 5); 32 more rows and
@@ -97,6 +94,21 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 #pragma unroll
         for (int i = 0; i < VLD; ++i) async_copy16(v_head + (size_t)jt * 64, v_ld[i], &sm.v[buf][512 * (wave * VLD + i)]);
     };
+
+    const int qt = CAUSAL ? (item == 0 ? nqt - 1 - qt0 : qt0) : qt0;
+    const int row0_w = qt * 256 + wave * 32;
+    const bool has_rows = row0_w < Lp;                   // false only in the last tile of a head
+    const int q_row = row0_w + ln;
+
+    // Q^F operand: this lane's query row, d-slots 16*ds + 8*hf .. +7
+    half8 qreg[DS];
+    {
+        const half_t* qp = Qh + ((size_t)bh * Lp + (has_rows ? q_row : 0)) * D + 8 * hf;
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) qreg[ds] = *reinterpret_cast<const half8*>(qp + 16 * ds);
+    }
+    const int nkt = CAUSAL ? min(4 * qt + 4, nkt_all) : nkt_all;     // key tiles this item visits
+    const int wave_qmax = row0_w + 31;
 
     floatx16 o[MB], op[TRAIN ? MB : 1];
 #pragma unroll
@@ -455,6 +467,9 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
             }
         if (hf == 0) lse[row] = m * (c * 0.6931471805599453f) + logf(l);   // m is in raw q.k units
     }
+    // (a second item may overwrite the tile buffers at once: every wave's last read of them lies before a barrier that
+    //  all eight waves have passed by now)
+    }
 }
 
 template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ>
@@ -463,12 +478,13 @@ static int launch_t(const void* qh, const void* kh, const void* vt, int B, int H
 {
     const int Lp = round_up(L, kRowPad);
     const int nqt = (Lp + 255) / 256;
+    const int per_head = CAUSAL ? (nqt + 1) / 2 : nqt;         // under a causal mask a workgroup takes a long and a short tile
     const size_t smem = sizeof(FwdSmem<D>);
     auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP, PQ>;
     static unsigned long long lds_set = 0;          // one per instantiation
     if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * nqt)), dim3(512), smem, st,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * per_head)), dim3(512), smem, st,
                        (const half_t*)qh, (const half_t*)kh, (const half_t*)vt, (uint16_t*)o, lse, o_hp,
                        L, Lp, Hq, Hq / Hkv, c, dump_row0, p_dump);
     return hipGetLastError() == hipSuccess ? 0 : -1;

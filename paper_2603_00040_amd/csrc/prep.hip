@@ -62,29 +62,60 @@ __global__ __launch_bounds__(256) void prep_kernel(
             for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
             const float s = block_scale_exact(amax);
             uint32_t clo = 0, chi = 0;
+            if (sub) {
+                // (inputs with 24 significant bits, after the K smoothing subtraction: IEEE division and the grid rounding
+                //  of common.hpp; the short cut below relies on bf16 inputs)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t sign = __float_as_uint(v[i]) >> 31;
-                float q = 0.0f;
-                if (s > 0.0f) {
-                    // IEEE division then RNE to the E2M1 grid == RNE of the real quotient:
-                    // |x| has 8 significant bits and s has 4, so a quotient that is not on
-                    // a rounding boundary is at least 2^-9 (relative) away from it.
-                    float r = fabsf(v[i]) / s;
-                    r = r < 6.0f ? r : 6.0f;
-                    q = rne_e2m1_grid(r);
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t sign = __float_as_uint(v[i]) >> 31;
+                    float q = 0.0f;
+                    if (s > 0.0f) {
+                        float r = fabsf(v[i]) / s;
+                        r = r < 6.0f ? r : 6.0f;
+                        q = rne_e2m1_grid(r);
+                    }
+                    const uint32_t code = (sign << 3) | e2m1_index_of(q);
+                    if (i < 8) clo |= code << (4 * i); else chi |= code << (4 * (i - 8));
+                    const float d = q * s;                   // exact: <= 6 significant bits
+                    xf[i] = sign ? -d : d;
                 }
-                const uint32_t code = (sign << 3) | e2m1_index_of(q);
-                if (i < 8) clo |= code << (4 * i); else chi |= code << (4 * (i - 8));
-                const float d = q * s;                   // exact: <= 6 significant bits
-                xf[i] = sign ? -d : d;
+            } else {
+                // RNE of the real quotient x / s without a division per element (ten vector instructions each, which bound
+                // this kernel).  |x| has 8 significant bits and s has 4, so a quotient that is not on a rounding boundary of
+                // the E2M1 grid is at least 2^-9 (relative) away from it, and one that is on a boundary (a tie) has at most
+                // 3 significant bits.  x * (1/s) with the approximate reciprocal is within 2^-21 of the quotient; rounding
+                // that product to 12 significant bits puts a tie back on its boundary exactly and moves nothing else across
+                // one (it moves a value by at most 2^-12).  The rounding to E2M1 itself (nearest, ties to even, saturating
+                // at 6, sign kept) then is the hardware conversion, two elements per instruction, which leaves the codes
+                // packed as the public layout wants them (element 2k in the low nibble of byte k); the conversion back gives
+                // the code values, times s: exact (<= 6 significant bits).
+                const float inv_s = s > 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;      // s = 0: every quotient 0, every code 0
+                typedef float float2v __attribute__((ext_vector_type(2)));
+                auto snap = [](float r) __attribute__((always_inline)) {
+                    return __uint_as_float((__float_as_uint(r) + 0x800u) & 0xFFFFF000u);
+                };
+#define AQ_PAIR(W, PR, SEL) W = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(W, snap(v[2 * (PR)] * inv_s), snap(v[2 * (PR) + 1] * inv_s), 1.0f, SEL)
+                AQ_PAIR(clo, 0, 0); AQ_PAIR(clo, 1, 1); AQ_PAIR(clo, 2, 2); AQ_PAIR(clo, 3, 3);
+                AQ_PAIR(chi, 4, 0); AQ_PAIR(chi, 5, 1); AQ_PAIR(chi, 6, 2); AQ_PAIR(chi, 7, 3);
+#undef AQ_PAIR
+#define AQ_BACK(W, PR, SEL) { const float2v cv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(W, 1.0f, SEL); xf[2 * (PR)] = cv[0] * s; xf[2 * (PR) + 1] = cv[1] * s; }
+                AQ_BACK(clo, 0, 0) AQ_BACK(clo, 1, 1) AQ_BACK(clo, 2, 2) AQ_BACK(clo, 3, 3)
+                AQ_BACK(chi, 4, 0) AQ_BACK(chi, 5, 1) AQ_BACK(chi, 6, 2) AQ_BACK(chi, 7, 3)
+#undef AQ_BACK
             }
             if (l < L) {
                 if (codes) {
                     uint2v c2; c2[0] = clo; c2[1] = chi;
                     *reinterpret_cast<uint2v*>(codes + ((size_t)bh * L + l) * (D / 2) + cb * 8) = c2;
                 }
-                if (scales) scales[((size_t)bh * L + l) * nb + cb] = (uint8_t)e4m3_byte_of(s);
+            }
+            if (scales) {
+                // four neighbouring blocks of a row (four neighbouring lanes: nb is 4 or 8 and a wave starts at a multiple
+                // of 64 blocks) write their scale bytes as one dword; rows beyond L take part in the exchange and write nothing
+                uint32_t sb = e4m3_byte_of(s);
+                sb |= (uint32_t)__shfl_down((int)sb, 1) << 8;
+                sb |= (uint32_t)__shfl_down((int)sb, 2) << 16;
+                if (l < L && (cb & 3) == 0) *reinterpret_cast<uint32_t*>(scales + ((size_t)bh * L + l) * nb + cb) = sb;
             }
         } else {
 #pragma unroll
