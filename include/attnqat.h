@@ -106,6 +106,26 @@ int attnqat_fwd_infer(const void* q, const void* k, const void* v,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The packed-input forms: Alg. 1 as the paper writes it takes the quantized tensors (Q-hat, s_Q, K-hat, s_K, V-hat, s_V),
+ * and its training setup (appendix "Detailed Training Setup") saves the fake-quantized Q, K, V of the forward for the
+ * backward.  *_codes [B,H,L,d/2] and *_scales [B,H,L,d/16] are what attnqat_quantize wrote for q, k, v (H = Hq for q,
+ * Hkv for k and v; codes 8-byte aligned); everything else is as in attnqat_fwd_infer / attnqat_bwd, including the
+ * workspace sizes (ATTNQAT_WS_FWD_INFER, ATTNQAT_WS_BWD), and the results are bit-identical to those calls on the
+ * tensors the codes came from: the quantization pass is replaced by a pass that only unpacks (0.56 instead of 2 bytes
+ * read per element).  dtype is the type of o, d_o, dq, dk, dv (ATTNQAT_BF16).
+ */
+int attnqat_fwd_infer_packed(const uint8_t* q_codes, const uint8_t* q_scales, const uint8_t* k_codes, const uint8_t* k_scales,
+                             const uint8_t* v_codes, const uint8_t* v_scales,
+                             int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                             void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+int attnqat_bwd_packed(const uint8_t* q_codes, const uint8_t* q_scales, const uint8_t* k_codes, const uint8_t* k_scales,
+                       const uint8_t* v_codes, const uint8_t* v_scales, const void* d_o,
+                       const float* lse, const float* o_hp,
+                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                       void* dq, void* dk, void* dv,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * attnqat_fwd_infer for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit for bit)
  * as attnqat_fwd_infer, without the workspace: the scratch memory is a fixed array of ATTNQAT_STATIC_SCRATCH_BYTES

@@ -27,6 +27,8 @@ _SIGNATURES = {
     "attnqat_fwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_infer": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_infer_static": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "attnqat_fwd_infer_packed": (_i, [_vp] * 6 + [_i] * 7 + [_vp, _vp, _vp, _sz, _vp]),
+    "attnqat_bwd_packed": (_i, [_vp] * 9 + [_i] * 7 + [_vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
                          _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_ablation": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
@@ -296,6 +298,41 @@ def attnqat_fwd_infer_static(q, k, v, causal: bool, out):
     _check(lib().attnqat_fwd_infer_static(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                           _ptr(o), _ptr(lse), _stream()))
     return o, lse
+
+
+def attnqat_fwd_infer_packed(qp, kp, vp, causal: bool, d: int, workspace=None, out=None):
+    """Alg. 1 on already quantized tensors: qp, kp, vp are (codes, scales) pairs from attnqat_quantize.
+    Returns (o bf16, lse fp32), bit-identical to attnqat_fwd_infer on the tensors the codes came from."""
+    (qc, qs), (kc, ks), (vc, vs) = qp, kp, vp
+    B, Hq, L, _ = qc.shape
+    Hkv = kc.shape[1]
+    if out is None:
+        o = torch.empty((B, Hq, L, d), dtype=torch.bfloat16, device=qc.device)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=qc.device)
+    else:
+        o, lse = out
+    ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_fwd_infer_packed(_ptr(qc), _ptr(qs), _ptr(kc), _ptr(ks), _ptr(vc), _ptr(vs), B, Hq, Hkv, L, d,
+                                          int(causal), BF16, _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
+    return o, lse
+
+
+def attnqat_bwd_packed(qp, kp, vp, d_o, lse, o_hp, causal: bool, workspace=None, out=None):
+    """Alg. 3 from the saved quantized Q, K, V of the forward ((codes, scales) pairs).  Returns (dq, dk, dv) bf16."""
+    (qc, qs), (kc, ks), (vc, vs) = qp, kp, vp
+    _dev_bf16(d_o, "d_o")
+    B, Hq, L, d = d_o.shape
+    Hkv = kc.shape[1]
+    if out is None:
+        dq = torch.empty_like(d_o)
+        dk = torch.empty((B, Hkv, L, d), dtype=torch.bfloat16, device=d_o.device)
+        dv = torch.empty_like(dk)
+    else:
+        dq, dk, dv = out
+    ws, nb = _workspace(WS_BWD, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_bwd_packed(_ptr(qc), _ptr(qs), _ptr(kc), _ptr(ks), _ptr(vc), _ptr(vs), _ptr(d_o), _ptr(lse), _ptr(o_hp),
+                                    B, Hq, Hkv, L, d, int(causal), BF16, _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), nb, _stream()))
+    return dq, dk, dv
 
 
 def attnqat_quantize_mx(x, axis: int = 0, want_codes=True, want_xf=True):

@@ -466,6 +466,29 @@ int attnqat_fwd_infer_static(const void* q, const void* k, const void* v,
                       ws, need, stream);
 }
 
+int attnqat_fwd_infer_packed(const uint8_t* q_codes, const uint8_t* q_scales, const uint8_t* k_codes, const uint8_t* k_scales,
+                             const uint8_t* v_codes, const uint8_t* v_scales,
+                             int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                             void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q_codes || !q_scales || !k_codes || !k_scales || !v_codes || !v_scales || !o || !lse) return ATTNQAT_EINVAL;
+    if (((uintptr_t)q_codes | (uintptr_t)k_codes | (uintptr_t)v_codes) & 7) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, L, d, dtype);
+    if (rc) return rc;
+    FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d);
+    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    // Alg. 1 takes the quantized tensors: only the layout copies remain to be made
+    if (launch_unpack(q_codes, q_scales, B * Hq, L, d, true, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_unpack(k_codes, k_scales, B * Hkv, L, d, true, w.kh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_unpack(v_codes, v_scales, B * Hkv, L, d, true, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("unpack_qkv", st);
+    if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, false, 0, o, lse, nullptr, 0, nullptr, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("fwd_infer", st);
+    return ATTNQAT_OK;
+}
+
 int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                         void* o, float* lse, int row0, float* p_dump,
@@ -514,12 +537,21 @@ int attnqat_debug_fwd_p_mx(const void* q, const void* k, const void* v,
                       workspace, workspace_bytes, stream);
 }
 
+// The six arrays of an already quantized Q, K, V (attnqat_quantize's layout); null = quantize q, k, v here.
+struct PackedQKV { const uint8_t *qc, *qs, *kc, *ks, *vc, *vs; };
+
 static int bwd_common(const void* q, const void* k, const void* v, const void* d_o,
                       const float* lse, const void* o_acc, bool o_is_bf16, int p_quant /* 0 none, 1 NVFP4, 2 MX; 3 (two-level) is set from the options */,
                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                       void* dq, void* dk, void* dv,
-                      void* workspace, size_t workspace_bytes, void* stream, int options = 0)
+                      void* workspace, size_t workspace_bytes, void* stream, int options = 0, const PackedQKV* packed = nullptr)
 {
+    if (packed) {
+        if (!packed->qc || !packed->qs || !packed->kc || !packed->ks || !packed->vc || !packed->vs) return ATTNQAT_EINVAL;
+        if (((uintptr_t)packed->qc | (uintptr_t)packed->kc | (uintptr_t)packed->vc) & 7) return ATTNQAT_EINVAL;
+        if (options || p_quant != 1) return ATTNQAT_EINVAL;
+        q = packed->qc; k = packed->kc; v = packed->vc;            // for the null checks below
+    }
     if (!q || !k || !v || !d_o || !lse || !o_acc || !dq || !dk || !dv) return ATTNQAT_EINVAL;
     if ((options & ~(ATTNQAT_OPT_SMOOTH_K | ATTNQAT_OPT_TWO_LEVEL_P)) || (options && p_quant != 1)) return ATTNQAT_EINVAL;
     if (options & ATTNQAT_OPT_TWO_LEVEL_P) p_quant = 3;
@@ -530,6 +562,13 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
     if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
+    if (packed) {
+        // the saved quantized tensors of the forward (appendix "Detailed Training Setup": the extra buffers for the
+        // fake-quantized Q, K, V): only the layout copies remain to be made
+        if (launch_unpack(packed->qc, packed->qs, B * Hq, L, d, true, w.qb, nullptr, st)) return ATTNQAT_ELAUNCH;
+        if (launch_unpack(packed->kc, packed->ks, B * Hkv, L, d, true, w.kb, nullptr, st)) return ATTNQAT_ELAUNCH;
+        if (launch_unpack(packed->vc, packed->vs, B * Hkv, L, d, false, w.vb, nullptr, st)) return ATTNQAT_ELAUNCH;
+    } else {
     // Q^F, K^F, V^F again (bit-identical to the forward's) and a zero-padded copy of dO
     if (quant_copy(q, B * Hq, L, d, mx, 0, true, w.qb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
     const float* kmean = nullptr;
@@ -539,6 +578,7 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
     }
     if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kb, nullptr, w.tmp, st, kmean)) return ATTNQAT_ELAUNCH;
     if (quant_copy(v, B * Hkv, L, d, mx, 1, false, w.vb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    }
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkvdo", st);
     if (launch_delta(d_o, o_acc, o_is_bf16, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
@@ -563,6 +603,18 @@ int attnqat_bwd(const void* q, const void* k, const void* v, const void* d_o,
 {
     return bwd_common(q, k, v, d_o, lse, o_hp, false, 1, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
                       workspace, workspace_bytes, stream);
+}
+
+int attnqat_bwd_packed(const uint8_t* q_codes, const uint8_t* q_scales, const uint8_t* k_codes, const uint8_t* k_scales,
+                       const uint8_t* v_codes, const uint8_t* v_scales, const void* d_o,
+                       const float* lse, const float* o_hp,
+                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                       void* dq, void* dk, void* dv,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    const PackedQKV pk{q_codes, q_scales, k_codes, k_scales, v_codes, v_scales};
+    return bwd_common(nullptr, nullptr, nullptr, d_o, lse, o_hp, false, 1, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
+                      workspace, workspace_bytes, stream, 0, &pk);
 }
 
 int attnqat_bwd_opt(const void* q, const void* k, const void* v, const void* d_o,

@@ -15,6 +15,10 @@ int launch_prep(const void* x, int BH, int L, int D, bool quant, bool out_f16,
                 uint8_t* codes, uint8_t* scales, void* xf_pub, void* xr, void* xt, hipStream_t st,
                 const float* sub = nullptr);
 
+// The layout copies xr / xt (as launch_prep writes them) from an already quantized tensor: codes [BH, L, D/2] and E4M3
+// scale bytes [BH, L, D/16] in the layout attnqat_quantize produces.
+int launch_unpack(const uint8_t* codes, const uint8_t* scales, int BH, int L, int D, bool out_f16, void* xr, void* xt, hipStream_t st);
+
 // Token mean of every channel of x [BH, L, D] bf16 -> mean [BH, D] fp32 (fp64 sums in a fixed order).
 // scratch: colmean_scratch_bytes() bytes.
 size_t colmean_scratch_bytes(int BH, int D);

@@ -17,12 +17,16 @@ namespace aq {
 // 16-byte run of the transposed operand.
 __host__ __device__ inline int perm16(int p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
 
-template <bool QUANT, bool OUT_F16>
+// PACKED (with QUANT = false): the input is not x but an already quantized tensor, codes [BH, L, D/2] and E4M3 scale bytes
+// [BH, L, D/16] in the public layout of attnqat_quantize (read through `codes` and `scales`); the kernel writes the
+// dequantized layout copies, the same values the quantizing variant writes for the tensor those codes came from.
+template <bool QUANT, bool OUT_F16, bool PACKED = false>
 __global__ __launch_bounds__(256) void prep_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, int D,
     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint16_t* __restrict__ xf_pub,
     uint16_t* __restrict__ xr, uint16_t* __restrict__ xt, const float* __restrict__ sub)
 {
+    static_assert(!(QUANT && PACKED), "a packed input is already quantized");
     __shared__ uint16_t tile[64][128 + 2];
     const int bh = blockIdx.y;
     const int l0 = blockIdx.x * 64;
@@ -33,7 +37,21 @@ __global__ __launch_bounds__(256) void prep_kernel(
         const int row = blk / nb, cb = blk % nb;
         const int l = l0 + row;
         float v[16];
-        if (l < L) {
+        if (PACKED) {
+            if (l < L) {
+                typedef float float2v __attribute__((ext_vector_type(2)));
+                const uint2v cw = *reinterpret_cast<const uint2v*>(codes + ((size_t)bh * L + l) * (D / 2) + cb * 8);
+                // E4M3 byte -> value: the hardware conversion (OCP E4M3, subnormals kept), byte 0 of the operand
+                const float sv = __builtin_amdgcn_cvt_scalef32_f32_fp8((uint32_t)scales[((size_t)bh * L + l) * nb + cb], 1.0f, 0);
+#define AQ_BACK(W, PR, SEL) { const float2v cv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(W, 1.0f, SEL); v[2 * (PR)] = cv[0] * sv; v[2 * (PR) + 1] = cv[1] * sv; }
+                AQ_BACK(cw[0], 0, 0) AQ_BACK(cw[0], 1, 1) AQ_BACK(cw[0], 2, 2) AQ_BACK(cw[0], 3, 3)
+                AQ_BACK(cw[1], 4, 0) AQ_BACK(cw[1], 5, 1) AQ_BACK(cw[1], 6, 2) AQ_BACK(cw[1], 7, 3)
+#undef AQ_BACK
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = 0.0f;
+            }
+        } else if (l < L) {
             const uint4v* src = reinterpret_cast<const uint4v*>(x + in_base + (size_t)l * D + cb * 16);
             uint4v a = src[0], b = src[1];
 #pragma unroll
@@ -221,6 +239,17 @@ static int launch_prep_t(const void* x, int BH, int L, int D, uint8_t* codes, ui
     hipLaunchKernelGGL((prep_kernel<QUANT, OUT_F16>), grid, dim3(256), 0, st,
                        (const uint16_t*)x, L, Lp, D, codes, scales, (uint16_t*)xf_pub,
                        (uint16_t*)xr, (uint16_t*)xt, sub);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_unpack(const uint8_t* codes, const uint8_t* scales, int BH, int L, int D, bool out_f16, void* xr, void* xt, hipStream_t st)
+{
+    const int Lp = round_up(L, kRowPad);
+    dim3 grid(Lp / 64, BH);
+    if (out_f16) hipLaunchKernelGGL((prep_kernel<false, true, true>), grid, dim3(256), 0, st, (const uint16_t*)nullptr, L, Lp, D,
+                                    const_cast<uint8_t*>(codes), const_cast<uint8_t*>(scales), (uint16_t*)nullptr, (uint16_t*)xr, (uint16_t*)xt, (const float*)nullptr);
+    else         hipLaunchKernelGGL((prep_kernel<false, false, true>), grid, dim3(256), 0, st, (const uint16_t*)nullptr, L, Lp, D,
+                                    const_cast<uint8_t*>(codes), const_cast<uint8_t*>(scales), (uint16_t*)nullptr, (uint16_t*)xr, (uint16_t*)xt, (const float*)nullptr);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
