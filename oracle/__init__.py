@@ -250,6 +250,7 @@ def smooth_k(k):
 MX = 2      # scale_mode of the MX format: E2M1 blocks of 32 with E8M0 scales, V and P blocked along the keys
 TWO_LEVEL_P = 4  # NVFP4 with SageAttention3's two-level quantization of P (row factor, then blocks of 16); Bk = 64
 MX_FP8PV = 3    # mixed recipe: Q, K as in MX (FP4), V and P in MXFP8 (E4M3 elements, same blocks and scale format)
+BF16_PV = 5     # mixed recipe of Sec. 2.5: Q, K in NVFP4, P-tilde rounded to bf16, V left in bf16 (inference only)
 
 
 def _prep_qkv(q, k, v, quant_qkv, scale_mode):
@@ -258,6 +259,8 @@ def _prep_qkv(q, k, v, quant_qkv, scale_mode):
         q, k, v = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx(v, axis=-2)
     elif quant_qkv and scale_mode == MX_FP8PV:
         q, k, v = fake_quant_mx(q), fake_quant_mx(k), fake_quant_mx8(v, axis=-2)
+    elif quant_qkv and scale_mode == BF16_PV:
+        q, k = fake_quant(q), fake_quant(k)
     elif quant_qkv:    # Alg. 2 first line: Q^F, K^F, V^F (the two-level option only concerns P)
         sm = 0 if scale_mode == TWO_LEVEL_P else scale_mode
         q, k, v = fake_quant(q, sm), fake_quant(k, sm), fake_quant(v, sm)

@@ -284,6 +284,44 @@ static void phi_two_level(const double* P, int n, double* Pf)
     for (int k = 0; k < n; ++k) Pf[k] = s1 * Pf2[k];
 }
 
+/* ---------------------------------------------------- formats of P-tilde in the P V product */
+
+/* x (an fp32 value) rounded to bf16, nearest, ties to even: the "BF16" of the mixed recipes of Sec. 2.5
+ * ("Bypassing the softmax bottleneck": NVFP4 Q K^T with BF16 or FP8 P V). */
+static double bf16_rne(double x)
+{
+    float f = (float)x; uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* The format P-tilde takes before P V, chosen by scale_mode:
+ *   0, 1  NVFP4 blocks of 16 keys (1: with the un-rounded fp32 scale of Eq. 1, diagnostics)
+ *   2     MX FP4 blocks of 32 keys          3  MXFP8 blocks of 32 keys (mixed recipe FP4 Q K^T / FP8 P V)
+ *   4     NVFP4 after the two-level row factor (the row is the whole tile: Bk = 64)
+ *   5     bf16 (mixed recipe NVFP4 Q K^T / BF16 P V: P-tilde is not block-quantized at all) */
+enum { PF_NVFP4 = 0, PF_MX = 1, PF_MXFP8 = 2, PF_TWO_LEVEL = 3, PF_BF16 = 4 };
+static int p_format_of(int scale_mode)
+{
+    return scale_mode == 2 ? PF_MX : scale_mode == 3 ? PF_MXFP8 : scale_mode == 4 ? PF_TWO_LEVEL : scale_mode == 5 ? PF_BF16 : PF_NVFP4;
+}
+
+/* phi^-1(phi(.)) of one tile row of P-tilde: Pt[0..nk) are the visible keys, Pt[nk..Bk) are masked (0). */
+static void quantize_p_row(int pf, int scale_mode, const double* Pt, int nk, int Bk, double* Pf)
+{
+    const int pb = (pf == PF_MX || pf == PF_MXFP8) ? 32 : 16;
+    if (pf == PF_TWO_LEVEL) { phi_two_level(Pt, Bk, Pf); return; }
+    if (pf == PF_BF16) { for (int k = 0; k < nk; ++k) Pf[k] = bf16_rne(Pt[k]); return; }
+    for (int k = 0; k < nk; k += pb) {
+        if (pf == PF_MXFP8)   phi_mx8_block(Pt + k, pb, NULL, NULL, Pf + k);
+        else if (pf == PF_MX) phi_mx_block(Pt + k, pb, NULL, NULL, Pf + k);
+        else                  phi_block(Pt + k, pb, scale_mode, NULL, NULL, NULL, Pf + k);
+    }
+}
+
 /* ------------------------------------------------------------------ forward */
 
 static double dot(const float* a, const float* b, int d)
@@ -304,7 +342,7 @@ static double dot(const float* a, const float* b, int d)
  */
 static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                     int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
-                    int quant_p, int scale_mode, int mx,
+                    int quant_p, int scale_mode,
                     long nrows, const long* rows,
                     double* O, double* Op, double* Lse, float* Pdump,
                     const uint8_t* bmask, int mbq, int mbk)
@@ -314,9 +352,10 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
      * visited.  A row with no key left gets O = 0 and L = -inf. */
     if (bmask && (mbq < 1 || mbk < Bk || mbk % Bk)) return -1;
     const long nqb = bmask ? (L + mbq - 1) / mbq : 0, nkb = bmask ? (L + mbk - 1) / mbk : 0;
-    const int pb = (mx == 1 || mx == 2) ? 32 : 16;               /* keys per P block */
+    const int pf = p_format_of(scale_mode);
+    const int pb = (pf == PF_MX || pf == PF_MXFP8) ? 32 : 16;    /* keys per P block */
     if (!qf || !kf || !vf || Hq % Hkv || Bk < pb || Bk % pb || d < 1) return -1;
-    if (mx == 3 && Bk != TWO_LEVEL_SPAN) return -1;
+    if (pf == PF_TWO_LEVEL && Bk != TWO_LEVEL_SPAN) return -1;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     if (!rows) nrows = (long)B * Hq * L;
@@ -359,17 +398,8 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
                     rowsum += Pt[k];
                 }
                 for (int k = nk; k < Bk; ++k) Pt[k] = 0.0;      /* masked keys */
-                if (quant_p && mx == 3) {
-                    phi_two_level(Pt, Bk, Pf);                  /* the whole tile row, masked keys are 0 */
-                } else if (quant_p) {
-                    for (int k = 0; k < nk; k += pb) {
-                        if (mx == 2) phi_mx8_block(Pt + k, pb, NULL, NULL, Pf + k);
-                        else if (mx) phi_mx_block(Pt + k, pb, NULL, NULL, Pf + k);
-                        else    phi_block(Pt + k, pb, scale_mode, NULL, NULL, NULL, Pf + k);
-                    }
-                } else {
-                    for (int k = 0; k < nk; ++k) Pf[k] = Pt[k];
-                }
+                if (quant_p) quantize_p_row(pf, scale_mode, Pt, nk, Bk, Pf);
+                else for (int k = 0; k < nk; ++k) Pf[k] = Pt[k];
                 l = alpha * l + rowsum;                          /* un-quantized P-tilde */
                 m = mnew;
                 for (int c = 0; c < d; ++c) { o[c] *= alpha; op[c] *= alpha; }
@@ -397,7 +427,9 @@ static int fwd_rows_impl(const float* qf, const float* kf, const float* vf,
 /* scale_mode 2: the MX format (qf, kf, vf are then the MX fake-quantized tensors, V blocked along
  * the keys, and P-tilde is quantized in MX blocks of 32 keys).  scale_mode 3: the same with MXFP8
  * (E4M3 elements) for P-tilde (and, in the caller's vf, for V).  scale_mode 4: NVFP4 with the
- * two-level quantization of P-tilde (Bk must be 64). */
+ * two-level quantization of P-tilde (Bk must be 64).  scale_mode 5: P-tilde in bf16 (and, in the
+ * caller's vf, V left as it is): NVFP4 Q K^T with BF16 P V.  Modes 3 and 5 are inference recipes: the
+ * backward entry points refuse them. */
 int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
                     int B, int Hq, int Hkv, long L, int d, int causal, int Bk,
                     int quant_p, int scale_mode,
@@ -405,7 +437,6 @@ int oracle_fwd_rows(const float* qf, const float* kf, const float* vf,
                     double* O, double* Op, double* Lse, float* Pdump)
 {
     return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode,
-                         scale_mode == 2 ? 1 : scale_mode == 3 ? 2 : scale_mode == 4 ? 3 : 0,
                          nrows, rows, O, Op, Lse, Pdump, NULL, 0, 0);
 }
 
@@ -418,7 +449,6 @@ int oracle_fwd_rows_masked(const float* qf, const float* kf, const float* vf,
                            const uint8_t* bmask, int mbq, int mbk)
 {
     return fwd_rows_impl(qf, kf, vf, B, Hq, Hkv, L, d, causal, Bk, quant_p, scale_mode,
-                         scale_mode == 2 ? 1 : scale_mode == 3 ? 2 : scale_mode == 4 ? 3 : 0,
                          nrows, rows, O, Op, Lse, Pdump, bmask, mbq, mbk);
 }
 
@@ -494,7 +524,7 @@ int oracle_bwd(const float* qf, const float* kf, const float* vf, const float* d
                double* dQ, double* dK, double* dV)
 {
     if (!qf || !kf || !vf || !dO || !Lse || !Op || Hq % Hkv) return -1;
-    if (scale_mode == 3) return -3;
+    if (scale_mode == 3 || scale_mode == 5) return -3;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     const int pb = pb_of(scale_mode);
@@ -543,7 +573,7 @@ int oracle_bwd_dq_rows(const float* qf, const float* kf, const float* vf, const 
                        const double* Lse_rows, const double* Op_rows, double* dQ_rows)
 {
     if (!rows || Hq % Hkv) return -1;
-    if (scale_mode == 3) return -3;
+    if (scale_mode == 3 || scale_mode == 5) return -3;
     (void)B;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
@@ -583,7 +613,7 @@ int oracle_bwd_dkdv_keys(const float* qf, const float* kf, const float* vf, cons
                          double* dK_keys, double* dV_keys, float* Pf_dump)
 {
     if (!keys || Hq % Hkv || b < 0 || b >= B || hk < 0 || hk >= Hkv) return -1;
-    if (scale_mode == 3) return -3;
+    if (scale_mode == 3 || scale_mode == 5) return -3;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     const int pb = pb_of(scale_mode);
@@ -637,7 +667,7 @@ int oracle_bwd_rows_dkdv(const float* qf, const float* kf, const float* vf, cons
                          double* dK, double* dV)
 {
     if (!rows || Hq % Hkv) return -1;
-    if (scale_mode == 3) return -3;
+    if (scale_mode == 3 || scale_mode == 5) return -3;
     const int G = Hq / Hkv;
     const double rs = 1.0 / sqrt((double)d);
     const int pb = pb_of(scale_mode);
