@@ -69,7 +69,7 @@ def measure(aq, torch, np, W, w, steps, warmup, fmt="nvfp4", opts=0, ablation=0,
     """Time `steps` passes of the whole path on workload w (inputs resident in HBM) and the kernels of one pass."""
     fp8pv = fmt == "mx_fp8pv"
     mx = fmt == "mx" or fp8pv
-    train = w.passes == "fwd+bwd" and passes == "auto" and not fp8pv
+    train = w.passes == "fwd+bwd" and passes == "auto" and not fp8pv and not (opts & 4)
     t0 = time.time()
     x = W.make_inputs(w, with_do=train)
     gen_s = time.time() - t0
@@ -256,6 +256,8 @@ def main():
                     help="K smoothing option of Sec. 3.2 (nvfp4 format only): phi on K minus its token mean")
     ap.add_argument("--two-level-p", action="store_true",
                     help="two-level quantization of P, the other option of Sec. 3.2 (nvfp4 format only)")
+    ap.add_argument("--bf16-pv", action="store_true",
+                    help="the mixed recipe of Sec. 2.5 (nvfp4 format only): NVFP4 Q K^T, P-tilde and V in bf16; inference forward only")
     ap.add_argument("--paged-lq", type=int, default=0,
                     help="serving mode (not a benchmark configuration): the MX forward over a paged FP4 KV cache with this many "
                          "query positions per sequence (1 = a decode step) for 32 sequences of 4k-16k keys, 32 query / 8 kv heads")
@@ -271,10 +273,13 @@ def main():
                     help="also time the other four benchmark configurations for a few steps each and report them in per_config "
                          "(auto: only in the default run, i.e. the headline workload in the paper's format without options)")
     args = ap.parse_args()
-    if (args.smooth_k or args.two_level_p) and (args.format != "nvfp4" or args.ablation):
-        print("bench.py: --smooth-k and --two-level-p go with --format nvfp4 and no ablation", file=sys.stderr)
+    if (args.smooth_k or args.two_level_p or args.bf16_pv) and (args.format != "nvfp4" or args.ablation):
+        print("bench.py: --smooth-k, --two-level-p and --bf16-pv go with --format nvfp4 and no ablation", file=sys.stderr)
         sys.exit(2)
-    opts = (1 if args.smooth_k else 0) | (2 if args.two_level_p else 0)
+    if args.bf16_pv and args.two_level_p:
+        print("bench.py: --bf16-pv leaves P-tilde un-blocked; it does not go with --two-level-p", file=sys.stderr)
+        sys.exit(2)
+    opts = (1 if args.smooth_k else 0) | (2 if args.two_level_p else 0) | (4 if args.bf16_pv else 0)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(heads shard across GPUs without communication, see DESIGN.md)", file=sys.stderr)
@@ -317,7 +322,7 @@ def main():
 
     cpu = None
     if args.cpu_seconds > 0:
-        cpu = cpu_baseline(w, r["x"], train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k, args.two_level_p)
+        cpu = cpu_baseline(w, r["x"], train, args.cpu_seconds, aq.block_k(), mx, fp8pv, args.smooth_k, args.two_level_p, args.bf16_pv)
     r["x"] = None
 
     # the other benchmark configurations, a few steps each (the headline line above stays the one `value` refers to)
@@ -340,12 +345,14 @@ def main():
         "ms_per_step": round(r["ms_per_step"], 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": round(value / PAPER_FWD_TFLOPS[w.name], 4) if (w.name in PAPER_FWD_TFLOPS and not train) else None,
         "dtype": "fp4 Q K^T, fp8 (E4M3) P V MFMA operands with E8M0 block scales, fp32 accumulate and softmax" if fp8pv
+                 else "f16 MFMA on exact NVFP4 values for Q K^T, bf16 MFMA for P V, fp32 accumulate and softmax" if args.bf16_pv
                  else "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax" if (mx and not train)
                  else "f16/bf16 MFMA operands (exact %s values), fp32 accumulate and softmax" % ("MXFP4" if mx else "NVFP4"),
         "data": "synthetic",
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "d": d, "causal": w.causal,
                    "passes": w.passes if train else "fwd_infer", "block_k": aq.block_k(), "seed": w.seed,
-                   "bwd_ablation": args.ablation, "format": args.format, "smooth_k": bool(args.smooth_k), "two_level_p": bool(args.two_level_p)},
+                   "bwd_ablation": args.ablation, "format": args.format, "smooth_k": bool(args.smooth_k), "two_level_p": bool(args.two_level_p),
+                   "bf16_pv": bool(args.bf16_pv)},
         "fwd_tflops": round(w.fwd_flops / (r["fwd_ms"] * 1e-3) / 1e12, 2) if r["fwd_ms"] > 0 else None,
         "fwd_ms": round(r["fwd_ms"], 3),
         "frac_of_mfma_peak_model_flops": round(value / peak, 4),
@@ -469,7 +476,7 @@ def bench_sparse(args, aq, torch, np, w, W):
         "cpu_baseline": None}), flush=True)
 
 
-def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False, two_level=False):
+def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k=False, two_level=False, bf16pv=False):
     """Time the oracle (as it stands) on a bounded sample of the same workload: the forward of sampled query rows and,
     for training workloads, their dQ and their contributions to dK and dV over all keys (the whole of Alg. 3 for those
     rows: 14 model FLOPs per row-key-d with the forward)."""
@@ -490,7 +497,7 @@ def cpu_baseline(w, x, train, target_s, block_k, mx=False, fp8pv=False, smooth_k
     def run(n):
         rows = np.sort(rng.choice(w.L, size=min(n, w.L), replace=False)).astype(np.int64)
         t0 = time.perf_counter()
-        sm = oracle.MX_FP8PV if fp8pv else oracle.MX if mx else oracle.TWO_LEVEL_P if two_level else 0
+        sm = oracle.MX_FP8PV if fp8pv else oracle.MX if mx else oracle.TWO_LEVEL_P if two_level else oracle.BF16_PV if bf16pv else 0
         r = oracle.fwd(f["q"], f["k"], f["v"], w.causal, block_k, scale_mode=sm, rows=rows)
         if train:
             oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], rows, r["L"], r["Op"], w.causal, scale_mode=sm)

@@ -214,6 +214,12 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
  *                          blocks of 16 and multiplied back, so that blocks far below the row maximum of the whole
  *                          sequence keep their values instead of under-flowing the E4M3 scale.  Masked keys and keys
  *                          beyond L count as 0.  Only P^F changes (O, dV).
+ *   ATTNQAT_OPT_BF16_PV    the mixed recipe that Sec. 2.5 proposes against the cost of quantizing P in the kernel:
+ *                          S = Q^F K^F^T on NVFP4 operands as everywhere, but P-tilde is only rounded to bf16 (nearest
+ *                          even) and V is used as given (bf16, not quantized), so the P V product is a bf16 product with
+ *                          fp32 accumulation.  m, l and lse are untouched.  Inference forward only (o_hp must be NULL;
+ *                          attnqat_bwd_opt refuses the bit); not together with ATTNQAT_OPT_TWO_LEVEL_P (P has no blocks
+ *                          here): ATTNQAT_EINVAL.  attnqat_fwd_infer_bf16pv is attnqat_fwd_opt with this bit alone.
  * attnqat_fwd_opt: o_hp != NULL selects the training forward (Alg. 2), NULL the inference forward (Alg. 1).
  * attnqat_bwd_opt must be given the same options as the forward whose lse and o_hp it consumes.
  * options = 0 is attnqat_fwd / attnqat_fwd_infer / attnqat_bwd; unknown bits: ATTNQAT_EINVAL.
@@ -221,6 +227,7 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
  */
 #define ATTNQAT_OPT_SMOOTH_K        1
 #define ATTNQAT_OPT_TWO_LEVEL_P     2
+#define ATTNQAT_OPT_BF16_PV         4
 int attnqat_fwd_opt(const void* q, const void* k, const void* v,
                     int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
                     void* o, float* lse, float* o_hp,
@@ -230,6 +237,10 @@ int attnqat_bwd_opt(const void* q, const void* k, const void* v, const void* d_o
                     int B, int Hq, int Hkv, int L, int d, int causal, int dtype, int options,
                     void* dq, void* dk, void* dv,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+int attnqat_fwd_infer_bf16pv(const void* q, const void* k, const void* v,
+                             int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                             void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /* attnqat_debug_fwd_p with the option bits of attnqat_fwd_opt (workspace ATTNQAT_WS_FWD). */
 int attnqat_debug_fwd_p_opt(const void* q, const void* k, const void* v,

@@ -26,6 +26,7 @@ _SIGNATURES = {
     "attnqat_quantize": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "attnqat_fwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_infer": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_fwd_infer_bf16pv": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_infer_static": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
     "attnqat_fwd_infer_packed": (_i, [_vp] * 6 + [_i] * 7 + [_vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_packed": (_i, [_vp] * 9 + [_i] * 7 + [_vp, _vp, _vp, _vp, _sz, _vp]),
@@ -129,7 +130,7 @@ def attnqat_quantize(x, want_codes=True, want_xf=True):
     return codes, scales, xf
 
 
-OPT_SMOOTH_K, OPT_TWO_LEVEL_P = 1, 2
+OPT_SMOOTH_K, OPT_TWO_LEVEL_P, OPT_BF16_PV = 1, 2, 4
 
 
 def attnqat_fwd_infer_mx_sparse(q, k, v, causal: bool, block_mask, workspace=None, out=None):
@@ -284,6 +285,23 @@ def attnqat_fwd_infer(q, k, v, causal: bool, workspace=None, out=None):
     ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, workspace)
     _check(lib().attnqat_fwd_infer(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
                                    _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
+    return o, lse
+
+
+def attnqat_fwd_infer_bf16pv(q, k, v, causal: bool, workspace=None, out=None):
+    """Alg. 1 in the mixed recipe of Sec. 2.5: NVFP4 Q K^T, P-tilde and V in bf16.  Returns (o bf16, lse fp32)."""
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _dev_bf16(t, n)
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    ws, nb = _workspace(WS_FWD_INFER, B, Hq, Hkv, L, d, workspace)
+    _check(lib().attnqat_fwd_infer_bf16pv(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16,
+                                          _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
     return o, lse
 
 

@@ -181,7 +181,9 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
                int dump_row0, float* p_dump, void* workspace, size_t workspace_bytes, void* stream, int options = 0)
 {
     if (!q || !k || !v || !o || !lse || (train && !o_hp)) return ATTNQAT_EINVAL;
-    if ((options & ~(ATTNQAT_OPT_SMOOTH_K | ATTNQAT_OPT_TWO_LEVEL_P)) || (options && mx)) return ATTNQAT_EINVAL;
+    if ((options & ~(ATTNQAT_OPT_SMOOTH_K | ATTNQAT_OPT_TWO_LEVEL_P | ATTNQAT_OPT_BF16_PV)) || (options && mx)) return ATTNQAT_EINVAL;
+    const bool bf16pv = (options & ATTNQAT_OPT_BF16_PV) != 0;
+    if (bf16pv && (train || (options & ATTNQAT_OPT_TWO_LEVEL_P))) return ATTNQAT_EINVAL;     // an inference recipe; P has no blocks
     int rc = check_dims(B, Hq, Hkv, L, d, dtype);
     if (rc) return rc;
     FwdWs w = carve_fwd(workspace, B, Hq, Hkv, L, d, mx);
@@ -196,9 +198,11 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
         kmean = w.kmean;
     }
     if (quant_copy(k, B * Hkv, L, d, mx, 0, true, w.kh, nullptr, w.tmp, st, kmean)) return ATTNQAT_ELAUNCH;
-    if (quant_copy(v, B * Hkv, L, d, mx, 1, true, nullptr, w.vt, w.tmp, st)) return ATTNQAT_ELAUNCH;
+    if (bf16pv) {      // Sec. 2.5, NVFP4 Q K^T with BF16 P V: V only changes layout
+        if (launch_prep(v, B * Hkv, L, d, false, false, nullptr, nullptr, nullptr, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
+    } else if (quant_copy(v, B * Hkv, L, d, mx, 1, true, nullptr, w.vt, w.tmp, st)) return ATTNQAT_ELAUNCH;
     prof_mark("prep_qkv", st);
-    const int p_quant = mx ? 1 : (options & ATTNQAT_OPT_TWO_LEVEL_P) ? 2 : 0;
+    const int p_quant = mx ? 1 : bf16pv ? 3 : (options & ATTNQAT_OPT_TWO_LEVEL_P) ? 2 : 0;
     if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, p_quant, o, lse, o_hp, dump_row0, p_dump, st))
         return ATTNQAT_ELAUNCH;
     prof_mark(train ? "fwd_train" : "fwd_infer", st);
@@ -506,6 +510,14 @@ int attnqat_fwd_opt(const void* q, const void* k, const void* v,
 {
     return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, o_hp != nullptr, false, o, lse, o_hp, 0, nullptr,
                       workspace, workspace_bytes, stream, options);
+}
+
+int attnqat_fwd_infer_bf16pv(const void* q, const void* k, const void* v,
+                             int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                             void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_common(q, k, v, B, Hq, Hkv, L, d, causal, dtype, false, false, o, lse, nullptr, 0, nullptr,
+                      workspace, workspace_bytes, stream, ATTNQAT_OPT_BF16_PV);
 }
 
 int attnqat_debug_fwd_p_opt(const void* q, const void* k, const void* v,

@@ -31,6 +31,12 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
 __device__ inline uint32_t pack_bf16x2_rne(float lo, float hi) {
     return (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
 }
+// The same rounding by the conversion instruction of gfx950 (one instruction per pair; finite inputs give the same bits).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack_bf16x2_cvt(float lo, float hi) {
+    const bf16x2 r = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, r);
+}
 __device__ inline uint32_t pack_f16x2(float lo, float hi) {
     half2v h; h[0] = (half_t)lo; h[1] = (half_t)hi;      // RNE conversions
     return __builtin_bit_cast(uint32_t, h);

@@ -28,7 +28,10 @@ struct FwdSmem {
     half_t v[2][D * 64];      // V^T tile [d][key], likewise
 };
 
-template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ /* phi(P-tilde): 0 NVFP4, 1 MX, 2 NVFP4 with the two-level row factor */>
+// PQ, the format of P-tilde in the P V product: 0 NVFP4, 1 MX, 2 NVFP4 with the two-level row factor,
+// 3 bf16 with V left in bf16 as well (the mixed recipe "NVFP4 Q K^T, BF16 P V" of Sec. 2.5; the tile buffer of V^T then
+// holds bf16 bit patterns and the P V products are bf16 MFMAs; inference only).
+template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ>
 __global__ __launch_bounds__(512, 2) void fwd_kernel(
     const half_t* __restrict__ Qh, const half_t* __restrict__ Kh, const half_t* __restrict__ Vt,
     uint16_t* __restrict__ O, float* __restrict__ lse, float* __restrict__ Ohp,
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         // maximum from those four.  exp2 of a group's largest score, by the same instructions on the same inputs as
         // that element's P-tilde, then is the group's largest P-tilde, which the block scale of phi needs below.
         float mt, gmax[4];
-        if constexpr (PQ == 1) {
+        if constexpr (PQ == 1 || PQ == 3) {
             float mp[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) mp[t] = max_nc(s[0][t], s[1][t]);
@@ -265,6 +268,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { o[mb][i] *= alpha; if constexpr (TRAIN) op[mb][i] *= alpha; }
         }
+        if constexpr (PQ == 3) return;      // bf16 P-tilde has no block scales
         if constexpr (PQ == 1) {
             // MX format: one power-of-two scale per 32 keys = all 16 registers of s[kb] in both halves;
             // the two 16-key groups of a block share it
@@ -321,6 +325,25 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
         auto q_part = [&](int ks, int part, QState& st, uint4v& bq, uint4v& bu) __attribute__((always_inline)) {
             const int b0 = 8 * (ks & 1);
             const floatx16& sv = s[ks >> 1];
+            if constexpr (PQ == 3) {
+                // bf16 P-tilde: one rounding (nearest even), no codes and no scales
+                if (part == 0) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) bq[i] = pack_bf16x2_cvt(sv[b0 + 2 * i], sv[b0 + 2 * i + 1]);
+                    if constexpr (DUMP) {
+                        if (q_row >= dump_row0 && q_row < dump_row0 + 128 && q_row < L) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) {
+                                const int key = k0 + 32 * (ks >> 1) + 16 * (ks & 1) + 8 * (i >> 2) + 4 * hf + (i & 3);
+                                if (key < L)
+                                    pdump[((size_t)bh * 128 + (q_row - dump_row0)) * L + key] =
+                                        __uint_as_float((i & 1) ? (bq[i >> 1] & 0xFFFF0000u) : (bq[i >> 1] << 16));
+                            }
+                        }
+                    }
+                }
+                return;
+            }
             const float inv = binv[ks];
             if (part == 0) {
                 // (the conversion replaces one byte of its first operand; bytes 2 and 3 of the code registers are never
@@ -378,7 +401,10 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 if constexpr (!DUMP) __builtin_amdgcn_sched_barrier(0);
-                o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], bqh, o[mb], 0, 0, 0);
+                if constexpr (PQ == 3)
+                    o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[mb]), __builtin_bit_cast(bf16x8, bqh), o[mb], 0, 0, 0);
+                else
+                    o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], bqh, o[mb], 0, 0, 0);
                 if constexpr (TRAIN) {
                     if constexpr (!DUMP) __builtin_amdgcn_sched_barrier(0);
                     op[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb], buh, op[mb], 0, 0, 0);
@@ -499,9 +525,11 @@ static int launch_d(const void* qh, const void* kh, const void* vt, int B, int H
         return causal ? launch_t<D, false, true, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st)
                       : launch_t<D, false, false, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st);
     }
-    if (train) {
-        return causal ? launch_t<D, true, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
-                      : launch_t<D, true, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+    if constexpr (PQ != 3) {
+        if (train) {
+            return causal ? launch_t<D, true, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
+                          : launch_t<D, true, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+        }
     }
     return causal ? launch_t<D, false, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
                   : launch_t<D, false, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
@@ -512,8 +540,9 @@ int launch_fwd(const void* qh, const void* kh, const void* vt,
                void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st)
 {
 #define AQ_FWD(DD, PQ) launch_d<DD, PQ>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st)
-    if (D == 128) return p_quant == 1 ? AQ_FWD(128, 1) : p_quant == 2 ? AQ_FWD(128, 2) : AQ_FWD(128, 0);
-    if (D == 64)  return p_quant == 1 ? AQ_FWD(64, 1) : p_quant == 2 ? AQ_FWD(64, 2) : AQ_FWD(64, 0);
+    if (p_quant == 3 && train) return -1;           // the bf16 P V recipe has no backward
+    if (D == 128) return p_quant == 1 ? AQ_FWD(128, 1) : p_quant == 2 ? AQ_FWD(128, 2) : p_quant == 3 ? AQ_FWD(128, 3) : AQ_FWD(128, 0);
+    if (D == 64)  return p_quant == 1 ? AQ_FWD(64, 1) : p_quant == 2 ? AQ_FWD(64, 2) : p_quant == 3 ? AQ_FWD(64, 3) : AQ_FWD(64, 0);
 #undef AQ_FWD
     return -1;
 }
