@@ -325,6 +325,34 @@ int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, in
                                void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same serving setting in the paper's own format: an NVFP4 KV cache and Alg. 1 (attnqat_fwd_infer) over it.
+ *
+ * Cache: num_pages * attnqat_kv_cache_page_bytes_nvfp4(Hkv, d) bytes of caller-owned device memory.  A page holds 128
+ * consecutive positions of one sequence for all Hkv heads; per head, in this order, K codes [128][d/2], K scale bytes
+ * [128][d/16], V codes [128][d/2], V scale bytes [128][d/16]: the layout of attnqat_quantize (Eq. 1, blocks of 16 along
+ * d) cut into pages, 4.5 bits per element.  Blocks do not span positions, so a sequence grows in place:
+ *
+ * attnqat_kv_cache_write quantizes k, v [1,Hkv,n,d] bf16, the n >= 1 positions pos0 .. pos0+n-1 of one sequence, into
+ * the pages page_ids[pos / 128] (device int32; the sequence's page list from its first page on, ceil((pos0+n)/128)
+ * entries) and clears the slots of the last page behind position pos0+n-1.  Slots before pos0 are left as they are.
+ * A page id outside [0, num_pages) is not written (nothing outside the cache is touched).
+ *
+ * attnqat_fwd_infer_paged: arguments as attnqat_fwd_infer_mx_paged; kv_lens[b] must be >= 1, and >= Lq under the causal
+ * mask (other values: that sequence's outputs are unspecified; no access outside the cache or the workspace).  Positions
+ * of a page table entry outside [0, num_pages) read as zeros.  The result is attnqat_fwd_infer of every sequence on its
+ * own (the last Lq rows of it), bit for bit when the pages hold what attnqat_quantize gives for K and V.
+ * Workspace: attnqat_paged_workspace_bytes(B, Hq, Hkv, Lq, max_pages, d) (the dequantized fp16 copies of Q and of the
+ * sequences' K and V, laid out for max_pages * 128 positions each; max_pages <= 8192); 0 for bad arguments.
+ */
+size_t attnqat_kv_cache_page_bytes_nvfp4(int Hkv, int d);
+int attnqat_kv_cache_write(const void* k, const void* v, int Hkv, int n, int d, int dtype, int pos0,
+                           void* cache, int num_pages, const int* page_ids, void* stream);
+size_t attnqat_paged_workspace_bytes(int B, int Hq, int Hkv, int Lq, int max_pages, int d);
+int attnqat_fwd_infer_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
+                            const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                            void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Block-sparse attention (Sec. 5: the paper's datacenter inference kernel supports it): attnqat_fwd_infer_mx with a
  * block mask.  block_mask [B,Hq,nb,nb] bytes (device, read), nb = ceil(L/128): a zero byte removes the block of 128
  * queries x 128 keys, i.e. those keys count as masked for those queries and their key tiles are not visited (the

@@ -46,6 +46,10 @@ _SIGNATURES = {
     "attnqat_kv_cache_page_bytes": (_sz, [_i, _i]),
     "attnqat_kv_cache_write_mx": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _i, _vp, _vp]),
     "attnqat_fwd_infer_mx_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_kv_cache_page_bytes_nvfp4": (_sz, [_i, _i]),
+    "attnqat_kv_cache_write": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp]),
+    "attnqat_paged_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
+    "attnqat_fwd_infer_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_infer_mx_sparse": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
@@ -192,6 +196,49 @@ def attnqat_fwd_infer_mx_paged(q, cache, num_pages, page_table, kv_lens, Hkv, ca
     _check(lib().attnqat_fwd_infer_mx_paged(_ptr(q), B, Hq, Hkv, Lq, d, int(causal), BF16, _ptr(cache), int(num_pages),
                                             _ptr(page_table), page_table.shape[1], _ptr(kv_lens),
                                             _ptr(o), _ptr(lse), _ptr(ws), nb, _stream()))
+    return o, lse
+
+
+def kv_cache_page_bytes_nvfp4(Hkv: int, d: int) -> int:
+    return lib().attnqat_kv_cache_page_bytes_nvfp4(Hkv, d)
+
+
+def attnqat_kv_cache_write(k, v, cache, page_ids, pos0: int = 0, num_pages=None):
+    """Quantize positions pos0 .. pos0+n-1 of one sequence, k, v [1,Hkv,n,d] bf16, into the pages ``page_ids`` (int32 CUDA
+    tensor, the sequence's page list from its first page on) of the NVFP4 KV ``cache`` (uint8 CUDA tensor)."""
+    _dev_bf16(k, "k"); _dev_bf16(v, "v")
+    _, Hkv, n, d = k.shape
+    if k.shape[0] != 1 or v.shape != k.shape:
+        raise AttnQatError("k and v must be [1,Hkv,n,d] of one sequence")
+    if not (page_ids.is_cuda and page_ids.dtype == torch.int32 and page_ids.is_contiguous() and page_ids.numel() >= (pos0 + n + 127) // 128):
+        raise AttnQatError("page_ids must be a contiguous int32 CUDA tensor with ceil((pos0+n)/128) entries")
+    if num_pages is None:
+        num_pages = cache.numel() // kv_cache_page_bytes_nvfp4(Hkv, d)
+    _check(lib().attnqat_kv_cache_write(_ptr(k), _ptr(v), Hkv, n, d, BF16, int(pos0), _ptr(cache), int(num_pages), _ptr(page_ids), _stream()))
+
+
+def attnqat_fwd_infer_paged(q, cache, num_pages, page_table, kv_lens, Hkv, causal: bool, workspace=None, out=None):
+    """Alg. 1 over a paged NVFP4 KV cache.  q [B,Hq,Lq,d]: the last Lq positions of every sequence; page_table int32
+    [B,max_pages]; kv_lens int32 [B].  Returns (o bf16, lse fp32)."""
+    _dev_bf16(q, "q")
+    B, Hq, Lq, d = q.shape
+    for t, n in ((page_table, "page_table"), (kv_lens, "kv_lens")):
+        if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+            raise AttnQatError(f"{n} must be a contiguous int32 CUDA tensor")
+    if page_table.dim() != 2 or page_table.shape[0] != B or kv_lens.numel() != B:
+        raise AttnQatError("page_table must be [B,max_pages] and kv_lens [B]")
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+    max_pages = page_table.shape[1]
+    need = lib().attnqat_paged_workspace_bytes(B, Hq, Hkv, Lq, max_pages, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+    _check(lib().attnqat_fwd_infer_paged(_ptr(q), B, Hq, Hkv, Lq, d, int(causal), BF16, _ptr(cache), int(num_pages),
+                                         _ptr(page_table), max_pages, _ptr(kv_lens),
+                                         _ptr(o), _ptr(lse), _ptr(workspace), workspace.numel(), _stream()))
     return o, lse
 
 

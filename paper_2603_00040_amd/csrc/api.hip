@@ -400,6 +400,69 @@ int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, in
     return ATTNQAT_OK;
 }
 
+size_t attnqat_kv_cache_page_bytes_nvfp4(int Hkv, int d)
+{
+    if (Hkv < 1 || (d != 64 && d != 128)) return 0;
+    return nvfp4_page_bytes(Hkv, d);
+}
+
+int attnqat_kv_cache_write(const void* k, const void* v, int Hkv, int n, int d, int dtype, int pos0,
+                           void* cache, int num_pages, const int* page_ids, void* stream)
+{
+    if (!k || !v || !cache || !page_ids || num_pages < 1 || pos0 < 0) return ATTNQAT_EINVAL;
+    int rc = check_dims(1, Hkv, Hkv, n, d, dtype);
+    if (rc) return rc;
+    if ((long long)pos0 + n > (1 << 20)) return ATTNQAT_ESHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    if (launch_kv_page_write(k, v, Hkv, n, d, pos0, cache, num_pages, page_ids, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("kv_cache_write", st);
+    return ATTNQAT_OK;
+}
+
+namespace {
+struct PagedWs { void *qh, *kh, *vt; size_t bytes; int Lkp; };
+PagedWs carve_paged(void* ws, int B, int Hq, int Hkv, int Lq, int max_pages, int d)
+{
+    Carver c{(unsigned char*)ws, 0};
+    PagedWs w;
+    w.Lkp = (int)round_up(max_pages * 128, kRowPad);
+    w.qh = c.take((size_t)B * Hq * round_up(Lq, kRowPad) * d * 2);
+    w.kh = c.take((size_t)B * Hkv * w.Lkp * d * 2);
+    w.vt = c.take((size_t)B * Hkv * w.Lkp * d * 2);
+    w.bytes = c.off;
+    return w;
+}
+}  // namespace
+
+size_t attnqat_paged_workspace_bytes(int B, int Hq, int Hkv, int Lq, int max_pages, int d)
+{
+    if (check_dims(B, Hq, Hkv, Lq, d, ATTNQAT_BF16) || max_pages < 1 || max_pages > (1 << 13)) return 0;
+    return carve_paged(nullptr, B, Hq, Hkv, Lq, max_pages, d).bytes;
+}
+
+int attnqat_fwd_infer_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
+                            const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                            void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !cache || !page_table || !kv_lens || !o || !lse || num_pages < 1 || max_pages < 1) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, Lq, d, dtype);
+    if (rc) return rc;
+    if (max_pages > (1 << 13) || (long long)B * Hkv > 65535) return ATTNQAT_ESHAPE;          // 2^20 keys per sequence
+    PagedWs w = carve_paged(workspace, B, Hq, Hkv, Lq, max_pages, d);
+    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    // phi(Q); K^F and V^F are in the cache already and only change layout
+    if (launch_prep(q, B * Hq, Lq, d, true, true, nullptr, nullptr, nullptr, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_unpack_pages(cache, page_table, kv_lens, B, Hkv, max_pages, num_pages, d, 0, w.kh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_unpack_pages(cache, page_table, kv_lens, B, Hkv, max_pages, num_pages, d, 1, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_q_unpack_pages", st);
+    if (launch_fwd_varlen(w.qh, w.kh, w.vt, B, Hq, Hkv, Lq, w.Lkp, d, causal != 0, kv_lens, o, lse, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("fwd_infer_paged", st);
+    return ATTNQAT_OK;
+}
+
 int attnqat_debug_dkdv_tile_counts(void* stream, unsigned long long* counts)
 {
     std::lock_guard<std::mutex> lock(g_dbg_mutex);

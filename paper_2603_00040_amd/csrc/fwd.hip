@@ -31,11 +31,15 @@ struct FwdSmem {
 // PQ, the format of P-tilde in the P V product: 0 NVFP4, 1 MX, 2 NVFP4 with the two-level row factor,
 // 3 bf16 with V left in bf16 as well (the mixed recipe "NVFP4 Q K^T, BF16 P V" of Sec. 2.5; the tile buffer of V^T then
 // holds bf16 bit patterns and the P V products are bf16 MFMAs; inference only).
-template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ>
+// VARLEN (serving): every sequence b has its own number of keys kv_lens[b] (read here, on the device), the copies of K and V^T
+// are laid out for Lkp positions per head, and the L query rows are the LAST L positions of their sequence: under the causal
+// mask query i sees keys 0 .. kv_lens[b] - L + i (a chunk of a prefill; needs kv_lens[b] >= L).
+template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ, bool VARLEN = false>
 __global__ __launch_bounds__(512, 2) void fwd_kernel(
     const half_t* __restrict__ Qh, const half_t* __restrict__ Kh, const half_t* __restrict__ Vt,
     uint16_t* __restrict__ O, float* __restrict__ lse, float* __restrict__ Ohp,
-    int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */, int dump_row0, float* __restrict__ pdump)
+    int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */, int dump_row0, float* __restrict__ pdump,
+    int Lkp_arg, const int* __restrict__ kv_lens)
 {
     constexpr int DS = D / 16;      // contraction steps of S
     constexpr int MB = D / 32;      // 32-row blocks of O^T
@@ -58,7 +62,11 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     const int bhkv = b * (Hq / G) + h / G;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);        // scalar: LDS destinations and branches use it
     const bool late = wave >= 4;                         // the group that runs one phase behind
-    const int nkt_all = (L + 63) / 64;
+    // keys of this sequence, row stride of the K / V^T copies, and how far the causal diagonal is shifted
+    const int Lk = VARLEN ? max(1, min(kv_lens[b], Lkp_arg)) : L;
+    const int Lkp = VARLEN ? Lkp_arg : Lp;
+    const int off = (VARLEN && CAUSAL) ? max(0, Lk - L) : 0;
+    const int nkt_all = (Lk + 63) / 64;
 
     for (int item = 0; item < nitems; ++item) {
     // (the lane number is taken afresh for every item and made opaque: everything formed from it would otherwise be kept
@@ -85,10 +93,10 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 #pragma unroll
     for (int i = 0; i < VLD; ++i) {
         const int slot = 64 * (wave * VLD + i) + lane, r = slot / 8, pc = slot % 8;
-        v_ld[i] = 2u * ((uint32_t)r * (uint32_t)Lp + 8u * (uint32_t)swz<8>(r, pc));
+        v_ld[i] = 2u * ((uint32_t)r * (uint32_t)Lkp + 8u * (uint32_t)swz<8>(r, pc));
     }
-    const half_t* k_head = Kh + (size_t)bhkv * Lp * D;      // [key][d]
-    const half_t* v_head = Vt + (size_t)bhkv * D * Lp;      // [d][key]
+    const half_t* k_head = Kh + (size_t)bhkv * Lkp * D;      // [key][d]
+    const half_t* v_head = Vt + (size_t)bhkv * D * Lkp;      // [d][key]
     auto issue_k = [&](int buf, int jt) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < KLD; ++i) async_copy16(k_head + (size_t)jt * (64 * D), k_ld[i], &sm.k[buf][512 * (wave * KLD + i)]);
@@ -110,8 +118,8 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) qreg[ds] = *reinterpret_cast<const half8*>(qp + 16 * ds);
     }
-    const int nkt = CAUSAL ? min(4 * qt + 4, nkt_all) : nkt_all;     // key tiles this item visits
-    const int wave_qmax = row0_w + 31;
+    const int nkt = CAUSAL ? min((qt * 256 + 255 + off) / 64 + 1, nkt_all) : nkt_all;     // key tiles this item visits
+    const int wave_qmax = row0_w + 31 + off;             // the last key that a row of this wave sees
 
     floatx16 o[MB], op[TRAIN ? MB : 1];
 #pragma unroll
@@ -184,9 +192,9 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     auto vector_phase = [&](int j, float (&bsc)[4], float (&binv)[4]) __attribute__((always_inline)) {
         const int k0 = j * 64;
         // mask: keys beyond L, and keys after the query when causal
-        const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > row0_w);
+        const bool need_mask = (k0 + 64 > Lk) || (CAUSAL && k0 + 63 > row0_w + off);
         if (__builtin_expect(need_mask, 0)) {
-            const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
+            const int klim = CAUSAL ? min(Lk - 1, q_row + off) : Lk - 1;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -428,7 +436,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     // starts at the workgroup's first row included; rows inside it are masked in the vector phase), and only the last
     // three have waves that skip.  The two kinds of tile get loops of their own: the form with the skipping branch
     // schedules markedly worse (17 % slower on tiles where nobody skips), so it only runs where somebody does.
-    const int j_all = CAUSAL ? min(nkt, 4 * qt + 1) : nkt;
+    const int j_all = CAUSAL ? min(nkt, (qt * 256 + 31 + off) / 64 + 1) : nkt;
     for (int j = 0; j < j_all; ++j) {
         const int k0 = j * 64;
         float bsc[4], binv[4];
@@ -498,21 +506,22 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     }
 }
 
-template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ>
+template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ, bool VARLEN = false>
 static int launch_t(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int L,
-                    void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st)
+                    void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st,
+                    int Lkp = 0, const int* kv_lens = nullptr)
 {
     const int Lp = round_up(L, kRowPad);
     const int nqt = (Lp + 255) / 256;
     const int per_head = CAUSAL ? (nqt + 1) / 2 : nqt;         // under a causal mask a workgroup takes a long and a short tile
     const size_t smem = sizeof(FwdSmem<D>);
-    auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP, PQ>;
+    auto kern = fwd_kernel<D, TRAIN, CAUSAL, DUMP, PQ, VARLEN>;
     static unsigned long long lds_set = 0;          // one per instantiation
     if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float c = 1.4426950408889634f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * per_head)), dim3(512), smem, st,
                        (const half_t*)qh, (const half_t*)kh, (const half_t*)vt, (uint16_t*)o, lse, o_hp,
-                       L, Lp, Hq, Hq / Hkv, c, dump_row0, p_dump);
+                       L, Lp, Hq, Hq / Hkv, c, dump_row0, p_dump, Lkp, kv_lens);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -544,6 +553,19 @@ int launch_fwd(const void* qh, const void* kh, const void* vt,
     if (D == 128) return p_quant == 1 ? AQ_FWD(128, 1) : p_quant == 2 ? AQ_FWD(128, 2) : p_quant == 3 ? AQ_FWD(128, 3) : AQ_FWD(128, 0);
     if (D == 64)  return p_quant == 1 ? AQ_FWD(64, 1) : p_quant == 2 ? AQ_FWD(64, 2) : p_quant == 3 ? AQ_FWD(64, 3) : AQ_FWD(64, 0);
 #undef AQ_FWD
+    return -1;
+}
+
+// Alg. 1 for sequences of different lengths: the last Lq positions of every sequence as queries, kv_lens[b] keys, K and V^T
+// copies laid out for Lkp positions per head (a multiple of 64).
+int launch_fwd_varlen(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int Lq, int Lkp, int D, bool causal,
+                      const int* kv_lens, void* o, float* lse, hipStream_t st)
+{
+    if (!kv_lens || Lkp < 64 || Lkp % 64) return -1;
+#define AQ_FWDV(DD, C) launch_t<DD, false, C, false, 0, true>(qh, kh, vt, B, Hq, Hkv, Lq, o, lse, nullptr, 0, nullptr, st, Lkp, kv_lens)
+    if (D == 128) return causal ? AQ_FWDV(128, true) : AQ_FWDV(128, false);
+    if (D == 64)  return causal ? AQ_FWDV(64, true) : AQ_FWDV(64, false);
+#undef AQ_FWDV
     return -1;
 }
 

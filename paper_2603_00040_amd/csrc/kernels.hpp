@@ -31,6 +31,19 @@ int launch_fwd(const void* qh, const void* kh, const void* vt,
                int B, int Hq, int Hkv, int L, int D, bool causal, bool train, int p_quant,
                void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st);
 
+// Alg. 1 for sequences of different lengths (serving): queries are the last Lq positions of every sequence, sequence b has
+// kv_lens[b] keys (device array), kh / vt are laid out for Lkp positions per kv head.
+int launch_fwd_varlen(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int Lq, int Lkp, int D, bool causal,
+                      const int* kv_lens, void* o, float* lse, hipStream_t st);
+
+// The NVFP4 KV cache (pages of 128 positions; per kv head K codes, K scales, V codes, V scales in the public layout).
+size_t nvfp4_page_bytes(int Hkv, int D);
+int launch_kv_page_write(const void* k, const void* v, int Hkv, int n, int D, int pos0,
+                         void* cache, int num_pages, const int* page_ids, hipStream_t st);
+// which: 0 the K part (xr: rows), 1 the V part (xt: transposed); copies laid out for max_pages * 128 positions per sequence
+int launch_unpack_pages(const void* cache, const int* page_table, const int* kv_lens, int B, int Hkv, int max_pages, int num_pages,
+                        int D, int which, void* xr, void* xt, hipStream_t st);
+
 // Per-row statistics of the backward: rowstat [BHq, Lp, 2] = {L log2(e), D / sqrt(d)} with
 // D = rowsum(dO o O') (Alg. 3, first line); padding rows hold zeros.  d_o bf16, o_hp fp32, [rows, D].
 // o_acc: O' fp32, or (ablation) the bf16 O when o_is_bf16.

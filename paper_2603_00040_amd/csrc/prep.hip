@@ -17,36 +17,105 @@ namespace aq {
 // 16-byte run of the transposed operand.
 __host__ __device__ inline int perm16(int p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
 
+// phi of one block of 16 values that are bf16 numbers (Eq. 1): the E4M3 scale s and the 16 E2M1 codes, element 2k in the low
+// nibble of byte k of {clo, chi}.
+// RNE of the real quotient x / s without a division per element (ten vector instructions each, which bound the streaming
+// kernels).  |x| has 8 significant bits and s has 4, so a quotient that is not on a rounding boundary of the E2M1 grid is at
+// least 2^-9 (relative) away from it, and one that is on a boundary (a tie) has at most 3 significant bits.  x * (1/s) with the
+// approximate reciprocal is within 2^-21 of the quotient; rounding that product to 12 significant bits puts a tie back on its
+// boundary exactly and moves nothing else across one (it moves a value by at most 2^-12).  The rounding to E2M1 itself
+// (nearest, ties to even, saturating at 6, sign kept) then is the hardware conversion, two elements per instruction, which
+// leaves the codes packed as the public layout wants them.
+__device__ inline void phi_block16_bf16(const float (&v)[16], float& s, uint32_t& clo, uint32_t& chi)
+{
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
+    s = block_scale_exact(amax);
+    const float inv_s = s > 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;      // s = 0: every quotient 0, every code 0
+    auto snap = [](float r) __attribute__((always_inline)) {
+        return __uint_as_float((__float_as_uint(r) + 0x800u) & 0xFFFFF000u);
+    };
+    clo = 0; chi = 0;
+#define AQ_PAIR(W, PR, SEL) W = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(W, snap(v[2 * (PR)] * inv_s), snap(v[2 * (PR) + 1] * inv_s), 1.0f, SEL)
+    AQ_PAIR(clo, 0, 0); AQ_PAIR(clo, 1, 1); AQ_PAIR(clo, 2, 2); AQ_PAIR(clo, 3, 3);
+    AQ_PAIR(chi, 4, 0); AQ_PAIR(chi, 5, 1); AQ_PAIR(chi, 6, 2); AQ_PAIR(chi, 7, 3);
+#undef AQ_PAIR
+}
+
+// The 16 values of a block from its codes and its scale (exact: <= 6 significant bits).
+__device__ inline void dequant_block16(uint32_t clo, uint32_t chi, float s, float (&xf)[16])
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+#define AQ_BACK(W, PR, SEL) { const float2v cv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(W, 1.0f, SEL); xf[2 * (PR)] = cv[0] * s; xf[2 * (PR) + 1] = cv[1] * s; }
+    AQ_BACK(clo, 0, 0) AQ_BACK(clo, 1, 1) AQ_BACK(clo, 2, 2) AQ_BACK(clo, 3, 3)
+    AQ_BACK(chi, 4, 0) AQ_BACK(chi, 5, 1) AQ_BACK(chi, 6, 2) AQ_BACK(chi, 7, 3)
+#undef AQ_BACK
+}
+
+// The NVFP4 KV cache: a page holds 128 consecutive positions of one sequence for all kv heads; per kv head, in this order,
+// K codes [128][D/2], K scale bytes [128][D/16], V codes [128][D/2], V scale bytes [128][D/16]: the public layout of
+// attnqat_quantize cut into pages.  Blocks run along d, so positions are independent of each other: a sequence grows by
+// writing its new positions only.
+__host__ __device__ inline size_t nvfp4_page_head_bytes(int D) { return (size_t)2 * 128 * (D / 2 + D / 16); }
+struct PagedSrc {
+    const unsigned char* cache; const int* table; const int* kv_lens;
+    int max_pages, num_pages, Hkv, which;          // which: 0 the K part, 1 the V part
+};
+// Codes and scale byte of block cb of position l (nullptr for a page id outside the cache).
+__device__ inline const unsigned char* nvfp4_page_part(const unsigned char* cache, int page, int num_pages, int Hkv, int h, int D, int which) {
+    if (page < 0 || page >= num_pages) return nullptr;
+    return cache + ((size_t)page * Hkv + h) * nvfp4_page_head_bytes(D) + (size_t)which * 128 * (D / 2 + D / 16);
+}
+
 // PACKED (with QUANT = false): the input is not x but an already quantized tensor, codes [BH, L, D/2] and E4M3 scale bytes
 // [BH, L, D/16] in the public layout of attnqat_quantize (read through `codes` and `scales`); the kernel writes the
 // dequantized layout copies, the same values the quantizing variant writes for the tensor those codes came from.
-template <bool QUANT, bool OUT_F16, bool PACKED = false>
+// PAGED (with PACKED): the quantized tensor is the K or the V part of the pages of an NVFP4 KV cache; bh = sequence * Hkv + kv
+// head, position l of sequence b is slot l % 128 of page table[b][l / 128], positions from kv_lens[b] on read as zeros, and
+// L is the capacity max_pages * 128 that the copies are laid out for.
+template <bool QUANT, bool OUT_F16, bool PACKED = false, bool PAGED = false>
 __global__ __launch_bounds__(256) void prep_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, int D,
     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint16_t* __restrict__ xf_pub,
-    uint16_t* __restrict__ xr, uint16_t* __restrict__ xt, const float* __restrict__ sub)
+    uint16_t* __restrict__ xr, uint16_t* __restrict__ xt, const float* __restrict__ sub, PagedSrc ps)
 {
     static_assert(!(QUANT && PACKED), "a packed input is already quantized");
+    static_assert(!PAGED || PACKED, "pages hold quantized tensors");
     __shared__ uint16_t tile[64][128 + 2];
     const int bh = blockIdx.y;
     const int l0 = blockIdx.x * 64;
     const int nb = D / 16;                       // 16-element blocks per row
     const size_t in_base = (size_t)bh * L * D;
+    int Lseq = L;
+    const unsigned char* page_part[PAGED ? 1 : 1] = {nullptr};
+    if constexpr (PAGED) {
+        const int b = bh / ps.Hkv;
+        Lseq = max(0, min(ps.kv_lens[b], L));
+        if (l0 >= Lseq) return;                  // key tiles that start beyond the sequence are never read
+        // a workgroup's 64 positions lie in one page
+        page_part[0] = nvfp4_page_part(ps.cache, ps.table[(size_t)b * ps.max_pages + (l0 >> 7)], ps.num_pages, ps.Hkv, bh % ps.Hkv, D, ps.which);
+    }
 
     for (int blk = threadIdx.x; blk < 64 * nb; blk += 256) {
         const int row = blk / nb, cb = blk % nb;
         const int l = l0 + row;
         float v[16];
         if (PACKED) {
-            if (l < L) {
-                typedef float float2v __attribute__((ext_vector_type(2)));
-                const uint2v cw = *reinterpret_cast<const uint2v*>(codes + ((size_t)bh * L + l) * (D / 2) + cb * 8);
+            const unsigned char* cp = nullptr; const unsigned char* sp = nullptr;
+            if constexpr (PAGED) {
+                if (l < Lseq && page_part[0]) {
+                    cp = page_part[0] + (size_t)(l & 127) * (D / 2) + cb * 8;
+                    sp = page_part[0] + (size_t)128 * (D / 2) + (size_t)(l & 127) * nb + cb;
+                }
+            } else if (l < L) {
+                cp = codes + ((size_t)bh * L + l) * (D / 2) + cb * 8;
+                sp = scales + ((size_t)bh * L + l) * nb + cb;
+            }
+            if (cp) {
+                const uint2v cw = *reinterpret_cast<const uint2v*>(cp);
                 // E4M3 byte -> value: the hardware conversion (OCP E4M3, subnormals kept), byte 0 of the operand
-                const float sv = __builtin_amdgcn_cvt_scalef32_f32_fp8((uint32_t)scales[((size_t)bh * L + l) * nb + cb], 1.0f, 0);
-#define AQ_BACK(W, PR, SEL) { const float2v cv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(W, 1.0f, SEL); v[2 * (PR)] = cv[0] * sv; v[2 * (PR) + 1] = cv[1] * sv; }
-                AQ_BACK(cw[0], 0, 0) AQ_BACK(cw[0], 1, 1) AQ_BACK(cw[0], 2, 2) AQ_BACK(cw[0], 3, 3)
-                AQ_BACK(cw[1], 4, 0) AQ_BACK(cw[1], 5, 1) AQ_BACK(cw[1], 6, 2) AQ_BACK(cw[1], 7, 3)
-#undef AQ_BACK
+                dequant_block16(cw[0], cw[1], __builtin_amdgcn_cvt_scalef32_f32_fp8((uint32_t)*sp, 1.0f, 0), v);
             } else {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) v[i] = 0.0f;
@@ -75,12 +144,13 @@ __global__ __launch_bounds__(256) void prep_kernel(
 
         float xf[16];
         if (QUANT) {
-            float amax = 0.0f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
-            const float s = block_scale_exact(amax);
+            float s;
             uint32_t clo = 0, chi = 0;
             if (sub) {
+                float amax = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
+                s = block_scale_exact(amax);
                 // (inputs with 24 significant bits, after the K smoothing subtraction: IEEE division and the grid rounding
                 //  of common.hpp; the short cut below relies on bf16 inputs)
 #pragma unroll
@@ -98,28 +168,8 @@ __global__ __launch_bounds__(256) void prep_kernel(
                     xf[i] = sign ? -d : d;
                 }
             } else {
-                // RNE of the real quotient x / s without a division per element (ten vector instructions each, which bound
-                // this kernel).  |x| has 8 significant bits and s has 4, so a quotient that is not on a rounding boundary of
-                // the E2M1 grid is at least 2^-9 (relative) away from it, and one that is on a boundary (a tie) has at most
-                // 3 significant bits.  x * (1/s) with the approximate reciprocal is within 2^-21 of the quotient; rounding
-                // that product to 12 significant bits puts a tie back on its boundary exactly and moves nothing else across
-                // one (it moves a value by at most 2^-12).  The rounding to E2M1 itself (nearest, ties to even, saturating
-                // at 6, sign kept) then is the hardware conversion, two elements per instruction, which leaves the codes
-                // packed as the public layout wants them (element 2k in the low nibble of byte k); the conversion back gives
-                // the code values, times s: exact (<= 6 significant bits).
-                const float inv_s = s > 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;      // s = 0: every quotient 0, every code 0
-                typedef float float2v __attribute__((ext_vector_type(2)));
-                auto snap = [](float r) __attribute__((always_inline)) {
-                    return __uint_as_float((__float_as_uint(r) + 0x800u) & 0xFFFFF000u);
-                };
-#define AQ_PAIR(W, PR, SEL) W = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(W, snap(v[2 * (PR)] * inv_s), snap(v[2 * (PR) + 1] * inv_s), 1.0f, SEL)
-                AQ_PAIR(clo, 0, 0); AQ_PAIR(clo, 1, 1); AQ_PAIR(clo, 2, 2); AQ_PAIR(clo, 3, 3);
-                AQ_PAIR(chi, 4, 0); AQ_PAIR(chi, 5, 1); AQ_PAIR(chi, 6, 2); AQ_PAIR(chi, 7, 3);
-#undef AQ_PAIR
-#define AQ_BACK(W, PR, SEL) { const float2v cv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(W, 1.0f, SEL); xf[2 * (PR)] = cv[0] * s; xf[2 * (PR) + 1] = cv[1] * s; }
-                AQ_BACK(clo, 0, 0) AQ_BACK(clo, 1, 1) AQ_BACK(clo, 2, 2) AQ_BACK(clo, 3, 3)
-                AQ_BACK(chi, 4, 0) AQ_BACK(chi, 5, 1) AQ_BACK(chi, 6, 2) AQ_BACK(chi, 7, 3)
-#undef AQ_BACK
+                phi_block16_bf16(v, s, clo, chi);
+                dequant_block16(clo, chi, s, xf);
             }
             if (l < L) {
                 if (codes) {
@@ -187,6 +237,78 @@ __global__ __launch_bounds__(256) void prep_kernel(
     }
 }
 
+// Writer of the NVFP4 KV cache: phi of n new positions pos0 .. pos0 + n - 1 of one sequence, k and v [Hkv, n, D] bf16, into
+// the pages page_ids[pos / 128] (the sequence's page list).  The slots between the last new position and the end of its page
+// are cleared (codes and scales 0: they read as zeros until the sequence grows into them).  A page id outside [0, num_pages)
+// is left out.  One thread per block of 16 elements; grid (64-row groups, Hkv, 2: K then V).
+template <int D>
+__global__ __launch_bounds__(256) void kv_page_write_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int n, int pos0, int Hkv,
+    unsigned char* __restrict__ cache, int num_pages, const int* __restrict__ page_ids)
+{
+    constexpr int nb = D / 16;
+    const int h = blockIdx.y, which = blockIdx.z;
+    const uint16_t* x = (which ? v : k) + (size_t)h * n * D;
+    const int rows_total = ((pos0 + n + 127) & ~127) - pos0;
+    for (int blk = threadIdx.x; blk < 64 * nb; blk += 256) {
+        const int row = blockIdx.x * 64 + blk / nb, cb = blk % nb;
+        float s = 0.0f;
+        uint32_t clo = 0, chi = 0;
+        if (row < n) {
+            const uint4v* src = reinterpret_cast<const uint4v*>(x + (size_t)row * D + cb * 16);
+            const uint4v a = src[0], b = src[1];
+            float val[16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                val[2 * i]         = __uint_as_float(a[i] << 16);
+                val[2 * i + 1]     = __uint_as_float(a[i] & 0xFFFF0000u);
+                val[8 + 2 * i]     = __uint_as_float(b[i] << 16);
+                val[8 + 2 * i + 1] = __uint_as_float(b[i] & 0xFFFF0000u);
+            }
+            phi_block16_bf16(val, s, clo, chi);
+        }
+        // the scale bytes of four neighbouring blocks of a row as one dword (rows beyond the page end take part and write nothing)
+        uint32_t sb = e4m3_byte_of(s);
+        sb |= (uint32_t)__shfl_down((int)sb, 1) << 8;
+        sb |= (uint32_t)__shfl_down((int)sb, 2) << 16;
+        if (row >= rows_total) continue;
+        const int pos = pos0 + row;
+        unsigned char* part = const_cast<unsigned char*>(nvfp4_page_part(cache, page_ids[pos >> 7], num_pages, Hkv, h, D, which));
+        if (!part) continue;
+        uint2v c2; c2[0] = clo; c2[1] = chi;
+        *reinterpret_cast<uint2v*>(part + (size_t)(pos & 127) * (D / 2) + cb * 8) = c2;
+        if ((cb & 3) == 0) *reinterpret_cast<uint32_t*>(part + (size_t)128 * (D / 2) + (size_t)(pos & 127) * nb + cb) = sb;
+    }
+}
+
+size_t nvfp4_page_bytes(int Hkv, int D) { return (size_t)Hkv * nvfp4_page_head_bytes(D); }
+
+int launch_kv_page_write(const void* k, const void* v, int Hkv, int n, int D, int pos0,
+                         void* cache, int num_pages, const int* page_ids, hipStream_t st)
+{
+    if (Hkv > 65535 || (D != 64 && D != 128) || n < 1 || pos0 < 0) return -1;
+    const int rows_total = ((pos0 + n + 127) & ~127) - pos0;
+    dim3 grid((rows_total + 63) / 64, Hkv, 2);
+    if (D == 128) hipLaunchKernelGGL((kv_page_write_kernel<128>), grid, dim3(256), 0, st, (const uint16_t*)k, (const uint16_t*)v, n, pos0, Hkv,
+                                     (unsigned char*)cache, num_pages, page_ids);
+    else          hipLaunchKernelGGL((kv_page_write_kernel<64>), grid, dim3(256), 0, st, (const uint16_t*)k, (const uint16_t*)v, n, pos0, Hkv,
+                                     (unsigned char*)cache, num_pages, page_ids);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// The layout copies of the forward (K row-major fp16, or V transposed fp16) from the pages of B sequences; the copies are laid
+// out for max_pages * 128 positions per sequence.
+int launch_unpack_pages(const void* cache, const int* page_table, const int* kv_lens, int B, int Hkv, int max_pages, int num_pages,
+                        int D, int which, void* xr, void* xt, hipStream_t st)
+{
+    const int L = max_pages * 128, Lp = round_up(L, kRowPad);
+    if ((size_t)B * Hkv > 65535) return -1;
+    PagedSrc ps{(const unsigned char*)cache, page_table, kv_lens, max_pages, num_pages, Hkv, which};
+    hipLaunchKernelGGL((prep_kernel<false, true, true, true>), dim3(Lp / 64, B * Hkv), dim3(256), 0, st, (const uint16_t*)nullptr, L, Lp, D,
+                       (uint8_t*)nullptr, (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)xr, (uint16_t*)xt, (const float*)nullptr, ps);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 // Token mean of every channel, for K smoothing: fp64 partial sums of NCHUNK row ranges, then their sum in a fixed
 // order, divided by L and rounded to fp32.  Deterministic; x [BH, L, D] bf16.
 constexpr int kMeanChunks = 32;
@@ -238,7 +360,7 @@ static int launch_prep_t(const void* x, int BH, int L, int D, uint8_t* codes, ui
     dim3 grid(Lp / 64, BH);
     hipLaunchKernelGGL((prep_kernel<QUANT, OUT_F16>), grid, dim3(256), 0, st,
                        (const uint16_t*)x, L, Lp, D, codes, scales, (uint16_t*)xf_pub,
-                       (uint16_t*)xr, (uint16_t*)xt, sub);
+                       (uint16_t*)xr, (uint16_t*)xt, sub, PagedSrc{});
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -247,9 +369,9 @@ int launch_unpack(const uint8_t* codes, const uint8_t* scales, int BH, int L, in
     const int Lp = round_up(L, kRowPad);
     dim3 grid(Lp / 64, BH);
     if (out_f16) hipLaunchKernelGGL((prep_kernel<false, true, true>), grid, dim3(256), 0, st, (const uint16_t*)nullptr, L, Lp, D,
-                                    const_cast<uint8_t*>(codes), const_cast<uint8_t*>(scales), (uint16_t*)nullptr, (uint16_t*)xr, (uint16_t*)xt, (const float*)nullptr);
+                                    const_cast<uint8_t*>(codes), const_cast<uint8_t*>(scales), (uint16_t*)nullptr, (uint16_t*)xr, (uint16_t*)xt, (const float*)nullptr, PagedSrc{});
     else         hipLaunchKernelGGL((prep_kernel<false, false, true>), grid, dim3(256), 0, st, (const uint16_t*)nullptr, L, Lp, D,
-                                    const_cast<uint8_t*>(codes), const_cast<uint8_t*>(scales), (uint16_t*)nullptr, (uint16_t*)xr, (uint16_t*)xt, (const float*)nullptr);
+                                    const_cast<uint8_t*>(codes), const_cast<uint8_t*>(scales), (uint16_t*)nullptr, (uint16_t*)xr, (uint16_t*)xt, (const float*)nullptr, PagedSrc{});
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
