@@ -341,8 +341,23 @@ int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, in
  * mask (other values: that sequence's outputs are unspecified; no access outside the cache or the workspace).  Positions
  * of a page table entry outside [0, num_pages) read as zeros.  The result is attnqat_fwd_infer of every sequence on its
  * own (the last Lq rows of it), bit for bit when the pages hold what attnqat_quantize gives for K and V.
- * Workspace: attnqat_paged_workspace_bytes(B, Hq, Hkv, Lq, max_pages, d) (the dequantized fp16 copies of Q and of the
- * sequences' K and V, laid out for max_pages * 128 positions each; max_pages <= 8192); 0 for bad arguments.
+ * Workspace: attnqat_paged_workspace_bytes(B, Hq, Hkv, Lq, max_pages, d) (max_pages <= 8192); 0 for bad arguments.
+ * cache must be 16-byte aligned.
+ *
+ * Two paths, chosen by the number of query rows per (sequence, kv head), (Hq / Hkv) * Lq:
+ *   more than 16: the pages are unpacked into the fp16 K and V^T copies of attnqat_fwd_infer's kernel (the workspace
+ *     holds them, laid out for max_pages * 128 positions per sequence), which then runs with per-sequence lengths.
+ *   at most 16 (decode steps): one kernel reads the pages directly, once.  The keys of a sequence are cut into chunks
+ *     that workgroups take from a queue, so that long sequences do not set the pace of the step.  P-tilde is quantized
+ *     against the running maximum in key order (Alg. 1), which a chunk cannot know before the chunks in front of it have
+ *     computed their scores: every chunk first computes its scores (the K half of its pages), publishes its row maxima
+ *     in the workspace and waits for those of its predecessors, then does the rest (the V half).  Tickets are handed out
+ *     in chunk order, so a predecessor is always running or finished when someone waits for it and the wait ends; it is
+ *     bounded nevertheless (2^22 polls), and a wait that expired leaves a wrong result for that sequence.  The partial
+ *     sums of the chunks are added by whichever chunk finishes last.  The result is not bit-identical to
+ *     attnqat_fwd_infer (the sums are grouped differently) but holds the same parity bars against the oracle.
+ * attnqat_debug_fwd_infer_paged is the same call with the poll limit as an argument (tests force the expiry path with
+ * 0); it synchronizes the stream and sets *wait_expired (host) to 1 if any wait of the decode path ran out.
  */
 size_t attnqat_kv_cache_page_bytes_nvfp4(int Hkv, int d);
 int attnqat_kv_cache_write(const void* k, const void* v, int Hkv, int n, int d, int dtype, int pos0,
@@ -351,6 +366,10 @@ size_t attnqat_paged_workspace_bytes(int B, int Hq, int Hkv, int Lq, int max_pag
 int attnqat_fwd_infer_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
                             const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
                             void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+int attnqat_debug_fwd_infer_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
+                                  const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                                  void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream,
+                                  int spin_limit, int* wait_expired);
 
 /*
  * Block-sparse attention (Sec. 5: the paper's datacenter inference kernel supports it): attnqat_fwd_infer_mx with a

@@ -50,6 +50,7 @@ _SIGNATURES = {
     "attnqat_kv_cache_write": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp]),
     "attnqat_paged_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "attnqat_fwd_infer_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "attnqat_debug_fwd_infer_paged": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp, _i, _vp]),
     "attnqat_fwd_infer_mx_sparse": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_fwd_mx": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "attnqat_bwd_mx": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i,
@@ -217,9 +218,10 @@ def attnqat_kv_cache_write(k, v, cache, page_ids, pos0: int = 0, num_pages=None)
     _check(lib().attnqat_kv_cache_write(_ptr(k), _ptr(v), Hkv, n, d, BF16, int(pos0), _ptr(cache), int(num_pages), _ptr(page_ids), _stream()))
 
 
-def attnqat_fwd_infer_paged(q, cache, num_pages, page_table, kv_lens, Hkv, causal: bool, workspace=None, out=None):
+def attnqat_fwd_infer_paged(q, cache, num_pages, page_table, kv_lens, Hkv, causal: bool, workspace=None, out=None, spin_limit=None):
     """Alg. 1 over a paged NVFP4 KV cache.  q [B,Hq,Lq,d]: the last Lq positions of every sequence; page_table int32
-    [B,max_pages]; kv_lens int32 [B].  Returns (o bf16, lse fp32)."""
+    [B,max_pages]; kv_lens int32 [B].  Returns (o bf16, lse fp32); with spin_limit (test hook) also whether a wait of the
+    decode path expired."""
     _dev_bf16(q, "q")
     B, Hq, Lq, d = q.shape
     for t, n in ((page_table, "page_table"), (kv_lens, "kv_lens")):
@@ -236,6 +238,12 @@ def attnqat_fwd_infer_paged(q, cache, num_pages, page_table, kv_lens, Hkv, causa
     need = lib().attnqat_paged_workspace_bytes(B, Hq, Hkv, Lq, max_pages, d)
     if workspace is None:
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+    if spin_limit is not None:
+        expired = ctypes.c_int(0)
+        _check(lib().attnqat_debug_fwd_infer_paged(_ptr(q), B, Hq, Hkv, Lq, d, int(causal), BF16, _ptr(cache), int(num_pages),
+                                                   _ptr(page_table), max_pages, _ptr(kv_lens), _ptr(o), _ptr(lse), _ptr(workspace),
+                                                   workspace.numel(), _stream(), int(spin_limit), ctypes.addressof(expired)))
+        return o, lse, bool(expired.value)
     _check(lib().attnqat_fwd_infer_paged(_ptr(q), B, Hq, Hkv, Lq, d, int(causal), BF16, _ptr(cache), int(num_pages),
                                          _ptr(page_table), max_pages, _ptr(kv_lens),
                                          _ptr(o), _ptr(lse), _ptr(workspace), workspace.numel(), _stream()))

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattnqat.so")
-SOURCES = ["prep.hip", "fwd.hip", "bwd.hip", "mx.hip", "api.hip"]
+SOURCES = ["prep.hip", "fwd.hip", "bwd.hip", "mx.hip", "decode.hip", "api.hip"]
 # bench-only helper with its own library: measurement code stays out of the attention library and its ABI
 AUX_SRC = os.path.join(HERE, "benchaux", "mfma_burn.hip")
 AUX_LIB = os.path.join(HERE, "benchaux", "libattnqat_benchaux.so")

@@ -421,17 +421,61 @@ int attnqat_kv_cache_write(const void* k, const void* v, int Hkv, int n, int d, 
 }
 
 namespace {
-struct PagedWs { void *qh, *kh, *vt; size_t bytes; int Lkp; };
+// Few rows per (sequence, kv head): the decode kernel reads the pages itself (dec != null); otherwise the pages are unpacked
+// into the K / V^T copies of the general forward.
+struct PagedWs { void *qh, *kh, *vt, *dec; size_t bytes; int Lkp; };
 PagedWs carve_paged(void* ws, int B, int Hq, int Hkv, int Lq, int max_pages, int d)
 {
     Carver c{(unsigned char*)ws, 0};
-    PagedWs w;
-    w.Lkp = (int)round_up(max_pages * 128, kRowPad);
-    w.qh = c.take((size_t)B * Hq * round_up(Lq, kRowPad) * d * 2);
-    w.kh = c.take((size_t)B * Hkv * w.Lkp * d * 2);
-    w.vt = c.take((size_t)B * Hkv * w.Lkp * d * 2);
+    PagedWs w{};
+    const int R = (Hq / Hkv) * Lq;
+    if (R <= decode_max_rows()) {
+        w.qh = c.take((size_t)B * Hkv * kRowPad * d * 2);
+        w.dec = c.take(decode_ws_bytes(B, Hkv, R, max_pages, d));
+    } else {
+        w.Lkp = (int)round_up(max_pages * 128, kRowPad);
+        w.qh = c.take((size_t)B * Hq * round_up(Lq, kRowPad) * d * 2);
+        w.kh = c.take((size_t)B * Hkv * w.Lkp * d * 2);
+        w.vt = c.take((size_t)B * Hkv * w.Lkp * d * 2);
+    }
     w.bytes = c.off;
     return w;
+}
+
+constexpr int kDecodeSpinLimit = 1 << 22;       // polls (each at least a microsecond apart) before a chunk gives up waiting
+
+int paged_common(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
+                 const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                 void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream, int spin_limit, void** dec_ws)
+{
+    if (!q || !cache || !page_table || !kv_lens || !o || !lse || num_pages < 1 || max_pages < 1) return ATTNQAT_EINVAL;
+    if ((uintptr_t)cache & 15) return ATTNQAT_EINVAL;
+    int rc = check_dims(B, Hq, Hkv, Lq, d, dtype);
+    if (rc) return rc;
+    if (max_pages > (1 << 13) || (long long)B * Hkv > 65535) return ATTNQAT_ESHAPE;          // 2^20 keys per sequence
+    PagedWs w = carve_paged(workspace, B, Hq, Hkv, Lq, max_pages, d);
+    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    prof_begin(st);
+    if (w.dec) {
+        // q [B,Hq,Lq,d] is [B*Hkv, G*Lq, d] in memory: the rows of a kv group form one tile
+        if (launch_prep(q, B * Hkv, (Hq / Hkv) * Lq, d, true, true, nullptr, nullptr, nullptr, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
+        prof_mark("prep_q", st);
+        if (launch_decode(w.qh, cache, num_pages, page_table, max_pages, kv_lens, B, Hq, Hkv, Lq, d, causal != 0, w.dec, spin_limit, o, lse, st))
+            return ATTNQAT_ELAUNCH;
+        prof_mark("decode_paged", st);
+        if (dec_ws) *dec_ws = w.dec;
+        return ATTNQAT_OK;
+    }
+    if (dec_ws) *dec_ws = nullptr;
+    // phi(Q); K^F and V^F are in the cache already and only change layout
+    if (launch_prep(q, B * Hq, Lq, d, true, true, nullptr, nullptr, nullptr, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_unpack_pages(cache, page_table, kv_lens, B, Hkv, max_pages, num_pages, d, 0, w.kh, nullptr, st)) return ATTNQAT_ELAUNCH;
+    if (launch_unpack_pages(cache, page_table, kv_lens, B, Hkv, max_pages, num_pages, d, 1, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("prep_q_unpack_pages", st);
+    if (launch_fwd_varlen(w.qh, w.kh, w.vt, B, Hq, Hkv, Lq, w.Lkp, d, causal != 0, kv_lens, o, lse, st)) return ATTNQAT_ELAUNCH;
+    prof_mark("fwd_infer_paged", st);
+    return ATTNQAT_OK;
 }
 }  // namespace
 
@@ -445,21 +489,25 @@ int attnqat_fwd_infer_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d
                             const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
                             void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!q || !cache || !page_table || !kv_lens || !o || !lse || num_pages < 1 || max_pages < 1) return ATTNQAT_EINVAL;
-    int rc = check_dims(B, Hq, Hkv, Lq, d, dtype);
+    return paged_common(q, B, Hq, Hkv, Lq, d, causal, dtype, cache, num_pages, page_table, max_pages, kv_lens, o, lse,
+                        workspace, workspace_bytes, stream, kDecodeSpinLimit, nullptr);
+}
+
+int attnqat_debug_fwd_infer_paged(const void* q, int B, int Hq, int Hkv, int Lq, int d, int causal, int dtype,
+                                  const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                                  void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream,
+                                  int spin_limit, int* wait_expired)
+{
+    if (spin_limit < 0 || !wait_expired) return ATTNQAT_EINVAL;
+    void* dec = nullptr;
+    int rc = paged_common(q, B, Hq, Hkv, Lq, d, causal, dtype, cache, num_pages, page_table, max_pages, kv_lens, o, lse,
+                          workspace, workspace_bytes, stream, spin_limit, &dec);
     if (rc) return rc;
-    if (max_pages > (1 << 13) || (long long)B * Hkv > 65535) return ATTNQAT_ESHAPE;          // 2^20 keys per sequence
-    PagedWs w = carve_paged(workspace, B, Hq, Hkv, Lq, max_pages, d);
-    if (!workspace || workspace_bytes < w.bytes) return ATTNQAT_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    prof_begin(st);
-    // phi(Q); K^F and V^F are in the cache already and only change layout
-    if (launch_prep(q, B * Hq, Lq, d, true, true, nullptr, nullptr, nullptr, w.qh, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_unpack_pages(cache, page_table, kv_lens, B, Hkv, max_pages, num_pages, d, 0, w.kh, nullptr, st)) return ATTNQAT_ELAUNCH;
-    if (launch_unpack_pages(cache, page_table, kv_lens, B, Hkv, max_pages, num_pages, d, 1, nullptr, w.vt, st)) return ATTNQAT_ELAUNCH;
-    prof_mark("prep_q_unpack_pages", st);
-    if (launch_fwd_varlen(w.qh, w.kh, w.vt, B, Hq, Hkv, Lq, w.Lkp, d, causal != 0, kv_lens, o, lse, st)) return ATTNQAT_ELAUNCH;
-    prof_mark("fwd_infer_paged", st);
+    *wait_expired = 0;
+    if (dec) {
+        if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ATTNQAT_ELAUNCH;
+        if (hipMemcpy(wait_expired, (const unsigned char*)dec + 4, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return ATTNQAT_ELAUNCH;
+    }
     return ATTNQAT_OK;
 }
 

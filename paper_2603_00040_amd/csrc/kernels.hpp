@@ -44,6 +44,16 @@ int launch_kv_page_write(const void* k, const void* v, int Hkv, int n, int D, in
 int launch_unpack_pages(const void* cache, const int* page_table, const int* kv_lens, int B, int Hkv, int max_pages, int num_pages,
                         int D, int which, void* xr, void* xt, hipStream_t st);
 
+// Alg. 1 for decode steps over the NVFP4 pages: at most decode_max_rows() query rows per (sequence, kv head), i.e.
+// (Hq / Hkv) * Lq of them; qh [B*Hkv][128][D] fp16 is phi(Q) with the rows of a kv group together (launch_prep on q taken as
+// [B*Hkv, (Hq/Hkv)*Lq, D]).  ws: decode_ws_bytes() bytes.  spin_limit bounds the polls of a chunk waiting for the row maxima
+// of the chunks before it (see decode.hip); if it runs out the int at ws + 4 is set and that result is wrong.
+int decode_max_rows();
+int decode_chunk_keys(int R);
+size_t decode_ws_bytes(int B, int Hkv, int R, int max_pages, int D);
+int launch_decode(const void* qh, const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
+                  int B, int Hq, int Hkv, int Lq, int D, bool causal, void* ws, int spin_limit, void* o, float* lse, hipStream_t st);
+
 // Per-row statistics of the backward: rowstat [BHq, Lp, 2] = {L log2(e), D / sqrt(d)} with
 // D = rowsum(dO o O') (Alg. 3, first line); padding rows hold zeros.  d_o bf16, o_hp fp32, [rows, D].
 // o_acc: O' fp32, or (ablation) the bf16 O when o_is_bf16.

@@ -9,6 +9,11 @@ from tests.gpu_util import check_bf16_output, f32, host, max_abs, random_inputs,
 
 pytestmark = pytest.mark.gpu
 
+
+def host_bits(t):
+    """bf16 CUDA tensor -> its bit patterns (uint16 numpy)."""
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
 TOL = 2e-3
 
 
@@ -75,6 +80,40 @@ def test_decode_step(causal):
 def test_few_positions_grouped_heads(d, causal):
     _run(2, 2, d, [64, 65, 128, 129, 2500], 7, causal, seed=40 + d, k_chan=4)
     _run(16, 2, d, [4, 257, 1111], 4, causal, seed=41 + d)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+def test_decode_sequences_cut_into_chunks(d, causal):
+    # 4 rows per (sequence, kv head): chunks of 1024 keys, up to 5 of them; 12 rows: chunks of 256 keys, up to 12; 16 rows (the
+    # most the decode kernel takes); lengths at chunk and tile edges; more (sequence, head, chunk) units than workgroups wait for
+    _run(8, 2, d, [5000, 1030, 1024, 3, 2049], 1, causal, seed=50 + d, k_chan=4)
+    _run(8, 2, d, [3000, 700, 257], 3, causal, seed=51 + d)
+    _run(16, 1, d, [1500, 256], 1, causal, seed=52 + d, dist="t3", scale=0.5)
+
+
+def test_decode_wait_limit_is_honoured_and_leaves_no_state():
+    """The bounded wait of a chunk for the maxima of the chunks before it: with no polls allowed the kernel still finishes
+    (waits that found nothing are reported), and the next ordinary call is unaffected."""
+    import paper_2603_00040_amd as aq
+    Hq, Hkv, d, lens = 8, 2, 128, [6000, 4100, 5000, 2100]
+    x = random_inputs(len(lens), Hq, Hkv, max(lens), d, 77)
+    cache, num_pages, table = _fill_cache(aq, x, Hkv, d, lens, 77)
+    q = to_dev(np.ascontiguousarray(np.stack([x["q"][b, :, n - 1:n] for b, n in enumerate(lens)])))
+    tab, kl = torch.from_numpy(table).cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda")
+    o0, l0, expired0 = aq.attnqat_fwd_infer_paged(q, cache, num_pages, tab, kl, Hkv, True, spin_limit=0)
+    o1, l1, expired1 = aq.attnqat_fwd_infer_paged(q, cache, num_pages, tab, kl, Hkv, True, spin_limit=1 << 22)
+    o2, l2 = aq.attnqat_fwd_infer_paged(q, cache, num_pages, tab, kl, Hkv, True)
+    torch.cuda.synchronize()
+    print(f"decode wait limit 0: expired={expired0}; limit 2^22: expired={expired1}", flush=True)
+    assert expired1 is False
+    assert torch.equal(l1, l2)          # lse depends on the scores and the row sums of P-tilde only: the same in any order of arrival
+    for b, n in enumerate(lens):
+        qf = np.zeros((1, Hq, n, d), np.float32)
+        qf[0, :, n - 1:] = f32(host_bits(q[b]))
+        rows = oracle.flat_rows(1, Hq, n, [(0, h, n - 1) for h in range(Hq)])
+        ref = oracle.fwd(qf, f32(x["k"][b:b + 1, :, :n]), f32(x["v"][b:b + 1, :, :n]), True, aq.block_k(), rows=rows)
+        check_bf16_output("O", host(o2[b]).reshape(-1, d), ref["O"], TOL, label=f"sequence {b}")
 
 
 def test_whole_sequences_d64_gqa():
