@@ -259,7 +259,7 @@ def main():
     ap.add_argument("--bf16-pv", action="store_true",
                     help="the mixed recipe of Sec. 2.5 (nvfp4 format only): NVFP4 Q K^T, P-tilde and V in bf16; inference forward only")
     ap.add_argument("--paged-lq", type=int, default=0,
-                    help="serving mode (not a benchmark configuration): the MX forward over a paged FP4 KV cache with this many "
+                    help="serving mode (not a benchmark configuration): the forward over a paged FP4 KV cache (--format nvfp4 or mx) with this many "
                          "query positions per sequence (1 = a decode step) for 32 sequences of 4k-16k keys, 32 query / 8 kv heads")
     ap.add_argument("--sparse-keep", type=float, default=0.0,
                     help="block-sparse mode (not a benchmark configuration): the MX inference forward of the workload's shape "
@@ -366,8 +366,11 @@ def main():
 
 def bench_paged(args, aq, torch, np):
     """Serving shapes: 32 sequences with 4096..16384 keys (seeded), Hq = 32, Hkv = 8, d = 128, causal; the KV cache is
-    written once (untimed), a step is one attnqat_fwd_infer_mx_paged call over all sequences."""
+    written once (untimed), a step is one attnqat_fwd_infer_paged (--format nvfp4) or attnqat_fwd_infer_mx_paged (--format mx)
+    call over all sequences."""
     B, Hq, Hkv, d, Lq = 32, 32, 8, 128, args.paged_lq
+    nv = args.format == "nvfp4"
+    page_bytes = (aq.kv_cache_page_bytes_nvfp4 if nv else aq.kv_cache_page_bytes)(Hkv, d)
     rng = np.random.default_rng(7)
     kv_lens = rng.integers(4096, 16385, B).astype(np.int32)
     kv_lens = np.maximum(kv_lens, Lq)
@@ -376,7 +379,7 @@ def bench_paged(args, aq, torch, np):
     num_pages = sum(pages_of)
     perm = rng.permutation(num_pages).astype(np.int32)
     table = np.zeros((B, max_pages), np.int32)
-    cache = torch.empty(num_pages * aq.kv_cache_page_bytes(Hkv, d), dtype=torch.uint8, device="cuda")
+    cache = torch.empty(num_pages * page_bytes, dtype=torch.uint8, device="cuda")
     import workloads as W
     dev = lambda bits: torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
     nxt = 0
@@ -387,12 +390,20 @@ def bench_paged(args, aq, torch, np):
         k = dev(W.fill(1, Hkv, n, d, 500 + b, W.TENSOR_K, "normal", 1.0, n_chan=4, chan_mult=20.0))
         v = dev(W.fill(1, Hkv, n, d, 500 + b, W.TENSOR_V, "normal", 1.0))
         qb.append(W.fill(1, Hq, Lq, d, 500 + b, W.TENSOR_Q, "normal", 1.0)[0])
-        aq.attnqat_kv_cache_write_mx(k, v, cache, torch.from_numpy(table[b, :pages_of[b]].copy()).cuda(), num_pages)
+        ids = torch.from_numpy(table[b, :pages_of[b]].copy()).cuda()
+        if nv:
+            aq.attnqat_kv_cache_write(k, v, cache, ids, 0, num_pages)
+        else:
+            aq.attnqat_kv_cache_write_mx(k, v, cache, ids, num_pages)
     q = dev(np.ascontiguousarray(np.stack(qb)))
     tab, lens = torch.from_numpy(table).cuda(), torch.from_numpy(kv_lens).cuda()
     o = torch.empty_like(q); lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device="cuda")
-    ws = torch.empty(aq.workspace_bytes(aq.WS_FWD_INFER_MX_PAGED, B, Hq, Hkv, Lq, d), dtype=torch.uint8, device="cuda")
-    step = lambda: aq.attnqat_fwd_infer_mx_paged(q, cache, num_pages, tab, lens, Hkv, True, workspace=ws, out=(o, lse))
+    if nv:
+        ws = torch.empty(aq.lib().attnqat_paged_workspace_bytes(B, Hq, Hkv, Lq, max_pages, d), dtype=torch.uint8, device="cuda")
+        step = lambda: aq.attnqat_fwd_infer_paged(q, cache, num_pages, tab, lens, Hkv, True, workspace=ws, out=(o, lse))
+    else:
+        ws = torch.empty(aq.workspace_bytes(aq.WS_FWD_INFER_MX_PAGED, B, Hq, Hkv, Lq, d), dtype=torch.uint8, device="cuda")
+        step = lambda: aq.attnqat_fwd_infer_mx_paged(q, cache, num_pages, tab, lens, Hkv, True, workspace=ws, out=(o, lse))
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -405,24 +416,28 @@ def bench_paged(args, aq, torch, np):
     step(); torch.cuda.synchronize()
     kern = dict(aq.profile_read())
     aq.profile_enable(False)
-    kms = kern["fwd_infer_mx_paged"]
+    kname = next(n for n in ("decode_paged", "fwd_infer_paged", "fwd_infer_mx_paged") if n in kern)
+    kms = kern[kname]
     # causal chunk: query i of the last Lq positions sees kv_len - Lq + i + 1 keys
     pairs = float(sum(Hq * (Lq * (int(n) - Lq) + Lq * (Lq + 1) / 2) for n in kv_lens))
     flops = 4.0 * pairs * d
-    cache_bytes = float(sum(pages_of)) * aq.kv_cache_page_bytes(Hkv, d)          # every page of every sequence, once
-    decode = Lq <= 16
-    roofline = ({"bound": "hbm", "kernel": "fwd_infer_mx_paged", "achieved": round(cache_bytes / (kms * 1e-3) / 1e9, 1), "peak": 8000.0,
+    cache_bytes = float(sum(pages_of)) * page_bytes          # every page of every sequence, once
+    decode = Lq <= 16 if not nv else kname == "decode_paged"
+    mfma_peak = MFMA_PEAK_TFLOPS if nv else MFMA_FP4_PEAK_TFLOPS
+    roofline = ({"bound": "hbm", "kernel": kname, "achieved": round(cache_bytes / (kms * 1e-3) / 1e9, 1), "peak": 8000.0,
                  "unit": "GB/s", "frac": round(cache_bytes / (kms * 1e-3) / 8e12, 4), "traffic": None, "kernel_ms": round(kms, 3)}
                 if decode else
-                {"bound": "mfma", "kernel": "fwd_infer_mx_paged", "achieved": round(flops / (kms * 1e-3) / 1e12, 2), "peak": MFMA_FP4_PEAK_TFLOPS,
-                 "unit": "TFLOP/s", "frac": round(flops / (kms * 1e-3) / 1e12 / MFMA_FP4_PEAK_TFLOPS, 4), "traffic": None, "kernel_ms": round(kms, 3)})
+                {"bound": "mfma", "kernel": kname, "achieved": round(flops / (kms * 1e-3) / 1e12, 2), "peak": mfma_peak,
+                 "unit": "TFLOP/s", "frac": round(flops / (kms * 1e-3) / 1e12 / mfma_peak, 4), "traffic": None, "kernel_ms": round(kms, 3)})
     print(json.dumps({
         "metric": "FP4-attention fwd TFLOPS (1 MI355X)", "value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax", "data": "synthetic",
+        "vs_baseline": None,
+        "dtype": "f16 MFMA operands (exact NVFP4 values), fp32 accumulate and softmax" if nv
+                 else "fp4 (E2M1 codes with E8M0 block scales) MFMA operands, fp32 accumulate and softmax", "data": "synthetic",
         "config": {"workload": "serving_paged_kv (not a benchmark configuration)", "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "Lq": Lq,
                    "kv_len_min": int(kv_lens.min()), "kv_len_max": int(kv_lens.max()), "kv_len_sum": int(kv_lens.sum()), "causal": True,
-                   "page_keys": 128, "cache_bytes": int(cache_bytes), "format": "mx"},
+                   "page_keys": 128, "cache_bytes": int(cache_bytes), "format": args.format},
         "tokens_per_s": round(B * Lq / (ms * 1e-3), 1), "per_kernel_ms": {k_: round(v_, 3) for k_, v_ in kern.items()},
         "roofline": roofline, "cpu_baseline": None}), flush=True)
 
