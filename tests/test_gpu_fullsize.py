@@ -307,12 +307,17 @@ def test_full_size_block_sparse_forward(cfg):
     assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(rf["L"]).max())
 
 
+@pytest.mark.parametrize("fmt", ["mx", "nvfp4"])
 @pytest.mark.parametrize("Lq", [1, 512])
-def test_full_size_paged_serving(Lq):
-    """attnqat_fwd_infer_mx_paged on the serving shape bench.py --paged-lq times (32 sequences of 4096..16384 keys, 32 query
-    and 8 kv heads, d = 128, causal, pages scattered over the cache): a decode step and a 512-query chunk; O and L of
-    sampled (sequence, head, position) against the oracle's MX forward of that sequence."""
+def test_full_size_paged_serving(Lq, fmt):
+    """attnqat_fwd_infer_mx_paged / attnqat_fwd_infer_paged on the serving shape bench.py --paged-lq times (32 sequences of
+    4096..16384 keys, 32 query and 8 kv heads, d = 128, causal, pages scattered over the cache): a decode step (NVFP4: the
+    kernel that cuts sequences into chunks, up to 16 per sequence here) and a 512-query chunk; O and L of sampled (sequence,
+    head, position) against the oracle's forward of that sequence in the same format."""
     import paper_2603_00040_amd as aq
+    nv = fmt == "nvfp4"
+    page_bytes, write, fwd = ((aq.kv_cache_page_bytes_nvfp4, aq.attnqat_kv_cache_write, aq.attnqat_fwd_infer_paged) if nv else
+                              (aq.kv_cache_page_bytes, aq.attnqat_kv_cache_write_mx, aq.attnqat_fwd_infer_mx_paged))
     B, Hq, Hkv, d = 32, 32, 8, 128
     rng = np.random.default_rng(7)
     kv_lens = np.maximum(rng.integers(4096, 16385, B), Lq).astype(np.int32)
@@ -320,7 +325,7 @@ def test_full_size_paged_serving(Lq):
     max_pages, num_pages = max(pages_of), sum(pages_of)
     perm = rng.permutation(num_pages).astype(np.int32)
     table = np.zeros((B, max_pages), np.int32)
-    cache = torch.empty(num_pages * aq.kv_cache_page_bytes(Hkv, d), dtype=torch.uint8, device="cuda")
+    cache = torch.empty(num_pages * page_bytes(Hkv, d), dtype=torch.uint8, device="cuda")
     cache.random_(0, 256)
     check = sorted({0, B - 1, int(np.argmin(kv_lens)), int(np.argmax(kv_lens))})
     kept, qb, nxt = {}, [], 0
@@ -331,13 +336,12 @@ def test_full_size_paged_serving(Lq):
         kb = W.fill(1, Hkv, n, d, 500 + bb, W.TENSOR_K, "normal", 1.0, n_chan=4, chan_mult=20.0)
         vb = W.fill(1, Hkv, n, d, 500 + bb, W.TENSOR_V, "normal", 1.0)
         qf = W.fill(1, Hq, Lq, d, 500 + bb, W.TENSOR_Q, "normal", 1.0)
-        aq.attnqat_kv_cache_write_mx(to_dev(kb), to_dev(vb), cache, torch.from_numpy(table[bb, :pages_of[bb]].copy()).cuda())
+        write(to_dev(kb), to_dev(vb), cache, torch.from_numpy(table[bb, :pages_of[bb]].copy()).cuda())
         qb.append(qf[0])
         if bb in check:
             kept[bb] = (kb, vb)
     qall = np.ascontiguousarray(np.stack(qb))
-    o, lse = aq.attnqat_fwd_infer_mx_paged(to_dev(qall), cache, num_pages, torch.from_numpy(table).cuda(),
-                                           torch.from_numpy(kv_lens).cuda(), Hkv, True)
+    o, lse = fwd(to_dev(qall), cache, num_pages, torch.from_numpy(table).cuda(), torch.from_numpy(kv_lens).cuda(), Hkv, True)
     torch.cuda.synchronize()
     assert not torch.isnan(o.float()).any() and not torch.isnan(lse).any()
     pos = sorted({0, Lq - 1, Lq // 2, *np.random.default_rng(8).integers(0, Lq, 3).tolist()})
@@ -347,8 +351,8 @@ def test_full_size_paged_serving(Lq):
         qf = np.zeros((1, Hq, n, d), np.float32)
         qf[0, :, n - Lq:] = f32(qall[bb])
         rows = oracle.flat_rows(1, Hq, n, [(0, h, n - Lq + i) for h in range(Hq) for i in pos])
-        ref = oracle.fwd(qf, f32(kb), f32(vb), True, aq.block_k(), scale_mode=oracle.MX, rows=rows)
+        ref = oracle.fwd(qf, f32(kb), f32(vb), True, aq.block_k(), scale_mode=0 if nv else oracle.MX, rows=rows)
         got_o = host(o[bb][:, pos]).reshape(-1, d); got_l = host(lse[bb][:, pos]).reshape(-1)
         eO = rel_l2(got_o, ref["O"]); eL = max_abs(got_l, ref["L"])
-        print(f"[paged Lq={Lq}] sequence {bb} ({n} keys): O rel-L2 {eO:.2e}  L max-abs {eL:.2e} on {rows.size} rows", flush=True)
+        print(f"[paged {fmt} Lq={Lq}] sequence {bb} ({n} keys): O rel-L2 {eO:.2e}  L max-abs {eL:.2e} on {rows.size} rows", flush=True)
         assert eO <= TOL and eL <= 2e-5 * max(1.0, np.abs(ref["L"]).max())
