@@ -36,10 +36,10 @@ def _traffic(gb, source):
 
 
 TRAFFIC_BEYOND_L2 = {
-    "dit720p_train": {k: _traffic(v, "profiles/hbm_traffic_dit720p_train.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate runs; "
-                                     "kernels as of commit 63a7b2d)")
-                      for k, v in {"fwd_train": 20.0, "bwd_dq": 33.0, "bwd_dkdv": 707.4}.items()},
-    "dit480p_infer": {"fwd_infer_mx": _traffic(1.116, "profiles/dit480p_infer_mx_fwd_kernels.txt (kernels as of commit 63a7b2d)")},
+    "dit720p_train": {k: _traffic(v, "profiles/hbm_traffic_dit720p_train.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate runs, scaled by "
+                                     "the copy-kernel calibration; stored from that run, not collected live)")
+                      for k, v in {"fwd_train": 17.5 + 4.09, "bwd_dq": 56.5 + 0.77, "bwd_dkdv": 758.6 + 1.56}.items()},
+    "dit480p_infer": {"fwd_infer_mx": _traffic(0.883, "profiles/dit480p_infer_mx_fwd_kernels.txt (FETCH_SIZE, scaled; stored from that run)")},
 }
 
 
@@ -267,6 +267,9 @@ def main():
     ap.add_argument("--mfma-sustained", action="store_true",
                     help="measurement only: the 16-bit MFMA rate and clock the part sustains with nothing else running "
                          "(context for the roofline fractions, which are quoted against the published 2.5 PFLOP/s)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="measurement only: three launches of a plain 1 GiB copy kernel (reads 1 GiB, writes 1 GiB), the known-size "
+                         "kernel against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
     ap.add_argument("--passes", default="auto", choices=["auto", "fwd_infer"],
                     help="auto: the passes of the workload; fwd_infer: the inference forward (Alg. 1) on the workload's shape")
     ap.add_argument("--per-config", default="auto", choices=["auto", "on", "off"],
@@ -300,6 +303,13 @@ def main():
         print(json.dumps({"metric": "sustained v_mfma_f32_32x32x16_f16 rate, register operands, 2 waves per SIMD (1 MI355X)",
                           "value": round(tf, 1), "unit": "TFLOP/s", "n_gpus": 1, "clock_ghz": round(ghz, 3),
                           "published_peak": MFMA_PEAK_TFLOPS, "frac_of_published_peak": round(tf / MFMA_PEAK_TFLOPS, 4)}), flush=True)
+        return
+    if args.copy_calibration:
+        from paper_2603_00040_amd import benchaux
+        nbytes, ms = benchaux.copy_calibration()
+        print(json.dumps({"metric": "plain copy kernel (1 MI355X)", "value": round(2.0 * nbytes / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                          "n_gpus": 1, "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes, "launches": 3,
+                          "kernel": "copy16_kernel", "ms": round(ms, 4)}), flush=True)
         return
     if args.paged_lq > 0:
         return bench_paged(args, aq, torch, np)

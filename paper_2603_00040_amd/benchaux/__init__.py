@@ -1,4 +1,5 @@
-"""Bench-only helper (not part of the attention library): the 16-bit MFMA rate the GPU sustains on its own."""
+"""Bench-only helpers (not part of the attention library): the 16-bit MFMA rate the GPU sustains on its own, and a copy
+kernel of known size for calibrating the profiler's traffic counters."""
 import ctypes
 import os
 
@@ -16,7 +17,27 @@ def _load():
         _lib = ctypes.CDLL(LIB_PATH)
         _lib.benchaux_mfma_burn.restype = ctypes.c_int
         _lib.benchaux_mfma_burn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        _lib.benchaux_copy.restype = ctypes.c_int
+        _lib.benchaux_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     return _lib
+
+
+def copy_calibration(gib: float = 1.0, launches: int = 3):
+    """Runs the plain copy kernel on `gib` GiB `launches` times (reads and writes exactly that many bytes per launch) and
+    returns (bytes per launch, ms of the last launch)."""
+    lib = _load()
+    n = int(gib * (1 << 30)) // 16 * 16
+    src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(launches):
+        e0.record()
+        if lib.benchaux_copy(src.data_ptr(), dst.data_ptr(), n, st):
+            raise RuntimeError("benchaux_copy failed")
+        e1.record()
+        torch.cuda.synchronize()
+    return n, e0.elapsed_time(e1)
 
 
 def mfma_sustained(rounds: int = 4, iters: int = 40000):

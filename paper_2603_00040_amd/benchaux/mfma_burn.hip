@@ -56,3 +56,21 @@ extern "C" int benchaux_mfma_burn(int blocks, int iters, float* out, unsigned lo
     hipLaunchKernelGGL(mfma_burn_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, out, clk, iters);
     return hipGetLastError() == hipSuccess ? 0 : -5;
 }
+
+namespace {
+// Plain grid-stride copy, 16 bytes per lane and step: the known-size kernel against which the profiler's traffic
+// counters are calibrated.
+__global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+}  // namespace
+
+// Copies `bytes` (a multiple of 16) from src to dst (device, 16-byte aligned, not overlapping): reads and writes exactly
+// that many bytes.  Only enqueues.  Returns 0, -1 for bad arguments, -5 if the launch failed.
+extern "C" int benchaux_copy(const void* src, void* dst, size_t bytes, void* stream)
+{
+    if (!src || !dst || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return -1;
+    hipLaunchKernelGGL(copy16_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, bytes / 16);
+    return hipGetLastError() == hipSuccess ? 0 : -5;
+}
