@@ -200,6 +200,18 @@ int attnqat_debug_fwd_p(const void* q, const void* k, const void* v,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Test hook: attnqat_bwd that also writes P^F = phi^-1(phi(P)), the re-quantized recomputed P that enters
+ * dV = P^F^T dO (Alg. 3), for the 128 query rows [row0, row0+128) of every head and all keys: p_dump [B,Hq,128,L] fp32
+ * (device).  The caller zeroes it before the call: tiles of 32 queries x 32 keys in which every block scale rounds to 0
+ * are skipped (their P^F is 0) and not written, nor are masked keys and rows beyond L.
+ */
+int attnqat_debug_bwd_p(const void* q, const void* k, const void* v, const void* d_o,
+                        const float* lse, const float* o_hp,
+                        int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                        void* dq, void* dk, void* dv, int row0, float* p_dump,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The NVFP4 forward and backward with options that Sec. 3.2 studies inside QAT (SageAttention's heuristics):
  *   ATTNQAT_OPT_SMOOTH_K   K smoothing (Sec. 2.1): phi is applied to K minus its mean over the tokens, per
  *                          (batch, kv head, channel).  S changes by a per-query constant that softmax ignores

@@ -62,6 +62,7 @@ _SIGNATURES = {
     "attnqat_strerror": (ctypes.c_char_p, [_i]),
     "attnqat_debug_fwd_p": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp,
                                  _vp, _sz, _vp]),
+    "attnqat_debug_bwd_p": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "attnqat_debug_dkdv_tile_counts": (_i, [_vp, _vp]),
     "attnqat_profile_enable": (_i, [_vp, _i]),
     "attnqat_profile_read": (_i, [_vp, _i, _vp, _vp]),
@@ -261,6 +262,19 @@ def attnqat_debug_fwd_p_opt(q, k, v, causal: bool, row0: int, options: int):
     _check(lib().attnqat_debug_fwd_p_opt(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, L, d, int(causal), BF16, int(options),
                                          _ptr(o), _ptr(lse), row0, _ptr(p), _ptr(ws), nb, _stream()))
     return o, lse, p
+
+
+def attnqat_debug_bwd_p(q, k, v, d_o, lse, o_hp, causal: bool, row0: int):
+    """attnqat_bwd that also returns P^F (the re-quantized recomputed P of Alg. 3) of query rows [row0, row0+128):
+    (dq, dk, dv, p [B,Hq,128,L] fp32)."""
+    B, Hq, L, d = q.shape
+    Hkv = k.shape[1]
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    p = torch.zeros((B, Hq, 128, L), dtype=torch.float32, device=q.device)
+    ws, nb = _workspace(WS_BWD, B, Hq, Hkv, L, d, None)
+    _check(lib().attnqat_debug_bwd_p(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(o_hp), B, Hq, Hkv, L, d, int(causal), BF16,
+                                     _ptr(dq), _ptr(dk), _ptr(dv), int(row0), _ptr(p), _ptr(ws), nb, _stream()))
+    return dq, dk, dv, p
 
 
 def attnqat_fwd_opt(q, k, v, causal: bool, options: int, train: bool = True, workspace=None, out=None):

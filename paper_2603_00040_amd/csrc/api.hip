@@ -667,8 +667,10 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
                       const float* lse, const void* o_acc, bool o_is_bf16, int p_quant /* 0 none, 1 NVFP4, 2 MX; 3 (two-level) is set from the options */,
                       int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
                       void* dq, void* dk, void* dv,
-                      void* workspace, size_t workspace_bytes, void* stream, int options = 0, const PackedQKV* packed = nullptr)
+                      void* workspace, size_t workspace_bytes, void* stream, int options = 0, const PackedQKV* packed = nullptr,
+                      float* p_dump = nullptr, int dump_row0 = 0)
 {
+    if (p_dump && (p_quant != 1 || (options & ATTNQAT_OPT_TWO_LEVEL_P))) return ATTNQAT_EINVAL;
     if (packed) {
         if (!packed->qc || !packed->qs || !packed->kc || !packed->ks || !packed->vc || !packed->vs) return ATTNQAT_EINVAL;
         if (((uintptr_t)packed->qc | (uintptr_t)packed->kc | (uintptr_t)packed->vc) & 7) return ATTNQAT_EINVAL;
@@ -712,7 +714,7 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
     if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv,
-                        dkdv_counts_of(st), p_quant, st))
+                        dkdv_counts_of(st), p_quant, st, p_dump, dump_row0))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;
@@ -748,6 +750,17 @@ int attnqat_bwd_opt(const void* q, const void* k, const void* v, const void* d_o
 {
     return bwd_common(q, k, v, d_o, lse, o_hp, false, 1, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
                       workspace, workspace_bytes, stream, options);
+}
+
+int attnqat_debug_bwd_p(const void* q, const void* k, const void* v, const void* d_o,
+                        const float* lse, const float* o_hp,
+                        int B, int Hq, int Hkv, int L, int d, int causal, int dtype,
+                        void* dq, void* dk, void* dv, int row0, float* p_dump,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!p_dump || row0 < 0 || row0 % 128 != 0) return ATTNQAT_EINVAL;
+    return bwd_common(q, k, v, d_o, lse, o_hp, false, 1, B, Hq, Hkv, L, d, causal, dtype, dq, dk, dv,
+                      workspace, workspace_bytes, stream, 0, nullptr, p_dump, row0);
 }
 
 int attnqat_bwd_mx(const void* q, const void* k, const void* v, const void* d_o,

@@ -431,13 +431,14 @@ struct DkvSmem {
     float rmax[4][32];               // two-level P: per wave, the largest P of every query row over the wave's 32 keys
 };
 
-template <int D, bool CAUSAL, bool COUNT /* measurement variant: count tiles */,
+template <int D, bool CAUSAL, bool COUNT /* measurement / test variant: count tiles, dump P^F */,
           int PQ /* phi(P): 0 none (ablation: dV from the fp32 P), 1 NVFP4, 2 MX, 3 NVFP4 after the two-level row factor */>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
     uint16_t* __restrict__ dK, uint16_t* __restrict__ dV, unsigned long long* __restrict__ tile_counts,
-    int L, int Lp, int Hq, int G, int NHq, float c, float rs)
+    int L, int Lp, int Hq, int G, int NHq, float c, float rs,
+    float* __restrict__ pdump /* COUNT only, may be null: P^F of query rows [dump_row0, dump_row0 + 128), [B*Hq][128][L] */, int dump_row0)
 {
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
     constexpr int NWL = (32 * KCH) / 64;             // 1 KiB wave-loads per tile of 32 rows
@@ -697,6 +698,16 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                         uint2v wp;
                         wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
                         lds_write8_at(tw_ad + (uint32_t)(16 * (r0 >> 2)), wp);
+                        if constexpr (COUNT) {
+                            const int qr = q0 + ln;      // registers r0 .. r0 + 3: keys key0_w + 8 t4 + 4 hf + e of query row qr
+                            if (pdump && qr >= dump_row0 && qr < dump_row0 + 128 && qr < L) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const int key = key0_w + 8 * t4 + 4 * hf + e;
+                                    if (key < L) pdump[((size_t)(bh0 + cur_g) * 128 + (qr - dump_row0)) * L + key] = pf[e];
+                                }
+                            }
+                        }
                     }
                 }
             }
@@ -798,7 +809,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
         asm volatile("" : "+v"(st_n.x), "+v"(st_n.y));     // the next tile's row scalars are consumed here, not earlier
     }
 
-    if (COUNT && lane == 0) {
+    if (COUNT && lane == 0 && tile_counts) {
         atomicAdd(&tile_counts[0], (unsigned long long)n_tiles);
         atomicAdd(&tile_counts[1], (unsigned long long)n_pf_tiles);
     }
@@ -821,35 +832,35 @@ template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
                          int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts,
-                         int p_quant, hipStream_t st)
+                         int p_quant, hipStream_t st, float* p_dump, int dump_row0)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DkvSmem<D>);
     auto kern = p_quant == 0 ? bwd_dkdv_kernel<D, CAUSAL, false, 0>
               : p_quant == 2 ? bwd_dkdv_kernel<D, CAUSAL, false, 2>
               : p_quant == 3 ? bwd_dkdv_kernel<D, CAUSAL, false, 3>
-              : tile_counts ? bwd_dkdv_kernel<D, CAUSAL, true, 1> : bwd_dkdv_kernel<D, CAUSAL, false, 1>;
-    if (p_quant != 1) tile_counts = nullptr;
+              : (tile_counts || p_dump) ? bwd_dkdv_kernel<D, CAUSAL, true, 1> : bwd_dkdv_kernel<D, CAUSAL, false, 1>;
+    if (p_quant != 1) { if (p_dump) return -1; tile_counts = nullptr; }
     if (p_quant < 0 || p_quant > 3) return -1;
     static unsigned long long lds_set[5] = {0, 0, 0, 0, 0};      // one per variant of this instantiation
-    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set[p_quant == 1 && tile_counts ? 4 : p_quant])) return -1;
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set[p_quant == 1 && (tile_counts || p_dump) ? 4 : p_quant])) return -1;
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
                        (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv, tile_counts,
-                       L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs, rs);
+                       L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs, rs, p_dump, dump_row0);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
-                    unsigned long long* tile_counts, int p_quant, hipStream_t st)
+                    unsigned long long* tile_counts, int p_quant, hipStream_t st, float* p_dump, int dump_row0)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st)
-                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st);
-    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st)
-                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0)
+                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0);
+    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0)
+                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0);
     return -1;
 }
 

@@ -129,3 +129,34 @@ def test_dkdv_tile_count_hook():
     assert nonzero == int(tile_nz.sum())
     for a, b in zip(ref, got):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_PF_code_flips_in_the_backward(causal):
+    """P^F = phi^-1(phi(P)) of the recomputed P (Alg. 3), the operand of dV, element by element against the oracle's: short
+    rows, so that the block scales do not round to zero and every tile is quantized.  Both sides are fed the oracle's L."""
+    import paper_2603_00040_amd as aq
+    B, Hq, Hkv, L, d = 1, 4, 2, 200, 128
+    x = random_inputs(B, Hq, Hkv, L, d, seed=41, k_chan=4)
+    q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
+    fq, fk, fv, fdo = (f32(x[n]) for n in ("q", "k", "v", "do"))
+    rf = oracle.fwd(fq, fk, fv, causal, aq.block_k())
+    lse = torch.from_numpy(rf["L"].astype(np.float32)).cuda()
+    ohp = torch.from_numpy(rf["Op"].astype(np.float32)).cuda()
+    G = Hq // Hkv
+    keys = np.arange(L, dtype=np.int64)
+    bad = tot = nonzero = 0
+    for row0 in (0, 128):
+        _, _, _, p = aq.attnqat_debug_bwd_p(q, k, v, do, lse, ohp, causal, row0)
+        torch.cuda.synchronize()
+        nrow = min(128, L - row0)
+        got = p.cpu().numpy()[0, :, :nrow]                                    # [Hq, rows, keys]
+        for hk in range(Hkv):
+            _, _, P = oracle.bwd_dkdv_keys(fq, fk, fv, fdo, 0, hk, keys, rf["L"][0, hk * G:(hk + 1) * G], rf["Op"][0, hk * G:(hk + 1) * G],
+                                           causal, dump_p=True)             # [keys, G, queries]
+            ref = np.transpose(P, (1, 2, 0))[:, row0:row0 + nrow]             # [G, rows, keys]
+            g = got[hk * G:(hk + 1) * G]
+            bad += int((g != ref).sum()); tot += ref.size; nonzero += int((ref != 0).sum())
+    print(f"backward P^F flips causal{int(causal)}: {bad} of {tot} ({bad / tot:.2e}); {nonzero} non-zero", flush=True)
+    assert nonzero > 0.05 * tot * (0.5 if causal else 1.0)          # enough quantized elements for the count to mean something
+    assert bad / tot < 1e-4
