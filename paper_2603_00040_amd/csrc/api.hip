@@ -117,7 +117,7 @@ int check_dims(int B, int Hq, int Hkv, int L, int d, int dtype)
 }
 
 // Workspace of the forward: fp16 Q^F, K^F (row-major) and V^F^T.
-struct FwdWs { void *qh, *kh, *vt, *tmp; double* kpart; float* kmean; size_t bytes; };
+struct FwdWs { void *qh, *kh, *vt, *tmp, *qsc; double* kpart; float* kmean; size_t bytes; };
 FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 {
     const size_t Lp = round_up(L, kRowPad);
@@ -127,6 +127,8 @@ FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
     w.kh = c.take((size_t)B * Hkv * Lp * d * 2);
     w.vt = c.take((size_t)B * Hkv * Lp * d * 2);
     w.tmp = mx ? c.take((size_t)B * Hq * L * d * 2) : nullptr;      // MX: the dequantized bf16 tensor before its layout copy
+    // MX: qh and kh hold the operands of the FP4 instruction (smaller than the fp16 copies); the Q scale dwords come extra
+    w.qsc = mx ? c.take(mx_qsc_bytes(B * Hq, L)) : nullptr;
     w.kpart = (double*)c.take(colmean_scratch_bytes(B * Hkv, d));  // K smoothing: partial sums and the token mean of K
     w.kmean = (float*)c.take((size_t)B * Hkv * d * 4);
     w.bytes = c.off;
@@ -191,6 +193,17 @@ int fwd_common(const void* q, const void* k, const void* v, int B, int Hq, int H
     hipStream_t st = (hipStream_t)stream;
     prof_begin(st);
     // Alg. 1 line "phi(Q), phi(K), phi(V)" / Alg. 2 line "Q^F, K^F, V^F"
+    if (mx) {
+        // Q and K as operands of the scaled FP4 instruction (the scores are computed from the codes), V^F^T as the fp16 copy
+        if (launch_mx_quant(q, B * Hq, L, d, 0, 1, false, (unsigned char*)w.qh, (unsigned char*)w.qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
+        if (launch_mx_quant(k, B * Hkv, L, d, 0, 3, false, (unsigned char*)w.kh, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+        if (quant_copy(v, B * Hkv, L, d, true, 1, true, nullptr, w.vt, w.tmp, st)) return ATTNQAT_ELAUNCH;
+        prof_mark("prep_qkv", st);
+        if (launch_fwd(w.qh, w.kh, w.vt, B, Hq, Hkv, L, d, causal != 0, train, 1, o, lse, o_hp, dump_row0, p_dump, st, w.qsc))
+            return ATTNQAT_ELAUNCH;
+        prof_mark(train ? "fwd_train" : "fwd_infer", st);
+        return ATTNQAT_OK;
+    }
     if (quant_copy(q, B * Hq, L, d, mx, 0, true, w.qh, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
     const float* kmean = nullptr;
     if (options & ATTNQAT_OPT_SMOOTH_K) {          // K minus its token mean (Sec. 2.1), then phi

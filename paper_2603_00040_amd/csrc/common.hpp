@@ -96,6 +96,9 @@ __device__ inline uint32_t e8m0_of_amax_fp8(float amax) {
 __device__ inline float e8m0_as_f32(uint32_t byte) { return __uint_as_float(byte << 23); }            // 1 <= byte <= 254
 __device__ inline float e8m0_inverse_as_f32(uint32_t byte) { return __uint_as_float((254u - byte) << 23); }   // 1 <= byte <= 253
 
+// Bytes of one 64-key K record of the MX training forward (operands of the scaled FP4 instruction and their scale dwords).
+__host__ __device__ constexpr int mx_ktrain_rec_bytes(int D) { return 2 * (D / 64) * 1024 + 1024; }
+
 // max(a, b) written as median(a, b, +inf): fmaxf() on values the compiler cannot prove quiet (MFMA
 // results) costs a canonicalizing v_max per operand, the median has no such requirement and the
 // compiler folds chains of it into v_max3.  No NaN reaches these reductions.

@@ -39,8 +39,17 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     const half_t* __restrict__ Qh, const half_t* __restrict__ Kh, const half_t* __restrict__ Vt,
     uint16_t* __restrict__ O, float* __restrict__ lse, float* __restrict__ Ohp,
     int L, int Lp, int Hq, int G, float c /* log2(e)/sqrt(d) */, int dump_row0, float* __restrict__ pdump,
-    int Lkp_arg, const int* __restrict__ kv_lens)
+    int Lkp_arg, const int* __restrict__ kv_lens, const uint32_t* __restrict__ Qsc)
 {
+    // PQ == 1 (MX): S = Q^F K^F^T comes from the E2M1 codes and E8M0 scales by v_mfma_scale_f32_32x32x64_f8f6f4 (a quarter of
+    // the matrix time of the 16-bit products, a quarter of the K bytes through LDS).  Qh then holds the Q operands of that
+    // instruction (64 d per step: lane (row, half) has d-slots 64 ks + 32 half .. + 31 of its row) with one dword of scale
+    // bytes per lane in Qsc, and Kh the K records of mx_ktrain_rec_bytes(D) bytes per key tile.  The accumulator layout is
+    // that of the 16-bit products, so everything after the scores is unchanged (O and O' stay 16-bit products: O' needs the
+    // un-quantized P-tilde, which is no operand of that instruction).
+    constexpr bool MXS = PQ == 1;
+    constexpr int KSM = D / 64, KREC = mx_ktrain_rec_bytes(D);
+    typedef int int8v __attribute__((ext_vector_type(8)));
     constexpr int DS = D / 16;      // contraction steps of S
     constexpr int MB = D / 32;      // 32-row blocks of O^T
     constexpr int KCH = D / 8;      // 16-byte chunks per K row
@@ -97,9 +106,15 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     }
     const half_t* k_head = Kh + (size_t)bhkv * Lkp * D;      // [key][d]
     const half_t* v_head = Vt + (size_t)bhkv * D * Lkp;      // [d][key]
+    const unsigned char* k_recs = reinterpret_cast<const unsigned char*>(Kh) + (size_t)bhkv * (Lkp / 64) * KREC;
     auto issue_k = [&](int buf, int jt) __attribute__((always_inline)) {
+        if constexpr (MXS) {      // a record is KREC / 1024 wave copies of 1 KiB
+            if (wave < KREC / 1024)
+                async_copy16(k_recs + (size_t)jt * KREC, (uint32_t)(wave * 1024 + lane * 16), reinterpret_cast<unsigned char*>(&sm.k[buf][0]) + wave * 1024);
+        } else {
 #pragma unroll
-        for (int i = 0; i < KLD; ++i) async_copy16(k_head + (size_t)jt * (64 * D), k_ld[i], &sm.k[buf][512 * (wave * KLD + i)]);
+            for (int i = 0; i < KLD; ++i) async_copy16(k_head + (size_t)jt * (64 * D), k_ld[i], &sm.k[buf][512 * (wave * KLD + i)]);
+        }
     };
     auto issue_v = [&](int buf, int jt) __attribute__((always_inline)) {
 #pragma unroll
@@ -112,8 +127,16 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     const int q_row = row0_w + ln;
 
     // Q^F operand: this lane's query row, d-slots 16*ds + 8*hf .. +7
-    half8 qreg[DS];
-    {
+    half8 qreg[MXS ? 1 : DS];
+    uint4v qop[MXS ? KSM : 1];
+    uint32_t qs = 0u;
+    if constexpr (MXS) {
+        const size_t grp = (size_t)bh * (Lp / 32) + ((has_rows ? row0_w : 0) >> 5);
+        const unsigned char* qo = reinterpret_cast<const unsigned char*>(Qh);
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks) qop[ks] = *reinterpret_cast<const uint4v*>(qo + ((grp * KSM + ks) * 64 + lane) * 16);
+        qs = Qsc[grp * 64 + lane];
+    } else {
         const half_t* qp = Qh + ((size_t)bh * Lp + (has_rows ? q_row : 0)) * D + 8 * hf;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) qreg[ds] = *reinterpret_cast<const half8*>(qp + 16 * ds);
@@ -137,6 +160,28 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     // read latency is ~130 cycles, so the K operands are read RING steps ahead of the MFMA that consumes
     // them (the scheduling groups keep the compiler from sinking them).
     auto scores = [&](int buf) __attribute__((always_inline)) {
+        if constexpr (MXS) {
+            const uint32_t rec = lds_addr_of(kbase) + (uint32_t)(buf * (int)sizeof(sm.k[0]));
+            const uint32_t ksc = *(const __attribute__((address_space(3))) uint32_t*)(uintptr_t)(rec + 2 * KSM * 1024 + lane * 4);
+            uint4v a[2][KSM];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int ks = 0; ks < KSM; ++ks) a[kb][ks] = lds_read16_at(rec + (uint32_t)(((kb * KSM + ks) * 64 + lane) * 16));
+            auto as8 = [](const uint4v& x) __attribute__((always_inline)) -> int8v {
+                int8v r = {(int)x[0], (int)x[1], (int)x[2], (int)x[3], 0, 0, 0, 0};
+                return r;
+            };
+            const floatx16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+            // (format codes 4, 4: both operands E2M1; the scale operands are a dword of four bytes and the index of the byte)
+            s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][0]), as8(qop[0]), zero, 4, 4, 0, ksc, 0, qs);
+            s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][0]), as8(qop[0]), zero, 4, 4, KSM, ksc, 0, qs);
+            if constexpr (KSM == 2) {
+                s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][1]), as8(qop[1]), s[0], 4, 4, 1, ksc, 1, qs);
+                s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][1]), as8(qop[1]), s[1], 4, 4, 3, ksc, 1, qs);
+            }
+            return;
+        }
         // per-lane offset of this tile, opaque to the compiler: it would otherwise hoist every
         // (offset ^ constant) out of the loop and pay for it with registers
         int k_it = k_rd + buf * (int)sizeof(sm.k[0]) + (int)lds_addr_of(kbase);
@@ -172,8 +217,14 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
     if (nkt > 1) issue_k(1, 1);
     // The Q registers must have arrived BEFORE the loop: a load still pending at loop entry makes the
     // compiler wait for all vector-memory traffic at the first product of every iteration.
+    if constexpr (MXS) {
 #pragma unroll
-    for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(qreg[ds]));
+        for (int ks = 0; ks < KSM; ++ks) asm volatile("" : "+v"(qop[ks]));
+        asm volatile("" : "+v"(qs));
+    } else {
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(qreg[ds]));
+    }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (has_rows) scores(0);
@@ -509,8 +560,9 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
 template <int D, bool TRAIN, bool CAUSAL, bool DUMP, int PQ, bool VARLEN = false>
 static int launch_t(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int L,
                     void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st,
-                    int Lkp = 0, const int* kv_lens = nullptr)
+                    int Lkp = 0, const int* kv_lens = nullptr, const void* qsc = nullptr)
 {
+    if (PQ == 1 && !qsc) return -1;
     const int Lp = round_up(L, kRowPad);
     const int nqt = (Lp + 255) / 256;
     const int per_head = CAUSAL ? (nqt + 1) / 2 : nqt;         // under a causal mask a workgroup takes a long and a short tile
@@ -521,34 +573,34 @@ static int launch_t(const void* qh, const void* kh, const void* vt, int B, int H
     const float c = 1.4426950408889634f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * per_head)), dim3(512), smem, st,
                        (const half_t*)qh, (const half_t*)kh, (const half_t*)vt, (uint16_t*)o, lse, o_hp,
-                       L, Lp, Hq, Hq / Hkv, c, dump_row0, p_dump, Lkp, kv_lens);
+                       L, Lp, Hq, Hq / Hkv, c, dump_row0, p_dump, Lkp, kv_lens, (const uint32_t*)qsc);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 template <int D, int PQ>
 static int launch_d(const void* qh, const void* kh, const void* vt, int B, int Hq, int Hkv, int L,
                     bool causal, bool train, void* o, float* lse, float* o_hp,
-                    int dump_row0, float* p_dump, hipStream_t st)
+                    int dump_row0, float* p_dump, hipStream_t st, const void* qsc)
 {
     if (p_dump) {
-        return causal ? launch_t<D, false, true, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st)
-                      : launch_t<D, false, false, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st);
+        return causal ? launch_t<D, false, true, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st, 0, nullptr, qsc)
+                      : launch_t<D, false, false, true, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, dump_row0, p_dump, st, 0, nullptr, qsc);
     }
     if constexpr (PQ != 3) {
         if (train) {
-            return causal ? launch_t<D, true, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
-                          : launch_t<D, true, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+            return causal ? launch_t<D, true, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st, 0, nullptr, qsc)
+                          : launch_t<D, true, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st, 0, nullptr, qsc);
         }
     }
-    return causal ? launch_t<D, false, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st)
-                  : launch_t<D, false, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st);
+    return causal ? launch_t<D, false, true, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st, 0, nullptr, qsc)
+                  : launch_t<D, false, false, false, PQ>(qh, kh, vt, B, Hq, Hkv, L, o, lse, o_hp, 0, nullptr, st, 0, nullptr, qsc);
 }
 
 int launch_fwd(const void* qh, const void* kh, const void* vt,
                int B, int Hq, int Hkv, int L, int D, bool causal, bool train, int p_quant,
-               void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st)
+               void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st, const void* qsc)
 {
-#define AQ_FWD(DD, PQ) launch_d<DD, PQ>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st)
+#define AQ_FWD(DD, PQ) launch_d<DD, PQ>(qh, kh, vt, B, Hq, Hkv, L, causal, train, o, lse, o_hp, dump_row0, p_dump, st, qsc)
     if (p_quant == 3 && train) return -1;           // the bf16 P V recipe has no backward
     if (D == 128) return p_quant == 1 ? AQ_FWD(128, 1) : p_quant == 2 ? AQ_FWD(128, 2) : p_quant == 3 ? AQ_FWD(128, 3) : AQ_FWD(128, 0);
     if (D == 64)  return p_quant == 1 ? AQ_FWD(64, 1) : p_quant == 2 ? AQ_FWD(64, 2) : p_quant == 3 ? AQ_FWD(64, 3) : AQ_FWD(64, 0);

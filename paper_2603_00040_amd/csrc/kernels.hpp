@@ -25,11 +25,13 @@ size_t colmean_scratch_bytes(int BH, int D);
 int launch_colmean(const void* x, int BH, int L, int D, double* scratch, float* mean, hipStream_t st);
 
 // Alg. 1 (train=false) / Alg. 2 (train=true) on fp16 copies made by launch_prep.
+// p_quant 1 (MX): qh and kh are NOT fp16 copies but the operand arrays of the scaled FP4 instruction (launch_mx_quant mode 1
+// for Q, with its scale dwords in qsc, and mode 3 for K): the scores are computed from the codes; vt stays the fp16 copy.
 // p_quant: phi(P-tilde) 0 NVFP4; 1 in the MX format (blocks of 32 keys, power-of-two scale); 2 NVFP4 after the
 // two-level row factor (every 64-key tile row divided by a power of two that brings its maximum just below 448 * 6).
 int launch_fwd(const void* qh, const void* kh, const void* vt,
                int B, int Hq, int Hkv, int L, int D, bool causal, bool train, int p_quant,
-               void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st);
+               void* o, float* lse, float* o_hp, int dump_row0, float* p_dump, hipStream_t st, const void* qsc = nullptr);
 
 // Alg. 1 for sequences of different lengths (serving): queries are the last Lq positions of every sequence, sequence b has
 // kv_lens[b] keys (device array), kh / vt are laid out for Lkp positions per kv head.
@@ -84,6 +86,7 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
 //   mode 0: public layout (codes, scales, optional bf16 xf, see attnqat.h)
 //   mode 1: Q operands of the scaled MFMA (axis 0 only): codes -> operand array, scales -> scale dwords
 //   mode 2: the K part (axis 0) or the V part (axis 1) of the 64-key kv records at `codes`
+//   mode 3: K records of the training forward (axis 0 only): natural key order, see mx.hip
 // fp8: E4M3 elements instead of E2M1 (axis 1 only); with axis 0 and mode 2 it selects the record layout whose V part is FP8.
 // page_ids (mode 2, FP4 only; device int32, one entry per 128 positions): the records go into the pages of a KV cache
 // laid out [page][kv head][2 records] instead of one after another; BH then is the number of kv heads of ONE sequence.
@@ -91,6 +94,7 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
 int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
                     unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids = nullptr, int num_pages = 0);
 size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v);
+size_t mx_ktrain_bytes(int BHkv, int L, int D);      // K records of the MX training forward (launch_mx_quant mode 3)
 size_t mx_qops_bytes(int BHq, int L, int D);
 size_t mx_qsc_bytes(int BHq, int L);
 // Alg. 1 on the arrays made by launch_mx_quant (modes 1 and 2).  fp8pv: P-tilde and V in MXFP8 (mixed recipe).

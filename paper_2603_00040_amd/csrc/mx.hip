@@ -99,6 +99,10 @@ __device__ inline int mx_srow_of_key(int kk) { const int w = kk & 15; return 8 *
 //   MODE 0: public layout   codes [rows, D/2], scales [rows, D/32], optional bf16 xf
 //   MODE 1: Q operands      ops [rows/32, D/64, 64 lanes, 16 B], sc [rows/32, 64 lanes] (byte ks)
 //   MODE 2: K part of the kv records
+//   MODE 3: K records of the training forward (16-bit P V, scores on the FP4 instruction): per 64-key tile
+//           mx_ktrain_rec_bytes(D) bytes = ops [2 blocks of 32 keys][D/64][64 lanes][16 B] with the keys of a block in their
+//           natural order as operand rows (so that the score tile has the accumulator layout of the 16-bit kernels), then
+//           per lane one dword of scale bytes (byte = block * D/64 + ks), padded to a whole KiB
 template <int D, int MODE, bool FP8V = false /* MODE 2: records whose V part is FP8 */>
 __global__ __launch_bounds__(256) void mx_quant_d_kernel(
     const uint16_t* __restrict__ x, int L, int Lp, unsigned char* __restrict__ codes, unsigned char* __restrict__ scales,
@@ -155,6 +159,14 @@ __global__ __launch_bounds__(256) void mx_quant_d_kernel(
         scales[(grp * 64 + lane) * 4 + ks] = (unsigned char)byte;
         if (KS == 1) { scales[(grp * 64 + lane) * 4 + 1] = 1; }
         if (ks == 0) { scales[(grp * 64 + lane) * 4 + 2] = 1; scales[(grp * 64 + lane) * 4 + 3] = 1; }
+    } else if (MODE == 3) {
+        constexpr int REC = mx_ktrain_rec_bytes(D), KOPS = 2 * KS * 1024;
+        const int tile = row >> 6, kk = row & 63, kb = kk >> 5;
+        const int ks = blk >> 1, lane = (blk & 1) * 32 + (kk & 31);
+        unsigned char* rec = codes + ((size_t)bh * (Lp / 64) + tile) * REC;
+        *reinterpret_cast<uint4v*>(rec + ((kb * KS + ks) * 64 + lane) * 16) = c;
+        rec[KOPS + lane * 4 + kb * KS + ks] = (unsigned char)byte;
+        if (KS == 1 && kb == 0) { rec[KOPS + lane * 4 + 2] = 1; rec[KOPS + lane * 4 + 3] = 1; }
     } else {
         constexpr int REC = mx_rec_bytes(D, FP8V), KOPS = 2 * KS * 1024, VOPS = NB * (FP8V ? 2048 : 1024);
         const int tile = row >> 6, kk = row & 63, t = (kk >> 4) & 1;
@@ -736,6 +748,7 @@ static int quant_d(const void* x, int BH, int L, int mode, bool fp8v, unsigned c
     const int rows = mode == 0 ? L : Lp;
     const dim3 grid((unsigned)(((size_t)rows * (D / 32) + 255) / 256), (unsigned)BH);
     if (mode == 0)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 0>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
+    else if (mode == 3) hipLaunchKernelGGL((mx_quant_d_kernel<D, 3>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
     else if (mode == 1) hipLaunchKernelGGL((mx_quant_d_kernel<D, 1>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
     else if (fp8v)      hipLaunchKernelGGL((mx_quant_d_kernel<D, 2, true>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
     else                hipLaunchKernelGGL((mx_quant_d_kernel<D, 2>), grid, dim3(256), 0, st, (const uint16_t*)x, L, Lp, codes, scales, (uint16_t*)xf, page_ids, num_pages);
@@ -756,13 +769,14 @@ static int quant_l(const void* x, int BH, int L, int mode, unsigned char* codes,
 int launch_mx_quant(const void* x, int BH, int L, int D, int axis, int mode, bool fp8,
                     unsigned char* codes, unsigned char* scales, void* xf, hipStream_t st, const int* page_ids, int num_pages)
 {
-    if (BH > 65535 || (axis == 0 && fp8 && mode != 2) || (page_ids && (mode != 2 || fp8))) return -1;
+    if (BH > 65535 || (axis == 0 && fp8 && mode != 2) || (page_ids && (mode != 2 || fp8)) || (mode == 3 && axis != 0)) return -1;
     if (axis == 0) return D == 128 ? quant_d<128>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, num_pages, st) : quant_d<64>(x, BH, L, mode, fp8, codes, scales, xf, page_ids, num_pages, st);
     if (fp8) return D == 128 ? quant_l<128, true>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st) : quant_l<64, true>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st);
     return D == 128 ? quant_l<128, false>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st) : quant_l<64, false>(x, BH, L, mode, codes, scales, xf, page_ids, num_pages, st);
 }
 
 size_t mx_kv_bytes(int BHkv, int L, int D, bool fp8v) { return (size_t)BHkv * (round_up(L, kRowPad) / 64) * mx_rec_bytes(D, fp8v); }
+size_t mx_ktrain_bytes(int BHkv, int L, int D) { return (size_t)BHkv * (round_up(L, kRowPad) / 64) * mx_ktrain_rec_bytes(D); }
 size_t mx_qops_bytes(int BHq, int L, int D) { return (size_t)BHq * round_up(L, kRowPad) * (D / 2); }
 size_t mx_qsc_bytes(int BHq, int L) { return (size_t)BHq * (round_up(L, kRowPad) / 32) * 64 * 4; }
 size_t mx_page_bytes(int D) { return 2 * (size_t)mx_rec_bytes(D, false); }
