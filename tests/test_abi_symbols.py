@@ -34,8 +34,10 @@ def test_host_side_queries_need_no_gpu():
     ksm = Hkv * 32 * d * 8 + Hkv * d * 4
     assert aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d) == (Hq + 2 * Hkv) * Lp * d * 2 + ksm
     assert aq.workspace_bytes(aq.WS_BWD, B, Hq, Hkv, L, d) == (2 * Hq + 2 * Hkv) * Lp * d * 2 + Hq * Lp * 8 + 3 * Hq * 64 * 4 + ksm
-    # the MX training path adds the dequantized bf16 tensor that the MX fake-quantizer hands to the layout copy
-    assert aq.workspace_bytes(aq.WS_FWD_MX, B, Hq, Hkv, L, d) == aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d) + Hq * L * d * 2
+    # the MX training path adds the dequantized bf16 tensor that the MX fake-quantizer hands to the layout copy (V), and one
+    # dword of scale bytes per lane and group of 32 query rows for the Q operands of the FP4 instruction
+    assert aq.workspace_bytes(aq.WS_FWD_MX, B, Hq, Hkv, L, d) == (aq.workspace_bytes(aq.WS_FWD, B, Hq, Hkv, L, d) + Hq * L * d * 2
+                                                                  + Hq * (Lp // 32) * 64 * 4)
     assert aq.workspace_bytes(aq.WS_FWD, B, Hq, 3, L, d) == 0
     assert aq.workspace_bytes(99, B, Hq, Hkv, L, d) == 0
 
