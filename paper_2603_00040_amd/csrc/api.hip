@@ -137,7 +137,8 @@ FwdWs carve_fwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 
 // Workspace of the backward: row-major copies (Q^F, K^F fp16; V^F and dO bf16: dO is not exactly
 // representable in fp16), the per-row {L, D} pairs and the partial maxima that bound |dS|.
-struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; float* bounds; void* tmp; double* kpart; float* kmean; size_t bytes; };
+struct BwdWs { void *qb, *kb, *vb, *dob; float* rowstat; float* bounds; void* tmp; double* kpart; float* kmean; size_t bytes;
+               void *qops, *qsc, *kops, *ksc, *krec; };
 BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
 {
     const size_t Lp = round_up(L, kRowPad);
@@ -150,6 +151,12 @@ BwdWs carve_bwd(void* ws, int B, int Hq, int Hkv, int L, int d, bool mx = false)
     w.tmp = mx ? c.take((size_t)B * Hq * L * d * 2) : nullptr;
     w.kpart = (double*)c.take(colmean_scratch_bytes(B * Hkv, d));
     w.kmean = (float*)c.take((size_t)B * Hkv * d * 4);
+    // MX: the operand arrays of the FP4 instruction from which both passes recompute the scores
+    w.qops = mx ? c.take(mx_qops_bytes(B * Hq, L, d)) : nullptr;
+    w.qsc  = mx ? c.take(mx_qsc_bytes(B * Hq, L)) : nullptr;
+    w.kops = mx ? c.take(mx_qops_bytes(B * Hkv, L, d)) : nullptr;
+    w.ksc  = mx ? c.take(mx_qsc_bytes(B * Hkv, L)) : nullptr;
+    w.krec = mx ? c.take(mx_ktrain_bytes(B * Hkv, L, d)) : nullptr;
     w.bytes = c.off;
     return w;
 }
@@ -718,16 +725,22 @@ static int bwd_common(const void* q, const void* k, const void* v, const void* d
     if (quant_copy(v, B * Hkv, L, d, mx, 1, false, w.vb, nullptr, w.tmp, st)) return ATTNQAT_ELAUNCH;
     }
     if (launch_prep(d_o, B * Hq, L, d, false, false, nullptr, nullptr, nullptr, w.dob, nullptr, st)) return ATTNQAT_ELAUNCH;
+    MxScoreOps mxo{w.qops, w.qsc, w.kops, w.ksc, w.krec};
+    if (mx) {
+        if (launch_mx_quant(q, B * Hq, L, d, 0, 1, false, (unsigned char*)w.qops, (unsigned char*)w.qsc, nullptr, st)) return ATTNQAT_ELAUNCH;
+        if (launch_mx_quant(k, B * Hkv, L, d, 0, 1, false, (unsigned char*)w.kops, (unsigned char*)w.ksc, nullptr, st)) return ATTNQAT_ELAUNCH;
+        if (launch_mx_quant(k, B * Hkv, L, d, 0, 3, false, (unsigned char*)w.krec, nullptr, nullptr, st)) return ATTNQAT_ELAUNCH;
+    }
     prof_mark("prep_qkvdo", st);
     if (launch_delta(d_o, o_acc, o_is_bf16, lse, B * Hq, L, d, w.rowstat, st)) return ATTNQAT_ELAUNCH;
     prof_mark("delta", st);
     if (launch_bounds(w.vb, w.dob, w.rowstat, B * Hkv, B * Hq, L, d, w.bounds, st)) return ATTNQAT_ELAUNCH;
     prof_mark("bounds", st);
-    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dq, st))
+    if (launch_bwd_dq(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dq, st, mx ? &mxo : nullptr))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dq", st);
     if (launch_bwd_dkdv(w.qb, w.kb, w.vb, w.dob, w.rowstat, w.bounds, B, Hq, Hkv, L, d, causal != 0, dk, dv,
-                        dkdv_counts_of(st), p_quant, st, p_dump, dump_row0))
+                        dkdv_counts_of(st), p_quant, st, p_dump, dump_row0, mx ? &mxo : nullptr))
         return ATTNQAT_ELAUNCH;
     prof_mark("bwd_dkdv", st);
     return ATTNQAT_OK;

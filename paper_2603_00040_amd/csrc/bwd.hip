@@ -185,22 +185,34 @@ int launch_bounds(const void* vb, const void* dob, const float* rowstat, int BHk
 }
 
 // ------------------------------------------------------------------ dQ pass
-template <int D>
+template <int D, bool MXS>
 struct DqSmem {
     uint16_t k[2][64 * D];       // K^F tile [key][d], fp16, swizzled
     uint16_t v[2][64 * D];       // V^F tile [key][d], bf16, swizzled
+    unsigned char krec[MXS ? 2 : 1][MXS ? mx_ktrain_rec_bytes(D) : 16];      // MX: K operands of the FP4 instruction and their scales
 };
 
-template <int D, bool CAUSAL>
+typedef int int8v_t __attribute__((ext_vector_type(8)));
+__device__ inline int8v_t fp4_opnd(const uint4v& x) {
+    int8v_t r = {(int)x[0], (int)x[1], (int)x[2], (int)x[3], 0, 0, 0, 0};
+    return r;
+}
+
+// MXS (the MX format): S^T = K^F Q^F^T is recomputed from the E2M1 codes and E8M0 scales by v_mfma_scale_f32_32x32x64_f8f6f4
+// (Qops / Qsc: operands and scale dwords of the query rows, launch_mx_quant mode 1; Krec: the K records of mode 3); the
+// accumulator layout is that of the 16-bit products, and dP, dS and dQ are computed as before (dO, dS are 16-bit values).
+template <int D, bool CAUSAL, bool MXS>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb,
     const float2* __restrict__ rowstat, const float* __restrict__ bound_part, uint16_t* __restrict__ dQ,
-    int L, int Lp, int Hq, int G, int NHq, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */)
+    int L, int Lp, int Hq, int G, int NHq, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */,
+    const unsigned char* __restrict__ Qops, const uint32_t* __restrict__ Qsc, const unsigned char* __restrict__ Krec)
 {
     constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, KLD = KCH / 4;
+    constexpr int KSM = D / 64, KREC = mx_ktrain_rec_bytes(D);
     extern __shared__ __align__(256) unsigned char smem_raw[];
-    DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
+    DqSmem<D, MXS>& sm = *reinterpret_cast<DqSmem<D, MXS>*>(smem_raw);
 
     const int nqt = Lp / 128;
     int bh, qt;
@@ -212,13 +224,20 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: LDS destinations and branches use it
     const int q_row = qt * 128 + wave * 32 + ln;
 
-    uint4v qreg[DS], doreg[DS];
+    uint4v qreg[MXS ? 1 : DS], doreg[DS], qop[MXS ? KSM : 1];
+    uint32_t qs = 0u;
     {
         const size_t off = ((size_t)bh * Lp + q_row) * D + 8 * hf;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
-            qreg[ds] = *reinterpret_cast<const uint4v*>(Qb + off + 16 * ds);
+            if constexpr (!MXS) qreg[ds] = *reinterpret_cast<const uint4v*>(Qb + off + 16 * ds);
             doreg[ds] = *reinterpret_cast<const uint4v*>(dOb + off + 16 * ds);
+        }
+        if constexpr (MXS) {
+            const size_t grp = (size_t)bh * (Lp / 32) + ((qt * 128 + wave * 32) >> 5);
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks) qop[ks] = *reinterpret_cast<const uint4v*>(Qops + ((grp * KSM + ks) * 64 + lane) * 16);
+            qs = Qsc[grp * 64 + lane];
         }
     }
     const float2 st_ = rowstat[(size_t)bh * Lp + q_row];
@@ -254,11 +273,16 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     }
     const uint16_t* k_head = Kb + (size_t)bhkv * Lp * D;
     const uint16_t* v_head = Vb + (size_t)bhkv * Lp * D;
+    const unsigned char* k_recs = MXS ? Krec + (size_t)bhkv * (Lp / 64) * KREC : nullptr;
     auto issue_tile = [&](int buf, int jt) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < KLD; ++i) {
             async_copy16(k_head + (size_t)jt * (64 * D), kv_ld[i], &sm.k[buf][512 * (wave * KLD + i)]);
             async_copy16(v_head + (size_t)jt * (64 * D), kv_ld[i], &sm.v[buf][512 * (wave * KLD + i)]);
+        }
+        if constexpr (MXS) {
+            for (int i = wave; i < KREC / 1024; i += 4)
+                async_copy16(k_recs + (size_t)jt * KREC, (uint32_t)(i * 1024 + lane * 16), &sm.krec[buf][i * 1024]);
         }
     };
 
@@ -292,7 +316,15 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     // makes the compiler wait for all vector-memory traffic at the first product of every iteration,
     // i.e. for the tile prefetch it has just issued.
 #pragma unroll
-    for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(qreg[ds]), "+v"(doreg[ds]));
+    for (int ds = 0; ds < DS; ++ds) {
+        if constexpr (!MXS) asm volatile("" : "+v"(qreg[ds]));
+        asm volatile("" : "+v"(doreg[ds]));
+    }
+    if constexpr (MXS) {
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks) asm volatile("" : "+v"(qop[ks]));
+        asm volatile("" : "+v"(qs));
+    }
     asm volatile("" :: "v"(Ls), "v"(rs_s), "v"(Dq_s));
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -305,6 +337,41 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         const bool active = !CAUSAL || k0 <= wave_qmax;
         if (active) {
             floatx16 s[2], dp[2];
+            if constexpr (MXS) {
+                // S^T from the codes (2 * D/64 products), then dP^T = V^F dO^T: 2*DS steps, step i: ds = i/2, kb = i%2
+                const uint32_t rec = lds_addr_of(&sm.krec[BUF][0]);
+                const uint32_t ksc = *(const __attribute__((address_space(3))) uint32_t*)(uintptr_t)(rec + 2 * KSM * 1024 + lane * 4);
+                uint4v a[2][KSM];
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int ks = 0; ks < KSM; ++ks) a[kb][ks] = lds_read16_at(rec + (uint32_t)(((kb * KSM + ks) * 64 + lane) * 16));
+                const floatx16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+                s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_opnd(a[0][0]), fp4_opnd(qop[0]), zero, 4, 4, 0, ksc, 0, qs);
+                s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_opnd(a[1][0]), fp4_opnd(qop[0]), zero, 4, 4, KSM, ksc, 0, qs);
+                if constexpr (KSM == 2) {
+                    s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_opnd(a[0][1]), fp4_opnd(qop[1]), s[0], 4, 4, 1, ksc, 1, qs);
+                    s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_opnd(a[1][1]), fp4_opnd(qop[1]), s[1], 4, 4, 3, ksc, 1, qs);
+                }
+                mfma_scale_settle(s[0], s[1]);
+                constexpr int NST = 2 * DS, RING = 6;
+                auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
+                    return lds_read16_at(koff[i >> 1] + (uint32_t)(BUF * kTileB + kVfromK + (i & 1) * (32 * D * 2)));
+                };
+                uint4v ring[RING];
+#pragma unroll
+                for (int i = 0; i < RING; ++i) ring[i] = opnd(i);
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) dp[kb][i] = 0.0f;
+#pragma unroll
+                for (int i = 0; i < NST; ++i) {
+                    const uint4v av = ring[i % RING];
+                    if (i + RING < NST) ring[i % RING] = opnd(i + RING);
+                    dp[i & 1] = mfma_bf16(av, doreg[i >> 1], dp[i & 1]);
+                }
+            } else
             {   // S^T = K^F Q^F^T and dP^T = V^F dO^T: 4*DS steps, step i: ds = i/4, kb = (i/2)%2, K or V = i%2
                 constexpr int NST = 4 * DS, RING = 6;
                 auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
@@ -390,31 +457,36 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     }
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool MXS>
 static int launch_dq_t(const void* qb, const void* kb, const void* vb, const void* dob,
-                       const float* rowstat, const float* bound_part, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st)
+                       const float* rowstat, const float* bound_part, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st,
+                       const MxScoreOps* mx)
 {
     const int Lp = round_up(L, kRowPad);
-    const size_t smem = sizeof(DqSmem<D>);
-    auto kern = bwd_dq_kernel<D, CAUSAL>;
+    const size_t smem = sizeof(DqSmem<D, MXS>);
+    auto kern = bwd_dq_kernel<D, CAUSAL, MXS>;
     static unsigned long long lds_set = 0;          // one per instantiation
     if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float rs = 1.0f / sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
                        (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv, B * Hq,
-                       1.4426950408889634f * rs, rs);
+                       1.4426950408889634f * rs, rs,
+                       (const unsigned char*)(mx ? mx->qops : nullptr), (const uint32_t*)(mx ? mx->qsc : nullptr),
+                       (const unsigned char*)(mx ? mx->krec : nullptr));
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
                   const float* rowstat, const float* bound_part,
-                  int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st)
+                  int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st, const MxScoreOps* mx)
 {
-    if (D == 128) return causal ? launch_dq_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st);
-    if (D == 64)  return causal ? launch_dq_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st)
-                                : launch_dq_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st);
+    if (mx && (!mx->qops || !mx->qsc || !mx->krec)) return -1;
+#define AQ_DQ(DD, C) (mx ? launch_dq_t<DD, C, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st, mx) \
+                         : launch_dq_t<DD, C, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st, nullptr))
+    if (D == 128) return causal ? AQ_DQ(128, true) : AQ_DQ(128, false);
+    if (D == 64)  return causal ? AQ_DQ(64, true) : AQ_DQ(64, false);
+#undef AQ_DQ
     return -1;
 }
 
@@ -423,12 +495,13 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 // operands) and walks over the query rows of every query head of the group in tiles of 32.
 constexpr int kTPad = 36;            // row length (elements) of the per-wave [query][key] staging tiles
 
-template <int D>
+template <int D, bool MXS>
 struct DkvSmem {
     uint16_t q[2][32 * D];           // Q^F rows [query][d], fp16, swizzled
     uint16_t g[2][32 * D];           // dO rows  [query][d], bf16, swizzled
     uint16_t t[4][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
     float rmax[4][32];               // two-level P: per wave, the largest P of every query row over the wave's 32 keys
+    unsigned char qrec[MXS ? 2 : 1][MXS ? (D / 64) * 1024 + 256 : 16];      // MX: Q operands of the FP4 instruction of a tile and their scale dwords
 };
 
 template <int D, bool CAUSAL, bool COUNT /* measurement / test variant: count tiles, dump P^F */,
@@ -438,13 +511,17 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
     uint16_t* __restrict__ dK, uint16_t* __restrict__ dV, unsigned long long* __restrict__ tile_counts,
     int L, int Lp, int Hq, int G, int NHq, float c, float rs,
-    float* __restrict__ pdump /* COUNT only, may be null: P^F of query rows [dump_row0, dump_row0 + 128), [B*Hq][128][L] */, int dump_row0)
+    float* __restrict__ pdump /* COUNT only, may be null: P^F of query rows [dump_row0, dump_row0 + 128), [B*Hq][128][L] */, int dump_row0,
+    const unsigned char* __restrict__ Qops, const uint32_t* __restrict__ Qsc,      // PQ == 2 (MX) only: the scores come from the
+    const unsigned char* __restrict__ Kops, const uint32_t* __restrict__ Ksc)      // codes, see bwd_dq_kernel
 {
+    constexpr bool MXS = PQ == 2;
+    constexpr int KSM = D / 64, QREC = KSM * 1024 + 256;
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
     constexpr int NWL = (32 * KCH) / 64;             // 1 KiB wave-loads per tile of 32 rows
     constexpr int PER_WAVE = NWL >= 4 ? NWL / 4 : 1;
     extern __shared__ __align__(256) unsigned char smem_raw[];   // XORs of address bits 5..7 below commute with adding this base
-    DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
+    DkvSmem<D, MXS>& sm = *reinterpret_cast<DkvSmem<D, MXS>*>(smem_raw);
 
     const int nkt = Lp / 128;
     int bhkv, kt_;
@@ -456,13 +533,20 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const int key0_w = kt_ * 128 + wave * 32;       // this wave's first key
 
     // K^F, V^F rows of this lane's key: A operands (row = key, d-slots 16*ds + 8*hf)
-    uint4v kreg[DS], vreg[DS];
+    uint4v kreg[MXS ? 1 : DS], vreg[DS], kop[MXS ? KSM : 1];
+    uint32_t ksc = 0u;
     {
         const size_t off = ((size_t)bhkv * Lp + key0_w + ln) * D + 8 * hf;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
-            kreg[ds] = *reinterpret_cast<const uint4v*>(Kb + off + 16 * ds);
+            if constexpr (!MXS) kreg[ds] = *reinterpret_cast<const uint4v*>(Kb + off + 16 * ds);
             vreg[ds] = *reinterpret_cast<const uint4v*>(Vb + off + 16 * ds);
+        }
+        if constexpr (MXS) {
+            const size_t grp = (size_t)bhkv * (Lp / 32) + (key0_w >> 5);
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks) kop[ks] = *reinterpret_cast<const uint4v*>(Kops + ((grp * KSM + ks) * 64 + lane) * 16);
+            ksc = Ksc[grp * 64 + lane];
         }
     }
 
@@ -512,6 +596,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
                 async_copy16(dOb + row0 * D, slot_off[i], &sm.g[buf][512 * (wave * PER_WAVE + i)]);
             }
         }
+        if constexpr (MXS) {      // the tile's Q operands (KSM wave copies of 1 KiB) and their 64 scale dwords
+            const size_t grp = (bh0 + ld_g) * (Lp / 32) + (size_t)(qt_first + ld_t);
+            if (wave < KSM) async_copy16(Qops + grp * (KSM * 1024), (uint32_t)(wave * 1024 + lane * 16), &sm.qrec[buf][wave * 1024]);
+            if (wave == 3 && lane < 16) async_copy16(Qsc + grp * 64, (uint32_t)(lane * 16), &sm.qrec[buf][KSM * 1024]);
+        }
         if (++ld_t == per_head) { ld_t = 0; ++ld_g; }
     };
 
@@ -540,7 +629,15 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     if (niter > 0) { issue_next(0); st_n = rowstat[bh0 * Lp + (size_t)qt_first * 32 + ln]; }
     // every load of the prologue must have arrived before the loop (see the dQ pass)
 #pragma unroll
-    for (int ds = 0; ds < DS; ++ds) asm volatile("" : "+v"(kreg[ds]), "+v"(vreg[ds]));
+    for (int ds = 0; ds < DS; ++ds) {
+        if constexpr (!MXS) asm volatile("" : "+v"(kreg[ds]));
+        asm volatile("" : "+v"(vreg[ds]));
+    }
+    if constexpr (MXS) {
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks) asm volatile("" : "+v"(kop[ks]));
+        asm volatile("" : "+v"(ksc));
+    }
     asm volatile("" : "+v"(st_n.x), "+v"(st_n.y));
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -569,6 +666,34 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
             int a_it = a_rd + buf * kBufB + lds0, g_it0 = g_rd[0] + buf * kBufB + lds0, g_it1 = g_rd[1] + buf * kBufB + lds0;
             asm volatile("" : "+v"(a_it), "+v"(g_it0), "+v"(g_it1));
             floatx16 s, dp;
+            if constexpr (MXS) {
+                // S^T from the codes (D/64 products), then dP^T = V^F dO^T over the dO tile (DS steps)
+                const uint32_t rec = lds_addr_of(&sm.qrec[buf][0]);
+                const uint32_t qsl = *(const __attribute__((address_space(3))) uint32_t*)(uintptr_t)(rec + KSM * 1024 + lane * 4);
+                uint4v bq4[KSM];
+#pragma unroll
+                for (int ks = 0; ks < KSM; ++ks) bq4[ks] = lds_read16_at(rec + (uint32_t)((ks * 64 + lane) * 16));
+                const floatx16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+                s = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_opnd(kop[0]), fp4_opnd(bq4[0]), zero, 4, 4, 0, ksc, 0, qsl);
+                if constexpr (KSM == 2)
+                    s = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_opnd(kop[1]), fp4_opnd(bq4[1]), s, 4, 4, 1, ksc, 1, qsl);
+                mfma_scale_settle(s);
+                constexpr int RING = 3;
+                auto opnd = [&](int i) __attribute__((always_inline)) -> uint4v {
+                    return lds_read16_at((uint32_t)((a_it ^ (i << 5)) + kGB));
+                };
+                uint4v ring[RING];
+#pragma unroll
+                for (int i = 0; i < RING; ++i) ring[i] = opnd(i);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dp[i] = 0.0f;
+#pragma unroll
+                for (int i = 0; i < DS; ++i) {
+                    const uint4v bq = ring[i % RING];
+                    if (i + RING < DS) ring[i % RING] = opnd(i + RING);
+                    dp = mfma_bf16(vreg[i], bq, dp);
+                }
+            } else
             {   // S^T = K^F Q^F^T, dP^T = V^F dO^T: 2*DS steps, step i: ds = i/2, Q or dO = i%2
                 // (the two-level variant carries the exchanged row maximum and its LDS slot on top: its ring is one shorter)
                 constexpr int NST = 2 * DS, RING = PQ == 3 ? 2 : 3;
@@ -832,10 +957,11 @@ template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
                          int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts,
-                         int p_quant, hipStream_t st, float* p_dump, int dump_row0)
+                         int p_quant, hipStream_t st, float* p_dump, int dump_row0, const MxScoreOps* mx)
 {
     const int Lp = round_up(L, kRowPad);
-    const size_t smem = sizeof(DkvSmem<D>);
+    if (p_quant == 2 && !(mx && mx->qops && mx->qsc && mx->kops && mx->ksc)) return -1;
+    const size_t smem = p_quant == 2 ? sizeof(DkvSmem<D, true>) : sizeof(DkvSmem<D, false>);
     auto kern = p_quant == 0 ? bwd_dkdv_kernel<D, CAUSAL, false, 0>
               : p_quant == 2 ? bwd_dkdv_kernel<D, CAUSAL, false, 2>
               : p_quant == 3 ? bwd_dkdv_kernel<D, CAUSAL, false, 3>
@@ -848,19 +974,21 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
     hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
                        (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv, tile_counts,
-                       L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs, rs, p_dump, dump_row0);
+                       L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs, rs, p_dump, dump_row0,
+                       (const unsigned char*)(mx ? mx->qops : nullptr), (const uint32_t*)(mx ? mx->qsc : nullptr),
+                       (const unsigned char*)(mx ? mx->kops : nullptr), (const uint32_t*)(mx ? mx->ksc : nullptr));
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
                     const float* rowstat, const float* bound_part,
                     int B, int Hq, int Hkv, int L, int D, bool causal, void* dk, void* dv,
-                    unsigned long long* tile_counts, int p_quant, hipStream_t st, float* p_dump, int dump_row0)
+                    unsigned long long* tile_counts, int p_quant, hipStream_t st, float* p_dump, int dump_row0, const MxScoreOps* mx)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0)
-                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0);
-    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0)
-                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0, mx)
+                                : launch_dkdv_t<128, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0, mx);
+    if (D == 64)  return causal ? launch_dkdv_t<64, true>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0, mx)
+                                : launch_dkdv_t<64, false>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, tile_counts, p_quant, st, p_dump, dump_row0, mx);
     return -1;
 }
 

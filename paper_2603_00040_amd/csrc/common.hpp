@@ -99,6 +99,14 @@ __device__ inline float e8m0_inverse_as_f32(uint32_t byte) { return __uint_as_fl
 // Bytes of one 64-key K record of the MX training forward (operands of the scaled FP4 instruction and their scale dwords).
 __host__ __device__ constexpr int mx_ktrain_rec_bytes(int D) { return 2 * (D / 64) * 1024 + 1024; }
 
+// The result of v_mfma_scale_f32_32x32x64_f8f6f4 must not be read by a vector instruction before the wait states of the matrix
+// pipeline have passed; the compiler counts them inside a basic block, but when the product is the last instruction of a
+// block it inserts nothing at the start of the next one (seen: the first score register read too early, NaN).  These
+// no-ops, tied to the accumulators by a data dependence, stand behind the last score product of a tile in every kernel
+// that uses the instruction on the 16-bit path.
+__device__ inline void mfma_scale_settle(floatx16& a) { asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a)); }
+__device__ inline void mfma_scale_settle(floatx16& a, floatx16& b) { asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a), "+v"(b)); }
+
 // max(a, b) written as median(a, b, +inf): fmaxf() on values the compiler cannot prove quiet (MFMA
 // results) costs a canonicalizing v_max per operand, the median has no such requirement and the
 // compiler folds chains of it into v_max3.  No NaN reaches these reductions.

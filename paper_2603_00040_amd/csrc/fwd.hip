@@ -180,6 +180,7 @@ __global__ __launch_bounds__(512, 2) void fwd_kernel(
                 s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[0][1]), as8(qop[1]), s[0], 4, 4, 1, ksc, 1, qs);
                 s[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as8(a[1][1]), as8(qop[1]), s[1], 4, 4, 3, ksc, 1, qs);
             }
+            mfma_scale_settle(s[0], s[1]);
             return;
         }
         // per-lane offset of this tile, opaque to the compiler: it would otherwise hoist every

@@ -56,6 +56,11 @@ size_t decode_ws_bytes(int B, int Hkv, int R, int max_pages, int D);
 int launch_decode(const void* qh, const void* cache, int num_pages, const int* page_table, int max_pages, const int* kv_lens,
                   int B, int Hq, int Hkv, int Lq, int D, bool causal, void* ws, int spin_limit, void* o, float* lse, hipStream_t st);
 
+// The MX format's operand arrays of the scaled FP4 instruction, from which the backward recomputes the scores (launch_mx_quant):
+// qops / qsc: mode 1 on Q; kops / ksc: mode 1 on K (a wave's 32 keys as the A operand of the dK/dV pass); krec: mode 3 on K
+// (64-key records, the A operand of the dQ pass).
+struct MxScoreOps { const void *qops, *qsc, *kops, *ksc, *krec; };
+
 // Per-row statistics of the backward: rowstat [BHq, Lp, 2] = {L log2(e), D / sqrt(d)} with
 // D = rowsum(dO o O') (Alg. 3, first line); padding rows hold zeros.  d_o bf16, o_hp fp32, [rows, D].
 // o_acc: O' fp32, or (ablation) the bf16 O when o_is_bf16.
@@ -70,7 +75,8 @@ int launch_bounds(const void* vb, const void* dob, const float* rowstat, int BHk
 // Alg. 3, query-stationary pass: dQ.  qh, kh: fp16 copies; vb, dob: bf16 copies.
 int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
                   const float* rowstat, const float* bound_part,
-                  int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st);
+                  int B, int Hq, int Hkv, int L, int D, bool causal, void* dq, hipStream_t st,
+                  const MxScoreOps* mx = nullptr /* the MX format: scores from the codes */);
 
 // Alg. 3, key-stationary pass: dK, dV (summed over the query heads of a group).
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
@@ -79,7 +85,7 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
                     unsigned long long* tile_counts /* may be null */,
                     int p_quant /* phi(P): 0 none (ablation), 1 NVFP4, 2 MX, 3 NVFP4 with the two-level row factor */, hipStream_t st,
                     float* p_dump = nullptr /* test hook, p_quant 1 only: P^F of query rows [dump_row0, dump_row0 + 128), [B*Hq][128][L] */,
-                    int dump_row0 = 0);
+                    int dump_row0 = 0, const MxScoreOps* mx = nullptr /* p_quant 2: required */);
 
 // ---- MX variant (E2M1, blocks of 32, E8M0 scale; mx.hip) ----
 // phi with the blocks along d (axis 0) or along the sequence (axis 1).  x [BH, L, D] bf16.
