@@ -399,11 +399,12 @@ int attnqat_fwd_infer_mx_sparse(const void* q, const void* k, const void* v,
  * Training forward (Alg. 2) and backward (Alg. 3) in the MX format, for training against
  * attnqat_fwd_infer_mx: the same quantizers (Q^F, K^F blocked along d; V^F, P-tilde^F and the
  * backward's recomputed P^F in blocks of 32 keys; power-of-two scales), O' from the un-quantized
- * P-tilde, D from O', dS from the fp32 P.  These two run on the 16-bit matrix instructions with the
- * dequantized values (Eq. 4), which are the numbers the FP4 instruction multiplies (Eq. 3): O and lse
- * agree with attnqat_fwd_infer_mx up to fp32 summation order, except that dequantized values below
- * the fp16 range (2^-24; P-tilde^F far below the row maximum, elements of all-tiny Q/K/V blocks)
- * are flushed here.  Arguments as attnqat_fwd / attnqat_bwd; workspace sizes ATTNQAT_WS_FWD_MX and
+ * P-tilde, D from O', dS from the fp32 P.  The score product S = Q^F K^F^T is computed from the codes and
+ * scales by the FP4 matrix instruction in the forward and in both backward passes; the other products
+ * (O and O' from V^F, dP, dS K, dS^T Q, P^F^T dO) run on the 16-bit matrix instructions with the dequantized
+ * values (Eq. 4), which are the numbers the FP4 instruction multiplies (Eq. 3): O and lse agree with
+ * attnqat_fwd_infer_mx up to fp32 summation order, except that dequantized values of P-tilde^F and V^F below
+ * the fp16 range (2^-24; P-tilde^F far below the row maximum) are flushed here.  Arguments as attnqat_fwd / attnqat_bwd; workspace sizes ATTNQAT_WS_FWD_MX and
  * ATTNQAT_WS_BWD_MX.  attnqat_debug_fwd_p_mx is attnqat_debug_fwd_p for this forward.
  */
 int attnqat_fwd_mx(const void* q, const void* k, const void* v,
