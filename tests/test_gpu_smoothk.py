@@ -76,5 +76,6 @@ def test_smoothk_option_errors():
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     call = lambda opt: L_.attnqat_fwd_opt(q.data_ptr(), q.data_ptr(), q.data_ptr(), 1, 2, 2, 64, 128, 0, 0, opt,
                                          o.data_ptr(), lse.data_ptr(), None, ws.data_ptr(), need, None)
-    assert call(0) == aq.OK and call(1) == aq.OK and call(2) == aq.OK and call(4) == aq.EINVAL and call(-1) == aq.EINVAL
+    assert call(0) == aq.OK and call(1) == aq.OK and call(2) == aq.OK and call(4) == aq.OK          # 4: the bf16 P V recipe
+    assert call(8) == aq.EINVAL and call(6) == aq.EINVAL and call(-1) == aq.EINVAL                  # unknown bit; 2 | 4 exclude each other
     torch.cuda.synchronize()
