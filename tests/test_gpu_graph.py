@@ -105,3 +105,58 @@ def test_mfma_sustained_probe_reports_a_plausible_rate_and_clock():
     print(f"sustained MFMA probe: {tf:.0f} TFLOP/s at {ghz:.2f} GHz", flush=True)
     assert 1.0 < ghz < 2.6          # the part's clock range
     assert 800.0 < tf < 2600.0      # below the published 2.5 PFLOP/s, well above what a stalled launch would give
+
+
+def test_graph_replay_of_the_paged_nvfp4_forward():
+    """The NVFP4 paged forward under capture: the decode path (counter reset, chunk queue, merge: three kernels, tickets and row
+    maxima in the workspace) and the chunked-prefill path, replayed after the cache, the lengths and the queries changed."""
+    import paper_2603_00040_amd as aq
+    Hq, Hkv, d, max_pages = 8, 2, 128, 24
+    B = 3
+    num_pages = B * max_pages
+    cache = torch.empty(num_pages * aq.kv_cache_page_bytes_nvfp4(Hkv, d), dtype=torch.uint8, device="cuda")
+    table = torch.arange(num_pages, dtype=torch.int32, device="cuda").reshape(B, max_pages).flip(1).contiguous()
+    lens = torch.zeros(B, dtype=torch.int32, device="cuda")
+    q1 = torch.empty((B, Hq, 1, d), dtype=torch.bfloat16, device="cuda")
+    q64 = torch.empty((B, Hq, 64, d), dtype=torch.bfloat16, device="cuda")
+    o1, l1 = torch.empty_like(q1), torch.empty((B, Hq, 1), dtype=torch.float32, device="cuda")
+    o64, l64 = torch.empty_like(q64), torch.empty((B, Hq, 64), dtype=torch.float32, device="cuda")
+    nb = max(aq.lib().attnqat_paged_workspace_bytes(B, Hq, Hkv, 1, max_pages, d), aq.lib().attnqat_paged_workspace_bytes(B, Hq, Hkv, 64, max_pages, d))
+    ws1 = torch.empty(nb, dtype=torch.uint8, device="cuda"); ws64 = torch.empty(nb, dtype=torch.uint8, device="cuda")
+
+    def step():
+        aq.attnqat_fwd_infer_paged(q1, cache, num_pages, table, lens, Hkv, True, workspace=ws1, out=(o1, l1))
+        aq.attnqat_fwd_infer_paged(q64, cache, num_pages, table, lens, Hkv, True, workspace=ws64, out=(o64, l64))
+
+    def load(seed, kv_lens):
+        cache.random_(0, 256)
+        x = random_inputs(B, Hq, Hkv, max(kv_lens), d, seed, k_chan=4)
+        for b, n in enumerate(kv_lens):
+            aq.attnqat_kv_cache_write(to_dev(x["k"][b:b + 1, :, :n]).contiguous(), to_dev(x["v"][b:b + 1, :, :n]).contiguous(), cache, table[b].contiguous())
+        lens.copy_(torch.tensor(kv_lens, dtype=torch.int32))
+        q1.copy_(to_dev(np.ascontiguousarray(np.stack([x["q"][b, :, n - 1:n] for b, n in enumerate(kv_lens)]))))
+        q64.copy_(to_dev(np.ascontiguousarray(np.stack([x["q"][b, :, n - 64:n] for b, n in enumerate(kv_lens)]))))
+
+    outs = (o1, l1, o64, l64)
+    load(1, [3000, 1025, 70])                         # decode: three chunks, two chunks, one
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep, (seed, kv_lens) in enumerate(((1, [3000, 1025, 70]), (2, [64, 2049, 3072]), (3, [1500, 1500, 100]), (2, [64, 2049, 3072]))):
+        load(seed, kv_lens)
+        step()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in outs]
+        for t in outs:
+            t.fill_(float("nan")) if t.dtype != torch.bfloat16 else t.zero_()
+        _ = (want[0].float().sum() + q64.float().sum()).item()
+        g.replay()
+        torch.cuda.synchronize()
+        for t, w in zip(outs, want):
+            assert torch.equal(t, w), (rep, seed)
+        assert not torch.isnan(l1).any() and not torch.isnan(l64).any()
+    print("paged NVFP4 forward: graph replays bit-identical to eager", flush=True)
