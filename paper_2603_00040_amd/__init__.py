@@ -64,6 +64,7 @@ _SIGNATURES = {
                                  _vp, _sz, _vp]),
     "attnqat_debug_bwd_p": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "attnqat_debug_dkdv_tile_counts": (_i, [_vp, _vp]),
+    "attnqat_debug_dkdv_waves": (_i, [_i]),
     "attnqat_profile_enable": (_i, [_vp, _i]),
     "attnqat_profile_read": (_i, [_vp, _i, _vp, _vp]),
 }
@@ -546,6 +547,11 @@ def debug_dkdv_tile_counts(counts):
     """counts: zeroed int64 CUDA tensor of 2 elements (tiles visited, tiles with non-zero P^F) or None; applies to
     attnqat_bwd calls on the current stream."""
     _check(lib().attnqat_debug_dkdv_tile_counts(_stream(), _ptr(counts) if counts is not None else None))
+
+
+def debug_dkdv_waves(waves: int):
+    """Force the workgroup shape of the dK/dV pass (4 or 8 waves; 0 = automatic).  Process-wide."""
+    _check(lib().attnqat_debug_dkdv_waves(int(waves)))
 
 
 def profile_enable(on: bool):

@@ -541,6 +541,13 @@ int attnqat_debug_dkdv_tile_counts(void* stream, unsigned long long* counts)
     return ATTNQAT_OK;
 }
 
+int attnqat_debug_dkdv_waves(int waves)
+{
+    if (waves != 0 && waves != 4 && waves != 8) return ATTNQAT_EINVAL;
+    aq::set_dkdv_waves(waves);
+    return ATTNQAT_OK;
+}
+
 int attnqat_profile_enable(void* stream, int on)
 {
     std::lock_guard<std::mutex> lock(g_dbg_mutex);

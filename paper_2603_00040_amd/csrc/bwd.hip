@@ -491,22 +491,25 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 }
 
 // ------------------------------------------------------------------ dK/dV pass
-// A workgroup owns 128 keys of one kv head (32 per wave, held in registers as MFMA A
-// operands) and walks over the query rows of every query head of the group in tiles of 32.
+// A workgroup of NW waves owns 32 NW keys of one kv head (32 per wave, held in registers as MFMA A
+// operands) and walks over the query rows of every query head of the group in tiles of 32.  NW = 4
+// everywhere except the non-causal NVFP4 training pass of a large problem, which runs NW = 8: every
+// Q / dO tile a workgroup fetches then serves twice the keys, which halves the pass's read traffic.
 constexpr int kTPad = 36;            // row length (elements) of the per-wave [query][key] staging tiles
 
-template <int D, bool MXS>
+template <int D, bool MXS, int NW>
 struct DkvSmem {
     uint16_t q[2][32 * D];           // Q^F rows [query][d], fp16, swizzled
     uint16_t g[2][32 * D];           // dO rows  [query][d], bf16, swizzled
-    uint16_t t[4][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
-    float rmax[4][32];               // two-level P: per wave, the largest P of every query row over the wave's 32 keys
+    uint16_t t[NW][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
+    float rmax[NW][32];              // two-level P: per wave, the largest P of every query row over the wave's 32 keys
     unsigned char qrec[MXS ? 2 : 1][MXS ? (D / 64) * 1024 + 256 : 16];      // MX: Q operands of the FP4 instruction of a tile and their scale dwords
 };
 
 template <int D, bool CAUSAL, bool COUNT /* measurement / test variant: count tiles, dump P^F */,
-          int PQ /* phi(P): 0 none (ablation: dV from the fp32 P), 1 NVFP4, 2 MX, 3 NVFP4 after the two-level row factor */>
-__global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
+          int PQ /* phi(P): 0 none (ablation: dV from the fp32 P), 1 NVFP4, 2 MX, 3 NVFP4 after the two-level row factor */,
+          int NW = 4 /* waves, 32 keys each */>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb, const float2* __restrict__ rowstat, const float* __restrict__ bound_part,
     uint16_t* __restrict__ dK, uint16_t* __restrict__ dV, unsigned long long* __restrict__ tile_counts,
@@ -519,31 +522,33 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     constexpr int KSM = D / 64, QREC = KSM * 1024 + 256;
     constexpr int DS = D / 16, NB = D / 32, KCH = D / 8;
     constexpr int NWL = (32 * KCH) / 64;             // 1 KiB wave-loads per tile of 32 rows
-    constexpr int PER_WAVE = NWL >= 4 ? NWL / 4 : 1;
+    constexpr int PER_WAVE = NWL >= NW ? NWL / NW : 1;
     extern __shared__ __align__(256) unsigned char smem_raw[];   // XORs of address bits 5..7 below commute with adding this base
-    DkvSmem<D, MXS>& sm = *reinterpret_cast<DkvSmem<D, MXS>*>(smem_raw);
+    DkvSmem<D, MXS, NW>& sm = *reinterpret_cast<DkvSmem<D, MXS, NW>*>(smem_raw);
 
-    const int nkt = Lp / 128;
+    constexpr int KT = 32 * NW;                      // keys of a workgroup
+    const int nkt = (Lp + KT - 1) / KT;              // (Lp is a multiple of 128: with 8 waves the last workgroup may own only 128 keys)
     int bhkv, kt_;
     head_tile_of_block(blockIdx.x, gridDim.x / nkt, nkt, bhkv, kt_);    // key tiles in increasing order: under a causal
     const int Hkv = Hq / G;                         // mask the first tiles see the most queries
     const int b = bhkv / Hkv, hk = bhkv % Hkv;
     const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: LDS destinations and branches use it
-    const int key0_w = kt_ * 128 + wave * 32;       // this wave's first key
+    const int key0_w = kt_ * KT + wave * 32;        // this wave's first key
+    const bool wave_live = NW == 4 || key0_w < Lp;  // a wave past the padded rows takes part in the copies and barriers only
 
     // K^F, V^F rows of this lane's key: A operands (row = key, d-slots 16*ds + 8*hf)
     uint4v kreg[MXS ? 1 : DS], vreg[DS], kop[MXS ? KSM : 1];
     uint32_t ksc = 0u;
     {
-        const size_t off = ((size_t)bhkv * Lp + key0_w + ln) * D + 8 * hf;
+        const size_t off = ((size_t)bhkv * Lp + (wave_live ? key0_w : 0) + ln) * D + 8 * hf;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
             if constexpr (!MXS) kreg[ds] = *reinterpret_cast<const uint4v*>(Kb + off + 16 * ds);
             vreg[ds] = *reinterpret_cast<const uint4v*>(Vb + off + 16 * ds);
         }
         if constexpr (MXS) {
-            const size_t grp = (size_t)bhkv * (Lp / 32) + (key0_w >> 5);
+            const size_t grp = (size_t)bhkv * (Lp / 32) + ((wave_live ? key0_w : 0) >> 5);
 #pragma unroll
             for (int ks = 0; ks < KSM; ++ks) kop[ks] = *reinterpret_cast<const uint4v*>(Kops + ((grp * KSM + ks) * 64 + lane) * 16);
             ksc = Ksc[grp * 64 + lane];
@@ -559,7 +564,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     // query tiles of 32 rows, query heads of the group one after another; under a causal mask
     // only rows >= the workgroup's first key matter
     const int nq32 = (L + 31) / 32;
-    const int qt_first = CAUSAL ? (kt_ * 128) / 32 : 0;
+    const int qt_first = CAUSAL ? (kt_ * KT) / 32 : 0;
     const int per_head = nq32 - qt_first;
     const int niter = per_head > 0 ? per_head * G : 0;
     const size_t bh0 = (size_t)b * Hq + hk * G;      // first query head of the group
@@ -578,7 +583,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
     const float rs_s = rs * ds_scale;
 
     // direct-to-LDS loads: this wave's chunk slots and their (row, swizzled chunk)
-    const bool loader = NWL >= 4 || wave < NWL;
+    const bool loader = NWL >= NW || wave < NWL;
     uint32_t slot_off[PER_WAVE];                     // this lane's byte offset inside a tile's source rows
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
@@ -658,7 +663,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
         // wave-uniform.  With the two-level P every wave takes part in every tile: the exchange of the row maxima below
         // contains a workgroup barrier, and a wave whose keys all lie after the tile's queries computes P = 0 throughout
         // (which costs the first four query tiles of a workgroup some idle products and nothing else).
-        const bool active = PQ == 3 || !CAUSAL || q0 + 31 >= key0_w;
+        const bool active = PQ == 3 || ((!CAUSAL || q0 + 31 >= key0_w) && wave_live);
         if (active) {
             // Q^F tile of this iteration (dO is kGB further).  The per-lane offsets are made opaque once
             // per iteration: otherwise the compiler hoists every (offset ^ constant) out of the loop and
@@ -953,6 +958,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(
         }
 }
 
+static int g_dkdv_waves = 0;          // 0: chosen per problem; 4 / 8: forced (tests)
+void set_dkdv_waves(int waves) { __atomic_store_n(&g_dkdv_waves, waves, __ATOMIC_RELAXED); }
+
 template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
@@ -961,7 +969,25 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
 {
     const int Lp = round_up(L, kRowPad);
     if (p_quant == 2 && !(mx && mx->qops && mx->qsc && mx->kops && mx->ksc)) return -1;
-    const size_t smem = p_quant == 2 ? sizeof(DkvSmem<D, true>) : sizeof(DkvSmem<D, false>);
+    // eight waves where that still leaves every compute unit two workgroups to balance with
+    const int forced = __atomic_load_n(&g_dkdv_waves, __ATOMIC_RELAXED);
+    const bool wide = !CAUSAL && p_quant == 1 && !tile_counts && !p_dump &&
+                      (forced == 8 || (forced == 0 && (long long)B * Hkv * ((Lp + 255) / 256) >= 2LL * device_cu_count()));
+    if constexpr (!CAUSAL) if (wide) {
+        auto kern8 = bwd_dkdv_kernel<D, false, false, 1, 8>;
+        const size_t smem8 = sizeof(DkvSmem<D, false, 8>);
+        static unsigned long long lds_set8 = 0;
+        if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern8), (int)smem8, lds_set8)) return -1;
+        const float rs8 = 1.0f / sqrtf((float)D);
+        hipLaunchKernelGGL(kern8, dim3((unsigned)(B * Hkv * ((Lp + 255) / 256))), dim3(512), smem8, st,
+                           (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
+                           (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv,
+                           (unsigned long long*)nullptr, L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs8, rs8,
+                           (float*)nullptr, 0, (const unsigned char*)nullptr, (const uint32_t*)nullptr,
+                           (const unsigned char*)nullptr, (const uint32_t*)nullptr);
+        return hipGetLastError() == hipSuccess ? 0 : -1;
+    }
+    const size_t smem = p_quant == 2 ? sizeof(DkvSmem<D, true, 4>) : sizeof(DkvSmem<D, false, 4>);
     auto kern = p_quant == 0 ? bwd_dkdv_kernel<D, CAUSAL, false, 0>
               : p_quant == 2 ? bwd_dkdv_kernel<D, CAUSAL, false, 2>
               : p_quant == 3 ? bwd_dkdv_kernel<D, CAUSAL, false, 3>

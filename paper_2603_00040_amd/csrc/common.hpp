@@ -246,6 +246,19 @@ __device__ inline void head_tile_of_block(int block, int nheads, int per_head, i
     }
 }
 
+// Host side: compute units of the current device, asked once per device (256 if the runtime does not say).
+inline int device_cu_count() {
+    static int ncu[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    int cus = __atomic_load_n(&ncu[dev & 63], __ATOMIC_RELAXED);
+    if (cus == 0) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        __atomic_store_n(&ncu[dev & 63], cus, __ATOMIC_RELAXED);
+    }
+    return cus;
+}
+
 // Host side: raise a kernel's dynamic LDS limit once per kernel instantiation and device instead of on every launch.
 // `done` is a bit mask of devices (a static of the calling instantiation).  Returns false if the runtime refuses.
 inline bool ensure_dynamic_lds(const void* kernel, int bytes, unsigned long long& done) {

@@ -462,14 +462,7 @@ int launch_decode(const void* qh, const void* cache, int num_pages, const int* p
     const int nz = (int)nz64;
     hipLaunchKernelGGL(zero_ints_kernel, dim3((nz + 255) / 256), dim3(256), 0, st, ctl, nz);
     if (hipGetLastError() != hipSuccess) return -1;
-    static int ncu[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return -1;
-    int cus = __atomic_load_n(&ncu[dev & 63], __ATOMIC_RELAXED);
-    if (cus == 0) {
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-        __atomic_store_n(&ncu[dev & 63], cus, __ATOMIC_RELAXED);
-    }
+    const int cus = device_cu_count();
     const unsigned grid = (unsigned)min((size_t)2 * cus, units);
     const float c = 1.4426950408889634f / sqrtf((float)D);
 #define AQ_DEC(DD, C) hipLaunchKernelGGL((decode_kernel<DD, C>), dim3(grid), dim3(256), 0, st, (const half_t*)qh, (const unsigned char*)cache, \

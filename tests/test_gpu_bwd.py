@@ -47,6 +47,43 @@ def test_d64_heavy_tails(causal):
     _run(1, 3, 1, 333, 64, causal, seed=9, dist="t3", scale=0.5, tok_mod=50)
 
 
+@pytest.fixture
+def eight_waves():
+    import paper_2603_00040_amd as aq
+    aq.debug_dkdv_waves(8)
+    yield
+    aq.debug_dkdv_waves(0)
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 2, 256, 64), (2, 4, 2, 129, 128), (1, 3, 1, 333, 64), (1, 2, 1, 700, 128)])
+def test_eight_wave_dkdv_shape(shape, eight_waves):
+    """The 256-key workgroups of the non-causal dK/dV pass, which small problems never pick by themselves: against the
+    oracle, with lengths that leave the last workgroup a single wave (129), a ragged second half (333, 700) or exactly
+    full (256)."""
+    B, Hq, Hkv, L, d = shape
+    _run(B, Hq, Hkv, L, d, False, seed=77 + L, k_chan=2)
+
+
+def test_eight_wave_dkdv_equals_four_wave():
+    """Both shapes add the same 32 x 32 tile products in the same order: the same bits."""
+    import paper_2603_00040_amd as aq
+    x = random_inputs(1, 4, 2, 900, 128, seed=5)
+    q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
+    o, lse, ohp = aq.attnqat_fwd(q, k, v, False)
+    out = {}
+    try:
+        for w in (4, 8):
+            aq.debug_dkdv_waves(w)
+            out[w] = aq.attnqat_bwd(q, k, v, do, lse, ohp, False)
+            torch.cuda.synchronize()
+    finally:
+        aq.debug_dkdv_waves(0)
+    for a, b in zip(out[4], out[8]):
+        assert torch.equal(a, b)
+    with pytest.raises(aq.AttnQatError):
+        aq.debug_dkdv_waves(6)
+
+
 def test_backward_with_oracle_forward_state():
     """Feeding the oracle's L and O' (instead of the GPU forward's) isolates the backward."""
     import paper_2603_00040_amd as aq
