@@ -440,16 +440,16 @@ int attnqat_debug_fwd_p_mx(const void* q, const void* k, const void* v,
  * on it adds to counts[0] the number of tiles the pass visited and to counts[1] the number with a non-zero P^F.
  * NULL switches it off (the default).
  *
- * attnqat_debug_dkdv_waves: the dK/dV pass runs workgroups of 4 waves (128 keys), and workgroups of 8 waves (256 keys)
- * for the non-causal NVFP4 pass of a problem large enough to keep two of them per compute unit; both compute the same
- * sums over the same 32 x 32 tiles.  waves = 4 or 8 forces one shape (8 only where that variant exists), 0 returns to
+ * attnqat_debug_bwd_waves: the dQ and dK/dV passes run workgroups of 4 waves (128 query rows / 128 keys), and workgroups
+ * of 8 waves (256) for the non-causal NVFP4 passes of a problem large enough to keep two of them per compute unit; both
+ * compute the same sums over the same tiles in the same order.  waves = 4 or 8 forces one shape (8 only where that variant exists), 0 returns to
  * the automatic choice.  Process-wide, for tests that compare the two shapes at small sizes.  ATTNQAT_EINVAL for any
  * other value.
  */
 int attnqat_profile_enable(void* stream, int on);
 int attnqat_profile_read(void* stream, int max_entries, float* ms, const char** names);
 int attnqat_debug_dkdv_tile_counts(void* stream, unsigned long long* counts);
-int attnqat_debug_dkdv_waves(int waves);
+int attnqat_debug_bwd_waves(int waves);
 
 #ifdef __cplusplus
 }

@@ -64,7 +64,7 @@ _SIGNATURES = {
                                  _vp, _sz, _vp]),
     "attnqat_debug_bwd_p": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "attnqat_debug_dkdv_tile_counts": (_i, [_vp, _vp]),
-    "attnqat_debug_dkdv_waves": (_i, [_i]),
+    "attnqat_debug_bwd_waves": (_i, [_i]),
     "attnqat_profile_enable": (_i, [_vp, _i]),
     "attnqat_profile_read": (_i, [_vp, _i, _vp, _vp]),
 }
@@ -549,9 +549,9 @@ def debug_dkdv_tile_counts(counts):
     _check(lib().attnqat_debug_dkdv_tile_counts(_stream(), _ptr(counts) if counts is not None else None))
 
 
-def debug_dkdv_waves(waves: int):
-    """Force the workgroup shape of the dK/dV pass (4 or 8 waves; 0 = automatic).  Process-wide."""
-    _check(lib().attnqat_debug_dkdv_waves(int(waves)))
+def debug_bwd_waves(waves: int):
+    """Force the workgroup shape of the dQ and dK/dV passes (4 or 8 waves; 0 = automatic).  Process-wide."""
+    _check(lib().attnqat_debug_bwd_waves(int(waves)))
 
 
 def profile_enable(on: bool):

@@ -541,10 +541,10 @@ int attnqat_debug_dkdv_tile_counts(void* stream, unsigned long long* counts)
     return ATTNQAT_OK;
 }
 
-int attnqat_debug_dkdv_waves(int waves)
+int attnqat_debug_bwd_waves(int waves)
 {
     if (waves != 0 && waves != 4 && waves != 8) return ATTNQAT_EINVAL;
-    aq::set_dkdv_waves(waves);
+    aq::set_bwd_waves(waves);
     return ATTNQAT_OK;
 }
 

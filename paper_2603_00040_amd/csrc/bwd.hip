@@ -184,6 +184,9 @@ int launch_bounds(const void* vb, const void* dob, const float* rowstat, int BHk
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+static int g_bwd_waves = 0;           // waves per workgroup of the dQ and dK/dV passes, 0: chosen per problem; 4 / 8: forced (tests)
+void set_bwd_waves(int waves) { __atomic_store_n(&g_bwd_waves, waves, __ATOMIC_RELAXED); }
+
 // ------------------------------------------------------------------ dQ pass
 template <int D, bool MXS>
 struct DqSmem {
@@ -201,20 +204,22 @@ __device__ inline int8v_t fp4_opnd(const uint4v& x) {
 // MXS (the MX format): S^T = K^F Q^F^T is recomputed from the E2M1 codes and E8M0 scales by v_mfma_scale_f32_32x32x64_f8f6f4
 // (Qops / Qsc: operands and scale dwords of the query rows, launch_mx_quant mode 1; Krec: the K records of mode 3); the
 // accumulator layout is that of the 16-bit products, and dP, dS and dQ are computed as before (dO, dS are 16-bit values).
-template <int D, bool CAUSAL, bool MXS>
-__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
+// NW waves of 32 query rows each share the K / V tiles: 4, or 8 for the non-causal NVFP4 pass of a large problem (half the
+// tile copies per query row).
+template <int D, bool CAUSAL, bool MXS, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dq_kernel(
     const uint16_t* __restrict__ Qb, const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     const uint16_t* __restrict__ dOb,
     const float2* __restrict__ rowstat, const float* __restrict__ bound_part, uint16_t* __restrict__ dQ,
     int L, int Lp, int Hq, int G, int NHq, float c /* log2e/sqrt(d) */, float rs /* 1/sqrt(d) */,
     const unsigned char* __restrict__ Qops, const uint32_t* __restrict__ Qsc, const unsigned char* __restrict__ Krec)
 {
-    constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, KLD = KCH / 4;
+    constexpr int DS = D / 16, MB = D / 32, KCH = D / 8, KLD = KCH / NW, QT = 32 * NW /* query rows of a workgroup */;
     constexpr int KSM = D / 64, KREC = mx_ktrain_rec_bytes(D);
     extern __shared__ __align__(256) unsigned char smem_raw[];
     DqSmem<D, MXS>& sm = *reinterpret_cast<DqSmem<D, MXS>*>(smem_raw);
 
-    const int nqt = Lp / 128;
+    const int nqt = (Lp + QT - 1) / QT;              // (Lp is a multiple of 128: with 8 waves the last workgroup may own only 128 rows)
     int bh, qt;
     head_tile_of_block(blockIdx.x, gridDim.x / nqt, nqt, bh, qt);
     if (CAUSAL) qt = nqt - 1 - qt;
@@ -222,25 +227,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const int bhkv = b * (Hq / G) + h / G;
     const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: LDS destinations and branches use it
-    const int q_row = qt * 128 + wave * 32 + ln;
+    const int q_row = qt * QT + wave * 32 + ln;
+    const bool wave_live = NW == 4 || qt * QT + wave * 32 < Lp;      // a wave past the padded rows takes part in the copies and barriers only
+    const int q_ld = wave_live ? q_row : ln;         // row its loads read instead
 
     uint4v qreg[MXS ? 1 : DS], doreg[DS], qop[MXS ? KSM : 1];
     uint32_t qs = 0u;
     {
-        const size_t off = ((size_t)bh * Lp + q_row) * D + 8 * hf;
+        const size_t off = ((size_t)bh * Lp + q_ld) * D + 8 * hf;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
             if constexpr (!MXS) qreg[ds] = *reinterpret_cast<const uint4v*>(Qb + off + 16 * ds);
             doreg[ds] = *reinterpret_cast<const uint4v*>(dOb + off + 16 * ds);
         }
         if constexpr (MXS) {
-            const size_t grp = (size_t)bh * (Lp / 32) + ((qt * 128 + wave * 32) >> 5);
+            const size_t grp = (size_t)bh * (Lp / 32) + ((q_ld - ln) >> 5);
 #pragma unroll
             for (int ks = 0; ks < KSM; ++ks) qop[ks] = *reinterpret_cast<const uint4v*>(Qops + ((grp * KSM + ks) * 64 + lane) * 16);
             qs = Qsc[grp * 64 + lane];
         }
     }
-    const float2 st_ = rowstat[(size_t)bh * Lp + q_row];
+    const float2 st_ = rowstat[(size_t)bh * Lp + q_ld];
     const float Ls = st_.x;                                          // L_i log2(e)
     // dS of this row goes to fp16 after multiplication by ds_scale = 2^k, k from the bound
     // (|dO_i| max_j |V^F_j| + |D_i|) / sqrt(d) >= |dS_ij|; rs_s and Dq_s carry the factor.
@@ -261,8 +268,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
     const float rs_s = rs * ds_scale, Dq_s = st_.y * ds_scale;        // D_i / sqrt(d), scaled
 
     const int nkt_all = (L + 63) / 64;
-    const int nkt = CAUSAL ? min(2 * qt + 2, nkt_all) : nkt_all;
-    const int wave_qmax = qt * 128 + wave * 32 + 31;
+    const int nkt = CAUSAL ? min((qt + 1) * (QT / 64), nkt_all) : nkt_all;
+    const int wave_qmax = qt * QT + wave * 32 + 31;
 
     // direct-to-LDS tile loads: wave-uniform tile base + this lane's byte offset inside the tile
     uint32_t kv_ld[KLD];
@@ -281,7 +288,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
             async_copy16(v_head + (size_t)jt * (64 * D), kv_ld[i], &sm.v[buf][512 * (wave * KLD + i)]);
         }
         if constexpr (MXS) {
-            for (int i = wave; i < KREC / 1024; i += 4)
+            for (int i = wave; i < KREC / 1024; i += NW)
                 async_copy16(k_recs + (size_t)jt * KREC, (uint32_t)(i * 1024 + lane * 16), &sm.krec[buf][i * 1024]);
         }
     };
@@ -334,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         constexpr int BUF = decltype(buf_tag)::value;
         const int k0 = j * 64;
         if (j + 1 < nkt) issue_tile(BUF ^ 1, j + 1);
-        const bool active = !CAUSAL || k0 <= wave_qmax;
+        const bool active = (!CAUSAL || k0 <= wave_qmax) && wave_live;
         if (active) {
             floatx16 s[2], dp[2];
             if constexpr (MXS) {
@@ -400,7 +407,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
                 }
             }
             // masked keys (beyond L, or after the query): S = -inf so that P = 0
-            const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > qt * 128 + wave * 32);
+            const bool need_mask = (k0 + 64 > L) || (CAUSAL && k0 + 63 > qt * QT + wave * 32);
             if (__builtin_expect(need_mask, 0)) {
                 const int klim = CAUSAL ? min(L - 1, q_row) : L - 1;
 #pragma unroll
@@ -442,7 +449,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(
         if (j + 1 < nkt) tile(std::integral_constant<int, 1>{}, j + 1);
     }
 
-    if (q_row < L) {
+    if (q_row < L && wave_live) {
         const size_t row = (size_t)bh * L + q_row;
         const float un = rs / rs_s;                                  // 1 / ds_scale, exact: a power of two
 #pragma unroll
@@ -464,6 +471,22 @@ static int launch_dq_t(const void* qb, const void* kb, const void* vb, const voi
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DqSmem<D, MXS>);
+    // eight waves where that still leaves every compute unit two workgroups to balance with
+    if constexpr (!CAUSAL && !MXS) {
+        const int forced = __atomic_load_n(&g_bwd_waves, __ATOMIC_RELAXED);
+        if (forced == 8 || (forced == 0 && (long long)B * Hq * ((Lp + 255) / 256) >= 2LL * device_cu_count())) {
+            auto kern8 = bwd_dq_kernel<D, false, false, 8>;
+            static unsigned long long lds_set8 = 0;
+            if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern8), (int)smem, lds_set8)) return -1;
+            const float rs8 = 1.0f / sqrtf((float)D);
+            hipLaunchKernelGGL(kern8, dim3((unsigned)(B * Hq * ((Lp + 255) / 256))), dim3(512), smem, st,
+                               (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
+                               (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv, B * Hq,
+                               1.4426950408889634f * rs8, rs8,
+                               (const unsigned char*)nullptr, (const uint32_t*)nullptr, (const unsigned char*)nullptr);
+            return hipGetLastError() == hipSuccess ? 0 : -1;
+        }
+    }
     auto kern = bwd_dq_kernel<D, CAUSAL, MXS>;
     static unsigned long long lds_set = 0;          // one per instantiation
     if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
@@ -958,9 +981,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
         }
 }
 
-static int g_dkdv_waves = 0;          // 0: chosen per problem; 4 / 8: forced (tests)
-void set_dkdv_waves(int waves) { __atomic_store_n(&g_dkdv_waves, waves, __ATOMIC_RELAXED); }
-
 template <int D, bool CAUSAL>
 static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
@@ -970,7 +990,7 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
     const int Lp = round_up(L, kRowPad);
     if (p_quant == 2 && !(mx && mx->qops && mx->qsc && mx->kops && mx->ksc)) return -1;
     // eight waves where that still leaves every compute unit two workgroups to balance with
-    const int forced = __atomic_load_n(&g_dkdv_waves, __ATOMIC_RELAXED);
+    const int forced = __atomic_load_n(&g_bwd_waves, __ATOMIC_RELAXED);
     const bool wide = !CAUSAL && p_quant == 1 && !tile_counts && !p_dump &&
                       (forced == 8 || (forced == 0 && (long long)B * Hkv * ((Lp + 255) / 256) >= 2LL * device_cu_count()));
     if constexpr (!CAUSAL) if (wide) {

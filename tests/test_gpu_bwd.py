@@ -50,21 +50,21 @@ def test_d64_heavy_tails(causal):
 @pytest.fixture
 def eight_waves():
     import paper_2603_00040_amd as aq
-    aq.debug_dkdv_waves(8)
+    aq.debug_bwd_waves(8)
     yield
-    aq.debug_dkdv_waves(0)
+    aq.debug_bwd_waves(0)
 
 
 @pytest.mark.parametrize("shape", [(1, 2, 2, 256, 64), (2, 4, 2, 129, 128), (1, 3, 1, 333, 64), (1, 2, 1, 700, 128)])
-def test_eight_wave_dkdv_shape(shape, eight_waves):
-    """The 256-key workgroups of the non-causal dK/dV pass, which small problems never pick by themselves: against the
+def test_eight_wave_backward_shape(shape, eight_waves):
+    """The 256-row / 256-key workgroups of the non-causal dQ and dK/dV passes, which small problems never pick by themselves: against the
     oracle, with lengths that leave the last workgroup a single wave (129), a ragged second half (333, 700) or exactly
     full (256)."""
     B, Hq, Hkv, L, d = shape
     _run(B, Hq, Hkv, L, d, False, seed=77 + L, k_chan=2)
 
 
-def test_eight_wave_dkdv_equals_four_wave():
+def test_eight_wave_backward_equals_four_wave():
     """Both shapes add the same 32 x 32 tile products in the same order: the same bits."""
     import paper_2603_00040_amd as aq
     x = random_inputs(1, 4, 2, 900, 128, seed=5)
@@ -73,15 +73,15 @@ def test_eight_wave_dkdv_equals_four_wave():
     out = {}
     try:
         for w in (4, 8):
-            aq.debug_dkdv_waves(w)
+            aq.debug_bwd_waves(w)
             out[w] = aq.attnqat_bwd(q, k, v, do, lse, ohp, False)
             torch.cuda.synchronize()
     finally:
-        aq.debug_dkdv_waves(0)
+        aq.debug_bwd_waves(0)
     for a, b in zip(out[4], out[8]):
         assert torch.equal(a, b)
     with pytest.raises(aq.AttnQatError):
-        aq.debug_dkdv_waves(6)
+        aq.debug_bwd_waves(6)
 
 
 def test_backward_with_oracle_forward_state():
