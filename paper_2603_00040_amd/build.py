@@ -17,6 +17,9 @@ AUX_LIB = os.path.join(HERE, "benchaux", "libattnqat_benchaux.so")
 # -packed-fp32-ops off: plain fp32 VALU code only (packed fp32 forms are not trusted here)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # one lane's atomic add stays one atomic add: the wave-wide rewrite of atomics makes the wave wait for the returned
+         # value at once, which the decode kernel's ticket prefetch exists to avoid
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-option-ignored"]
 
 
