@@ -41,7 +41,7 @@ def _fill_cache(aq, x, Hkv, d, kv_lens, seed, pieces=1):
     return cache, num_pages, table
 
 
-def _run(Hq, Hkv, d, kv_lens, Lq, causal, seed, pieces=1, **kw):
+def _run(Hq, Hkv, d, kv_lens, Lq, causal, seed, pieces=1, tol=TOL, **kw):
     import paper_2603_00040_amd as aq
     B = len(kv_lens)
     x = random_inputs(B, Hq, Hkv, max(kv_lens), d, seed, **kw)      # sequence b uses its first kv_lens[b] positions
@@ -57,7 +57,7 @@ def _run(Hq, Hkv, d, kv_lens, Lq, causal, seed, pieces=1, **kw):
         qf[0, :, n - Lq:] = f32(qb[b])
         rows = oracle.flat_rows(1, Hq, n, [(0, h, i) for h in range(Hq) for i in range(n - Lq, n)])
         ref = oracle.fwd(qf, f32(x["k"][b:b + 1, :, :n]), f32(x["v"][b:b + 1, :, :n]), causal, aq.block_k(), rows=rows)
-        check_bf16_output("O", host(o[b]).reshape(-1, d), ref["O"], TOL, label=f"sequence {b} ({n} keys)")
+        check_bf16_output("O", host(o[b]).reshape(-1, d), ref["O"], tol, label=f"sequence {b} ({n} keys)")
         eL = max_abs(host(lse[b]).reshape(-1), ref["L"])
         worst = max(worst, eL)
         assert eL <= 2e-5 * max(1.0, np.abs(ref["L"]).max()), (b, n, eL)
@@ -90,6 +90,18 @@ def test_decode_sequences_cut_into_chunks(d, causal):
     _run(8, 2, d, [5000, 1030, 1024, 3, 2049], 1, causal, seed=50 + d, k_chan=4)
     _run(8, 2, d, [3000, 700, 257], 3, causal, seed=51 + d)
     _run(16, 1, d, [1500, 256], 1, causal, seed=52 + d, dist="t3", scale=0.5)
+    # more than 16 chunks in front of a chunk (19 chunks of 256 keys): the maxima a lane did not ask for early
+    _run(16, 1, d, [4700, 300], 1, causal, seed=53 + d, k_chan=2)
+
+
+def test_decode_many_short_sequences():
+    """More sequences than the chunk list's builder stages next to its lanes (2048): the list is built from the lengths in
+    memory, and every sequence is a single chunk."""
+    rng = np.random.default_rng(9)
+    lens = [int(n) for n in rng.integers(1, 41, size=2100)]
+    # (128 output values per sequence: the rounding of the bf16 output alone scatters to 2.2e-3 in rel-L2 on so few; the
+    #  bars that leave that rounding out are the usual ones)
+    _run(2, 1, 64, lens, 1, True, seed=60, tol=3e-3)
 
 
 def test_decode_wait_limit_is_honoured_and_leaves_no_state():
