@@ -38,7 +38,7 @@ def _traffic(gb, source):
 TRAFFIC_BEYOND_L2 = {
     "dit720p_train": {k: _traffic(v, "profiles/hbm_traffic_dit720p_train.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate runs, scaled by "
                                      "the copy-kernel calibration; stored from that run, not collected live)")
-                      for k, v in {"fwd_train": 17.5 + 3.75, "bwd_dq": 64.8 + 0.77, "bwd_dkdv": 310.0 + 1.55}.items()},
+                      for k, v in {"fwd_train": 17.5 + 4.51, "bwd_dq": 19.7 + 0.77, "bwd_dkdv": 310.8 + 1.55}.items()},
     "dit480p_infer": {"fwd_infer_mx": _traffic(0.883, "profiles/dit480p_infer_mx_fwd_kernels.txt (FETCH_SIZE, scaled; stored from that run)")},
 }
 
