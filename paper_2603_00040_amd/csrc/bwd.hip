@@ -204,7 +204,7 @@ __device__ inline int8v_t fp4_opnd(const uint4v& x) {
 // MXS (the MX format): S^T = K^F Q^F^T is recomputed from the E2M1 codes and E8M0 scales by v_mfma_scale_f32_32x32x64_f8f6f4
 // (Qops / Qsc: operands and scale dwords of the query rows, launch_mx_quant mode 1; Krec: the K records of mode 3); the
 // accumulator layout is that of the 16-bit products, and dP, dS and dQ are computed as before (dO, dS are 16-bit values).
-// NW waves of 32 query rows each share the K / V tiles: 4, or 8 for the non-causal NVFP4 pass of a large problem (half the
+// NW waves of 32 query rows each share the K / V tiles: 4, or 8 for the non-causal pass of a large problem (half the
 // tile copies per query row).
 template <int D, bool CAUSAL, bool MXS, int NW = 4>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dq_kernel(
@@ -464,40 +464,43 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dq_kernel(
     }
 }
 
-template <int D, bool CAUSAL, bool MXS>
-static int launch_dq_t(const void* qb, const void* kb, const void* vb, const void* dob,
+template <int D, bool CAUSAL, bool MXS, int NW>
+static int launch_dq_v(const void* qb, const void* kb, const void* vb, const void* dob,
                        const float* rowstat, const float* bound_part, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st,
                        const MxScoreOps* mx)
 {
     const int Lp = round_up(L, kRowPad);
     const size_t smem = sizeof(DqSmem<D, MXS>);
-    // eight waves where that still leaves every compute unit two workgroups to balance with
-    if constexpr (!CAUSAL && !MXS) {
-        const int forced = __atomic_load_n(&g_bwd_waves, __ATOMIC_RELAXED);
-        if (forced == 8 || (forced == 0 && (long long)B * Hq * ((Lp + 255) / 256) >= 2LL * device_cu_count())) {
-            auto kern8 = bwd_dq_kernel<D, false, false, 8>;
-            static unsigned long long lds_set8 = 0;
-            if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern8), (int)smem, lds_set8)) return -1;
-            const float rs8 = 1.0f / sqrtf((float)D);
-            hipLaunchKernelGGL(kern8, dim3((unsigned)(B * Hq * ((Lp + 255) / 256))), dim3(512), smem, st,
-                               (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
-                               (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv, B * Hq,
-                               1.4426950408889634f * rs8, rs8,
-                               (const unsigned char*)nullptr, (const uint32_t*)nullptr, (const unsigned char*)nullptr);
-            return hipGetLastError() == hipSuccess ? 0 : -1;
-        }
-    }
-    auto kern = bwd_dq_kernel<D, CAUSAL, MXS>;
+    auto kern = bwd_dq_kernel<D, CAUSAL, MXS, NW>;
     static unsigned long long lds_set = 0;          // one per instantiation
     if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float rs = 1.0f / sqrtf((float)D);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * (Lp / 128))), dim3(256), smem, st,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hq * ((Lp + 32 * NW - 1) / (32 * NW)))), dim3(64 * NW), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
                        (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dq, L, Lp, Hq, Hq / Hkv, B * Hq,
                        1.4426950408889634f * rs, rs,
                        (const unsigned char*)(mx ? mx->qops : nullptr), (const uint32_t*)(mx ? mx->qsc : nullptr),
                        (const unsigned char*)(mx ? mx->krec : nullptr));
     return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Eight waves per workgroup for a non-causal pass whose problem still leaves every compute unit two such workgroups to
+// balance with (or when a test forces them); four otherwise.
+static bool wide_workgroups(bool causal, long long groups_of_256)
+{
+    const int forced = __atomic_load_n(&g_bwd_waves, __ATOMIC_RELAXED);
+    return !causal && (forced == 8 || (forced == 0 && groups_of_256 >= 2LL * device_cu_count()));
+}
+
+template <int D, bool CAUSAL, bool MXS>
+static int launch_dq_t(const void* qb, const void* kb, const void* vb, const void* dob,
+                       const float* rowstat, const float* bound_part, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st,
+                       const MxScoreOps* mx)
+{
+    if constexpr (!CAUSAL)
+        if (wide_workgroups(false, (long long)B * Hq * ((round_up(L, kRowPad) + 255) / 256)))
+            return launch_dq_v<D, false, MXS, 8>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st, mx);
+    return launch_dq_v<D, CAUSAL, MXS, 4>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st, mx);
 }
 
 int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* dob,
@@ -516,7 +519,7 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 // ------------------------------------------------------------------ dK/dV pass
 // A workgroup of NW waves owns 32 NW keys of one kv head (32 per wave, held in registers as MFMA A
 // operands) and walks over the query rows of every query head of the group in tiles of 32.  NW = 4
-// everywhere except the non-causal NVFP4 training pass of a large problem, which runs NW = 8: every
+// everywhere except the non-causal pass of a large problem (any format of P except the ablation), which runs NW = 8: every
 // Q / dO tile a workgroup fetches then serves twice the keys, which halves the pass's read traffic.
 constexpr int kTPad = 36;            // row length (elements) of the per-wave [query][key] staging tiles
 
@@ -981,49 +984,45 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
         }
 }
 
-template <int D, bool CAUSAL>
-static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
+template <int D, bool CAUSAL, bool COUNT, int PQ, int NW>
+static int launch_dkdv_v(const void* qb, const void* kb, const void* vb, const void* dob,
                          const float* rowstat, const float* bound_part,
                          int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts,
-                         int p_quant, hipStream_t st, float* p_dump, int dump_row0, const MxScoreOps* mx)
+                         hipStream_t st, float* p_dump, int dump_row0, const MxScoreOps* mx)
 {
     const int Lp = round_up(L, kRowPad);
-    if (p_quant == 2 && !(mx && mx->qops && mx->qsc && mx->kops && mx->ksc)) return -1;
-    // eight waves where that still leaves every compute unit two workgroups to balance with
-    const int forced = __atomic_load_n(&g_bwd_waves, __ATOMIC_RELAXED);
-    const bool wide = !CAUSAL && p_quant == 1 && !tile_counts && !p_dump &&
-                      (forced == 8 || (forced == 0 && (long long)B * Hkv * ((Lp + 255) / 256) >= 2LL * device_cu_count()));
-    if constexpr (!CAUSAL) if (wide) {
-        auto kern8 = bwd_dkdv_kernel<D, false, false, 1, 8>;
-        const size_t smem8 = sizeof(DkvSmem<D, false, 8>);
-        static unsigned long long lds_set8 = 0;
-        if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern8), (int)smem8, lds_set8)) return -1;
-        const float rs8 = 1.0f / sqrtf((float)D);
-        hipLaunchKernelGGL(kern8, dim3((unsigned)(B * Hkv * ((Lp + 255) / 256))), dim3(512), smem8, st,
-                           (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
-                           (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv,
-                           (unsigned long long*)nullptr, L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs8, rs8,
-                           (float*)nullptr, 0, (const unsigned char*)nullptr, (const uint32_t*)nullptr,
-                           (const unsigned char*)nullptr, (const uint32_t*)nullptr);
-        return hipGetLastError() == hipSuccess ? 0 : -1;
-    }
-    const size_t smem = p_quant == 2 ? sizeof(DkvSmem<D, true, 4>) : sizeof(DkvSmem<D, false, 4>);
-    auto kern = p_quant == 0 ? bwd_dkdv_kernel<D, CAUSAL, false, 0>
-              : p_quant == 2 ? bwd_dkdv_kernel<D, CAUSAL, false, 2>
-              : p_quant == 3 ? bwd_dkdv_kernel<D, CAUSAL, false, 3>
-              : (tile_counts || p_dump) ? bwd_dkdv_kernel<D, CAUSAL, true, 1> : bwd_dkdv_kernel<D, CAUSAL, false, 1>;
-    if (p_quant != 1) { if (p_dump) return -1; tile_counts = nullptr; }
-    if (p_quant < 0 || p_quant > 3) return -1;
-    static unsigned long long lds_set[5] = {0, 0, 0, 0, 0};      // one per variant of this instantiation
-    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set[p_quant == 1 && (tile_counts || p_dump) ? 4 : p_quant])) return -1;
+    const size_t smem = sizeof(DkvSmem<D, PQ == 2, NW>);
+    auto kern = bwd_dkdv_kernel<D, CAUSAL, COUNT, PQ, NW>;
+    static unsigned long long lds_set = 0;          // one per instantiation
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return -1;
     const float rs = 1.0f / sqrtf((float)D);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * (Lp / 128))), dim3(256), smem, st,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(B * Hkv * ((Lp + 32 * NW - 1) / (32 * NW)))), dim3(64 * NW), smem, st,
                        (const uint16_t*)qb, (const uint16_t*)kb, (const uint16_t*)vb,
                        (const uint16_t*)dob, (const float2*)rowstat, bound_part, (uint16_t*)dk, (uint16_t*)dv, tile_counts,
                        L, Lp, Hq, Hq / Hkv, B * Hq, 1.4426950408889634f * rs, rs, p_dump, dump_row0,
                        (const unsigned char*)(mx ? mx->qops : nullptr), (const uint32_t*)(mx ? mx->qsc : nullptr),
                        (const unsigned char*)(mx ? mx->kops : nullptr), (const uint32_t*)(mx ? mx->ksc : nullptr));
     return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int D, bool CAUSAL>
+static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const void* dob,
+                         const float* rowstat, const float* bound_part,
+                         int B, int Hq, int Hkv, int L, void* dk, void* dv, unsigned long long* tile_counts,
+                         int p_quant, hipStream_t st, float* p_dump, int dump_row0, const MxScoreOps* mx)
+{
+    if (p_quant < 0 || p_quant > 3) return -1;
+    if (p_quant == 2 && !(mx && mx->qops && mx->qsc && mx->kops && mx->ksc)) return -1;
+    if (p_quant != 1) { if (p_dump) return -1; tile_counts = nullptr; }
+#define AQ_DKV(COUNT, PQ, NW) launch_dkdv_v<D, CAUSAL, COUNT, PQ, NW>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dk, dv, \
+                                                                       tile_counts, st, p_dump, dump_row0, mx)
+    if (tile_counts || p_dump) return AQ_DKV(true, 1, 4);       // the counting / dumping variant
+    if (p_quant == 0) return AQ_DKV(false, 0, 4);               // the ablation
+    if constexpr (!CAUSAL)
+        if (wide_workgroups(false, (long long)B * Hkv * ((round_up(L, kRowPad) + 255) / 256)))
+            return p_quant == 1 ? AQ_DKV(false, 1, 8) : p_quant == 2 ? AQ_DKV(false, 2, 8) : AQ_DKV(false, 3, 8);
+    return p_quant == 1 ? AQ_DKV(false, 1, 4) : p_quant == 2 ? AQ_DKV(false, 2, 4) : AQ_DKV(false, 3, 4);
+#undef AQ_DKV
 }
 
 int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* dob,
