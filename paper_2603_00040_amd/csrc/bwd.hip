@@ -521,13 +521,22 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 // operands) and walks over the query rows of every query head of the group in tiles of 32.  NW = 4
 // everywhere except the non-causal pass of a large problem (any format of P except the ablation), which runs NW = 8: every
 // Q / dO tile a workgroup fetches then serves twice the keys, which halves the pass's read traffic.
-constexpr int kTPad = 36;            // row length (elements) of the per-wave [query][key] staging tiles
+// The per-wave [query][key] staging tiles (32 queries x 32 keys, 16-bit values, rows of 64 bytes).  By the bank-conflict
+// counter the LDS takes an 8-byte store from 16 lanes per cycle on 32 banks of 4 bytes and serves an 8-byte (transposing)
+// read to 32 lanes per cycle on 64 banks.  A store instruction writes one 8-byte chunk of 16 consecutive queries per cycle,
+// a read fetches the whole rows of four consecutive queries.  The rows of four consecutive queries (a group) are therefore
+// contiguous, 256 bytes: a read touches every bank once.  For the stores every group is followed by 16 bytes of padding
+// (the next group starts four banks further) and in the third and fourth row of a group neighbouring chunks are swapped:
+// with the row's own 64 bytes = 16 banks that puts the 16 queries of a cycle on 16 different bank pairs.  (Rows padded
+// to 72 bytes instead made every read collide once: 6 % of the pass's LDS cycles.)
+constexpr int kTGroupB = 4 * 64 + 16;  // bytes of a group of four queries
+constexpr int kTTileB = 8 * kTGroupB;  // bytes of a tile
 
 template <int D, bool MXS, int NW>
 struct DkvSmem {
     uint16_t q[2][32 * D];           // Q^F rows [query][d], fp16, swizzled
     uint16_t g[2][32 * D];           // dO rows  [query][d], bf16, swizzled
-    uint16_t t[NW][2][32 * kTPad];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
+    uint16_t t[NW][2][kTTileB / 2];    // per wave: P^F (bf16) and dS (fp16, scaled) as [query][key]
     float rmax[NW][32];              // two-level P: per wave, the largest P of every query row over the wave's 32 keys
     unsigned char qrec[MXS ? 2 : 1][MXS ? (D / 64) * 1024 + 256 : 16];      // MX: Q operands of the FP4 instruction of a tile and their scale dwords
 };
@@ -649,10 +658,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
     for (int v = 0; v < 2; ++v) g_rd[v] = 2 * swz_elem<KCH>(8 * hf + (tr_r >> 2) + 4 * v, 16 * tr_grp + 4 * (tr_r & 3));
     // staging tiles of this wave, as LDS byte addresses (integers: pointer arithmetic on the dynamic LDS symbol costs an
     // add per access): this lane's writes and its transpose reads; the dS tile lies kTB bytes after the P^F tile
-    constexpr int kTB = 32 * kTPad * 2;
+    constexpr int kTB = kTTileB;
     const uint32_t t_base = lds_addr_of(&sm.t[wave][0][0]);
-    const uint32_t tw_ad = t_base + 2u * (uint32_t)(ln * kTPad + 4 * hf);
-    const uint32_t ta_ad = t_base + 2u * (uint32_t)((8 * hf + (tr_r >> 2)) * kTPad + 16 * tr_grp + 4 * (tr_r & 3));
+    // writes: query ln, chunk hf + 2 t4 (keys 4 hf + 8 t4 .. + 3; t4 = 0..3 at compile time); reads: query 8 hf + tr_r/4 +
+    // 16 ks + 4 s (group 2 hf + 4 ks + s), chunk 4 tr_grp + tr_r%4; the swap of neighbouring chunks flips the lane's part
+    const uint32_t tw_ad = t_base + (uint32_t)(kTGroupB * (ln >> 2) + 64 * (ln & 3) + 8 * (hf ^ ((ln >> 1) & 1)));
+    const uint32_t ta_ad = t_base + (uint32_t)(kTGroupB * (2 * hf) + 64 * (tr_r >> 2) + 32 * tr_grp + 8 * ((tr_r & 3) ^ ((tr_r >> 3) & 1)));
     const int lds0 = (int)lds_addr_of(smem_raw);
 
     // {L_i log2(e), D_i / sqrt(d)} of this lane's query row of the next tile
@@ -853,7 +864,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
                         fq_pair_f32(s[r0 + 2] * inv[gq], s[r0 + 3] * inv[gq], sc[gq], pf[2], pf[3]);
                         uint2v wp;
                         wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
-                        lds_write8_at(tw_ad + (uint32_t)(16 * (r0 >> 2)), wp);
+                        lds_write8_at(tw_ad + (uint32_t)(16 * t4), wp);
                         if constexpr (COUNT) {
                             const int qr = q0 + ln;      // registers r0 .. r0 + 3: keys key0_w + 8 t4 + 4 hf + e of query row qr
                             if (pdump && qr >= dump_row0 && qr < dump_row0 + 128 && qr < L) {
@@ -877,7 +888,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
                 uint2v wh;
                 wh[0] = pack_f16x2(dsv[0], dsv[1]); wh[1] = pack_f16x2(dsv[2], dsv[3]);
                 // registers r0..r0+3 <-> keys 8*(r0>>2) + 4*hf + 0..3 of this wave's 32 keys
-                lds_write8_at(tw_ad + (uint32_t)(kTB + 16 * (r0 >> 2)), wh);
+                lds_write8_at(tw_ad + (uint32_t)(kTB + 16 * t4), wh);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -893,8 +904,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
                             lds_read_tr16_at((uint32_t)((g_it1 ^ (nb << 6)) + ks * (16 * kRowB) + extra)));
             };
             auto rd_t = [&](int tb /* 0: P^F tile, kTB: dS tile */, int ks) __attribute__((always_inline)) -> uint4v {
-                const uint32_t ta = ta_ad + (uint32_t)(tb + ks * (16 * kTPad * 2));
-                return join(lds_read_tr16_at(ta), lds_read_tr16_at(ta + 4 * kTPad * 2));
+                const uint32_t ta = ta_ad + (uint32_t)(tb + ks * (4 * kTGroupB));       // 16 rows = 4 groups further
+                return join(lds_read_tr16_at(ta), lds_read_tr16_at(ta + kTGroupB));
             };
             // steps [FIRST, LAST) of the stream
             auto products = [&](auto first_tag, auto last_tag) __attribute__((always_inline)) {
@@ -947,7 +958,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dkdv_kernel(
                         }
                         uint2v wp;
                         wp[0] = pack_bf16x2(pf[0], pf[1]); wp[1] = pack_bf16x2(pf[2], pf[3]);
-                        lds_write8_at(tw_ad + (uint32_t)(16 * (r0 >> 2)), wp);
+                        lds_write8_at(tw_ad + (uint32_t)(16 * t4), wp);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
