@@ -360,13 +360,14 @@ int attnqat_fwd_infer_mx_paged(const void* q, int B, int Hq, int Hkv, int Lq, in
  *   more than 16: the pages are unpacked into the fp16 K and V^T copies of attnqat_fwd_infer's kernel (the workspace
  *     holds them, laid out for max_pages * 128 positions per sequence), which then runs with per-sequence lengths.
  *   at most 16 (decode steps): one kernel reads the pages directly, once.  The keys of a sequence are cut into chunks
- *     that workgroups take from a queue, so that long sequences do not set the pace of the step.  P-tilde is quantized
+ *     that workgroups take from a queue (a small kernel in front lists the chunks that exist, from kv_lens and the page
+ *     table as they are in memory when it runs), so that long sequences do not set the pace of the step.  P-tilde is quantized
  *     against the running maximum in key order (Alg. 1), which a chunk cannot know before the chunks in front of it have
  *     computed their scores: every chunk first computes its scores (the K half of its pages), publishes its row maxima
  *     in the workspace and waits for those of its predecessors, then does the rest (the V half).  Tickets are handed out
  *     in chunk order, so a predecessor is always running or finished when someone waits for it and the wait ends; it is
  *     bounded nevertheless (2^22 polls), and a wait that expired leaves a wrong result for that sequence.  The partial
- *     sums of the chunks are added by whichever chunk finishes last.  The result is not bit-identical to
+ *     sums of the chunks of a sequence are added by a third kernel.  The result is not bit-identical to
  *     attnqat_fwd_infer (the sums are grouped differently) but holds the same parity bars against the oracle.
  * attnqat_debug_fwd_infer_paged is the same call with the poll limit as an argument (tests force the expiry path with
  * 0); it synchronizes the stream and sets *wait_expired (host) to 1 if any wait of the decode path ran out.
