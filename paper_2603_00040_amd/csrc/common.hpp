@@ -208,6 +208,9 @@ __device__ inline uint2v lds_read_tr16_at(uint32_t addr) {
 __device__ inline void lds_write8_at(uint32_t addr, uint2v v) {
     *(__attribute__((address_space(3))) uint2v*)(uintptr_t)addr = v;
 }
+__device__ inline void lds_write16_at(uint32_t addr /* a multiple of 16 */, uint4v v) {
+    *(__attribute__((address_space(3))) uint4v*)(uintptr_t)addr = v;
+}
 __device__ inline uint32_t lds_addr_of(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(
     constexpr size_t HB = (size_t)2 * 128 * (D / 2 + D / 16);     // bytes per kv head in a page
     constexpr size_t VOFF = (size_t)128 * (D / 2 + D / 16);       // the V part behind the K part
 
-    __shared__ float sbuf[kDecSFloats];                            // scores of the chunk [R][CK]
+    __shared__ __align__(16) float sbuf[kDecSFloats];              // scores of the chunk [R][CK]
     __shared__ __align__(16) unsigned char stage[4 * 32 * RS];     // per wave: V^F of 32 keys [key][d] fp16; later the merge buffer
     __shared__ __align__(16) unsigned char pfb[4 * kDecRows * PS]; // per wave: P^F of a tile [row][key] fp16
     __shared__ float tmax[kDecRows][kDecMaxTiles + 1];             // row maximum of every tile
@@ -185,6 +185,7 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(
     const int cc = lane & 15, g = lane >> 4;
     const int row = cc < R ? cc : 0;                               // lanes of unused columns follow row 0 (never stored)
     float* mbuf = reinterpret_cast<float*>(stage);                 // [4][R][D] when the waves' partial sums are added
+    const uint32_t sbuf_ad = lds_addr_of(sbuf);
     const int nwork = __builtin_amdgcn_readfirstlane(ctl[2]);
     if (nwork < 1) return;
 
@@ -299,7 +300,8 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(
                             if (k_t + 16 * blk + 4 * g + i > klim) acc[i] = -INFINITY;
                     }
                     mx = max_nc(max_nc(mx, max_nc(acc[0], acc[1])), max_nc(acc[2], acc[3]));
-                    if (cc < R) *reinterpret_cast<floatx4*>(&sbuf[cc * CK + 64 * t + 16 * blk + 4 * g]) = acc;
+                    // (CK is a multiple of 128: the address is a multiple of 16, which the compiler cannot see in an index)
+                    if (cc < R) lds_write16_at(sbuf_ad + 4u * (uint32_t)(cc * CK + 64 * t + 16 * blk + 4 * g), __builtin_bit_cast(uint4v, acc));
                 }
                 mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -379,7 +381,7 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(
                 if (4 * ps < R) {
                     const int prow = min(4 * ps + pq, R - 1);
                     const float mrow = run[prow][t], ms = mrow * c;
-                    const floatx4 sv = *reinterpret_cast<const floatx4*>(&sbuf[prow * CK + 64 * t + 4 * pj]);
+                    const floatx4 sv = __builtin_bit_cast(floatx4, lds_read16_at(sbuf_ad + 4u * (uint32_t)(prow * CK + 64 * t + 4 * pj)));
                     float pt[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) pt[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], c, -ms));
