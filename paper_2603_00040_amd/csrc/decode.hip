@@ -480,7 +480,7 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(
         } else {
             // several chunks: the partial sums go to memory for the kernel that adds them
             for (int e = tid; e < R * D; e += 256)
-                part_o[unit * kDecRows * D + e] = (mbuf[e] + mbuf[R * D + e]) + (mbuf[2 * R * D + e] + mbuf[3 * R * D + e]);
+                part_o[unit * R * D + e] = (mbuf[e] + mbuf[R * D + e]) + (mbuf[2 * R * D + e] + mbuf[3 * R * D + e]);
             if (tid < R) {
                 part_l[unit * kDecRows + tid] = (lsum_w[0][tid] + lsum_w[1][tid]) + (lsum_w[2][tid] + lsum_w[3][tid]);
                 part_m[unit * kDecRows + tid] = run[tid][NT - 1];
@@ -518,7 +518,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(
             for (int k = 0; k < 8; ++k) {
                 const size_t u = u0 + min(i0 + k, nch - 1);
                 pm[k] = i0 + k < nch ? part_m[u * kDecRows + r] : -INFINITY;
-                po[k] = part_o[u * kDecRows * D + e];
+                po[k] = part_o[u * R * D + e];
                 pl[k] = part_l[u * kDecRows + r];
             }
             float Mn = M;
@@ -550,7 +550,7 @@ size_t decode_ws_bytes(int B, int Hkv, int R, int max_pages, int D)
     size_t n = 256;                                                   // ticket counter, error word, number of chunks
     n += units * kDecRows * 8;                                         // row maxima with their tags
     n += units * kDecRows * 4 * 2;                                     // l and m of the partial sums
-    n += units * kDecRows * D * 4;                                     // O of the partial sums
+    n += units * R * D * 4;                                            // O of the partial sums (R rows each)
     n += units * kDecItemInts * 4;                                     // the list of chunks
     return n;
 }
@@ -568,7 +568,7 @@ int launch_decode(const void* qh, const void* cache, int num_pages, const int* p
     unsigned long long* cmax = (unsigned long long*)p;     p += units * kDecRows * 8;
     float* part_l = (float*)p;               p += units * kDecRows * 4;
     float* part_m = (float*)p;               p += units * kDecRows * 4;
-    float* part_o = (float*)p;               p += units * kDecRows * D * 4;
+    float* part_o = (float*)p;               p += units * R * D * 4;
     int* work = (int*)p;
     // the counters and the tagged row maxima are one run of ints from ctl on
     const size_t nz64 = ((unsigned char*)cmax - (unsigned char*)ctl) / 4 + units * kDecRows * 2;
