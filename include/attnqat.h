@@ -442,8 +442,9 @@ int attnqat_debug_fwd_p_mx(const void* q, const void* k, const void* v,
  * NULL switches it off (the default).
  *
  * attnqat_debug_bwd_waves: the dQ and dK/dV passes run workgroups of 4 waves (128 query rows / 128 keys), and workgroups
- * of 8 waves (256) for the non-causal passes (NVFP4, with or without the options, and MX) of a problem large enough to keep
- * two of them per compute unit; both compute the same sums over the same tiles in the same order.  waves = 4 or 8 forces one shape (8 only where that variant exists), 0 returns to
+ * of 8 waves (256) for the passes (NVFP4, with or without the options, and MX) of a problem large enough to keep two of
+ * them per compute unit, under a causal mask only from 16384 positions on; both compute the same sums over the same tiles
+ * in the same order.  waves = 4 or 8 forces one shape (8 only where that variant exists), 0 returns to
  * the automatic choice.  Process-wide, for tests that compare the two shapes at small sizes.  ATTNQAT_EINVAL for any
  * other value.
  */

@@ -204,7 +204,7 @@ __device__ inline int8v_t fp4_opnd(const uint4v& x) {
 // MXS (the MX format): S^T = K^F Q^F^T is recomputed from the E2M1 codes and E8M0 scales by v_mfma_scale_f32_32x32x64_f8f6f4
 // (Qops / Qsc: operands and scale dwords of the query rows, launch_mx_quant mode 1; Krec: the K records of mode 3); the
 // accumulator layout is that of the 16-bit products, and dP, dS and dQ are computed as before (dO, dS are 16-bit values).
-// NW waves of 32 query rows each share the K / V tiles: 4, or 8 for the non-causal pass of a large problem (half the
+// NW waves of 32 query rows each share the K / V tiles: 4, or 8 for the passes of a large problem (half the
 // tile copies per query row).
 template <int D, bool CAUSAL, bool MXS, int NW = 4>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void bwd_dq_kernel(
@@ -484,12 +484,15 @@ static int launch_dq_v(const void* qb, const void* kb, const void* vb, const voi
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// Eight waves per workgroup for a non-causal pass whose problem still leaves every compute unit two such workgroups to
-// balance with (or when a test forces them); four otherwise.
-static bool wide_workgroups(bool causal, long long groups_of_256)
+// Eight waves per workgroup for a pass whose problem still leaves every compute unit two such workgroups to balance
+// with, and, under a causal mask, whose sequences are long enough for the 256 rows at the diagonal, where part of the
+// workgroup idles, not to matter (llm32k_gqa: 1.5 % faster with eight; llm4k_gqa: 2 - 8 % slower); or when a test
+// forces them; four otherwise.
+static bool wide_workgroups(bool causal, long long groups_of_256, int Lp)
 {
     const int forced = __atomic_load_n(&g_bwd_waves, __ATOMIC_RELAXED);
-    return !causal && (forced == 8 || (forced == 0 && groups_of_256 >= 2LL * device_cu_count()));
+    if (forced != 0) return forced == 8;
+    return groups_of_256 >= 2LL * device_cu_count() && (!causal || Lp >= 16384);
 }
 
 template <int D, bool CAUSAL, bool MXS>
@@ -497,9 +500,8 @@ static int launch_dq_t(const void* qb, const void* kb, const void* vb, const voi
                        const float* rowstat, const float* bound_part, int B, int Hq, int Hkv, int L, void* dq, hipStream_t st,
                        const MxScoreOps* mx)
 {
-    if constexpr (!CAUSAL)
-        if (wide_workgroups(false, (long long)B * Hq * ((round_up(L, kRowPad) + 255) / 256)))
-            return launch_dq_v<D, false, MXS, 8>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st, mx);
+    if (wide_workgroups(CAUSAL, (long long)B * Hq * ((round_up(L, kRowPad) + 255) / 256), round_up(L, kRowPad)))
+        return launch_dq_v<D, CAUSAL, MXS, 8>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st, mx);
     return launch_dq_v<D, CAUSAL, MXS, 4>(qb, kb, vb, dob, rowstat, bound_part, B, Hq, Hkv, L, dq, st, mx);
 }
 
@@ -519,7 +521,7 @@ int launch_bwd_dq(const void* qb, const void* kb, const void* vb, const void* do
 // ------------------------------------------------------------------ dK/dV pass
 // A workgroup of NW waves owns 32 NW keys of one kv head (32 per wave, held in registers as MFMA A
 // operands) and walks over the query rows of every query head of the group in tiles of 32.  NW = 4
-// everywhere except the non-causal pass of a large problem (any format of P except the ablation), which runs NW = 8: every
+// everywhere except the passes of a large problem (any format of P except the ablation), which run NW = 8: every
 // Q / dO tile a workgroup fetches then serves twice the keys, which halves the pass's read traffic.
 // The per-wave [query][key] staging tiles (32 queries x 32 keys, 16-bit values, rows of 64 bytes).  By the bank-conflict
 // counter the LDS takes an 8-byte store from 16 lanes per cycle on 32 banks of 4 bytes and serves an 8-byte (transposing)
@@ -1029,9 +1031,8 @@ static int launch_dkdv_t(const void* qb, const void* kb, const void* vb, const v
                                                                        tile_counts, st, p_dump, dump_row0, mx)
     if (tile_counts || p_dump) return AQ_DKV(true, 1, 4);       // the counting / dumping variant
     if (p_quant == 0) return AQ_DKV(false, 0, 4);               // the ablation
-    if constexpr (!CAUSAL)
-        if (wide_workgroups(false, (long long)B * Hkv * ((round_up(L, kRowPad) + 255) / 256)))
-            return p_quant == 1 ? AQ_DKV(false, 1, 8) : p_quant == 2 ? AQ_DKV(false, 2, 8) : AQ_DKV(false, 3, 8);
+    if (wide_workgroups(CAUSAL, (long long)B * Hkv * ((round_up(L, kRowPad) + 255) / 256), round_up(L, kRowPad)))
+        return p_quant == 1 ? AQ_DKV(false, 1, 8) : p_quant == 2 ? AQ_DKV(false, 2, 8) : AQ_DKV(false, 3, 8);
     return p_quant == 1 ? AQ_DKV(false, 1, 4) : p_quant == 2 ? AQ_DKV(false, 2, 4) : AQ_DKV(false, 3, 4);
 #undef AQ_DKV
 }

@@ -87,7 +87,7 @@ int launch_bwd_dkdv(const void* qb, const void* kb, const void* vb, const void* 
                     float* p_dump = nullptr /* test hook, p_quant 1 only: P^F of query rows [dump_row0, dump_row0 + 128), [B*Hq][128][L] */,
                     int dump_row0 = 0, const MxScoreOps* mx = nullptr /* p_quant 2: required */);
 // Waves per workgroup of the dQ and dK/dV passes: 0 = chosen per problem (the default), 4 or 8 = forced where that
-// variant exists (8: non-causal passes, not the ablation and not the counting variant).  Process-wide; for tests.
+// variant exists (8: not the ablation and not the counting variant).  Process-wide; for tests.
 void set_bwd_waves(int waves);
 
 // ---- MX variant (E2M1, blocks of 32, E8M0 scale; mx.hip) ----

@@ -55,26 +55,28 @@ def eight_waves():
     aq.debug_bwd_waves(0)
 
 
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("shape", [(1, 2, 2, 256, 64), (2, 4, 2, 129, 128), (1, 3, 1, 333, 64), (1, 2, 1, 700, 128)])
-def test_eight_wave_backward_shape(shape, eight_waves):
-    """The 256-row / 256-key workgroups of the non-causal dQ and dK/dV passes, which small problems never pick by themselves: against the
+def test_eight_wave_backward_shape(shape, causal, eight_waves):
+    """The 256-row / 256-key workgroups of the dQ and dK/dV passes, which small problems never pick by themselves: against the
     oracle, with lengths that leave the last workgroup a single wave (129), a ragged second half (333, 700) or exactly
     full (256)."""
     B, Hq, Hkv, L, d = shape
-    _run(B, Hq, Hkv, L, d, False, seed=77 + L, k_chan=2)
+    _run(B, Hq, Hkv, L, d, causal, seed=77 + L, k_chan=2)
 
 
-def test_eight_wave_backward_equals_four_wave():
+@pytest.mark.parametrize("causal", [False, True])
+def test_eight_wave_backward_equals_four_wave(causal):
     """Both shapes add the same 32 x 32 tile products in the same order: the same bits."""
     import paper_2603_00040_amd as aq
     x = random_inputs(1, 4, 2, 900, 128, seed=5)
     q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
-    o, lse, ohp = aq.attnqat_fwd(q, k, v, False)
+    o, lse, ohp = aq.attnqat_fwd(q, k, v, causal)
     out = {}
     try:
         for w in (4, 8):
             aq.debug_bwd_waves(w)
-            out[w] = aq.attnqat_bwd(q, k, v, do, lse, ohp, False)
+            out[w] = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
             torch.cuda.synchronize()
     finally:
         aq.debug_bwd_waves(0)

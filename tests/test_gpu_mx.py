@@ -167,21 +167,22 @@ def test_mx_train_ragged_lengths_d128_gqa(L, causal):
     _run_train(2, 4, 2, L, 128, causal, seed=300 + L, k_chan=4)
 
 
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("shape", [(2, 4, 2, 129, 128), (1, 3, 1, 333, 64), (1, 2, 1, 700, 128)])
-def test_mx_train_eight_wave_backward(shape):
-    """The 256-row / 256-key workgroups of the non-causal backward passes (large problems pick them by themselves): against
+def test_mx_train_eight_wave_backward(shape, causal):
+    """The 256-row / 256-key workgroups of the backward passes (large problems pick them by themselves): against
     the oracle, and the same bits as the 128-row shape."""
     import paper_2603_00040_amd as aq
     B, Hq, Hkv, L, d = shape
     try:
         aq.debug_bwd_waves(8)
-        _run_train(B, Hq, Hkv, L, d, False, seed=340 + L, k_chan=2)
+        _run_train(B, Hq, Hkv, L, d, causal, seed=340 + L, k_chan=2)
         x = random_inputs(B, Hq, Hkv, L, d, 341 + L)
         q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
-        o, lse, ohp = aq.attnqat_fwd_mx(q, k, v, False)
-        g8 = aq.attnqat_bwd_mx(q, k, v, do, lse, ohp, False)
+        o, lse, ohp = aq.attnqat_fwd_mx(q, k, v, causal)
+        g8 = aq.attnqat_bwd_mx(q, k, v, do, lse, ohp, causal)
         aq.debug_bwd_waves(4)
-        g4 = aq.attnqat_bwd_mx(q, k, v, do, lse, ohp, False)
+        g4 = aq.attnqat_bwd_mx(q, k, v, do, lse, ohp, causal)
         torch.cuda.synchronize()
     finally:
         aq.debug_bwd_waves(0)

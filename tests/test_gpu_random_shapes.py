@@ -45,7 +45,7 @@ def test_random_shape_forward_backward(B, Hq, Hkv, L, d, causal, dist, seed):
     rb = oracle.bwd(fq, fk, fv, fdo, rf["L"], rf["Op"], causal)
     grads = {}
     try:
-        for waves in (4, 8):            # 8 applies to the non-causal passes; a causal problem runs 4 either way
+        for waves in (4, 8):
             aq.debug_bwd_waves(waves)
             grads[waves] = aq.attnqat_bwd(q, k, v, do, lse, ohp, causal)
             torch.cuda.synchronize()

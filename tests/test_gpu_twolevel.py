@@ -51,21 +51,22 @@ def test_twolevel_d64_heavy_tails(causal):
     _run(1, 3, 1, 333, 64, causal, seed=9, dist="t3", scale=0.5, tok_mod=50)
 
 
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("shape", [(2, 4, 2, 129, 128), (1, 3, 1, 333, 64), (1, 2, 1, 700, 128)])
-def test_twolevel_eight_wave_backward(shape):
-    """The 256-row / 256-key workgroups of the non-causal backward passes (large problems pick them by themselves): against
+def test_twolevel_eight_wave_backward(shape, causal):
+    """The 256-row / 256-key workgroups of the backward passes (large problems pick them by themselves): against
     the oracle, and the same bits as the 128-row shape.  The pairs of waves that exchange row maxima stay pairs."""
     import paper_2603_00040_amd as aq
     B, Hq, Hkv, L, d = shape
     try:
         aq.debug_bwd_waves(8)
-        _run(B, Hq, Hkv, L, d, False, seed=640 + L, k_chan=2)
+        _run(B, Hq, Hkv, L, d, causal, seed=640 + L, k_chan=2)
         x = random_inputs(B, Hq, Hkv, L, d, 641 + L)
         q, k, v, do = (to_dev(x[n]) for n in ("q", "k", "v", "do"))
-        o, lse, ohp = aq.attnqat_fwd_opt(q, k, v, False, aq.OPT_TWO_LEVEL_P)
-        g8 = aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, False, aq.OPT_TWO_LEVEL_P)
+        o, lse, ohp = aq.attnqat_fwd_opt(q, k, v, causal, aq.OPT_TWO_LEVEL_P)
+        g8 = aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, causal, aq.OPT_TWO_LEVEL_P)
         aq.debug_bwd_waves(4)
-        g4 = aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, False, aq.OPT_TWO_LEVEL_P)
+        g4 = aq.attnqat_bwd_opt(q, k, v, do, lse, ohp, causal, aq.OPT_TWO_LEVEL_P)
         torch.cuda.synchronize()
     finally:
         aq.debug_bwd_waves(0)
